@@ -1,0 +1,27 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session")
+def golden():
+    """Constants the paper prints, parsed from tests/golden/paper_constants.txt."""
+    out = {}
+    path = os.path.join(ROOT, "tests", "golden", "paper_constants.txt")
+    with open(path) as f:
+        for line in f:
+            line = line.split("#", 1)[0].strip()
+            if not line:
+                continue
+            name, val = line.split()
+            out[name] = int(val, 16) if val.startswith("0x") else float(val)
+    return out
