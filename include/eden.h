@@ -1,0 +1,159 @@
+/*
+ * eden.h -- C ABI of the MI355X (gfx950) EDEN library.
+ *
+ * EDEN (arXiv 2108.08842) is a distributed-mean-estimation method: each of n senders
+ * holds a d-dimensional fp32 vector x_c, sends one short message, and a receiver
+ * returns an estimate of (1/n) sum_c x_c  (Sec. 2.1, the DME problem statement).
+ *
+ * The three hot calls follow that statement:
+ *   eden_encode            -- the senders' side  (Sec. 2.2.1 rotation, quantization, Sec. 2.3 scale)
+ *   eden_decode_accumulate -- the receiver's per-sender reconstruction, summed (Sec. 2.2.2, Sec. 4.2)
+ *   eden_finalize_mean     -- the division by n   (Sec. 2.2.2)
+ *
+ * Conventions common to every call
+ *   - Return value: 0 (EDEN_OK) or a negative eden_status.  Nothing throws or aborts.
+ *   - "_dev" pointers are HIP device pointers on the context's device; pointer ARRAYS
+ *     (x_dev[], msgs_dev[], recv_bitmaps_dev[]) and the id / budget arrays are HOST arrays,
+ *     read before the call returns and not retained.
+ *   - The caller owns every buffer it passes.  The library reads inputs, writes outputs,
+ *     and keeps no caller pointer after the call returns.  Its only own device memory is the
+ *     context workspace allocated by eden_create.
+ *   - `stream` is a hipStream_t cast to void* (NULL = the default stream).  Encode, decode and
+ *     finalize only enqueue work on that stream; they never synchronise the host.
+ *     Conditions that can only be seen on the device (zero or non-finite vector, nothing
+ *     received, header mismatch) are recorded in the message header's status word and in a
+ *     device status word that eden_last_device_status() reads (it synchronises).
+ *   - One context must not be used from two streams at once (they would share the workspace).
+ *
+ * Dimensions and layout
+ *   - d is padded with zeros to D = 2^ceil(log2 d); the rotation, the quantization and the
+ *     payload cover all D coordinates; the decoder drops the tail.  1 <= d <= 2^27.
+ *   - Rotation: R x = D^-1/2 H (s o x), H = Sylvester-ordered Hadamard matrix, s = +-1 diagonal
+ *     drawn from the shared seed and the sender's id (Sec. 2.1 shared randomness, Sec. 5
+ *     randomized Hadamard transform).  Bit (i & 63) of hash word (i >> 6) of the SIGN stream is 1
+ *     where s_i = -1.
+ *   - Hash: word(key, j) = mix(key + PHI*(j+1)), mix = the splitmix64 output function,
+ *     key = mix(mix(seed + PHI) + PHI*((stream << 32) | client) + PHI), PHI = 0x9E3779B97F4A7C15;
+ *     streams: 0 = signs, 1 = sub-sampling, 2 = packet loss.
+ *   - Bit budget b is passed as b_q8 = 256*b.  Supported: 256, 512, 1024 (b = 1, 2, 4, the
+ *     2^b-level Lloyd-Max quantizer of N(0,1), Sec. 3) and 128 (b = 1/2: the b = 1 quantizer,
+ *     then of every two consecutive rotated coordinates (2g, 2g+1) only the one at offset
+ *     bit (g & 63) of word (g >> 6) of the SUB-SAMPLING stream is sent; Sec. 4.1, applied after
+ *     the rotation, so the receiver treats the rest like lost coordinates, Sec. 4.2).
+ *   - Index of a coordinate = rank of its interval in ascending order (0 = most negative).  At an
+ *     interval endpoint the interval closer to zero is taken; z = 0 belongs to the non-negative
+ *     side (Sec. 2.2.1 and its footnote).
+ *   - Message = 64-byte little-endian header + payload of uint32 words:
+ *       off  0 u32 magic 0x4E454445   off  4 u32 log2(D)      off  8 u64 d
+ *       off 16 u32 b_q8               off 20 u32 client id    off 24 u32 status bits
+ *       off 28 u32 0                  off 32 f64 S            off 40 f64 |x|^2
+ *       off 48 f64 <R(x), Q>          off 56 u64 seed
+ *     Payload: the j-th transmitted index occupies bits [(j*b) mod 32, +b) of word floor(j*b/32),
+ *     least significant bit first; the payload is padded with zero bits to a multiple of 64 bits.
+ *     S = |x|^2 / <R(x), Q(eta R(x))> is the sender's scale (Sec. 2.3), always computed over all
+ *     D coordinates (the sender does not change under loss or sub-sampling, Sec. 4.2).
+ *   - A packet is 1024 consecutive rotated coordinates (one packet if D < 1024).  A received-packet
+ *     bitmap has bit (j & 31) of uint32 word (j >> 5) set when packet j arrived.
+ */
+#ifndef EDEN_H
+#define EDEN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct eden_ctx eden_ctx;
+
+typedef enum eden_status {
+    EDEN_OK = 0,
+    EDEN_ERR_INVALID_ARG = -1,      /* NULL pointer, d = 0, d > 2^27, n = 0, unsupported budget, n or d above the context's limits */
+    EDEN_ERR_CAPACITY = -2,         /* a message buffer is smaller than eden_message_bytes() */
+    EDEN_ERR_HIP = -3,              /* a HIP runtime call failed */
+    EDEN_ERR_NO_DEVICE = -4         /* no usable gfx950 device / device index out of range */
+} eden_status;
+
+/* bits of the status word in a message header and of the device status word */
+#define EDEN_DEV_ZERO_VECTOR     1u   /* |x|^2 == 0: S = 0, payload zero, decodes to nothing (Sec. 2.1 footnote) */
+#define EDEN_DEV_NONFINITE       2u   /* |x|^2 is inf or nan: message marked, decodes to nothing */
+#define EDEN_DEV_HEADER_MISMATCH 4u   /* decode: header disagrees with the call (magic, D, d, budget, client, seed) */
+#define EDEN_DEV_NOTHING_ARRIVED 8u   /* decode: every packet of a message was lost; it contributes nothing */
+
+#define EDEN_HEADER_BYTES 64
+#define EDEN_PACKET_COORDS 1024
+#define EDEN_MAX_LOG2_D 27
+
+/* Creates a context on HIP device `hip_device` able to handle vectors up to d_max coordinates and
+ * batches up to n_max senders per call.  Allocates the workspace: min(n_max, 32) * 4 * D_max bytes for the
+ * transform's intermediate passes (none if D_max <= 4096) plus a few KiB of partial sums per sender;
+ * solves the Lloyd-Max tables of Sec. 3 in double precision on the host and uploads them.
+ * On failure *out is NULL. */
+int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device);
+
+/* Frees the workspace.  The caller must have synchronised the streams it used. */
+int eden_destroy(eden_ctx *ctx);
+
+/* Header + payload size in bytes of one message for dimension d and budget b_q8; 0 if unsupported. */
+size_t eden_message_bytes(uint64_t d, uint32_t b_q8);
+
+/* Sender side for n senders at once (each sender is independent; batching only amortises launches).
+ *   x_dev[c]        device fp32[d], sender c's vector, read-only               (Sec. 2.1)
+ *   client_ids[c]   the id that selects sender c's independent rotation         (Sec. 2.1, 2.2.1)
+ *   b_q8[c]         sender c's bit budget                                        (Sec. 4.1)
+ *   seed            the round's shared seed                                      (Sec. 2.1)
+ *   msgs_dev[c]     device buffer of at least eden_message_bytes(d, b_q8[c]) bytes, 16-byte aligned,
+ *                   written: header then payload
+ *   msg_capacity[c] size of that buffer in bytes
+ * Per sender: u = H (s o x) by a fast Walsh-Hadamard transform, |x|^2, indices of u/|x| against the
+ * Lloyd-Max thresholds, <R(x),Q>, S, packed payload. */
+int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids,
+                const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
+                void *const *msgs_dev, const size_t *msg_capacity, void *stream);
+
+/* Receiver side for a batch of n messages: for each, unpack, centroid lookup, zero the coordinates
+ * that were not sampled or whose packet did not arrive, multiply by S/p with p = (coordinates that
+ * arrived)/D counted from the bitmap (Sec. 4.2), inverse rotation (Sec. 2.2.2); the n reconstructions
+ * are summed in registers and added once to acc_dev:  acc[i] += sum_c x^_c[i],  i < d.
+ *   msgs_dev[c]          device message as written by eden_encode, read-only
+ *   client_ids[c], b_q8[c], seed, d   what the receiver agreed with sender c; checked against the header
+ *   recv_bitmaps_dev     NULL (nothing lost) or host array of n device pointers, each NULL or a
+ *                        bitmap of ceil(max(1, D/1024) / 32) uint32 words
+ *   acc_dev              device fp32[d], read and written; the caller zeroes it once per round */
+int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
+                           const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
+                           const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream);
+
+/* mean[i] = acc[i] / n for i < d (Sec. 2.2.2: the plain average, also with mixed budgets).
+ * mean_dev may alias acc_dev. */
+int eden_finalize_mean(eden_ctx *ctx, const float *acc_dev, uint64_t d, uint32_t n, float *mean_dev,
+                       void *stream);
+
+/* Synchronises `stream`, returns the OR of the device status bits raised since the last call of this
+ * function, and clears them. */
+int eden_last_device_status(eden_ctx *ctx, void *stream, uint32_t *status_out);
+
+/* Test helpers: the kernels' own hash streams, written out so that masks can be compared bit for bit.
+ *   eden_make_loss_bitmap   packet j of `client` is dropped iff the top 32 bits of word(LOSS key, j)
+ *                           are below drop_q32 (drop probability drop_q32 / 2^32); writes
+ *                           ceil(max(1, D/1024)/32) words
+ *   eden_make_sign_bits     writes D/64 (at least 1) uint64 words of the SIGN stream
+ *   eden_make_subsample_bits writes max(1, D/128) uint64 words of the SUB-SAMPLING stream */
+int eden_make_loss_bitmap(eden_ctx *ctx, uint64_t seed, uint32_t client_id, uint64_t D,
+                          uint32_t drop_q32, uint32_t *bitmap_dev, void *stream);
+int eden_make_sign_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, uint64_t D,
+                        uint64_t *bits_dev, void *stream);
+int eden_make_subsample_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, uint64_t D,
+                             uint64_t *bits_dev, void *stream);
+
+/* Copies the library's own Lloyd-Max tables for an integer budget `bits` (1..4) to host arrays:
+ * thresholds[2^bits - 1] and centroids[2^bits], ascending, double precision (Sec. 3). */
+int eden_get_tables(uint32_t bits, double *thresholds, double *centroids);
+
+const char *eden_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EDEN_H */

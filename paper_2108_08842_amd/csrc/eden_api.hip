@@ -1,0 +1,311 @@
+// C ABI of the EDEN library (see include/eden.h for the contract of every call).
+// Host code only: argument checks, the pass plan, workspace, launches.  Every step of the path runs
+// in the kernels of eden_kernels.hip.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "eden.h"
+#include "eden_device.h"
+#include "eden_kernels.h"
+#include "eden_tables.h"
+
+using namespace eden;
+
+struct eden_ctx {
+    int device;
+    uint64_t d_max;
+    int log2D_max;
+    uint32_t n_max;          // senders per call the workspace was sized for (chunks of kMaxBatch are used)
+    uint32_t slots;          // workspace slots = min(n_max, kMaxBatch)
+    float *T;                // slots * D_max floats (nullptr if D_max <= 4096)
+    double *partials;        // slots * partial_stride doubles
+    uint32_t partial_stride;
+    EncScratch *enc_scratch; // slots
+    DecScratch *dec_scratch; // slots
+    DevTables *tables;
+    uint32_t *dev_status;
+};
+
+namespace {
+
+int ceil_log2(uint64_t d) {
+    int l = 0;
+    while ((1ull << l) < d) ++l;
+    return l;
+}
+
+// Split of the index bits above the lo pass into hi passes of at most 6 bits, as even as possible.
+struct Plan {
+    int nhi;
+    int M[4];
+    int p[4];   // lowest bit of each hi pass, ascending
+};
+Plan make_plan(int log2D) {
+    Plan pl{};
+    const int hi_bits = log2D - kLoBits;
+    if (hi_bits <= 0) return pl;
+    pl.nhi = (hi_bits + 5) / 6;
+    int pos = kLoBits;
+    for (int i = 0; i < pl.nhi; ++i) {
+        const int m = hi_bits / pl.nhi + (i < hi_bits % pl.nhi ? 1 : 0);
+        pl.M[i] = m;
+        pl.p[i] = pos;
+        pos += m;
+    }
+    return pl;
+}
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+        if (prev == dev) prev = -1;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+size_t payload_bytes(uint64_t D, int bits, int k) {
+    const uint64_t nbits = (D / (uint64_t)k) * (uint64_t)bits;
+    return (size_t)(((nbits + 63) / 64) * 8);
+}
+
+bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+}  // namespace
+
+extern "C" {
+
+size_t eden_message_bytes(uint64_t d, uint32_t b_q8) {
+    int bits, k;
+    if (d == 0 || d > (1ull << EDEN_MAX_LOG2_D) || !budget_of(b_q8, bits, k)) return 0;
+    const uint64_t D = 1ull << ceil_log2(d);
+    if (D < (uint64_t)k) return 0;
+    return EDEN_HEADER_BYTES + payload_bytes(D, bits, k);
+}
+
+int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) {
+    if (!out) return EDEN_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (d_max == 0 || d_max > (1ull << EDEN_MAX_LOG2_D) || n_max == 0) return EDEN_ERR_INVALID_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || hip_device < 0 || hip_device >= ndev) return EDEN_ERR_NO_DEVICE;
+    DeviceGuard guard(hip_device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+
+    eden_ctx *ctx = new (std::nothrow) eden_ctx();
+    if (!ctx) return EDEN_ERR_HIP;
+    ctx->device = hip_device;
+    ctx->d_max = d_max;
+    ctx->log2D_max = ceil_log2(d_max);
+    ctx->n_max = n_max;
+    ctx->slots = n_max < (uint32_t)kMaxBatch ? n_max : (uint32_t)kMaxBatch;
+    const uint64_t D_max = 1ull << ctx->log2D_max;
+    ctx->partial_stride = (uint32_t)(D_max / 256 + 16);
+
+    bool ok = true;
+    if (ctx->log2D_max > kLoBits)
+        ok = ok && hipMalloc(&ctx->T, (size_t)ctx->slots * D_max * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->partials, (size_t)ctx->slots * ctx->partial_stride * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->enc_scratch, ctx->slots * sizeof(EncScratch)) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->dec_scratch, ctx->slots * sizeof(DecScratch)) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->tables, sizeof(DevTables)) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->dev_status, sizeof(uint32_t)) == hipSuccess;
+    if (ok) {
+        DevTables host{};
+        for (int bits = 1; bits <= EDEN_MAX_TABLE_BITS; ++bits) {
+            const EdenHalfTable *ht = eden_half_table(bits);
+            for (int i = 0; i < ht->half_levels; ++i) { host.t[bits][i] = ht->t[i]; host.q[bits][i] = ht->q[i]; }
+        }
+        ok = ok && hipMemcpy(ctx->tables, &host, sizeof(host), hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemset(ctx->enc_scratch, 0, ctx->slots * sizeof(EncScratch)) == hipSuccess;
+        ok = ok && hipMemset(ctx->dec_scratch, 0, ctx->slots * sizeof(DecScratch)) == hipSuccess;
+        ok = ok && hipMemset(ctx->dev_status, 0, sizeof(uint32_t)) == hipSuccess;
+        ok = ok && hipDeviceSynchronize() == hipSuccess;
+    }
+    if (!ok) {
+        eden_destroy(ctx);
+        return EDEN_ERR_HIP;
+    }
+    *out = ctx;
+    return EDEN_OK;
+}
+
+int eden_destroy(eden_ctx *ctx) {
+    if (!ctx) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    bool ok = guard.ok;
+    void *ptrs[] = {ctx->T, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
+    for (void *p : ptrs)
+        if (p) ok = (hipFree(p) == hipSuccess) && ok;
+    delete ctx;
+    return ok ? EDEN_OK : EDEN_ERR_HIP;
+}
+
+int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8,
+                uint32_t n, uint64_t d, uint64_t seed, void *const *msgs_dev, const size_t *msg_capacity,
+                void *stream) {
+    if (!ctx || !x_dev || !client_ids || !b_q8 || !msgs_dev || !msg_capacity) return EDEN_ERR_INVALID_ARG;
+    if (n == 0 || n > ctx->n_max || d == 0 || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
+    for (uint32_t c = 0; c < n; ++c) {
+        if (!x_dev[c] || !msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
+        const size_t need = eden_message_bytes(d, b_q8[c]);
+        if (need == 0) return EDEN_ERR_INVALID_ARG;
+        if (msg_capacity[c] < need) return EDEN_ERR_CAPACITY;
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int log2D = ceil_log2(d);
+    const Plan pl = make_plan(log2D);
+
+    for (uint32_t first = 0; first < n; first += kMaxBatch) {
+        const uint32_t nb = (n - first < (uint32_t)kMaxBatch) ? n - first : (uint32_t)kMaxBatch;
+        EncBatch B;
+        std::memset(&B, 0, sizeof(B));
+        for (uint32_t i = 0; i < nb; ++i) {
+            B.x[i] = x_dev[first + i];
+            B.msg[i] = msgs_dev[first + i];
+            B.client[i] = client_ids[first + i];
+            B.b_q8[i] = b_q8[first + i];
+        }
+        if (pl.nhi == 0) {
+            launch_enc_small(B, nb, d, log2D, seed, ctx->tables, ctx->dev_status, st);
+        } else {
+            // top bits first; the first pass reads x, the rest work in place on the workspace
+            const int top = pl.nhi - 1;
+            launch_enc_hi_first(pl.M[top], B, nb, d, log2D, pl.p[top], seed, ctx->T, ctx->partials, ctx->partial_stride,
+                                ctx->enc_scratch, ctx->tables, st);
+            for (int i = top - 1; i >= 0; --i) launch_hi_mid(pl.M[i], nb, ctx->T, log2D, pl.p[i], st);
+            launch_enc_lo(B, nb, d, log2D, seed, ctx->T, ctx->partials, ctx->partial_stride, ctx->enc_scratch,
+                          ctx->dev_status, st);
+        }
+        if (!launch_ok()) return EDEN_ERR_HIP;
+    }
+    return EDEN_OK;
+}
+
+int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
+                           const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
+                           const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream) {
+    if (!ctx || !msgs_dev || !client_ids || !b_q8 || !acc_dev) return EDEN_ERR_INVALID_ARG;
+    if (n == 0 || n > ctx->n_max || d == 0 || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
+    for (uint32_t c = 0; c < n; ++c) {
+        if (!msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
+        if (eden_message_bytes(d, b_q8[c]) == 0) return EDEN_ERR_INVALID_ARG;
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int log2D = ceil_log2(d);
+    const Plan pl = make_plan(log2D);
+
+    for (uint32_t first = 0; first < n; first += kMaxBatch) {
+        const uint32_t nb = (n - first < (uint32_t)kMaxBatch) ? n - first : (uint32_t)kMaxBatch;
+        DecBatch B;
+        std::memset(&B, 0, sizeof(B));
+        for (uint32_t i = 0; i < nb; ++i) {
+            B.msg[i] = msgs_dev[first + i];
+            B.bitmap[i] = recv_bitmaps_dev ? recv_bitmaps_dev[first + i] : nullptr;
+            B.client[i] = client_ids[first + i];
+            B.b_q8[i] = b_q8[first + i];
+        }
+        if (pl.nhi == 0) {
+            launch_dec_small(B, nb, d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
+        } else {
+            launch_dec_prepare(B, nb, d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
+            launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
+            for (int i = 0; i < pl.nhi - 1; ++i) launch_hi_mid(pl.M[i], nb, ctx->T, log2D, pl.p[i], st);
+            const int top = pl.nhi - 1;
+            launch_dec_hi_last(pl.M[top], B, nb, d, log2D, pl.p[top], seed, ctx->T, acc_dev, st);
+        }
+        if (!launch_ok()) return EDEN_ERR_HIP;
+    }
+    return EDEN_OK;
+}
+
+int eden_finalize_mean(eden_ctx *ctx, const float *acc_dev, uint64_t d, uint32_t n, float *mean_dev, void *stream) {
+    if (!ctx || !acc_dev || !mean_dev || d == 0 || d > ctx->d_max || n == 0) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    launch_finalize_mean(acc_dev, d, n, mean_dev, static_cast<hipStream_t>(stream));
+    return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
+}
+
+int eden_last_device_status(eden_ctx *ctx, void *stream, uint32_t *status_out) {
+    if (!ctx || !status_out) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t v = 0;
+    if (hipMemcpyAsync(&v, ctx->dev_status, sizeof(v), hipMemcpyDeviceToHost, st) != hipSuccess) return EDEN_ERR_HIP;
+    if (hipMemsetAsync(ctx->dev_status, 0, sizeof(uint32_t), st) != hipSuccess) return EDEN_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return EDEN_ERR_HIP;
+    *status_out = v;
+    return EDEN_OK;
+}
+
+static bool pow2_dim(uint64_t D) { return D >= 1 && D <= (1ull << EDEN_MAX_LOG2_D) && (D & (D - 1)) == 0; }
+
+int eden_make_loss_bitmap(eden_ctx *ctx, uint64_t seed, uint32_t client_id, uint64_t D, uint32_t drop_q32,
+                          uint32_t *bitmap_dev, void *stream) {
+    if (!ctx || !bitmap_dev || !pow2_dim(D)) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    const uint32_t npk = D >= EDEN_PACKET_COORDS ? (uint32_t)(D / EDEN_PACKET_COORDS) : 1u;
+    launch_loss_bitmap(stream_key(seed, kStreamLoss, client_id), npk, drop_q32, bitmap_dev,
+                       static_cast<hipStream_t>(stream));
+    return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
+}
+
+int eden_make_sign_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, uint64_t D, uint64_t *bits_dev, void *stream) {
+    if (!ctx || !bits_dev || !pow2_dim(D)) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    const uint64_t nwords = D >= 64 ? D / 64 : 1;
+    launch_hash_bits(stream_key(seed, kStreamSign, client_id), nwords, bits_dev, static_cast<hipStream_t>(stream));
+    return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
+}
+
+int eden_make_subsample_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, uint64_t D, uint64_t *bits_dev,
+                             void *stream) {
+    if (!ctx || !bits_dev || !pow2_dim(D)) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    const uint64_t nwords = D >= 128 ? D / 128 : 1;
+    launch_hash_bits(stream_key(seed, kStreamSubsample, client_id), nwords, bits_dev, static_cast<hipStream_t>(stream));
+    return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
+}
+
+int eden_get_tables(uint32_t bits, double *thresholds, double *centroids) {
+    const EdenHalfTable *ht = eden_half_table((int)bits);
+    if (!ht || !thresholds || !centroids) return EDEN_ERR_INVALID_ARG;
+    const int h = ht->half_levels;
+    for (int i = 0; i < h; ++i) {
+        centroids[h + i] = ht->q[i];
+        centroids[h - 1 - i] = -ht->q[i];
+    }
+    thresholds[h - 1] = 0.0;
+    for (int i = 1; i < h; ++i) {
+        thresholds[h - 1 + i] = ht->t[i];
+        thresholds[h - 1 - i] = -ht->t[i];
+    }
+    return EDEN_OK;
+}
+
+const char *eden_strerror(int status) {
+    switch (status) {
+        case EDEN_OK: return "ok";
+        case EDEN_ERR_INVALID_ARG: return "invalid argument";
+        case EDEN_ERR_CAPACITY: return "message buffer too small";
+        case EDEN_ERR_HIP: return "HIP runtime error";
+        case EDEN_ERR_NO_DEVICE: return "no usable device";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

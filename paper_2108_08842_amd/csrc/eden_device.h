@@ -1,0 +1,134 @@
+// Device-side building blocks shared by the EDEN kernels (gfx950, wave64).
+#ifndef EDEN_DEVICE_H
+#define EDEN_DEVICE_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace eden {
+
+constexpr int kMaxBatch = 32;            // senders handled by one launch; larger batches are chunked
+constexpr int kLoBits = 12;              // index bits transformed by the contiguous (wave-tile) pass
+constexpr int kLoTile = 1 << kLoBits;    // 4096 coordinates = 64 lanes x 64 registers
+constexpr int kLdsRow = 68;              // padded row length (floats) of the 64x64 LDS transpose
+
+// ---- shared randomness (Sec. 2.1): counter hash = splitmix64 stream started at a per-(seed,stream,client) key
+constexpr uint64_t kPhi = 0x9E3779B97F4A7C15ull;
+enum : uint32_t { kStreamSign = 0, kStreamSubsample = 1, kStreamLoss = 2 };
+
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+__host__ __device__ inline uint64_t stream_key(uint64_t seed, uint32_t stream, uint32_t client) {
+    const uint64_t tag = ((uint64_t)stream << 32) | (uint64_t)client;
+    return mix64(mix64(seed + kPhi) + kPhi * tag + kPhi);
+}
+__host__ __device__ inline uint64_t hash_word(uint64_t key, uint64_t j) { return mix64(key + kPhi * (j + 1)); }
+
+// ---- bit budgets (Sec. 4.1): b_q8 = 256 b -> bits per transmitted index, keep one coordinate in k
+__host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
+    if (b_q8 == 128) { bits = 1; k = 2; return true; }
+    if (b_q8 == 256 || b_q8 == 512 || b_q8 == 1024) { bits = (int)(b_q8 >> 8); k = 1; return true; }
+    return false;
+}
+
+// ---- message header (64 bytes, little endian)
+struct MsgHeader {
+    uint32_t magic, log2D;
+    uint64_t d;
+    uint32_t b_q8, client, status, zero;
+    double S, N2, IP;
+    uint64_t seed;
+};
+static_assert(sizeof(MsgHeader) == 64, "header layout");
+constexpr uint32_t kMagic = 0x4E454445u;
+
+// ---- device copies of the Lloyd-Max tables (positive halves, Sec. 3), index [bits][k]
+struct DevTables {
+    double t[5][8];
+    double q[5][8];
+};
+
+// per-sender scalars that travel between the passes of one encode
+struct EncScratch {
+    double n2;              // |x|^2 (Sec. 2.2.1: equals |R(x)|^2)
+    float thr[8];           // positive thresholds of I_b times |x|: compared against |H(s o x)|
+    float qpos[8];          // positive centroids
+    unsigned done_first;    // blocks of the first pass that have finished
+    unsigned done_last;     // blocks of the last pass that have finished
+    unsigned pad[2];
+};
+
+// per-message scalars of one decode
+struct DecScratch {
+    float deq[16];          // (S / (p sqrt(D))) * q_l for every index l (all zero if the message contributes nothing)
+    uint32_t flags;
+    uint32_t pad[3];
+};
+
+struct EncBatch {
+    const float *x[kMaxBatch];
+    void *msg[kMaxBatch];
+    uint32_t client[kMaxBatch];
+    uint32_t b_q8[kMaxBatch];
+};
+struct DecBatch {
+    const void *msg[kMaxBatch];
+    const uint32_t *bitmap[kMaxBatch];
+    uint32_t client[kMaxBatch];
+    uint32_t b_q8[kMaxBatch];
+};
+
+// ---- wave-level helpers
+__device__ inline uint32_t lane_id() { return threadIdx.x & 63u; }
+__device__ inline uint32_t wave_in_block() { return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); }
+
+// LDS traffic of one wave is processed in issue order; this only stops the compiler from moving
+// the reads of a transpose above the writes of other lanes.
+__device__ inline void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// v or -v per lane, chosen by bit `lane` of a wave-uniform 64-bit mask (one VALU op: the mask is
+// used directly as the lane-select operand).
+__device__ inline float negate_where(float v, uint64_t mask) {
+    float r;
+    asm("v_cndmask_b32_e64 %0, %1, -%1, %2" : "=v"(r) : "v"(v), "s"(mask));
+    return r;
+}
+
+// In-register Walsh-Hadamard butterflies over the register index: (a,b) -> (a+b, a-b) at spans 1..N/2.
+template <int N>
+__device__ inline void fwht_regs(float (&v)[N]) {
+#pragma unroll
+    for (int h = 1; h < N; h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < N; i += 2 * h) {
+#pragma unroll
+            for (int j = i; j < i + h; ++j) {
+                const float a = v[j], b = v[j + h];
+                v[j] = a + b;
+                v[j + h] = a - b;
+            }
+        }
+    }
+}
+
+__device__ inline double wave_sum(double v) {          // fixed order: deterministic
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ inline uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace eden
+#endif

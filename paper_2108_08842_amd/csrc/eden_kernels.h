@@ -1,0 +1,32 @@
+// Host-callable launchers of the EDEN kernels (all asynchronous on the given stream).
+#ifndef EDEN_KERNELS_H
+#define EDEN_KERNELS_H
+
+#include "eden.h"
+#include "eden_device.h"
+
+namespace eden {
+
+void launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
+                         double *partials, uint32_t partial_stride, EncScratch *scratch, const DevTables *tab,
+                         hipStream_t st);
+void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
+void launch_dec_hi_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed,
+                        const float *T, float *acc, hipStream_t st);
+void launch_enc_lo(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+                   double *partials, uint32_t partial_stride, EncScratch *scratch, uint32_t *dev_status,
+                   hipStream_t st);
+void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+                        DecScratch *scratch, uint32_t *dev_status, hipStream_t st);
+void launch_dec_lo(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, float *T,
+                   hipStream_t st);
+void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st);
+void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+                      uint32_t *dev_status, hipStream_t st);
+void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+                      float *acc, uint32_t *dev_status, hipStream_t st);
+void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st);
+void launch_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t *bitmap, hipStream_t st);
+
+}  // namespace eden
+#endif

@@ -1,0 +1,675 @@
+// HIP kernels of the EDEN hot path for gfx950 (MI355X).  Wave64 throughout.
+//
+// The rotation R x = D^-1/2 H (s o x) (Sec. 2.2.1; Sec. 5: randomized Hadamard transform) is computed
+// unnormalised, u = H (s o x), with the D^-1/2 folded into scalars.  The index bits of the padded
+// dimension D = 2^L are split into groups; one kernel ("pass") transforms one group:
+//
+//   lo pass   bits 0..11   one wave owns 4096 consecutive coordinates: 64 registers per lane, six
+//                          butterfly stages in registers, a 64x64 transpose through LDS, six more.
+//   hi pass   bits p..p+M-1 (M <= 6): one wave owns 2^M rows of 64 consecutive coordinates at stride 2^p;
+//                          every lane keeps one column in registers; no LDS at all.
+//
+// Encode runs the hi passes first (the first one reads x, applies the signs and sums |x|^2) and the lo
+// pass last, fused with quantization, <R(x),Q> and bit packing (Sec. 2.2.1, 2.3).  Decode runs the lo
+// pass first, fused with unpacking and centroid lookup (Sec. 2.2.2, 4.2), and the hi passes after it; the
+// last one applies the signs and sums the senders in registers before touching the accumulator once.
+// D <= 4096 is handled by one workgroup per sender with the vector resident in LDS.
+#include "eden_device.h"
+#include "eden_kernels.h"
+
+namespace eden {
+
+// ------------------------------------------------------------------------------------------------
+// block-level deterministic sum of one double per thread; result valid in thread 0
+template <int THREADS>
+__device__ inline double block_sum(double v, double *red /* shared, THREADS/64 */) {
+    v = wave_sum(v);
+    const uint32_t w = threadIdx.x >> 6;
+    if (lane_id() == 0) red[w] = v;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < THREADS / 64; ++i) total += red[i];
+    }
+    __syncthreads();
+    return total;
+}
+
+// Writes this block's partial and finds out whether it is the last block of its sender to do so.
+// The last block then sums every partial in index order, so the result does not depend on timing.
+template <int THREADS>
+__device__ inline bool publish_partial(double block_total, double *partials, uint32_t nblocks,
+                                       unsigned *done_counter, double *red, double &grand_total) {
+    __shared__ bool last;
+    if (threadIdx.x == 0) {
+        partials[blockIdx.x] = block_total;
+        __threadfence();
+        const unsigned prev = atomicAdd(done_counter, 1u);
+        last = (prev == nblocks - 1);
+    }
+    __syncthreads();
+    if (!last) return false;
+    __threadfence();
+    double s = 0.0;
+    for (uint32_t i = threadIdx.x; i < nblocks; i += THREADS) s += partials[i];
+    grand_total = block_sum<THREADS>(s, red);
+    if (threadIdx.x == 0) *done_counter = 0;      // ready for the next call
+    return true;
+}
+
+// After |x|^2 is known: the thresholds of I_b scaled to the unnormalised transform.
+// z = eta R(x) = u / |x| (Sec. 2.2.1 with d -> D), so z > t  <=>  u > t |x|.
+__device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8, const DevTables *tab) {
+    int bits, k;
+    budget_of(b_q8, bits, k);
+    s->n2 = n2;
+    const double norm = sqrt(n2);
+    for (int i = 0; i < 8; ++i) {
+        s->thr[i] = (float)(tab->t[bits][i] * norm);
+        s->qpos[i] = (float)tab->q[bits][i];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// hi passes
+template <int M>
+__device__ inline void hi_tile_origin(uint32_t tile, int p, uint64_t &base) {
+    const uint32_t cb_bits = (uint32_t)p - 6u;                  // 2^(p-6) blocks of 64 columns
+    const uint32_t colblock = tile & ((1u << cb_bits) - 1u);
+    const uint32_t upper = tile >> cb_bits;
+    base = ((uint64_t)upper << (p + M)) | ((uint64_t)colblock << 6);
+}
+
+// Encode, first pass: x -> T.  Zero padding (Sec. 5: the transform needs a power of two), the sign
+// diagonal of the rotation from the shared seed (Sec. 2.1), |x|^2 for eta and S (Sec. 2.2.1, 2.3).
+template <int M>
+__global__ __launch_bounds__(256) void k_enc_hi_first(EncBatch B, uint64_t d, int log2D, int p, uint64_t seed,
+                                                      float *T, double *partials, uint32_t partial_stride,
+                                                      EncScratch *scratch, const DevTables *tab) {
+    constexpr int R = 1 << M;
+    __shared__ double red[4];
+    const uint32_t c = blockIdx.y;
+    const uint32_t lane = lane_id();
+    const uint32_t tile = blockIdx.x * 4u + wave_in_block();
+    const uint32_t ntiles = 1u << (log2D - 6 - M);
+    double n2 = 0.0;
+    if (tile < ntiles) {
+        uint64_t base;
+        hi_tile_origin<M>(tile, p, base);
+        const float *x = B.x[c];
+        float v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint64_t i = base + ((uint64_t)r << p) + lane;
+            v[r] = (i < d) ? __builtin_nontemporal_load(x + i) : 0.0f;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) n2 += (double)v[r] * (double)v[r];
+        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint64_t word = hash_word(key, (base + ((uint64_t)r << p)) >> 6);
+            v[r] = negate_where(v[r], word) + 0.0f;          // + 0 turns -0 into +0: no negative zeros enter
+        }
+        fwht_regs<R>(v);
+        float *Tc = T + ((size_t)c << log2D);
+#pragma unroll
+        for (int r = 0; r < R; ++r) Tc[base + ((uint64_t)r << p) + lane] = v[r];
+    }
+    const double block_total = block_sum<256>(n2, red);
+    double total;
+    if (publish_partial<256>(block_total, partials + (size_t)c * partial_stride, gridDim.x,
+                             &scratch[c].done_first, red, total)) {
+        if (threadIdx.x == 0) fill_enc_scratch(&scratch[c], total, B.b_q8[c], tab);
+    }
+}
+
+// Middle pass, in place on the workspace (tiles are disjoint).
+template <int M>
+__global__ __launch_bounds__(256) void k_hi_mid(float *T, int log2D, int p) {
+    constexpr int R = 1 << M;
+    const uint32_t c = blockIdx.y;
+    const uint32_t lane = lane_id();
+    const uint32_t tile = blockIdx.x * 4u + wave_in_block();
+    const uint32_t ntiles = 1u << (log2D - 6 - M);
+    if (tile >= ntiles) return;
+    uint64_t base;
+    hi_tile_origin<M>(tile, p, base);
+    float *Tc = T + ((size_t)c << log2D) + base + lane;
+    float v[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) v[r] = Tc[(uint64_t)r << p];
+    fwht_regs<R>(v);
+#pragma unroll
+    for (int r = 0; r < R; ++r) Tc[(uint64_t)r << p] = v[r];
+}
+
+// Decode, last pass: for every sender of the batch finish H, apply its sign diagonal (R^-1 = s o D^-1/2 H,
+// Sec. 2.2.2; D^-1/2 is already inside the dequantization scale) and add; then acc += sum (i < d).
+template <int M>
+__global__ __launch_bounds__(256) void k_dec_hi_last(DecBatch B, uint32_t n, uint64_t d, int log2D, int p,
+                                                     uint64_t seed, const float *T, float *acc) {
+    constexpr int R = 1 << M;
+    const uint32_t lane = lane_id();
+    const uint32_t tile = blockIdx.x * 4u + wave_in_block();
+    const uint32_t ntiles = 1u << (log2D - 6 - M);
+    if (tile >= ntiles) return;
+    uint64_t base;
+    hi_tile_origin<M>(tile, p, base);
+    if (base >= d) return;                                   // whole tile lies in the padding (rows only go up)
+    float sum[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) sum[r] = 0.0f;
+    for (uint32_t c = 0; c < n; ++c) {
+        const float *Tc = T + ((size_t)c << log2D) + base + lane;
+        float v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] = __builtin_nontemporal_load(Tc + ((uint64_t)r << p));
+        fwht_regs<R>(v);
+        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint64_t word = hash_word(key, (base + ((uint64_t)r << p)) >> 6);
+            sum[r] += negate_where(v[r], word);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint64_t i = base + ((uint64_t)r << p) + lane;
+        if (i < d) acc[i] += sum[r];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// lo pass, encode side: T -> payload.  Quantization to the Lloyd-Max intervals (Sec. 2.2.1, Sec. 3),
+// <R(x), Q(eta R(x))> for the scale (Sec. 2.3), sub-sampling for b = 1/2 (Sec. 4.1), packing.
+template <int BITS>
+__device__ inline void quantize_pack(const float (&v)[64], const EncScratch *s, uint32_t *out /* 2*BITS words */,
+                                     float &ip) {
+    constexpr int H = 1 << (BITS - 1);
+    constexpr int PER = 32 / BITS;
+    float thr[H], qp[H];
+#pragma unroll
+    for (int i = 0; i < H; ++i) { thr[i] = s->thr[i]; qp[i] = s->qpos[i]; }
+    ip = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 2 * BITS; ++w) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const float u = v[w * PER + e];
+            const float a = fabsf(u);
+            uint32_t mag = 0;
+            float qa = qp[0];
+#pragma unroll
+            for (int t = 1; t < H; ++t) {                      // strict: a value on a threshold stays in the
+                const bool above = a > thr[t];                 // interval closer to zero (Sec. 2.2.1 footnote)
+                mag = above ? (uint32_t)t : mag;
+                qa = above ? qp[t] : qa;
+            }
+            ip = fmaf(a, qa, ip);
+            const uint32_t neg = __float_as_uint(u) >> 31;     // u = +0 counts as non-negative
+            const uint32_t code = neg ? (uint32_t)(H - 1) - mag : (uint32_t)H + mag;
+            word |= code << (e * BITS);
+        }
+        out[w] = word;
+    }
+}
+
+__global__ __launch_bounds__(128) void k_enc_lo(EncBatch B, uint64_t d, int log2D, uint64_t seed, const float *T,
+                                                double *partials, uint32_t partial_stride, EncScratch *scratch,
+                                                uint32_t *dev_status) {
+    __shared__ float lds[2][64 * kLdsRow];
+    __shared__ double red[2];
+    const uint32_t c = blockIdx.y;
+    const uint32_t lane = lane_id();
+    const uint32_t wv = wave_in_block();
+    const uint32_t tile = blockIdx.x * 2u + wv;               // D >= 2^13: always an even number of tiles
+    const float *Tc = T + ((size_t)c << log2D) + ((size_t)tile << kLoBits);
+    float v[64];
+#pragma unroll
+    for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(Tc + 64 * j + lane);
+    fwht_regs<64>(v);                                          // index bits 6..11
+    float *L = lds[wv];
+#pragma unroll
+    for (int j = 0; j < 64; ++j) L[j * kLdsRow + lane] = v[j];
+    wave_lds_sync();
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const float4 t = *reinterpret_cast<const float4 *>(&L[lane * kLdsRow + 4 * q]);
+        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+    }
+    fwht_regs<64>(v);                                          // index bits 0..5; lane owns 64 consecutive u_i
+
+    const EncScratch *s = &scratch[c];
+    const double n2 = s->n2;
+    const bool valid = (n2 > 0.0) && (n2 < INFINITY);         // false for 0, inf, nan
+    const uint32_t b_q8 = B.b_q8[c];
+    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const size_t seg = (size_t)tile * 64 + lane;               // index of this lane's run of 64 coordinates
+    float ip = 0.0f;
+    if (b_q8 == 256 || b_q8 == 128) {
+        // I_1 = {(-inf,0],[0,inf)}: the index is the sign; <R(x),Q> = q_1 * sum |u| / sqrt(D)
+        float sa = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 64; ++k) sa += fabsf(v[k]);
+        ip = sa * s->qpos[0];
+        if (b_q8 == 256) {
+            uint32_t w0 = 0, w1 = 0;                           // shift the sign bits in, last coordinate first
+#pragma unroll
+            for (int k = 31; k >= 0; --k) w0 = __builtin_amdgcn_alignbit(w0, __float_as_uint(v[k]), 31);
+#pragma unroll
+            for (int k = 63; k >= 32; --k) w1 = __builtin_amdgcn_alignbit(w1, __float_as_uint(v[k]), 31);
+            uint2 o = make_uint2(valid ? ~w0 : 0u, valid ? ~w1 : 0u);   // index 1 = non-negative
+            *reinterpret_cast<uint2 *>(payload + seg * 2) = o;
+        } else {
+            // b = 1/2: of each pair (2g, 2g+1) send the coordinate chosen by the sub-sampling stream
+            uint32_t ev = 0, od = 0;
+#pragma unroll
+            for (int g = 31; g >= 0; --g) {
+                ev = __builtin_amdgcn_alignbit(ev, __float_as_uint(v[2 * g]), 31);
+                od = __builtin_amdgcn_alignbit(od, __float_as_uint(v[2 * g + 1]), 31);
+            }
+            const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+            const uint64_t hw = hash_word(key, seg >> 1);      // 64 pairs per hash word = two lanes
+            const uint32_t off = (uint32_t)(hw >> ((seg & 1) * 32));
+            payload[seg] = valid ? ((~ev & ~off) | (~od & off)) : 0u;
+        }
+    } else if (b_q8 == 512) {
+        uint32_t w[4];
+        quantize_pack<2>(v, s, w, ip);
+        *reinterpret_cast<uint4 *>(payload + seg * 4) =
+            valid ? make_uint4(w[0], w[1], w[2], w[3]) : make_uint4(0, 0, 0, 0);
+    } else {
+        uint32_t w[8];
+        quantize_pack<4>(v, s, w, ip);
+        uint4 *o = reinterpret_cast<uint4 *>(payload + seg * 8);
+        o[0] = valid ? make_uint4(w[0], w[1], w[2], w[3]) : make_uint4(0, 0, 0, 0);
+        o[1] = valid ? make_uint4(w[4], w[5], w[6], w[7]) : make_uint4(0, 0, 0, 0);
+    }
+
+    const double block_total = block_sum<128>((double)ip, red);
+    double total;
+    if (publish_partial<128>(block_total, partials + (size_t)c * partial_stride, gridDim.x,
+                             &scratch[c].done_last, red, total)) {
+        if (threadIdx.x == 0) {
+            MsgHeader h;
+            h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = b_q8; h.client = B.client[c];
+            h.zero = 0; h.seed = seed; h.N2 = n2;
+            if (valid) {
+                h.IP = total * exp2(-0.5 * (double)log2D);   // <R(x),Q> = D^-1/2 sum u_i q_i
+                h.S = n2 / h.IP;                              // Sec. 2.3
+                h.status = 0;
+            } else {
+                h.IP = 0.0; h.S = 0.0;
+                h.status = (n2 == 0.0) ? EDEN_DEV_ZERO_VECTOR : EDEN_DEV_NONFINITE;
+                atomicOr(dev_status, h.status);
+            }
+            *static_cast<MsgHeader *>(B.msg[c]) = h;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// decode side
+//
+// One wave per message: check the header against what the receiver agreed on, count the coordinates
+// that arrived (Sec. 4.2: the receiver finds p by counting), and build the dequantization table
+// (S / (p sqrt(D))) * q_l  -- S/p from Sec. 4.2, D^-1/2 from the inverse rotation.
+__device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap, uint32_t client, uint32_t b_q8,
+                                        uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+                                        DecScratch *out, uint32_t *dev_status) {
+    const uint32_t lane = lane_id();
+    const MsgHeader h = *static_cast<const MsgHeader *>(msg);
+    uint32_t flags = 0;
+    if (h.magic != kMagic || h.log2D != (uint32_t)log2D || h.d != d || h.b_q8 != b_q8 || h.client != client ||
+        h.seed != seed)
+        flags |= EDEN_DEV_HEADER_MISMATCH;
+    else
+        flags |= h.status & (EDEN_DEV_ZERO_VECTOR | EDEN_DEV_NONFINITE);
+    const uint64_t D = 1ull << log2D;
+    const uint32_t npk = D >= EDEN_PACKET_COORDS ? (uint32_t)(D / EDEN_PACKET_COORDS) : 1u;
+    uint32_t got = 0;
+    if (bitmap) {
+        const uint32_t nw = (npk + 31u) / 32u;
+        for (uint32_t w = lane; w < nw; w += 64) {
+            uint32_t bits = bitmap[w];
+            if (w == nw - 1 && (npk & 31u)) bits &= (1u << (npk & 31u)) - 1u;
+            got += __popc(bits);
+        }
+        got = wave_sum_u32(got);
+    } else {
+        got = npk;
+    }
+    int bits, k;
+    budget_of(b_q8, bits, k);
+    const uint64_t per_packet = D >= EDEN_PACKET_COORDS ? EDEN_PACKET_COORDS : D;
+    const uint64_t arrived = (uint64_t)got * per_packet / (uint64_t)k;
+    if (flags == 0 && arrived == 0) flags |= EDEN_DEV_NOTHING_ARRIVED;
+    double coef = 0.0;
+    if (flags == 0) coef = h.S * exp2(0.5 * (double)log2D) / (double)arrived;     // S / (p sqrt(D)), p = arrived / D
+    if (lane < 16) {
+        const int H = 1 << (bits - 1);
+        double q = 0.0;
+        if ((int)lane < 2 * H) q = ((int)lane >= H) ? tab->q[bits][lane - H] : -tab->q[bits][H - 1 - lane];
+        out->deq[lane] = (float)(coef * q);
+    }
+    if (lane == 0) {
+        out->flags = flags;
+        if (flags & (EDEN_DEV_HEADER_MISMATCH | EDEN_DEV_NOTHING_ARRIVED)) atomicOr(dev_status, flags);
+    }
+}
+
+__global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t d, int log2D, uint64_t seed,
+                                                    const DevTables *tab, DecScratch *scratch, uint32_t *dev_status) {
+    const uint32_t c = blockIdx.x;
+    dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, log2D, seed, tab, &scratch[c], dev_status);
+}
+
+// lo pass, decode side: payload -> T.  Unpack, centroid lookup times S/(p sqrt D), zero for coordinates that
+// were not sampled or whose packet was lost (Sec. 4.2), then index bits 0..11 of H.
+__global__ __launch_bounds__(128) void k_dec_lo(DecBatch B, int log2D, uint64_t seed, const DecScratch *scratch,
+                                                float *T) {
+    __shared__ float lds[2][64 * kLdsRow];
+    __shared__ float table[2][16];
+    const uint32_t c = blockIdx.y;
+    const uint32_t lane = lane_id();
+    const uint32_t wv = wave_in_block();
+    const uint32_t tile = blockIdx.x * 2u + wv;
+    const size_t seg = (size_t)tile * 64 + lane;               // this lane decodes coordinates [64 seg, 64 seg + 64)
+    const uint32_t b_q8 = B.b_q8[c];
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const DecScratch *s = &scratch[c];
+
+    bool here = true;                                          // did this lane's packet arrive?
+    if (const uint32_t *bm = B.bitmap[c]) {
+        const uint32_t pk = (uint32_t)((seg * 64) >> 10);
+        here = (bm[pk >> 5] >> (pk & 31u)) & 1u;
+    }
+    float v[64];
+    if (b_q8 == 256) {
+        const uint2 w = *reinterpret_cast<const uint2 *>(payload + seg * 2);
+        const uint32_t mag = here ? __float_as_uint(s->deq[1]) : 0u;       // +a, or 0 for a lost packet
+        const uint32_t n0 = ~w.x, n1 = ~w.y;                               // bit set = index 0 = negative
+#pragma unroll
+        for (int k = 0; k < 32; ++k) v[k] = __uint_as_float(mag | ((n0 << (31 - k)) & 0x80000000u));
+#pragma unroll
+        for (int k = 0; k < 32; ++k) v[32 + k] = __uint_as_float(mag | ((n1 << (31 - k)) & 0x80000000u));
+    } else if (b_q8 == 128) {
+        const uint32_t w = payload[seg];
+        const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+        const uint64_t hw = hash_word(key, seg >> 1);
+        const uint32_t off = (uint32_t)(hw >> ((seg & 1) * 32));
+        const uint32_t mag = here ? __float_as_uint(s->deq[1]) : 0u;
+        const uint32_t nw = ~w;
+#pragma unroll
+        for (int g = 0; g < 32; ++g) {
+            const float val = __uint_as_float(mag | ((nw << (31 - g)) & 0x80000000u));
+            const bool odd = (off >> g) & 1u;
+            v[2 * g] = odd ? 0.0f : val;
+            v[2 * g + 1] = odd ? val : 0.0f;
+        }
+    } else {
+        if (lane < 16) table[wv][lane] = s->deq[lane];
+        wave_lds_sync();
+        const float *tb = table[wv];
+        if (b_q8 == 512) {
+            const uint4 w4 = *reinterpret_cast<const uint4 *>(payload + seg * 4);
+            const uint32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+            for (int k = 0; k < 64; ++k) v[k] = tb[(w[k / 16] >> ((k % 16) * 2)) & 3u];
+        } else {
+            const uint4 *p4 = reinterpret_cast<const uint4 *>(payload + seg * 8);
+            const uint4 a = p4[0], b = p4[1];
+            const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int k = 0; k < 64; ++k) v[k] = tb[(w[k / 8] >> ((k % 8) * 4)) & 15u];
+        }
+        if (!here) {
+#pragma unroll
+            for (int k = 0; k < 64; ++k) v[k] = 0.0f;
+        }
+    }
+    fwht_regs<64>(v);                                          // index bits 0..5
+    float *L = lds[wv];
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+        *reinterpret_cast<float4 *>(&L[lane * kLdsRow + 4 * q]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    wave_lds_sync();
+#pragma unroll
+    for (int j = 0; j < 64; ++j) v[j] = L[j * kLdsRow + lane];
+    fwht_regs<64>(v);                                          // index bits 6..11
+    float *Tc = T + ((size_t)c << log2D) + ((size_t)tile << kLoBits);
+#pragma unroll
+    for (int j = 0; j < 64; ++j) Tc[64 * j + lane] = v[j];
+}
+
+__global__ void k_finalize_mean(const float *acc, uint64_t d, float n, float *mean) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < d) mean[i] = acc[i] / n;                          // Sec. 2.2.2: the plain average
+}
+
+// ------------------------------------------------------------------------------------------------
+// D <= 4096: one workgroup per sender, the padded vector lives in LDS.
+__device__ inline void fwht_lds(float *buf, uint32_t D) {
+    for (uint32_t h = 1; h < D; h <<= 1) {
+        __syncthreads();
+        for (uint32_t pidx = threadIdx.x; pidx < D / 2; pidx += blockDim.x) {
+            const uint32_t i = ((pidx & ~(h - 1)) << 1) | (pidx & (h - 1));
+            const float a = buf[i], b = buf[i + h];
+            buf[i] = a + b;
+            buf[i + h] = a - b;
+        }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int log2D, uint64_t seed,
+                                                   const DevTables *tab, uint32_t *dev_status) {
+    __shared__ float buf[kLoTile];
+    __shared__ uint8_t code[kLoTile];
+    __shared__ double red[4];
+    __shared__ EncScratch s;
+    const uint32_t c = blockIdx.x;
+    const uint32_t D = 1u << log2D;
+    const float *x = B.x[c];
+    const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+    double n2p = 0.0;
+    for (uint32_t i = threadIdx.x; i < D; i += 256) {
+        const float xi = (i < d) ? x[i] : 0.0f;
+        n2p += (double)xi * (double)xi;
+        const bool neg = (hash_word(key, i >> 6) >> (i & 63u)) & 1ull;
+        buf[i] = (neg ? -xi : xi) + 0.0f;
+    }
+    const double n2t = block_sum<256>(n2p, red);
+    const uint32_t b_q8 = B.b_q8[c];
+    if (threadIdx.x == 0) fill_enc_scratch(&s, n2t, b_q8, tab);
+    fwht_lds(buf, D);                                          // includes the barriers that publish `s`
+    int bits, k;
+    budget_of(b_q8, bits, k);
+    const int H = 1 << (bits - 1);
+    const double n2 = s.n2;
+    const bool valid = (n2 > 0.0) && (n2 < INFINITY);
+    float ip = 0.0f;
+    for (uint32_t i = threadIdx.x; i < D; i += 256) {
+        const float u = buf[i];
+        const float a = fabsf(u);
+        uint32_t mag = 0;
+        for (int t = 1; t < H; ++t) mag = (a > s.thr[t]) ? (uint32_t)t : mag;
+        ip = fmaf(a, s.qpos[mag], ip);
+        const uint32_t neg = __float_as_uint(u) >> 31;
+        code[i] = (uint8_t)(neg ? (uint32_t)(H - 1) - mag : (uint32_t)H + mag);
+    }
+    const double ipt = block_sum<256>((double)ip, red);        // barriers inside also publish `code`
+    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const uint32_t nsent = D / (uint32_t)k;                    // transmitted indices
+    const uint32_t nwords = 2u * ((nsent * (uint32_t)bits + 63u) / 64u);
+    const uint32_t per = 32u / (uint32_t)bits;
+    const uint64_t subkey = stream_key(seed, kStreamSubsample, B.client[c]);
+    for (uint32_t w = threadIdx.x; w < nwords; w += 256) {
+        uint32_t word = 0;
+        for (uint32_t e = 0; e < per; ++e) {
+            const uint32_t j = w * per + e;                    // j-th transmitted index
+            if (j >= nsent) break;
+            uint32_t i = j;
+            if (k == 2) i = 2u * j + (uint32_t)((hash_word(subkey, j >> 6) >> (j & 63u)) & 1ull);
+            word |= (uint32_t)code[i] << (e * (uint32_t)bits);
+        }
+        payload[w] = valid ? word : 0u;
+    }
+    if (threadIdx.x == 0) {
+        MsgHeader h;
+        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = b_q8; h.client = B.client[c];
+        h.zero = 0; h.seed = seed; h.N2 = n2;
+        if (valid) {
+            h.IP = ipt * exp2(-0.5 * (double)log2D);
+            h.S = n2 / h.IP;
+            h.status = 0;
+        } else {
+            h.IP = 0.0; h.S = 0.0;
+            h.status = (n2 == 0.0) ? EDEN_DEV_ZERO_VECTOR : EDEN_DEV_NONFINITE;
+            atomicOr(dev_status, h.status);
+        }
+        *static_cast<MsgHeader *>(B.msg[c]) = h;
+    }
+}
+
+// One workgroup decodes the whole batch: per sender fill LDS with the dequantized rotated vector,
+// transform, apply the signs and add into per-thread sums; acc is touched once at the end.
+__global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+                                                   const DevTables *tab, float *acc, uint32_t *dev_status) {
+    __shared__ float buf[kLoTile];
+    __shared__ DecScratch s;
+    const uint32_t D = 1u << log2D;
+    float sum[kLoTile / 256];
+#pragma unroll
+    for (int r = 0; r < kLoTile / 256; ++r) sum[r] = 0.0f;
+    for (uint32_t c = 0; c < n; ++c) {
+        __syncthreads();
+        if (threadIdx.x < 64)
+            dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, log2D, seed, tab, &s, dev_status);
+        __syncthreads();
+        const uint32_t b_q8 = B.b_q8[c];
+        int bits, k;
+        budget_of(b_q8, bits, k);
+        const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+        const uint32_t *bm = B.bitmap[c];
+        const uint64_t subkey = stream_key(seed, kStreamSubsample, B.client[c]);
+        for (uint32_t i = threadIdx.x; i < D; i += 256) {
+            const uint32_t pk = i >> 10;
+            bool here = bm ? ((bm[pk >> 5] >> (pk & 31u)) & 1u) : true;
+            uint32_t j = i;
+            if (k == 2) {
+                j = i >> 1;
+                const uint32_t off = (uint32_t)((hash_word(subkey, j >> 6) >> (j & 63u)) & 1ull);
+                here = here && ((i & 1u) == off);
+            }
+            const uint32_t bitpos = j * (uint32_t)bits;
+            const uint32_t idx = (payload[bitpos >> 5] >> (bitpos & 31u)) & ((1u << bits) - 1u);
+            buf[i] = here ? s.deq[idx] : 0.0f;
+        }
+        fwht_lds(buf, D);
+        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+#pragma unroll
+        for (int r = 0; r < kLoTile / 256; ++r) {
+            const uint32_t i = threadIdx.x + 256u * r;
+            if (i < D) {
+                const bool neg = (hash_word(key, i >> 6) >> (i & 63u)) & 1ull;
+                sum[r] += neg ? -buf[i] : buf[i];
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kLoTile / 256; ++r) {
+        const uint32_t i = threadIdx.x + 256u * r;
+        if (i < d && i < D) acc[i] += sum[r];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// test helpers: the hash streams written out
+__global__ void k_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out) {
+    const uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < nwords) out[j] = hash_word(key, j);
+}
+__global__ void k_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t *bitmap) {
+    const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t nw = (npk + 31u) / 32u;
+    if (w >= nw) return;
+    uint32_t bits = 0;
+    for (uint32_t e = 0; e < 32; ++e) {
+        const uint32_t j = w * 32u + e;
+        if (j >= npk) break;
+        const uint32_t top = (uint32_t)(hash_word(key, j) >> 32);
+        if (top >= drop_q32) bits |= 1u << e;                  // received
+    }
+    bitmap[w] = bits;
+}
+
+// ------------------------------------------------------------------------------------------------
+// host-side launchers
+#define EDEN_HI_SWITCH(M, CALL)            \
+    switch (M) {                           \
+        case 1: { constexpr int MM = 1; CALL; } break; \
+        case 2: { constexpr int MM = 2; CALL; } break; \
+        case 3: { constexpr int MM = 3; CALL; } break; \
+        case 4: { constexpr int MM = 4; CALL; } break; \
+        case 5: { constexpr int MM = 5; CALL; } break; \
+        default: { constexpr int MM = 6; CALL; } break; \
+    }
+
+void launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
+                         double *partials, uint32_t partial_stride, EncScratch *scratch, const DevTables *tab,
+                         hipStream_t st) {
+    const uint32_t ntiles = 1u << (log2D - 6 - M);
+    dim3 grid((ntiles + 3) / 4, n);
+    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_enc_hi_first<MM>, grid, dim3(256), 0, st, B, d, log2D, p, seed, T, partials,
+                                         partial_stride, scratch, tab));
+}
+void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st) {
+    const uint32_t ntiles = 1u << (log2D - 6 - M);
+    dim3 grid((ntiles + 3) / 4, n);
+    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_hi_mid<MM>, grid, dim3(256), 0, st, T, log2D, p));
+}
+void launch_dec_hi_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, const float *T,
+                        float *acc, hipStream_t st) {
+    const uint32_t ntiles = 1u << (log2D - 6 - M);
+    dim3 grid((ntiles + 3) / 4);
+    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_last<MM>, grid, dim3(256), 0, st, B, n, d, log2D, p, seed, T, acc));
+}
+void launch_enc_lo(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T, double *partials,
+                   uint32_t partial_stride, EncScratch *scratch, uint32_t *dev_status, hipStream_t st) {
+    dim3 grid(1u << (log2D - kLoBits - 1), n);
+    hipLaunchKernelGGL(k_enc_lo, grid, dim3(128), 0, st, B, d, log2D, seed, T, partials, partial_stride, scratch, dev_status);
+}
+void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+                        DecScratch *scratch, uint32_t *dev_status, hipStream_t st) {
+    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, d, log2D, seed, tab, scratch, dev_status);
+}
+void launch_dec_lo(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, float *T,
+                   hipStream_t st) {
+    dim3 grid(1u << (log2D - kLoBits - 1), n);
+    hipLaunchKernelGGL(k_dec_lo, grid, dim3(128), 0, st, B, log2D, seed, scratch, T);
+}
+void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st) {
+    const uint32_t blocks = (uint32_t)((d + 255) / 256);
+    hipLaunchKernelGGL(k_finalize_mean, dim3(blocks), dim3(256), 0, st, acc, d, (float)n, mean);
+}
+void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+                      uint32_t *dev_status, hipStream_t st) {
+    hipLaunchKernelGGL(k_enc_small, dim3(n), dim3(256), 0, st, B, d, log2D, seed, tab, dev_status);
+}
+void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab, float *acc,
+                      uint32_t *dev_status, hipStream_t st) {
+    hipLaunchKernelGGL(k_dec_small, dim3(1), dim3(256), 0, st, B, n, d, log2D, seed, tab, acc, dev_status);
+}
+void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st) {
+    hipLaunchKernelGGL(k_hash_bits, dim3((uint32_t)((nwords + 255) / 256)), dim3(256), 0, st, key, nwords, out);
+}
+void launch_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t *bitmap, hipStream_t st) {
+    const uint32_t nw = (npk + 31u) / 32u;
+    hipLaunchKernelGGL(k_loss_bitmap, dim3((nw + 255) / 256), dim3(256), 0, st, key, npk, drop_q32, bitmap);
+}
+
+}  // namespace eden

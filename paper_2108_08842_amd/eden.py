@@ -1,0 +1,220 @@
+"""ctypes binding of the EDEN C ABI (include/eden.h).  Argument marshalling only.
+
+Tensors are torch CUDA(HIP) tensors; the binding passes their `data_ptr()` and the current torch
+stream to the library.  Nothing here computes: every step of the path runs in the HIP kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libeden_hip.so")
+_lib = None
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_CAPACITY = -2
+ERR_HIP = -3
+ERR_NO_DEVICE = -4
+DEV_ZERO_VECTOR = 1
+DEV_NONFINITE = 2
+DEV_HEADER_MISMATCH = 4
+DEV_NOTHING_ARRIVED = 8
+HEADER_BYTES = 64
+PACKET_COORDS = 1024
+
+EXPORTS = [
+    "eden_create", "eden_destroy", "eden_message_bytes", "eden_encode", "eden_decode_accumulate",
+    "eden_finalize_mean", "eden_last_device_status", "eden_make_loss_bitmap", "eden_make_sign_bits",
+    "eden_make_subsample_bits", "eden_get_tables", "eden_strerror",
+]
+
+
+class EdenError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+def lib():
+    """Loads the built library; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2108_08842_amd.build` "
+            "(or __graft_entry__.build()); the EDEN path has no CPU fallback")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, u64, u32, sz, ci = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_size_t, ctypes.c_int
+    P = ctypes.POINTER
+    L.eden_create.argtypes = [P(vp), u64, u32, ci]
+    L.eden_create.restype = ci
+    L.eden_destroy.argtypes = [vp]
+    L.eden_destroy.restype = ci
+    L.eden_message_bytes.argtypes = [u64, u32]
+    L.eden_message_bytes.restype = sz
+    L.eden_encode.argtypes = [vp, P(vp), P(u32), P(u32), u32, u64, u64, P(vp), P(sz), vp]
+    L.eden_encode.restype = ci
+    L.eden_decode_accumulate.argtypes = [vp, P(vp), P(u32), P(u32), u32, u64, u64, P(vp), vp, vp]
+    L.eden_decode_accumulate.restype = ci
+    L.eden_finalize_mean.argtypes = [vp, vp, u64, u32, vp, vp]
+    L.eden_finalize_mean.restype = ci
+    L.eden_last_device_status.argtypes = [vp, vp, P(u32)]
+    L.eden_last_device_status.restype = ci
+    L.eden_make_loss_bitmap.argtypes = [vp, u64, u32, u64, u32, vp, vp]
+    L.eden_make_loss_bitmap.restype = ci
+    L.eden_make_sign_bits.argtypes = [vp, u64, u32, u64, vp, vp]
+    L.eden_make_sign_bits.restype = ci
+    L.eden_make_subsample_bits.argtypes = [vp, u64, u32, u64, vp, vp]
+    L.eden_make_subsample_bits.restype = ci
+    L.eden_get_tables.argtypes = [u32, P(ctypes.c_double), P(ctypes.c_double)]
+    L.eden_get_tables.restype = ci
+    L.eden_strerror.argtypes = [ci]
+    L.eden_strerror.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def strerror(code: int) -> str:
+    return lib().eden_strerror(code).decode()
+
+
+def message_bytes(d: int, b_q8: int) -> int:
+    return int(lib().eden_message_bytes(d, b_q8))
+
+
+def get_tables(bits: int):
+    n = 1 << bits
+    t = (ctypes.c_double * (n - 1))()
+    q = (ctypes.c_double * n)()
+    rc = lib().eden_get_tables(bits, t, q)
+    if rc != OK:
+        raise EdenError(rc, "eden_get_tables")
+    return list(t), list(q)
+
+
+def _stream_ptr(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _u32_array(values: Sequence[int]):
+    return (ctypes.c_uint32 * len(values))(*[int(v) for v in values])
+
+
+def _ptr_array(ptrs: Sequence[Optional[int]]):
+    return (ctypes.c_void_p * len(ptrs))(*[ctypes.c_void_p(p) if p else None for p in ptrs])
+
+
+class Context:
+    """Owns one eden_ctx (workspace + tables) on a HIP device."""
+
+    def __init__(self, d_max: int, n_max: int, device: int = 0):
+        h = ctypes.c_void_p()
+        rc = lib().eden_create(ctypes.byref(h), d_max, n_max, device)
+        if rc != OK:
+            raise EdenError(rc, "eden_create")
+        self._h = h
+        self.d_max, self.n_max, self.device = d_max, n_max, device
+
+    def close(self):
+        if self._h:
+            lib().eden_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- raw calls: return the library's status code, raise nothing
+    def encode_raw(self, x_ptrs, client_ids, b_q8, d, seed, msg_ptrs, msg_caps, stream=None) -> int:
+        n = len(x_ptrs)
+        caps = (ctypes.c_size_t * n)(*[int(c) for c in msg_caps])
+        return lib().eden_encode(self._h, _ptr_array(x_ptrs), _u32_array(client_ids), _u32_array(b_q8), n, d,
+                                 ctypes.c_uint64(seed & (2 ** 64 - 1)), _ptr_array(msg_ptrs), caps,
+                                 _stream_ptr(stream))
+
+    def decode_accumulate_raw(self, msg_ptrs, client_ids, b_q8, d, seed, bitmap_ptrs, acc_ptr, stream=None) -> int:
+        n = len(msg_ptrs)
+        bm = _ptr_array(bitmap_ptrs) if bitmap_ptrs is not None else None
+        return lib().eden_decode_accumulate(self._h, _ptr_array(msg_ptrs), _u32_array(client_ids), _u32_array(b_q8),
+                                            n, d, ctypes.c_uint64(seed & (2 ** 64 - 1)), bm,
+                                            ctypes.c_void_p(acc_ptr), _stream_ptr(stream))
+
+    def finalize_mean_raw(self, acc_ptr, d, n, mean_ptr, stream=None) -> int:
+        return lib().eden_finalize_mean(self._h, ctypes.c_void_p(acc_ptr), d, n, ctypes.c_void_p(mean_ptr),
+                                        _stream_ptr(stream))
+
+    # ---- tensor-level convenience (allocation + marshalling only)
+    def alloc_messages(self, d: int, b_q8: Sequence[int]):
+        import torch
+        return [torch.empty(message_bytes(d, b), dtype=torch.uint8, device=f"cuda:{self.device}") for b in b_q8]
+
+    def encode(self, xs, client_ids, b_q8, seed: int, msgs=None, stream=None):
+        d = xs[0].numel()
+        for x in xs:
+            assert x.is_cuda and x.dtype.is_floating_point and x.element_size() == 4 and x.is_contiguous() and x.numel() == d
+        if msgs is None:
+            msgs = self.alloc_messages(d, b_q8)
+        rc = self.encode_raw([x.data_ptr() for x in xs], client_ids, b_q8, d, seed,
+                             [m.data_ptr() for m in msgs], [m.numel() for m in msgs], stream)
+        if rc != OK:
+            raise EdenError(rc, "eden_encode")
+        return msgs
+
+    def decode_accumulate(self, msgs, client_ids, b_q8, d: int, seed: int, acc, bitmaps=None, stream=None):
+        assert acc.is_cuda and acc.element_size() == 4 and acc.numel() == d and acc.is_contiguous()
+        bm = None if bitmaps is None else [None if b is None else b.data_ptr() for b in bitmaps]
+        rc = self.decode_accumulate_raw([m.data_ptr() for m in msgs], client_ids, b_q8, d, seed, bm,
+                                        acc.data_ptr(), stream)
+        if rc != OK:
+            raise EdenError(rc, "eden_decode_accumulate")
+        return acc
+
+    def finalize_mean(self, acc, n: int, out=None, stream=None):
+        out = acc if out is None else out
+        rc = self.finalize_mean_raw(acc.data_ptr(), acc.numel(), n, out.data_ptr(), stream)
+        if rc != OK:
+            raise EdenError(rc, "eden_finalize_mean")
+        return out
+
+    def last_device_status(self, stream=None) -> int:
+        v = ctypes.c_uint32(0)
+        rc = lib().eden_last_device_status(self._h, _stream_ptr(stream), ctypes.byref(v))
+        if rc != OK:
+            raise EdenError(rc, "eden_last_device_status")
+        return int(v.value)
+
+    def make_loss_bitmap(self, seed: int, client: int, D: int, drop_q32: int, stream=None):
+        import torch
+        npk = max(1, D // PACKET_COORDS)
+        out = torch.empty((npk + 31) // 32, dtype=torch.int32, device=f"cuda:{self.device}")
+        rc = lib().eden_make_loss_bitmap(self._h, ctypes.c_uint64(seed), client, D, drop_q32,
+                                         ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
+        if rc != OK:
+            raise EdenError(rc, "eden_make_loss_bitmap")
+        return out
+
+    def make_sign_bits(self, seed: int, client: int, D: int, stream=None):
+        import torch
+        out = torch.empty(max(1, D // 64), dtype=torch.int64, device=f"cuda:{self.device}")
+        rc = lib().eden_make_sign_bits(self._h, ctypes.c_uint64(seed), client, D, ctypes.c_void_p(out.data_ptr()),
+                                       _stream_ptr(stream))
+        if rc != OK:
+            raise EdenError(rc, "eden_make_sign_bits")
+        return out
+
+    def make_subsample_bits(self, seed: int, client: int, D: int, stream=None):
+        import torch
+        out = torch.empty(max(1, D // 128), dtype=torch.int64, device=f"cuda:{self.device}")
+        rc = lib().eden_make_subsample_bits(self._h, ctypes.c_uint64(seed), client, D,
+                                            ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
+        if rc != OK:
+            raise EdenError(rc, "eden_make_subsample_bits")
+        return out

@@ -1,0 +1,77 @@
+"""Parity checker: compares the HIP library's output with the float64 oracle on the same inputs.
+
+Bars (from the project's stated tolerances):
+  * header integers, signs, masks, bitmaps: bit exact
+  * packed indices: bit exact, except coordinates whose scaled rotated value lies within 1e-5 of the
+    threshold between the two indices; those are counted and their fraction must be <= 1e-6
+  * |x|^2: relative 1e-12;  S and <R(x),Q>: relative 1e-6
+  * decoded means: relative L2 error <= 1e-5 (fp32 arithmetic on the GPU, float64 in the oracle),
+    both sides decoding the same messages
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import numpy as np
+
+from oracle import eden_oracle as o
+
+INDEX_BOUNDARY_TOL = 1e-5
+INDEX_MISMATCH_FRACTION = 1e-6
+SCALE_RTOL = 1e-6
+MEAN_REL_L2 = 1e-5
+
+
+@dataclass
+class EncodeParity:
+    coords: int = 0
+    mismatches: int = 0
+    worst_boundary_distance: float = 0.0
+
+
+def to_oracle_message(msg_tensor) -> o.Message:
+    return o.Message.from_bytes(msg_tensor.cpu().numpy().tobytes())
+
+
+def check_encode(x: np.ndarray, seed: int, client: int, b_q8: int, gpu_msg: o.Message, stats: EncodeParity):
+    """x: the fp32 input as given to the GPU.  Raises AssertionError on any violation."""
+    ref, tr = o.encode(x.astype(np.float64), seed, client, b_q8, want_trace=True)
+    assert (gpu_msg.log2D, gpu_msg.d, gpu_msg.b_q8, gpu_msg.client, gpu_msg.seed) == \
+           (ref.log2D, ref.d, ref.b_q8, ref.client, ref.seed & (2 ** 64 - 1))
+    assert gpu_msg.status == ref.status
+    assert gpu_msg.payload.size == ref.payload.size
+    if ref.status != 0:
+        assert gpu_msg.S == 0.0 and not gpu_msg.payload.any()
+        return
+    assert abs(gpu_msg.N2 - ref.N2) <= 1e-12 * ref.N2
+    assert abs(gpu_msg.IP - ref.IP) <= SCALE_RTOL * ref.IP
+    assert abs(gpu_msg.S - ref.S) <= SCALE_RTOL * ref.S
+    bits, _ = o.budget(b_q8)
+    thresholds, _ = o.tables(bits)
+    nsent = tr.kept.size
+    got = o.unpack_indices(gpu_msg.payload, bits, nsent)
+    want = tr.idx[tr.kept]
+    # padding bits after the last index are zero
+    used = nsent * bits
+    allbits = ((gpu_msg.payload[:, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(-1)
+    assert not allbits[used:].any()
+    bad = np.flatnonzero(got != want)
+    stats.coords += nsent
+    stats.mismatches += bad.size
+    if bad.size:
+        lo = np.minimum(got[bad], want[bad])
+        assert np.all(np.abs(got[bad] - want[bad]) == 1), "index differs by more than one interval"
+        dist = np.abs(tr.z[tr.kept][bad] - thresholds[lo])
+        stats.worst_boundary_distance = max(stats.worst_boundary_distance, float(dist.max()))
+        assert dist.max() <= INDEX_BOUNDARY_TOL, f"index mismatch {dist.max():.3e} away from its threshold"
+
+
+def finish_encode(stats: EncodeParity):
+    assert stats.mismatches <= INDEX_MISMATCH_FRACTION * stats.coords, \
+        f"{stats.mismatches} near-boundary mismatches in {stats.coords} coordinates"
+
+
+def rel_l2(a: np.ndarray, b: np.ndarray) -> float:
+    den = float(np.linalg.norm(b))
+    return float(np.linalg.norm(a.astype(np.float64) - b)) / (den if den > 0 else 1.0)

@@ -1,0 +1,218 @@
+"""GPU parity: the HIP library (through its C ABI) against the float64 oracle, element by element."""
+import numpy as np
+import pytest
+
+from oracle import eden_oracle as o
+from paper_2108_08842_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2108_08842_amd import eden
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    c = eden.Context(d_max=1 << 20, n_max=40, device=0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def _run_case(ctx, xs, client_ids, budgets, seed, drop_q32=0, also_oracle_msgs=True):
+    """Encode on the GPU, compare with the oracle; decode the same messages on both sides."""
+    from paper_2108_08842_amd import eden
+    n, d = len(xs), xs[0].size
+    D = o.padded_dim(d)
+    print(f"case n={n} d={d} D=2^{D.bit_length() - 1} budgets={sorted(set(budgets))} seed={seed} drop={drop_q32}", flush=True)
+    x_dev = [torch.from_numpy(x).cuda() for x in xs]
+    msgs = ctx.encode(x_dev, client_ids, budgets, seed)
+    torch.cuda.synchronize()
+    assert ctx.last_device_status() == 0
+    stats = parity.EncodeParity()
+    omsgs = []
+    for c in range(n):
+        gm = parity.to_oracle_message(msgs[c])
+        parity.check_encode(xs[c], seed, client_ids[c], budgets[c], gm, stats)
+        omsgs.append(gm)
+    parity.finish_encode(stats)
+
+    bitmaps_np, bitmaps_dev = None, None
+    if drop_q32:
+        bitmaps_dev = [ctx.make_loss_bitmap(seed, client_ids[c], D, drop_q32) for c in range(n)]
+        bitmaps_np = [b.cpu().numpy().view(np.uint32) for b in bitmaps_dev]
+        for c in range(n):            # the helper's mask is the oracle's mask, bit for bit
+            np.testing.assert_array_equal(bitmaps_np[c], o.loss_bitmap(seed, client_ids[c], D, drop_q32))
+
+    # receiver: both sides decode the GPU's messages
+    acc = torch.zeros(d, dtype=torch.float32, device="cuda")
+    ctx.decode_accumulate(msgs, client_ids, budgets, d, seed, acc, bitmaps_dev)
+    mean = ctx.finalize_mean(acc, n).cpu().numpy()
+    assert ctx.last_device_status() == 0
+    want = o.decode_mean(omsgs, d, bitmaps_np)
+    err = parity.rel_l2(mean, want)
+    assert err <= parity.MEAN_REL_L2, f"decoded mean off by {err:.3e}"
+
+    if also_oracle_msgs:
+        # and the GPU decodes messages the oracle wrote
+        ref_msgs = [o.encode(xs[c].astype(np.float64), seed, client_ids[c], budgets[c]) for c in range(n)]
+        dev_msgs = [torch.from_numpy(np.frombuffer(m.to_bytes(), dtype=np.uint8).copy()).cuda() for m in ref_msgs]
+        acc2 = torch.zeros(d, dtype=torch.float32, device="cuda")
+        ctx.decode_accumulate(dev_msgs, client_ids, budgets, d, seed, acc2, bitmaps_dev)
+        mean2 = ctx.finalize_mean(acc2, n).cpu().numpy()
+        want2 = o.decode_mean(ref_msgs, d, bitmaps_np)
+        err2 = parity.rel_l2(mean2, want2)
+        assert err2 <= parity.MEAN_REL_L2, f"decode of oracle messages off by {err2:.3e}"
+    return stats
+
+
+def test_hash_streams_bit_exact(ctx):
+    for seed, client, D in [(0, 0, 64), (1, 5, 1024), (2 ** 63 + 11, 4_000_000_000, 1 << 16), (7, 3, 1 << 20)]:
+        s = ctx.make_sign_bits(seed, client, D).cpu().numpy().view(np.uint64)
+        want = o.hash_words(o.stream_key(seed, o.STREAM_SIGN, client), 0, max(1, D // 64))
+        np.testing.assert_array_equal(s, want)
+        m = ctx.make_subsample_bits(seed, client, D).cpu().numpy().view(np.uint64)
+        want = o.hash_words(o.stream_key(seed, o.STREAM_SUBSAMPLE, client), 0, max(1, D // 128))
+        np.testing.assert_array_equal(m, want)
+        for drop in (0, int(0.1 * 2 ** 32), 2 ** 32 - 1):
+            bm = ctx.make_loss_bitmap(seed, client, D, drop).cpu().numpy().view(np.uint32)
+            np.testing.assert_array_equal(bm, o.loss_bitmap(seed, client, D, drop))
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 5, 63, 64, 65, 1000, 1024, 4095, 4096])
+def test_single_workgroup_sizes(ctx, d):
+    w = synth.Workload("t", 3, d, [256, 512, 1024], 100 + d, "normal")
+    xs = [synth.client_vector(w, c) for c in range(3)]
+    _run_case(ctx, xs, [0, 1, 2], w.b_q8, w.seed)
+    if d >= 2:
+        _run_case(ctx, xs, [7, 8, 9], [128, 128, 256], w.seed + 1)
+
+
+@pytest.mark.parametrize("d", [4097, 8192, 20_000, (1 << 16) + 17, 300_000, 1 << 18])
+def test_multi_pass_sizes(ctx, d):
+    w = synth.Workload("t", 4, d, [128, 256, 512, 1024], 200 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(4)]
+    _run_case(ctx, xs, [3, 1, 4, 1_000_000], w.b_q8, w.seed)
+
+
+@pytest.mark.parametrize("d", [5000, 70_000])
+def test_packet_loss_and_mixed_budgets(ctx, d):
+    w = synth.Workload("t", 6, d, [128, 256, 512, 1024, 256, 128], 300 + d % 1000, "lognormal")
+    xs = [synth.client_vector(w, c) for c in range(6)]
+    _run_case(ctx, xs, list(range(6)), w.b_q8, w.seed, drop_q32=int(0.1 * 2 ** 32))
+    _run_case(ctx, xs, list(range(6)), w.b_q8, w.seed, drop_q32=int(0.6 * 2 ** 32), also_oracle_msgs=False)
+
+
+def test_config1_exact(ctx):
+    w = synth.config(1)
+    xs = [synth.client_vector(w, c) for c in range(w.n)]
+    _run_case(ctx, xs, w.client_ids, w.b_q8, w.seed)
+
+
+def test_config2_full_size(ctx):
+    w = synth.config(2)
+    xs = [synth.client_vector(w, c) for c in range(w.n)]
+    st = _run_case(ctx, xs, w.client_ids, w.b_q8, w.seed, also_oracle_msgs=False)
+    print("config 2:", st)
+
+
+def test_config3_full_size(ctx):
+    w = synth.config(3)
+    assert set(w.b_q8) == {128, 256, 512, 1024}
+    xs = [synth.client_vector(w, c) for c in range(w.n)]
+    st = _run_case(ctx, xs, w.client_ids, w.b_q8, w.seed, drop_q32=w.drop_q32, also_oracle_msgs=False)
+    print("config 3:", st)
+
+
+def test_batches_larger_than_one_launch(ctx):
+    # 40 senders: the library splits them into launches of at most 32
+    d = 5000
+    w = synth.Workload("t", 40, d, [256] * 40, 77, "normal")
+    xs = [synth.client_vector(w, c) for c in range(40)]
+    _run_case(ctx, xs, list(range(40)), w.b_q8, w.seed, also_oracle_msgs=False)
+
+
+def test_decode_is_additive_and_repeatable(ctx):
+    d = 100_000
+    w = synth.Workload("t", 5, d, [256, 512, 1024, 128, 256], 55, "layers")
+    xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(5)]
+    ids = list(range(5))
+    msgs = ctx.encode(xs, ids, w.b_q8, w.seed)
+    msgs_again = ctx.encode(xs, ids, w.b_q8, w.seed)
+    for a, b in zip(msgs, msgs_again):                       # encode is deterministic, bit for bit
+        assert torch.equal(a, b)
+    acc_all = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs, ids, w.b_q8, d, w.seed, acc_all)
+    acc_split = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs[:2], ids[:2], w.b_q8[:2], d, w.seed, acc_split)
+    ctx.decode_accumulate(msgs[2:], ids[2:], w.b_q8[2:], d, w.seed, acc_split)
+    err = (acc_all - acc_split).norm() / acc_all.norm()
+    assert err < 1e-6
+    acc_all2 = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs, ids, w.b_q8, d, w.seed, acc_all2)
+    assert torch.equal(acc_all, acc_all2)
+
+
+def test_degenerate_vectors_and_status(ctx):
+    from paper_2108_08842_amd import eden
+    for d in (100, 10_000):
+        x0 = np.zeros(d, dtype=np.float32)
+        x1 = synth.client_vector(synth.Workload("t", 1, d, [256], 1, "normal"), 0)
+        xn = x1.copy(); xn[d // 2] = np.inf
+        xs = [x0, x1, xn]
+        x_dev = [torch.from_numpy(x).cuda() for x in xs]
+        msgs = ctx.encode(x_dev, [0, 1, 2], [256, 512, 256], 9)
+        status = ctx.last_device_status()
+        assert status == eden.DEV_ZERO_VECTOR | eden.DEV_NONFINITE
+        stats = parity.EncodeParity()
+        for c in range(3):
+            parity.check_encode(xs[c], 9, c, [256, 512, 256][c], parity.to_oracle_message(msgs[c]), stats)
+        acc = torch.zeros(d, device="cuda")
+        ctx.decode_accumulate(msgs, [0, 1, 2], [256, 512, 256], d, 9, acc)
+        only = torch.zeros(d, device="cuda")
+        ctx.decode_accumulate(msgs[1:2], [1], [512], d, 9, only)
+        assert torch.equal(acc, only)                        # zero / non-finite senders add nothing
+        assert ctx.last_device_status() == 0
+        # every packet lost -> contributes nothing, flagged
+        D = o.padded_dim(d)
+        empty = torch.zeros(max(1, (max(1, D // 1024) + 31) // 32), dtype=torch.int32, device="cuda")
+        acc2 = torch.zeros(d, device="cuda")
+        ctx.decode_accumulate(msgs[1:2], [1], [512], d, 9, acc2, [empty])
+        assert not acc2.any().item()
+        assert ctx.last_device_status() == eden.DEV_NOTHING_ARRIVED
+        # receiver expecting another client id / seed / budget: flagged, nothing added
+        acc3 = torch.zeros(d, device="cuda")
+        ctx.decode_accumulate(msgs[1:2], [5], [512], d, 9, acc3)
+        ctx.decode_accumulate(msgs[1:2], [1], [512], d, 10, acc3)
+        ctx.decode_accumulate(msgs[1:2], [1], [256], d, 9, acc3)
+        assert not acc3.any().item()
+        assert ctx.last_device_status() == eden.DEV_HEADER_MISMATCH
+
+
+def test_argument_errors(ctx):
+    from paper_2108_08842_amd import eden
+    d = 1000
+    x = torch.zeros(d, device="cuda")
+    msg = torch.zeros(eden.message_bytes(d, 256), dtype=torch.uint8, device="cuda")
+    acc = torch.zeros(d, device="cuda")
+    ok = dict(x_ptrs=[x.data_ptr()], client_ids=[0], b_q8=[256], d=d, seed=1, msg_ptrs=[msg.data_ptr()],
+              msg_caps=[msg.numel()])
+    assert ctx.encode_raw(**ok) == eden.OK
+    assert ctx.encode_raw(**{**ok, "b_q8": [300]}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw(**{**ok, "b_q8": [768]}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw(**{**ok, "d": 0}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw(**{**ok, "d": (1 << 20) + 1}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw(**{**ok, "x_ptrs": [None]}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw(**{**ok, "msg_caps": [msg.numel() - 1]}) == eden.ERR_CAPACITY
+    assert ctx.encode_raw(**{**ok, "msg_ptrs": [msg.data_ptr() + 4]}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw([], [], [], d, 1, [], []) == eden.ERR_INVALID_ARG
+    assert ctx.decode_accumulate_raw([msg.data_ptr()], [0], [256], d, 1, None, acc.data_ptr()) == eden.OK
+    assert ctx.decode_accumulate_raw([msg.data_ptr()], [0], [256], d, 1, None, None) == eden.ERR_INVALID_ARG
+    assert ctx.decode_accumulate_raw([None], [0], [256], d, 1, None, acc.data_ptr()) == eden.ERR_INVALID_ARG
+    assert ctx.finalize_mean_raw(acc.data_ptr(), d, 0, acc.data_ptr()) == eden.ERR_INVALID_ARG
+    assert eden.message_bytes(1, 128) == 0                   # one coordinate cannot be sub-sampled in pairs
+    assert eden.message_bytes((1 << 27) + 1, 256) == 0
+    torch.cuda.synchronize()
+    ctx.last_device_status()

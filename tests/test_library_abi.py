@@ -1,0 +1,59 @@
+"""CPU-side checks of the built library: it loads, exports every declared symbol, and its host-only
+entry points (sizes, tables, error strings) agree with the oracle.  No GPU work is started."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import eden_oracle as o
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def eden():
+    from paper_2108_08842_amd import eden as e
+    if not os.path.exists(e._LIB_PATH):
+        from paper_2108_08842_amd import build
+        build.build(verbose=False)
+    e.lib()
+    return e
+
+
+def test_every_declared_symbol_is_exported(eden):
+    header = open(os.path.join(ROOT, "include", "eden.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(eden_[a-z_]+)\s*\(", header))
+    assert {"eden_encode", "eden_decode_accumulate", "eden_finalize_mean", "eden_create"} <= declared
+    assert declared == set(eden.EXPORTS)
+    for name in declared:
+        assert getattr(eden.lib(), name) is not None
+
+
+def test_message_bytes_matches_oracle(eden):
+    for d in (1, 2, 3, 64, 1000, 1024, 4097, 1 << 20, 11_173_962, 1 << 27):
+        for b in (128, 256, 512, 1024):
+            if b == 128 and d == 1:
+                assert eden.message_bytes(d, b) == 0
+                continue
+            assert eden.message_bytes(d, b) == o.message_bytes(d, b)
+    assert eden.message_bytes(0, 256) == 0
+    assert eden.message_bytes(100, 300) == 0
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_library_tables_match_oracle_tables(eden, bits):
+    # two independent Lloyd-Max solvers (C++ on the positive half line, numpy on the full line)
+    t, q = eden.get_tables(bits)
+    to, qo = o.tables(bits)
+    np.testing.assert_allclose(t, to, atol=2e-12)
+    np.testing.assert_allclose(q, qo, atol=2e-12)
+    # and fp32 rounding of either is the same number almost everywhere
+    assert np.sum(np.float32(q) != np.float32(qo)) == 0
+
+
+def test_error_strings(eden):
+    assert eden.strerror(0) == "ok"
+    assert "argument" in eden.strerror(eden.ERR_INVALID_ARG)
+    assert "small" in eden.strerror(eden.ERR_CAPACITY)
