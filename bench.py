@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Throughput of the EDEN hot path on one MI355X.
+
+One step = encode of all n senders + decode_accumulate of all n messages + finalize_mean on one
+synthetic batch that is already resident in device memory.  Prints ONE JSON line (see README / DESIGN).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def passes_of(log2D: int) -> int:
+    """HBM passes of the transform in the byte model the metric is defined on (2^12 on-chip block)."""
+    return max(1, -(-log2D // 12))
+
+
+def model_bytes(n, d, D, budgets):
+    """Kernel-minimum traffic of one step: per sender encode 4d + 8D(P-1) + bD/8, decode bD/8 + 8D(P-1),
+    plus 4d once for the mean."""
+    P = passes_of(D.bit_length() - 1)
+    total = 0.0
+    for b in budgets:
+        payload = D * (b / 256.0) / 8.0
+        total += 4 * d + 8 * D * (P - 1) + payload          # encode
+        total += payload + 8 * D * (P - 1)                  # decode
+    return total + 4 * d
+
+
+def kernel_bytes(kind, senders, d, D, budgets_mean_bits):
+    """Algorithmic bytes one launch of a kernel kind must move (what it reads + what it writes)."""
+    payload = D * budgets_mean_bits / 8.0
+    per_sender = {
+        "enc_hi_first": 4 * d + 4 * D,       # x in, workspace out
+        "hi_mid": 8 * D,                     # workspace in and out
+        "enc_lo": 4 * D + payload,           # workspace in, packed indices out
+        "dec_lo": payload + 4 * D,           # packed indices in, workspace out
+        "dec_hi_last": 4 * D,                # workspace in (per sender) ...
+    }
+    if kind == "dec_hi_last":
+        return senders * per_sender[kind] + 8 * d   # ... plus one read-modify-write of the accumulator
+    if kind == "finalize_mean":
+        return 8 * d
+    return senders * per_sender.get(kind, 0.0)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="synthetic configuration 1..5 (4 = the headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-all", action="store_true", help="time every kernel kind, print a table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (each box has one); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2108_08842_amd import eden, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    eden.lib()                                              # fails loudly if the HIP library is not built
+    w = synth.config(args.config)
+    n, d = w.n, w.d
+    D = 1 << (d - 1).bit_length()
+    log2D = D.bit_length() - 1
+    mean_bits = sum(w.b_q8) / len(w.b_q8) / 256.0
+
+    xs_host = [synth.client_vector(w, c) for c in range(n)]
+    xs = [torch.from_numpy(x).cuda() for x in xs_host]
+    ctx = eden.Context(d_max=d, n_max=n, device=0)
+    msgs = ctx.alloc_messages(d, w.b_q8)
+    acc = torch.zeros(d, dtype=torch.float32, device="cuda")
+    mean = torch.empty_like(acc)
+    bitmaps = None
+    if w.drop_q32:
+        bitmaps = [ctx.make_loss_bitmap(w.seed, w.client_ids[c], D, w.drop_q32) for c in range(n)]
+
+    def step():
+        acc.zero_()
+        ctx.encode(xs, w.client_ids, w.b_q8, w.seed, msgs=msgs)
+        ctx.decode_accumulate(msgs, w.client_ids, w.b_q8, d, w.seed, acc, bitmaps)
+        ctx.finalize_mean(acc, n, out=mean)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # find the dominant kernel with every kind timed (untimed region), then time only that one
+    all_kinds = [k for k in eden.KERNEL_KINDS]
+    ctx.profile_enable(all_kinds, 4096)
+    step()
+    torch.cuda.synchronize()
+    per_kind = {}
+    for kind, senders, ms in ctx.profile_collect():
+        per_kind.setdefault(kind, []).append((senders, ms))
+    dominant = max(per_kind, key=lambda k: sum(ms for _, ms in per_kind[k]))
+    if args.profile_all:
+        for kind, recs in sorted(per_kind.items(), key=lambda kv: -sum(ms for _, ms in kv[1])):
+            tot = sum(ms for _, ms in recs)
+            byts = sum(kernel_bytes(kind, s, d, D, mean_bits) for s, _ in recs)
+            print(f"  {kind:14s} launches={len(recs):3d} total={tot:8.3f} ms  alg={byts / 1e9:7.3f} GB  "
+                  f"{byts / 1e6 / max(tot, 1e-9):8.1f} GB/s", file=sys.stderr)
+    ctx.profile_enable([dominant], 4096)
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    status = ctx.last_device_status()
+    assert status == 0, f"device status {status}"
+
+    recs = ctx.profile_collect()
+    dom_ms = [ms for _, _, ms in recs]
+    dom_bytes = [kernel_bytes(k, s, d, D, mean_bits) for k, s, _ in recs]
+    avg_ms = sum(dom_ms) / len(dom_ms)
+    achieved = (sum(dom_bytes) / len(dom_bytes)) / (avg_ms * 1e-3) / 1e9
+    ctx.profile_enable([], 0)
+
+    coords = 2.0 * n * D
+    value = coords / (ms_per_step * 1e-3) / 1e9
+    mbytes = model_bytes(n, d, D, w.b_q8)
+    model_gbs = mbytes / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": "encode+decode Gcoords/s (2*n*D coordinates per step)",
+        "value": round(value, 3),
+        "unit": "Gcoords/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n": n, "d": d, "D": D, "b": mean_bits, "dist": w.dist,
+                   "loss": w.drop_q32 / 2 ** 32},
+        "hbm_model": {"bytes_per_step": mbytes, "GBps": round(model_gbs, 1),
+                      "frac_of_peak": round(model_gbs / HBM_PEAK_GBS, 4),
+                      "note": "kernel-minimum traffic (2^12 on-chip block) / step time / 8 TB/s"},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_launch_ms": round(avg_ms, 4), "launches": len(dom_ms)},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import eden_oracle as o
+        # bounded sample: senders 0..k-1 of the same workload, full dimension, through the float64 oracle
+        k = 1 if D >= (1 << 22) else min(n, 4)
+        t0 = time.perf_counter()
+        omsgs = [o.encode(xs_host[c].astype(np.float64), w.seed, w.client_ids[c], w.b_q8[c]) for c in range(k)]
+        _ = o.decode_mean(omsgs, d)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * k * D / dt / 1e9, 5), "unit": "Gcoords/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"{k} of {n} senders at full d, encode+decode+mean, numpy float64, {dt:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

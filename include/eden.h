@@ -151,6 +151,29 @@ int eden_make_subsample_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, u
  * thresholds[2^bits - 1] and centroids[2^bits], ascending, double precision (Sec. 3). */
 int eden_get_tables(uint32_t bits, double *thresholds, double *centroids);
 
+/* Kernel timing for the benchmark: while enabled, every launch of a kernel whose kind is in
+ * `kind_mask` (bit k = kind k) is bracketed by two HIP events on the caller's stream.
+ * eden_profile_enable allocates the event pool (max_records pairs) on first use; passing kind_mask = 0
+ * switches timing off.  eden_profile_collect synchronises the recorded events, writes up to `cap`
+ * records (kind, senders in that launch, elapsed milliseconds) in launch order, stores the number
+ * written in *count, and empties the pool.  Launches beyond max_records are not recorded. */
+typedef enum eden_kernel_kind {
+    EDEN_K_ENC_HI_FIRST = 0,   /* encode: first strided pass (reads x, signs, |x|^2) */
+    EDEN_K_HI_MID = 1,         /* middle strided pass, in place on the workspace */
+    EDEN_K_ENC_LO = 2,         /* encode: contiguous pass + quantize + pack */
+    EDEN_K_DEC_PREPARE = 3,    /* decode: per-message scalars */
+    EDEN_K_DEC_LO = 4,         /* decode: unpack + dequantize + contiguous pass */
+    EDEN_K_DEC_HI_LAST = 5,    /* decode: last strided pass + signs + sum over senders */
+    EDEN_K_FINALIZE = 6,       /* division by n */
+    EDEN_K_ENC_SMALL = 7,      /* encode, D <= 4096, one workgroup per sender */
+    EDEN_K_DEC_SMALL = 8,      /* decode, D <= 4096 */
+    EDEN_K_COUNT = 9
+} eden_kernel_kind;
+int eden_profile_enable(eden_ctx *ctx, uint32_t kind_mask, uint32_t max_records);
+int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, float *ms, uint32_t cap,
+                         uint32_t *count);
+const char *eden_kernel_name(uint32_t kind);
+
 const char *eden_strerror(int status);
 
 #ifdef __cplusplus

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "eden.h"
 #include "eden_device.h"
@@ -27,6 +28,11 @@ struct eden_ctx {
     DecScratch *dec_scratch; // slots
     DevTables *tables;
     uint32_t *dev_status;
+    // optional kernel timing (eden_profile_*)
+    uint32_t prof_mask = 0;
+    uint32_t prof_used = 0;
+    std::vector<hipEvent_t> prof_start, prof_stop;
+    std::vector<uint32_t> prof_kind, prof_senders;
 };
 
 namespace {
@@ -75,6 +81,21 @@ size_t payload_bytes(uint64_t D, int bits, int k) {
 }
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+// Brackets one kernel launch with two events when timing of that kernel kind is switched on.
+struct Timed {
+    eden_ctx *ctx;
+    hipStream_t st;
+    int slot = -1;
+    Timed(eden_ctx *c, uint32_t kind, uint32_t senders, hipStream_t s) : ctx(c), st(s) {
+        if (!((c->prof_mask >> kind) & 1u) || c->prof_used >= c->prof_start.size()) return;
+        slot = (int)c->prof_used++;
+        c->prof_kind[slot] = kind;
+        c->prof_senders[slot] = senders;
+        (void)hipEventRecord(c->prof_start[slot], st);
+    }
+    ~Timed() { if (slot >= 0) (void)hipEventRecord(ctx->prof_stop[slot], st); }
+};
 
 }  // namespace
 
@@ -139,6 +160,8 @@ int eden_destroy(eden_ctx *ctx) {
     if (!ctx) return EDEN_ERR_INVALID_ARG;
     DeviceGuard guard(ctx->device);
     bool ok = guard.ok;
+    for (hipEvent_t e : ctx->prof_start) ok = (hipEventDestroy(e) == hipSuccess) && ok;
+    for (hipEvent_t e : ctx->prof_stop) ok = (hipEventDestroy(e) == hipSuccess) && ok;
     void *ptrs[] = {ctx->T, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
     for (void *p : ptrs)
         if (p) ok = (hipFree(p) == hipSuccess) && ok;
@@ -174,15 +197,25 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             B.b_q8[i] = b_q8[first + i];
         }
         if (pl.nhi == 0) {
+            Timed t(ctx, EDEN_K_ENC_SMALL, nb, st);
             launch_enc_small(B, nb, d, log2D, seed, ctx->tables, ctx->dev_status, st);
         } else {
             // top bits first; the first pass reads x, the rest work in place on the workspace
             const int top = pl.nhi - 1;
-            launch_enc_hi_first(pl.M[top], B, nb, d, log2D, pl.p[top], seed, ctx->T, ctx->partials, ctx->partial_stride,
-                                ctx->enc_scratch, ctx->tables, st);
-            for (int i = top - 1; i >= 0; --i) launch_hi_mid(pl.M[i], nb, ctx->T, log2D, pl.p[i], st);
-            launch_enc_lo(B, nb, d, log2D, seed, ctx->T, ctx->partials, ctx->partial_stride, ctx->enc_scratch,
-                          ctx->dev_status, st);
+            {
+                Timed t(ctx, EDEN_K_ENC_HI_FIRST, nb, st);
+                launch_enc_hi_first(pl.M[top], B, nb, d, log2D, pl.p[top], seed, ctx->T, ctx->partials,
+                                    ctx->partial_stride, ctx->enc_scratch, ctx->tables, st);
+            }
+            for (int i = top - 1; i >= 0; --i) {
+                Timed t(ctx, EDEN_K_HI_MID, nb, st);
+                launch_hi_mid(pl.M[i], nb, ctx->T, log2D, pl.p[i], st);
+            }
+            {
+                Timed t(ctx, EDEN_K_ENC_LO, nb, st);
+                launch_enc_lo(B, nb, d, log2D, seed, ctx->T, ctx->partials, ctx->partial_stride, ctx->enc_scratch,
+                              ctx->dev_status, st);
+            }
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
     }
@@ -215,13 +248,26 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             B.b_q8[i] = b_q8[first + i];
         }
         if (pl.nhi == 0) {
+            Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);
             launch_dec_small(B, nb, d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
         } else {
-            launch_dec_prepare(B, nb, d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
-            launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
-            for (int i = 0; i < pl.nhi - 1; ++i) launch_hi_mid(pl.M[i], nb, ctx->T, log2D, pl.p[i], st);
+            {
+                Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
+                launch_dec_prepare(B, nb, d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
+            }
+            {
+                Timed t(ctx, EDEN_K_DEC_LO, nb, st);
+                launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
+            }
+            for (int i = 0; i < pl.nhi - 1; ++i) {
+                Timed t(ctx, EDEN_K_HI_MID, nb, st);
+                launch_hi_mid(pl.M[i], nb, ctx->T, log2D, pl.p[i], st);
+            }
             const int top = pl.nhi - 1;
-            launch_dec_hi_last(pl.M[top], B, nb, d, log2D, pl.p[top], seed, ctx->T, acc_dev, st);
+            {
+                Timed t(ctx, EDEN_K_DEC_HI_LAST, nb, st);
+                launch_dec_hi_last(pl.M[top], B, nb, d, log2D, pl.p[top], seed, ctx->T, acc_dev, st);
+            }
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
     }
@@ -232,7 +278,10 @@ int eden_finalize_mean(eden_ctx *ctx, const float *acc_dev, uint64_t d, uint32_t
     if (!ctx || !acc_dev || !mean_dev || d == 0 || d > ctx->d_max || n == 0) return EDEN_ERR_INVALID_ARG;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return EDEN_ERR_HIP;
-    launch_finalize_mean(acc_dev, d, n, mean_dev, static_cast<hipStream_t>(stream));
+    {
+        Timed t(ctx, EDEN_K_FINALIZE, n, static_cast<hipStream_t>(stream));
+        launch_finalize_mean(acc_dev, d, n, mean_dev, static_cast<hipStream_t>(stream));
+    }
     return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
 }
 
@@ -295,6 +344,47 @@ int eden_get_tables(uint32_t bits, double *thresholds, double *centroids) {
         thresholds[h - 1 - i] = -ht->t[i];
     }
     return EDEN_OK;
+}
+
+int eden_profile_enable(eden_ctx *ctx, uint32_t kind_mask, uint32_t max_records) {
+    if (!ctx || max_records > (1u << 20)) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    while (ctx->prof_start.size() < max_records) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess) return EDEN_ERR_HIP;
+        if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return EDEN_ERR_HIP; }
+        ctx->prof_start.push_back(a);
+        ctx->prof_stop.push_back(b);
+    }
+    ctx->prof_kind.resize(ctx->prof_start.size());
+    ctx->prof_senders.resize(ctx->prof_start.size());
+    ctx->prof_mask = kind_mask;
+    return EDEN_OK;
+}
+
+int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, float *ms, uint32_t cap, uint32_t *count) {
+    if (!ctx || !kinds || !senders || !ms || !count) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    uint32_t n = 0;
+    for (uint32_t i = 0; i < ctx->prof_used && n < cap; ++i, ++n) {
+        if (hipEventSynchronize(ctx->prof_stop[i]) != hipSuccess) return EDEN_ERR_HIP;
+        float t = 0.0f;
+        if (hipEventElapsedTime(&t, ctx->prof_start[i], ctx->prof_stop[i]) != hipSuccess) return EDEN_ERR_HIP;
+        kinds[n] = ctx->prof_kind[i];
+        senders[n] = ctx->prof_senders[i];
+        ms[n] = t;
+    }
+    ctx->prof_used = 0;
+    *count = n;
+    return EDEN_OK;
+}
+
+const char *eden_kernel_name(uint32_t kind) {
+    static const char *names[EDEN_K_COUNT] = {"enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_lo",
+                                              "dec_hi_last", "finalize_mean", "enc_small", "dec_small"};
+    return kind < EDEN_K_COUNT ? names[kind] : "?";
 }
 
 const char *eden_strerror(int status) {

@@ -57,9 +57,7 @@ struct EncScratch {
     double n2;              // |x|^2 (Sec. 2.2.1: equals |R(x)|^2)
     float thr[8];           // positive thresholds of I_b times |x|: compared against |H(s o x)|
     float qpos[8];          // positive centroids
-    unsigned done_first;    // blocks of the first pass that have finished
-    unsigned done_last;     // blocks of the last pass that have finished
-    unsigned pad[2];
+    unsigned pad[4];
 };
 
 // per-message scalars of one decode
@@ -100,6 +98,13 @@ __device__ inline float negate_where(float v, uint64_t mask) {
     float r;
     asm("v_cndmask_b32_e64 %0, %1, -%1, %2" : "=v"(r) : "v"(v), "s"(mask));
     return r;
+}
+
+// The 64-bit value held by lane `src` (compile-time constant), as a wave-uniform scalar.
+__device__ inline uint64_t wave_read64(uint64_t v, int src) {
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, src);
+    const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(v >> 32), src);
+    return ((uint64_t)hi << 32) | lo;
 }
 
 // In-register Walsh-Hadamard butterflies over the register index: (a,b) -> (a+b, a-b) at spans 1..N/2.

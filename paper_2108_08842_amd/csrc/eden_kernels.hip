@@ -36,28 +36,6 @@ __device__ inline double block_sum(double v, double *red /* shared, THREADS/64 *
     return total;
 }
 
-// Writes this block's partial and finds out whether it is the last block of its sender to do so.
-// The last block then sums every partial in index order, so the result does not depend on timing.
-template <int THREADS>
-__device__ inline bool publish_partial(double block_total, double *partials, uint32_t nblocks,
-                                       unsigned *done_counter, double *red, double &grand_total) {
-    __shared__ bool last;
-    if (threadIdx.x == 0) {
-        partials[blockIdx.x] = block_total;
-        __threadfence();
-        const unsigned prev = atomicAdd(done_counter, 1u);
-        last = (prev == nblocks - 1);
-    }
-    __syncthreads();
-    if (!last) return false;
-    __threadfence();
-    double s = 0.0;
-    for (uint32_t i = threadIdx.x; i < nblocks; i += THREADS) s += partials[i];
-    grand_total = block_sum<THREADS>(s, red);
-    if (threadIdx.x == 0) *done_counter = 0;      // ready for the next call
-    return true;
-}
-
 // After |x|^2 is known: the thresholds of I_b scaled to the unnormalised transform.
 // z = eta R(x) = u / |x| (Sec. 2.2.1 with d -> D), so z > t  <=>  u > t |x|.
 __device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8, const DevTables *tab) {
@@ -85,8 +63,7 @@ __device__ inline void hi_tile_origin(uint32_t tile, int p, uint64_t &base) {
 // diagonal of the rotation from the shared seed (Sec. 2.1), |x|^2 for eta and S (Sec. 2.2.1, 2.3).
 template <int M>
 __global__ __launch_bounds__(256) void k_enc_hi_first(EncBatch B, uint64_t d, int log2D, int p, uint64_t seed,
-                                                      float *T, double *partials, uint32_t partial_stride,
-                                                      EncScratch *scratch, const DevTables *tab) {
+                                                      float *T, double *partials, uint32_t partial_stride) {
     constexpr int R = 1 << M;
     __shared__ double red[4];
     const uint32_t c = blockIdx.y;
@@ -106,11 +83,13 @@ __global__ __launch_bounds__(256) void k_enc_hi_first(EncBatch B, uint64_t d, in
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) n2 += (double)v[r] * (double)v[r];
+        // lane r hashes the sign word of row r (all rows at once on the vector unit); row r's word is
+        // then read back as a wave-uniform lane mask
         const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+        const uint64_t my_word = hash_word(key, (base + ((uint64_t)(lane & (R - 1)) << p)) >> 6);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const uint64_t word = hash_word(key, (base + ((uint64_t)r << p)) >> 6);
-            v[r] = negate_where(v[r], word) + 0.0f;          // + 0 turns -0 into +0: no negative zeros enter
+            v[r] = negate_where(v[r], wave_read64(my_word, r)) + 0.0f;   // + 0 turns -0 into +0
         }
         fwht_regs<R>(v);
         float *Tc = T + ((size_t)c << log2D);
@@ -118,11 +97,21 @@ __global__ __launch_bounds__(256) void k_enc_hi_first(EncBatch B, uint64_t d, in
         for (int r = 0; r < R; ++r) Tc[base + ((uint64_t)r << p) + lane] = v[r];
     }
     const double block_total = block_sum<256>(n2, red);
-    double total;
-    if (publish_partial<256>(block_total, partials + (size_t)c * partial_stride, gridDim.x,
-                             &scratch[c].done_first, red, total)) {
-        if (threadIdx.x == 0) fill_enc_scratch(&scratch[c], total, B.b_q8[c], tab);
-    }
+    if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
+}
+
+// One workgroup per sender: sums the per-workgroup partials of |x|^2 in index order (deterministic)
+// and scales the thresholds.  Runs between the first pass and the quantizing pass because eta
+// depends on the whole vector (Sec. 2.2.1).
+__global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *partials, uint32_t partial_stride,
+                                                  uint32_t nparts, EncScratch *scratch, const DevTables *tab) {
+    __shared__ double red[4];
+    const uint32_t c = blockIdx.x;
+    const double *pc = partials + (size_t)c * partial_stride;
+    double s = 0.0;
+    for (uint32_t i = threadIdx.x; i < nparts; i += 256) s += pc[i];
+    const double total = block_sum<256>(s, red);
+    if (threadIdx.x == 0) fill_enc_scratch(&scratch[c], total, B.b_q8[c], tab);
 }
 
 // Middle pass, in place on the workspace (tiles are disjoint).
@@ -168,11 +157,9 @@ __global__ __launch_bounds__(256) void k_dec_hi_last(DecBatch B, uint32_t n, uin
         for (int r = 0; r < R; ++r) v[r] = __builtin_nontemporal_load(Tc + ((uint64_t)r << p));
         fwht_regs<R>(v);
         const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+        const uint64_t my_word = hash_word(key, (base + ((uint64_t)(lane & (R - 1)) << p)) >> 6);
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const uint64_t word = hash_word(key, (base + ((uint64_t)r << p)) >> 6);
-            sum[r] += negate_where(v[r], word);
-        }
+        for (int r = 0; r < R; ++r) sum[r] += negate_where(v[r], wave_read64(my_word, r));
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -217,9 +204,9 @@ __device__ inline void quantize_pack(const float (&v)[64], const EncScratch *s, 
     }
 }
 
-__global__ __launch_bounds__(128) void k_enc_lo(EncBatch B, uint64_t d, int log2D, uint64_t seed, const float *T,
-                                                double *partials, uint32_t partial_stride, EncScratch *scratch,
-                                                uint32_t *dev_status) {
+__global__ __launch_bounds__(128) void k_enc_lo(EncBatch B, int log2D, uint64_t seed, const float *T,
+                                                double *partials, uint32_t partial_stride,
+                                                const EncScratch *scratch) {
     __shared__ float lds[2][64 * kLdsRow];
     __shared__ double red[2];
     const uint32_t c = blockIdx.y;
@@ -290,24 +277,44 @@ __global__ __launch_bounds__(128) void k_enc_lo(EncBatch B, uint64_t d, int log2
     }
 
     const double block_total = block_sum<128>((double)ip, red);
-    double total;
-    if (publish_partial<128>(block_total, partials + (size_t)c * partial_stride, gridDim.x,
-                             &scratch[c].done_last, red, total)) {
-        if (threadIdx.x == 0) {
-            MsgHeader h;
-            h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = b_q8; h.client = B.client[c];
-            h.zero = 0; h.seed = seed; h.N2 = n2;
-            if (valid) {
-                h.IP = total * exp2(-0.5 * (double)log2D);   // <R(x),Q> = D^-1/2 sum u_i q_i
-                h.S = n2 / h.IP;                              // Sec. 2.3
-                h.status = 0;
-            } else {
-                h.IP = 0.0; h.S = 0.0;
-                h.status = (n2 == 0.0) ? EDEN_DEV_ZERO_VECTOR : EDEN_DEV_NONFINITE;
-                atomicOr(dev_status, h.status);
-            }
-            *static_cast<MsgHeader *>(B.msg[c]) = h;
+    if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
+}
+
+// One workgroup per sender: sums the partials of sum_i u_i q_i in index order, forms
+// <R(x),Q> = D^-1/2 sum and the scale S = |x|^2 / <R(x),Q> (Sec. 2.3), writes the header.
+// A zero or non-finite vector gets S = 0, a status bit and an all-zero payload.
+__global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int log2D, uint64_t seed,
+                                                    const double *partials, uint32_t partial_stride, uint32_t nparts,
+                                                    const EncScratch *scratch, uint32_t payload_words_b1,
+                                                    uint32_t *dev_status) {
+    __shared__ double red[4];
+    const uint32_t c = blockIdx.x;
+    const double *pc = partials + (size_t)c * partial_stride;
+    double s = 0.0;
+    for (uint32_t i = threadIdx.x; i < nparts; i += 256) s += pc[i];
+    const double total = block_sum<256>(s, red);
+    const double n2 = scratch[c].n2;
+    const bool valid = (n2 > 0.0) && (n2 < INFINITY);
+    const uint32_t b_q8 = B.b_q8[c];
+    if (!valid) {
+        uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+        const uint64_t nw = ((uint64_t)payload_words_b1 * b_q8) >> 8;      // payload words for this budget
+        for (uint64_t i = threadIdx.x; i < nw; i += 256) payload[i] = 0u;
+    }
+    if (threadIdx.x == 0) {
+        MsgHeader h;
+        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = b_q8; h.client = B.client[c];
+        h.zero = 0; h.seed = seed; h.N2 = n2;
+        if (valid) {
+            h.IP = total * exp2(-0.5 * (double)log2D);       // <R(x),Q> = D^-1/2 sum u_i q_i
+            h.S = n2 / h.IP;                                  // Sec. 2.3
+            h.status = 0;
+        } else {
+            h.IP = 0.0; h.S = 0.0;
+            h.status = (n2 == 0.0) ? EDEN_DEV_ZERO_VECTOR : EDEN_DEV_NONFINITE;
+            atomicOr(dev_status, h.status);
         }
+        *static_cast<MsgHeader *>(B.msg[c]) = h;
     }
 }
 
@@ -625,7 +632,8 @@ void launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int l
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
     EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_enc_hi_first<MM>, grid, dim3(256), 0, st, B, d, log2D, p, seed, T, partials,
-                                         partial_stride, scratch, tab));
+                                         partial_stride));
+    hipLaunchKernelGGL(k_enc_norm, dim3(n), dim3(256), 0, st, B, partials, partial_stride, grid.x, scratch, tab);
 }
 void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
@@ -641,7 +649,10 @@ void launch_dec_hi_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int lo
 void launch_enc_lo(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T, double *partials,
                    uint32_t partial_stride, EncScratch *scratch, uint32_t *dev_status, hipStream_t st) {
     dim3 grid(1u << (log2D - kLoBits - 1), n);
-    hipLaunchKernelGGL(k_enc_lo, grid, dim3(128), 0, st, B, d, log2D, seed, T, partials, partial_stride, scratch, dev_status);
+    hipLaunchKernelGGL(k_enc_lo, grid, dim3(128), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
+    const uint32_t words_b1 = 1u << (log2D - 5);
+    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, log2D, seed, partials, partial_stride, grid.x,
+                       scratch, words_b1, dev_status);
 }
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st) {

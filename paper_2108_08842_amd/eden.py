@@ -28,8 +28,11 @@ PACKET_COORDS = 1024
 EXPORTS = [
     "eden_create", "eden_destroy", "eden_message_bytes", "eden_encode", "eden_decode_accumulate",
     "eden_finalize_mean", "eden_last_device_status", "eden_make_loss_bitmap", "eden_make_sign_bits",
-    "eden_make_subsample_bits", "eden_get_tables", "eden_strerror",
+    "eden_make_subsample_bits", "eden_get_tables", "eden_strerror", "eden_profile_enable", "eden_profile_collect",
+    "eden_kernel_name",
 ]
+KERNEL_KINDS = ["enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_lo", "dec_hi_last", "finalize_mean",
+                "enc_small", "dec_small"]
 
 
 class EdenError(RuntimeError):
@@ -74,6 +77,12 @@ def lib():
     L.eden_get_tables.restype = ci
     L.eden_strerror.argtypes = [ci]
     L.eden_strerror.restype = ctypes.c_char_p
+    L.eden_profile_enable.argtypes = [vp, u32, u32]
+    L.eden_profile_enable.restype = ci
+    L.eden_profile_collect.argtypes = [vp, P(u32), P(u32), P(ctypes.c_float), u32, P(u32)]
+    L.eden_profile_collect.restype = ci
+    L.eden_kernel_name.argtypes = [u32]
+    L.eden_kernel_name.restype = ctypes.c_char_p
     _lib = L
     return L
 
@@ -190,6 +199,26 @@ class Context:
         if rc != OK:
             raise EdenError(rc, "eden_last_device_status")
         return int(v.value)
+
+    def profile_enable(self, kinds, max_records: int = 4096):
+        """Time every launch of the named kernel kinds with HIP events (empty list = off)."""
+        mask = 0
+        for k in kinds:
+            mask |= 1 << KERNEL_KINDS.index(k)
+        rc = lib().eden_profile_enable(self._h, mask, max_records)
+        if rc != OK:
+            raise EdenError(rc, "eden_profile_enable")
+
+    def profile_collect(self, cap: int = 4096):
+        """-> list of (kernel kind name, senders in the launch, milliseconds), in launch order."""
+        kinds = (ctypes.c_uint32 * cap)()
+        senders = (ctypes.c_uint32 * cap)()
+        ms = (ctypes.c_float * cap)()
+        cnt = ctypes.c_uint32(0)
+        rc = lib().eden_profile_collect(self._h, kinds, senders, ms, cap, ctypes.byref(cnt))
+        if rc != OK:
+            raise EdenError(rc, "eden_profile_collect")
+        return [(KERNEL_KINDS[kinds[i]], int(senders[i]), float(ms[i])) for i in range(cnt.value)]
 
     def make_loss_bitmap(self, seed: int, client: int, D: int, drop_q32: int, stream=None):
         import torch
