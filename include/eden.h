@@ -167,7 +167,9 @@ typedef enum eden_kernel_kind {
     EDEN_K_FINALIZE = 6,       /* division by n */
     EDEN_K_ENC_SMALL = 7,      /* encode, D <= 4096, one workgroup per sender */
     EDEN_K_DEC_SMALL = 8,      /* decode, D <= 4096 */
-    EDEN_K_COUNT = 9
+    EDEN_K_ENC_NORM = 9,       /* encode: |x|^2 from per-workgroup partials, scaled thresholds */
+    EDEN_K_ENC_FINISH = 10,    /* encode: <R(x),Q>, S, header */
+    EDEN_K_COUNT = 11
 } eden_kernel_kind;
 int eden_profile_enable(eden_ctx *ctx, uint32_t kind_mask, uint32_t max_records);
 int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, float *ms, uint32_t cap,

@@ -43,23 +43,28 @@ int ceil_log2(uint64_t d) {
     return l;
 }
 
-// Split of the index bits above the lo pass into hi passes of at most 6 bits, as even as possible.
+// Pass plan.  The contiguous pass covers the low 12 bits (wave tiles) or 14 bits (workgroup tiles); the
+// bits above it are covered by one or two strided passes: wave tiles handle up to 6 bits each,
+// workgroup tiles 7..10 bits.  D <= 2^24 needs two passes in all, D up to 2^27 three.
+struct HiPass {
+    bool wg;    // workgroup-tile kernel (32-column tiles) or wave-tile kernel (64-column tiles)
+    int M, p;   // bits transformed, lowest bit
+};
 struct Plan {
+    int lo_bits;        // 0: single-workgroup path (D <= 4096)
     int nhi;
-    int M[4];
-    int p[4];   // lowest bit of each hi pass, ascending
+    HiPass hi[2];       // ascending p
 };
 Plan make_plan(int log2D) {
     Plan pl{};
-    const int hi_bits = log2D - kLoBits;
-    if (hi_bits <= 0) return pl;
-    pl.nhi = (hi_bits + 5) / 6;
-    int pos = kLoBits;
-    for (int i = 0; i < pl.nhi; ++i) {
-        const int m = hi_bits / pl.nhi + (i < hi_bits % pl.nhi ? 1 : 0);
-        pl.M[i] = m;
-        pl.p[i] = pos;
-        pos += m;
+    if (log2D <= kLoBits) return pl;
+    if (log2D <= 18) {
+        pl.lo_bits = 12; pl.nhi = 1; pl.hi[0] = {false, log2D - 12, 12};
+    } else if (log2D <= 24) {
+        const int M = log2D - 14;
+        pl.lo_bits = 14; pl.nhi = 1; pl.hi[0] = {M > 6, M, 14};
+    } else {
+        pl.lo_bits = 14; pl.nhi = 2; pl.hi[0] = {true, 10, 14}; pl.hi[1] = {false, log2D - 24, 24};
     }
     return pl;
 }
@@ -196,26 +201,40 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             B.client[i] = client_ids[first + i];
             B.b_q8[i] = b_q8[first + i];
         }
-        if (pl.nhi == 0) {
+        if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_ENC_SMALL, nb, st);
             launch_enc_small(B, nb, d, log2D, seed, ctx->tables, ctx->dev_status, st);
         } else {
             // top bits first; the first pass reads x, the rest work in place on the workspace
-            const int top = pl.nhi - 1;
-            {
-                Timed t(ctx, EDEN_K_ENC_HI_FIRST, nb, st);
-                launch_enc_hi_first(pl.M[top], B, nb, d, log2D, pl.p[top], seed, ctx->T, ctx->partials,
-                                    ctx->partial_stride, ctx->enc_scratch, ctx->tables, st);
-            }
-            for (int i = top - 1; i >= 0; --i) {
-                Timed t(ctx, EDEN_K_HI_MID, nb, st);
-                launch_hi_mid(pl.M[i], nb, ctx->T, log2D, pl.p[i], st);
+            uint32_t nparts = 0;
+            for (int i = pl.nhi - 1; i >= 0; --i) {
+                const HiPass &h = pl.hi[i];
+                if (i == pl.nhi - 1) {
+                    {
+                        Timed t(ctx, EDEN_K_ENC_HI_FIRST, nb, st);
+                        nparts = h.wg ? launch_hix_first(h.M, B, nb, d, log2D, h.p, seed, ctx->T, ctx->partials,
+                                                         ctx->partial_stride, st)
+                                      : launch_enc_hi_first(h.M, B, nb, d, log2D, h.p, seed, ctx->T, ctx->partials,
+                                                            ctx->partial_stride, st);
+                    }
+                    Timed t(ctx, EDEN_K_ENC_NORM, nb, st);
+                    launch_enc_norm(B, nb, ctx->partials, ctx->partial_stride, nparts, ctx->enc_scratch, ctx->tables, st);
+                } else {
+                    Timed t(ctx, EDEN_K_HI_MID, nb, st);
+                    if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
+                    else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
+                }
             }
             {
                 Timed t(ctx, EDEN_K_ENC_LO, nb, st);
-                launch_enc_lo(B, nb, d, log2D, seed, ctx->T, ctx->partials, ctx->partial_stride, ctx->enc_scratch,
-                              ctx->dev_status, st);
+                nparts = pl.lo_bits == 14 ? launch_enc_lo14(B, nb, log2D, seed, ctx->T, ctx->partials, ctx->partial_stride,
+                                                            ctx->enc_scratch, st)
+                                          : launch_enc_lo(B, nb, log2D, seed, ctx->T, ctx->partials, ctx->partial_stride,
+                                                          ctx->enc_scratch, st);
             }
+            Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
+            launch_enc_finish(B, nb, d, log2D, seed, ctx->partials, ctx->partial_stride, nparts, ctx->enc_scratch,
+                              ctx->dev_status, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
     }
@@ -247,7 +266,7 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             B.client[i] = client_ids[first + i];
             B.b_q8[i] = b_q8[first + i];
         }
-        if (pl.nhi == 0) {
+        if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);
             launch_dec_small(B, nb, d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
         } else {
@@ -257,16 +276,20 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             }
             {
                 Timed t(ctx, EDEN_K_DEC_LO, nb, st);
-                launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
+                if (pl.lo_bits == 14) launch_dec_lo14(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
+                else launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
             }
-            for (int i = 0; i < pl.nhi - 1; ++i) {
-                Timed t(ctx, EDEN_K_HI_MID, nb, st);
-                launch_hi_mid(pl.M[i], nb, ctx->T, log2D, pl.p[i], st);
-            }
-            const int top = pl.nhi - 1;
-            {
-                Timed t(ctx, EDEN_K_DEC_HI_LAST, nb, st);
-                launch_dec_hi_last(pl.M[top], B, nb, d, log2D, pl.p[top], seed, ctx->T, acc_dev, st);
+            for (int i = 0; i < pl.nhi; ++i) {
+                const HiPass &h = pl.hi[i];
+                if (i < pl.nhi - 1) {
+                    Timed t(ctx, EDEN_K_HI_MID, nb, st);
+                    if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
+                    else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
+                } else {
+                    Timed t(ctx, EDEN_K_DEC_HI_LAST, nb, st);
+                    if (h.wg) launch_hix_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, acc_dev, st);
+                    else launch_dec_hi_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, acc_dev, st);
+                }
             }
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
@@ -383,7 +406,8 @@ int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, floa
 
 const char *eden_kernel_name(uint32_t kind) {
     static const char *names[EDEN_K_COUNT] = {"enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_lo",
-                                              "dec_hi_last", "finalize_mean", "enc_small", "dec_small"};
+                                              "dec_hi_last", "finalize_mean", "enc_small", "dec_small",
+                                              "enc_norm", "enc_finish"};
     return kind < EDEN_K_COUNT ? names[kind] : "?";
 }
 

@@ -135,5 +135,58 @@ __device__ inline uint32_t wave_sum_u32(uint32_t v) {
     return v;
 }
 
+// block-level deterministic sum of one double per thread; result valid in thread 0
+template <int THREADS>
+__device__ inline double block_sum(double v, double *red /* shared, THREADS/64 */) {
+    v = wave_sum(v);
+    const uint32_t w = threadIdx.x >> 6;
+    if (lane_id() == 0) red[w] = v;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < THREADS / 64; ++i) total += red[i];
+    }
+    __syncthreads();
+    return total;
+}
+
+// Interval rank of one coordinate of the unnormalised transform against the scaled thresholds of I_b
+// (Sec. 2.2.1, Sec. 3), and its contribution |u| q to sum_i u_i Q_i (Sec. 2.3).  H = 2^(b-1) levels per sign.
+// A value exactly on a threshold stays in the interval closer to zero (strict compare); u = +0 is
+// non-negative.  thr[0] is unused (it is the threshold 0, decided by the sign).
+template <int H>
+__device__ inline uint32_t quantize_one(float u, const float (&thr)[H], const float (&qp)[H], float &ip) {
+    const float a = fabsf(u);
+    uint32_t mag = 0;
+    float qa = qp[0];
+#pragma unroll
+    for (int t = 1; t < H; ++t) {
+        const bool above = a > thr[t];
+        mag = above ? (uint32_t)t : mag;
+        qa = above ? qp[t] : qa;
+    }
+    ip = fmaf(a, qa, ip);
+    const uint32_t neg = __float_as_uint(u) >> 31;
+    return neg ? (uint32_t)(H - 1) - mag : (uint32_t)H + mag;
+}
+
+// Butterflies over the low LOGB bits of the register index only.
+template <int N, int LOGB>
+__device__ inline void fwht_regs_low(float (&v)[N]) {
+#pragma unroll
+    for (int h = 1; h < (1 << LOGB); h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < N; i += 2 * h) {
+#pragma unroll
+            for (int j = i; j < i + h; ++j) {
+                const float a = v[j], b = v[j + h];
+                v[j] = a + b;
+                v[j + h] = a - b;
+            }
+        }
+    }
+}
+
 }  // namespace eden
 #endif

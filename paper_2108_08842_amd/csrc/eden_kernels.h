@@ -7,15 +7,20 @@
 
 namespace eden {
 
-void launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
-                         double *partials, uint32_t partial_stride, EncScratch *scratch, const DevTables *tab,
-                         hipStream_t st);
+// wave-tile passes (eden_kernels.hip).  Launchers of kernels that leave per-workgroup partial sums
+// return how many partials each sender got.
+uint32_t launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
+                             double *partials, uint32_t partial_stride, hipStream_t st);
+void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint32_t partial_stride, uint32_t nparts,
+                     EncScratch *scratch, const DevTables *tab, hipStream_t st);
+void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials,
+                       uint32_t partial_stride, uint32_t nparts, const EncScratch *scratch, uint32_t *dev_status,
+                       hipStream_t st);
 void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
 void launch_dec_hi_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed,
                         const float *T, float *acc, hipStream_t st);
-void launch_enc_lo(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
-                   double *partials, uint32_t partial_stride, EncScratch *scratch, uint32_t *dev_status,
-                   hipStream_t st);
+uint32_t launch_enc_lo(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
+                       uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st);
 void launch_dec_lo(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, float *T,
@@ -27,6 +32,17 @@ void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint
                       float *acc, uint32_t *dev_status, hipStream_t st);
 void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st);
 void launch_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t *bitmap, hipStream_t st);
+
+// workgroup-tile passes for D >= 2^19 (eden_kernels_wg.hip)
+uint32_t launch_hix_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
+                          double *partials, uint32_t partial_stride, hipStream_t st);
+void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
+void launch_hix_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, const float *T,
+                     float *acc, hipStream_t st);
+uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
+                         uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
+void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, float *T,
+                     hipStream_t st);
 
 }  // namespace eden
 #endif

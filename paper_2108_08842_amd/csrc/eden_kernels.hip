@@ -19,23 +19,6 @@
 
 namespace eden {
 
-// ------------------------------------------------------------------------------------------------
-// block-level deterministic sum of one double per thread; result valid in thread 0
-template <int THREADS>
-__device__ inline double block_sum(double v, double *red /* shared, THREADS/64 */) {
-    v = wave_sum(v);
-    const uint32_t w = threadIdx.x >> 6;
-    if (lane_id() == 0) red[w] = v;
-    __syncthreads();
-    double total = 0.0;
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int i = 0; i < THREADS / 64; ++i) total += red[i];
-    }
-    __syncthreads();
-    return total;
-}
-
 // After |x|^2 is known: the thresholds of I_b scaled to the unnormalised transform.
 // z = eta R(x) = u / |x| (Sec. 2.2.1 with d -> D), so z > t  <=>  u > t |x|.
 __device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8, const DevTables *tab) {
@@ -626,14 +609,24 @@ __global__ void k_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uin
         default: { constexpr int MM = 6; CALL; } break; \
     }
 
-void launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
-                         double *partials, uint32_t partial_stride, EncScratch *scratch, const DevTables *tab,
-                         hipStream_t st) {
+uint32_t launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
+                             double *partials, uint32_t partial_stride, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
     EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_enc_hi_first<MM>, grid, dim3(256), 0, st, B, d, log2D, p, seed, T, partials,
                                          partial_stride));
-    hipLaunchKernelGGL(k_enc_norm, dim3(n), dim3(256), 0, st, B, partials, partial_stride, grid.x, scratch, tab);
+    return grid.x;
+}
+void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint32_t partial_stride, uint32_t nparts,
+                     EncScratch *scratch, const DevTables *tab, hipStream_t st) {
+    hipLaunchKernelGGL(k_enc_norm, dim3(n), dim3(256), 0, st, B, partials, partial_stride, nparts, scratch, tab);
+}
+void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials,
+                       uint32_t partial_stride, uint32_t nparts, const EncScratch *scratch, uint32_t *dev_status,
+                       hipStream_t st) {
+    const uint32_t words_b1 = 1u << (log2D - 5);
+    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, log2D, seed, partials, partial_stride, nparts,
+                       scratch, words_b1, dev_status);
 }
 void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
@@ -646,13 +639,11 @@ void launch_dec_hi_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int lo
     dim3 grid((ntiles + 3) / 4);
     EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_last<MM>, grid, dim3(256), 0, st, B, n, d, log2D, p, seed, T, acc));
 }
-void launch_enc_lo(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T, double *partials,
-                   uint32_t partial_stride, EncScratch *scratch, uint32_t *dev_status, hipStream_t st) {
+uint32_t launch_enc_lo(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
+                       uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
     dim3 grid(1u << (log2D - kLoBits - 1), n);
     hipLaunchKernelGGL(k_enc_lo, grid, dim3(128), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
-    const uint32_t words_b1 = 1u << (log2D - 5);
-    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, log2D, seed, partials, partial_stride, grid.x,
-                       scratch, words_b1, dev_status);
+    return grid.x;
 }
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st) {

@@ -1,0 +1,460 @@
+// Workgroup-tile passes of the Walsh-Hadamard transform for large D (2^19 .. 2^27), gfx950.
+//
+// Two passes through memory are enough for D <= 2^24 when a workgroup keeps 2^14 .. 2^15 coordinates
+// on chip (registers + one or two exchanges through LDS):
+//
+//   hiX pass  index bits p .. p+M-1, M = 7..10: a workgroup owns 2^M rows of 32 consecutive coordinates
+//             (128-byte segments) at stride 2^p.  Every thread keeps 64 rows of one column in registers
+//             (six butterfly stages), the remaining M-6 row bits are reached by one exchange through
+//             LDS (for M = 10 in two halves of 64 KiB so that two workgroups fit on a CU).
+//   lo14 pass index bits 0 .. 13: four waves, each transforms 4096 consecutive coordinates in
+//             registers (6 + 6 bits with a wave-private 64x64 LDS transpose), then one exchange between
+//             the four waves gives bits 12 and 13.
+//
+// Fusions are those of the wave-tile kernels: the first encode pass reads x, applies the rotation's sign
+// diagonal and sums |x|^2 (Sec. 2.1, 2.2.1); the last encode pass quantizes against the Lloyd-Max
+// thresholds, accumulates <R(x),Q> and packs (Sec. 2.2.1, 2.3, 3, 4.1); the first decode pass unpacks and
+// dequantizes with S/(p sqrt D) (Sec. 2.2.2, 4.2); the last decode pass applies the signs and sums the
+// senders in registers.
+#include "eden_device.h"
+#include "eden_kernels.h"
+
+namespace eden {
+
+// ------------------------------------------------------------------------------------------------
+template <int M>
+struct HiX {
+    static constexpr int RL = 1 << (M - 6);       // row groups: the low M-6 row bits live across thread groups
+    static constexpr int THREADS = 32 * RL;
+    static constexpr int PH = (M == 10) ? 2 : 1;  // halves of the exchange
+    static constexpr int RP = 64 / PH;            // registers exchanged per half
+    static constexpr int RHL = RP / RL;           // high-row values a thread holds after the exchange
+    static constexpr int LDS_FLOATS = RP * RL * 32;
+};
+
+template <int M>
+__device__ inline uint64_t hix_base(uint32_t tile, int p) {
+    const uint32_t cb_bits = (uint32_t)p - 5u;                   // 2^(p-5) blocks of 32 columns
+    const uint32_t cb = tile & ((1u << cb_bits) - 1u);
+    const uint32_t upper = tile >> cb_bits;
+    return ((uint64_t)upper << (p + M)) | ((uint64_t)cb << 5);
+}
+
+// row held in stage-1 register r by a thread of group g
+template <int M>
+__device__ inline uint32_t hix_row1(uint32_t g, uint32_t r) { return g + (uint32_t)HiX<M>::RL * r; }
+// row held after the exchange of half ph in register s by a thread of group g
+template <int M>
+__device__ inline uint32_t hix_row2(uint32_t g, int ph, int s) {
+    using X = HiX<M>;
+    const uint32_t e = (uint32_t)s / X::RL, rl = (uint32_t)s % X::RL;
+    const uint32_t rh = (uint32_t)ph * X::RP + g * X::RHL + e;
+    return rl + (uint32_t)X::RL * rh;
+}
+
+// Exchange of half `PHASE`: stage-1 registers -> LDS -> registers that hold all low row bits of
+// RHL high-row values; then the butterflies over those low row bits.
+template <int M, int PHASE>
+__device__ inline void hix_exchange(const float (&v)[64], float *lds, float (&out)[HiX<M>::RP]) {
+    using X = HiX<M>;
+    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
+#pragma unroll
+    for (int i = 0; i < X::RP; ++i) lds[(i * X::RL + g) * 32 + col] = v[PHASE * X::RP + i];
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < X::RP; ++s) {
+        const int e = s / X::RL, rl = s % X::RL;
+        out[s] = lds[((g * X::RHL + e) * X::RL + rl) * 32 + col];
+    }
+    __syncthreads();
+    fwht_regs_low<X::RP, M - 6>(out);
+}
+
+// The 32 sign bits of the rotation's diagonal for one row segment of a tile.
+__device__ inline uint32_t sign_half_word(uint64_t key, uint64_t first_index) {
+    const uint64_t word = hash_word(key, first_index >> 6);
+    return (uint32_t)(word >> (((first_index >> 5) & 1ull) * 32));
+}
+__device__ inline uint64_t pair_mask(uint32_t lo_words, uint32_t hi_words, int src) {
+    const uint32_t lo = __builtin_amdgcn_readlane(lo_words, src);
+    const uint32_t hi = __builtin_amdgcn_readlane(hi_words, src);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+template <int M>
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_first(EncBatch B, uint64_t d, int log2D, int p,
+                                                                uint64_t seed, float *T, double *partials,
+                                                                uint32_t partial_stride) {
+    using X = HiX<M>;
+    __shared__ float lds[X::LDS_FLOATS];
+    __shared__ double red[X::THREADS / 64];
+    const uint32_t c = blockIdx.y;
+    const uint64_t base = hix_base<M>(blockIdx.x, p);
+    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
+    const uint32_t g0 = 2u * wave_in_block();                    // the two groups of this wave: g0, g0 + 1
+    const float *x = B.x[c];
+    float v[64];
+#pragma unroll
+    for (int r = 0; r < 64; ++r) {
+        const uint64_t i = base + ((uint64_t)hix_row1<M>(g, r) << p) + col;
+        v[r] = (i < d) ? __builtin_nontemporal_load(x + i) : 0.0f;
+    }
+    double n2 = 0.0;
+#pragma unroll
+    for (int r = 0; r < 64; ++r) n2 += (double)v[r] * (double)v[r];
+    // lane l hashes the sign bits of register l's two row segments; register r reads them back as a lane mask
+    const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+    const uint32_t wa = sign_half_word(key, base + ((uint64_t)hix_row1<M>(g0, lane) << p));
+    const uint32_t wb = sign_half_word(key, base + ((uint64_t)hix_row1<M>(g0 + 1, lane) << p));
+#pragma unroll
+    for (int r = 0; r < 64; ++r) v[r] = negate_where(v[r], pair_mask(wa, wb, r)) + 0.0f;   // + 0: no negative zeros
+    fwht_regs<64>(v);
+    float *Tc = T + ((size_t)c << log2D) + base + col;
+    float out[X::RP];
+    hix_exchange<M, 0>(v, lds, out);
+#pragma unroll
+    for (int s = 0; s < X::RP; ++s) Tc[(uint64_t)hix_row2<M>(g, 0, s) << p] = out[s];
+    if constexpr (X::PH == 2) {
+        hix_exchange<M, 1>(v, lds, out);
+#pragma unroll
+        for (int s = 0; s < X::RP; ++s) Tc[(uint64_t)hix_row2<M>(g, 1, s) << p] = out[s];
+    }
+    const double block_total = block_sum<X::THREADS>(n2, red);
+    if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
+}
+
+template <int M>
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D, int p) {
+    using X = HiX<M>;
+    __shared__ float lds[X::LDS_FLOATS];
+    const uint64_t base = hix_base<M>(blockIdx.x, p);
+    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
+    float *Tc = T + ((size_t)blockIdx.y << log2D) + base + col;
+    float v[64];
+#pragma unroll
+    for (int r = 0; r < 64; ++r) v[r] = Tc[(uint64_t)hix_row1<M>(g, r) << p];
+    fwht_regs<64>(v);
+    float out[X::RP];
+    hix_exchange<M, 0>(v, lds, out);
+#pragma unroll
+    for (int s = 0; s < X::RP; ++s) Tc[(uint64_t)hix_row2<M>(g, 0, s) << p] = out[s];
+    if constexpr (X::PH == 2) {
+        hix_exchange<M, 1>(v, lds, out);
+#pragma unroll
+        for (int s = 0; s < X::RP; ++s) Tc[(uint64_t)hix_row2<M>(g, 1, s) << p] = out[s];
+    }
+}
+
+// Decode, last pass (Sec. 2.2.2): finish H for every sender of the batch, apply that sender's sign diagonal,
+// add; acc is read and written once.
+template <int M>
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_last(DecBatch B, uint32_t n, uint64_t d, int log2D, int p,
+                                                               uint64_t seed, const float *T, float *acc) {
+    using X = HiX<M>;
+    __shared__ float lds[X::LDS_FLOATS];
+    const uint64_t base = hix_base<M>(blockIdx.x, p);
+    if (base >= d) return;                                       // the whole tile lies in the padding
+    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
+    const uint32_t g0 = 2u * wave_in_block();
+    float sum[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) sum[i] = 0.0f;
+    // lane l <-> (half, register) = (l / RP, l % RP): the rows whose sign bits this lane hashes
+    const uint64_t rowa = (uint64_t)hix_row2<M>(g0, (int)(lane / X::RP), (int)(lane % X::RP)) << p;
+    const uint64_t rowb = (uint64_t)hix_row2<M>(g0 + 1, (int)(lane / X::RP), (int)(lane % X::RP)) << p;
+    for (uint32_t c = 0; c < n; ++c) {
+        const float *Tc = T + ((size_t)c << log2D) + base + col;
+        float v[64];
+#pragma unroll
+        for (int r = 0; r < 64; ++r) v[r] = __builtin_nontemporal_load(Tc + ((uint64_t)hix_row1<M>(g, r) << p));
+        fwht_regs<64>(v);
+        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+        const uint32_t wa = sign_half_word(key, base + rowa);
+        const uint32_t wb = sign_half_word(key, base + rowb);
+        float out[X::RP];
+        hix_exchange<M, 0>(v, lds, out);
+#pragma unroll
+        for (int s = 0; s < X::RP; ++s) sum[s] += negate_where(out[s], pair_mask(wa, wb, s));
+        if constexpr (X::PH == 2) {
+            hix_exchange<M, 1>(v, lds, out);
+#pragma unroll
+            for (int s = 0; s < X::RP; ++s) sum[X::RP + s] += negate_where(out[s], pair_mask(wa, wb, X::RP + s));
+        }
+    }
+#pragma unroll
+    for (int ph = 0; ph < X::PH; ++ph) {
+#pragma unroll
+        for (int s = 0; s < X::RP; ++s) {
+            const uint64_t i = base + ((uint64_t)hix_row2<M>(g, ph, s) << p) + col;
+            if (i < d) acc[i] += sum[ph * X::RP + s];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// lo14
+constexpr int kLo14Bits = 14;
+constexpr int kLo14Lds = 4 * 64 * kLdsRow;       // floats
+
+// 4 waves x 4096 coordinates.  On return thread t holds, for each of the four 4096-regions r, the final
+// values of the 16 consecutive coordinates  tile*2^14 + r*4096 + 64*(t >> 2) + 16*(t & 3) + kk.
+__device__ inline void lo14_forward(const float *Tt /* tile start */, float *lds, float (&u)[4][16]) {
+    const uint32_t lane = lane_id(), wv = wave_in_block();
+    float v[64];
+#pragma unroll
+    for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(Tt + wv * 4096u + 64 * j + lane);
+    fwht_regs<64>(v);                                            // bits 6..11
+    float *L = lds + wv * (64 * kLdsRow);
+#pragma unroll
+    for (int j = 0; j < 64; ++j) L[j * kLdsRow + lane] = v[j];
+    wave_lds_sync();
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const float4 t = *reinterpret_cast<const float4 *>(&L[lane * kLdsRow + 4 * q]);
+        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+    }
+    fwht_regs<64>(v);                                            // bits 0..5
+    wave_lds_sync();
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+        *reinterpret_cast<float4 *>(&L[lane * kLdsRow + 4 * q]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    __syncthreads();
+    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 t = *reinterpret_cast<const float4 *>(&lds[(r * 64 + src) * kLdsRow + 16 * kq + 4 * i]);
+            u[r][4 * i] = t.x; u[r][4 * i + 1] = t.y; u[r][4 * i + 2] = t.z; u[r][4 * i + 3] = t.w;
+        }
+    }
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {                            // bits 12, 13
+        const float a = u[0][kk] + u[1][kk], b = u[0][kk] - u[1][kk];
+        const float c = u[2][kk] + u[3][kk], e = u[2][kk] - u[3][kk];
+        u[0][kk] = a + c; u[1][kk] = b + e; u[2][kk] = a - c; u[3][kk] = b - e;
+    }
+}
+
+// The mirror image for decode: u (same layout as above, not yet transformed) -> T.
+__device__ inline void lo14_backward(float (&u)[4][16], float *lds, float *Tt) {
+    const uint32_t lane = lane_id(), wv = wave_in_block();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+        const float a = u[0][kk] + u[1][kk], b = u[0][kk] - u[1][kk];
+        const float c = u[2][kk] + u[3][kk], e = u[2][kk] - u[3][kk];
+        u[0][kk] = a + c; u[1][kk] = b + e; u[2][kk] = a - c; u[3][kk] = b - e;
+    }
+    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<float4 *>(&lds[(r * 64 + src) * kLdsRow + 16 * kq + 4 * i]) =
+                make_float4(u[r][4 * i], u[r][4 * i + 1], u[r][4 * i + 2], u[r][4 * i + 3]);
+    }
+    __syncthreads();
+    float *L = lds + wv * (64 * kLdsRow);
+    float v[64];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const float4 t = *reinterpret_cast<const float4 *>(&L[lane * kLdsRow + 4 * q]);
+        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+    }
+    fwht_regs<64>(v);                                            // bits 0..5
+    wave_lds_sync();
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+        *reinterpret_cast<float4 *>(&L[lane * kLdsRow + 4 * q]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    wave_lds_sync();
+#pragma unroll
+    for (int j = 0; j < 64; ++j) v[j] = L[j * kLdsRow + lane];
+    fwht_regs<64>(v);                                            // bits 6..11
+#pragma unroll
+    for (int j = 0; j < 64; ++j) Tt[wv * 4096u + 64 * j + lane] = v[j];
+}
+
+__device__ inline uint32_t quad_swap1(uint32_t x) {   // value of lane ^ 1
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);
+}
+__device__ inline uint32_t quad_swap2(uint32_t x) {   // value of lane ^ 2
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true);
+}
+
+template <int BITS>
+__device__ inline void lo14_quantize_store(const float (&u)[4][16], const EncScratch *s, uint32_t *payload,
+                                           uint64_t tile_base, float &ip) {
+    constexpr int H = 1 << (BITS - 1);
+    float thr[H], qp[H];
+#pragma unroll
+    for (int i = 0; i < H; ++i) { thr[i] = s->thr[i]; qp[i] = s->qpos[i]; }
+    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint64_t first = tile_base + (uint64_t)r * 4096u + 64u * src + 16u * kq;   // first coordinate of the run
+        uint32_t w[BITS / 2] = {};
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const uint32_t code = quantize_one<H>(u[r][kk], thr, qp, ip);
+            w[(kk * BITS) / 32] |= code << ((kk * BITS) % 32);
+        }
+        if constexpr (BITS == 2) payload[first >> 4] = w[0];
+        else *reinterpret_cast<uint2 *>(payload + (first >> 3)) = make_uint2(w[0], w[1]);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_enc_lo14(EncBatch B, int log2D, uint64_t seed, const float *T, double *partials,
+                                                  uint32_t partial_stride, const EncScratch *scratch) {
+    __shared__ __attribute__((aligned(16))) float lds[kLo14Lds];
+    __shared__ double red[4];
+    const uint32_t c = blockIdx.y;
+    const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
+    float u[4][16];
+    lo14_forward(T + ((size_t)c << log2D) + tile_base, lds, u);
+
+    const EncScratch *s = &scratch[c];
+    const uint32_t b_q8 = B.b_q8[c];
+    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
+    float ip = 0.0f;
+    if (b_q8 == 256 || b_q8 == 128) {
+        float sa = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) sa += fabsf(u[r][kk]);
+        ip = sa * s->qpos[0];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint64_t run = tile_base + (uint64_t)r * 4096u + 64u * src;       // this quad's 64 coordinates
+            if (b_q8 == 256) {
+                uint32_t neg = 0;                                // sign bits, last coordinate first
+#pragma unroll
+                for (int kk = 15; kk >= 0; --kk) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(u[r][kk]), 31);
+                const uint32_t mine = ~neg & 0xFFFFu;            // index 1 = non-negative
+                const uint32_t other = quad_swap1(mine);
+                if (!(kq & 1u)) payload[(run >> 5) + (kq >> 1)] = mine | (other << 16);
+            } else {
+                uint32_t ev = 0, od = 0;
+#pragma unroll
+                for (int g = 7; g >= 0; --g) {
+                    ev = __builtin_amdgcn_alignbit(ev, __float_as_uint(u[r][2 * g]), 31);
+                    od = __builtin_amdgcn_alignbit(od, __float_as_uint(u[r][2 * g + 1]), 31);
+                }
+                const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+                const uint64_t hw = hash_word(key, run >> 7);    // 64 pairs per hash word = 128 coordinates
+                const uint32_t off = (uint32_t)(hw >> (((run >> 6) & 1ull) * 32 + 8 * kq)) & 0xFFu;
+                uint32_t piece = (((~ev & ~off) | (~od & off)) & 0xFFu) << (8 * kq);
+                piece |= quad_swap1(piece);
+                piece |= quad_swap2(piece);
+                if (kq == 0) payload[run >> 6] = piece;
+            }
+        }
+    } else if (b_q8 == 512) {
+        lo14_quantize_store<2>(u, s, payload, tile_base, ip);
+    } else {
+        lo14_quantize_store<4>(u, s, payload, tile_base, ip);
+    }
+    const double block_total = block_sum<256>((double)ip, red);
+    if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
+}
+
+__global__ __launch_bounds__(256) void k_dec_lo14(DecBatch B, int log2D, uint64_t seed, const DecScratch *scratch,
+                                                  float *T) {
+    __shared__ __attribute__((aligned(16))) float lds[kLo14Lds];
+    __shared__ float table[16];
+    const uint32_t c = blockIdx.y;
+    const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
+    const uint32_t b_q8 = B.b_q8[c];
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const DecScratch *s = &scratch[c];
+    const uint32_t *bm = B.bitmap[c];
+    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
+    if (threadIdx.x < 16) table[threadIdx.x] = s->deq[threadIdx.x];
+    __syncthreads();
+    float u[4][16];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint64_t run = tile_base + (uint64_t)r * 4096u + 64u * src;
+        const uint64_t first = run + 16u * kq;
+        bool here = true;                                        // Sec. 4.2: a lost packet's coordinates are zero
+        if (bm) {
+            const uint32_t pk = (uint32_t)(first >> 10);
+            here = (bm[pk >> 5] >> (pk & 31u)) & 1u;
+        }
+        if (b_q8 == 256) {
+            const uint32_t w = payload[(run >> 5) + (kq >> 1)] >> (16u * (kq & 1u));
+            const uint32_t mag = here ? __float_as_uint(table[1]) : 0u;
+            const uint32_t neg = ~w;
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) u[r][kk] = __uint_as_float(mag | ((neg << (31 - kk)) & 0x80000000u));
+        } else if (b_q8 == 128) {
+            const uint32_t w = payload[run >> 6] >> (8u * kq);
+            const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+            const uint64_t hw = hash_word(key, run >> 7);
+            const uint32_t off = (uint32_t)(hw >> (((run >> 6) & 1ull) * 32 + 8 * kq));
+            const uint32_t mag = here ? __float_as_uint(table[1]) : 0u;
+            const uint32_t neg = ~w;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const float val = __uint_as_float(mag | ((neg << (31 - g)) & 0x80000000u));
+                const bool odd = (off >> g) & 1u;
+                u[r][2 * g] = odd ? 0.0f : val;
+                u[r][2 * g + 1] = odd ? val : 0.0f;
+            }
+        } else if (b_q8 == 512) {
+            const uint32_t w = payload[first >> 4];
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) u[r][kk] = here ? table[(w >> (2 * kk)) & 3u] : 0.0f;
+        } else {
+            const uint2 w2 = *reinterpret_cast<const uint2 *>(payload + (first >> 3));
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) u[r][kk] = here ? table[(w2.x >> (4 * kk)) & 15u] : 0.0f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) u[r][8 + kk] = here ? table[(w2.y >> (4 * kk)) & 15u] : 0.0f;
+        }
+    }
+    lo14_backward(u, lds, T + ((size_t)c << log2D) + tile_base);
+}
+
+// ------------------------------------------------------------------------------------------------
+#define EDEN_HIX_SWITCH(M, CALL)                         \
+    switch (M) {                                         \
+        case 7: { constexpr int MM = 7; CALL; } break;   \
+        case 8: { constexpr int MM = 8; CALL; } break;   \
+        case 9: { constexpr int MM = 9; CALL; } break;   \
+        default: { constexpr int MM = 10; CALL; } break; \
+    }
+
+static uint32_t hix_tiles(int M, int log2D) { return 1u << (log2D - M - 5); }
+
+uint32_t launch_hix_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
+                          double *partials, uint32_t partial_stride, hipStream_t st) {
+    dim3 grid(hix_tiles(M, log2D), n);
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D, p, seed, T,
+                                          partials, partial_stride));
+    return grid.x;
+}
+void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st) {
+    dim3 grid(hix_tiles(M, log2D), n);
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_mid<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D, p));
+}
+void launch_hix_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, const float *T,
+                     float *acc, hipStream_t st) {
+    dim3 grid(hix_tiles(M, log2D));
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_last<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, n, d, log2D, p, seed, T,
+                                          acc));
+}
+uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
+                         uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
+    dim3 grid(1u << (log2D - kLo14Bits), n);
+    hipLaunchKernelGGL(k_enc_lo14, grid, dim3(256), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
+    return grid.x;
+}
+void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, float *T,
+                     hipStream_t st) {
+    dim3 grid(1u << (log2D - kLo14Bits), n);
+    hipLaunchKernelGGL(k_dec_lo14, grid, dim3(256), 0, st, B, log2D, seed, scratch, T);
+}
+
+}  // namespace eden

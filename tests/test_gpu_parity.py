@@ -15,7 +15,7 @@ torch = pytest.importorskip("torch")
 def ctx():
     from paper_2108_08842_amd import eden
     assert torch.cuda.is_available(), "these tests need the MI355X"
-    c = eden.Context(d_max=1 << 20, n_max=40, device=0)
+    c = eden.Context(d_max=1 << 23, n_max=40, device=0)
     yield c
     torch.cuda.synchronize()
     c.close()
@@ -95,6 +95,14 @@ def test_multi_pass_sizes(ctx, d):
     w = synth.Workload("t", 4, d, [128, 256, 512, 1024], 200 + d % 1000, "lognormal_signed")
     xs = [synth.client_vector(w, c) for c in range(4)]
     _run_case(ctx, xs, [3, 1, 4, 1_000_000], w.b_q8, w.seed)
+
+
+@pytest.mark.parametrize("d,budgets", [(1 << 21, [256, 1024]), ((1 << 21) + 5, [128, 512]), (5_000_000, [256, 512])])
+def test_workgroup_tile_sizes(ctx, d, budgets):
+    # D = 2^21, 2^22, 2^23: strided pass of 7, 8, 9 bits in workgroup tiles + 14-bit contiguous pass
+    w = synth.Workload("t", 2, d, budgets, 400 + d % 1000, "normal_outliers")
+    xs = [synth.client_vector(w, c) for c in range(2)]
+    _run_case(ctx, xs, [11, 12], w.b_q8, w.seed, drop_q32=int(0.05 * 2 ** 32), also_oracle_msgs=(d == 1 << 21))
 
 
 @pytest.mark.parametrize("d", [5000, 70_000])
@@ -203,7 +211,7 @@ def test_argument_errors(ctx):
     assert ctx.encode_raw(**{**ok, "b_q8": [300]}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "b_q8": [768]}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "d": 0}) == eden.ERR_INVALID_ARG
-    assert ctx.encode_raw(**{**ok, "d": (1 << 20) + 1}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw(**{**ok, "d": (1 << 23) + 1}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "x_ptrs": [None]}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "msg_caps": [msg.numel() - 1]}) == eden.ERR_CAPACITY
     assert ctx.encode_raw(**{**ok, "msg_ptrs": [msg.data_ptr() + 4]}) == eden.ERR_INVALID_ARG
