@@ -270,13 +270,15 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);
             launch_dec_small(B, nb, d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
         } else {
+            // b <= 1 senders: int16 workspace when the consumer of the contiguous pass understands it
+            const int narrow = (pl.lo_bits == 14 && pl.nhi == 1 && pl.hi[0].wg) ? 1 : 0;
             {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
                 launch_dec_prepare(B, nb, d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
             }
             {
                 Timed t(ctx, EDEN_K_DEC_LO, nb, st);
-                if (pl.lo_bits == 14) launch_dec_lo14(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
+                if (pl.lo_bits == 14) launch_dec_lo14(B, nb, log2D, seed, ctx->dec_scratch, narrow, ctx->T, st);
                 else launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
             }
             for (int i = 0; i < pl.nhi; ++i) {
@@ -287,7 +289,7 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
                     else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
                 } else {
                     Timed t(ctx, EDEN_K_DEC_HI_LAST, nb, st);
-                    if (h.wg) launch_hix_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, acc_dev, st);
+                    if (h.wg) launch_hix_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
                     else launch_dec_hi_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, acc_dev, st);
                 }
             }

@@ -107,6 +107,21 @@ __device__ inline uint64_t wave_read64(uint64_t v, int src) {
     return ((uint64_t)hi << 32) | lo;
 }
 
+// ---- buffer addressing: one resource descriptor per sender buffer, a per-lane byte offset in a VGPR and
+// a wave-uniform byte offset in an SGPR per access.  Strided passes issue 64 loads back to back; with flat
+// 64-bit addresses each of them would pin two VGPRs.  Reads beyond `bytes` return 0 and writes beyond it
+// are dropped, which is exactly the zero padding of d up to D.
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+__device__ inline rsrc_t make_rsrc(const void *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ inline float buf_load(rsrc_t r, uint32_t lane_off, uint32_t wave_off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)wave_off, 0));
+}
+__device__ inline void buf_store(rsrc_t r, uint32_t lane_off, uint32_t wave_off, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)wave_off, 0);
+}
+
 // In-register Walsh-Hadamard butterflies over the register index: (a,b) -> (a+b, a-b) at spans 1..N/2.
 template <int N>
 __device__ inline void fwht_regs(float (&v)[N]) {

@@ -57,13 +57,12 @@ __global__ __launch_bounds__(256) void k_enc_hi_first(EncBatch B, uint64_t d, in
     if (tile < ntiles) {
         uint64_t base;
         hi_tile_origin<M>(tile, p, base);
-        const float *x = B.x[c];
+        const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));          // reads past d give the zero padding
+        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
+        const uint32_t lane_off = lane * 4u, base_off = (uint32_t)base * 4u;
         float v[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const uint64_t i = base + ((uint64_t)r << p) + lane;
-            v[r] = (i < d) ? __builtin_nontemporal_load(x + i) : 0.0f;
-        }
+        for (int r = 0; r < R; ++r) v[r] = buf_load(rx, lane_off, base_off + ((uint32_t)r << (p + 2)));
 #pragma unroll
         for (int r = 0; r < R; ++r) n2 += (double)v[r] * (double)v[r];
         // lane r hashes the sign word of row r (all rows at once on the vector unit); row r's word is
@@ -75,9 +74,8 @@ __global__ __launch_bounds__(256) void k_enc_hi_first(EncBatch B, uint64_t d, in
             v[r] = negate_where(v[r], wave_read64(my_word, r)) + 0.0f;   // + 0 turns -0 into +0
         }
         fwht_regs<R>(v);
-        float *Tc = T + ((size_t)c << log2D);
 #pragma unroll
-        for (int r = 0; r < R; ++r) Tc[base + ((uint64_t)r << p) + lane] = v[r];
+        for (int r = 0; r < R; ++r) buf_store(rt, lane_off, base_off + ((uint32_t)r << (p + 2)), v[r]);
     }
     const double block_total = block_sum<256>(n2, red);
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
@@ -108,13 +106,14 @@ __global__ __launch_bounds__(256) void k_hi_mid(float *T, int log2D, int p) {
     if (tile >= ntiles) return;
     uint64_t base;
     hi_tile_origin<M>(tile, p, base);
-    float *Tc = T + ((size_t)c << log2D) + base + lane;
+    const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
+    const uint32_t lane_off = lane * 4u, base_off = (uint32_t)base * 4u;
     float v[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) v[r] = Tc[(uint64_t)r << p];
+    for (int r = 0; r < R; ++r) v[r] = buf_load(rt, lane_off, base_off + ((uint32_t)r << (p + 2)));
     fwht_regs<R>(v);
 #pragma unroll
-    for (int r = 0; r < R; ++r) Tc[(uint64_t)r << p] = v[r];
+    for (int r = 0; r < R; ++r) buf_store(rt, lane_off, base_off + ((uint32_t)r << (p + 2)), v[r]);
 }
 
 // Decode, last pass: for every sender of the batch finish H, apply its sign diagonal (R^-1 = s o D^-1/2 H,
@@ -133,21 +132,23 @@ __global__ __launch_bounds__(256) void k_dec_hi_last(DecBatch B, uint32_t n, uin
     float sum[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) sum[r] = 0.0f;
+    const uint32_t lane_off = lane * 4u, base_off = (uint32_t)base * 4u;
     for (uint32_t c = 0; c < n; ++c) {
-        const float *Tc = T + ((size_t)c << log2D) + base + lane;
+        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
         float v[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) v[r] = __builtin_nontemporal_load(Tc + ((uint64_t)r << p));
+        for (int r = 0; r < R; ++r) v[r] = buf_load(rt, lane_off, base_off + ((uint32_t)r << (p + 2)));
         fwht_regs<R>(v);
         const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
         const uint64_t my_word = hash_word(key, (base + ((uint64_t)(lane & (R - 1)) << p)) >> 6);
 #pragma unroll
         for (int r = 0; r < R; ++r) sum[r] += negate_where(v[r], wave_read64(my_word, r));
     }
+    const rsrc_t ra = make_rsrc(acc, (uint32_t)(d * 4));                 // coordinates past d are dropped
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const uint64_t i = base + ((uint64_t)r << p) + lane;
-        if (i < d) acc[i] += sum[r];
+        const uint32_t off = base_off + ((uint32_t)r << (p + 2));
+        buf_store(ra, lane_off, off, buf_load(ra, lane_off, off) + sum[r]);
     }
 }
 

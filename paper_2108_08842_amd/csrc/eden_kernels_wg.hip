@@ -22,6 +22,8 @@
 namespace eden {
 
 // ------------------------------------------------------------------------------------------------
+constexpr int kHixP = 14;     // lowest index bit of every workgroup-tile strided pass (it sits on top of lo14)
+
 template <int M>
 struct HiX {
     static constexpr int RL = 1 << (M - 6);       // row groups: the low M-6 row bits live across thread groups
@@ -82,23 +84,26 @@ __device__ inline uint64_t pair_mask(uint32_t lo_words, uint32_t hi_words, int s
 }
 
 template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_first(EncBatch B, uint64_t d, int log2D, int p,
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_first(EncBatch B, uint64_t d, int log2D, int p_arg,
                                                                 uint64_t seed, float *T, double *partials,
                                                                 uint32_t partial_stride) {
     using X = HiX<M>;
     __shared__ float lds[X::LDS_FLOATS];
     __shared__ double red[X::THREADS / 64];
+    constexpr int p = kHixP;
+    (void)p_arg;
     const uint32_t c = blockIdx.y;
     const uint64_t base = hix_base<M>(blockIdx.x, p);
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
     const uint32_t g0 = 2u * wave_in_block();                    // the two groups of this wave: g0, g0 + 1
-    const float *x = B.x[c];
+    const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));              // reads past d give the zero padding
+    const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
+    const uint32_t base_off = (uint32_t)base * 4u;
+    const uint32_t off1 = ((g << p) + col) * 4u;                         // stage-1 rows: g + RL r
+    const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;      // stage-2 rows: rl + RL (ph RP + g RHL + e)
     float v[64];
 #pragma unroll
-    for (int r = 0; r < 64; ++r) {
-        const uint64_t i = base + ((uint64_t)hix_row1<M>(g, r) << p) + col;
-        v[r] = (i < d) ? __builtin_nontemporal_load(x + i) : 0.0f;
-    }
+    for (int r = 0; r < 64; ++r) v[r] = buf_load(rx, off1, base_off + (((uint32_t)X::RL * r) << (p + 2)));
     double n2 = 0.0;
 #pragma unroll
     for (int r = 0; r < 64; ++r) n2 += (double)v[r] * (double)v[r];
@@ -109,49 +114,86 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_first(EncBatch B, uint6
 #pragma unroll
     for (int r = 0; r < 64; ++r) v[r] = negate_where(v[r], pair_mask(wa, wb, r)) + 0.0f;   // + 0: no negative zeros
     fwht_regs<64>(v);
-    float *Tc = T + ((size_t)c << log2D) + base + col;
     float out[X::RP];
     hix_exchange<M, 0>(v, lds, out);
 #pragma unroll
-    for (int s = 0; s < X::RP; ++s) Tc[(uint64_t)hix_row2<M>(g, 0, s) << p] = out[s];
+    for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 0, s) << (p + 2)), out[s]);
     if constexpr (X::PH == 2) {
         hix_exchange<M, 1>(v, lds, out);
 #pragma unroll
-        for (int s = 0; s < X::RP; ++s) Tc[(uint64_t)hix_row2<M>(g, 1, s) << p] = out[s];
+        for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 1, s) << (p + 2)), out[s]);
     }
     const double block_total = block_sum<X::THREADS>(n2, red);
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
 }
 
 template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D, int p) {
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D, int p_arg) {
     using X = HiX<M>;
     __shared__ float lds[X::LDS_FLOATS];
+    constexpr int p = kHixP;
+    (void)p_arg;
     const uint64_t base = hix_base<M>(blockIdx.x, p);
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
-    float *Tc = T + ((size_t)blockIdx.y << log2D) + base + col;
+    const rsrc_t rt = make_rsrc(T + ((size_t)blockIdx.y << log2D), 4u << log2D);
+    const uint32_t base_off = (uint32_t)base * 4u;
+    const uint32_t off1 = ((g << p) + col) * 4u;
+    const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;
     float v[64];
 #pragma unroll
-    for (int r = 0; r < 64; ++r) v[r] = Tc[(uint64_t)hix_row1<M>(g, r) << p];
+    for (int r = 0; r < 64; ++r) v[r] = buf_load(rt, off1, base_off + (((uint32_t)X::RL * r) << (p + 2)));
     fwht_regs<64>(v);
     float out[X::RP];
     hix_exchange<M, 0>(v, lds, out);
 #pragma unroll
-    for (int s = 0; s < X::RP; ++s) Tc[(uint64_t)hix_row2<M>(g, 0, s) << p] = out[s];
+    for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 0, s) << (p + 2)), out[s]);
     if constexpr (X::PH == 2) {
         hix_exchange<M, 1>(v, lds, out);
 #pragma unroll
-        for (int s = 0; s < X::RP; ++s) Tc[(uint64_t)hix_row2<M>(g, 1, s) << p] = out[s];
+        for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 1, s) << (p + 2)), out[s]);
     }
 }
 
 // Decode, last pass (Sec. 2.2.2): finish H for every sender of the batch, apply that sender's sign diagonal,
-// add; acc is read and written once.
+// add; acc is read and written once.  The next sender's tile is loaded while the current one is transformed
+// (one workgroup owns the CU here, so nothing else would hide the load latency).
+//
+// `narrow`: senders with b <= 1 had their workspace written as int16 by the contiguous pass.  Their
+// dequantized rotated vector is (+-a or 0) per coordinate, so the partial transform is a times an integer of
+// magnitude <= 2^14: storing the integer is exact and halves the traffic; a is applied at the very end.
 template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_last(DecBatch B, uint32_t n, uint64_t d, int log2D, int p,
-                                                               uint64_t seed, const float *T, float *acc) {
+struct HiXLoader {
+    using X = HiX<M>;
+    const float *T;
+    int log2D;
+    uint32_t base_off, off1;      // byte offsets (fp32 units) of the tile and of this thread's first element
+    __device__ inline void load(uint32_t c, bool i16, uint32_t (&raw)[64]) const {
+        constexpr int p = kHixP;
+        // the tile's origin goes into the descriptor so that every row offset is a compile-time constant
+        const char *slot = reinterpret_cast<const char *>(T + ((size_t)c << log2D));
+        if (i16) {
+            const rsrc_t rt = make_rsrc(slot + (base_off >> 1), (2u << log2D) - (base_off >> 1));
+#pragma unroll
+            for (int r = 0; r < 64; ++r)
+                raw[r] = (uint32_t)(int)(short)__builtin_amdgcn_raw_buffer_load_b16(
+                    rt, (int)(off1 >> 1), (int)((((uint32_t)X::RL * r) << (p + 2)) >> 1), 0);
+        } else {
+            const rsrc_t rt = make_rsrc(slot + base_off, (4u << log2D) - base_off);
+#pragma unroll
+            for (int r = 0; r < 64; ++r)
+                raw[r] = __builtin_amdgcn_raw_buffer_load_b32(rt, (int)off1, (int)(((uint32_t)X::RL * r) << (p + 2)), 0);
+        }
+    }
+};
+
+template <int M>
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_last(DecBatch B, uint32_t n, uint64_t d, int log2D, int p_arg,
+                                                               uint64_t seed, const float *T, const DecScratch *scratch,
+                                                               int narrow, float *acc) {
     using X = HiX<M>;
     __shared__ float lds[X::LDS_FLOATS];
+    constexpr int p = kHixP;
+    (void)p_arg;
     const uint64_t base = hix_base<M>(blockIdx.x, p);
     if (base >= d) return;                                       // the whole tile lies in the padding
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
@@ -162,11 +204,17 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_last(DecBatch B, uint32
     // lane l <-> (half, register) = (l / RP, l % RP): the rows whose sign bits this lane hashes
     const uint64_t rowa = (uint64_t)hix_row2<M>(g0, (int)(lane / X::RP), (int)(lane % X::RP)) << p;
     const uint64_t rowb = (uint64_t)hix_row2<M>(g0 + 1, (int)(lane / X::RP), (int)(lane % X::RP)) << p;
-    for (uint32_t c = 0; c < n; ++c) {
-        const float *Tc = T + ((size_t)c << log2D) + base + col;
+    const uint32_t base_off = (uint32_t)base * 4u;
+    const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;
+    const HiXLoader<M> loader{T, log2D, base_off, ((g << p) + col) * 4u};
+
+    auto is_narrow = [&](uint32_t c) { return narrow && B.b_q8[c] <= 256u; };
+    auto process = [&](uint32_t c, uint32_t (&raw)[64]) {
+        const bool i16 = is_narrow(c);
+        const float scale = i16 ? scratch[c].deq[1] : 1.0f;      // x * 1 + s is exact: same result as a plain add
         float v[64];
 #pragma unroll
-        for (int r = 0; r < 64; ++r) v[r] = __builtin_nontemporal_load(Tc + ((uint64_t)hix_row1<M>(g, r) << p));
+        for (int r = 0; r < 64; ++r) v[r] = i16 ? (float)(int)raw[r] : __uint_as_float(raw[r]);
         fwht_regs<64>(v);
         const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
         const uint32_t wa = sign_half_word(key, base + rowa);
@@ -174,19 +222,32 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_last(DecBatch B, uint32
         float out[X::RP];
         hix_exchange<M, 0>(v, lds, out);
 #pragma unroll
-        for (int s = 0; s < X::RP; ++s) sum[s] += negate_where(out[s], pair_mask(wa, wb, s));
+        for (int s = 0; s < X::RP; ++s) sum[s] = fmaf(negate_where(out[s], pair_mask(wa, wb, s)), scale, sum[s]);
         if constexpr (X::PH == 2) {
             hix_exchange<M, 1>(v, lds, out);
 #pragma unroll
-            for (int s = 0; s < X::RP; ++s) sum[X::RP + s] += negate_where(out[s], pair_mask(wa, wb, X::RP + s));
+            for (int s = 0; s < X::RP; ++s)
+                sum[X::RP + s] = fmaf(negate_where(out[s], pair_mask(wa, wb, X::RP + s)), scale, sum[X::RP + s]);
+        }
+    };
+
+    uint32_t ra_[64], rb_[64];
+    loader.load(0, is_narrow(0), ra_);
+    for (uint32_t c = 0; c < n; c += 2) {
+        if (c + 1 < n) loader.load(c + 1, is_narrow(c + 1), rb_);
+        process(c, ra_);
+        if (c + 1 < n) {
+            if (c + 2 < n) loader.load(c + 2, is_narrow(c + 2), ra_);
+            process(c + 1, rb_);
         }
     }
+    const rsrc_t ra = make_rsrc(acc, (uint32_t)(d * 4));                 // coordinates past d are dropped
 #pragma unroll
     for (int ph = 0; ph < X::PH; ++ph) {
 #pragma unroll
         for (int s = 0; s < X::RP; ++s) {
-            const uint64_t i = base + ((uint64_t)hix_row2<M>(g, ph, s) << p) + col;
-            if (i < d) acc[i] += sum[ph * X::RP + s];
+            const uint32_t off = base_off + (hix_row2<M>(0, ph, s) << (p + 2));
+            buf_store(ra, off2, off, buf_load(ra, off2, off) + sum[ph * X::RP + s]);
         }
     }
 }
@@ -237,6 +298,7 @@ __device__ inline void lo14_forward(const float *Tt /* tile start */, float *lds
 }
 
 // The mirror image for decode: u (same layout as above, not yet transformed) -> T.
+template <bool NARROW>
 __device__ inline void lo14_backward(float (&u)[4][16], float *lds, float *Tt) {
     const uint32_t lane = lane_id(), wv = wave_in_block();
 #pragma unroll
@@ -270,8 +332,14 @@ __device__ inline void lo14_backward(float (&u)[4][16], float *lds, float *Tt) {
 #pragma unroll
     for (int j = 0; j < 64; ++j) v[j] = L[j * kLdsRow + lane];
     fwht_regs<64>(v);                                            // bits 6..11
+    if constexpr (NARROW) {                                      // exact small integers: store as int16
+        short *T16 = reinterpret_cast<short *>(Tt);
 #pragma unroll
-    for (int j = 0; j < 64; ++j) Tt[wv * 4096u + 64 * j + lane] = v[j];
+        for (int j = 0; j < 64; ++j) T16[wv * 4096u + 64 * j + lane] = (short)(int)v[j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 64; ++j) Tt[wv * 4096u + 64 * j + lane] = v[j];
+    }
 }
 
 __device__ inline uint32_t quad_swap1(uint32_t x) {   // value of lane ^ 1
@@ -359,8 +427,10 @@ __global__ __launch_bounds__(256) void k_enc_lo14(EncBatch B, int log2D, uint64_
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
 }
 
+// `narrow` != 0: for senders with b <= 1 the unit pattern (+-1 or 0) is transformed and the exact integers are
+// stored as int16 at the same element index (the consumer multiplies by the sender's magnitude at the end).
 __global__ __launch_bounds__(256) void k_dec_lo14(DecBatch B, int log2D, uint64_t seed, const DecScratch *scratch,
-                                                  float *T) {
+                                                  int narrow, float *T) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14Lds];
     __shared__ float table[16];
     const uint32_t c = blockIdx.y;
@@ -370,7 +440,8 @@ __global__ __launch_bounds__(256) void k_dec_lo14(DecBatch B, int log2D, uint64_
     const DecScratch *s = &scratch[c];
     const uint32_t *bm = B.bitmap[c];
     const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
-    if (threadIdx.x < 16) table[threadIdx.x] = s->deq[threadIdx.x];
+    const bool i16 = narrow && b_q8 <= 256u;
+    if (threadIdx.x < 16) table[threadIdx.x] = (i16 && threadIdx.x == 1) ? 1.0f : s->deq[threadIdx.x];
     __syncthreads();
     float u[4][16];
 #pragma unroll
@@ -414,7 +485,12 @@ __global__ __launch_bounds__(256) void k_dec_lo14(DecBatch B, int log2D, uint64_
             for (int kk = 0; kk < 8; ++kk) u[r][8 + kk] = here ? table[(w2.y >> (4 * kk)) & 15u] : 0.0f;
         }
     }
-    lo14_backward(u, lds, T + ((size_t)c << log2D) + tile_base);
+    if (i16) {
+        // tile_base counts elements; the int16 copy of element i sits at byte 2 i of the sender's slot
+        lo14_backward<true>(u, lds, reinterpret_cast<float *>(reinterpret_cast<short *>(T + ((size_t)c << log2D)) + tile_base));
+    } else {
+        lo14_backward<false>(u, lds, T + ((size_t)c << log2D) + tile_base);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -440,10 +516,10 @@ void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t s
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_mid<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D, p));
 }
 void launch_hix_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, const float *T,
-                     float *acc, hipStream_t st) {
+                     const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
     dim3 grid(hix_tiles(M, log2D));
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_last<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, n, d, log2D, p, seed, T,
-                                          acc));
+                                          scratch, narrow, acc));
 }
 uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
                          uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
@@ -451,10 +527,10 @@ uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed
     hipLaunchKernelGGL(k_enc_lo14, grid, dim3(256), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
     return grid.x;
 }
-void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, float *T,
-                     hipStream_t st) {
+void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, int narrow,
+                     float *T, hipStream_t st) {
     dim3 grid(1u << (log2D - kLo14Bits), n);
-    hipLaunchKernelGGL(k_dec_lo14, grid, dim3(256), 0, st, B, log2D, seed, scratch, T);
+    hipLaunchKernelGGL(k_dec_lo14, grid, dim3(256), 0, st, B, log2D, seed, scratch, narrow, T);
 }
 
 }  // namespace eden
