@@ -43,8 +43,10 @@ def kernel_bytes(kind, senders, d, D, budgets_mean_bits):
         "enc_lo": 4 * D + payload,           # workspace in, packed indices out
         "dec_lo": payload + 4 * D,           # packed indices in, workspace out
         "dec_hi_last": 4 * D,                # workspace in (per sender) ...
+        "dec_hi_first": payload + 4 * D,     # packed indices in, workspace out
+        "dec_lo_last": 4 * D,                # workspace in (per sender) ...
     }
-    if kind == "dec_hi_last":
+    if kind in ("dec_hi_last", "dec_lo_last"):
         return senders * per_sender[kind] + 8 * d   # ... plus one read-modify-write of the accumulator
     if kind == "finalize_mean":
         return 8 * d

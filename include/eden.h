@@ -120,7 +120,7 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
  *   client_ids[c], b_q8[c], seed, d   what the receiver agreed with sender c; checked against the header
  *   recv_bitmaps_dev     NULL (nothing lost) or host array of n device pointers, each NULL or a
  *                        bitmap of ceil(max(1, D/1024) / 32) uint32 words
- *   acc_dev              device fp32[d], read and written; the caller zeroes it once per round */
+ *   acc_dev              device fp32[d], 16-byte aligned, read and written; the caller zeroes it once per round */
 int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
                            const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
                            const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream);
@@ -169,7 +169,9 @@ typedef enum eden_kernel_kind {
     EDEN_K_DEC_SMALL = 8,      /* decode, D <= 4096 */
     EDEN_K_ENC_NORM = 9,       /* encode: |x|^2 from per-workgroup partials, scaled thresholds */
     EDEN_K_ENC_FINISH = 10,    /* encode: <R(x),Q>, S, header */
-    EDEN_K_COUNT = 11
+    EDEN_K_DEC_HI_FIRST = 11,  /* decode: unpack + dequantize + strided pass (2^21 <= D <= 2^24) */
+    EDEN_K_DEC_LO_LAST = 12,   /* decode: contiguous pass + signs + sum over senders (2^21 <= D <= 2^24) */
+    EDEN_K_COUNT = 13
 } eden_kernel_kind;
 int eden_profile_enable(eden_ctx *ctx, uint32_t kind_mask, uint32_t max_records);
 int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, float *ms, uint32_t cap,

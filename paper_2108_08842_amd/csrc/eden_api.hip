@@ -245,6 +245,7 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
                            const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
                            const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream) {
     if (!ctx || !msgs_dev || !client_ids || !b_q8 || !acc_dev) return EDEN_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(acc_dev) & 15u) return EDEN_ERR_INVALID_ARG;
     if (n == 0 || n > ctx->n_max || d == 0 || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
     for (uint32_t c = 0; c < n; ++c) {
         if (!msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
@@ -270,27 +271,38 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);
             launch_dec_small(B, nb, d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
         } else {
-            // b <= 1 senders: int16 workspace when the consumer of the contiguous pass understands it
+            // plan "one workgroup-tile strided pass + lo14": decode runs strided-first / contiguous-last, and
+            // senders with b <= 1 use an int16 workspace
             const int narrow = (pl.lo_bits == 14 && pl.nhi == 1 && pl.hi[0].wg) ? 1 : 0;
             {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
                 launch_dec_prepare(B, nb, d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
             }
-            {
-                Timed t(ctx, EDEN_K_DEC_LO, nb, st);
-                if (pl.lo_bits == 14) launch_dec_lo14(B, nb, log2D, seed, ctx->dec_scratch, narrow, ctx->T, st);
-                else launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
-            }
-            for (int i = 0; i < pl.nhi; ++i) {
-                const HiPass &h = pl.hi[i];
-                if (i < pl.nhi - 1) {
-                    Timed t(ctx, EDEN_K_HI_MID, nb, st);
-                    if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
-                    else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
-                } else {
-                    Timed t(ctx, EDEN_K_DEC_HI_LAST, nb, st);
-                    if (h.wg) launch_hix_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
-                    else launch_dec_hi_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, acc_dev, st);
+            if (narrow) {
+                // strided pass first (independent per sender), contiguous pass last (sums the senders)
+                {
+                    Timed t(ctx, EDEN_K_DEC_HI_FIRST, nb, st);
+                    launch_dec_hix_first(pl.hi[0].M, B, nb, log2D, seed, ctx->dec_scratch, 1, ctx->T, st);
+                }
+                Timed t(ctx, EDEN_K_DEC_LO_LAST, nb, st);
+                launch_dec_lo14_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, 1, acc_dev, st);
+            } else {
+                {
+                    Timed t(ctx, EDEN_K_DEC_LO, nb, st);
+                    if (pl.lo_bits == 14) launch_dec_lo14(B, nb, log2D, seed, ctx->dec_scratch, 0, ctx->T, st);
+                    else launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
+                }
+                for (int i = 0; i < pl.nhi; ++i) {
+                    const HiPass &h = pl.hi[i];
+                    if (i < pl.nhi - 1) {
+                        Timed t(ctx, EDEN_K_HI_MID, nb, st);
+                        if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
+                        else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
+                    } else {
+                        Timed t(ctx, EDEN_K_DEC_HI_LAST, nb, st);
+                        if (h.wg) launch_hix_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, ctx->dec_scratch, 0, acc_dev, st);
+                        else launch_dec_hi_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, acc_dev, st);
+                    }
                 }
             }
         }
@@ -409,7 +421,7 @@ int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, floa
 const char *eden_kernel_name(uint32_t kind) {
     static const char *names[EDEN_K_COUNT] = {"enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_lo",
                                               "dec_hi_last", "finalize_mean", "enc_small", "dec_small",
-                                              "enc_norm", "enc_finish"};
+                                              "enc_norm", "enc_finish", "dec_hi_first", "dec_lo_last"};
     return kind < EDEN_K_COUNT ? names[kind] : "?";
 }
 

@@ -39,6 +39,10 @@ uint32_t launch_hix_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int 
 void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
 void launch_hix_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, const float *T,
                      const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
+void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch,
+                          int narrow, float *T, hipStream_t st);
+void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+                          const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
 uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
                          uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
 void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, int narrow,

@@ -259,11 +259,9 @@ constexpr int kLo14Lds = 4 * 64 * kLdsRow;       // floats
 
 // 4 waves x 4096 coordinates.  On return thread t holds, for each of the four 4096-regions r, the final
 // values of the 16 consecutive coordinates  tile*2^14 + r*4096 + 64*(t >> 2) + 16*(t & 3) + kk.
-__device__ inline void lo14_forward(const float *Tt /* tile start */, float *lds, float (&u)[4][16]) {
+// v[j] must hold coordinate  wave*4096 + 64 j + lane  of the tile.
+__device__ inline void lo14_forward(float (&v)[64], float *lds, float (&u)[4][16]) {
     const uint32_t lane = lane_id(), wv = wave_in_block();
-    float v[64];
-#pragma unroll
-    for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(Tt + wv * 4096u + 64 * j + lane);
     fwht_regs<64>(v);                                            // bits 6..11
     float *L = lds + wv * (64 * kLdsRow);
 #pragma unroll
@@ -378,7 +376,13 @@ __global__ __launch_bounds__(256) void k_enc_lo14(EncBatch B, int log2D, uint64_
     const uint32_t c = blockIdx.y;
     const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
     float u[4][16];
-    lo14_forward(T + ((size_t)c << log2D) + tile_base, lds, u);
+    {
+        const float *Tt = T + ((size_t)c << log2D) + tile_base + wave_in_block() * 4096u + lane_id();
+        float v[64];
+#pragma unroll
+        for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(Tt + 64 * j);
+        lo14_forward(v, lds, u);
+    }
 
     const EncScratch *s = &scratch[c];
     const uint32_t b_q8 = B.b_q8[c];
@@ -494,6 +498,209 @@ __global__ __launch_bounds__(256) void k_dec_lo14(DecBatch B, int log2D, uint64_
 }
 
 // ------------------------------------------------------------------------------------------------
+// Decode in the order "strided pass first, contiguous pass last" (used when the plan is one workgroup-tile
+// strided pass on top of lo14).  The first pass has no dependency between senders, so every (tile, sender)
+// pair is its own workgroup; the last pass sums the senders in registers and touches acc once, with fully
+// contiguous accesses.
+
+// v or 0 per lane, chosen by bit `lane` of a wave-uniform mask
+__device__ inline float keep_where(float v, uint64_t mask) {
+    float r;
+    asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(v), "s"(mask));
+    return r;
+}
+
+// First decode pass (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit pattern when the
+// workspace is int16), zero for coordinates that were not sampled or whose packet was lost, then index bits
+// 14 .. 14+M-1 of H.
+template <int M>
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, int log2D, uint64_t seed,
+                                                                    const DecScratch *scratch, int narrow, float *T) {
+    using X = HiX<M>;
+    constexpr int p = kHixP;
+    __shared__ float lds[X::LDS_FLOATS];
+    __shared__ float table[16];
+    const uint32_t c = blockIdx.y;
+    const uint64_t base = hix_base<M>(blockIdx.x, p);
+    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
+    const uint32_t g0 = 2u * wave_in_block();
+    const uint32_t b_q8 = B.b_q8[c];
+    const bool i16 = narrow && b_q8 <= 256u;
+    const DecScratch *sc = &scratch[c];
+    if (threadIdx.x < 16) table[threadIdx.x] = (i16 && threadIdx.x == 1) ? 1.0f : sc->deq[threadIdx.x];
+    __syncthreads();
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    int bits, k;
+    budget_of(b_q8, bits, k);
+    const uint32_t payload_bytes = (uint32_t)(((((1ull << log2D) >> (k == 2)) * (uint32_t)bits + 63) >> 6) << 3);
+
+    // rows of this wave whose packet arrived, as lane masks over the register index (bit r <-> register r)
+    const uint64_t row_a = (uint64_t)hix_row1<M>(g0, lane) << p, row_b = (uint64_t)hix_row1<M>(g0 + 1, lane) << p;
+    uint64_t recv_a = ~0ull, recv_b = ~0ull;
+    const uint32_t *bm = B.bitmap[c];
+    if (bm) {
+        const uint32_t pa = (uint32_t)((base + row_a) >> 10), pb = (uint32_t)((base + row_b) >> 10);
+        recv_a = __ballot((bm[pa >> 5] >> (pa & 31u)) & 1u);
+        recv_b = __ballot((bm[pb >> 5] >> (pb & 31u)) & 1u);
+    }
+    float v[64];
+    if (b_q8 == 128) {
+        // b = 1/2: pair j = i >> 1 carries one bit; coordinate i was sent iff (i & 1) equals the pair's offset bit
+        const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+        const uint32_t sh = 16u * (uint32_t)((base >> 5) & 3u);                  // this tile's 16 pairs inside a hash word
+        const uint32_t fa = (uint32_t)(hash_word(key, (base + row_a) >> 7) >> sh) & 0xFFFFu;
+        const uint32_t fb = (uint32_t)(hash_word(key, (base + row_b) >> 7) >> sh) & 0xFFFFu;
+        const uint32_t both = fa | (fb << 16);
+        const rsrc_t rp = make_rsrc(payload + (base >> 6), payload_bytes - (uint32_t)(base >> 6) * 4u);
+        const uint32_t voff = (g << (p - 6)) * 4u;
+        const uint32_t bitpos = 16u * (uint32_t)((base >> 5) & 1u) + (col >> 1);
+        const uint32_t mag = __float_as_uint(table[1]);
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)X::RL * r) << (p - 6)) * 4u), 0);
+            const uint32_t offs = __builtin_amdgcn_readlane(both, r) >> (16u * (lane >> 5));
+            const bool kept = ((offs >> (col >> 1)) & 1u) == (col & 1u);
+            const uint32_t neg = (~(w >> bitpos) & 1u) << 31;                    // index 0 = negative
+            v[r] = kept ? __uint_as_float(mag | neg) : 0.0f;
+        }
+    } else {
+        const uint32_t cbits = col * (uint32_t)bits;
+        const rsrc_t rp = make_rsrc(payload + ((base * (uint32_t)bits) >> 5), payload_bytes - (uint32_t)((base * (uint32_t)bits) >> 5) * 4u);
+        const uint32_t voff = (((g * (uint32_t)bits) << (p - 5)) + (cbits >> 5)) * 4u;
+        const uint32_t shift = cbits & 31u;
+        if (b_q8 == 256) {
+            const uint32_t mag = __float_as_uint(table[1]);
+#pragma unroll
+            for (int r = 0; r < 64; ++r) {
+                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)X::RL * r) << (p - 5)) * 4u), 0);
+                v[r] = __uint_as_float(mag | ((~(w >> shift) & 1u) << 31));
+            }
+        } else if (b_q8 == 512) {
+#pragma unroll
+            for (int r = 0; r < 64; ++r) {
+                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)X::RL * r * 2u) << (p - 5)) * 4u), 0);
+                v[r] = table[(w >> shift) & 3u];
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 64; ++r) {
+                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)X::RL * r * 4u) << (p - 5)) * 4u), 0);
+                v[r] = table[(w >> shift) & 15u];
+            }
+        }
+    }
+    if (bm) {
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const uint64_t m = (((recv_a >> r) & 1ull) ? 0x00000000FFFFFFFFull : 0ull) |
+                               (((recv_b >> r) & 1ull) ? 0xFFFFFFFF00000000ull : 0ull);
+            v[r] = keep_where(v[r], m);
+        }
+    }
+    fwht_regs<64>(v);
+    const uint32_t base_off = (uint32_t)base * 4u;
+    const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;
+    const char *slot = reinterpret_cast<const char *>(T + ((size_t)c << log2D));
+    float out[X::RP];
+    if (i16) {
+        // exact integers of magnitude <= 2^M: int16 at the same element index
+        const rsrc_t rt = make_rsrc(slot + (base_off >> 1), (2u << log2D) - (base_off >> 1));
+        hix_exchange<M, 0>(v, lds, out);
+#pragma unroll
+        for (int s = 0; s < X::RP; ++s)
+            __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 0, s) << (p + 2)) >> 1), 0);
+        if constexpr (X::PH == 2) {
+            hix_exchange<M, 1>(v, lds, out);
+#pragma unroll
+            for (int s = 0; s < X::RP; ++s)
+                __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 1, s) << (p + 2)) >> 1), 0);
+        }
+    } else {
+        const rsrc_t rt = make_rsrc(slot + base_off, (4u << log2D) - base_off);
+        hix_exchange<M, 0>(v, lds, out);
+#pragma unroll
+        for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, hix_row2<M>(0, 0, s) << (p + 2), out[s]);
+        if constexpr (X::PH == 2) {
+            hix_exchange<M, 1>(v, lds, out);
+#pragma unroll
+            for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, hix_row2<M>(0, 1, s) << (p + 2), out[s]);
+        }
+    }
+}
+
+__device__ inline uint32_t quad_bcast(uint32_t x, int src) {   // value of lane (lane & ~3) + src
+    switch (src) {
+        case 0: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x00, 0xF, 0xF, true);
+        case 1: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x55, 0xF, 0xF, true);
+        case 2: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xAA, 0xF, 0xF, true);
+        default: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xFF, 0xF, 0xF, true);
+    }
+}
+
+// Last decode pass: index bits 0..13 of H for every sender, that sender's sign diagonal (R^-1 = s o D^-1/2 H,
+// Sec. 2.2.2), sum over senders in registers, one contiguous read-modify-write of acc.
+__global__ __launch_bounds__(256) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+                                                       const float *T, const DecScratch *scratch, int narrow, float *acc) {
+    __shared__ __attribute__((aligned(16))) float lds[kLo14Lds];
+    const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
+    if (tile_base >= d) return;                                  // whole tile in the padding
+    const uint32_t lane = lane_id(), wv = wave_in_block();
+    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
+    float sum[4][16];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) sum[r][kk] = 0.0f;
+    for (uint32_t c = 0; c < n; ++c) {
+        const bool i16 = narrow && B.b_q8[c] <= 256u;
+        float v[64];
+        if (i16) {
+            const short *t16 = reinterpret_cast<const short *>(T + ((size_t)c << log2D)) + tile_base + wv * 4096u + lane;
+#pragma unroll
+            for (int j = 0; j < 64; ++j) v[j] = (float)(int)__builtin_nontemporal_load(t16 + 64 * j);
+        } else {
+            const float *t32 = T + ((size_t)c << log2D) + tile_base + wv * 4096u + lane;
+#pragma unroll
+            for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(t32 + 64 * j);
+        }
+        float u[4][16];
+        lo14_forward(v, lds, u);
+        const uint32_t scale = __float_as_uint(i16 ? scratch[c].deq[1] : 1.0f) & 0x7FFFFFFFu;   // > 0; x*1+s is exact
+        // thread kq of a quad hashes the sign word of region kq; the quad shares the four words
+        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+        const uint64_t mine = hash_word(key, (tile_base + (uint64_t)kq * 4096u + 64u * src) >> 6);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t wlo = quad_bcast((uint32_t)mine, r), whi = quad_bcast((uint32_t)(mine >> 32), r);
+            const uint32_t f16 = ((kq & 2u) ? whi : wlo) >> (16u * (kq & 1u));   // the 16 sign bits of this thread's run
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) {
+                const uint32_t sgn = (f16 << (31 - kk)) & 0x80000000u;           // hash bit 1 -> s_i = -1
+                sum[r][kk] = fmaf(u[r][kk], __uint_as_float(scale | sgn), sum[r][kk]);
+            }
+        }
+        __syncthreads();                                         // LDS is reused by the next sender
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint64_t first = tile_base + (uint64_t)r * 4096u + 64u * src + 16u * kq;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint64_t i = first + 4u * q;
+            if (i + 3 < d) {
+                float4 a = *reinterpret_cast<const float4 *>(acc + i);
+                a.x += sum[r][4 * q]; a.y += sum[r][4 * q + 1]; a.z += sum[r][4 * q + 2]; a.w += sum[r][4 * q + 3];
+                *reinterpret_cast<float4 *>(acc + i) = a;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (i + e < d) acc[i + e] += sum[r][4 * q + e];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 #define EDEN_HIX_SWITCH(M, CALL)                         \
     switch (M) {                                         \
         case 7: { constexpr int MM = 7; CALL; } break;   \
@@ -520,6 +727,17 @@ void launch_hix_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D
     dim3 grid(hix_tiles(M, log2D));
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_last<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, n, d, log2D, p, seed, T,
                                           scratch, narrow, acc));
+}
+void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch,
+                          int narrow, float *T, hipStream_t st) {
+    dim3 grid(hix_tiles(M, log2D), n);
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, log2D, seed, scratch,
+                                          narrow, T));
+}
+void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+                          const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
+    dim3 grid(1u << (log2D - kLo14Bits));
+    hipLaunchKernelGGL(k_dec_lo14_last, grid, dim3(256), 0, st, B, n, d, log2D, seed, T, scratch, narrow, acc);
 }
 uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
                          uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {

@@ -32,7 +32,7 @@ EXPORTS = [
     "eden_kernel_name",
 ]
 KERNEL_KINDS = ["enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_lo", "dec_hi_last", "finalize_mean",
-                "enc_small", "dec_small", "enc_norm", "enc_finish"]
+                "enc_small", "dec_small", "enc_norm", "enc_finish", "dec_hi_first", "dec_lo_last"]
 
 
 class EdenError(RuntimeError):
