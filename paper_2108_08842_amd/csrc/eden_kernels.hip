@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void k_dec_hi_last(DecBatch B, uint32_t n, uin
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t off = base_off + ((uint32_t)r << (p + 2));
-        buf_store(ra, lane_off, off, buf_load(ra, lane_off, off) + sum[r]);
+        buf_store_keep(ra, lane_off, off, buf_load_keep(ra, lane_off, off) + sum[r]);
     }
 }
 

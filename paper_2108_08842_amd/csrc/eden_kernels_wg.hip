@@ -34,6 +34,18 @@ struct HiX {
     static constexpr int LDS_FLOATS = RP * RL * 32;
 };
 
+// Workgroups are dealt to the 8 XCDs round robin and each XCD has its own L2.  Neighbouring tiles touch
+// neighbouring 64..128-byte pieces of the same rows (and, in decode, the same 64-byte sectors of the payload),
+// so runs of 16 consecutive tiles are kept on one XCD.
+__device__ inline uint32_t xcd_local_tile() {
+    uint32_t tile = blockIdx.x;
+    if (gridDim.x % 128u == 0) {
+        const uint32_t xcd = tile & 7u, q = tile >> 3;
+        tile = ((q >> 4) * 8u + xcd) * 16u + (q & 15u);
+    }
+    return tile;
+}
+
 template <int M>
 __device__ inline uint64_t hix_base(uint32_t tile, int p) {
     const uint32_t cb_bits = (uint32_t)p - 5u;                   // 2^(p-5) blocks of 32 columns
@@ -93,7 +105,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_first(EncBatch B, uint6
     constexpr int p = kHixP;
     (void)p_arg;
     const uint32_t c = blockIdx.y;
-    const uint64_t base = hix_base<M>(blockIdx.x, p);
+    const uint64_t base = hix_base<M>(xcd_local_tile(), p);
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
     const uint32_t g0 = 2u * wave_in_block();                    // the two groups of this wave: g0, g0 + 1
     const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));              // reads past d give the zero padding
@@ -176,12 +188,12 @@ struct HiXLoader {
 #pragma unroll
             for (int r = 0; r < 64; ++r)
                 raw[r] = (uint32_t)(int)(short)__builtin_amdgcn_raw_buffer_load_b16(
-                    rt, (int)(off1 >> 1), (int)((((uint32_t)X::RL * r) << (p + 2)) >> 1), 0);
+                    rt, (int)(off1 >> 1), (int)((((uint32_t)X::RL * r) << (p + 2)) >> 1), kStream);
         } else {
             const rsrc_t rt = make_rsrc(slot + base_off, (4u << log2D) - base_off);
 #pragma unroll
             for (int r = 0; r < 64; ++r)
-                raw[r] = __builtin_amdgcn_raw_buffer_load_b32(rt, (int)off1, (int)(((uint32_t)X::RL * r) << (p + 2)), 0);
+                raw[r] = __builtin_amdgcn_raw_buffer_load_b32(rt, (int)off1, (int)(((uint32_t)X::RL * r) << (p + 2)), kStream);
         }
     }
 };
@@ -247,7 +259,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_last(DecBatch B, uint32
 #pragma unroll
         for (int s = 0; s < X::RP; ++s) {
             const uint32_t off = base_off + (hix_row2<M>(0, ph, s) << (p + 2));
-            buf_store(ra, off2, off, buf_load(ra, off2, off) + sum[ph * X::RP + s]);
+            buf_store_keep(ra, off2, off, buf_load_keep(ra, off2, off) + sum[ph * X::RP + s]);
         }
     }
 }
@@ -369,63 +381,76 @@ __device__ inline void lo14_quantize_store(const float (&u)[4][16], const EncScr
     }
 }
 
+// TPW tiles per workgroup, processed in a loop: the next tile's 64 loads per thread are in flight while the
+// current tile is transformed and quantized.
+template <int TPW>
 __global__ __launch_bounds__(256) void k_enc_lo14(EncBatch B, int log2D, uint64_t seed, const float *T, double *partials,
                                                   uint32_t partial_stride, const EncScratch *scratch) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14Lds];
     __shared__ double red[4];
     const uint32_t c = blockIdx.y;
-    const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
-    float u[4][16];
-    {
-        const float *Tt = T + ((size_t)c << log2D) + tile_base + wave_in_block() * 4096u + lane_id();
-        float v[64];
-#pragma unroll
-        for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(Tt + 64 * j);
-        lo14_forward(v, lds, u);
-    }
-
     const EncScratch *s = &scratch[c];
     const uint32_t b_q8 = B.b_q8[c];
     uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
+    const float *Tw = T + ((size_t)c << log2D) + wave_in_block() * 4096u + lane_id();
     float ip = 0.0f;
-    if (b_q8 == 256 || b_q8 == 128) {
-        float sa = 0.0f;
+    float next[64];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+    for (int j = 0; j < 64; ++j) next[j] = __builtin_nontemporal_load(Tw + (((uint64_t)blockIdx.x * TPW) << kLo14Bits) + 64 * j);
 #pragma unroll
-            for (int kk = 0; kk < 16; ++kk) sa += fabsf(u[r][kk]);
-        ip = sa * s->qpos[0];
+    for (int t = 0; t < TPW; ++t) {
+        const uint64_t tile_base = ((uint64_t)blockIdx.x * TPW + t) << kLo14Bits;
+        float u[4][16];
+        {
+            float v[64];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint64_t run = tile_base + (uint64_t)r * 4096u + 64u * src;       // this quad's 64 coordinates
-            if (b_q8 == 256) {
-                uint32_t neg = 0;                                // sign bits, last coordinate first
+            for (int j = 0; j < 64; ++j) v[j] = next[j];
+            if (t + 1 < TPW) {
 #pragma unroll
-                for (int kk = 15; kk >= 0; --kk) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(u[r][kk]), 31);
-                const uint32_t mine = ~neg & 0xFFFFu;            // index 1 = non-negative
-                const uint32_t other = quad_swap1(mine);
-                if (!(kq & 1u)) payload[(run >> 5) + (kq >> 1)] = mine | (other << 16);
-            } else {
-                uint32_t ev = 0, od = 0;
-#pragma unroll
-                for (int g = 7; g >= 0; --g) {
-                    ev = __builtin_amdgcn_alignbit(ev, __float_as_uint(u[r][2 * g]), 31);
-                    od = __builtin_amdgcn_alignbit(od, __float_as_uint(u[r][2 * g + 1]), 31);
-                }
-                const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
-                const uint64_t hw = hash_word(key, run >> 7);    // 64 pairs per hash word = 128 coordinates
-                const uint32_t off = (uint32_t)(hw >> (((run >> 6) & 1ull) * 32 + 8 * kq)) & 0xFFu;
-                uint32_t piece = (((~ev & ~off) | (~od & off)) & 0xFFu) << (8 * kq);
-                piece |= quad_swap1(piece);
-                piece |= quad_swap2(piece);
-                if (kq == 0) payload[run >> 6] = piece;
+                for (int j = 0; j < 64; ++j) next[j] = __builtin_nontemporal_load(Tw + tile_base + (1u << kLo14Bits) + 64 * j);
             }
+            lo14_forward(v, lds, u);
         }
-    } else if (b_q8 == 512) {
-        lo14_quantize_store<2>(u, s, payload, tile_base, ip);
-    } else {
-        lo14_quantize_store<4>(u, s, payload, tile_base, ip);
+        if (b_q8 == 256 || b_q8 == 128) {
+            float sa = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk) sa += fabsf(u[r][kk]);
+            ip += sa * s->qpos[0];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint64_t run = tile_base + (uint64_t)r * 4096u + 64u * src;   // this quad's 64 coordinates
+                if (b_q8 == 256) {
+                    uint32_t neg = 0;                            // sign bits, last coordinate first
+#pragma unroll
+                    for (int kk = 15; kk >= 0; --kk) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(u[r][kk]), 31);
+                    const uint32_t mine = ~neg & 0xFFFFu;        // index 1 = non-negative
+                    const uint32_t other = quad_swap1(mine);
+                    if (!(kq & 1u)) payload[(run >> 5) + (kq >> 1)] = mine | (other << 16);
+                } else {
+                    uint32_t ev = 0, od = 0;
+#pragma unroll
+                    for (int g = 7; g >= 0; --g) {
+                        ev = __builtin_amdgcn_alignbit(ev, __float_as_uint(u[r][2 * g]), 31);
+                        od = __builtin_amdgcn_alignbit(od, __float_as_uint(u[r][2 * g + 1]), 31);
+                    }
+                    const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+                    const uint64_t hw = hash_word(key, run >> 7);   // 64 pairs per hash word = 128 coordinates
+                    const uint32_t off = (uint32_t)(hw >> (((run >> 6) & 1ull) * 32 + 8 * kq)) & 0xFFu;
+                    uint32_t piece = (((~ev & ~off) | (~od & off)) & 0xFFu) << (8 * kq);
+                    piece |= quad_swap1(piece);
+                    piece |= quad_swap2(piece);
+                    if (kq == 0) payload[run >> 6] = piece;
+                }
+            }
+        } else if (b_q8 == 512) {
+            lo14_quantize_store<2>(u, s, payload, tile_base, ip);
+        } else {
+            lo14_quantize_store<4>(u, s, payload, tile_base, ip);
+        }
+        if (t + 1 < TPW) __syncthreads();                        // LDS is reused by the next tile
     }
     const double block_total = block_sum<256>((double)ip, red);
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
@@ -521,7 +546,8 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, i
     __shared__ float lds[X::LDS_FLOATS];
     __shared__ float table[16];
     const uint32_t c = blockIdx.y;
-    const uint64_t base = hix_base<M>(blockIdx.x, p);
+    const uint32_t tile = xcd_local_tile();
+    const uint64_t base = hix_base<M>(tile, p);
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
     const uint32_t g0 = 2u * wave_in_block();
     const uint32_t b_q8 = B.b_q8[c];
@@ -608,12 +634,12 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, i
         hix_exchange<M, 0>(v, lds, out);
 #pragma unroll
         for (int s = 0; s < X::RP; ++s)
-            __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 0, s) << (p + 2)) >> 1), 0);
+            __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 0, s) << (p + 2)) >> 1), kStream);
         if constexpr (X::PH == 2) {
             hix_exchange<M, 1>(v, lds, out);
 #pragma unroll
             for (int s = 0; s < X::RP; ++s)
-                __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 1, s) << (p + 2)) >> 1), 0);
+                __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 1, s) << (p + 2)) >> 1), kStream);
         }
     } else {
         const rsrc_t rt = make_rsrc(slot + base_off, (4u << log2D) - base_off);
@@ -741,8 +767,14 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, 
 }
 uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
                          uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
-    dim3 grid(1u << (log2D - kLo14Bits), n);
-    hipLaunchKernelGGL(k_enc_lo14, grid, dim3(256), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
+    const uint32_t tiles = 1u << (log2D - kLo14Bits);
+    if (tiles >= 256) {                                          // enough workgroups left to fill the chip
+        dim3 grid(tiles / 4, n);
+        hipLaunchKernelGGL(k_enc_lo14<4>, grid, dim3(256), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
+        return grid.x;
+    }
+    dim3 grid(tiles, n);
+    hipLaunchKernelGGL(k_enc_lo14<1>, grid, dim3(256), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
     return grid.x;
 }
 void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, int narrow,
