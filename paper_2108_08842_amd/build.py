@@ -6,7 +6,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libeden_hip.so")
-SOURCES = ["eden_tables.cpp", "eden_kernels.hip", "eden_kernels_wg.hip", "eden_api.hip"]
+SOURCES = ["eden_tables.cpp", "eden_kernels.hip", "eden_kernels_wg.hip", "eden_kernels_lo14.hip", "eden_api.hip"]
 
 
 def hipcc_path() -> str:

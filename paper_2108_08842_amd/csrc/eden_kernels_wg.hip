@@ -37,11 +37,12 @@ struct HiX {
 // Workgroups are dealt to the 8 XCDs round robin and each XCD has its own L2.  Neighbouring tiles touch
 // neighbouring 64..128-byte pieces of the same rows (and, in decode, the same 64-byte sectors of the payload),
 // so runs of 16 consecutive tiles are kept on one XCD.
+template <int RUN = 16>
 __device__ inline uint32_t xcd_local_tile() {
     uint32_t tile = blockIdx.x;
-    if (gridDim.x % 128u == 0) {
+    if (gridDim.x % (8u * RUN) == 0) {
         const uint32_t xcd = tile & 7u, q = tile >> 3;
-        tile = ((q >> 4) * 8u + xcd) * 16u + (q & 15u);
+        tile = ((q / RUN) * 8u + xcd) * RUN + (q % RUN);
     }
     return tile;
 }
@@ -67,13 +68,19 @@ __device__ inline uint32_t hix_row2(uint32_t g, int ph, int s) {
 }
 
 // Exchange of half `PHASE`: stage-1 registers -> LDS -> registers that hold all low row bits of
-// RHL high-row values; then the butterflies over those low row bits.
+// RHL high-row values; then the butterflies over those low row bits.  Split in two so that a caller can
+// start loading the next tile into the registers the write has just freed.
 template <int M, int PHASE>
-__device__ inline void hix_exchange(const float (&v)[64], float *lds, float (&out)[HiX<M>::RP]) {
+__device__ inline void hix_exchange_write(const float (&v)[64], float *lds) {
     using X = HiX<M>;
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
 #pragma unroll
     for (int i = 0; i < X::RP; ++i) lds[(i * X::RL + g) * 32 + col] = v[PHASE * X::RP + i];
+}
+template <int M>
+__device__ inline void hix_exchange_read(float *lds, float (&out)[HiX<M>::RP]) {
+    using X = HiX<M>;
+    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < X::RP; ++s) {
@@ -82,6 +89,11 @@ __device__ inline void hix_exchange(const float (&v)[64], float *lds, float (&ou
     }
     __syncthreads();
     fwht_regs_low<X::RP, M - 6>(out);
+}
+template <int M, int PHASE>
+__device__ inline void hix_exchange(const float (&v)[64], float *lds, float (&out)[HiX<M>::RP]) {
+    hix_exchange_write<M, PHASE>(v, lds);
+    hix_exchange_read<M>(lds, out);
 }
 
 // The 32 sign bits of the rotation's diagonal for one row segment of a tile.
@@ -95,7 +107,10 @@ __device__ inline uint64_t pair_mask(uint32_t lo_words, uint32_t hi_words, int s
     return ((uint64_t)hi << 32) | lo;
 }
 
-template <int M>
+// TPW tiles per workgroup (neighbouring column blocks).  The loads of the next tile are issued into the
+// registers that each half of the exchange has just written to LDS, so they are in flight during the rest of
+// the current tile at no cost in registers.
+template <int M, int TPW>
 __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_first(EncBatch B, uint64_t d, int log2D, int p_arg,
                                                                 uint64_t seed, float *T, double *partials,
                                                                 uint32_t partial_stride) {
@@ -105,35 +120,53 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_first(EncBatch B, uint6
     constexpr int p = kHixP;
     (void)p_arg;
     const uint32_t c = blockIdx.y;
-    const uint64_t base = hix_base<M>(xcd_local_tile(), p);
+    const uint32_t tile0 = xcd_local_tile<16 / TPW>() * TPW;
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
     const uint32_t g0 = 2u * wave_in_block();                    // the two groups of this wave: g0, g0 + 1
     const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));              // reads past d give the zero padding
     const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
-    const uint32_t base_off = (uint32_t)base * 4u;
     const uint32_t off1 = ((g << p) + col) * 4u;                         // stage-1 rows: g + RL r
     const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;      // stage-2 rows: rl + RL (ph RP + g RHL + e)
-    float v[64];
-#pragma unroll
-    for (int r = 0; r < 64; ++r) v[r] = buf_load(rx, off1, base_off + (((uint32_t)X::RL * r) << (p + 2)));
-    double n2 = 0.0;
-#pragma unroll
-    for (int r = 0; r < 64; ++r) n2 += (double)v[r] * (double)v[r];
-    // lane l hashes the sign bits of register l's two row segments; register r reads them back as a lane mask
     const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
-    const uint32_t wa = sign_half_word(key, base + ((uint64_t)hix_row1<M>(g0, lane) << p));
-    const uint32_t wb = sign_half_word(key, base + ((uint64_t)hix_row1<M>(g0 + 1, lane) << p));
+    double n2 = 0.0;
+    float v[64];
+    {
+        const uint32_t b0 = (uint32_t)hix_base<M>(tile0, p) * 4u;
 #pragma unroll
-    for (int r = 0; r < 64; ++r) v[r] = negate_where(v[r], pair_mask(wa, wb, r)) + 0.0f;   // + 0: no negative zeros
-    fwht_regs<64>(v);
-    float out[X::RP];
-    hix_exchange<M, 0>(v, lds, out);
+        for (int r = 0; r < 64; ++r) v[r] = buf_load(rx, off1, b0 + (((uint32_t)X::RL * r) << (p + 2)));
+    }
 #pragma unroll
-    for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 0, s) << (p + 2)), out[s]);
-    if constexpr (X::PH == 2) {
-        hix_exchange<M, 1>(v, lds, out);
+    for (int k = 0; k < TPW; ++k) {
+        const uint64_t base = hix_base<M>(tile0 + k, p);
+        const uint32_t base_off = (uint32_t)base * 4u;
+        const uint32_t next_off = (uint32_t)hix_base<M>(tile0 + k + 1, p) * 4u;
 #pragma unroll
-        for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 1, s) << (p + 2)), out[s]);
+        for (int r = 0; r < 64; ++r) n2 += (double)v[r] * (double)v[r];
+        // lane l hashes the sign bits of register l's two row segments; register r reads them back as a lane mask
+        const uint32_t wa = sign_half_word(key, base + ((uint64_t)hix_row1<M>(g0, lane) << p));
+        const uint32_t wb = sign_half_word(key, base + ((uint64_t)hix_row1<M>(g0 + 1, lane) << p));
+#pragma unroll
+        for (int r = 0; r < 64; ++r) v[r] = negate_where(v[r], pair_mask(wa, wb, r)) + 0.0f;   // + 0: no negative zeros
+        fwht_regs<64>(v);
+        float out[X::RP];
+        hix_exchange_write<M, 0>(v, lds);
+        if (k + 1 < TPW) {
+#pragma unroll
+            for (int r = 0; r < X::RP; ++r) v[r] = buf_load(rx, off1, next_off + (((uint32_t)X::RL * r) << (p + 2)));
+        }
+        hix_exchange_read<M>(lds, out);
+#pragma unroll
+        for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 0, s) << (p + 2)), out[s]);
+        if constexpr (X::PH == 2) {
+            hix_exchange_write<M, 1>(v, lds);
+            if (k + 1 < TPW) {
+#pragma unroll
+                for (int r = X::RP; r < 64; ++r) v[r] = buf_load(rx, off1, next_off + (((uint32_t)X::RL * r) << (p + 2)));
+            }
+            hix_exchange_read<M>(lds, out);
+#pragma unroll
+            for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 1, s) << (p + 2)), out[s]);
+        }
     }
     const double block_total = block_sum<X::THREADS>(n2, red);
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
@@ -269,44 +302,9 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_last(DecBatch B, uint32
 constexpr int kLo14Bits = 14;
 constexpr int kLo14Lds = 4 * 64 * kLdsRow;       // floats
 
-// 4 waves x 4096 coordinates.  On return thread t holds, for each of the four 4096-regions r, the final
-// values of the 16 consecutive coordinates  tile*2^14 + r*4096 + 64*(t >> 2) + 16*(t & 3) + kk.
-// v[j] must hold coordinate  wave*4096 + 64 j + lane  of the tile.
-__device__ inline void lo14_forward(float (&v)[64], float *lds, float (&u)[4][16]) {
-    const uint32_t lane = lane_id(), wv = wave_in_block();
-    fwht_regs<64>(v);                                            // bits 6..11
-    float *L = lds + wv * (64 * kLdsRow);
-#pragma unroll
-    for (int j = 0; j < 64; ++j) L[j * kLdsRow + lane] = v[j];
-    wave_lds_sync();
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        const float4 t = *reinterpret_cast<const float4 *>(&L[lane * kLdsRow + 4 * q]);
-        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
-    }
-    fwht_regs<64>(v);                                            // bits 0..5
-    wave_lds_sync();
-#pragma unroll
-    for (int q = 0; q < 16; ++q)
-        *reinterpret_cast<float4 *>(&L[lane * kLdsRow + 4 * q]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-    __syncthreads();
-    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float4 t = *reinterpret_cast<const float4 *>(&lds[(r * 64 + src) * kLdsRow + 16 * kq + 4 * i]);
-            u[r][4 * i] = t.x; u[r][4 * i + 1] = t.y; u[r][4 * i + 2] = t.z; u[r][4 * i + 3] = t.w;
-        }
-    }
-#pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {                            // bits 12, 13
-        const float a = u[0][kk] + u[1][kk], b = u[0][kk] - u[1][kk];
-        const float c = u[2][kk] + u[3][kk], e = u[2][kk] - u[3][kk];
-        u[0][kk] = a + c; u[1][kk] = b + e; u[2][kk] = a - c; u[3][kk] = b - e;
-    }
-}
-
+// Decode-side 14-bit contiguous pass in four waves of 4096 coordinates (used when the contiguous pass comes
+// first in decode).  Thread t handles, for each of the four 4096-regions r, the 16 consecutive coordinates
+// tile*2^14 + r*4096 + 64*(t >> 2) + 16*(t & 3) + kk: unpacked values in, transformed tile out.
 // The mirror image for decode: u (same layout as above, not yet transformed) -> T.
 template <bool NARROW>
 __device__ inline void lo14_backward(float (&u)[4][16], float *lds, float *Tt) {
@@ -352,109 +350,6 @@ __device__ inline void lo14_backward(float (&u)[4][16], float *lds, float *Tt) {
     }
 }
 
-__device__ inline uint32_t quad_swap1(uint32_t x) {   // value of lane ^ 1
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);
-}
-__device__ inline uint32_t quad_swap2(uint32_t x) {   // value of lane ^ 2
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true);
-}
-
-template <int BITS>
-__device__ inline void lo14_quantize_store(const float (&u)[4][16], const EncScratch *s, uint32_t *payload,
-                                           uint64_t tile_base, float &ip) {
-    constexpr int H = 1 << (BITS - 1);
-    float thr[H], qp[H];
-#pragma unroll
-    for (int i = 0; i < H; ++i) { thr[i] = s->thr[i]; qp[i] = s->qpos[i]; }
-    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const uint64_t first = tile_base + (uint64_t)r * 4096u + 64u * src + 16u * kq;   // first coordinate of the run
-        uint32_t w[BITS / 2] = {};
-#pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-            const uint32_t code = quantize_one<H>(u[r][kk], thr, qp, ip);
-            w[(kk * BITS) / 32] |= code << ((kk * BITS) % 32);
-        }
-        if constexpr (BITS == 2) payload[first >> 4] = w[0];
-        else *reinterpret_cast<uint2 *>(payload + (first >> 3)) = make_uint2(w[0], w[1]);
-    }
-}
-
-// TPW tiles per workgroup, processed in a loop: the next tile's 64 loads per thread are in flight while the
-// current tile is transformed and quantized.
-template <int TPW>
-__global__ __launch_bounds__(256) void k_enc_lo14(EncBatch B, int log2D, uint64_t seed, const float *T, double *partials,
-                                                  uint32_t partial_stride, const EncScratch *scratch) {
-    __shared__ __attribute__((aligned(16))) float lds[kLo14Lds];
-    __shared__ double red[4];
-    const uint32_t c = blockIdx.y;
-    const EncScratch *s = &scratch[c];
-    const uint32_t b_q8 = B.b_q8[c];
-    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
-    const float *Tw = T + ((size_t)c << log2D) + wave_in_block() * 4096u + lane_id();
-    float ip = 0.0f;
-    float next[64];
-#pragma unroll
-    for (int j = 0; j < 64; ++j) next[j] = __builtin_nontemporal_load(Tw + (((uint64_t)blockIdx.x * TPW) << kLo14Bits) + 64 * j);
-#pragma unroll
-    for (int t = 0; t < TPW; ++t) {
-        const uint64_t tile_base = ((uint64_t)blockIdx.x * TPW + t) << kLo14Bits;
-        float u[4][16];
-        {
-            float v[64];
-#pragma unroll
-            for (int j = 0; j < 64; ++j) v[j] = next[j];
-            if (t + 1 < TPW) {
-#pragma unroll
-                for (int j = 0; j < 64; ++j) next[j] = __builtin_nontemporal_load(Tw + tile_base + (1u << kLo14Bits) + 64 * j);
-            }
-            lo14_forward(v, lds, u);
-        }
-        if (b_q8 == 256 || b_q8 == 128) {
-            float sa = 0.0f;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int kk = 0; kk < 16; ++kk) sa += fabsf(u[r][kk]);
-            ip += sa * s->qpos[0];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint64_t run = tile_base + (uint64_t)r * 4096u + 64u * src;   // this quad's 64 coordinates
-                if (b_q8 == 256) {
-                    uint32_t neg = 0;                            // sign bits, last coordinate first
-#pragma unroll
-                    for (int kk = 15; kk >= 0; --kk) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(u[r][kk]), 31);
-                    const uint32_t mine = ~neg & 0xFFFFu;        // index 1 = non-negative
-                    const uint32_t other = quad_swap1(mine);
-                    if (!(kq & 1u)) payload[(run >> 5) + (kq >> 1)] = mine | (other << 16);
-                } else {
-                    uint32_t ev = 0, od = 0;
-#pragma unroll
-                    for (int g = 7; g >= 0; --g) {
-                        ev = __builtin_amdgcn_alignbit(ev, __float_as_uint(u[r][2 * g]), 31);
-                        od = __builtin_amdgcn_alignbit(od, __float_as_uint(u[r][2 * g + 1]), 31);
-                    }
-                    const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
-                    const uint64_t hw = hash_word(key, run >> 7);   // 64 pairs per hash word = 128 coordinates
-                    const uint32_t off = (uint32_t)(hw >> (((run >> 6) & 1ull) * 32 + 8 * kq)) & 0xFFu;
-                    uint32_t piece = (((~ev & ~off) | (~od & off)) & 0xFFu) << (8 * kq);
-                    piece |= quad_swap1(piece);
-                    piece |= quad_swap2(piece);
-                    if (kq == 0) payload[run >> 6] = piece;
-                }
-            }
-        } else if (b_q8 == 512) {
-            lo14_quantize_store<2>(u, s, payload, tile_base, ip);
-        } else {
-            lo14_quantize_store<4>(u, s, payload, tile_base, ip);
-        }
-        if (t + 1 < TPW) __syncthreads();                        // LDS is reused by the next tile
-    }
-    const double block_total = block_sum<256>((double)ip, red);
-    if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
-}
 
 // `narrow` != 0: for senders with b <= 1 the unit pattern (+-1 or 0) is transformed and the exact integers are
 // stored as int16 at the same element index (the consumer multiplies by the sender's magnitude at the end).
@@ -654,78 +549,6 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, i
     }
 }
 
-__device__ inline uint32_t quad_bcast(uint32_t x, int src) {   // value of lane (lane & ~3) + src
-    switch (src) {
-        case 0: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x00, 0xF, 0xF, true);
-        case 1: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x55, 0xF, 0xF, true);
-        case 2: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xAA, 0xF, 0xF, true);
-        default: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xFF, 0xF, 0xF, true);
-    }
-}
-
-// Last decode pass: index bits 0..13 of H for every sender, that sender's sign diagonal (R^-1 = s o D^-1/2 H,
-// Sec. 2.2.2), sum over senders in registers, one contiguous read-modify-write of acc.
-__global__ __launch_bounds__(256) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
-                                                       const float *T, const DecScratch *scratch, int narrow, float *acc) {
-    __shared__ __attribute__((aligned(16))) float lds[kLo14Lds];
-    const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
-    if (tile_base >= d) return;                                  // whole tile in the padding
-    const uint32_t lane = lane_id(), wv = wave_in_block();
-    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
-    float sum[4][16];
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int kk = 0; kk < 16; ++kk) sum[r][kk] = 0.0f;
-    for (uint32_t c = 0; c < n; ++c) {
-        const bool i16 = narrow && B.b_q8[c] <= 256u;
-        float v[64];
-        if (i16) {
-            const short *t16 = reinterpret_cast<const short *>(T + ((size_t)c << log2D)) + tile_base + wv * 4096u + lane;
-#pragma unroll
-            for (int j = 0; j < 64; ++j) v[j] = (float)(int)__builtin_nontemporal_load(t16 + 64 * j);
-        } else {
-            const float *t32 = T + ((size_t)c << log2D) + tile_base + wv * 4096u + lane;
-#pragma unroll
-            for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(t32 + 64 * j);
-        }
-        float u[4][16];
-        lo14_forward(v, lds, u);
-        const uint32_t scale = __float_as_uint(i16 ? scratch[c].deq[1] : 1.0f) & 0x7FFFFFFFu;   // > 0; x*1+s is exact
-        // thread kq of a quad hashes the sign word of region kq; the quad shares the four words
-        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
-        const uint64_t mine = hash_word(key, (tile_base + (uint64_t)kq * 4096u + 64u * src) >> 6);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t wlo = quad_bcast((uint32_t)mine, r), whi = quad_bcast((uint32_t)(mine >> 32), r);
-            const uint32_t f16 = ((kq & 2u) ? whi : wlo) >> (16u * (kq & 1u));   // the 16 sign bits of this thread's run
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk) {
-                const uint32_t sgn = (f16 << (31 - kk)) & 0x80000000u;           // hash bit 1 -> s_i = -1
-                sum[r][kk] = fmaf(u[r][kk], __uint_as_float(scale | sgn), sum[r][kk]);
-            }
-        }
-        __syncthreads();                                         // LDS is reused by the next sender
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const uint64_t first = tile_base + (uint64_t)r * 4096u + 64u * src + 16u * kq;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const uint64_t i = first + 4u * q;
-            if (i + 3 < d) {
-                float4 a = *reinterpret_cast<const float4 *>(acc + i);
-                a.x += sum[r][4 * q]; a.y += sum[r][4 * q + 1]; a.z += sum[r][4 * q + 2]; a.w += sum[r][4 * q + 3];
-                *reinterpret_cast<float4 *>(acc + i) = a;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (i + e < d) acc[i + e] += sum[r][4 * q + e];
-            }
-        }
-    }
-}
-
 // ------------------------------------------------------------------------------------------------
 #define EDEN_HIX_SWITCH(M, CALL)                         \
     switch (M) {                                         \
@@ -739,9 +562,16 @@ static uint32_t hix_tiles(int M, int log2D) { return 1u << (log2D - M - 5); }
 
 uint32_t launch_hix_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
                           double *partials, uint32_t partial_stride, hipStream_t st) {
-    dim3 grid(hix_tiles(M, log2D), n);
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D, p, seed, T,
-                                          partials, partial_stride));
+    const uint32_t tiles = hix_tiles(M, log2D);
+    if (tiles % 256u == 0) {                                     // two neighbouring tiles per workgroup
+        dim3 grid(tiles / 2, n);
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_hix_first<MM, 2>), grid, dim3(HiX<MM>::THREADS), 0, st, B, d,
+                                              log2D, p, seed, T, partials, partial_stride));
+        return grid.x;
+    }
+    dim3 grid(tiles, n);
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_hix_first<MM, 1>), grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D,
+                                          p, seed, T, partials, partial_stride));
     return grid.x;
 }
 void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st) {
@@ -759,23 +589,6 @@ void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint6
     dim3 grid(hix_tiles(M, log2D), n);
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, log2D, seed, scratch,
                                           narrow, T));
-}
-void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
-                          const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
-    dim3 grid(1u << (log2D - kLo14Bits));
-    hipLaunchKernelGGL(k_dec_lo14_last, grid, dim3(256), 0, st, B, n, d, log2D, seed, T, scratch, narrow, acc);
-}
-uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
-                         uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
-    const uint32_t tiles = 1u << (log2D - kLo14Bits);
-    if (tiles >= 256) {                                          // enough workgroups left to fill the chip
-        dim3 grid(tiles / 4, n);
-        hipLaunchKernelGGL(k_enc_lo14<4>, grid, dim3(256), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
-        return grid.x;
-    }
-    dim3 grid(tiles, n);
-    hipLaunchKernelGGL(k_enc_lo14<1>, grid, dim3(256), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
-    return grid.x;
 }
 void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, int narrow,
                      float *T, hipStream_t st) {
