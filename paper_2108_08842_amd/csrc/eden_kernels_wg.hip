@@ -549,6 +549,116 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, i
     }
 }
 
+// First decode pass for senders with b <= 1, two columns per thread.  The unit pattern is +-1 or 0 and M <= 10
+// stages keep every value within +-1024, so the whole pass runs on pairs of int16 packed in one register
+// (v_pk_add_i16 / v_pk_sub_i16: two butterflies per instruction) and a tile is 64 columns wide: the workspace
+// is written in 128-byte segments.
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+
+template <int N, int LOGB>
+__device__ inline void fwht_pk(s16x2 (&v)[N]) {
+#pragma unroll
+    for (int h = 1; h < (1 << LOGB); h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < N; i += 2 * h) {
+#pragma unroll
+            for (int j = i; j < i + h; ++j) {
+                const s16x2 a = v[j], b = v[j + h];
+                v[j] = a + b;
+                v[j + h] = a - b;
+            }
+        }
+    }
+}
+
+template <int M>
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first_pk(DecBatch B, int log2D, uint64_t seed, float *T) {
+    using X = HiX<M>;
+    constexpr int p = kHixP;
+    __shared__ uint32_t lds[X::LDS_FLOATS];
+    const uint32_t c = blockIdx.y;
+    const uint32_t tile = xcd_local_tile();
+    // 64-column blocks: 2^(p-6) of them per row
+    const uint32_t cb = tile & ((1u << (p - 6)) - 1u), upper = tile >> (p - 6);
+    const uint64_t base = ((uint64_t)upper << (p + M)) | ((uint64_t)cb << 6);
+    const uint32_t cp = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
+    const uint32_t g0 = 2u * wave_in_block();
+    const uint32_t b_q8 = B.b_q8[c];
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const uint32_t payload_bytes = (uint32_t)(((((1ull << log2D) >> (b_q8 == 128u)) + 63) >> 6) << 3);
+    const uint64_t row_a = (uint64_t)hix_row1<M>(g0, lane) << p, row_b = (uint64_t)hix_row1<M>(g0 + 1, lane) << p;
+    uint64_t recv_a = ~0ull, recv_b = ~0ull;                     // bit r: did the packet of register r's row arrive
+    const uint32_t *bm = B.bitmap[c];
+    if (bm) {
+        const uint32_t pa = (uint32_t)((base + row_a) >> 10), pb = (uint32_t)((base + row_b) >> 10);
+        recv_a = __ballot((bm[pa >> 5] >> (pa & 31u)) & 1u);
+        recv_b = __ballot((bm[pb >> 5] >> (pb & 31u)) & 1u);
+    }
+    uint32_t v32[64];
+    if (b_q8 == 256) {
+        // the two index bits of columns 2cp, 2cp+1 -> (+-1, +-1); index 1 = non-negative
+        const rsrc_t rp = make_rsrc(payload + (base >> 5), payload_bytes - (uint32_t)(base >> 5) * 4u);
+        const uint32_t voff = ((g << (p - 5)) + (cp >> 4)) * 4u;
+        const uint32_t sh = 2u * (cp & 15u);
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)X::RL * r) << (p - 5)) * 4u), 0);
+            const uint32_t x = w >> sh;
+            v32[r] = 0xFFFFFFFFu ^ (((x & 1u) * 0xFFFEu) | ((x & 2u) * 0x7FFF0000u));
+        }
+    } else {
+        // b = 1/2: the pair (2cp, 2cp+1) carries one bit; the offset bit of the sub-sampling stream says which one
+        const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+        const uint32_t hs = 32u * (uint32_t)((base >> 6) & 1u);
+        const uint32_t fa = (uint32_t)(hash_word(key, (base + row_a) >> 7) >> hs);
+        const uint32_t fb = (uint32_t)(hash_word(key, (base + row_b) >> 7) >> hs);
+        const rsrc_t rp = make_rsrc(payload + (base >> 6), payload_bytes - (uint32_t)(base >> 6) * 4u);
+        const uint32_t voff = (g << (p - 6)) * 4u;
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)X::RL * r) << (p - 6)) * 4u), 0);
+            const uint32_t offs = (lane < 32u) ? __builtin_amdgcn_readlane(fa, r) : __builtin_amdgcn_readlane(fb, r);
+            const uint32_t val = ((w >> cp) & 1u) ? 0x0001u : 0xFFFFu;           // +1 or -1 as int16
+            v32[r] = ((offs >> cp) & 1u) ? (val << 16) : val;
+        }
+    }
+    if (bm) {
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const uint64_t m = (((recv_a >> r) & 1ull) ? 0x00000000FFFFFFFFull : 0ull) |
+                               (((recv_b >> r) & 1ull) ? 0xFFFFFFFF00000000ull : 0ull);
+            v32[r] = __float_as_uint(keep_where(__uint_as_float(v32[r]), m));
+        }
+    }
+    s16x2 v[64];
+#pragma unroll
+    for (int r = 0; r < 64; ++r) v[r] = __builtin_bit_cast(s16x2, v32[r]);
+    fwht_pk<64, 6>(v);
+    // int16 element i of the sender's slot sits at byte 2 i: the pair of this thread is one 32-bit store
+    char *slot = reinterpret_cast<char *>(T + ((size_t)c << log2D)) + base * 2u;
+    const rsrc_t rt = make_rsrc(slot, (2u << log2D) - (uint32_t)base * 2u);
+    const uint32_t off2 = (((g * X::RHL * X::RL) << p) * 2u) + cp * 4u;
+    const uint32_t col = cp;                                     // exchange slot of this thread
+#pragma unroll
+    for (int ph = 0; ph < X::PH; ++ph) {
+#pragma unroll
+        for (int i = 0; i < X::RP; ++i) lds[(i * X::RL + g) * 32 + col] = __builtin_bit_cast(uint32_t, v[ph * X::RP + i]);
+        __syncthreads();
+        s16x2 out[X::RP];
+#pragma unroll
+        for (int s2 = 0; s2 < X::RP; ++s2) {
+            const int e = s2 / X::RL, rl = s2 % X::RL;
+            out[s2] = __builtin_bit_cast(s16x2, lds[((g * X::RHL + e) * X::RL + rl) * 32 + col]);
+        }
+        __syncthreads();
+        fwht_pk<X::RP, M - 6>(out);
+#pragma unroll
+        for (int s2 = 0; s2 < X::RP; ++s2)
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, out[s2]), rt, (int)off2,
+                                                  (int)((hix_row2<M>(0, ph, s2) << p) * 2u), kStream);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 #define EDEN_HIX_SWITCH(M, CALL)                         \
     switch (M) {                                         \
@@ -586,6 +696,13 @@ void launch_hix_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D
 }
 void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch,
                           int narrow, float *T, hipStream_t st) {
+    bool all_unit = narrow != 0;                                 // every sender b <= 1: packed int16 kernel
+    for (uint32_t c = 0; c < n; ++c) all_unit = all_unit && B.b_q8[c] <= 256u;
+    if (all_unit) {
+        dim3 grid(hix_tiles(M, log2D) / 2, n);                   // 64-column tiles
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first_pk<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, log2D, seed, T));
+        return;
+    }
     dim3 grid(hix_tiles(M, log2D), n);
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, log2D, seed, scratch,
                                           narrow, T));
