@@ -22,7 +22,7 @@ struct eden_ctx {
     uint32_t n_max;          // senders per call the workspace was sized for (chunks of kMaxBatch are used)
     uint32_t slots;          // workspace slots = min(n_max, kMaxBatch)
     float *T;                // slots * D_max floats (nullptr if D_max <= 4096)
-    double *partials;        // slots * partial_stride doubles
+    double *partials;        // 2 * slots * partial_stride doubles: |x|^2 partials, then sum u q partials
     uint32_t partial_stride;
     EncScratch *enc_scratch; // slots
     DecScratch *dec_scratch; // slots
@@ -136,7 +136,7 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     bool ok = true;
     if (ctx->log2D_max > kLoBits)
         ok = ok && hipMalloc(&ctx->T, (size_t)ctx->slots * D_max * sizeof(float)) == hipSuccess;
-    ok = ok && hipMalloc(&ctx->partials, (size_t)ctx->slots * ctx->partial_stride * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->partials, 2 * (size_t)ctx->slots * ctx->partial_stride * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->enc_scratch, ctx->slots * sizeof(EncScratch)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->dec_scratch, ctx->slots * sizeof(DecScratch)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->tables, sizeof(DevTables)) == hipSuccess;
@@ -206,19 +206,24 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             launch_enc_small(B, nb, d, log2D, seed, ctx->tables, ctx->dev_status, st);
         } else {
             // top bits first; the first pass reads x, the rest work in place on the workspace
-            uint32_t nparts = 0;
+            uint32_t nparts_n2 = 0, nparts_ip = 0;
+            double *part_n2 = ctx->partials, *part_ip = ctx->partials + (size_t)ctx->slots * ctx->partial_stride;
+            bool need_thresholds = false;                        // b = 1 and 1/2 quantize by sign alone
+            for (uint32_t i = 0; i < nb; ++i) need_thresholds = need_thresholds || B.b_q8[i] > 256u;
             for (int i = pl.nhi - 1; i >= 0; --i) {
                 const HiPass &h = pl.hi[i];
                 if (i == pl.nhi - 1) {
                     {
                         Timed t(ctx, EDEN_K_ENC_HI_FIRST, nb, st);
-                        nparts = h.wg ? launch_hix_first(h.M, B, nb, d, log2D, h.p, seed, ctx->T, ctx->partials,
-                                                         ctx->partial_stride, st)
-                                      : launch_enc_hi_first(h.M, B, nb, d, log2D, h.p, seed, ctx->T, ctx->partials,
-                                                            ctx->partial_stride, st);
+                        nparts_n2 = h.wg ? launch_hix_first(h.M, B, nb, d, log2D, h.p, seed, ctx->T, part_n2,
+                                                            ctx->partial_stride, st)
+                                         : launch_enc_hi_first(h.M, B, nb, d, log2D, h.p, seed, ctx->T, part_n2,
+                                                               ctx->partial_stride, st);
                     }
-                    Timed t(ctx, EDEN_K_ENC_NORM, nb, st);
-                    launch_enc_norm(B, nb, ctx->partials, ctx->partial_stride, nparts, ctx->enc_scratch, ctx->tables, st);
+                    if (need_thresholds) {
+                        Timed t(ctx, EDEN_K_ENC_NORM, nb, st);
+                        launch_enc_norm(B, nb, part_n2, ctx->partial_stride, nparts_n2, ctx->enc_scratch, ctx->tables, st);
+                    }
                 } else {
                     Timed t(ctx, EDEN_K_HI_MID, nb, st);
                     if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
@@ -227,13 +232,13 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             }
             {
                 Timed t(ctx, EDEN_K_ENC_LO, nb, st);
-                nparts = pl.lo_bits == 14 ? launch_enc_lo14(B, nb, log2D, seed, ctx->T, ctx->partials, ctx->partial_stride,
-                                                            ctx->enc_scratch, st)
-                                          : launch_enc_lo(B, nb, log2D, seed, ctx->T, ctx->partials, ctx->partial_stride,
-                                                          ctx->enc_scratch, st);
+                nparts_ip = pl.lo_bits == 14 ? launch_enc_lo14(B, nb, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
+                                                               ctx->enc_scratch, st)
+                                             : launch_enc_lo(B, nb, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
+                                                             ctx->enc_scratch, st);
             }
             Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
-            launch_enc_finish(B, nb, d, log2D, seed, ctx->partials, ctx->partial_stride, nparts, ctx->enc_scratch,
+            launch_enc_finish(B, nb, d, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
                               ctx->dev_status, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;

@@ -46,6 +46,9 @@ struct MsgHeader {
 static_assert(sizeof(MsgHeader) == 64, "header layout");
 constexpr uint32_t kMagic = 0x4E454445u;
 
+// the positive centroid of I_1, sqrt(2/pi) (Sec. 3: Q_{I_1} = {+-sqrt(2/pi)}); b = 1 and b = 1/2 need no other table
+constexpr float kQ1 = 0.7978845608028654f;
+
 // ---- device copies of the Lloyd-Max tables (positive halves, Sec. 3), index [bits][k]
 struct DevTables {
     double t[5][8];

@@ -13,9 +13,9 @@ uint32_t launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, i
                              double *partials, uint32_t partial_stride, hipStream_t st);
 void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint32_t partial_stride, uint32_t nparts,
                      EncScratch *scratch, const DevTables *tab, hipStream_t st);
-void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials,
-                       uint32_t partial_stride, uint32_t nparts, const EncScratch *scratch, uint32_t *dev_status,
-                       hipStream_t st);
+void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials_n2,
+                       uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip, uint32_t partial_stride,
+                       uint32_t *dev_status, hipStream_t st);
 void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
 void launch_dec_hi_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed,
                         const float *T, float *acc, hipStream_t st);

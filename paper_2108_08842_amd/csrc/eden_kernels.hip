@@ -214,8 +214,7 @@ __global__ __launch_bounds__(128) void k_enc_lo(EncBatch B, int log2D, uint64_t 
     fwht_regs<64>(v);                                          // index bits 0..5; lane owns 64 consecutive u_i
 
     const EncScratch *s = &scratch[c];
-    const double n2 = s->n2;
-    const bool valid = (n2 > 0.0) && (n2 < INFINITY);         // false for 0, inf, nan
+    constexpr bool valid = true;     // a zero or non-finite vector is detected, and its payload cleared, by k_enc_finish
     const uint32_t b_q8 = B.b_q8[c];
     uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     const size_t seg = (size_t)tile * 64 + lane;               // index of this lane's run of 64 coordinates
@@ -225,7 +224,7 @@ __global__ __launch_bounds__(128) void k_enc_lo(EncBatch B, int log2D, uint64_t 
         float sa = 0.0f;
 #pragma unroll
         for (int k = 0; k < 64; ++k) sa += fabsf(v[k]);
-        ip = sa * s->qpos[0];
+        ip = sa * kQ1;
         if (b_q8 == 256) {
             uint32_t w0 = 0, w1 = 0;                           // shift the sign bits in, last coordinate first
 #pragma unroll
@@ -268,16 +267,24 @@ __global__ __launch_bounds__(128) void k_enc_lo(EncBatch B, int log2D, uint64_t 
 // <R(x),Q> = D^-1/2 sum and the scale S = |x|^2 / <R(x),Q> (Sec. 2.3), writes the header.
 // A zero or non-finite vector gets S = 0, a status bit and an all-zero payload.
 __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int log2D, uint64_t seed,
-                                                    const double *partials, uint32_t partial_stride, uint32_t nparts,
-                                                    const EncScratch *scratch, uint32_t payload_words_b1,
+                                                    const double *partials_n2, uint32_t nparts_n2,
+                                                    const double *partials_ip, uint32_t nparts_ip,
+                                                    uint32_t partial_stride, uint32_t payload_words_b1,
                                                     uint32_t *dev_status) {
     __shared__ double red[4];
+    __shared__ double n2_shared;
     const uint32_t c = blockIdx.x;
-    const double *pc = partials + (size_t)c * partial_stride;
+    const double *pn = partials_n2 + (size_t)c * partial_stride;
+    const double *pi = partials_ip + (size_t)c * partial_stride;
     double s = 0.0;
-    for (uint32_t i = threadIdx.x; i < nparts; i += 256) s += pc[i];
+    for (uint32_t i = threadIdx.x; i < nparts_n2; i += 256) s += pn[i];
+    const double n2_t0 = block_sum<256>(s, red);                  // |x|^2, same summation order as k_enc_norm
+    s = 0.0;
+    for (uint32_t i = threadIdx.x; i < nparts_ip; i += 256) s += pi[i];
     const double total = block_sum<256>(s, red);
-    const double n2 = scratch[c].n2;
+    if (threadIdx.x == 0) n2_shared = n2_t0;
+    __syncthreads();
+    const double n2 = n2_shared;
     const bool valid = (n2 > 0.0) && (n2 < INFINITY);
     const uint32_t b_q8 = B.b_q8[c];
     if (!valid) {
@@ -436,9 +443,17 @@ __global__ __launch_bounds__(128) void k_dec_lo(DecBatch B, int log2D, uint64_t 
     for (int j = 0; j < 64; ++j) Tc[64 * j + lane] = v[j];
 }
 
-__global__ void k_finalize_mean(const float *acc, uint64_t d, float n, float *mean) {
-    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < d) mean[i] = acc[i] / n;                          // Sec. 2.2.2: the plain average
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// Sec. 2.2.2: the plain average.  Four coordinates per thread when both pointers are 16-byte aligned.
+__global__ void k_finalize_mean(const float *acc, uint64_t d, float n, float *mean, int vec) {
+    const uint64_t i = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) * (vec ? 4u : 1u);
+    if (vec && i + 3 < d) {
+        f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(acc + i));
+        a.x /= n; a.y /= n; a.z /= n; a.w /= n;
+        *reinterpret_cast<f32x4 *>(mean + i) = a;
+    } else {
+        for (uint64_t e = i; e < d && e < i + (vec ? 4u : 1u); ++e) mean[e] = acc[e] / n;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -622,12 +637,12 @@ void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint
                      EncScratch *scratch, const DevTables *tab, hipStream_t st) {
     hipLaunchKernelGGL(k_enc_norm, dim3(n), dim3(256), 0, st, B, partials, partial_stride, nparts, scratch, tab);
 }
-void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials,
-                       uint32_t partial_stride, uint32_t nparts, const EncScratch *scratch, uint32_t *dev_status,
-                       hipStream_t st) {
+void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials_n2,
+                       uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip, uint32_t partial_stride,
+                       uint32_t *dev_status, hipStream_t st) {
     const uint32_t words_b1 = 1u << (log2D - 5);
-    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, log2D, seed, partials, partial_stride, nparts,
-                       scratch, words_b1, dev_status);
+    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, log2D, seed, partials_n2, nparts_n2, partials_ip,
+                       nparts_ip, partial_stride, words_b1, dev_status);
 }
 void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
@@ -656,8 +671,10 @@ void launch_dec_lo(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, cons
     hipLaunchKernelGGL(k_dec_lo, grid, dim3(128), 0, st, B, log2D, seed, scratch, T);
 }
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st) {
-    const uint32_t blocks = (uint32_t)((d + 255) / 256);
-    hipLaunchKernelGGL(k_finalize_mean, dim3(blocks), dim3(256), 0, st, acc, d, (float)n, mean);
+    const int vec = ((reinterpret_cast<uintptr_t>(acc) | reinterpret_cast<uintptr_t>(mean)) & 15u) == 0;
+    const uint64_t per_block = 256u * (vec ? 4u : 1u);
+    const uint32_t blocks = (uint32_t)((d + per_block - 1) / per_block);
+    hipLaunchKernelGGL(k_finalize_mean, dim3(blocks), dim3(256), 0, st, acc, d, (float)n, mean, vec);
 }
 void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                       uint32_t *dev_status, hipStream_t st) {

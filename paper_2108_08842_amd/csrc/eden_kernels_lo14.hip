@@ -111,7 +111,7 @@ __global__ __launch_bounds__(512) void k_enc_lo14(EncBatch B, int log2D, uint64_
             float sa = 0.0f;
 #pragma unroll
             for (int e = 0; e < 32; ++e) sa += fabsf(u[e]);
-            ip += sa * s->qpos[0];
+            ip += sa * kQ1;
             if (b_q8 == 256) {
                 uint32_t neg = 0;                                // shift the sign bits in, last coordinate first
 #pragma unroll
