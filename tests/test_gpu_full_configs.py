@@ -65,3 +65,113 @@ def test_config4_full_size():
     assert 0.8 < nm / theory < 1.25
     assert ctx.last_device_status() == 0
     ctx.close()
+
+
+def _sampled_rows_check(x64, seed, client, idx_gpu_at, samples, thresholds):
+    """Indices of single coordinates computed one by one: z_i = sqrt(D)/|x| * D^-1/2 * sum_j H[i][j] s_j x_j."""
+    D = o.padded_dim(x64.size)
+    s = o.rademacher(seed, client, D)
+    xp = np.zeros(D)
+    xp[:x64.size] = x64
+    sx = s * xp
+    n2 = float(np.dot(x64, x64))
+    j = np.arange(D, dtype=np.int64)
+    near = 0
+    for i in samples:
+        par = np.bitwise_and(j, int(i))
+        # parity of popcount(i & j) by folding
+        for sh in (32, 16, 8, 4, 2, 1):
+            par ^= par >> sh
+        row = 1.0 - 2.0 * (par & 1)
+        z = float(np.dot(row, sx)) / np.sqrt(n2)
+        want = int(o.quantize_indices(np.array([z]), thresholds)[0])
+        got = int(idx_gpu_at(int(i)))
+        if got != want:
+            assert abs(got - want) == 1 and abs(z - thresholds[min(got, want)]) <= parity.INDEX_BOUNDARY_TOL, (i, z, got, want)
+            near += 1
+    return near
+
+
+def test_three_pass_size():
+    """D = 2^25: wave-tile strided pass on bit 24, workgroup-tile strided pass on bits 14..23, lo14."""
+    from paper_2108_08842_amd import eden
+    d = (1 << 24) + 12345
+    w = synth.Workload("three_pass", 2, d, [256, 1024], 25, "normal_outliers")
+    print(f"three passes: n=2 d={d} D=2^25 budgets={w.b_q8} seed={w.seed}", flush=True)
+    xs = [synth.client_vector(w, c) for c in range(2)]
+    ctx = eden.Context(d_max=d, n_max=2, device=0)
+    msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], [5, 9], w.b_q8, w.seed)
+    assert ctx.last_device_status() == 0
+    stats = parity.EncodeParity()
+    om = [parity.to_oracle_message(m) for m in msgs]
+    parity.check_encode(xs[1], w.seed, 9, 1024, om[1], stats)        # one whole sender through the oracle (b = 4)
+    parity.finish_encode(stats)
+    print("encode:", stats, flush=True)
+    bm = [ctx.make_loss_bitmap(w.seed, cid, 1 << 25, int(0.1 * 2 ** 32)) for cid in (5, 9)]
+    acc = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs[1:], [9], [1024], d, w.seed, acc, bm[1:])
+    got = ctx.finalize_mean(acc, 1).cpu().numpy()
+    want = o.decode_mean([om[1]], d, [bm[1].cpu().numpy().view(np.uint32)])
+    err = parity.rel_l2(got, want)
+    print(f"decode with 10% loss: rel L2 {err:.2e}", flush=True)
+    assert err <= parity.MEAN_REL_L2
+    # b = 1 sender: sampled coordinates against rows of H computed one by one
+    bits1 = o.unpack_indices(om[0].payload, 1, 1 << 25)
+    rng = np.random.default_rng(3)
+    samples = rng.integers(0, 1 << 25, 6)
+    t1, _ = o.tables(1)
+    _sampled_rows_check(xs[0].astype(np.float64), w.seed, 5, lambda i: bits1[i], samples, t1)
+    assert ctx.last_device_status() == 0
+    ctx.close()
+
+
+@pytest.mark.timeout(600)
+def test_config5_full_size():
+    """n=8, d=2^27, b=4: three passes through memory.  One sender is checked coordinate by coordinate on sampled
+    rows of H (a whole float64 transform of 2^27 coordinates is too slow to run for every sender); the receiver
+    is checked through properties that hold at any size."""
+    from paper_2108_08842_amd import eden
+    w = synth.config(5)
+    n, d = w.n, w.d
+    print(f"config 5: n={n} d=2^27 b=4 seed={w.seed}", flush=True)
+    ctx = eden.Context(d_max=d, n_max=n, device=0)
+    x_dev = []
+    x0 = None
+    for c in range(n):
+        x = synth.client_vector(w, c)
+        if c == 0:
+            x0 = x
+        x_dev.append(torch.from_numpy(x).cuda())
+        del x
+    msgs = ctx.encode(x_dev, w.client_ids, w.b_q8, w.seed)
+    torch.cuda.synchronize()
+    assert ctx.last_device_status() == 0
+    m0 = parity.to_oracle_message(msgs[0])
+    x64 = x0.astype(np.float64)
+    n2 = float(np.dot(x64, x64))
+    assert m0.status == 0 and abs(m0.N2 - n2) <= 1e-12 * n2
+    t4, q4 = o.tables(4)
+    words = m0.payload
+    rng = np.random.default_rng(11)
+    samples = rng.integers(0, 1 << 27, 8)
+    near = _sampled_rows_check(x64, w.seed, w.client_ids[0], lambda i: (int(words[i >> 3]) >> (4 * (i & 7))) & 15, samples, t4)
+    print(f"sampled indices ok ({near} near a threshold)", flush=True)
+    # scale: <R(x),Q> = (|x|/sqrt(D)) sum_i z_i Q(z_i) -> |x| sqrt(D) E[Q^2], so S -> |x| / (sqrt(D) E[Q^2]) (Sec. 2.3, 2.4)
+    eq2 = o.expected_q2(t4, q4)
+    assert abs(m0.S * eq2 * np.sqrt(float(1 << 27) / n2) - 1.0) < 0.01, m0.S
+    # receiver: tangent property <x^, x> = |x|^2 (Sec. 2.3) for one sender, and linearity over the batch
+    acc = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs[:1], w.client_ids[:1], w.b_q8[:1], d, w.seed, acc)
+    dot = float(torch.dot(acc.double(), x_dev[0].double()))
+    assert abs(dot / n2 - 1.0) < 1e-5, dot / n2
+    vn = float(((acc.double() - x_dev[0].double()) ** 2).sum()) / n2
+    print(f"vNMSE of sender 0: {vn:.5f} (Lloyd-Max b=4: {1 / eq2 - 1:.5f})", flush=True)
+    assert abs(vn / (1 / eq2 - 1) - 1) < 0.05
+    acc8 = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs, w.client_ids, w.b_q8, d, w.seed, acc8)
+    half = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs[:3], w.client_ids[:3], w.b_q8[:3], d, w.seed, half)
+    ctx.decode_accumulate(msgs[3:], w.client_ids[3:], w.b_q8[3:], d, w.seed, half)
+    assert ((acc8 - half).norm() / acc8.norm()).item() < 1e-6
+    assert ctx.last_device_status() == 0
+    ctx.close()
