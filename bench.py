@@ -2,7 +2,7 @@
 """Throughput of the EDEN hot path on one MI355X.
 
 One step = encode of all n senders + decode_accumulate of all n messages + finalize_mean on one
-synthetic batch that is already resident in device memory.  Prints ONE JSON line (see README / DESIGN).
+synthetic batch that is already resident in device memory.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -57,7 +57,7 @@ def kernel_bytes(kind, senders, d, D, mean_bits, narrow):
 
 
 # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain 1 GiB
-# copy gives); see profiles/hbm_traffic_cfg4_bench.txt.  Keyed by (workload, kernel kind).
+# copy gives; the summary of those runs is kept with the other profiler summaries).  Keyed by (workload, kernel kind).
 MEASURED_TRAFFIC = {
     ("cfg4_n16_d11173962_b1", "enc_hi_first"): (682.3 + 1024.2) * 2 ** 20,
     ("cfg4_n16_d11173962_b1", "enc_lo"): (1024.2 + 32.1) * 2 ** 20,
