@@ -36,20 +36,19 @@ def model_bytes(n, d, D, budgets):
 
 def kernel_bytes(kind, senders, d, D, mean_bits, narrow):
     """Algorithmic bytes one launch of a kernel kind must move (what its role reads + what it writes).
-    `narrow`: the decode workspace of this workload is int16 (every sender has b <= 1 and 2^21 <= D <= 2^24)."""
+    `narrow`: the decode workspace of this workload is int16 (every sender has b <= 1 and 2^13 <= D <= 2^24)."""
     payload = D * mean_bits / 8.0
     ws = 2 * D if narrow else 4 * D                   # decode workspace bytes per sender
-    tiles = -(-d // (1 << 14)) * (1 << 14)            # the last decode pass only touches tiles below d
+    lo = 12 if D <= (1 << 18) else 14
+    tiles = min(D, -(-d // (1 << lo)) * (1 << lo))    # the last decode pass only touches tiles below d
     per_sender = {
         "enc_hi_first": 4 * d + 4 * D,       # x in, workspace out
         "hi_mid": 8 * D,                     # workspace in and out
         "enc_lo": 4 * D + payload,           # workspace in, packed indices out
-        "dec_lo": payload + 4 * D,           # packed indices in, workspace out
-        "dec_hi_last": 4 * D,                # workspace in (per sender) ...
         "dec_hi_first": payload + ws,        # packed indices in, workspace out
         "dec_lo_last": ws * tiles / D,       # workspace in (per sender) ...
     }
-    if kind in ("dec_hi_last", "dec_lo_last"):
+    if kind == "dec_lo_last":
         return senders * per_sender[kind] + 8 * d   # ... plus one read-modify-write of the accumulator
     if kind == "finalize_mean":
         return 8 * d
@@ -90,7 +89,7 @@ def main():
     D = 1 << (d - 1).bit_length()
     log2D = D.bit_length() - 1
     mean_bits = sum(w.b_q8) / len(w.b_q8) / 256.0
-    narrow = all(b <= 256 for b in w.b_q8) and 21 <= log2D <= 24
+    narrow = all(b <= 256 for b in w.b_q8) and 13 <= log2D <= 24
 
     xs_host = [synth.client_vector(w, c) for c in range(n)]
     xs = [torch.from_numpy(x).cuda() for x in xs_host]

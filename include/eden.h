@@ -162,16 +162,14 @@ typedef enum eden_kernel_kind {
     EDEN_K_HI_MID = 1,         /* middle strided pass, in place on the workspace */
     EDEN_K_ENC_LO = 2,         /* encode: contiguous pass + quantize + pack */
     EDEN_K_DEC_PREPARE = 3,    /* decode: per-message scalars */
-    EDEN_K_DEC_LO = 4,         /* decode: unpack + dequantize + contiguous pass */
-    EDEN_K_DEC_HI_LAST = 5,    /* decode: last strided pass + signs + sum over senders */
+    EDEN_K_DEC_HI_FIRST = 4,   /* decode: unpack + dequantize + first strided pass */
+    EDEN_K_DEC_LO_LAST = 5,    /* decode: contiguous pass + signs + sum over senders */
     EDEN_K_FINALIZE = 6,       /* division by n */
     EDEN_K_ENC_SMALL = 7,      /* encode, D <= 4096, one workgroup per sender */
     EDEN_K_DEC_SMALL = 8,      /* decode, D <= 4096 */
     EDEN_K_ENC_NORM = 9,       /* encode: |x|^2 from per-workgroup partials, scaled thresholds */
     EDEN_K_ENC_FINISH = 10,    /* encode: <R(x),Q>, S, header */
-    EDEN_K_DEC_HI_FIRST = 11,  /* decode: unpack + dequantize + strided pass (2^21 <= D <= 2^24) */
-    EDEN_K_DEC_LO_LAST = 12,   /* decode: contiguous pass + signs + sum over senders (2^21 <= D <= 2^24) */
-    EDEN_K_COUNT = 13
+    EDEN_K_COUNT = 11
 } eden_kernel_kind;
 int eden_profile_enable(eden_ctx *ctx, uint32_t kind_mask, uint32_t max_records);
 int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, float *ms, uint32_t cap,

@@ -276,40 +276,28 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);
             launch_dec_small(B, nb, d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
         } else {
-            // plan "one workgroup-tile strided pass + lo14": decode runs strided-first / contiguous-last, and
-            // senders with b <= 1 use an int16 workspace
-            const int narrow = (pl.lo_bits == 14 && pl.nhi == 1 && pl.hi[0].wg) ? 1 : 0;
+            // Strided passes first (every sender on its own), contiguous pass last (sums the senders in registers
+            // and touches acc once).  With a single strided pass the workspace of a b <= 1 sender holds int16.
+            const int narrow = (pl.nhi == 1) ? 1 : 0;
             {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
                 launch_dec_prepare(B, nb, d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
             }
-            if (narrow) {
-                // strided pass first (independent per sender), contiguous pass last (sums the senders)
-                {
+            for (int i = pl.nhi - 1; i >= 0; --i) {
+                const HiPass &h = pl.hi[i];
+                if (i == pl.nhi - 1) {
                     Timed t(ctx, EDEN_K_DEC_HI_FIRST, nb, st);
-                    launch_dec_hix_first(pl.hi[0].M, B, nb, log2D, seed, ctx->dec_scratch, 1, ctx->T, st);
-                }
-                Timed t(ctx, EDEN_K_DEC_LO_LAST, nb, st);
-                launch_dec_lo14_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, 1, acc_dev, st);
-            } else {
-                {
-                    Timed t(ctx, EDEN_K_DEC_LO, nb, st);
-                    if (pl.lo_bits == 14) launch_dec_lo14(B, nb, log2D, seed, ctx->dec_scratch, 0, ctx->T, st);
-                    else launch_dec_lo(B, nb, log2D, seed, ctx->dec_scratch, ctx->T, st);
-                }
-                for (int i = 0; i < pl.nhi; ++i) {
-                    const HiPass &h = pl.hi[i];
-                    if (i < pl.nhi - 1) {
-                        Timed t(ctx, EDEN_K_HI_MID, nb, st);
-                        if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
-                        else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
-                    } else {
-                        Timed t(ctx, EDEN_K_DEC_HI_LAST, nb, st);
-                        if (h.wg) launch_hix_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, ctx->dec_scratch, 0, acc_dev, st);
-                        else launch_dec_hi_last(h.M, B, nb, d, log2D, h.p, seed, ctx->T, acc_dev, st);
-                    }
+                    if (h.wg) launch_dec_hix_first(h.M, B, nb, log2D, seed, ctx->dec_scratch, narrow, ctx->T, st);
+                    else launch_dec_hi_first(h.M, B, nb, log2D, h.p, seed, ctx->dec_scratch, narrow, ctx->T, st);
+                } else {
+                    Timed t(ctx, EDEN_K_HI_MID, nb, st);
+                    if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
+                    else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
                 }
             }
+            Timed t(ctx, EDEN_K_DEC_LO_LAST, nb, st);
+            if (pl.lo_bits == 14) launch_dec_lo14_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
+            else launch_dec_lo_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
     }
@@ -424,9 +412,9 @@ int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, floa
 }
 
 const char *eden_kernel_name(uint32_t kind) {
-    static const char *names[EDEN_K_COUNT] = {"enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_lo",
-                                              "dec_hi_last", "finalize_mean", "enc_small", "dec_small",
-                                              "enc_norm", "enc_finish", "dec_hi_first", "dec_lo_last"};
+    static const char *names[EDEN_K_COUNT] = {"enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_hi_first",
+                                              "dec_lo_last", "finalize_mean", "enc_small", "dec_small",
+                                              "enc_norm", "enc_finish"};
     return kind < EDEN_K_COUNT ? names[kind] : "?";
 }
 

@@ -103,6 +103,13 @@ __device__ inline float negate_where(float v, uint64_t mask) {
     return r;
 }
 
+// v or 0 per lane, chosen by bit `lane` of a wave-uniform mask
+__device__ inline float keep_where(float v, uint64_t mask) {
+    float r;
+    asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(v), "s"(mask));
+    return r;
+}
+
 // The 64-bit value held by lane `src` (compile-time constant), as a wave-uniform scalar.
 __device__ inline uint64_t wave_read64(uint64_t v, int src) {
     const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, src);

@@ -17,14 +17,14 @@ void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uin
                        uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip, uint32_t partial_stride,
                        uint32_t *dev_status, hipStream_t st);
 void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
-void launch_dec_hi_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed,
-                        const float *T, float *acc, hipStream_t st);
+void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, int log2D, int p, uint64_t seed, const DecScratch *scratch,
+                         int narrow, float *T, hipStream_t st);
 uint32_t launch_enc_lo(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
                        uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st);
-void launch_dec_lo(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, float *T,
-                   hipStream_t st);
+void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+                        const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st);
 void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                       uint32_t *dev_status, hipStream_t st);
@@ -37,16 +37,12 @@ void launch_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t 
 uint32_t launch_hix_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
                           double *partials, uint32_t partial_stride, hipStream_t st);
 void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
-void launch_hix_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, const float *T,
-                     const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
 void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch,
                           int narrow, float *T, hipStream_t st);
 void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
                           const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
 uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
                          uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
-void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, int narrow,
-                     float *T, hipStream_t st);
 
 }  // namespace eden
 #endif

@@ -116,39 +116,78 @@ __global__ __launch_bounds__(256) void k_hi_mid(float *T, int log2D, int p) {
     for (int r = 0; r < R; ++r) buf_store(rt, lane_off, base_off + ((uint32_t)r << (p + 2)), v[r]);
 }
 
-// Decode, last pass: for every sender of the batch finish H, apply its sign diagonal (R^-1 = s o D^-1/2 H,
-// Sec. 2.2.2; D^-1/2 is already inside the dequantization scale) and add; then acc += sum (i < d).
+// Decode, first pass in wave tiles (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit
+// pattern +-1 when the workspace of a b <= 1 sender is int16), zero for coordinates that were not sampled or
+// whose packet was lost, then index bits p .. p+M-1 of H.  Every (tile, sender) pair is independent.
 template <int M>
-__global__ __launch_bounds__(256) void k_dec_hi_last(DecBatch B, uint32_t n, uint64_t d, int log2D, int p,
-                                                     uint64_t seed, const float *T, float *acc) {
+__global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, int log2D, int p, uint64_t seed,
+                                                      const DecScratch *scratch, int narrow, float *T) {
     constexpr int R = 1 << M;
-    const uint32_t lane = lane_id();
-    const uint32_t tile = blockIdx.x * 4u + wave_in_block();
+    __shared__ float table[4][16];
+    const uint32_t c = blockIdx.y;
+    const uint32_t lane = lane_id(), wv = wave_in_block();
+    const uint32_t tile = blockIdx.x * 4u + wv;
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     if (tile >= ntiles) return;
     uint64_t base;
     hi_tile_origin<M>(tile, p, base);
-    if (base >= d) return;                                   // whole tile lies in the padding (rows only go up)
-    float sum[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) sum[r] = 0.0f;
-    const uint32_t lane_off = lane * 4u, base_off = (uint32_t)base * 4u;
-    for (uint32_t c = 0; c < n; ++c) {
-        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
-        float v[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) v[r] = buf_load(rt, lane_off, base_off + ((uint32_t)r << (p + 2)));
-        fwht_regs<R>(v);
-        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
-        const uint64_t my_word = hash_word(key, (base + ((uint64_t)(lane & (R - 1)) << p)) >> 6);
-#pragma unroll
-        for (int r = 0; r < R; ++r) sum[r] += negate_where(v[r], wave_read64(my_word, r));
+    const uint32_t b_q8 = B.b_q8[c];
+    const bool i16 = narrow && b_q8 <= 256u;
+    if (lane < 16) table[wv][lane] = (i16 && lane == 1) ? 1.0f : scratch[c].deq[lane];
+    wave_lds_sync();
+    const float *tb = table[wv];
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    int bits, k;
+    budget_of(b_q8, bits, k);
+    const uint32_t payload_bytes = (uint32_t)(((((1ull << log2D) >> (k == 2)) * (uint32_t)bits + 63) >> 6) << 3);
+    const uint64_t my_row = base + ((uint64_t)(lane & (R - 1)) << p);       // lane r looks after row r
+    uint64_t recv = ~0ull;                                       // bit r: the packet of row r arrived
+    if (const uint32_t *bm = B.bitmap[c]) {
+        const uint32_t pk = (uint32_t)(my_row >> 10);
+        recv = __ballot((bm[pk >> 5] >> (pk & 31u)) & 1u);
     }
-    const rsrc_t ra = make_rsrc(acc, (uint32_t)(d * 4));                 // coordinates past d are dropped
+    float v[R];
+    if (b_q8 == 128) {
+        // b = 1/2: pair j = i >> 1 carries one bit; coordinate i was sent iff (i & 1) equals the pair's offset bit
+        const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+        const uint32_t offs_mine = (uint32_t)(hash_word(key, my_row >> 7) >> (32u * (uint32_t)((base >> 6) & 1u)));
+        const rsrc_t rp = make_rsrc(payload + (base >> 6), payload_bytes - (uint32_t)(base >> 6) * 4u);
+        const uint32_t mag = __float_as_uint(tb[1]);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint32_t off = base_off + ((uint32_t)r << (p + 2));
-        buf_store_keep(ra, lane_off, off, buf_load_keep(ra, lane_off, off) + sum[r]);
+        for (int r = 0; r < R; ++r) {
+            const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, 0, (int)(((uint32_t)r << (p - 6)) * 4u), 0);
+            const uint32_t offs = __builtin_amdgcn_readlane(offs_mine, r);
+            const bool kept = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
+            const uint32_t neg = (~(w >> (lane >> 1)) & 1u) << 31;          // index 0 = negative
+            v[r] = kept ? __uint_as_float(mag | neg) : 0.0f;
+        }
+    } else {
+        const uint32_t lbits = lane * (uint32_t)bits;
+        const rsrc_t rp = make_rsrc(payload + ((base * (uint32_t)bits) >> 5), payload_bytes - (uint32_t)((base * (uint32_t)bits) >> 5) * 4u);
+        const uint32_t voff = (lbits >> 5) * 4u, shift = lbits & 31u;
+        const uint32_t mag = __float_as_uint(tb[1]);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)r * (uint32_t)bits) << (p - 5)) * 4u), 0);
+            const uint32_t idx = (w >> shift) & ((1u << bits) - 1u);
+            v[r] = (bits == 1) ? __uint_as_float(mag | ((~idx & 1u) << 31)) : tb[idx];
+        }
+    }
+    if (B.bitmap[c]) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] = ((recv >> r) & 1ull) ? v[r] : 0.0f;     // wave-uniform per row
+    }
+    fwht_regs<R>(v);
+    if (i16) {                                                   // exact integers of magnitude <= 2^M
+        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 2u << log2D);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            __builtin_amdgcn_raw_buffer_store_b16((short)(int)v[r], rt, (int)(lane * 2u),
+                                                  (int)(((uint32_t)base + ((uint32_t)r << p)) * 2u), kStream);
+    } else {
+        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
+#pragma unroll
+        for (int r = 0; r < R; ++r) buf_store(rt, lane * 4u, ((uint32_t)base + ((uint32_t)r << p)) * 4u, v[r]);
     }
 }
 
@@ -365,82 +404,66 @@ __global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t d, int 
     dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, log2D, seed, tab, &scratch[c], dev_status);
 }
 
-// lo pass, decode side: payload -> T.  Unpack, centroid lookup times S/(p sqrt D), zero for coordinates that
-// were not sampled or whose packet was lost (Sec. 4.2), then index bits 0..11 of H.
-__global__ __launch_bounds__(128) void k_dec_lo(DecBatch B, int log2D, uint64_t seed, const DecScratch *scratch,
-                                                float *T) {
+// Decode, last pass in wave tiles: index bits 0..11 of H for every sender, that sender's sign diagonal
+// (R^-1 = s o D^-1/2 H, Sec. 2.2.2; D^-1/2 is inside the dequantization scale), sum over senders in registers,
+// one contiguous read-modify-write of acc.  A lane ends with 64 consecutive coordinates = one sign word.
+__global__ __launch_bounds__(128) void k_dec_lo_last(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+                                                     const float *T, const DecScratch *scratch, int narrow, float *acc) {
     __shared__ float lds[2][64 * kLdsRow];
-    __shared__ float table[2][16];
-    const uint32_t c = blockIdx.y;
-    const uint32_t lane = lane_id();
-    const uint32_t wv = wave_in_block();
+    const uint32_t lane = lane_id(), wv = wave_in_block();
     const uint32_t tile = blockIdx.x * 2u + wv;
-    const size_t seg = (size_t)tile * 64 + lane;               // this lane decodes coordinates [64 seg, 64 seg + 64)
-    const uint32_t b_q8 = B.b_q8[c];
-    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const DecScratch *s = &scratch[c];
-
-    bool here = true;                                          // did this lane's packet arrive?
-    if (const uint32_t *bm = B.bitmap[c]) {
-        const uint32_t pk = (uint32_t)((seg * 64) >> 10);
-        here = (bm[pk >> 5] >> (pk & 31u)) & 1u;
+    const uint64_t tile_base = (uint64_t)tile << kLoBits;
+    if (tile_base >= d) return;                                  // whole tile in the padding (no block-wide barrier below)
+    const uint64_t first = tile_base + 64u * lane;               // this lane's 64 coordinates after the transpose
+    float *L = lds[wv];
+    float sum[64];
+#pragma unroll
+    for (int k = 0; k < 64; ++k) sum[k] = 0.0f;
+    for (uint32_t c = 0; c < n; ++c) {
+        const bool i16 = narrow && B.b_q8[c] <= 256u;
+        float v[64];
+        if (i16) {
+            const short *t16 = reinterpret_cast<const short *>(T + ((size_t)c << log2D)) + tile_base + lane;
+#pragma unroll
+            for (int j = 0; j < 64; ++j) v[j] = (float)(int)__builtin_nontemporal_load(t16 + 64 * j);
+        } else {
+            const float *t32 = T + ((size_t)c << log2D) + tile_base + lane;
+#pragma unroll
+            for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(t32 + 64 * j);
+        }
+        fwht_regs<64>(v);                                        // index bits 6..11
+#pragma unroll
+        for (int j = 0; j < 64; ++j) L[j * kLdsRow + lane] = v[j];
+        wave_lds_sync();
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const float4 t = *reinterpret_cast<const float4 *>(&L[lane * kLdsRow + 4 * q]);
+            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+        }
+        wave_lds_sync();                                         // the next sender overwrites the rows
+        fwht_regs<64>(v);                                        // index bits 0..5
+        const uint32_t scale = __float_as_uint(i16 ? scratch[c].deq[1] : 1.0f) & 0x7FFFFFFFu;   // > 0; x*1+s is exact
+        const uint64_t word = hash_word(stream_key(seed, kStreamSign, B.client[c]), first >> 6);
+        const uint32_t wlo = (uint32_t)word, whi = (uint32_t)(word >> 32);
+#pragma unroll
+        for (int k = 0; k < 32; ++k)
+            sum[k] = fmaf(v[k], __uint_as_float(scale | ((wlo << (31 - k)) & 0x80000000u)), sum[k]);   // bit 1 -> s_i = -1
+#pragma unroll
+        for (int k = 0; k < 32; ++k)
+            sum[32 + k] = fmaf(v[32 + k], __uint_as_float(scale | ((whi << (31 - k)) & 0x80000000u)), sum[32 + k]);
     }
-    float v[64];
-    if (b_q8 == 256) {
-        const uint2 w = *reinterpret_cast<const uint2 *>(payload + seg * 2);
-        const uint32_t mag = here ? __float_as_uint(s->deq[1]) : 0u;       // +a, or 0 for a lost packet
-        const uint32_t n0 = ~w.x, n1 = ~w.y;                               // bit set = index 0 = negative
+    if (first + 64 <= d) {
 #pragma unroll
-        for (int k = 0; k < 32; ++k) v[k] = __uint_as_float(mag | ((n0 << (31 - k)) & 0x80000000u));
-#pragma unroll
-        for (int k = 0; k < 32; ++k) v[32 + k] = __uint_as_float(mag | ((n1 << (31 - k)) & 0x80000000u));
-    } else if (b_q8 == 128) {
-        const uint32_t w = payload[seg];
-        const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
-        const uint64_t hw = hash_word(key, seg >> 1);
-        const uint32_t off = (uint32_t)(hw >> ((seg & 1) * 32));
-        const uint32_t mag = here ? __float_as_uint(s->deq[1]) : 0u;
-        const uint32_t nw = ~w;
-#pragma unroll
-        for (int g = 0; g < 32; ++g) {
-            const float val = __uint_as_float(mag | ((nw << (31 - g)) & 0x80000000u));
-            const bool odd = (off >> g) & 1u;
-            v[2 * g] = odd ? 0.0f : val;
-            v[2 * g + 1] = odd ? val : 0.0f;
+        for (int q = 0; q < 16; ++q) {
+            float4 a = *reinterpret_cast<const float4 *>(acc + first + 4 * q);
+            a.x += sum[4 * q]; a.y += sum[4 * q + 1]; a.z += sum[4 * q + 2]; a.w += sum[4 * q + 3];
+            *reinterpret_cast<float4 *>(acc + first + 4 * q) = a;
         }
     } else {
-        if (lane < 16) table[wv][lane] = s->deq[lane];
-        wave_lds_sync();
-        const float *tb = table[wv];
-        if (b_q8 == 512) {
-            const uint4 w4 = *reinterpret_cast<const uint4 *>(payload + seg * 4);
-            const uint32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
 #pragma unroll
-            for (int k = 0; k < 64; ++k) v[k] = tb[(w[k / 16] >> ((k % 16) * 2)) & 3u];
-        } else {
-            const uint4 *p4 = reinterpret_cast<const uint4 *>(payload + seg * 8);
-            const uint4 a = p4[0], b = p4[1];
-            const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-            for (int k = 0; k < 64; ++k) v[k] = tb[(w[k / 8] >> ((k % 8) * 4)) & 15u];
-        }
-        if (!here) {
-#pragma unroll
-            for (int k = 0; k < 64; ++k) v[k] = 0.0f;
-        }
+        for (int k = 0; k < 64; ++k)
+            if (first + k < d) acc[first + k] += sum[k];
     }
-    fwht_regs<64>(v);                                          // index bits 0..5
-    float *L = lds[wv];
-#pragma unroll
-    for (int q = 0; q < 16; ++q)
-        *reinterpret_cast<float4 *>(&L[lane * kLdsRow + 4 * q]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-    wave_lds_sync();
-#pragma unroll
-    for (int j = 0; j < 64; ++j) v[j] = L[j * kLdsRow + lane];
-    fwht_regs<64>(v);                                          // index bits 6..11
-    float *Tc = T + ((size_t)c << log2D) + ((size_t)tile << kLoBits);
-#pragma unroll
-    for (int j = 0; j < 64; ++j) Tc[64 * j + lane] = v[j];
 }
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -649,11 +672,11 @@ void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st
     dim3 grid((ntiles + 3) / 4, n);
     EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_hi_mid<MM>, grid, dim3(256), 0, st, T, log2D, p));
 }
-void launch_dec_hi_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, const float *T,
-                        float *acc, hipStream_t st) {
+void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, int log2D, int p, uint64_t seed, const DecScratch *scratch,
+                         int narrow, float *T, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
-    dim3 grid((ntiles + 3) / 4);
-    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_last<MM>, grid, dim3(256), 0, st, B, n, d, log2D, p, seed, T, acc));
+    dim3 grid((ntiles + 3) / 4, n);
+    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_first<MM>, grid, dim3(256), 0, st, B, log2D, p, seed, scratch, narrow, T));
 }
 uint32_t launch_enc_lo(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
                        uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
@@ -665,10 +688,10 @@ void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, ui
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st) {
     hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, d, log2D, seed, tab, scratch, dev_status);
 }
-void launch_dec_lo(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, float *T,
-                   hipStream_t st) {
-    dim3 grid(1u << (log2D - kLoBits - 1), n);
-    hipLaunchKernelGGL(k_dec_lo, grid, dim3(128), 0, st, B, log2D, seed, scratch, T);
+void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+                        const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
+    dim3 grid(1u << (log2D - kLoBits - 1));
+    hipLaunchKernelGGL(k_dec_lo_last, grid, dim3(128), 0, st, B, n, d, log2D, seed, T, scratch, narrow, acc);
 }
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st) {
     const int vec = ((reinterpret_cast<uintptr_t>(acc) | reinterpret_cast<uintptr_t>(mean)) & 15u) == 0;

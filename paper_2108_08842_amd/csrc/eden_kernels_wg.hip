@@ -199,236 +199,10 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D
     }
 }
 
-// Decode, last pass (Sec. 2.2.2): finish H for every sender of the batch, apply that sender's sign diagonal,
-// add; acc is read and written once.  The next sender's tile is loaded while the current one is transformed
-// (one workgroup owns the CU here, so nothing else would hide the load latency).
-//
-// `narrow`: senders with b <= 1 had their workspace written as int16 by the contiguous pass.  Their
-// dequantized rotated vector is (+-a or 0) per coordinate, so the partial transform is a times an integer of
-// magnitude <= 2^14: storing the integer is exact and halves the traffic; a is applied at the very end.
-template <int M>
-struct HiXLoader {
-    using X = HiX<M>;
-    const float *T;
-    int log2D;
-    uint32_t base_off, off1;      // byte offsets (fp32 units) of the tile and of this thread's first element
-    __device__ inline void load(uint32_t c, bool i16, uint32_t (&raw)[64]) const {
-        constexpr int p = kHixP;
-        // the tile's origin goes into the descriptor so that every row offset is a compile-time constant
-        const char *slot = reinterpret_cast<const char *>(T + ((size_t)c << log2D));
-        if (i16) {
-            const rsrc_t rt = make_rsrc(slot + (base_off >> 1), (2u << log2D) - (base_off >> 1));
-#pragma unroll
-            for (int r = 0; r < 64; ++r)
-                raw[r] = (uint32_t)(int)(short)__builtin_amdgcn_raw_buffer_load_b16(
-                    rt, (int)(off1 >> 1), (int)((((uint32_t)X::RL * r) << (p + 2)) >> 1), kStream);
-        } else {
-            const rsrc_t rt = make_rsrc(slot + base_off, (4u << log2D) - base_off);
-#pragma unroll
-            for (int r = 0; r < 64; ++r)
-                raw[r] = __builtin_amdgcn_raw_buffer_load_b32(rt, (int)off1, (int)(((uint32_t)X::RL * r) << (p + 2)), kStream);
-        }
-    }
-};
-
-template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_last(DecBatch B, uint32_t n, uint64_t d, int log2D, int p_arg,
-                                                               uint64_t seed, const float *T, const DecScratch *scratch,
-                                                               int narrow, float *acc) {
-    using X = HiX<M>;
-    __shared__ float lds[X::LDS_FLOATS];
-    constexpr int p = kHixP;
-    (void)p_arg;
-    const uint64_t base = hix_base<M>(blockIdx.x, p);
-    if (base >= d) return;                                       // the whole tile lies in the padding
-    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
-    const uint32_t g0 = 2u * wave_in_block();
-    float sum[64];
-#pragma unroll
-    for (int i = 0; i < 64; ++i) sum[i] = 0.0f;
-    // lane l <-> (half, register) = (l / RP, l % RP): the rows whose sign bits this lane hashes
-    const uint64_t rowa = (uint64_t)hix_row2<M>(g0, (int)(lane / X::RP), (int)(lane % X::RP)) << p;
-    const uint64_t rowb = (uint64_t)hix_row2<M>(g0 + 1, (int)(lane / X::RP), (int)(lane % X::RP)) << p;
-    const uint32_t base_off = (uint32_t)base * 4u;
-    const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;
-    const HiXLoader<M> loader{T, log2D, base_off, ((g << p) + col) * 4u};
-
-    auto is_narrow = [&](uint32_t c) { return narrow && B.b_q8[c] <= 256u; };
-    auto process = [&](uint32_t c, uint32_t (&raw)[64]) {
-        const bool i16 = is_narrow(c);
-        const float scale = i16 ? scratch[c].deq[1] : 1.0f;      // x * 1 + s is exact: same result as a plain add
-        float v[64];
-#pragma unroll
-        for (int r = 0; r < 64; ++r) v[r] = i16 ? (float)(int)raw[r] : __uint_as_float(raw[r]);
-        fwht_regs<64>(v);
-        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
-        const uint32_t wa = sign_half_word(key, base + rowa);
-        const uint32_t wb = sign_half_word(key, base + rowb);
-        float out[X::RP];
-        hix_exchange<M, 0>(v, lds, out);
-#pragma unroll
-        for (int s = 0; s < X::RP; ++s) sum[s] = fmaf(negate_where(out[s], pair_mask(wa, wb, s)), scale, sum[s]);
-        if constexpr (X::PH == 2) {
-            hix_exchange<M, 1>(v, lds, out);
-#pragma unroll
-            for (int s = 0; s < X::RP; ++s)
-                sum[X::RP + s] = fmaf(negate_where(out[s], pair_mask(wa, wb, X::RP + s)), scale, sum[X::RP + s]);
-        }
-    };
-
-    uint32_t ra_[64], rb_[64];
-    loader.load(0, is_narrow(0), ra_);
-    for (uint32_t c = 0; c < n; c += 2) {
-        if (c + 1 < n) loader.load(c + 1, is_narrow(c + 1), rb_);
-        process(c, ra_);
-        if (c + 1 < n) {
-            if (c + 2 < n) loader.load(c + 2, is_narrow(c + 2), ra_);
-            process(c + 1, rb_);
-        }
-    }
-    const rsrc_t ra = make_rsrc(acc, (uint32_t)(d * 4));                 // coordinates past d are dropped
-#pragma unroll
-    for (int ph = 0; ph < X::PH; ++ph) {
-#pragma unroll
-        for (int s = 0; s < X::RP; ++s) {
-            const uint32_t off = base_off + (hix_row2<M>(0, ph, s) << (p + 2));
-            buf_store_keep(ra, off2, off, buf_load_keep(ra, off2, off) + sum[ph * X::RP + s]);
-        }
-    }
-}
-
 // ------------------------------------------------------------------------------------------------
-// lo14
-constexpr int kLo14Bits = 14;
-constexpr int kLo14Lds = 4 * 64 * kLdsRow;       // floats
-
-// Decode-side 14-bit contiguous pass in four waves of 4096 coordinates (used when the contiguous pass comes
-// first in decode).  Thread t handles, for each of the four 4096-regions r, the 16 consecutive coordinates
-// tile*2^14 + r*4096 + 64*(t >> 2) + 16*(t & 3) + kk: unpacked values in, transformed tile out.
-// The mirror image for decode: u (same layout as above, not yet transformed) -> T.
-template <bool NARROW>
-__device__ inline void lo14_backward(float (&u)[4][16], float *lds, float *Tt) {
-    const uint32_t lane = lane_id(), wv = wave_in_block();
-#pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {
-        const float a = u[0][kk] + u[1][kk], b = u[0][kk] - u[1][kk];
-        const float c = u[2][kk] + u[3][kk], e = u[2][kk] - u[3][kk];
-        u[0][kk] = a + c; u[1][kk] = b + e; u[2][kk] = a - c; u[3][kk] = b - e;
-    }
-    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<float4 *>(&lds[(r * 64 + src) * kLdsRow + 16 * kq + 4 * i]) =
-                make_float4(u[r][4 * i], u[r][4 * i + 1], u[r][4 * i + 2], u[r][4 * i + 3]);
-    }
-    __syncthreads();
-    float *L = lds + wv * (64 * kLdsRow);
-    float v[64];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        const float4 t = *reinterpret_cast<const float4 *>(&L[lane * kLdsRow + 4 * q]);
-        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
-    }
-    fwht_regs<64>(v);                                            // bits 0..5
-    wave_lds_sync();
-#pragma unroll
-    for (int q = 0; q < 16; ++q)
-        *reinterpret_cast<float4 *>(&L[lane * kLdsRow + 4 * q]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-    wave_lds_sync();
-#pragma unroll
-    for (int j = 0; j < 64; ++j) v[j] = L[j * kLdsRow + lane];
-    fwht_regs<64>(v);                                            // bits 6..11
-    if constexpr (NARROW) {                                      // exact small integers: store as int16
-        short *T16 = reinterpret_cast<short *>(Tt);
-#pragma unroll
-        for (int j = 0; j < 64; ++j) T16[wv * 4096u + 64 * j + lane] = (short)(int)v[j];
-    } else {
-#pragma unroll
-        for (int j = 0; j < 64; ++j) Tt[wv * 4096u + 64 * j + lane] = v[j];
-    }
-}
-
-
-// `narrow` != 0: for senders with b <= 1 the unit pattern (+-1 or 0) is transformed and the exact integers are
-// stored as int16 at the same element index (the consumer multiplies by the sender's magnitude at the end).
-__global__ __launch_bounds__(256) void k_dec_lo14(DecBatch B, int log2D, uint64_t seed, const DecScratch *scratch,
-                                                  int narrow, float *T) {
-    __shared__ __attribute__((aligned(16))) float lds[kLo14Lds];
-    __shared__ float table[16];
-    const uint32_t c = blockIdx.y;
-    const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
-    const uint32_t b_q8 = B.b_q8[c];
-    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const DecScratch *s = &scratch[c];
-    const uint32_t *bm = B.bitmap[c];
-    const uint32_t src = threadIdx.x >> 2, kq = threadIdx.x & 3u;
-    const bool i16 = narrow && b_q8 <= 256u;
-    if (threadIdx.x < 16) table[threadIdx.x] = (i16 && threadIdx.x == 1) ? 1.0f : s->deq[threadIdx.x];
-    __syncthreads();
-    float u[4][16];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const uint64_t run = tile_base + (uint64_t)r * 4096u + 64u * src;
-        const uint64_t first = run + 16u * kq;
-        bool here = true;                                        // Sec. 4.2: a lost packet's coordinates are zero
-        if (bm) {
-            const uint32_t pk = (uint32_t)(first >> 10);
-            here = (bm[pk >> 5] >> (pk & 31u)) & 1u;
-        }
-        if (b_q8 == 256) {
-            const uint32_t w = payload[(run >> 5) + (kq >> 1)] >> (16u * (kq & 1u));
-            const uint32_t mag = here ? __float_as_uint(table[1]) : 0u;
-            const uint32_t neg = ~w;
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk) u[r][kk] = __uint_as_float(mag | ((neg << (31 - kk)) & 0x80000000u));
-        } else if (b_q8 == 128) {
-            const uint32_t w = payload[run >> 6] >> (8u * kq);
-            const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
-            const uint64_t hw = hash_word(key, run >> 7);
-            const uint32_t off = (uint32_t)(hw >> (((run >> 6) & 1ull) * 32 + 8 * kq));
-            const uint32_t mag = here ? __float_as_uint(table[1]) : 0u;
-            const uint32_t neg = ~w;
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                const float val = __uint_as_float(mag | ((neg << (31 - g)) & 0x80000000u));
-                const bool odd = (off >> g) & 1u;
-                u[r][2 * g] = odd ? 0.0f : val;
-                u[r][2 * g + 1] = odd ? val : 0.0f;
-            }
-        } else if (b_q8 == 512) {
-            const uint32_t w = payload[first >> 4];
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk) u[r][kk] = here ? table[(w >> (2 * kk)) & 3u] : 0.0f;
-        } else {
-            const uint2 w2 = *reinterpret_cast<const uint2 *>(payload + (first >> 3));
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) u[r][kk] = here ? table[(w2.x >> (4 * kk)) & 15u] : 0.0f;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) u[r][8 + kk] = here ? table[(w2.y >> (4 * kk)) & 15u] : 0.0f;
-        }
-    }
-    if (i16) {
-        // tile_base counts elements; the int16 copy of element i sits at byte 2 i of the sender's slot
-        lo14_backward<true>(u, lds, reinterpret_cast<float *>(reinterpret_cast<short *>(T + ((size_t)c << log2D)) + tile_base));
-    } else {
-        lo14_backward<false>(u, lds, T + ((size_t)c << log2D) + tile_base);
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
-// Decode in the order "strided pass first, contiguous pass last" (used when the plan is one workgroup-tile
-// strided pass on top of lo14).  The first pass has no dependency between senders, so every (tile, sender)
-// pair is its own workgroup; the last pass sums the senders in registers and touches acc once, with fully
-// contiguous accesses.
-
-// v or 0 per lane, chosen by bit `lane` of a wave-uniform mask
-__device__ inline float keep_where(float v, uint64_t mask) {
-    float r;
-    asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(v), "s"(mask));
-    return r;
-}
+// Decode runs the strided passes first and the contiguous pass last.  The first pass has no dependency
+// between senders, so every (tile, sender) pair is its own workgroup; the last pass sums the senders in
+// registers and touches acc once, with fully contiguous accesses.
 
 // First decode pass (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit pattern when the
 // workspace is int16), zero for coordinates that were not sampled or whose packet was lost, then index bits
@@ -688,12 +462,6 @@ void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t s
     dim3 grid(hix_tiles(M, log2D), n);
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_mid<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D, p));
 }
-void launch_hix_last(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, const float *T,
-                     const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
-    dim3 grid(hix_tiles(M, log2D));
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_last<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, n, d, log2D, p, seed, T,
-                                          scratch, narrow, acc));
-}
 void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch,
                           int narrow, float *T, hipStream_t st) {
     bool all_unit = narrow != 0;                                 // every sender b <= 1: packed int16 kernel
@@ -707,10 +475,4 @@ void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint6
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, log2D, seed, scratch,
                                           narrow, T));
 }
-void launch_dec_lo14(const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch, int narrow,
-                     float *T, hipStream_t st) {
-    dim3 grid(1u << (log2D - kLo14Bits), n);
-    hipLaunchKernelGGL(k_dec_lo14, grid, dim3(256), 0, st, B, log2D, seed, scratch, narrow, T);
-}
-
 }  // namespace eden

@@ -105,7 +105,7 @@ def test_workgroup_tile_sizes(ctx, d, budgets):
     _run_case(ctx, xs, [11, 12], w.b_q8, w.seed, drop_q32=int(0.05 * 2 ** 32), also_oracle_msgs=(d == 1 << 21))
 
 
-@pytest.mark.parametrize("d", [5000, 70_000])
+@pytest.mark.parametrize("d", [5000, 70_000, 300_000])
 def test_packet_loss_and_mixed_budgets(ctx, d):
     w = synth.Workload("t", 6, d, [128, 256, 512, 1024, 256, 128], 300 + d % 1000, "lognormal")
     xs = [synth.client_vector(w, c) for c in range(6)]
