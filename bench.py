@@ -36,20 +36,27 @@ def model_bytes(n, d, D, budgets):
 
 def kernel_bytes(kind, senders, d, D, mean_bits, narrow):
     """Algorithmic bytes one launch of a kernel kind must move (what its role reads + what it writes).
+    The contiguous pass works on whole tiles of 2^12 (D <= 2^18) or 2^14 coordinates and only touches the tiles
+    that hold part of the first d coordinates; the strided passes read / write the rest as implicit zeros.
     `narrow`: the decode workspace of this workload is int16 (every sender has b <= 1 and 2^13 <= D <= 2^24)."""
+    log2D = D.bit_length() - 1
+    lo = 12 if log2D <= 18 else 14
+
+    def ru(bits):                                     # d rounded up to whole tiles of 2^bits, at most D
+        return min(D, -(-d >> bits) << bits)
+
     payload = D * mean_bits / 8.0
-    ws = 2 * D if narrow else 4 * D                   # decode workspace bytes per sender
-    lo = 12 if D <= (1 << 18) else 14
-    tiles = min(D, -(-d // (1 << lo)) * (1 << lo))    # the last decode pass only touches tiles below d
+    ws = 2 if narrow else 4                           # decode workspace bytes per element
+    top = ru(lo) if log2D <= 24 else ru(24)           # what the pass next to the payload reads (encode) / writes (decode)
     per_sender = {
-        "enc_hi_first": 4 * d + 4 * D,       # x in, workspace out
-        "hi_mid": 8 * D,                     # workspace in and out
-        "enc_lo": 4 * D + payload,           # workspace in, packed indices out
-        "dec_hi_first": payload + ws,        # packed indices in, workspace out
-        "dec_lo_last": ws * tiles / D,       # workspace in (per sender) ...
+        "enc_first": 4 * d + 4 * ru(lo),              # x in, workspace out
+        "mid": 4 * ru(14) + 4 * ru(24),               # workspace in and out (three-pass sizes)
+        "enc_last": 4 * top + payload,                # workspace in, packed indices out
+        "dec_first": payload + ws * top,              # packed indices in, workspace out
+        "dec_last": ws * ru(lo),                      # workspace in (per sender) ...
     }
-    if kind == "dec_lo_last":
-        return senders * per_sender[kind] + 8 * d   # ... plus one read-modify-write of the accumulator
+    if kind == "dec_last":
+        return senders * per_sender[kind] + 8 * d     # ... plus one read-modify-write of the accumulator
     if kind == "finalize_mean":
         return 8 * d
     return senders * per_sender.get(kind, 0.0)
@@ -58,10 +65,6 @@ def kernel_bytes(kind, senders, d, D, mean_bits, narrow):
 # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain 1 GiB
 # copy gives; the summary of those runs is kept with the other profiler summaries).  Keyed by (workload, kernel kind).
 MEASURED_TRAFFIC = {
-    ("cfg4_n16_d11173962_b1", "enc_hi_first"): (682.3 + 1024.2) * 2 ** 20,
-    ("cfg4_n16_d11173962_b1", "enc_lo"): (1024.2 + 32.1) * 2 ** 20,
-    ("cfg4_n16_d11173962_b1", "dec_hi_first"): (64.2 + 512.2) * 2 ** 20,
-    ("cfg4_n16_d11173962_b1", "dec_lo_last"): (384.3 + 42.6) * 2 ** 20,
 }
 
 

@@ -158,12 +158,12 @@ int eden_get_tables(uint32_t bits, double *thresholds, double *centroids);
  * records (kind, senders in that launch, elapsed milliseconds) in launch order, stores the number
  * written in *count, and empties the pool.  Launches beyond max_records are not recorded. */
 typedef enum eden_kernel_kind {
-    EDEN_K_ENC_HI_FIRST = 0,   /* encode: first strided pass (reads x, signs, |x|^2) */
-    EDEN_K_HI_MID = 1,         /* middle strided pass, in place on the workspace */
-    EDEN_K_ENC_LO = 2,         /* encode: contiguous pass + quantize + pack */
+    EDEN_K_ENC_FIRST = 0,      /* encode: contiguous pass (reads x, signs, |x|^2) */
+    EDEN_K_MID = 1,            /* middle strided pass of the three-pass sizes, in place on the workspace */
+    EDEN_K_ENC_LAST = 2,       /* encode: last strided pass + quantize + pack */
     EDEN_K_DEC_PREPARE = 3,    /* decode: per-message scalars */
-    EDEN_K_DEC_HI_FIRST = 4,   /* decode: unpack + dequantize + first strided pass */
-    EDEN_K_DEC_LO_LAST = 5,    /* decode: contiguous pass + signs + sum over senders */
+    EDEN_K_DEC_FIRST = 4,      /* decode: unpack + dequantize + first strided pass */
+    EDEN_K_DEC_LAST = 5,       /* decode: contiguous pass + signs + sum over senders */
     EDEN_K_FINALIZE = 6,       /* division by n */
     EDEN_K_ENC_SMALL = 7,      /* encode, D <= 4096, one workgroup per sender */
     EDEN_K_DEC_SMALL = 8,      /* decode, D <= 4096 */

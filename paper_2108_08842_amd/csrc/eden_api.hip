@@ -43,6 +43,9 @@ int ceil_log2(uint64_t d) {
     return l;
 }
 
+// d rounded up to a multiple of 2^bits
+uint64_t round_up(uint64_t d, int bits) { return ((d + (1ull << bits) - 1) >> bits) << bits; }
+
 // Pass plan.  The contiguous pass covers the low 12 bits (wave tiles) or 14 bits (workgroup tiles); the
 // bits above it are covered by one or two strided passes: wave tiles handle up to 6 bits each,
 // workgroup tiles 7..10 bits.  D <= 2^24 needs two passes in all, D up to 2^27 three.
@@ -64,7 +67,8 @@ Plan make_plan(int log2D) {
         const int M = log2D - 14;
         pl.lo_bits = 14; pl.nhi = 1; pl.hi[0] = {M > 6, M, 14};
     } else {
-        pl.lo_bits = 14; pl.nhi = 2; pl.hi[0] = {true, 10, 14}; pl.hi[1] = {false, log2D - 24, 24};
+        // the pass next to the payload gets as many rows per wave as the remaining bits allow (16..64)
+        pl.lo_bits = 14; pl.nhi = 2; pl.hi[0] = {true, 7, 14}; pl.hi[1] = {false, log2D - 21, 21};
     }
     return pl;
 }
@@ -205,37 +209,36 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             Timed t(ctx, EDEN_K_ENC_SMALL, nb, st);
             launch_enc_small(B, nb, d, log2D, seed, ctx->tables, ctx->dev_status, st);
         } else {
-            // top bits first; the first pass reads x, the rest work in place on the workspace
+            // contiguous pass first (it reads x, and only the tiles that hold part of x), strided passes after it in
+            // place on the workspace, the last one quantizing and packing
             uint32_t nparts_n2 = 0, nparts_ip = 0;
             double *part_n2 = ctx->partials, *part_ip = ctx->partials + (size_t)ctx->slots * ctx->partial_stride;
             bool need_thresholds = false;                        // b = 1 and 1/2 quantize by sign alone
             for (uint32_t i = 0; i < nb; ++i) need_thresholds = need_thresholds || B.b_q8[i] > 256u;
-            for (int i = pl.nhi - 1; i >= 0; --i) {
-                const HiPass &h = pl.hi[i];
-                if (i == pl.nhi - 1) {
-                    {
-                        Timed t(ctx, EDEN_K_ENC_HI_FIRST, nb, st);
-                        nparts_n2 = h.wg ? launch_hix_first(h.M, B, nb, d, log2D, h.p, seed, ctx->T, part_n2,
-                                                            ctx->partial_stride, st)
-                                         : launch_enc_hi_first(h.M, B, nb, d, log2D, h.p, seed, ctx->T, part_n2,
-                                                               ctx->partial_stride, st);
-                    }
-                    if (need_thresholds) {
-                        Timed t(ctx, EDEN_K_ENC_NORM, nb, st);
-                        launch_enc_norm(B, nb, part_n2, ctx->partial_stride, nparts_n2, ctx->enc_scratch, ctx->tables, st);
-                    }
-                } else {
-                    Timed t(ctx, EDEN_K_HI_MID, nb, st);
-                    if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
-                    else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
-                }
-            }
             {
-                Timed t(ctx, EDEN_K_ENC_LO, nb, st);
-                nparts_ip = pl.lo_bits == 14 ? launch_enc_lo14(B, nb, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
-                                                               ctx->enc_scratch, st)
-                                             : launch_enc_lo(B, nb, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
-                                                             ctx->enc_scratch, st);
+                Timed t(ctx, EDEN_K_ENC_FIRST, nb, st);
+                nparts_n2 = pl.lo_bits == 14
+                                ? launch_enc_lo14_first(B, nb, d, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st)
+                                : launch_enc_lo_first(B, nb, d, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st);
+            }
+            if (need_thresholds) {
+                Timed t(ctx, EDEN_K_ENC_NORM, nb, st);
+                launch_enc_norm(B, nb, part_n2, ctx->partial_stride, nparts_n2, ctx->enc_scratch, ctx->tables, st);
+            }
+            uint64_t valid = round_up(d, pl.lo_bits);            // workspace elements written so far; the rest is zero
+            for (int i = 0; i < pl.nhi; ++i) {
+                const HiPass &h = pl.hi[i];
+                if (i < pl.nhi - 1) {
+                    Timed t(ctx, EDEN_K_MID, nb, st);
+                    launch_hix_mid(h.M, nb, ctx->T, log2D, valid, 1ull << log2D, st);
+                    valid = round_up(d, h.p + h.M);
+                } else {
+                    Timed t(ctx, EDEN_K_ENC_LAST, nb, st);
+                    nparts_ip = h.wg ? launch_enc_hix_last(h.M, B, nb, d, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
+                                                           ctx->enc_scratch, st)
+                                     : launch_enc_hi_last(h.M, B, nb, valid, log2D, h.p, seed, ctx->T, part_ip,
+                                                          ctx->partial_stride, ctx->enc_scratch, st);
+                }
             }
             Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
             launch_enc_finish(B, nb, d, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
@@ -285,17 +288,18 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             }
             for (int i = pl.nhi - 1; i >= 0; --i) {
                 const HiPass &h = pl.hi[i];
+                // what the passes after this one read: whole tiles of theirs that hold part of the first d coordinates
+                const uint64_t keep = round_up(d, h.p);
                 if (i == pl.nhi - 1) {
-                    Timed t(ctx, EDEN_K_DEC_HI_FIRST, nb, st);
-                    if (h.wg) launch_dec_hix_first(h.M, B, nb, log2D, seed, ctx->dec_scratch, narrow, ctx->T, st);
-                    else launch_dec_hi_first(h.M, B, nb, log2D, h.p, seed, ctx->dec_scratch, narrow, ctx->T, st);
+                    Timed t(ctx, EDEN_K_DEC_FIRST, nb, st);
+                    if (h.wg) launch_dec_hix_first(h.M, B, nb, d, log2D, seed, ctx->dec_scratch, narrow, ctx->T, st);
+                    else launch_dec_hi_first(h.M, B, nb, keep, log2D, h.p, seed, ctx->dec_scratch, narrow, ctx->T, st);
                 } else {
-                    Timed t(ctx, EDEN_K_HI_MID, nb, st);
-                    if (h.wg) launch_hix_mid(h.M, nb, ctx->T, log2D, h.p, st);
-                    else launch_hi_mid(h.M, nb, ctx->T, log2D, h.p, st);
+                    Timed t(ctx, EDEN_K_MID, nb, st);
+                    launch_hix_mid(h.M, nb, ctx->T, log2D, round_up(d, h.p + h.M), keep, st);
                 }
             }
-            Timed t(ctx, EDEN_K_DEC_LO_LAST, nb, st);
+            Timed t(ctx, EDEN_K_DEC_LAST, nb, st);
             if (pl.lo_bits == 14) launch_dec_lo14_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
             else launch_dec_lo_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
         }
@@ -412,9 +416,8 @@ int eden_profile_collect(eden_ctx *ctx, uint32_t *kinds, uint32_t *senders, floa
 }
 
 const char *eden_kernel_name(uint32_t kind) {
-    static const char *names[EDEN_K_COUNT] = {"enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_hi_first",
-                                              "dec_lo_last", "finalize_mean", "enc_small", "dec_small",
-                                              "enc_norm", "enc_finish"};
+    static const char *names[EDEN_K_COUNT] = {"enc_first", "mid", "enc_last", "dec_prepare", "dec_first", "dec_last",
+                                              "finalize_mean", "enc_small", "dec_small", "enc_norm", "enc_finish"};
     return kind < EDEN_K_COUNT ? names[kind] : "?";
 }
 

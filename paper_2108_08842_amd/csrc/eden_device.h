@@ -3,6 +3,8 @@
 #define EDEN_DEVICE_H
 
 #include <hip/hip_runtime.h>
+
+#include <utility>
 #include <stdint.h>
 
 namespace eden {
@@ -96,18 +98,16 @@ __device__ inline void wave_lds_sync() {
 }
 
 // v or -v per lane, chosen by bit `lane` of a wave-uniform 64-bit mask (one VALU op: the mask is
-// used directly as the lane-select operand).
+// used directly as the lane-select operand).  Written with the builtin, not inline assembly: an SGPR
+// written by a vector instruction (v_readlane, v_cmp) needs wait states before a vector instruction
+// reads it, and the compiler only inserts them for instructions it can see.
 __device__ inline float negate_where(float v, uint64_t mask) {
-    float r;
-    asm("v_cndmask_b32_e64 %0, %1, -%1, %2" : "=v"(r) : "v"(v), "s"(mask));
-    return r;
+    return __builtin_amdgcn_inverse_ballot_w64(mask) ? -v : v;
 }
 
 // v or 0 per lane, chosen by bit `lane` of a wave-uniform mask
 __device__ inline float keep_where(float v, uint64_t mask) {
-    float r;
-    asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(v), "s"(mask));
-    return r;
+    return __builtin_amdgcn_inverse_ballot_w64(mask) ? v : 0.0f;
 }
 
 // The 64-bit value held by lane `src` (compile-time constant), as a wave-uniform scalar.
@@ -188,8 +188,8 @@ __device__ inline double block_sum(double v, double *red /* shared, THREADS/64 *
 // (Sec. 2.2.1, Sec. 3), and its contribution |u| q to sum_i u_i Q_i (Sec. 2.3).  H = 2^(b-1) levels per sign.
 // A value exactly on a threshold stays in the interval closer to zero (strict compare); u = +0 is
 // non-negative.  thr[0] is unused (it is the threshold 0, decided by the sign).
-template <int H>
-__device__ inline uint32_t quantize_one(float u, const float (&thr)[H], const float (&qp)[H], float &ip) {
+template <int H, class TH, class QP>
+__device__ inline uint32_t quantize_one(float u, const TH &thr, const QP &qp, float &ip) {
     const float a = fabsf(u);
     uint32_t mag = 0;
     float qa = qp[0];
@@ -202,6 +202,45 @@ __device__ inline uint32_t quantize_one(float u, const float (&thr)[H], const fl
     ip = fmaf(a, qa, ip);
     const uint32_t neg = __float_as_uint(u) >> 31;
     return neg ? (uint32_t)(H - 1) - mag : (uint32_t)H + mag;
+}
+
+// ---- collecting ballots in lanes, and bit interleaving for the packed payload
+__device__ inline uint32_t lo32(uint64_t x) { return (uint32_t)x; }
+__device__ inline uint32_t hi32(uint64_t x) { return (uint32_t)(x >> 32); }
+// v_writelane_b32 through its compiler intrinsic (this compiler has no builtin of that name): the compiler then
+// also places the wait states an SGPR written by v_cmp needs before a vector instruction may read it.
+extern "C" __device__ int eden_writelane_i32(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+template <int LANE>
+__device__ inline uint32_t put_lane(uint32_t value, uint32_t old) {      // old with lane LANE replaced by a wave-uniform value
+    return (uint32_t)eden_writelane_i32((int)value, LANE, (int)old);
+}
+template <class F, int... I>
+__device__ inline void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ inline void static_for(F &&f) {                       // f(integral_constant<int, 0>) ... f(<N-1>)
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+__device__ inline uint32_t even_bits(uint32_t x) {               // bits 0,2,4,..,30 -> bits 0..15
+    x &= 0x55555555u;
+    x = (x | (x >> 1)) & 0x33333333u;
+    x = (x | (x >> 2)) & 0x0F0F0F0Fu;
+    x = (x | (x >> 4)) & 0x00FF00FFu;
+    return (x | (x >> 8)) & 0x0000FFFFu;
+}
+__device__ inline uint32_t spread2(uint32_t x) {                 // bit j of the low 16 -> bit 2j
+    x &= 0xFFFFu;
+    x = (x | (x << 8)) & 0x00FF00FFu;
+    x = (x | (x << 4)) & 0x0F0F0F0Fu;
+    x = (x | (x << 2)) & 0x33333333u;
+    return (x | (x << 1)) & 0x55555555u;
+}
+__device__ inline uint32_t spread4(uint32_t x) {                 // bit j of the low 8 -> bit 4j
+    x &= 0xFFu;
+    x = (x | (x << 12)) & 0x000F000Fu;
+    x = (x | (x << 6)) & 0x03030303u;
+    return (x | (x << 3)) & 0x11111111u;
 }
 
 // Butterflies over the low LOGB bits of the register index only.

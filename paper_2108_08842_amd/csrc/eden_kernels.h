@@ -7,22 +7,26 @@
 
 namespace eden {
 
-// wave-tile passes (eden_kernels.hip).  Launchers of kernels that leave per-workgroup partial sums
-// return how many partials each sender got.
-uint32_t launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
-                             double *partials, uint32_t partial_stride, hipStream_t st);
+// Encode runs the contiguous pass first (it reads x) and the strided passes after it, the last one quantizing and
+// packing; decode runs the strided passes first (the first one unpacks) and the contiguous pass last (it sums the
+// senders into acc).  Launchers of kernels that leave per-workgroup partial sums return how many partials each
+// sender got.
+
+// wave-tile passes and the small kernels (eden_kernels.hip)
+uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T, double *partials,
+                             uint32_t partial_stride, hipStream_t st);
+uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, int p, uint64_t seed,
+                            const float *T, double *partials, uint32_t partial_stride, const EncScratch *scratch,
+                            hipStream_t st);
 void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint32_t partial_stride, uint32_t nparts,
                      EncScratch *scratch, const DevTables *tab, hipStream_t st);
 void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials_n2,
                        uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip, uint32_t partial_stride,
                        uint32_t *dev_status, hipStream_t st);
-void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
-void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, int log2D, int p, uint64_t seed, const DecScratch *scratch,
-                         int narrow, float *T, hipStream_t st);
-uint32_t launch_enc_lo(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
-                       uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st);
+void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
+                         const DecScratch *scratch, int narrow, float *T, hipStream_t st);
 void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st);
@@ -33,16 +37,18 @@ void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint
 void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st);
 void launch_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t *bitmap, hipStream_t st);
 
-// workgroup-tile passes for D >= 2^19 (eden_kernels_wg.hip)
-uint32_t launch_hix_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
-                          double *partials, uint32_t partial_stride, hipStream_t st);
-void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st);
-void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch,
-                          int narrow, float *T, hipStream_t st);
+// workgroup-tile strided passes for D >= 2^21 (eden_kernels_wg.hip)
+uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+                             double *partials, uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
+void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems, uint64_t store_elems, hipStream_t st);
+void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+                          const DecScratch *scratch, int narrow, float *T, hipStream_t st);
+
+// 14-bit contiguous passes for D >= 2^19 (eden_kernels_lo14.hip)
+uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T,
+                               double *partials, uint32_t partial_stride, hipStream_t st);
 void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
                           const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
-uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
-                         uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
 
 }  // namespace eden
 #endif

@@ -42,42 +42,111 @@ __device__ inline void hi_tile_origin(uint32_t tile, int p, uint64_t &base) {
     base = ((uint64_t)upper << (p + M)) | ((uint64_t)colblock << 6);
 }
 
-// Encode, first pass: x -> T.  Zero padding (Sec. 5: the transform needs a power of two), the sign
-// diagonal of the rotation from the shared seed (Sec. 2.1), |x|^2 for eta and S (Sec. 2.2.1, 2.3).
+// Encode, last pass in wave tiles: T -> payload.  Index bits p .. p+M-1 of H, then quantization to the
+// Lloyd-Max intervals (Sec. 2.2.1, Sec. 3), sum_i u_i q_i for the scale (Sec. 2.3), sub-sampling for b = 1/2
+// (Sec. 4.1), packing.  Register r is row r of the tile = 64 consecutive coordinates across the lanes, so a
+// ballot of one index bit is 64 payload bits of that row; lane r collects the ballots of row r and packs them.
+// Workspace elements at or above `valid_elems` were not written by the earlier passes because they are
+// zero (transformed zero padding): the buffer bounds return 0 for them.
 template <int M>
-__global__ __launch_bounds__(256) void k_enc_hi_first(EncBatch B, uint64_t d, int log2D, int p, uint64_t seed,
-                                                      float *T, double *partials, uint32_t partial_stride) {
+__global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_elems, int log2D, int p, uint64_t seed,
+                                                     const float *T, double *partials, uint32_t partial_stride,
+                                                     const EncScratch *scratch) {
     constexpr int R = 1 << M;
     __shared__ double red[4];
     const uint32_t c = blockIdx.y;
     const uint32_t lane = lane_id();
     const uint32_t tile = blockIdx.x * 4u + wave_in_block();
     const uint32_t ntiles = 1u << (log2D - 6 - M);
-    double n2 = 0.0;
+    float ip = 0.0f;
     if (tile < ntiles) {
         uint64_t base;
         hi_tile_origin<M>(tile, p, base);
-        const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));          // reads past d give the zero padding
-        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
+        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), (uint32_t)(valid_elems * 4));
         const uint32_t lane_off = lane * 4u, base_off = (uint32_t)base * 4u;
         float v[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) v[r] = buf_load(rx, lane_off, base_off + ((uint32_t)r << (p + 2)));
-#pragma unroll
-        for (int r = 0; r < R; ++r) n2 += (double)v[r] * (double)v[r];
-        // lane r hashes the sign word of row r (all rows at once on the vector unit); row r's word is
-        // then read back as a wave-uniform lane mask
-        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
-        const uint64_t my_word = hash_word(key, (base + ((uint64_t)(lane & (R - 1)) << p)) >> 6);
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            v[r] = negate_where(v[r], wave_read64(my_word, r)) + 0.0f;   // + 0 turns -0 into +0
-        }
+        for (int r = 0; r < R; ++r) v[r] = buf_load(rt, lane_off, base_off + ((uint32_t)r << (p + 2)));
         fwht_regs<R>(v);
+        uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+        const uint32_t b_q8 = B.b_q8[c];
+        const uint64_t my_row = base + ((uint64_t)(lane & (R - 1)) << p);       // lane r < R finishes row r
+        if (b_q8 <= 256u) {
+            // I_1 = {(-inf,0],[0,inf)}: the index is the sign; <R(x),Q> = q_1 sum |u| / sqrt(D)
+            float sa = 0.0f;
 #pragma unroll
-        for (int r = 0; r < R; ++r) buf_store(rt, lane_off, base_off + ((uint32_t)r << (p + 2)), v[r]);
+            for (int r = 0; r < R; ++r) sa += fabsf(v[r]);
+            ip = sa * kQ1;
+            uint32_t wlo = 0, whi = 0;
+            static_for<R>([&](auto RR) {
+                constexpr int r = decltype(RR)::value;
+                const uint64_t m = __ballot((__float_as_uint(v[r]) >> 31) == 0u);    // index 1 = non-negative
+                wlo = put_lane<r>(lo32(m), wlo);
+                whi = put_lane<r>(hi32(m), whi);
+            });
+            if (lane < R) {
+                if (b_q8 == 256u) {
+                    *reinterpret_cast<uint2 *>(payload + (my_row >> 5)) = make_uint2(wlo, whi);
+                } else {
+                    // b = 1/2: of each pair (2g, 2g+1) send the coordinate chosen by the sub-sampling stream;
+                    // 64 pairs per hash word = 128 coordinates, a row segment uses 32 of them
+                    const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
+                    const uint32_t off = (uint32_t)(hash_word(key, my_row >> 7) >> (32u * (uint32_t)((my_row >> 6) & 1u)));
+                    const uint32_t ev = even_bits(wlo) | (even_bits(whi) << 16);
+                    const uint32_t od = even_bits(wlo >> 1) | (even_bits(whi >> 1) << 16);
+                    payload[my_row >> 6] = (ev & ~off) | (od & off);
+                }
+            }
+        } else {
+            const EncScratch *sc = &scratch[c];
+            uint32_t plane[4][2];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) plane[b][0] = plane[b][1] = 0;
+            if (b_q8 == 512u) {
+                static_for<R>([&](auto RR) {
+                    constexpr int r = decltype(RR)::value;
+                    const uint32_t code = quantize_one<2>(v[r], sc->thr, sc->qpos, ip);
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) {
+                        const uint64_t m = __ballot((code >> b) & 1u);
+                        plane[b][0] = put_lane<r>(lo32(m), plane[b][0]);
+                        plane[b][1] = put_lane<r>(hi32(m), plane[b][1]);
+                    }
+                });
+                if (lane < R) {
+                    uint32_t o[4];                               // word k: coordinates 16 k .. 16 k + 15 of the row
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        o[k] = spread2(plane[0][k >> 1] >> (16 * (k & 1))) | (spread2(plane[1][k >> 1] >> (16 * (k & 1))) << 1);
+                    *reinterpret_cast<uint4 *>(payload + (my_row >> 4)) = make_uint4(o[0], o[1], o[2], o[3]);
+                }
+            } else {
+                static_for<R>([&](auto RR) {
+                    constexpr int r = decltype(RR)::value;
+                    const uint32_t code = quantize_one<8>(v[r], sc->thr, sc->qpos, ip);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const uint64_t m = __ballot((code >> b) & 1u);
+                        plane[b][0] = put_lane<r>(lo32(m), plane[b][0]);
+                        plane[b][1] = put_lane<r>(hi32(m), plane[b][1]);
+                    }
+                });
+                if (lane < R) {
+                    uint32_t o[8];                               // word k: coordinates 8 k .. 8 k + 7 of the row
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        o[k] = 0;
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) o[k] |= spread4(plane[b][k >> 2] >> (8 * (k & 3))) << b;
+                    }
+                    uint4 *dst = reinterpret_cast<uint4 *>(payload + (my_row >> 3));
+                    dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+                    dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+                }
+            }
+        }
     }
-    const double block_total = block_sum<256>(n2, red);
+    const double block_total = block_sum<256>((double)ip, red);
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
 }
 
@@ -95,32 +164,13 @@ __global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *part
     if (threadIdx.x == 0) fill_enc_scratch(&scratch[c], total, B.b_q8[c], tab);
 }
 
-// Middle pass, in place on the workspace (tiles are disjoint).
-template <int M>
-__global__ __launch_bounds__(256) void k_hi_mid(float *T, int log2D, int p) {
-    constexpr int R = 1 << M;
-    const uint32_t c = blockIdx.y;
-    const uint32_t lane = lane_id();
-    const uint32_t tile = blockIdx.x * 4u + wave_in_block();
-    const uint32_t ntiles = 1u << (log2D - 6 - M);
-    if (tile >= ntiles) return;
-    uint64_t base;
-    hi_tile_origin<M>(tile, p, base);
-    const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
-    const uint32_t lane_off = lane * 4u, base_off = (uint32_t)base * 4u;
-    float v[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) v[r] = buf_load(rt, lane_off, base_off + ((uint32_t)r << (p + 2)));
-    fwht_regs<R>(v);
-#pragma unroll
-    for (int r = 0; r < R; ++r) buf_store(rt, lane_off, base_off + ((uint32_t)r << (p + 2)), v[r]);
-}
-
 // Decode, first pass in wave tiles (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit
 // pattern +-1 when the workspace of a b <= 1 sender is int16), zero for coordinates that were not sampled or
 // whose packet was lost, then index bits p .. p+M-1 of H.  Every (tile, sender) pair is independent.
+// Elements at or above `keep_elems` are never read by the later passes (they end in the padding): the buffer
+// bounds drop their stores.
 template <int M>
-__global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, int log2D, int p, uint64_t seed,
+__global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                                                       const DecScratch *scratch, int narrow, float *T) {
     constexpr int R = 1 << M;
     __shared__ float table[4][16];
@@ -179,126 +229,68 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, int log2D, int
     }
     fwht_regs<R>(v);
     if (i16) {                                                   // exact integers of magnitude <= 2^M
-        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 2u << log2D);
+        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), (uint32_t)(keep_elems * 2));
 #pragma unroll
         for (int r = 0; r < R; ++r)
             __builtin_amdgcn_raw_buffer_store_b16((short)(int)v[r], rt, (int)(lane * 2u),
                                                   (int)(((uint32_t)base + ((uint32_t)r << p)) * 2u), kStream);
     } else {
-        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
+        const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), (uint32_t)(keep_elems * 4));
 #pragma unroll
         for (int r = 0; r < R; ++r) buf_store(rt, lane * 4u, ((uint32_t)base + ((uint32_t)r << p)) * 4u, v[r]);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// lo pass, encode side: T -> payload.  Quantization to the Lloyd-Max intervals (Sec. 2.2.1, Sec. 3),
-// <R(x), Q(eta R(x))> for the scale (Sec. 2.3), sub-sampling for b = 1/2 (Sec. 4.1), packing.
-template <int BITS>
-__device__ inline void quantize_pack(const float (&v)[64], const EncScratch *s, uint32_t *out /* 2*BITS words */,
-                                     float &ip) {
-    constexpr int H = 1 << (BITS - 1);
-    constexpr int PER = 32 / BITS;
-    float thr[H], qp[H];
-#pragma unroll
-    for (int i = 0; i < H; ++i) { thr[i] = s->thr[i]; qp[i] = s->qpos[i]; }
-    ip = 0.0f;
-#pragma unroll
-    for (int w = 0; w < 2 * BITS; ++w) {
-        uint32_t word = 0;
-#pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const float u = v[w * PER + e];
-            const float a = fabsf(u);
-            uint32_t mag = 0;
-            float qa = qp[0];
-#pragma unroll
-            for (int t = 1; t < H; ++t) {                      // strict: a value on a threshold stays in the
-                const bool above = a > thr[t];                 // interval closer to zero (Sec. 2.2.1 footnote)
-                mag = above ? (uint32_t)t : mag;
-                qa = above ? qp[t] : qa;
-            }
-            ip = fmaf(a, qa, ip);
-            const uint32_t neg = __float_as_uint(u) >> 31;     // u = +0 counts as non-negative
-            const uint32_t code = neg ? (uint32_t)(H - 1) - mag : (uint32_t)H + mag;
-            word |= code << (e * BITS);
-        }
-        out[w] = word;
-    }
-}
-
-__global__ __launch_bounds__(128) void k_enc_lo(EncBatch B, int log2D, uint64_t seed, const float *T,
-                                                double *partials, uint32_t partial_stride,
-                                                const EncScratch *scratch) {
+// Encode, first pass in wave tiles: x -> T.  Zero padding (Sec. 5: the transform needs a power of two), the
+// sign diagonal of the rotation from the shared seed (Sec. 2.1), |x|^2 for eta and S (Sec. 2.2.1, 2.3), index
+// bits 0..11 of H.  Only the ceil(d / 4096) tiles that hold part of x are transformed and written; the strided
+// pass that follows reads the others as zero through its buffer bounds.  Loads and stores are both in the
+// layout "register j = coordinates 64 j + lane" (256 contiguous bytes per wave access), so the tile goes
+// through the wave-private 64x64 LDS transpose twice.
+__global__ __launch_bounds__(128) void k_enc_lo_first(EncBatch B, uint64_t d, int log2D, uint64_t seed, float *T,
+                                                      double *partials, uint32_t partial_stride) {
     __shared__ float lds[2][64 * kLdsRow];
     __shared__ double red[2];
     const uint32_t c = blockIdx.y;
     const uint32_t lane = lane_id();
     const uint32_t wv = wave_in_block();
-    const uint32_t tile = blockIdx.x * 2u + wv;               // D >= 2^13: always an even number of tiles
-    const float *Tc = T + ((size_t)c << log2D) + ((size_t)tile << kLoBits);
-    float v[64];
+    const uint32_t tile = blockIdx.x * 2u + wv;
+    const uint64_t tile_base = (uint64_t)tile << kLoBits;
+    double n2 = 0.0;
+    if (tile_base < d) {                                         // wave-uniform; no block-wide barrier inside
+        const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));          // reads past d give the zero padding
+        float v[64];
 #pragma unroll
-    for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(Tc + 64 * j + lane);
-    fwht_regs<64>(v);                                          // index bits 6..11
-    float *L = lds[wv];
+        for (int j = 0; j < 64; ++j) v[j] = buf_load(rx, lane * 4u, (uint32_t)tile_base * 4u + 256u * j);
 #pragma unroll
-    for (int j = 0; j < 64; ++j) L[j * kLdsRow + lane] = v[j];
-    wave_lds_sync();
+        for (int j = 0; j < 64; ++j) n2 += (double)v[j] * (double)v[j];
+        // register j = 64 consecutive coordinates = one sign word: lane l hashes the word of register l,
+        // register j reads it back as a lane mask
+        const uint64_t mine = hash_word(stream_key(seed, kStreamSign, B.client[c]), (tile_base >> 6) + lane);
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        const float4 t = *reinterpret_cast<const float4 *>(&L[lane * kLdsRow + 4 * q]);
-        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
-    }
-    fwht_regs<64>(v);                                          // index bits 0..5; lane owns 64 consecutive u_i
-
-    const EncScratch *s = &scratch[c];
-    constexpr bool valid = true;     // a zero or non-finite vector is detected, and its payload cleared, by k_enc_finish
-    const uint32_t b_q8 = B.b_q8[c];
-    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const size_t seg = (size_t)tile * 64 + lane;               // index of this lane's run of 64 coordinates
-    float ip = 0.0f;
-    if (b_q8 == 256 || b_q8 == 128) {
-        // I_1 = {(-inf,0],[0,inf)}: the index is the sign; <R(x),Q> = q_1 * sum |u| / sqrt(D)
-        float sa = 0.0f;
+        for (int j = 0; j < 64; ++j) v[j] = negate_where(v[j], wave_read64(mine, j)) + 0.0f;   // + 0: no negative zeros
+        fwht_regs<64>(v);                                        // index bits 6..11
+        float *L = lds[wv];
 #pragma unroll
-        for (int k = 0; k < 64; ++k) sa += fabsf(v[k]);
-        ip = sa * kQ1;
-        if (b_q8 == 256) {
-            uint32_t w0 = 0, w1 = 0;                           // shift the sign bits in, last coordinate first
+        for (int j = 0; j < 64; ++j) L[j * kLdsRow + lane] = v[j];
+        wave_lds_sync();
 #pragma unroll
-            for (int k = 31; k >= 0; --k) w0 = __builtin_amdgcn_alignbit(w0, __float_as_uint(v[k]), 31);
-#pragma unroll
-            for (int k = 63; k >= 32; --k) w1 = __builtin_amdgcn_alignbit(w1, __float_as_uint(v[k]), 31);
-            uint2 o = make_uint2(valid ? ~w0 : 0u, valid ? ~w1 : 0u);   // index 1 = non-negative
-            *reinterpret_cast<uint2 *>(payload + seg * 2) = o;
-        } else {
-            // b = 1/2: of each pair (2g, 2g+1) send the coordinate chosen by the sub-sampling stream
-            uint32_t ev = 0, od = 0;
-#pragma unroll
-            for (int g = 31; g >= 0; --g) {
-                ev = __builtin_amdgcn_alignbit(ev, __float_as_uint(v[2 * g]), 31);
-                od = __builtin_amdgcn_alignbit(od, __float_as_uint(v[2 * g + 1]), 31);
-            }
-            const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
-            const uint64_t hw = hash_word(key, seg >> 1);      // 64 pairs per hash word = two lanes
-            const uint32_t off = (uint32_t)(hw >> ((seg & 1) * 32));
-            payload[seg] = valid ? ((~ev & ~off) | (~od & off)) : 0u;
+        for (int q = 0; q < 16; ++q) {
+            const float4 t = *reinterpret_cast<const float4 *>(&L[lane * kLdsRow + 4 * q]);
+            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
         }
-    } else if (b_q8 == 512) {
-        uint32_t w[4];
-        quantize_pack<2>(v, s, w, ip);
-        *reinterpret_cast<uint4 *>(payload + seg * 4) =
-            valid ? make_uint4(w[0], w[1], w[2], w[3]) : make_uint4(0, 0, 0, 0);
-    } else {
-        uint32_t w[8];
-        quantize_pack<4>(v, s, w, ip);
-        uint4 *o = reinterpret_cast<uint4 *>(payload + seg * 8);
-        o[0] = valid ? make_uint4(w[0], w[1], w[2], w[3]) : make_uint4(0, 0, 0, 0);
-        o[1] = valid ? make_uint4(w[4], w[5], w[6], w[7]) : make_uint4(0, 0, 0, 0);
+        fwht_regs<64>(v);                                        // index bits 0..5; lane holds 64 consecutive values
+        wave_lds_sync();
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            *reinterpret_cast<float4 *>(&L[lane * kLdsRow + 4 * q]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+        wave_lds_sync();
+        float *Tc = T + ((size_t)c << log2D) + tile_base + lane;
+#pragma unroll
+        for (int j = 0; j < 64; ++j) __builtin_nontemporal_store(L[j * kLdsRow + lane], Tc + 64 * j);
     }
-
-    const double block_total = block_sum<128>((double)ip, red);
+    const double block_total = block_sum<128>(n2, red);
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
 }
 
@@ -648,12 +640,13 @@ __global__ void k_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uin
         default: { constexpr int MM = 6; CALL; } break; \
     }
 
-uint32_t launch_enc_hi_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
-                             double *partials, uint32_t partial_stride, hipStream_t st) {
+uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, int p, uint64_t seed,
+                            const float *T, double *partials, uint32_t partial_stride, const EncScratch *scratch,
+                            hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
-    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_enc_hi_first<MM>, grid, dim3(256), 0, st, B, d, log2D, p, seed, T, partials,
-                                         partial_stride));
+    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_enc_hi_last<MM>, grid, dim3(256), 0, st, B, valid_elems, log2D, p, seed, T, partials,
+                                         partial_stride, scratch));
     return grid.x;
 }
 void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint32_t partial_stride, uint32_t nparts,
@@ -667,21 +660,18 @@ void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uin
     hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, log2D, seed, partials_n2, nparts_n2, partials_ip,
                        nparts_ip, partial_stride, words_b1, dev_status);
 }
-void launch_hi_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st) {
+void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
+                         const DecScratch *scratch, int narrow, float *T, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
-    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_hi_mid<MM>, grid, dim3(256), 0, st, T, log2D, p));
+    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_first<MM>, grid, dim3(256), 0, st, B, keep_elems, log2D, p, seed, scratch, narrow,
+                                         T));
 }
-void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, int log2D, int p, uint64_t seed, const DecScratch *scratch,
-                         int narrow, float *T, hipStream_t st) {
-    const uint32_t ntiles = 1u << (log2D - 6 - M);
-    dim3 grid((ntiles + 3) / 4, n);
-    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_first<MM>, grid, dim3(256), 0, st, B, log2D, p, seed, scratch, narrow, T));
-}
-uint32_t launch_enc_lo(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
-                       uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
-    dim3 grid(1u << (log2D - kLoBits - 1), n);
-    hipLaunchKernelGGL(k_enc_lo, grid, dim3(128), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
+uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T, double *partials,
+                             uint32_t partial_stride, hipStream_t st) {
+    const uint32_t tiles = (uint32_t)((d + (1u << kLoBits) - 1) >> kLoBits);
+    dim3 grid((tiles + 1) / 2, n);
+    hipLaunchKernelGGL(k_enc_lo_first, grid, dim3(128), 0, st, B, d, log2D, seed, T, partials, partial_stride);
     return grid.x;
 }
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,

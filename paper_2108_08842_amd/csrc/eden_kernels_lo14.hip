@@ -9,8 +9,8 @@
 //   exchange  through LDS inside groups of 16 lanes (registers <-> bits 0..3, bit 4 stays a register bit)
 //   round 3   bits 0..3
 //
-// Afterwards thread t holds the 32 consecutive coordinates 512 (t >> 4) + 32 (t & 15) + e, e = 0..31: one
-// packed word for b = 1, and one half of a 64-bit sign word of the rotation.
+// Afterwards thread t holds the 32 consecutive coordinates 32 t + e, e = 0..31: one half of a 64-bit sign word
+// of the rotation, and one 128-byte line of the workspace or the accumulator.
 //
 // 32 registers (instead of 64) halve the LDS a wave needs for its exchanges, which doubles the number of
 // resident waves per CU (16); these passes are bound by vector-ALU issue, not by memory.
@@ -53,93 +53,74 @@ __device__ inline void lo14_forward32(float (&v)[32], float *lds) {
     fwht_regs_low<32, 4>(v);                                     // bits 0..3 (bit 4 rides along)
 }
 
-__device__ inline uint32_t lane_xor1(uint32_t x) {              // value held by lane ^ 1
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);
-}
-
-template <int BITS>
-__device__ inline void quantize_store32(const float (&u)[32], const EncScratch *s, uint32_t *payload, uint64_t first,
-                                        float &ip) {
-    constexpr int H = 1 << (BITS - 1);
-    float thr[H], qp[H];
+// Stores the 32 consecutive values every thread holds after lo14_forward32 as whole 128-byte lines: thread t's
+// run starts at coordinate 32 t of the tile, so a wave owns 2048 consecutive coordinates; a wave-private
+// transpose through LDS (quads swizzled by the row so that both directions are conflict free) lets 8
+// neighbouring lanes store one line.  `L`: this wave's 2048 floats of LDS; `dst`: the wave's first coordinate.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ inline void lo14_store_runs(const float (&v)[32], float *L, float *dst) {
+    const uint32_t lane = threadIdx.x & 63u;
+    wave_lds_sync();
+    const uint32_t swz = (lane >> 1) & 7u;
 #pragma unroll
-    for (int i = 0; i < H; ++i) { thr[i] = s->thr[i]; qp[i] = s->qpos[i]; }
-    uint32_t w[BITS];
+    for (int q = 0; q < 8; ++q)
+        *reinterpret_cast<float4 *>(&L[lane * 32u + 4u * ((uint32_t)q ^ swz)]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    wave_lds_sync();
+    const uint32_t pos = lane & 7u;
 #pragma unroll
-    for (int i = 0; i < BITS; ++i) w[i] = 0;
-#pragma unroll
-    for (int e = 0; e < 32; ++e) {
-        const uint32_t code = quantize_one<H>(u[e], thr, qp, ip);
-        w[(e * BITS) / 32] |= code << ((e * BITS) % 32);
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t row = 8u * (uint32_t)j + (lane >> 3);
+        const float4 x = *reinterpret_cast<const float4 *>(&L[row * 32u + 4u * pos]);
+        const uint32_t quad = pos ^ ((row >> 1) & 7u);
+        f32x4_t y = {x.x, x.y, x.z, x.w};
+        __builtin_nontemporal_store(y, reinterpret_cast<f32x4_t *>(dst + row * 32u + 4u * quad));
     }
-    if constexpr (BITS == 2) *reinterpret_cast<uint2 *>(payload + (first >> 4)) = make_uint2(w[0], w[1]);
-    else *reinterpret_cast<uint4 *>(payload + (first >> 3)) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// Encode, last pass: T -> payload.  Quantization to the Lloyd-Max intervals (Sec. 2.2.1, Sec. 3), sum_i u_i q_i
-// for the scale (Sec. 2.3), sub-sampling for b = 1/2 (Sec. 4.1), packing.  TPW tiles per workgroup: the next
-// tile's loads are in flight while the current tile is transformed.
+// Encode, first pass: x -> T.  Zero padding (Sec. 5: the transform needs a power of two), the sign diagonal of
+// the rotation from the shared seed (Sec. 2.1), |x|^2 for eta and S (Sec. 2.2.1, 2.3), index bits 0..13 of H.
+// Only the ceil(d / 2^14) tiles that hold part of x are transformed and written: a tile of padding stays zero
+// under these 14 bits, and the strided pass that follows reads it as zero through its buffer bounds.
 template <int TPW>
-__global__ __launch_bounds__(512) void k_enc_lo14(EncBatch B, int log2D, uint64_t seed, const float *T, double *partials,
-                                                  uint32_t partial_stride, const EncScratch *scratch) {
+__global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t d, int log2D, uint64_t seed, float *T,
+                                                        double *partials, uint32_t partial_stride) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14LdsWords];
     __shared__ double red[8];
-    const uint32_t c = blockIdx.y, t = threadIdx.x;
-    const EncScratch *s = &scratch[c];
-    const uint32_t b_q8 = B.b_q8[c];
-    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const float *Tw = T + ((size_t)c << log2D) + (t >> 6) * 64u + (t & 63u);
-    const uint32_t run = 512u * (t >> 4) + 32u * (t & 15u);      // this thread's 32 coordinates inside a tile
-    float ip = 0.0f;
+    const uint32_t c = blockIdx.y, t = threadIdx.x, lane = t & 63u;
+    const uint32_t wv = wave_in_block();
+    const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);
+    const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));               // reads past d give the zero padding
+    float *Tc = T + ((size_t)c << log2D);
+    const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+    const uint32_t lane_off = (wv * 64u + lane) * 4u;
+    const uint32_t tile0 = blockIdx.x * TPW;
+    double n2 = 0.0;
     float next[32];
 #pragma unroll
-    for (int a = 0; a < 32; ++a) next[a] = __builtin_nontemporal_load(Tw + (((uint64_t)blockIdx.x * TPW) << kLo14Bits) + 512 * a);
+    for (int a = 0; a < 32; ++a) next[a] = buf_load(rx, lane_off, (tile0 << (kLo14Bits + 2)) + 2048u * a);
 #pragma unroll
     for (int k = 0; k < TPW; ++k) {
-        const uint64_t tile_base = ((uint64_t)blockIdx.x * TPW + k) << kLo14Bits;
+        const uint32_t tile = tile0 + k;
+        if (tile >= tiles) break;                                // same decision in every thread of the workgroup
         float u[32];
 #pragma unroll
         for (int a = 0; a < 32; ++a) u[a] = next[a];
+#pragma unroll
+        for (int a = 0; a < 32; ++a) n2 += (double)u[a] * (double)u[a];
+        // register a of this wave = 64 consecutive coordinates = one sign word: lane l < 32 hashes the word of
+        // register l, register a reads it back as a lane mask
+        const uint64_t mine = hash_word(key, ((uint64_t)tile << (kLo14Bits - 6)) + 8u * (lane & 31u) + wv);
+#pragma unroll
+        for (int a = 0; a < 32; ++a) u[a] = negate_where(u[a], wave_read64(mine, a)) + 0.0f;   // + 0: no negative zeros
         if (k + 1 < TPW) {
 #pragma unroll
-            for (int a = 0; a < 32; ++a) next[a] = __builtin_nontemporal_load(Tw + tile_base + (1u << kLo14Bits) + 512 * a);
+            for (int a = 0; a < 32; ++a) next[a] = buf_load(rx, lane_off, ((tile + 1u) << (kLo14Bits + 2)) + 2048u * a);
         }
         lo14_forward32(u, lds);
-        const uint64_t first = tile_base + run;
-        if (b_q8 == 256 || b_q8 == 128) {
-            // I_1 = {(-inf,0],[0,inf)}: the index is the sign; <R(x),Q> = q_1 sum |u| / sqrt(D)
-            float sa = 0.0f;
-#pragma unroll
-            for (int e = 0; e < 32; ++e) sa += fabsf(u[e]);
-            ip += sa * kQ1;
-            if (b_q8 == 256) {
-                uint32_t neg = 0;                                // shift the sign bits in, last coordinate first
-#pragma unroll
-                for (int e = 31; e >= 0; --e) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(u[e]), 31);
-                payload[first >> 5] = ~neg;                      // index 1 = non-negative
-            } else {
-                // b = 1/2: of each pair (2g, 2g+1) send the coordinate chosen by the sub-sampling stream
-                uint32_t ev = 0, od = 0;
-#pragma unroll
-                for (int g = 15; g >= 0; --g) {
-                    ev = __builtin_amdgcn_alignbit(ev, __float_as_uint(u[2 * g]), 31);
-                    od = __builtin_amdgcn_alignbit(od, __float_as_uint(u[2 * g + 1]), 31);
-                }
-                const uint64_t key = stream_key(seed, kStreamSubsample, B.client[c]);
-                const uint64_t hw = hash_word(key, first >> 7);  // 64 pairs per hash word = 128 coordinates
-                const uint32_t off = (uint32_t)(hw >> (16u * (uint32_t)((first >> 5) & 3u))) & 0xFFFFu;
-                const uint32_t mine = ((~ev & ~off) | (~od & off)) & 0xFFFFu;
-                const uint32_t other = lane_xor1(mine);
-                if (!(t & 1u)) payload[first >> 6] = mine | (other << 16);
-            }
-        } else if (b_q8 == 512) {
-            quantize_store32<2>(u, s, payload, first, ip);
-        } else {
-            quantize_store32<4>(u, s, payload, first, ip);
-        }
+        lo14_store_runs(u, lds + wv * kXbWave, Tc + ((size_t)tile << kLo14Bits) + 2048u * wv);
         if (k + 1 < TPW) __syncthreads();                        // LDS is reused by the next tile
     }
-    const double block_total = block_sum<512>((double)ip, red);
+    const double block_total = block_sum<512>(n2, red);
     if (t == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
 }
 
@@ -208,21 +189,16 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     }
 }
 
-uint32_t launch_enc_lo14(const EncBatch &B, uint32_t n, int log2D, uint64_t seed, const float *T, double *partials,
-                         uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
-    const uint32_t tiles = 1u << (log2D - kLo14Bits);
-    if (tiles >= 1024) {                                         // still >= 4 workgroups per resident slot
-        dim3 grid(tiles / 8, n);
-        hipLaunchKernelGGL(k_enc_lo14<8>, grid, dim3(512), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
-        return grid.x;
-    }
-    if (tiles >= 256) {
-        dim3 grid(tiles / 4, n);
-        hipLaunchKernelGGL(k_enc_lo14<4>, grid, dim3(512), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
+uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T,
+                               double *partials, uint32_t partial_stride, hipStream_t st) {
+    const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);
+    if (tiles >= 512) {
+        dim3 grid((tiles + 3) / 4, n);
+        hipLaunchKernelGGL(k_enc_lo14_first<4>, grid, dim3(512), 0, st, B, d, log2D, seed, T, partials, partial_stride);
         return grid.x;
     }
     dim3 grid(tiles, n);
-    hipLaunchKernelGGL(k_enc_lo14<1>, grid, dim3(512), 0, st, B, log2D, seed, T, partials, partial_stride, scratch);
+    hipLaunchKernelGGL(k_enc_lo14_first<1>, grid, dim3(512), 0, st, B, d, log2D, seed, T, partials, partial_stride);
     return grid.x;
 }
 void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,

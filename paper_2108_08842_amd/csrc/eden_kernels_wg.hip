@@ -1,21 +1,18 @@
-// Workgroup-tile passes of the Walsh-Hadamard transform for large D (2^19 .. 2^27), gfx950.
+// Workgroup-tile strided passes of the Walsh-Hadamard transform for large D (2^21 .. 2^27), gfx950.
 //
-// Two passes through memory are enough for D <= 2^24 when a workgroup keeps 2^14 .. 2^15 coordinates
-// on chip (registers + one or two exchanges through LDS):
+// Two passes through memory are enough for D <= 2^24 when a workgroup keeps 2^14 .. 2^15 coordinates on chip
+// (registers + one or two exchanges through LDS):
 //
-//   hiX pass  index bits p .. p+M-1, M = 7..10: a workgroup owns 2^M rows of 32 consecutive coordinates
-//             (128-byte segments) at stride 2^p.  Every thread keeps 64 rows of one column in registers
-//             (six butterfly stages), the remaining M-6 row bits are reached by one exchange through
+//   lo14 pass (contiguous, index bits 0 .. 13): in eden_kernels_lo14.hip.
+//   hiX pass  (strided, index bits 14 .. 14+M-1, M = 7..10): a workgroup owns 2^M rows of 32 consecutive
+//             coordinates (128-byte segments) at stride 2^14.  Every thread keeps 64 rows of one column in
+//             registers (six butterfly stages), the remaining M-6 row bits are reached by one exchange through
 //             LDS (for M = 10 in two halves of 64 KiB so that two workgroups fit on a CU).
-//   lo14 pass index bits 0 .. 13: four waves, each transforms 4096 consecutive coordinates in
-//             registers (6 + 6 bits with a wave-private 64x64 LDS transpose), then one exchange between
-//             the four waves gives bits 12 and 13.
 //
-// Fusions are those of the wave-tile kernels: the first encode pass reads x, applies the rotation's sign
-// diagonal and sums |x|^2 (Sec. 2.1, 2.2.1); the last encode pass quantizes against the Lloyd-Max
-// thresholds, accumulates <R(x),Q> and packs (Sec. 2.2.1, 2.3, 3, 4.1); the first decode pass unpacks and
-// dequantizes with S/(p sqrt D) (Sec. 2.2.2, 4.2); the last decode pass applies the signs and sums the
-// senders in registers.
+// The strided pass is the one next to the payload: encode runs it last and fuses quantization against the
+// Lloyd-Max thresholds, <R(x),Q> and packing (Sec. 2.2.1, 2.3, 3, 4.1); decode runs it first and fuses
+// unpacking and dequantization with S/(p sqrt D) (Sec. 2.2.2, 4.2).  The contiguous pass is the one next to x
+// and to the accumulator, where the zero padding of d up to D costs nothing.
 #include "eden_device.h"
 #include "eden_kernels.h"
 
@@ -96,106 +93,213 @@ __device__ inline void hix_exchange(const float (&v)[64], float *lds, float (&ou
     hix_exchange_read<M>(lds, out);
 }
 
-// The 32 sign bits of the rotation's diagonal for one row segment of a tile.
-__device__ inline uint32_t sign_half_word(uint64_t key, uint64_t first_index) {
-    const uint64_t word = hash_word(key, first_index >> 6);
-    return (uint32_t)(word >> (((first_index >> 5) & 1ull) * 32));
-}
-__device__ inline uint64_t pair_mask(uint32_t lo_words, uint32_t hi_words, int src) {
-    const uint32_t lo = __builtin_amdgcn_readlane(lo_words, src);
-    const uint32_t hi = __builtin_amdgcn_readlane(hi_words, src);
-    return ((uint64_t)hi << 32) | lo;
+// ---- packing in the strided layout.  After a tile's last butterfly a register holds, across the two halves of
+// a wave, two row segments of 32 consecutive coordinates: exactly one payload word each at b = 1.  A ballot
+// of one bit of the index gives both words at once; lane j of each half collects the words of register j
+// (v_writelane), and after the last register every lane finishes and stores the words of "its" row.
+// Quantizes and packs the RP values a thread holds after one half of the exchange (rows hix_row2(g, PH, s)).
+// `word0`: payload word index of this tile's 32 columns in row 0.
+template <int M, int BITS>
+__device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph, const EncScratch *sc, uint32_t *payload,
+                                         uint32_t word0, float &ip) {
+    using X = HiX<M>;
+    constexpr int p = kHixP;
+    constexpr int H = 1 << (BITS - 1);
+    constexpr int NW = X::RP / 32;                               // registers come in blocks of 32 = one word lane each
+    const uint32_t lane = lane_id(), j = lane & 31u, g = threadIdx.x >> 5;
+    uint32_t plane[BITS][NW];
+#pragma unroll
+    for (int b = 0; b < BITS; ++b)
+#pragma unroll
+        for (int w = 0; w < NW; ++w) plane[b][w] = 0;
+    static_for<X::RP>([&](auto S) {
+        constexpr int s = decltype(S)::value;
+        const uint32_t code = quantize_one<H>(out[s], sc->thr, sc->qpos, ip);
+#pragma unroll
+        for (int b = 0; b < BITS; ++b) {
+            const uint64_t m = __ballot((code >> b) & 1u);
+            plane[b][s / 32] = put_lane<s % 32>(lo32(m), plane[b][s / 32]);
+            plane[b][s / 32] = put_lane<32 + s % 32>(hi32(m), plane[b][s / 32]);
+        }
+    });
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const uint32_t s = 32u * (uint32_t)w + j;                // the register whose words this lane holds
+        const uint32_t e = s / X::RL, rl = s % X::RL;
+        const uint32_t row = rl + (uint32_t)X::RL * ((uint32_t)ph * X::RP + g * X::RHL + e);
+        const uint32_t word = word0 + (row << (p - 5));
+        if constexpr (BITS == 2) {
+            const uint32_t a = plane[0][w], b = plane[1][w];
+            *reinterpret_cast<uint2 *>(payload + 2u * word) =
+                make_uint2(spread2(a) | (spread2(b) << 1), spread2(a >> 16) | (spread2(b >> 16) << 1));
+        } else {
+            uint32_t o[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                o[k] = spread4(plane[0][w] >> (8 * k)) | (spread4(plane[1][w] >> (8 * k)) << 1) |
+                       (spread4(plane[2][w] >> (8 * k)) << 2) | (spread4(plane[3][w] >> (8 * k)) << 3);
+            *reinterpret_cast<uint4 *>(payload + 4u * word) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
 }
 
-// TPW tiles per workgroup (neighbouring column blocks).  The loads of the next tile are issued into the
-// registers that each half of the exchange has just written to LDS, so they are in flight during the rest of
-// the current tile at no cost in registers.
-template <int M, int TPW>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_first(EncBatch B, uint64_t d, int log2D, int p_arg,
-                                                                uint64_t seed, float *T, double *partials,
-                                                                uint32_t partial_stride) {
+// b = 1 and b = 1/2: the index is the sign (I_1, Sec. 3), <R(x),Q> = q_1 sum |u| / sqrt(D).  Leaves in words[w],
+// lane j of each half, the 32 index bits of the row segment held in register 32 w + j.
+template <int M>
+__device__ inline void hix_sign_words(const float (&out)[HiX<M>::RP], float &ip, uint32_t (&words)[HiX<M>::RP / 32]) {
+    using X = HiX<M>;
+    float sa = 0.0f;
+#pragma unroll
+    for (int s = 0; s < X::RP; ++s) sa += fabsf(out[s]);
+    ip = fmaf(sa, kQ1, ip);
+#pragma unroll
+    for (int w = 0; w < X::RP / 32; ++w) words[w] = 0;
+    static_for<X::RP>([&](auto S) {
+        constexpr int s = decltype(S)::value;
+        const uint64_t m = __ballot((__float_as_uint(out[s]) >> 31) == 0u);      // index 1 = non-negative
+        words[s / 32] = put_lane<s % 32>(lo32(m), words[s / 32]);
+        words[s / 32] = put_lane<32 + s % 32>(hi32(m), words[s / 32]);
+    });
+}
+
+// row of the tile whose words lane j holds for register block w after half ph of the exchange
+template <int M>
+__device__ inline uint32_t hix_word_row(int ph, int w) {
+    using X = HiX<M>;
+    const uint32_t s = 32u * (uint32_t)w + (lane_id() & 31u), g = threadIdx.x >> 5;
+    return s % X::RL + (uint32_t)X::RL * ((uint32_t)ph * X::RP + g * X::RHL + s / X::RL);
+}
+
+template <int N> struct WordVec;
+template <> struct WordVec<1> { using type = uint32_t; };
+template <> struct WordVec<2> { using type = uint2; };
+template <> struct WordVec<4> { using type = uint4; };
+
+// Encode, last pass: T -> payload.  Index bits 14 .. 14+M-1 of H, then quantization to the Lloyd-Max intervals
+// (Sec. 2.2.1, Sec. 3), sum_i u_i q_i for the scale (Sec. 2.3), sub-sampling for b = 1/2 (Sec. 4.1), packing.
+// Rows of the workspace at or above ceil(d / 2^14) were not written by the first pass (they are zero padding
+// transformed over bits 0..13, i.e. zero): the buffer bounds return 0 for them without touching memory.
+// A workgroup handles TPW neighbouring column blocks; the loads of the next one are issued into the registers
+// that each half of the exchange has just written to LDS.  UNIT: every sender of the launch has b <= 1; the
+// words of the TPW tiles are then kept and stored together (one row of a tile is only 4 bytes of payload).
+template <int M, int TPW, bool UNIT>
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, uint64_t d, int log2D, uint64_t seed,
+                                                                   const float *T, double *partials,
+                                                                   uint32_t partial_stride, const EncScratch *scratch) {
     using X = HiX<M>;
     __shared__ float lds[X::LDS_FLOATS];
     __shared__ double red[X::THREADS / 64];
     constexpr int p = kHixP;
-    (void)p_arg;
+    constexpr int NW = X::RP / 32;
     const uint32_t c = blockIdx.y;
     const uint32_t tile0 = xcd_local_tile<16 / TPW>() * TPW;
-    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
-    const uint32_t g0 = 2u * wave_in_block();                    // the two groups of this wave: g0, g0 + 1
-    const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));              // reads past d give the zero padding
-    const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), 4u << log2D);
+    const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
+    const uint32_t rows_written = (uint32_t)((d + (1u << p) - 1) >> p);
+    const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), rows_written << (p + 2));
+    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const uint32_t b_q8 = B.b_q8[c];
+    const EncScratch *sc = &scratch[c];
     const uint32_t off1 = ((g << p) + col) * 4u;                         // stage-1 rows: g + RL r
-    const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;      // stage-2 rows: rl + RL (ph RP + g RHL + e)
-    const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
-    double n2 = 0.0;
+    float ip = 0.0f;
+    uint32_t held[TPW][X::PH][NW];
     float v[64];
     {
         const uint32_t b0 = (uint32_t)hix_base<M>(tile0, p) * 4u;
 #pragma unroll
-        for (int r = 0; r < 64; ++r) v[r] = buf_load(rx, off1, b0 + (((uint32_t)X::RL * r) << (p + 2)));
+        for (int r = 0; r < 64; ++r) v[r] = buf_load(rt, off1, b0 + (((uint32_t)X::RL * r) << (p + 2)));
     }
 #pragma unroll
     for (int k = 0; k < TPW; ++k) {
         const uint64_t base = hix_base<M>(tile0 + k, p);
-        const uint32_t base_off = (uint32_t)base * 4u;
         const uint32_t next_off = (uint32_t)hix_base<M>(tile0 + k + 1, p) * 4u;
-#pragma unroll
-        for (int r = 0; r < 64; ++r) n2 += (double)v[r] * (double)v[r];
-        // lane l hashes the sign bits of register l's two row segments; register r reads them back as a lane mask
-        const uint32_t wa = sign_half_word(key, base + ((uint64_t)hix_row1<M>(g0, lane) << p));
-        const uint32_t wb = sign_half_word(key, base + ((uint64_t)hix_row1<M>(g0 + 1, lane) << p));
-#pragma unroll
-        for (int r = 0; r < 64; ++r) v[r] = negate_where(v[r], pair_mask(wa, wb, r)) + 0.0f;   // + 0: no negative zeros
         fwht_regs<64>(v);
         float out[X::RP];
-        hix_exchange_write<M, 0>(v, lds);
-        if (k + 1 < TPW) {
 #pragma unroll
-            for (int r = 0; r < X::RP; ++r) v[r] = buf_load(rx, off1, next_off + (((uint32_t)X::RL * r) << (p + 2)));
-        }
-        hix_exchange_read<M>(lds, out);
-#pragma unroll
-        for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 0, s) << (p + 2)), out[s]);
-        if constexpr (X::PH == 2) {
-            hix_exchange_write<M, 1>(v, lds);
+        for (int ph = 0; ph < X::PH; ++ph) {
+            if (ph == 0) hix_exchange_write<M, 0>(v, lds);
+            else hix_exchange_write<M, X::PH - 1>(v, lds);
             if (k + 1 < TPW) {
 #pragma unroll
-                for (int r = X::RP; r < 64; ++r) v[r] = buf_load(rx, off1, next_off + (((uint32_t)X::RL * r) << (p + 2)));
+                for (int r = ph * X::RP; r < (ph + 1) * X::RP; ++r)
+                    v[r] = buf_load(rt, off1, next_off + (((uint32_t)X::RL * r) << (p + 2)));
             }
             hix_exchange_read<M>(lds, out);
-#pragma unroll
-            for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 1, s) << (p + 2)), out[s]);
+            if (UNIT || b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
+            else if (b_q8 == 512u) hix_quantize_pack<M, 2>(out, ph, sc, payload, (uint32_t)(base >> 5), ip);
+            else hix_quantize_pack<M, 4>(out, ph, sc, payload, (uint32_t)(base >> 5), ip);
         }
     }
-    const double block_total = block_sum<X::THREADS>(n2, red);
+    if (UNIT || b_q8 <= 256u) {
+        // tile0 is a multiple of TPW: the TPW words of a row are neighbours, aligned to their common size
+        const uint64_t base0 = hix_base<M>(tile0, p);
+        const uint32_t word0 = (uint32_t)(base0 >> 5);
+        const uint64_t subkey = stream_key(seed, kStreamSubsample, B.client[c]);
+#pragma unroll
+        for (int ph = 0; ph < X::PH; ++ph) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const uint32_t row = hix_word_row<M>(ph, w);
+                const uint32_t word = word0 + (row << (p - 5));
+                uint32_t o[TPW];
+                if (b_q8 == 256u) {
+#pragma unroll
+                    for (int k = 0; k < TPW; ++k) o[k] = held[k][ph][w];
+                    typename WordVec<TPW>::type pack;
+                    __builtin_memcpy(&pack, o, sizeof(pack));
+                    *reinterpret_cast<typename WordVec<TPW>::type *>(payload + word) = pack;
+                } else {
+                    // b = 1/2 (Sec. 4.1): of each pair (2k, 2k+1) send the coordinate chosen by the sub-sampling
+                    // stream; 64 pairs per hash word = 128 coordinates = four neighbouring row segments
+                    const uint64_t first = base0 + ((uint64_t)row << p);
+                    const uint64_t hw = hash_word(subkey, first >> 7) >> (16u * (uint32_t)((first >> 5) & 3u));
+                    uint16_t *half = reinterpret_cast<uint16_t *>(payload) + word;
+#pragma unroll
+                    for (int k = 0; k < TPW; ++k) {
+                        const uint32_t off = (uint32_t)(hw >> (16 * k)) & 0xFFFFu;
+                        const uint32_t ev = even_bits(held[k][ph][w]), od = even_bits(held[k][ph][w] >> 1);
+                        o[k] = (ev & ~off) | (od & off);
+                    }
+                    if constexpr (TPW == 1) half[0] = (uint16_t)o[0];
+                    else if constexpr (TPW == 2) *reinterpret_cast<uint32_t *>(half) = o[0] | (o[1] << 16);
+                    else *reinterpret_cast<uint2 *>(half) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
+                }
+            }
+        }
+    }
+    const double block_total = block_sum<X::THREADS>((double)ip, red);
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
 }
 
+// Middle pass of the three-pass sizes, in place on the workspace (tiles are disjoint).  Elements at or above
+// `load_elems` were not written by the pass before (encode: zero padding) and read as zero; elements at or above
+// `store_elems` are not read by the pass after (decode: they end in the padding) and are not written.  A tile
+// that lies wholly beyond either bound has nothing to do.
 template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D, int p_arg) {
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D, uint64_t load_elems, uint64_t store_elems) {
     using X = HiX<M>;
     __shared__ float lds[X::LDS_FLOATS];
     constexpr int p = kHixP;
-    (void)p_arg;
     const uint64_t base = hix_base<M>(blockIdx.x, p);
+    const uint64_t block_start = base >> (p + M) << (p + M);
+    if (block_start >= load_elems || block_start >= store_elems) return;     // same decision in the whole workgroup
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
-    const rsrc_t rt = make_rsrc(T + ((size_t)blockIdx.y << log2D), 4u << log2D);
+    const rsrc_t rl = make_rsrc(T + ((size_t)blockIdx.y << log2D), (uint32_t)(load_elems * 4));
+    const rsrc_t rs = make_rsrc(T + ((size_t)blockIdx.y << log2D), (uint32_t)(store_elems * 4));
     const uint32_t base_off = (uint32_t)base * 4u;
     const uint32_t off1 = ((g << p) + col) * 4u;
     const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;
     float v[64];
 #pragma unroll
-    for (int r = 0; r < 64; ++r) v[r] = buf_load(rt, off1, base_off + (((uint32_t)X::RL * r) << (p + 2)));
+    for (int r = 0; r < 64; ++r) v[r] = buf_load(rl, off1, base_off + (((uint32_t)X::RL * r) << (p + 2)));
     fwht_regs<64>(v);
     float out[X::RP];
     hix_exchange<M, 0>(v, lds, out);
 #pragma unroll
-    for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 0, s) << (p + 2)), out[s]);
+    for (int s = 0; s < X::RP; ++s) buf_store(rs, off2, base_off + (hix_row2<M>(0, 0, s) << (p + 2)), out[s]);
     if constexpr (X::PH == 2) {
         hix_exchange<M, 1>(v, lds, out);
 #pragma unroll
-        for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, base_off + (hix_row2<M>(0, 1, s) << (p + 2)), out[s]);
+        for (int s = 0; s < X::RP; ++s) buf_store(rs, off2, base_off + (hix_row2<M>(0, 1, s) << (p + 2)), out[s]);
     }
 }
 
@@ -208,7 +312,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D
 // workspace is int16), zero for coordinates that were not sampled or whose packet was lost, then index bits
 // 14 .. 14+M-1 of H.
 template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, int log2D, uint64_t seed,
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                     const DecScratch *scratch, int narrow, float *T) {
     using X = HiX<M>;
     constexpr int p = kHixP;
@@ -296,10 +400,12 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, i
     const uint32_t base_off = (uint32_t)base * 4u;
     const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;
     const char *slot = reinterpret_cast<const char *>(T + ((size_t)c << log2D));
+    // rows at or above ceil(d / 2^14) are never read by the last pass: the bounds drop their stores
+    const uint32_t rows_used = (uint32_t)((d + (1u << p) - 1) >> p);
     float out[X::RP];
     if (i16) {
         // exact integers of magnitude <= 2^M: int16 at the same element index
-        const rsrc_t rt = make_rsrc(slot + (base_off >> 1), (2u << log2D) - (base_off >> 1));
+        const rsrc_t rt = make_rsrc(slot + (base_off >> 1), (rows_used << (p + 1)) - (base_off >> 1));
         hix_exchange<M, 0>(v, lds, out);
 #pragma unroll
         for (int s = 0; s < X::RP; ++s)
@@ -311,7 +417,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, i
                 __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 1, s) << (p + 2)) >> 1), kStream);
         }
     } else {
-        const rsrc_t rt = make_rsrc(slot + base_off, (4u << log2D) - base_off);
+        const rsrc_t rt = make_rsrc(slot + base_off, (rows_used << (p + 2)) - base_off);
         hix_exchange<M, 0>(v, lds, out);
 #pragma unroll
         for (int s = 0; s < X::RP; ++s) buf_store(rt, off2, hix_row2<M>(0, 0, s) << (p + 2), out[s]);
@@ -346,7 +452,7 @@ __device__ inline void fwht_pk(s16x2 (&v)[N]) {
 }
 
 template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first_pk(DecBatch B, int log2D, uint64_t seed, float *T) {
+__global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first_pk(DecBatch B, uint64_t d, int log2D, uint64_t seed, float *T) {
     using X = HiX<M>;
     constexpr int p = kHixP;
     __shared__ uint32_t lds[X::LDS_FLOATS];
@@ -410,7 +516,9 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first_pk(DecBatch B
     fwht_pk<64, 6>(v);
     // int16 element i of the sender's slot sits at byte 2 i: the pair of this thread is one 32-bit store
     char *slot = reinterpret_cast<char *>(T + ((size_t)c << log2D)) + base * 2u;
-    const rsrc_t rt = make_rsrc(slot, (2u << log2D) - (uint32_t)base * 2u);
+    // rows at or above ceil(d / 2^14) are never read by the last pass: the bounds drop their stores
+    const uint32_t rows_used = (uint32_t)((d + (1u << p) - 1) >> p);
+    const rsrc_t rt = make_rsrc(slot, (rows_used << (p + 1)) - (uint32_t)base * 2u);
     const uint32_t off2 = (((g * X::RHL * X::RL) << p) * 2u) + cp * 4u;
     const uint32_t col = cp;                                     // exchange slot of this thread
 #pragma unroll
@@ -444,35 +552,43 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first_pk(DecBatch B
 
 static uint32_t hix_tiles(int M, int log2D) { return 1u << (log2D - M - 5); }
 
-uint32_t launch_hix_first(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, int p, uint64_t seed, float *T,
-                          double *partials, uint32_t partial_stride, hipStream_t st) {
-    const uint32_t tiles = hix_tiles(M, log2D);
-    if (tiles % 256u == 0) {                                     // two neighbouring tiles per workgroup
-        dim3 grid(tiles / 2, n);
-        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_hix_first<MM, 2>), grid, dim3(HiX<MM>::THREADS), 0, st, B, d,
-                                              log2D, p, seed, T, partials, partial_stride));
+uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+                             double *partials, uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
+    const uint32_t tiles = hix_tiles(M, log2D);                  // 512 whenever this pass sits directly on lo14
+    bool unit = true;                                            // every sender b <= 1
+    for (uint32_t c = 0; c < n; ++c) unit = unit && B.b_q8[c] <= 256u;
+    if (unit && tiles % 128u == 0) {                             // four neighbouring tiles per workgroup
+        dim3 grid(tiles / 4, n);
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, 4, true>), grid, dim3(HiX<MM>::THREADS), 0, st,
+                                              B, d, log2D, seed, T, partials, partial_stride, scratch));
+        return grid.x;
+    }
+    if (M < 10 && tiles % 256u == 0) {                           // two neighbouring tiles per workgroup (M = 10 would
+        dim3 grid(tiles / 2, n);                                 // need more than 128 registers: one workgroup per CU)
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, 2, false>), grid, dim3(HiX<MM>::THREADS), 0, st,
+                                              B, d, log2D, seed, T, partials, partial_stride, scratch));
         return grid.x;
     }
     dim3 grid(tiles, n);
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_hix_first<MM, 1>), grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D,
-                                          p, seed, T, partials, partial_stride));
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, 1, false>), grid, dim3(HiX<MM>::THREADS), 0, st, B,
+                                          d, log2D, seed, T, partials, partial_stride, scratch));
     return grid.x;
 }
-void launch_hix_mid(int M, uint32_t n, float *T, int log2D, int p, hipStream_t st) {
+void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems, uint64_t store_elems, hipStream_t st) {
     dim3 grid(hix_tiles(M, log2D), n);
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_mid<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D, p));
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_mid<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D, load_elems, store_elems));
 }
-void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, int log2D, uint64_t seed, const DecScratch *scratch,
-                          int narrow, float *T, hipStream_t st) {
+void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+                          const DecScratch *scratch, int narrow, float *T, hipStream_t st) {
     bool all_unit = narrow != 0;                                 // every sender b <= 1: packed int16 kernel
     for (uint32_t c = 0; c < n; ++c) all_unit = all_unit && B.b_q8[c] <= 256u;
     if (all_unit) {
         dim3 grid(hix_tiles(M, log2D) / 2, n);                   // 64-column tiles
-        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first_pk<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, log2D, seed, T));
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first_pk<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D, seed, T));
         return;
     }
     dim3 grid(hix_tiles(M, log2D), n);
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, log2D, seed, scratch,
-                                          narrow, T));
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D, seed,
+                                          scratch, narrow, T));
 }
 }  // namespace eden

@@ -31,7 +31,7 @@ EXPORTS = [
     "eden_make_subsample_bits", "eden_get_tables", "eden_strerror", "eden_profile_enable", "eden_profile_collect",
     "eden_kernel_name",
 ]
-KERNEL_KINDS = ["enc_hi_first", "hi_mid", "enc_lo", "dec_prepare", "dec_hi_first", "dec_lo_last", "finalize_mean",
+KERNEL_KINDS = ["enc_first", "mid", "enc_last", "dec_prepare", "dec_first", "dec_last", "finalize_mean",
                 "enc_small", "dec_small", "enc_norm", "enc_finish"]
 
 

@@ -38,6 +38,7 @@ def _run_case(ctx, xs, client_ids, budgets, seed, drop_q32=0, also_oracle_msgs=T
         parity.check_encode(xs[c], seed, client_ids[c], budgets[c], gm, stats)
         omsgs.append(gm)
     parity.finish_encode(stats)
+    print("encode:", stats, flush=True)
 
     bitmaps_np, bitmaps_dev = None, None
     if drop_q32:
@@ -224,3 +225,10 @@ def test_argument_errors(ctx):
     assert eden.message_bytes((1 << 27) + 1, 256) == 0
     torch.cuda.synchronize()
     ctx.last_device_status()
+
+
+@pytest.mark.gpu
+def test_mismatch_fraction_over_all_cases():
+    # runs last in this file: every encode comparison made so far in this process is in the pool
+    pool = parity.check_pool()
+    print("all cases:", pool, flush=True)
