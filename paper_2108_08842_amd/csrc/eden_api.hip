@@ -24,6 +24,9 @@ struct eden_ctx {
     float *T;                // slots * D_max floats (nullptr if D_max <= 4096)
     double *partials;        // 2 * slots * partial_stride doubles: |x|^2 partials, then sum u q partials
     uint32_t partial_stride;
+    uint32_t compute_units;      // of the context's device
+    float *dec_partial;          // sums of sender groups when the last decode pass splits tiles (D_max >= 2^19)
+    uint32_t dec_partial_tiles;  // its size in tiles of 2^14 floats
     EncScratch *enc_scratch; // slots
     DecScratch *dec_scratch; // slots
     DevTables *tables;
@@ -136,10 +139,17 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     ctx->slots = n_max < (uint32_t)kMaxBatch ? n_max : (uint32_t)kMaxBatch;
     const uint64_t D_max = 1ull << ctx->log2D_max;
     ctx->partial_stride = (uint32_t)(D_max / 256 + 16);
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, hip_device) != hipSuccess || cus <= 0) cus = 256;
+    ctx->compute_units = (uint32_t)cus;
 
     bool ok = true;
     if (ctx->log2D_max > kLoBits)
         ok = ok && hipMalloc(&ctx->T, (size_t)ctx->slots * D_max * sizeof(float)) == hipSuccess;
+    if (ctx->log2D_max >= 19 && ctx->slots > 1) {                // one round of split tiles at most
+        ctx->dec_partial_tiles = 2 * ctx->compute_units;
+        ok = ok && hipMalloc(&ctx->dec_partial, ((size_t)ctx->dec_partial_tiles << 14) * sizeof(float)) == hipSuccess;
+    }
     ok = ok && hipMalloc(&ctx->partials, 2 * (size_t)ctx->slots * ctx->partial_stride * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->enc_scratch, ctx->slots * sizeof(EncScratch)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->dec_scratch, ctx->slots * sizeof(DecScratch)) == hipSuccess;
@@ -171,7 +181,7 @@ int eden_destroy(eden_ctx *ctx) {
     bool ok = guard.ok;
     for (hipEvent_t e : ctx->prof_start) ok = (hipEventDestroy(e) == hipSuccess) && ok;
     for (hipEvent_t e : ctx->prof_stop) ok = (hipEventDestroy(e) == hipSuccess) && ok;
-    void *ptrs[] = {ctx->T, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
+    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
     for (void *p : ptrs)
         if (p) ok = (hipFree(p) == hipSuccess) && ok;
     delete ctx;
@@ -300,7 +310,9 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
                 }
             }
             Timed t(ctx, EDEN_K_DEC_LAST, nb, st);
-            if (pl.lo_bits == 14) launch_dec_lo14_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
+            if (pl.lo_bits == 14)
+                launch_dec_lo14_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, 2 * ctx->compute_units,
+                                     ctx->dec_partial, ctx->dec_partial_tiles, st);
             else launch_dec_lo_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;

@@ -47,8 +47,11 @@ void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
 // 14-bit contiguous passes for D >= 2^19 (eden_kernels_lo14.hip)
 uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T,
                                double *partials, uint32_t partial_stride, hipStream_t st);
+// `resident`: workgroups of the kernel the device holds at once (2 per CU); `partial`: room for `partial_tiles`
+// tiles of 2^14 floats, used when tiles are split over several workgroups by sender
 void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
-                          const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
+                          const DecScratch *scratch, int narrow, float *acc, uint32_t resident, float *partial,
+                          uint32_t partial_tiles, hipStream_t st);
 
 }  // namespace eden
 #endif

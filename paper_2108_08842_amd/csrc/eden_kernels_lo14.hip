@@ -106,7 +106,10 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
 #pragma unroll
         for (int a = 0; a < 32; ++a) u[a] = next[a];
 #pragma unroll
-        for (int a = 0; a < 32; ++a) n2 += (double)u[a] * (double)u[a];
+        for (int a = 0; a < 32; ++a) {
+            n2 += (double)u[a] * (double)u[a];
+            if ((a & 7) == 7) __builtin_amdgcn_sched_barrier(0);     // keeps the widened values of one group live at a time
+        }
         // register a of this wave = 64 consecutive coordinates = one sign word: lane l < 32 hashes the word of
         // register l, register a reads it back as a lane mask
         const uint64_t mine = hash_word(key, ((uint64_t)tile << (kLo14Bits - 6)) + 8u * (lane & 31u) + wv);
@@ -128,37 +131,53 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
 // Sec. 2.2.2), sum over senders in registers, one contiguous read-modify-write of acc.
 // `narrow`: senders with b <= 1 have an int16 workspace holding exact integers; their magnitude S/(p sqrt D) q_1
 // is applied together with the sign.
+//
+// Work split.  A workgroup's time is proportional to the senders it sums and the chip holds `2 x CUs` of these
+// workgroups at once, so a tile count far below that would leave most of the chip idle.  The first `full_tiles`
+// tiles get one workgroup each that sums all n senders into acc.  Each of the remaining tiles gets K workgroups: group 0 sums its share of the senders into acc,
+// group k > 0 stores its sum in partial[k-1][tile - full_tiles][2^14]; k_dec_lo14_combine then adds those to
+// acc in the order k = 1, 2, ... (fixed, so the result does not depend on scheduling).
 __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
-                                                       const float *T, const DecScratch *scratch, int narrow, float *acc) {
+                                                       const float *T, const DecScratch *scratch, int narrow, float *acc,
+                                                       uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
+                                                       float *partial) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14LdsWords];
-    const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
-    if (tile_base >= d) return;                                  // whole tile in the padding
     const uint32_t t = threadIdx.x, lane = t & 63u, wv = t >> 6;
-    const uint64_t first = tile_base + 512u * (t >> 4) + 32u * (t & 15u);
+    uint32_t tile = blockIdx.x, c_begin = 0, c_end = n;
+    float *part_run = nullptr;                                   // this thread's 32 values in the partial buffer
+    if (blockIdx.x >= full_tiles) {
+        const uint32_t idx = blockIdx.x - full_tiles, k = idx % K;
+        tile = full_tiles + idx / K;
+        c_begin = (uint32_t)(((uint64_t)n * k) / K);
+        c_end = (uint32_t)(((uint64_t)n * (k + 1)) / K);
+        if (k > 0) part_run = partial + (((size_t)(k - 1) * split_tiles + (tile - full_tiles)) << kLo14Bits) + 32u * t;
+    }
+    const uint64_t tile_base = (uint64_t)tile << kLo14Bits;
+    const uint64_t first = tile_base + 32u * t;
     const size_t in_off = tile_base + wv * 64u + lane;
     float sum[32];
 #pragma unroll
     for (int e = 0; e < 32; ++e) sum[e] = 0.0f;
 
-    auto load = [&](uint32_t c, float (&dst)[32]) {
+    auto load = [&](uint32_t c, float (&dst_regs)[32]) {
         if (narrow && B.b_q8[c] <= 256u) {
             const short *t16 = reinterpret_cast<const short *>(T + ((size_t)c << log2D)) + in_off;
 #pragma unroll
-            for (int a = 0; a < 32; ++a) dst[a] = __int_as_float((int)__builtin_nontemporal_load(t16 + 512 * a));
+            for (int a = 0; a < 32; ++a) dst_regs[a] = __int_as_float((int)__builtin_nontemporal_load(t16 + 512 * a));
         } else {
             const float *t32 = T + ((size_t)c << log2D) + in_off;
 #pragma unroll
-            for (int a = 0; a < 32; ++a) dst[a] = __builtin_nontemporal_load(t32 + 512 * a);
+            for (int a = 0; a < 32; ++a) dst_regs[a] = __builtin_nontemporal_load(t32 + 512 * a);
         }
     };
     float next[32];
-    load(0, next);
-    for (uint32_t c = 0; c < n; ++c) {
+    if (c_begin < c_end) load(c_begin, next);
+    for (uint32_t c = c_begin; c < c_end; ++c) {
         const bool i16 = narrow && B.b_q8[c] <= 256u;
         float u[32];
 #pragma unroll
         for (int a = 0; a < 32; ++a) u[a] = i16 ? (float)__float_as_int(next[a]) : next[a];
-        if (c + 1 < n) load(c + 1, next);
+        if (c + 1 < c_end) load(c + 1, next);
         lo14_forward32(u, lds);
         const uint32_t scale = __float_as_uint(i16 ? scratch[c].deq[1] : 1.0f) & 0x7FFFFFFFu;   // > 0; x*1+s is exact
         // the wave's 2048 coordinates use 32 sign words: lane l < 32 hashes word l, every thread fetches its own
@@ -175,7 +194,11 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
         }
         __syncthreads();                                         // LDS is reused by the next sender
     }
-    if (tile_base + (1u << kLo14Bits) <= d) {
+    if (part_run) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            *reinterpret_cast<float4 *>(part_run + 4 * q) = make_float4(sum[4 * q], sum[4 * q + 1], sum[4 * q + 2], sum[4 * q + 3]);
+    } else if (tile_base + (1u << kLo14Bits) <= d) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             float4 a = *reinterpret_cast<const float4 *>(acc + first + 4 * q);
@@ -189,12 +212,31 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     }
 }
 
+// acc[i] += partial[0][i'] + partial[1][i'] + ... for the tiles that k_dec_lo14_last split over K workgroups
+// (added one after the other, in this order).  One thread per four coordinates.
+__global__ __launch_bounds__(256) void k_dec_lo14_combine(float *acc, uint64_t d, uint32_t full_tiles, uint32_t K,
+                                                          uint32_t split_tiles, const float *partial) {
+    const uint64_t local = ((uint64_t)blockIdx.x * 256u + threadIdx.x) * 4u;         // inside the split tiles
+    const uint64_t i = ((uint64_t)full_tiles << kLo14Bits) + local;
+    if (local >= ((uint64_t)split_tiles << kLo14Bits) || i >= d) return;
+    float s[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s[e] = (i + e < d) ? acc[i + e] : 0.0f;
+    for (uint32_t k = 1; k < K; ++k) {
+        const float4 p = *reinterpret_cast<const float4 *>(partial + (((size_t)(k - 1) * split_tiles) << kLo14Bits) + local);
+        s[0] += p.x; s[1] += p.y; s[2] += p.z; s[3] += p.w;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (i + e < d) acc[i + e] = s[e];
+}
+
 uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T,
                                double *partials, uint32_t partial_stride, hipStream_t st) {
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);
-    if (tiles >= 512) {
-        dim3 grid((tiles + 3) / 4, n);
-        hipLaunchKernelGGL(k_enc_lo14_first<4>, grid, dim3(512), 0, st, B, d, log2D, seed, T, partials, partial_stride);
+    if (tiles >= 256) {                                          // pairs of tiles: the second one's loads overlap the first
+        dim3 grid((tiles + 1) / 2, n);
+        hipLaunchKernelGGL(k_enc_lo14_first<2>, grid, dim3(512), 0, st, B, d, log2D, seed, T, partials, partial_stride);
         return grid.x;
     }
     dim3 grid(tiles, n);
@@ -202,9 +244,26 @@ uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int lo
     return grid.x;
 }
 void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
-                          const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
-    dim3 grid(1u << (log2D - kLo14Bits));
-    hipLaunchKernelGGL(k_dec_lo14_last, grid, dim3(512), 0, st, B, n, d, log2D, seed, T, scratch, narrow, acc);
+                          const DecScratch *scratch, int narrow, float *acc, uint32_t resident, float *partial,
+                          uint32_t partial_tiles, hipStream_t st) {
+    const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);     // tiles that reach below d
+    // Fewer tiles than half the resident workgroups: split every tile K ways by sender so that the chip is filled
+    // (measured 2.2x on 64 tiles x 32 senders).  With more tiles than resident workgroups, splitting only the
+    // last, partly filled round was measured 3..10% slower than leaving it: a CU with one workgroup runs it faster.
+    uint32_t full = 0, rest = tiles, K = 1;
+    if (2 * tiles <= resident) {
+        K = resident / tiles;
+        if (K > n) K = n;
+        while (K > 1 && (uint64_t)(K - 1) * rest > partial_tiles) --K;    // what the partial buffer holds
+    }
+    if (K == 1) { full = tiles; rest = 0; }
+    dim3 grid(full + rest * K);
+    hipLaunchKernelGGL(k_dec_lo14_last, grid, dim3(512), 0, st, B, n, d, log2D, seed, T, scratch, narrow, acc, full, K, rest,
+                       partial);
+    if (K > 1) {
+        dim3 cgrid((uint32_t)((((uint64_t)rest << kLo14Bits) / 4 + 255) / 256));
+        hipLaunchKernelGGL(k_dec_lo14_combine, cgrid, dim3(256), 0, st, acc, d, full, K, rest, partial);
+    }
 }
 
 }  // namespace eden
