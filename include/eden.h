@@ -147,6 +147,14 @@ int eden_make_sign_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, uint64
 int eden_make_subsample_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, uint64_t D,
                              uint64_t *bits_dev, void *stream);
 
+/* Experiment helper (not on the hot path): out_dev[0] = sum_i (a_i - b_i)^2, out_dev[1] = sum_i a_i^2 over
+ * i < d, accumulated in double, deterministic.  With a = x and b = the decoded estimate, out[0] / out[1] is
+ * the squared error normalised by |x|^2 whose expectation is the vNMSE (Sec. 2.3, Thm 2.3); with a = the true
+ * mean of n vectors, out[0] * n / sum_c |x_c|^2 is the NMSE of Sec. 2.1.
+ * a_dev, b_dev: device, fp32[d], read only.  out_dev: device, 2 doubles, written.  Asynchronous on `stream`;
+ * uses the context's encoder scratch, so it must not overlap an eden_encode on another stream. */
+int eden_sq_error(eden_ctx *ctx, const float *a_dev, const float *b_dev, uint64_t d, double *out_dev, void *stream);
+
 /* Copies the library's own Lloyd-Max tables for an integer budget `bits` (1..4) to host arrays:
  * thresholds[2^bits - 1] and centroids[2^bits], ascending, double precision (Sec. 3). */
 int eden_get_tables(uint32_t bits, double *thresholds, double *centroids);

@@ -376,6 +376,16 @@ int eden_make_subsample_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, u
     return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
 }
 
+int eden_sq_error(eden_ctx *ctx, const float *a_dev, const float *b_dev, uint64_t d, double *out_dev, void *stream) {
+    if (!ctx || !a_dev || !b_dev || !out_dev || d == 0) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    // the partial-sum area of the encoder doubles as scratch: 2 doubles per workgroup
+    const uint32_t max_parts = ctx->slots * ctx->partial_stride;
+    launch_sq_error(a_dev, b_dev, d, ctx->partials, max_parts, out_dev, static_cast<hipStream_t>(stream));
+    return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
+}
+
 int eden_get_tables(uint32_t bits, double *thresholds, double *centroids) {
     const EdenHalfTable *ht = eden_half_table((int)bits);
     if (!ht || !thresholds || !centroids) return EDEN_ERR_INVALID_ARG;

@@ -34,6 +34,8 @@ void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint
                       uint32_t *dev_status, hipStream_t st);
 void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                       float *acc, uint32_t *dev_status, hipStream_t st);
+void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
+                     hipStream_t st);
 void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st);
 void launch_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t *bitmap, hipStream_t st);
 

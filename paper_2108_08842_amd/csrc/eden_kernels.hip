@@ -471,6 +471,29 @@ __global__ void k_finalize_mean(const float *acc, uint64_t d, float n, float *me
     }
 }
 
+// Experiment helper: sum_i (a_i - b_i)^2 and sum_i a_i^2 in double, the two terms of the (v)NMSE definitions
+// (Sec. 2.1: NMSE; Sec. 2.3: vNMSE).  Per-workgroup partials, then one workgroup adds them in index order.
+__global__ __launch_bounds__(256) void k_sq_error(const float *a, const float *b, uint64_t d, double *partials) {
+    __shared__ double red[4];
+    double e2 = 0.0, a2 = 0.0;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < d; i += (uint64_t)gridDim.x * 256u) {
+        const double x = a[i], y = b[i];
+        e2 += (x - y) * (x - y);
+        a2 += x * x;
+    }
+    const double te = block_sum<256>(e2, red);
+    const double ta = block_sum<256>(a2, red);
+    if (threadIdx.x == 0) { partials[2 * blockIdx.x] = te; partials[2 * blockIdx.x + 1] = ta; }
+}
+__global__ __launch_bounds__(256) void k_sq_error_finish(const double *partials, uint32_t nparts, double *out) {
+    __shared__ double red[4];
+    double e2 = 0.0, a2 = 0.0;
+    for (uint32_t i = threadIdx.x; i < nparts; i += 256) { e2 += partials[2 * i]; a2 += partials[2 * i + 1]; }
+    const double te = block_sum<256>(e2, red);
+    const double ta = block_sum<256>(a2, red);
+    if (threadIdx.x == 0) { out[0] = te; out[1] = ta; }
+}
+
 // ------------------------------------------------------------------------------------------------
 // D <= 4096: one workgroup per sender, the padded vector lives in LDS.
 __device__ inline void fwht_lds(float *buf, uint32_t D) {
@@ -688,6 +711,15 @@ void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean,
     const uint64_t per_block = 256u * (vec ? 4u : 1u);
     const uint32_t blocks = (uint32_t)((d + per_block - 1) / per_block);
     hipLaunchKernelGGL(k_finalize_mean, dim3(blocks), dim3(256), 0, st, acc, d, (float)n, mean, vec);
+}
+void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
+                     hipStream_t st) {
+    uint32_t blocks = (uint32_t)((d + 1023) / 1024);
+    if (blocks > 1024u) blocks = 1024u;
+    if (blocks > max_parts) blocks = max_parts;
+    if (blocks < 1u) blocks = 1u;
+    hipLaunchKernelGGL(k_sq_error, dim3(blocks), dim3(256), 0, st, a, b, d, partials);
+    hipLaunchKernelGGL(k_sq_error_finish, dim3(1), dim3(256), 0, st, partials, blocks, out);
 }
 void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
                       uint32_t *dev_status, hipStream_t st) {

@@ -29,7 +29,7 @@ EXPORTS = [
     "eden_create", "eden_destroy", "eden_message_bytes", "eden_encode", "eden_decode_accumulate",
     "eden_finalize_mean", "eden_last_device_status", "eden_make_loss_bitmap", "eden_make_sign_bits",
     "eden_make_subsample_bits", "eden_get_tables", "eden_strerror", "eden_profile_enable", "eden_profile_collect",
-    "eden_kernel_name",
+    "eden_kernel_name", "eden_sq_error",
 ]
 KERNEL_KINDS = ["enc_first", "mid", "enc_last", "dec_prepare", "dec_first", "dec_last", "finalize_mean",
                 "enc_small", "dec_small", "enc_norm", "enc_finish"]
@@ -83,6 +83,8 @@ def lib():
     L.eden_profile_collect.restype = ci
     L.eden_kernel_name.argtypes = [u32]
     L.eden_kernel_name.restype = ctypes.c_char_p
+    L.eden_sq_error.argtypes = [vp, vp, vp, u64, vp, vp]
+    L.eden_sq_error.restype = ci
     _lib = L
     return L
 
@@ -228,6 +230,19 @@ class Context:
                                          ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
         if rc != OK:
             raise EdenError(rc, "eden_make_loss_bitmap")
+        return out
+
+    def sq_error(self, a, b, out=None, stream=None):
+        """-> device tensor of 2 doubles: sum (a - b)^2, sum a^2 (asynchronous)."""
+        import torch
+        assert a.is_cuda and b.is_cuda and a.dtype == torch.float32 and b.dtype == torch.float32
+        assert a.is_contiguous() and b.is_contiguous() and a.numel() == b.numel()
+        if out is None:
+            out = torch.empty(2, dtype=torch.float64, device=a.device)
+        rc = lib().eden_sq_error(self._h, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()), a.numel(),
+                                 ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
+        if rc != OK:
+            raise EdenError(rc, "eden_sq_error")
         return out
 
     def make_sign_bits(self, seed: int, client: int, D: int, stream=None):

@@ -1,0 +1,137 @@
+"""Empirical vNMSE / NMSE of EDEN on the GPU next to the paper's asymptotic values.
+
+    python -m paper_2108_08842_amd.vnmse --dist lognormal --log2d 20 --budgets 0.5 1 2 4 --trials 32 --senders 8
+
+For every budget b the vector x is encoded by `trials` independent senders (same x, different client ids, so
+independent rotations), each message is decoded on its own and |x - x_hat|^2 / |x|^2 is averaged: that is the
+vNMSE of Sec. 2.3.  Theory (d -> infinity): 1 / E[Q^2] - 1 for b >= 1 (Cor. 2.4 with the Lloyd-Max levels of
+Sec. 3: pi/2 - 1 at b = 1), and 1 / (p E[Q^2]) - 1 when only a fraction p of the rotated coordinates is sent or
+arrives (Lemma 4.3; b = 1/2 sends p = 1/2 of them with the 1-bit quantizer: pi - 1).  For `senders` different
+vectors the NMSE of the estimated mean is compared with Thm 2.2's (1/n^2) sum_c vNMSE_c |x_c|^2 / ((1/n) sum_c |x_c|^2).
+
+The inputs are synthetic draws of the distributions the paper's appendix uses for this experiment
+(LogNormal(0,1), Normal(0,1), Exponential(1), chi^2(1), Half-Normal, Beta(2,5)); torch generates them on the device.
+Everything that is measured runs in the library's kernels; torch only holds the memory.
+"""
+from __future__ import annotations
+
+import argparse
+import math
+
+
+def expected_q2(bits: int) -> float:
+    """E[Q(z)^2] for z ~ N(0,1) and the library's Lloyd-Max table of 2^bits levels (Sec. 3)."""
+    from . import eden
+    t, q = eden.get_tables(bits)
+    edges = [-math.inf] + list(t) + [math.inf]
+    cdf = lambda v: 0.5 * (1.0 + math.erf(v / math.sqrt(2.0)))
+    return sum((cdf(edges[k + 1]) - cdf(edges[k])) * q[k] ** 2 for k in range(len(q)))
+
+
+def theory_vnmse(b: float, keep: float = 1.0) -> float:
+    """Asymptotic vNMSE for budget b (0.5, or an integer >= 1) when a fraction `keep` of the packets arrives."""
+    bits = max(1, int(b))
+    p = keep * min(1.0, b)
+    return 1.0 / (p * expected_q2(bits)) - 1.0
+
+
+def draw(dist: str, d: int, gen, device):
+    import torch
+    n = lambda: torch.randn(d, generator=gen, device=device, dtype=torch.float32)
+    if dist == "normal":
+        return n()
+    if dist == "lognormal":
+        return torch.exp(n())
+    if dist == "exponential":
+        return -torch.log1p(-torch.rand(d, generator=gen, device=device, dtype=torch.float32))
+    if dist == "chi2":
+        return n() ** 2
+    if dist == "halfnormal":
+        return n().abs()
+    if dist == "beta":            # Beta(2,5) as a ratio of sums of exponentials (Gamma(2) / (Gamma(2) + Gamma(5)))
+        e = lambda k: sum(-torch.log1p(-torch.rand(d, generator=gen, device=device, dtype=torch.float32)) for _ in range(k))
+        a, c = e(2), e(5)
+        return a / (a + c)
+    raise ValueError(dist)
+
+
+DISTS = ["lognormal", "normal", "exponential", "chi2", "halfnormal", "beta"]
+
+
+def measure_vnmse(ctx, x, b_q8: int, trials: int, seed: int, drop_q32: int = 0):
+    """Mean and standard error of |x - x_hat|^2 / |x|^2 over `trials` independent senders of the same x."""
+    import torch
+    d = x.numel()
+    D = 1 << max(0, (d - 1).bit_length())
+    ids = list(range(trials))
+    msgs = ctx.encode([x] * trials, ids, [b_q8] * trials, seed)
+    acc = torch.empty(d, dtype=torch.float32, device=x.device)
+    outs = torch.empty(trials, 2, dtype=torch.float64, device=x.device)
+    for c in range(trials):
+        acc.zero_()
+        bm = [ctx.make_loss_bitmap(seed, c, D, drop_q32)] if drop_q32 else None
+        ctx.decode_accumulate([msgs[c]], [c], [b_q8], d, seed, acc, bm)
+        ctx.sq_error(x, acc, out=outs[c])
+    torch.cuda.synchronize()
+    r = (outs[:, 0] / outs[:, 1]).cpu()
+    return float(r.mean()), float(r.std(unbiased=True) / math.sqrt(trials)) if trials > 1 else 0.0
+
+
+def measure_nmse(ctx, xs, b_q8, seed: int):
+    """|mean - estimate|^2 / ((1/n) sum |x_c|^2) for one round with the vectors xs (Sec. 2.1)."""
+    import torch
+    n, d = len(xs), xs[0].numel()
+    msgs = ctx.encode(xs, list(range(n)), b_q8, seed)
+    acc = torch.zeros(d, dtype=torch.float32, device=xs[0].device)
+    ctx.decode_accumulate(msgs, list(range(n)), b_q8, d, seed, acc)
+    est = ctx.finalize_mean(acc, n)
+    true_acc = torch.zeros(d, dtype=torch.float32, device=xs[0].device)
+    zero = torch.zeros(d, dtype=torch.float32, device=xs[0].device)
+    norms = 0.0
+    for x in xs:
+        true_acc += x                                   # memory-side bookkeeping of the experiment, not the method
+        norms += float(ctx.sq_error(x, zero)[1])
+    true_mean = true_acc / n
+    e2 = float(ctx.sq_error(true_mean, est)[0])
+    return e2 / (norms / n)
+
+
+def main(argv=None):
+    import torch
+    from . import eden
+    ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    ap.add_argument("--dist", default="lognormal", choices=DISTS + ["all"])
+    ap.add_argument("--log2d", type=int, nargs="+", default=[20])
+    ap.add_argument("--budgets", type=float, nargs="+", default=[0.5, 1, 2, 4])
+    ap.add_argument("--trials", type=int, default=32)
+    ap.add_argument("--senders", type=int, default=8, help="senders of the NMSE round (0: skip it)")
+    ap.add_argument("--loss", type=float, default=0.0, help="fraction of packets dropped at the receiver")
+    ap.add_argument("--seed", type=int, default=1)
+    args = ap.parse_args(argv)
+    assert torch.cuda.is_available(), "this experiment runs on the GPU"
+    eden.lib()
+    dev = torch.device("cuda:0")
+    drop_q32 = int(args.loss * 2 ** 32)
+    print(f"{'dist':11s} {'d':>9s} {'b':>4s} {'vNMSE':>9s} {'+-':>8s} {'theory':>8s} {'NMSE(n)':>9s} {'theory':>8s}")
+    for dist in (DISTS if args.dist == "all" else [args.dist]):
+        for l2 in args.log2d:
+            d = 1 << l2
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(args.seed * 1000 + l2)
+            trials = min(args.trials, 32)
+            ctx = eden.Context(d_max=d, n_max=max(trials, args.senders, 1), device=0)
+            x = draw(dist, d, gen, dev)
+            for b in args.budgets:
+                b_q8 = int(round(b * 256))
+                v, se = measure_vnmse(ctx, x, b_q8, trials, args.seed, drop_q32)
+                th = theory_vnmse(b, 1.0 - args.loss)
+                line = f"{dist:11s} {d:9d} {b:4g} {v:9.5f} {se:8.5f} {th:8.5f}"
+                if args.senders > 0 and not drop_q32:
+                    xs = [draw(dist, d, gen, dev) for _ in range(args.senders)]
+                    nm = measure_nmse(ctx, xs, [b_q8] * args.senders, args.seed + 1)
+                    line += f" {nm:9.5f} {th / args.senders:8.5f}"
+                print(line, flush=True)
+
+
+if __name__ == "__main__":
+    main()
