@@ -35,7 +35,7 @@
  *   - Hash: word(key, j) = mix(key + PHI*(j+1)), mix = the splitmix64 output function,
  *     key = mix(mix(seed + PHI) + PHI*((stream << 32) | client) + PHI), PHI = 0x9E3779B97F4A7C15;
  *     streams: 0 = signs, 1 = sub-sampling, 2 = packet loss.
- *   - Bit budget b is passed as b_q8 = 256*b.  Supported: 256, 512, 1024 (b = 1, 2, 4, the
+ *   - Bit budget b is passed as b_q8 = 256*b.  Supported: 256, 512, 768, 1024 (b = 1, 2, 3, 4, the
  *     2^b-level Lloyd-Max quantizer of N(0,1), Sec. 3) and 128 (b = 1/2: the b = 1 quantizer,
  *     then of every two consecutive rotated coordinates (2g, 2g+1) only the one at offset
  *     bit (g & 63) of word (g >> 6) of the SUB-SAMPLING stream is sent; Sec. 4.1, applied after

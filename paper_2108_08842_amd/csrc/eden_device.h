@@ -33,7 +33,7 @@ __host__ __device__ inline uint64_t hash_word(uint64_t key, uint64_t j) { return
 // ---- bit budgets (Sec. 4.1): b_q8 = 256 b -> bits per transmitted index, keep one coordinate in k
 __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
     if (b_q8 == 128) { bits = 1; k = 2; return true; }
-    if (b_q8 == 256 || b_q8 == 512 || b_q8 == 1024) { bits = (int)(b_q8 >> 8); k = 1; return true; }
+    if (b_q8 == 256 || b_q8 == 512 || b_q8 == 768 || b_q8 == 1024) { bits = (int)(b_q8 >> 8); k = 1; return true; }
     return false;
 }
 
@@ -241,6 +241,36 @@ __device__ inline uint32_t spread4(uint32_t x) {                 // bit j of the
     x = (x | (x << 12)) & 0x000F000Fu;
     x = (x | (x << 6)) & 0x03030303u;
     return (x | (x << 3)) & 0x11111111u;
+}
+
+__device__ inline uint32_t spread3(uint32_t x) {                 // bit j of the low 11 -> bit 3j
+    const uint32_t top = ((x >> 10) & 1u) << 30;
+    x &= 0x3FFu;
+    x = (x | (x << 16)) & 0x030000FFu;
+    x = (x | (x << 8)) & 0x0300F00Fu;
+    x = (x | (x << 4)) & 0x030C30C3u;
+    x = (x | (x << 2)) & 0x09249249u;
+    return x | top;
+}
+// 3-bit codes of 32 consecutive coordinates, given as three bit planes (bit i of plane k = bit k of code i),
+// as the 96-bit little-endian string in which code i occupies bits 3i .. 3i+2
+__device__ inline void pack3_planes(uint32_t p0, uint32_t p1, uint32_t p2, uint32_t (&out)[3]) {
+    const uint32_t plane[3] = {p0, p1, p2};
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {                            // coordinates 11c .. 11c+10 start at bit 33c + k
+            const uint64_t v = (uint64_t)spread3((plane[k] >> (11 * c)) & 0x7FFu) << ((33 * c + k) & 31);
+            w[(33 * c + k) >> 5] |= (uint32_t)v;
+            w[((33 * c + k) >> 5) + 1] |= (uint32_t)(v >> 32);
+        }
+    }
+    out[0] = w[0]; out[1] = w[1]; out[2] = w[2];
+}
+// the `bits`-wide code that starts `shift` bits into the 64-bit little-endian window w1:w0
+__device__ inline uint32_t code_at(uint32_t w0, uint32_t w1, uint32_t shift, int bits) {
+    return __builtin_amdgcn_alignbit(w1, w0, shift) & ((1u << bits) - 1u);
 }
 
 // Butterflies over the low LOGB bits of the register index only.

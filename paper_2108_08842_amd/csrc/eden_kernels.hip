@@ -1,4 +1,4 @@
-// HIP kernels of the EDEN hot path for gfx950 (MI355X).  Wave64 throughout.
+// HIP kernels of the EDEN hot path for gfx950 (MI355X), wave-tile passes and the small sizes.  Wave64 throughout.
 //
 // The rotation R x = D^-1/2 H (s o x) (Sec. 2.2.1; Sec. 5: randomized Hadamard transform) is computed
 // unnormalised, u = H (s o x), with the D^-1/2 folded into scalars.  The index bits of the padded
@@ -9,11 +9,11 @@
 //   hi pass   bits p..p+M-1 (M <= 6): one wave owns 2^M rows of 64 consecutive coordinates at stride 2^p;
 //                          every lane keeps one column in registers; no LDS at all.
 //
-// Encode runs the hi passes first (the first one reads x, applies the signs and sums |x|^2) and the lo
-// pass last, fused with quantization, <R(x),Q> and bit packing (Sec. 2.2.1, 2.3).  Decode runs the lo
-// pass first, fused with unpacking and centroid lookup (Sec. 2.2.2, 4.2), and the hi passes after it; the
-// last one applies the signs and sums the senders in registers before touching the accumulator once.
-// D <= 4096 is handled by one workgroup per sender with the vector resident in LDS.
+// Encode runs the lo pass first (it reads x, applies the signs and sums |x|^2, and only touches the tiles
+// that hold part of x) and the hi passes after it, the last one fused with quantization, <R(x),Q> and bit
+// packing (Sec. 2.2.1, 2.3).  Decode runs the hi passes first, the first one fused with unpacking and centroid
+// lookup (Sec. 2.2.2, 4.2), and the lo pass last: it applies the signs and sums the senders in registers before
+// touching the accumulator once.  D <= 4096 is handled by one workgroup per sender with the vector in LDS.
 #include "eden_device.h"
 #include "eden_kernels.h"
 
@@ -120,6 +120,26 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
                         o[k] = spread2(plane[0][k >> 1] >> (16 * (k & 1))) | (spread2(plane[1][k >> 1] >> (16 * (k & 1))) << 1);
                     *reinterpret_cast<uint4 *>(payload + (my_row >> 4)) = make_uint4(o[0], o[1], o[2], o[3]);
                 }
+            } else if (b_q8 == 768u) {
+                static_for<R>([&](auto RR) {
+                    constexpr int r = decltype(RR)::value;
+                    const uint32_t code = quantize_one<4>(v[r], sc->thr, sc->qpos, ip);
+#pragma unroll
+                    for (int b = 0; b < 3; ++b) {
+                        const uint64_t m = __ballot((code >> b) & 1u);
+                        plane[b][0] = put_lane<r>(lo32(m), plane[b][0]);
+                        plane[b][1] = put_lane<r>(hi32(m), plane[b][1]);
+                    }
+                });
+                if (lane < R) {
+                    uint32_t lo[3], hi[3];                       // 64 coordinates x 3 bits = 6 words
+                    pack3_planes(plane[0][0], plane[1][0], plane[2][0], lo);
+                    pack3_planes(plane[0][1], plane[1][1], plane[2][1], hi);
+                    uint2 *dst = reinterpret_cast<uint2 *>(payload + (my_row >> 6) * 6u);
+                    dst[0] = make_uint2(lo[0], lo[1]);
+                    dst[1] = make_uint2(lo[2], hi[0]);
+                    dst[2] = make_uint2(hi[1], hi[2]);
+                }
             } else {
                 static_for<R>([&](auto RR) {
                     constexpr int r = decltype(RR)::value;
@@ -210,6 +230,18 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
             const bool kept = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
             const uint32_t neg = (~(w >> (lane >> 1)) & 1u) << 31;          // index 0 = negative
             v[r] = kept ? __uint_as_float(mag | neg) : 0.0f;
+        }
+    } else if (bits == 3) {
+        // 64 columns x 3 bits = 6 words per row; an index may straddle two words
+        const uint32_t lbits = lane * 3u;
+        const rsrc_t rp = make_rsrc(payload + (base >> 6) * 6u, payload_bytes - (uint32_t)(base >> 6) * 24u);
+        const uint32_t voff = (lbits >> 5) * 4u, shift = lbits & 31u;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int soff = (int)((((uint32_t)r * 6u) << (p - 6)) * 4u);
+            const uint32_t w0 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, soff, 0);
+            const uint32_t w1 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0);
+            v[r] = tb[code_at(w0, w1, shift, 3)];
         }
     } else {
         const uint32_t lbits = lane * (uint32_t)bits;
@@ -549,16 +581,15 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int l
     uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     const uint32_t nsent = D / (uint32_t)k;                    // transmitted indices
     const uint32_t nwords = 2u * ((nsent * (uint32_t)bits + 63u) / 64u);
-    const uint32_t per = 32u / (uint32_t)bits;
     const uint64_t subkey = stream_key(seed, kStreamSubsample, B.client[c]);
-    for (uint32_t w = threadIdx.x; w < nwords; w += 256) {
+    for (uint32_t w = threadIdx.x; w < nwords; w += 256) {       // payload bit 32 w + e = bit (pos % bits) of index pos / bits
         uint32_t word = 0;
-        for (uint32_t e = 0; e < per; ++e) {
-            const uint32_t j = w * per + e;                    // j-th transmitted index
+        for (uint32_t e = 0; e < 32u; ++e) {
+            const uint32_t pos = 32u * w + e, j = pos / (uint32_t)bits, r = pos % (uint32_t)bits;
             if (j >= nsent) break;
             uint32_t i = j;
             if (k == 2) i = 2u * j + (uint32_t)((hash_word(subkey, j >> 6) >> (j & 63u)) & 1ull);
-            word |= (uint32_t)code[i] << (e * (uint32_t)bits);
+            word |= (((uint32_t)code[i] >> r) & 1u) << e;
         }
         payload[w] = valid ? word : 0u;
     }
@@ -600,6 +631,7 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
         const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
         const uint32_t *bm = B.bitmap[c];
         const uint64_t subkey = stream_key(seed, kStreamSubsample, B.client[c]);
+        const uint32_t nwords = 2u * (((D / (uint32_t)k) * (uint32_t)bits + 63u) / 64u);
         for (uint32_t i = threadIdx.x; i < D; i += 256) {
             const uint32_t pk = i >> 10;
             bool here = bm ? ((bm[pk >> 5] >> (pk & 31u)) & 1u) : true;
@@ -609,8 +641,9 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
                 const uint32_t off = (uint32_t)((hash_word(subkey, j >> 6) >> (j & 63u)) & 1ull);
                 here = here && ((i & 1u) == off);
             }
-            const uint32_t bitpos = j * (uint32_t)bits;
-            const uint32_t idx = (payload[bitpos >> 5] >> (bitpos & 31u)) & ((1u << bits) - 1u);
+            const uint32_t bitpos = j * (uint32_t)bits, w0 = bitpos >> 5;
+            const uint32_t next = (w0 + 1u < nwords) ? payload[w0 + 1u] : 0u;       // a 3-bit index may straddle two words
+            const uint32_t idx = code_at(payload[w0], next, bitpos & 31u, bits);
             buf[i] = here ? s.deq[idx] : 0.0f;
         }
         fwht_lds(buf, D);

@@ -132,6 +132,12 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
             const uint32_t a = plane[0][w], b = plane[1][w];
             *reinterpret_cast<uint2 *>(payload + 2u * word) =
                 make_uint2(spread2(a) | (spread2(b) << 1), spread2(a >> 16) | (spread2(b >> 16) << 1));
+        } else if constexpr (BITS == 3) {
+            uint32_t o[3];                                       // 32 coordinates x 3 bits = 3 words
+            pack3_planes(plane[0][w], plane[1][w], plane[2][w], o);
+            payload[3u * word] = o[0];
+            payload[3u * word + 1u] = o[1];
+            payload[3u * word + 2u] = o[2];
         } else {
             uint32_t o[4];
 #pragma unroll
@@ -226,6 +232,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
             hix_exchange_read<M>(lds, out);
             if (UNIT || b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
             else if (b_q8 == 512u) hix_quantize_pack<M, 2>(out, ph, sc, payload, (uint32_t)(base >> 5), ip);
+            else if (b_q8 == 768u) hix_quantize_pack<M, 3>(out, ph, sc, payload, (uint32_t)(base >> 5), ip);
             else hix_quantize_pack<M, 4>(out, ph, sc, payload, (uint32_t)(base >> 5), ip);
         }
     }
@@ -379,6 +386,14 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, u
             for (int r = 0; r < 64; ++r) {
                 const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)X::RL * r * 2u) << (p - 5)) * 4u), 0);
                 v[r] = table[(w >> shift) & 3u];
+            }
+        } else if (b_q8 == 768) {                                // an index may straddle two words
+#pragma unroll
+            for (int r = 0; r < 64; ++r) {
+                const int soff = (int)((((uint32_t)X::RL * r * 3u) << (p - 5)) * 4u);
+                const uint32_t w0 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, soff, 0);
+                const uint32_t w1 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0);
+                v[r] = table[code_at(w0, w1, shift, 3)];
             }
         } else {
 #pragma unroll

@@ -93,10 +93,10 @@ def _sampled_rows_check(x64, seed, client, idx_gpu_at, samples, thresholds):
 
 
 def test_three_pass_size():
-    """D = 2^25: wave-tile strided pass on bit 24, workgroup-tile strided pass on bits 14..23, lo14."""
+    """D = 2^25: lo14, workgroup-tile strided pass on bits 14..20, wave-tile strided pass on bits 21..24."""
     from paper_2108_08842_amd import eden
     d = (1 << 24) + 12345
-    w = synth.Workload("three_pass", 2, d, [256, 1024], 25, "normal_outliers")
+    w = synth.Workload("three_pass", 2, d, [256, 768], 25, "normal_outliers")
     print(f"three passes: n=2 d={d} D=2^25 budgets={w.b_q8} seed={w.seed}", flush=True)
     xs = [synth.client_vector(w, c) for c in range(2)]
     ctx = eden.Context(d_max=d, n_max=2, device=0)
@@ -104,12 +104,12 @@ def test_three_pass_size():
     assert ctx.last_device_status() == 0
     stats = parity.EncodeParity()
     om = [parity.to_oracle_message(m) for m in msgs]
-    parity.check_encode(xs[1], w.seed, 9, 1024, om[1], stats)        # one whole sender through the oracle (b = 4)
+    parity.check_encode(xs[1], w.seed, 9, 768, om[1], stats)         # one whole sender through the oracle (b = 3)
     parity.finish_encode(stats)
     print("encode:", stats, flush=True)
     bm = [ctx.make_loss_bitmap(w.seed, cid, 1 << 25, int(0.1 * 2 ** 32)) for cid in (5, 9)]
     acc = torch.zeros(d, device="cuda")
-    ctx.decode_accumulate(msgs[1:], [9], [1024], d, w.seed, acc, bm[1:])
+    ctx.decode_accumulate(msgs[1:], [9], [768], d, w.seed, acc, bm[1:])
     got = ctx.finalize_mean(acc, 1).cpu().numpy()
     want = o.decode_mean([om[1]], d, [bm[1].cpu().numpy().view(np.uint32)])
     err = parity.rel_l2(got, want)

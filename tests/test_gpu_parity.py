@@ -88,27 +88,30 @@ def test_single_workgroup_sizes(ctx, d):
     xs = [synth.client_vector(w, c) for c in range(3)]
     _run_case(ctx, xs, [0, 1, 2], w.b_q8, w.seed)
     if d >= 2:
-        _run_case(ctx, xs, [7, 8, 9], [128, 128, 256], w.seed + 1)
+        _run_case(ctx, xs, [7, 8, 9], [128, 768, 256], w.seed + 1)
 
 
 @pytest.mark.parametrize("d", [4097, 8192, 20_000, (1 << 16) + 17, 300_000, 1 << 18])
 def test_multi_pass_sizes(ctx, d):
-    w = synth.Workload("t", 4, d, [128, 256, 512, 1024], 200 + d % 1000, "lognormal_signed")
-    xs = [synth.client_vector(w, c) for c in range(4)]
-    _run_case(ctx, xs, [3, 1, 4, 1_000_000], w.b_q8, w.seed)
+    w = synth.Workload("t", 5, d, [128, 256, 512, 1024, 768], 200 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(5)]
+    _run_case(ctx, xs, [3, 1, 4, 1_000_000, 5], w.b_q8, w.seed)
 
 
-@pytest.mark.parametrize("d,budgets", [(1 << 21, [256, 1024]), ((1 << 21) + 5, [128, 512]), (5_000_000, [256, 512])])
+@pytest.mark.parametrize("d,budgets", [(1 << 21, [256, 1024]), ((1 << 21) + 5, [128, 512, 768]), (5_000_000, [256, 512]),
+                                       (3_000_000, [768, 768])])
 def test_workgroup_tile_sizes(ctx, d, budgets):
     # D = 2^21, 2^22, 2^23: strided pass of 7, 8, 9 bits in workgroup tiles + 14-bit contiguous pass
-    w = synth.Workload("t", 2, d, budgets, 400 + d % 1000, "normal_outliers")
-    xs = [synth.client_vector(w, c) for c in range(2)]
-    _run_case(ctx, xs, [11, 12], w.b_q8, w.seed, drop_q32=int(0.05 * 2 ** 32), also_oracle_msgs=(d == 1 << 21))
+    n = len(budgets)
+    w = synth.Workload("t", n, d, budgets, 400 + d % 1000, "normal_outliers")
+    xs = [synth.client_vector(w, c) for c in range(n)]
+    _run_case(ctx, xs, list(range(11, 11 + n)), w.b_q8, w.seed, drop_q32=int(0.05 * 2 ** 32),
+              also_oracle_msgs=(d == 1 << 21))
 
 
 @pytest.mark.parametrize("d", [5000, 70_000, 300_000])
 def test_packet_loss_and_mixed_budgets(ctx, d):
-    w = synth.Workload("t", 6, d, [128, 256, 512, 1024, 256, 128], 300 + d % 1000, "lognormal")
+    w = synth.Workload("t", 6, d, [128, 256, 512, 1024, 768, 128], 300 + d % 1000, "lognormal")
     xs = [synth.client_vector(w, c) for c in range(6)]
     _run_case(ctx, xs, list(range(6)), w.b_q8, w.seed, drop_q32=int(0.1 * 2 ** 32))
     _run_case(ctx, xs, list(range(6)), w.b_q8, w.seed, drop_q32=int(0.6 * 2 ** 32), also_oracle_msgs=False)
@@ -210,7 +213,7 @@ def test_argument_errors(ctx):
               msg_caps=[msg.numel()])
     assert ctx.encode_raw(**ok) == eden.OK
     assert ctx.encode_raw(**{**ok, "b_q8": [300]}) == eden.ERR_INVALID_ARG
-    assert ctx.encode_raw(**{**ok, "b_q8": [768]}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw(**{**ok, "b_q8": [1280]}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "d": 0}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "d": (1 << 23) + 1}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "x_ptrs": [None]}) == eden.ERR_INVALID_ARG
