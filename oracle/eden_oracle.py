@@ -24,6 +24,8 @@ Pins (tests/test_oracle_*.py) tie each part to something other than itself:
                         (Haar matrices from scipy for the theorem itself, the
                         structured rotation on a light-tailed vector for the path),
                         empirical vNMSE against the printed asymptotic values
+  * b = k + 1/2      -> a d=4 case worked by hand with the printed I_1 / I_2 values, the printed
+                        0.317 at b = 1.5, exact size and mask structure, tangent identity
   * hash             -> the published splitmix64 test vector (seed 0)
 parity unpinned: the b=4 table has no printed value in the paper (it is pinned
 only by the Lloyd fixed-point conditions, symmetry and the rate-distortion
@@ -54,6 +56,7 @@ _M2 = 0x94D049BB133111EB
 STREAM_SIGN = 0        # Rademacher diagonal of the rotation
 STREAM_SUBSAMPLE = 1   # which coordinate of each group is kept when b < 1
 STREAM_LOSS = 2        # Bernoulli packet drops (test helper)
+STREAM_MIX = 3         # which coordinate of each pair gets the extra bit when b is k + 1/2
 
 PACKET_COORDS = 1024   # reading: a packet is 1024 consecutive rotated coordinates
 
@@ -112,6 +115,17 @@ def subsample_offsets(seed: int, client: int, n_groups: int) -> np.ndarray:
     exact size D/2, applied after the rotation, treated by the receiver like a loss)."""
     key = stream_key(seed, STREAM_SUBSAMPLE, client)
     return _bits_of_words(hash_words(key, 0, (n_groups + 63) // 64), n_groups)
+
+
+def mix_offsets(seed: int, client: int, n_pairs: int) -> np.ndarray:
+    """For b = k + 1/2 (Sec. 4.1, super-bit compression with a non-integer budget): offset (0 or 1)
+    of the coordinate of each pair (2g, 2g+1) that is quantized with k+1 bits; the other one uses k.
+    reading: the paper draws an independent coin per coordinate from the shared randomness, which
+    makes the message length random; here exactly one coordinate of every pair is chosen (the
+    choice is still content independent, which is all the proofs of Thm 2.1 / 2.2 use), so the
+    message has exactly (k + 1/2) D bits and every position in it is known without a scan."""
+    key = stream_key(seed, STREAM_MIX, client)
+    return _bits_of_words(hash_words(key, 0, (n_pairs + 63) // 64), n_pairs)
 
 
 def n_packets(D: int) -> int:
@@ -282,19 +296,36 @@ def quantize_indices(z: np.ndarray, thresholds: np.ndarray) -> np.ndarray:
 # two rotated coordinates).
 # ----------------------------------------------------------------------------
 def budget(b_q8: int):
-    """-> (bits per kept coordinate, keep-one-in-k)."""
+    """-> (bits per kept coordinate, keep-one-in-k).  For b = k + 1/2 the bits are k (every coordinate
+    has k bits in the first part of the payload; see mixed())."""
     if b_q8 >= 256 and b_q8 % 256 == 0 and b_q8 // 256 <= 8:
         return b_q8 // 256, 1
     if b_q8 == 128:
         return 1, 2
+    if mixed(b_q8):
+        return b_q8 // 256, 1
     raise ValueError(f"unsupported bit budget b_q8={b_q8}")
 
 
-def payload_words(D: int, b_q8: int) -> int:
-    """uint32 words of payload; reading: rounded up to a multiple of two words."""
+def mixed(b_q8: int) -> bool:
+    """b = 1.5, 2.5, 3.5: half of the coordinates use one bit more (Sec. 4.1)."""
+    return b_q8 in (384, 640, 896)
+
+
+def plane_words(D: int, b_q8: int):
+    """-> (words of the index part, words of the extra-bit part); each part is rounded up to a
+    multiple of two words (reading)."""
     bits, k = budget(b_q8)
     nbits = (D // k if D >= k else 1) * bits
-    return 2 * ((nbits + 63) // 64)
+    a = 2 * ((nbits + 63) // 64)
+    b = 2 * ((D // 2 + 63) // 64) if mixed(b_q8) else 0
+    return a, b
+
+
+def payload_words(D: int, b_q8: int) -> int:
+    """uint32 words of payload."""
+    a, b = plane_words(D, b_q8)
+    return a + b
 
 
 def pack_indices(idx: np.ndarray, bits: int, n_words: int) -> np.ndarray:
@@ -387,6 +418,51 @@ class EncodeTrace:
     z: np.ndarray          # eta * R(x), all D coordinates
     idx: np.ndarray        # interval rank of every coordinate (before sub-sampling)
     kept: np.ndarray       # coordinates whose index is in the payload
+    up: np.ndarray | None = None   # b = k + 1/2: True where the coordinate uses the (k+1)-bit quantizer
+
+
+def upgraded_mask(seed: int, client: int, D: int) -> np.ndarray:
+    """True at the coordinate of every pair (2g, 2g+1) that gets the extra bit."""
+    off = mix_offsets(seed, client, D // 2).astype(np.int64)
+    up = np.zeros(D, dtype=bool)
+    up[2 * np.arange(D // 2) + off] = True
+    return up
+
+
+def _encode_mixed(y, N2, d, D, bits, b_q8, seed, client, want_trace):
+    """b = k + 1/2 (Sec. 4.1): coordinate i is quantized with I_{k+1} if it is the chosen one of its
+    pair, else with I_k; the scale is S = |x|^2 / <R(x), Q> with that coordinate-wise Q (Sec. 2.3).
+    reading of the layout: first the low k bits of every coordinate's index, packed as for budget k;
+    then one bit per pair, the top bit of the chosen coordinate's (k+1)-bit index."""
+    if D < 2:
+        raise ValueError("a half-integer budget needs at least one pair of coordinates")
+    t_lo, c_lo = tables(bits)
+    t_hi, c_hi = tables(bits + 1)
+    eta = math.sqrt(D) / math.sqrt(N2)
+    z = eta * y
+    up = upgraded_mask(seed, client, D)
+    idx = np.where(up, quantize_indices(z, t_hi), quantize_indices(z, t_lo))
+    Q = np.where(up, c_hi[np.minimum(idx, c_hi.size - 1)], c_lo[np.minimum(idx, c_lo.size - 1)])
+    IP = float(np.dot(y, Q))
+    S = N2 / IP
+    wa, wb = plane_words(D, b_q8)
+    low = idx & ((1 << bits) - 1)
+    top = (idx[up] >> bits) & 1                    # in pair order: exactly one chosen coordinate per pair
+    payload = np.concatenate([pack_indices(low, bits, wa), pack_indices(top, 1, wb)])
+    msg = Message(D.bit_length() - 1, d, b_q8, client, 0, S, N2, IP, seed, payload)
+    if want_trace:
+        return msg, EncodeTrace(z=z, idx=idx, kept=np.arange(D), up=up)
+    return msg
+
+
+def unpack_mixed(payload: np.ndarray, D: int, b_q8: int, up: np.ndarray) -> np.ndarray:
+    """The per-coordinate indices of a b = k + 1/2 payload (k+1 bits wide where `up`, else k)."""
+    bits, _ = budget(b_q8)
+    wa, wb = plane_words(D, b_q8)
+    idx = unpack_indices(payload[:wa], bits, D)
+    top = unpack_indices(payload[wa:wa + wb], 1, D // 2)
+    idx[up] |= top << bits
+    return idx
 
 
 def encode(x: np.ndarray, seed: int, client: int, b_q8: int, want_trace: bool = False):
@@ -409,6 +485,8 @@ def encode(x: np.ndarray, seed: int, client: int, b_q8: int, want_trace: bool = 
         return (msg, None) if want_trace else msg
 
     y = rotate(x, seed, client)                    # R(x)
+    if mixed(b_q8):
+        return _encode_mixed(y, N2, d, D, bits, b_q8, seed, client, want_trace)
     z, idx, Q, IP, S = quantize_and_scale(y, N2, bits)
 
     if k == 1:
@@ -438,6 +516,17 @@ def decode_rotated(msg: Message, bitmap: np.ndarray | None = None) -> np.ndarray
     _, centroids = tables(bits)
     yhat = np.zeros(D, dtype=np.float64)
     if msg.status != 0:
+        return yhat
+    if mixed(msg.b_q8):
+        up = upgraded_mask(msg.seed, msg.client, D)
+        idx = unpack_mixed(msg.payload, D, msg.b_q8, up)
+        _, c_hi = tables(bits + 1)
+        Q = np.where(up, c_hi[np.minimum(idx, c_hi.size - 1)], centroids[np.minimum(idx, centroids.size - 1)])
+        arrived = np.repeat(bitmap_to_packet_flags(bitmap, D), min(D, PACKET_COORDS))[:D]
+        count = int(arrived.sum())
+        if count == 0:
+            return yhat
+        yhat[arrived] = (msg.S / (count / D)) * Q[arrived]
         return yhat
     if k == 1:
         kept = np.arange(D)

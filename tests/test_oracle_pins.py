@@ -444,3 +444,102 @@ def test_mean_is_linear_in_messages():
     msgs = [o.encode(xs[c], 4, c, 512) for c in range(3)]
     total = sum(o.decode(m, d) for m in msgs) / 3.0
     np.testing.assert_allclose(o.decode_mean(msgs, d), total, atol=1e-14)
+
+
+# ---- b = k + 1/2 (Sec. 4.1, super-bit compression with a non-integer budget)
+def test_half_integer_budget_by_hand_d4():
+    # b = 1.5 on four coordinates, every step typed out: pairs (0,1) and (2,3); the chosen coordinate of
+    # a pair uses I_2, the other one I_1
+    seed, client = 3, 1
+    s = [1.0 - 2.0 * v for v in o.sign_bits(seed, client, 4).tolist()]
+    off = o.mix_offsets(seed, client, 2).tolist()
+    x = [1.5, -0.25, 4.0, 1.0]
+    a = [s[i] * x[i] for i in range(4)]
+    u = [a[0] + a[1] + a[2] + a[3], a[0] - a[1] + a[2] - a[3], a[0] + a[1] - a[2] - a[3], a[0] - a[1] - a[2] + a[3]]
+    y = [v / 2.0 for v in u]
+    n2 = sum(v * v for v in x)
+    z = [math.sqrt(4.0 / n2) * v for v in y]
+    c1 = math.sqrt(2.0 / math.pi)
+    t2, q2 = 0.9816, (0.45278, 1.51042)              # Sec. 3, Example 2 (five printed digits)
+    up = [off[0] == 0, off[0] == 1, off[1] == 0, off[1] == 1]
+    Q, low, top = [], [], []
+    for i in range(4):
+        if up[i]:
+            mag = 1 if abs(z[i]) > t2 else 0
+            idx = (2 + mag) if z[i] >= 0 else (1 - mag)
+            Q.append(math.copysign(q2[mag], z[i]) if z[i] != 0 else q2[0])
+            low.append(idx & 1); top.append(idx >> 1)
+        else:
+            Q.append(c1 if z[i] >= 0 else -c1)
+            low.append(1 if z[i] >= 0 else 0)
+    ip = sum(y[i] * Q[i] for i in range(4))
+    msg, tr = o.encode(np.array(x), seed, client, 384, want_trace=True)
+    assert tr.up.tolist() == up
+    assert msg.payload.tolist() == [low[0] | low[1] << 1 | low[2] << 2 | low[3] << 3, 0, top[0] | top[1] << 1, 0]
+    assert abs(msg.IP - ip) < 2e-5 * abs(ip)          # the printed table values carry five digits
+    assert abs(msg.S - n2 / ip) < 2e-5 * abs(n2 / ip)
+    w = [msg.S * Q[i] for i in range(4)]
+    v = [w[0] + w[1] + w[2] + w[3], w[0] - w[1] + w[2] - w[3], w[0] + w[1] - w[2] - w[3], w[0] - w[1] - w[2] + w[3]]
+    xhat = [s[i] * v[i] / 2.0 for i in range(4)]
+    np.testing.assert_allclose(o.decode(msg, 4), xhat, rtol=3e-5, atol=1e-5)
+
+
+@pytest.mark.parametrize("b_q8", [384, 640, 896])
+def test_half_integer_budget_size_mask_and_round_trip(b_q8):
+    d = 3000
+    D = 4096
+    rng = np.random.default_rng(b_q8)
+    x = rng.standard_normal(d)
+    msg, tr = o.encode(x, 11, 4, b_q8, want_trace=True)
+    assert msg.payload.size * 32 == (b_q8 * D) // 256                     # exactly (k + 1/2) D bits
+    assert o.message_bytes(d, b_q8) == len(msg.to_bytes())
+    assert tr.up.reshape(-1, 2).sum(axis=1).tolist() == [1] * (D // 2)    # one coordinate of every pair
+    assert abs(tr.up[0::2].mean() - 0.5) < 0.05                           # and which one is a fair coin
+    assert not np.array_equal(tr.up, o.upgraded_mask(11, 5, D))           # per sender
+    k = b_q8 // 256
+    assert tr.idx[~tr.up].max() < (1 << k) and tr.idx[tr.up].max() < (1 << (k + 1)) and tr.idx[tr.up].max() >= (1 << k)
+    back = o.Message.from_bytes(msg.to_bytes())
+    np.testing.assert_array_equal(o.unpack_mixed(back.payload, D, b_q8, tr.up), tr.idx)
+    # the two halves are the plain quantizers of their own budgets
+    t_lo, _ = o.tables(k); t_hi, _ = o.tables(k + 1)
+    np.testing.assert_array_equal(tr.idx[~tr.up], o.quantize_indices(tr.z[~tr.up], t_lo))
+    np.testing.assert_array_equal(tr.idx[tr.up], o.quantize_indices(tr.z[tr.up], t_hi))
+    # tangent property of the scale (Sec. 2.3): <x_hat, x> = |x|^2 when nothing is lost
+    xh = o.decode(back, d)
+    assert abs(np.dot(xh, x) - np.dot(x, x)) < 1e-10 * np.dot(x, x)
+
+
+def test_half_integer_budget_vnmse_matches_printed_value(golden):
+    # Sec. 4.1: b = 1.5 -> 1 / (E[Q_1^2]/2 + E[Q_2^2]/2) - 1 = 0.317; and the same form for 2.5, 3.5
+    d = 1 << 13
+    rng = np.random.default_rng(8)
+    x = rng.lognormal(size=d)
+    for b_q8 in (384, 640, 896):
+        k = b_q8 // 256
+        th = 1 / (0.5 * o.expected_q2(*o.tables(k)) + 0.5 * o.expected_q2(*o.tables(k + 1))) - 1
+        v = np.mean([o.vnmse_single(x, o.decode(o.encode(x, s, 0, b_q8), d)) for s in range(12)])
+        assert abs(v - th) < 0.03 * th, (b_q8, v, th)
+        if b_q8 == 384:
+            assert abs(v - golden["vnmse_b1p5"]) < 0.01
+
+
+def test_half_integer_budget_unbiased_and_lossy():
+    # Thm 2.1 through the whole path, and Lemma 4.3 (1/p with counted p) for a half-integer budget
+    d, trials = 512, 4000
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal(d)
+    acc = np.zeros(d); sq = 0.0
+    for tr in range(trials):
+        xh = o.decode(o.encode(x, seed=tr, client=0, b_q8=384), d)
+        acc += xh; sq += np.sum((xh - x) ** 2)
+    vn = sq / trials / np.dot(x, x)
+    err = np.linalg.norm(acc / trials - x) / np.linalg.norm(x)
+    assert err < 1.3 * math.sqrt(vn / trials)
+    d = 4096
+    x = rng.standard_normal(d)
+    msg = o.encode(x, 5, 2, 640)
+    bm = np.array([0b1011], dtype=np.uint32)                              # packet 2 of 4 lost
+    yh = o.decode_rotated(msg, bm)
+    full = o.decode_rotated(msg, None)
+    assert not yh[2048:3072].any()
+    np.testing.assert_allclose(yh[:2048], full[:2048] * (4 / 3), rtol=1e-14)
