@@ -34,12 +34,17 @@
  *     where s_i = -1.
  *   - Hash: word(key, j) = mix(key + PHI*(j+1)), mix = the splitmix64 output function,
  *     key = mix(mix(seed + PHI) + PHI*((stream << 32) | client) + PHI), PHI = 0x9E3779B97F4A7C15;
- *     streams: 0 = signs, 1 = sub-sampling, 2 = packet loss.
+ *     streams: 0 = signs, 1 = sub-sampling, 2 = packet loss, 3 = mix (which coordinates get the extra bit).
  *   - Bit budget b is passed as b_q8 = 256*b.  Supported: 256, 512, 768, 1024 (b = 1, 2, 3, 4, the
- *     2^b-level Lloyd-Max quantizer of N(0,1), Sec. 3) and 128 (b = 1/2: the b = 1 quantizer,
+ *     2^b-level Lloyd-Max quantizer of N(0,1), Sec. 3); 128 (b = 1/2: the b = 1 quantizer,
  *     then of every two consecutive rotated coordinates (2g, 2g+1) only the one at offset
  *     bit (g & 63) of word (g >> 6) of the SUB-SAMPLING stream is sent; Sec. 4.1, applied after
- *     the rotation, so the receiver treats the rest like lost coordinates, Sec. 4.2).
+ *     the rotation, so the receiver treats the rest like lost coordinates, Sec. 4.2); and
+ *     384, 640, 896 (b = k + 1/2, k = 1, 2, 3; Sec. 4.1, non-integer b > 1: of every pair
+ *     (2g, 2g+1) the coordinate at offset bit (g & 63) of word (g >> 6) of the MIX stream is quantized
+ *     with I_{k+1}, the other one with I_k.  The paper flips an independent coin per coordinate,
+ *     which makes the message length random; choosing exactly one coordinate of every pair is as
+ *     content independent and gives exactly (k + 1/2) D bits at positions known without a scan).
  *   - Index of a coordinate = rank of its interval in ascending order (0 = most negative).  At an
  *     interval endpoint the interval closer to zero is taken; z = 0 belongs to the non-negative
  *     side (Sec. 2.2.1 and its footnote).
@@ -50,6 +55,9 @@
  *       off 48 f64 <R(x), Q>          off 56 u64 seed
  *     Payload: the j-th transmitted index occupies bits [(j*b) mod 32, +b) of word floor(j*b/32),
  *     least significant bit first; the payload is padded with zero bits to a multiple of 64 bits.
+ *     For b = k + 1/2 the payload has two such parts: first the low k bits of every coordinate's index
+ *     (packed as for budget k), then, 64-bit aligned, one bit per pair: the top bit of the (k+1)-bit
+ *     index of the pair's chosen coordinate.
  *     S = |x|^2 / <R(x), Q(eta R(x))> is the sender's scale (Sec. 2.3), always computed over all
  *     D coordinates (the sender does not change under loss or sub-sampling, Sec. 4.2).
  *   - A packet is 1024 consecutive rotated coordinates (one packet if D < 1024).  A received-packet

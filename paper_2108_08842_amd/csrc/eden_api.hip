@@ -87,10 +87,6 @@ struct DeviceGuard {
     ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
 };
 
-size_t payload_bytes(uint64_t D, int bits, int k) {
-    const uint64_t nbits = (D / (uint64_t)k) * (uint64_t)bits;
-    return (size_t)(((nbits + 63) / 64) * 8);
-}
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
@@ -117,8 +113,8 @@ size_t eden_message_bytes(uint64_t d, uint32_t b_q8) {
     int bits, k;
     if (d == 0 || d > (1ull << EDEN_MAX_LOG2_D) || !budget_of(b_q8, bits, k)) return 0;
     const uint64_t D = 1ull << ceil_log2(d);
-    if (D < (uint64_t)k) return 0;
-    return EDEN_HEADER_BYTES + payload_bytes(D, bits, k);
+    if (D < (uint64_t)k || (budget_mixed(b_q8) && D < 2)) return 0;
+    return EDEN_HEADER_BYTES + (size_t)(payload_a_bytes(D, bits, k) + payload_b_bytes(D, b_q8));
 }
 
 int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) {

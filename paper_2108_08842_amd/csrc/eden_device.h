@@ -16,7 +16,7 @@ constexpr int kLdsRow = 68;              // padded row length (floats) of the 64
 
 // ---- shared randomness (Sec. 2.1): counter hash = splitmix64 stream started at a per-(seed,stream,client) key
 constexpr uint64_t kPhi = 0x9E3779B97F4A7C15ull;
-enum : uint32_t { kStreamSign = 0, kStreamSubsample = 1, kStreamLoss = 2 };
+enum : uint32_t { kStreamSign = 0, kStreamSubsample = 1, kStreamLoss = 2, kStreamMix = 3 };
 
 __host__ __device__ inline uint64_t mix64(uint64_t z) {
     z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
@@ -30,11 +30,25 @@ __host__ __device__ inline uint64_t stream_key(uint64_t seed, uint32_t stream, u
 }
 __host__ __device__ inline uint64_t hash_word(uint64_t key, uint64_t j) { return mix64(key + kPhi * (j + 1)); }
 
-// ---- bit budgets (Sec. 4.1): b_q8 = 256 b -> bits per transmitted index, keep one coordinate in k
+// ---- bit budgets (Sec. 4.1): b_q8 = 256 b -> bits per transmitted index, keep one coordinate in k.
+// b = 1.5, 2.5, 3.5 ("mixed"): every coordinate has floor(b) bits in the first part of the payload and one
+// coordinate of every pair, chosen by the MIX stream, one more bit in a second part (it is quantized with the
+// next finer table).
+__host__ __device__ inline bool budget_mixed(uint32_t b_q8) { return b_q8 == 384 || b_q8 == 640 || b_q8 == 896; }
 __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
     if (b_q8 == 128) { bits = 1; k = 2; return true; }
-    if (b_q8 == 256 || b_q8 == 512 || b_q8 == 768 || b_q8 == 1024) { bits = (int)(b_q8 >> 8); k = 1; return true; }
+    if (b_q8 == 256 || b_q8 == 512 || b_q8 == 768 || b_q8 == 1024 || budget_mixed(b_q8)) {
+        bits = (int)(b_q8 >> 8); k = 1; return true;
+    }
     return false;
+}
+// bytes of the first part of the payload (the floor(b)-bit indices), a multiple of 8
+__host__ __device__ inline uint64_t payload_a_bytes(uint64_t D, int bits, int k) {
+    return ((((D / (uint64_t)k) * (uint64_t)bits) + 63) / 64) * 8;
+}
+// bytes of the second part (one bit per pair of coordinates) of a mixed budget
+__host__ __device__ inline uint64_t payload_b_bytes(uint64_t D, uint32_t b_q8) {
+    return budget_mixed(b_q8) ? ((D / 2 + 63) / 64) * 8 : 0;
 }
 
 // ---- message header (64 bytes, little endian)
@@ -62,12 +76,15 @@ struct EncScratch {
     double n2;              // |x|^2 (Sec. 2.2.1: equals |R(x)|^2)
     float thr[8];           // positive thresholds of I_b times |x|: compared against |H(s o x)|
     float qpos[8];          // positive centroids
-    unsigned pad[4];
+    float thr2[8];          // mixed budgets: the same for I_{floor(b)+1}
+    float qpos2[8];
+    unsigned pad[2];
 };
 
 // per-message scalars of one decode
 struct DecScratch {
     float deq[16];          // (S / (p sqrt(D))) * q_l for every index l (all zero if the message contributes nothing)
+    float deq2[16];         // mixed budgets: the same for the indices of I_{floor(b)+1}
     uint32_t flags;
     uint32_t pad[3];
 };
@@ -271,6 +288,35 @@ __device__ inline void pack3_planes(uint32_t p0, uint32_t p1, uint32_t p2, uint3
 // the `bits`-wide code that starts `shift` bits into the 64-bit little-endian window w1:w0
 __device__ inline uint32_t code_at(uint32_t w0, uint32_t w1, uint32_t shift, int bits) {
     return __builtin_amdgcn_alignbit(w1, w0, shift) & ((1u << bits) - 1u);
+}
+
+// rank of |u| among the H positive levels and that level's centroid
+template <int H, class TH, class QP>
+__device__ inline void quantize_mag(float a, const TH &thr, const QP &qp, uint32_t &mag, float &qa) {
+    mag = 0;
+    qa = qp[0];
+#pragma unroll
+    for (int t = 1; t < H; ++t) {
+        const bool above = a > thr[t];
+        mag = above ? (uint32_t)t : mag;
+        qa = above ? qp[t] : qa;
+    }
+}
+// b = K + 1/2 (Sec. 4.1): the index of one coordinate, K+1 bits wide where `up` (quantized with I_{K+1}), else K
+// bits (I_K), and its contribution |u| q to sum_i u_i Q_i.
+template <int K>
+__device__ inline uint32_t quantize_mixed(float u, bool up, const EncScratch *sc, float &ip) {
+    constexpr int HL = 1 << (K - 1), HH = 1 << K;
+    const float a = fabsf(u);
+    uint32_t mag_lo, mag_hi;
+    float q_lo, q_hi;
+    quantize_mag<HL>(a, sc->thr, sc->qpos, mag_lo, q_lo);
+    quantize_mag<HH>(a, sc->thr2, sc->qpos2, mag_hi, q_hi);
+    ip = fmaf(a, up ? q_hi : q_lo, ip);
+    const bool neg = (__float_as_uint(u) >> 31) != 0u;
+    const uint32_t code_lo = neg ? (uint32_t)(HL - 1) - mag_lo : (uint32_t)HL + mag_lo;
+    const uint32_t code_hi = neg ? (uint32_t)(HH - 1) - mag_hi : (uint32_t)HH + mag_hi;
+    return up ? code_hi : code_lo;
 }
 
 // Butterflies over the low LOGB bits of the register index only.

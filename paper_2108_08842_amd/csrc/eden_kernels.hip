@@ -26,9 +26,12 @@ __device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8,
     budget_of(b_q8, bits, k);
     s->n2 = n2;
     const double norm = sqrt(n2);
+    const int finer = budget_mixed(b_q8) ? bits + 1 : bits;
     for (int i = 0; i < 8; ++i) {
         s->thr[i] = (float)(tab->t[bits][i] * norm);
         s->qpos[i] = (float)tab->q[bits][i];
+        s->thr2[i] = (float)(tab->t[finer][i] * norm);
+        s->qpos2[i] = (float)tab->q[finer][i];
     }
 }
 
@@ -40,6 +43,82 @@ __device__ inline void hi_tile_origin(uint32_t tile, int p, uint64_t &base) {
     const uint32_t colblock = tile & ((1u << cb_bits) - 1u);
     const uint32_t upper = tile >> cb_bits;
     base = ((uint64_t)upper << (p + M)) | ((uint64_t)colblock << 6);
+}
+
+// The K-bit indices of one row segment of 64 consecutive coordinates, given as bit planes (plane[b][0/1]: bit b of
+// the indices of coordinates 0..31 / 32..63), written as the 2K payload words that start at coordinate `first`
+// (a multiple of 64): index i occupies bits K i .. K i + K - 1 of the little-endian bit string.
+template <int K>
+__device__ inline void store_row_planes(const uint32_t (&plane)[4][2], uint32_t *payload, uint64_t first) {
+    if constexpr (K == 1) {
+        *reinterpret_cast<uint2 *>(payload + (first >> 5)) = make_uint2(plane[0][0], plane[0][1]);
+    } else if constexpr (K == 2) {
+        uint32_t o[4];                                           // word k: coordinates 16 k .. 16 k + 15
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            o[k] = spread2(plane[0][k >> 1] >> (16 * (k & 1))) | (spread2(plane[1][k >> 1] >> (16 * (k & 1))) << 1);
+        *reinterpret_cast<uint4 *>(payload + (first >> 4)) = make_uint4(o[0], o[1], o[2], o[3]);
+    } else if constexpr (K == 3) {
+        uint32_t lo[3], hi[3];                                   // 64 coordinates x 3 bits = 6 words
+        pack3_planes(plane[0][0], plane[1][0], plane[2][0], lo);
+        pack3_planes(plane[0][1], plane[1][1], plane[2][1], hi);
+        uint2 *dst = reinterpret_cast<uint2 *>(payload + (first >> 6) * 6u);
+        dst[0] = make_uint2(lo[0], lo[1]);
+        dst[1] = make_uint2(lo[2], hi[0]);
+        dst[2] = make_uint2(hi[1], hi[2]);
+    } else {
+        uint32_t o[8];                                           // word k: coordinates 8 k .. 8 k + 7
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            o[k] = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) o[k] |= spread4(plane[b][k >> 2] >> (8 * (k & 3))) << b;
+        }
+        uint4 *dst = reinterpret_cast<uint4 *>(payload + (first >> 3));
+        dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+        dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+    }
+}
+
+// Quantizes the R rows of a wave tile (register r = row r, one column per lane) and packs them.  K: bits of every
+// index in the first part of the payload.  MIX (b = K + 1/2, Sec. 4.1): the coordinate of every pair that the MIX
+// stream selects is quantized with I_{K+1}; the top bit of its index goes to the second part, one bit per pair.
+// `my_row`: first coordinate of the row that this lane (< R) finishes.
+template <int R, int K, bool MIX>
+__device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *sc, uint64_t mixkey, uint64_t my_row,
+                                        uint32_t *part_a, uint32_t *part_b, float &ip) {
+    constexpr int H = 1 << (K - 1);
+    const uint32_t lane = lane_id();
+    uint32_t plane[4][2], top[2] = {0u, 0u};
+#pragma unroll
+    for (int b = 0; b < 4; ++b) plane[b][0] = plane[b][1] = 0;
+    // 64 pairs per hash word = 128 coordinates; a row segment uses 32 of them
+    const uint32_t offs_mine = MIX ? (uint32_t)(hash_word(mixkey, my_row >> 7) >> (32u * (uint32_t)((my_row >> 6) & 1u))) : 0u;
+    static_for<R>([&](auto RR) {
+        constexpr int r = decltype(RR)::value;
+        uint32_t code;
+        if constexpr (MIX) {
+            const uint32_t offs = __builtin_amdgcn_readlane(offs_mine, r);
+            const bool up = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
+            code = quantize_mixed<K>(v[r], up, sc, ip);
+            const uint64_t m = __ballot((code >> K) & 1u);
+            top[0] = put_lane<r>(lo32(m), top[0]);
+            top[1] = put_lane<r>(hi32(m), top[1]);
+        } else {
+            code = quantize_one<H>(v[r], sc->thr, sc->qpos, ip);
+        }
+#pragma unroll
+        for (int b = 0; b < K; ++b) {
+            const uint64_t m = __ballot((code >> b) & 1u);
+            plane[b][0] = put_lane<r>(lo32(m), plane[b][0]);
+            plane[b][1] = put_lane<r>(hi32(m), plane[b][1]);
+        }
+    });
+    if (lane < R) {
+        store_row_planes<K>(plane, part_a, my_row);
+        if constexpr (MIX)                                       // only the chosen coordinate of a pair can have the bit
+            part_b[my_row >> 6] = even_bits(top[0] | (top[0] >> 1)) | (even_bits(top[1] | (top[1] >> 1)) << 16);
+    }
 }
 
 // Encode, last pass in wave tiles: T -> payload.  Index bits p .. p+M-1 of H, then quantization to the
@@ -99,70 +178,15 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
             }
         } else {
             const EncScratch *sc = &scratch[c];
-            uint32_t plane[4][2];
-#pragma unroll
-            for (int b = 0; b < 4; ++b) plane[b][0] = plane[b][1] = 0;
-            if (b_q8 == 512u) {
-                static_for<R>([&](auto RR) {
-                    constexpr int r = decltype(RR)::value;
-                    const uint32_t code = quantize_one<2>(v[r], sc->thr, sc->qpos, ip);
-#pragma unroll
-                    for (int b = 0; b < 2; ++b) {
-                        const uint64_t m = __ballot((code >> b) & 1u);
-                        plane[b][0] = put_lane<r>(lo32(m), plane[b][0]);
-                        plane[b][1] = put_lane<r>(hi32(m), plane[b][1]);
-                    }
-                });
-                if (lane < R) {
-                    uint32_t o[4];                               // word k: coordinates 16 k .. 16 k + 15 of the row
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        o[k] = spread2(plane[0][k >> 1] >> (16 * (k & 1))) | (spread2(plane[1][k >> 1] >> (16 * (k & 1))) << 1);
-                    *reinterpret_cast<uint4 *>(payload + (my_row >> 4)) = make_uint4(o[0], o[1], o[2], o[3]);
-                }
-            } else if (b_q8 == 768u) {
-                static_for<R>([&](auto RR) {
-                    constexpr int r = decltype(RR)::value;
-                    const uint32_t code = quantize_one<4>(v[r], sc->thr, sc->qpos, ip);
-#pragma unroll
-                    for (int b = 0; b < 3; ++b) {
-                        const uint64_t m = __ballot((code >> b) & 1u);
-                        plane[b][0] = put_lane<r>(lo32(m), plane[b][0]);
-                        plane[b][1] = put_lane<r>(hi32(m), plane[b][1]);
-                    }
-                });
-                if (lane < R) {
-                    uint32_t lo[3], hi[3];                       // 64 coordinates x 3 bits = 6 words
-                    pack3_planes(plane[0][0], plane[1][0], plane[2][0], lo);
-                    pack3_planes(plane[0][1], plane[1][1], plane[2][1], hi);
-                    uint2 *dst = reinterpret_cast<uint2 *>(payload + (my_row >> 6) * 6u);
-                    dst[0] = make_uint2(lo[0], lo[1]);
-                    dst[1] = make_uint2(lo[2], hi[0]);
-                    dst[2] = make_uint2(hi[1], hi[2]);
-                }
-            } else {
-                static_for<R>([&](auto RR) {
-                    constexpr int r = decltype(RR)::value;
-                    const uint32_t code = quantize_one<8>(v[r], sc->thr, sc->qpos, ip);
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const uint64_t m = __ballot((code >> b) & 1u);
-                        plane[b][0] = put_lane<r>(lo32(m), plane[b][0]);
-                        plane[b][1] = put_lane<r>(hi32(m), plane[b][1]);
-                    }
-                });
-                if (lane < R) {
-                    uint32_t o[8];                               // word k: coordinates 8 k .. 8 k + 7 of the row
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        o[k] = 0;
-#pragma unroll
-                        for (int b = 0; b < 4; ++b) o[k] |= spread4(plane[b][k >> 2] >> (8 * (k & 3))) << b;
-                    }
-                    uint4 *dst = reinterpret_cast<uint4 *>(payload + (my_row >> 3));
-                    dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
-                    dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
-                }
+            const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
+            uint32_t *part_b = payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4;
+            switch (b_q8) {
+                case 384u: hi_quantize_pack<R, 1, true>(v, sc, mixkey, my_row, payload, part_b, ip); break;
+                case 512u: hi_quantize_pack<R, 2, false>(v, sc, mixkey, my_row, payload, part_b, ip); break;
+                case 640u: hi_quantize_pack<R, 2, true>(v, sc, mixkey, my_row, payload, part_b, ip); break;
+                case 768u: hi_quantize_pack<R, 3, false>(v, sc, mixkey, my_row, payload, part_b, ip); break;
+                case 896u: hi_quantize_pack<R, 3, true>(v, sc, mixkey, my_row, payload, part_b, ip); break;
+                default: hi_quantize_pack<R, 4, false>(v, sc, mixkey, my_row, payload, part_b, ip); break;
             }
         }
     }
@@ -193,7 +217,7 @@ template <int M>
 __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                                                       const DecScratch *scratch, int narrow, float *T) {
     constexpr int R = 1 << M;
-    __shared__ float table[4][16];
+    __shared__ float table[4][32];
     const uint32_t c = blockIdx.y;
     const uint32_t lane = lane_id(), wv = wave_in_block();
     const uint32_t tile = blockIdx.x * 4u + wv;
@@ -204,8 +228,9 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
     const uint32_t b_q8 = B.b_q8[c];
     const bool i16 = narrow && b_q8 <= 256u;
     if (lane < 16) table[wv][lane] = (i16 && lane == 1) ? 1.0f : scratch[c].deq[lane];
+    else if (lane < 32) table[wv][lane] = scratch[c].deq2[lane - 16];
     wave_lds_sync();
-    const float *tb = table[wv];
+    const float *tb = table[wv], *tb2 = table[wv] + 16;
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     int bits, k;
     budget_of(b_q8, bits, k);
@@ -230,6 +255,28 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
             const bool kept = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
             const uint32_t neg = (~(w >> (lane >> 1)) & 1u) << 31;          // index 0 = negative
             v[r] = kept ? __uint_as_float(mag | neg) : 0.0f;
+        }
+    } else if (budget_mixed(b_q8)) {
+        // b = bits + 1/2 (Sec. 4.1): every coordinate has `bits` bits in the first part; the coordinate of each pair
+        // that the MIX stream selects was quantized with the finer table and has its top bit in the second part
+        const uint64_t key = stream_key(seed, kStreamMix, B.client[c]);
+        const uint32_t offs_mine = (uint32_t)(hash_word(key, my_row >> 7) >> (32u * (uint32_t)((base >> 6) & 1u)));
+        const uint32_t lbits = lane * (uint32_t)bits, words_row = 2u * (uint32_t)bits;      // words of one row segment
+        const rsrc_t rp = make_rsrc(payload + (base >> 6) * words_row, payload_bytes - (uint32_t)(base >> 6) * words_row * 4u);
+        const uint32_t *part_b = payload + payload_bytes / 4u;
+        const rsrc_t rb = make_rsrc(part_b + (base >> 6), (uint32_t)payload_b_bytes(1ull << log2D, b_q8) - (uint32_t)(base >> 6) * 4u);
+        const uint32_t voff = (lbits >> 5) * 4u, shift = lbits & 31u;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int soff = (int)((((uint32_t)r * words_row) << (p - 6)) * 4u);
+            const uint32_t w0 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, soff, 0);
+            const uint32_t w1 = (bits == 3) ? __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0) : 0u;
+            const uint32_t low = code_at(w0, w1, shift, bits);
+            const uint32_t wb = __builtin_amdgcn_raw_buffer_load_b32(rb, 0, (int)(((uint32_t)r << (p - 6)) * 4u), 0);
+            const uint32_t offs = __builtin_amdgcn_readlane(offs_mine, r);
+            const bool up = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
+            const uint32_t top = (wb >> (lane >> 1)) & 1u;
+            v[r] = up ? tb2[(top << bits) | low] : tb[low];
         }
     } else if (bits == 3) {
         // 64 columns x 3 bits = 6 words per row; an index may straddle two words
@@ -410,11 +457,13 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
     if (flags == 0 && arrived == 0) flags |= EDEN_DEV_NOTHING_ARRIVED;
     double coef = 0.0;
     if (flags == 0) coef = h.S * exp2(0.5 * (double)log2D) / (double)arrived;     // S / (p sqrt(D)), p = arrived / D
-    if (lane < 16) {
-        const int H = 1 << (bits - 1);
+    if (lane < 32) {                                             // lanes 16..31: the finer table of a mixed budget
+        const int tb = (lane < 16 || !budget_mixed(b_q8)) ? bits : bits + 1;
+        const int H = 1 << (tb - 1), l = (int)(lane & 15u);
         double q = 0.0;
-        if ((int)lane < 2 * H) q = ((int)lane >= H) ? tab->q[bits][lane - H] : -tab->q[bits][H - 1 - lane];
-        out->deq[lane] = (float)(coef * q);
+        if (l < 2 * H) q = (l >= H) ? tab->q[tb][l - H] : -tab->q[tb][H - 1 - l];
+        if (lane < 16) out->deq[l] = (float)(coef * q);
+        else out->deq2[l] = (float)(coef * q);
     }
     if (lane == 0) {
         out->flags = flags;
@@ -568,14 +617,20 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int l
     const double n2 = s.n2;
     const bool valid = (n2 > 0.0) && (n2 < INFINITY);
     float ip = 0.0f;
+    const bool mix = budget_mixed(b_q8);                       // b = k + 1/2: one coordinate of every pair uses I_{k+1}
+    const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
     for (uint32_t i = threadIdx.x; i < D; i += 256) {
         const float u = buf[i];
         const float a = fabsf(u);
+        const uint32_t g = i >> 1;
+        const bool up = mix && ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u));
+        const float *thr = up ? s.thr2 : s.thr, *qp = up ? s.qpos2 : s.qpos;
+        const int Hu = up ? 2 * H : H;
         uint32_t mag = 0;
-        for (int t = 1; t < H; ++t) mag = (a > s.thr[t]) ? (uint32_t)t : mag;
-        ip = fmaf(a, s.qpos[mag], ip);
+        for (int t = 1; t < Hu; ++t) mag = (a > thr[t]) ? (uint32_t)t : mag;
+        ip = fmaf(a, qp[mag], ip);
         const uint32_t neg = __float_as_uint(u) >> 31;
-        code[i] = (uint8_t)(neg ? (uint32_t)(H - 1) - mag : (uint32_t)H + mag);
+        code[i] = (uint8_t)(neg ? (uint32_t)(Hu - 1) - mag : (uint32_t)Hu + mag);
     }
     const double ipt = block_sum<256>((double)ip, red);        // barriers inside also publish `code`
     uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
@@ -592,6 +647,19 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int l
             word |= (((uint32_t)code[i] >> r) & 1u) << e;
         }
         payload[w] = valid ? word : 0u;
+    }
+    if (mix) {                                                 // second part: the top bit of every pair's finer index
+        const uint32_t npairs = D / 2u, nwords_b = 2u * ((npairs + 63u) / 64u);
+        for (uint32_t w = threadIdx.x; w < nwords_b; w += 256) {
+            uint32_t word = 0;
+            for (uint32_t e = 0; e < 32u; ++e) {
+                const uint32_t g = 32u * w + e;
+                if (g >= npairs) break;
+                const uint32_t i = 2u * g + (uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull);
+                word |= (((uint32_t)code[i] >> bits) & 1u) << e;
+            }
+            payload[nwords + w] = valid ? word : 0u;
+        }
     }
     if (threadIdx.x == 0) {
         MsgHeader h;
@@ -632,6 +700,8 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
         const uint32_t *bm = B.bitmap[c];
         const uint64_t subkey = stream_key(seed, kStreamSubsample, B.client[c]);
         const uint32_t nwords = 2u * (((D / (uint32_t)k) * (uint32_t)bits + 63u) / 64u);
+        const bool mix = budget_mixed(b_q8);
+        const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
         for (uint32_t i = threadIdx.x; i < D; i += 256) {
             const uint32_t pk = i >> 10;
             bool here = bm ? ((bm[pk >> 5] >> (pk & 31u)) & 1u) : true;
@@ -644,7 +714,13 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
             const uint32_t bitpos = j * (uint32_t)bits, w0 = bitpos >> 5;
             const uint32_t next = (w0 + 1u < nwords) ? payload[w0 + 1u] : 0u;       // a 3-bit index may straddle two words
             const uint32_t idx = code_at(payload[w0], next, bitpos & 31u, bits);
-            buf[i] = here ? s.deq[idx] : 0.0f;
+            float val = s.deq[idx];
+            if (mix) {
+                const uint32_t g = i >> 1;
+                if ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u))
+                    val = s.deq2[(((payload[nwords + (g >> 5)] >> (g & 31u)) & 1u) << bits) | idx];
+            }
+            buf[i] = here ? val : 0.0f;
         }
         fwht_lds(buf, D);
         const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);

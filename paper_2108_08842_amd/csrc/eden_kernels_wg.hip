@@ -97,24 +97,53 @@ __device__ inline void hix_exchange(const float (&v)[64], float *lds, float (&ou
 // a wave, two row segments of 32 consecutive coordinates: exactly one payload word each at b = 1.  A ballot
 // of one bit of the index gives both words at once; lane j of each half collects the words of register j
 // (v_writelane), and after the last register every lane finishes and stores the words of "its" row.
+// row of the tile whose words lane j holds for register block w after half ph of the exchange
+template <int M>
+__device__ inline uint32_t hix_word_row(int ph, int w) {
+    using X = HiX<M>;
+    const uint32_t s = 32u * (uint32_t)w + (lane_id() & 31u), g = threadIdx.x >> 5;
+    return s % X::RL + (uint32_t)X::RL * ((uint32_t)ph * X::RP + g * X::RHL + s / X::RL);
+}
+
 // Quantizes and packs the RP values a thread holds after one half of the exchange (rows hix_row2(g, PH, s)).
-// `word0`: payload word index of this tile's 32 columns in row 0.
-template <int M, int BITS>
+// `word0`: payload word index of this tile's 32 columns in row 0; `base`: first coordinate of the tile.
+// BITS: bits of every index in the first part of the payload.  MIX (b = BITS + 1/2, Sec. 4.1): the coordinate of
+// every pair that the MIX stream selects is quantized with I_{BITS+1}; the top bit of its index goes to the
+// second part of the payload, one bit per pair = 16 bits per row segment of a tile.
+template <int M, int BITS, bool MIX>
 __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph, const EncScratch *sc, uint32_t *payload,
-                                         uint32_t word0, float &ip) {
+                                         uint16_t *part_b, uint64_t mixkey, uint64_t base, float &ip) {
     using X = HiX<M>;
     constexpr int p = kHixP;
     constexpr int H = 1 << (BITS - 1);
     constexpr int NW = X::RP / 32;                               // registers come in blocks of 32 = one word lane each
-    const uint32_t lane = lane_id(), j = lane & 31u, g = threadIdx.x >> 5;
-    uint32_t plane[BITS][NW];
+    const uint32_t lane = lane_id(), col = lane & 31u;
+    const uint32_t word0 = (uint32_t)(base >> 5);
+    uint32_t plane[BITS][NW], top[NW], offs16[NW];
 #pragma unroll
-    for (int b = 0; b < BITS; ++b)
+    for (int w = 0; w < NW; ++w) {
+        top[w] = 0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) plane[b][w] = 0;
+        for (int b = 0; b < BITS; ++b) plane[b][w] = 0;
+        // this lane's row for register block w, and the 16 pair offsets of that row segment (64 pairs per hash word)
+        const uint64_t first = base + ((uint64_t)hix_word_row<M>(ph, w) << p);
+        offs16[w] = MIX ? (uint32_t)(hash_word(mixkey, first >> 7) >> (16u * (uint32_t)((first >> 5) & 3u))) & 0xFFFFu : 0u;
+    }
     static_for<X::RP>([&](auto S) {
         constexpr int s = decltype(S)::value;
-        const uint32_t code = quantize_one<H>(out[s], sc->thr, sc->qpos, ip);
+        uint32_t code;
+        if constexpr (MIX) {
+            const uint32_t oa = __builtin_amdgcn_readlane(offs16[s / 32], s % 32);
+            const uint32_t ob = __builtin_amdgcn_readlane(offs16[s / 32], 32 + s % 32);
+            const uint32_t offs = (lane < 32u) ? oa : ob;
+            const bool up = ((offs >> (col >> 1)) & 1u) == (col & 1u);
+            code = quantize_mixed<BITS>(out[s], up, sc, ip);
+            const uint64_t m = __ballot((code >> BITS) & 1u);
+            top[s / 32] = put_lane<s % 32>(lo32(m), top[s / 32]);
+            top[s / 32] = put_lane<32 + s % 32>(hi32(m), top[s / 32]);
+        } else {
+            code = quantize_one<H>(out[s], sc->thr, sc->qpos, ip);
+        }
 #pragma unroll
         for (int b = 0; b < BITS; ++b) {
             const uint64_t m = __ballot((code >> b) & 1u);
@@ -124,11 +153,10 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
     });
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-        const uint32_t s = 32u * (uint32_t)w + j;                // the register whose words this lane holds
-        const uint32_t e = s / X::RL, rl = s % X::RL;
-        const uint32_t row = rl + (uint32_t)X::RL * ((uint32_t)ph * X::RP + g * X::RHL + e);
-        const uint32_t word = word0 + (row << (p - 5));
-        if constexpr (BITS == 2) {
+        const uint32_t word = word0 + (hix_word_row<M>(ph, w) << (p - 5));
+        if constexpr (BITS == 1) {
+            payload[word] = plane[0][w];
+        } else if constexpr (BITS == 2) {
             const uint32_t a = plane[0][w], b = plane[1][w];
             *reinterpret_cast<uint2 *>(payload + 2u * word) =
                 make_uint2(spread2(a) | (spread2(b) << 1), spread2(a >> 16) | (spread2(b >> 16) << 1));
@@ -146,6 +174,7 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
                        (spread4(plane[2][w] >> (8 * k)) << 2) | (spread4(plane[3][w] >> (8 * k)) << 3);
             *reinterpret_cast<uint4 *>(payload + 4u * word) = make_uint4(o[0], o[1], o[2], o[3]);
         }
+        if constexpr (MIX) part_b[word] = (uint16_t)even_bits(top[w] | (top[w] >> 1));    // only the chosen one can be set
     }
 }
 
@@ -166,14 +195,6 @@ __device__ inline void hix_sign_words(const float (&out)[HiX<M>::RP], float &ip,
         words[s / 32] = put_lane<s % 32>(lo32(m), words[s / 32]);
         words[s / 32] = put_lane<32 + s % 32>(hi32(m), words[s / 32]);
     });
-}
-
-// row of the tile whose words lane j holds for register block w after half ph of the exchange
-template <int M>
-__device__ inline uint32_t hix_word_row(int ph, int w) {
-    using X = HiX<M>;
-    const uint32_t s = 32u * (uint32_t)w + (lane_id() & 31u), g = threadIdx.x >> 5;
-    return s % X::RL + (uint32_t)X::RL * ((uint32_t)ph * X::RP + g * X::RHL + s / X::RL);
 }
 
 template <int N> struct WordVec;
@@ -206,6 +227,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
     const uint32_t b_q8 = B.b_q8[c];
     const EncScratch *sc = &scratch[c];
     const uint32_t off1 = ((g << p) + col) * 4u;                         // stage-1 rows: g + RL r
+    const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
     float ip = 0.0f;
     uint32_t held[TPW][X::PH][NW];
     float v[64];
@@ -231,9 +253,17 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
             }
             hix_exchange_read<M>(lds, out);
             if (UNIT || b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
-            else if (b_q8 == 512u) hix_quantize_pack<M, 2>(out, ph, sc, payload, (uint32_t)(base >> 5), ip);
-            else if (b_q8 == 768u) hix_quantize_pack<M, 3>(out, ph, sc, payload, (uint32_t)(base >> 5), ip);
-            else hix_quantize_pack<M, 4>(out, ph, sc, payload, (uint32_t)(base >> 5), ip);
+            else {
+                uint16_t *part_b = reinterpret_cast<uint16_t *>(payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4);
+                switch (b_q8) {
+                    case 384u: hix_quantize_pack<M, 1, true>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
+                    case 512u: hix_quantize_pack<M, 2, false>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
+                    case 640u: hix_quantize_pack<M, 2, true>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
+                    case 768u: hix_quantize_pack<M, 3, false>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
+                    case 896u: hix_quantize_pack<M, 3, true>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
+                    default: hix_quantize_pack<M, 4, false>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
+                }
+            }
         }
     }
     if (UNIT || b_q8 <= 256u) {
@@ -324,7 +354,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, u
     using X = HiX<M>;
     constexpr int p = kHixP;
     __shared__ float lds[X::LDS_FLOATS];
-    __shared__ float table[16];
+    __shared__ float table[32];
     const uint32_t c = blockIdx.y;
     const uint32_t tile = xcd_local_tile();
     const uint64_t base = hix_base<M>(tile, p);
@@ -334,6 +364,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, u
     const bool i16 = narrow && b_q8 <= 256u;
     const DecScratch *sc = &scratch[c];
     if (threadIdx.x < 16) table[threadIdx.x] = (i16 && threadIdx.x == 1) ? 1.0f : sc->deq[threadIdx.x];
+    else if (threadIdx.x < 32) table[threadIdx.x] = sc->deq2[threadIdx.x - 16];
     __syncthreads();
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     int bits, k;
@@ -368,6 +399,33 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, u
             const bool kept = ((offs >> (col >> 1)) & 1u) == (col & 1u);
             const uint32_t neg = (~(w >> bitpos) & 1u) << 31;                    // index 0 = negative
             v[r] = kept ? __uint_as_float(mag | neg) : 0.0f;
+        }
+    } else if (budget_mixed(b_q8)) {
+        // b = bits + 1/2 (Sec. 4.1): every coordinate has `bits` bits in the first part; the coordinate of each pair
+        // that the MIX stream selects was quantized with the finer table and has its top bit in the second part
+        const uint64_t key = stream_key(seed, kStreamMix, B.client[c]);
+        const uint32_t sh = 16u * (uint32_t)((base >> 5) & 3u);                  // this tile's 16 pairs inside a hash word
+        const uint32_t fa = (uint32_t)(hash_word(key, (base + row_a) >> 7) >> sh) & 0xFFFFu;
+        const uint32_t fb = (uint32_t)(hash_word(key, (base + row_b) >> 7) >> sh) & 0xFFFFu;
+        const uint32_t both = fa | (fb << 16);
+        const uint32_t cbits = col * (uint32_t)bits;
+        const rsrc_t rp = make_rsrc(payload + ((base * (uint32_t)bits) >> 5), payload_bytes - (uint32_t)((base * (uint32_t)bits) >> 5) * 4u);
+        const uint32_t voff = (((g * (uint32_t)bits) << (p - 5)) + (cbits >> 5)) * 4u;
+        const uint32_t shift = cbits & 31u;
+        const uint16_t *part_b = reinterpret_cast<const uint16_t *>(payload + payload_bytes / 4u) + (base >> 5);
+        const rsrc_t rb = make_rsrc(part_b, (uint32_t)payload_b_bytes(1ull << log2D, b_q8) - (uint32_t)(base >> 5) * 2u);
+        const uint32_t voffb = (g << (p - 5)) * 2u;
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const int soff = (int)((((uint32_t)X::RL * r * (uint32_t)bits) << (p - 5)) * 4u);
+            const uint32_t w0 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, soff, 0);
+            const uint32_t w1 = (bits == 3) ? __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0) : 0u;
+            const uint32_t low = code_at(w0, w1, shift, bits);
+            const uint32_t hb = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, (int)voffb, (int)((((uint32_t)X::RL * r) << (p - 5)) * 2u), 0);
+            const uint32_t offs = __builtin_amdgcn_readlane(both, r) >> (16u * (lane >> 5));
+            const bool up = ((offs >> (col >> 1)) & 1u) == (col & 1u);
+            const uint32_t top = (hb >> (col >> 1)) & 1u;
+            v[r] = up ? table[16u + ((top << bits) | low)] : table[low];
         }
     } else {
         const uint32_t cbits = col * (uint32_t)bits;

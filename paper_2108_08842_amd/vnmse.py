@@ -6,7 +6,8 @@ For every budget b the vector x is encoded by `trials` independent senders (same
 independent rotations), each message is decoded on its own and |x - x_hat|^2 / |x|^2 is averaged: that is the
 vNMSE of Sec. 2.3.  Theory (d -> infinity): 1 / E[Q^2] - 1 for b >= 1 (Cor. 2.4 with the Lloyd-Max levels of
 Sec. 3: pi/2 - 1 at b = 1), and 1 / (p E[Q^2]) - 1 when only a fraction p of the rotated coordinates is sent or
-arrives (Lemma 4.3; b = 1/2 sends p = 1/2 of them with the 1-bit quantizer: pi - 1).  For `senders` different
+arrives (Lemma 4.3; b = 1/2 sends p = 1/2 of them with the 1-bit quantizer: pi - 1), and the half-and-half mixture
+of E[Q^2] for b = k + 1/2 (Sec. 4.1: 0.317 at b = 1.5).  For `senders` different
 vectors the NMSE of the estimated mean is compared with Thm 2.2's (1/n^2) sum_c vNMSE_c |x_c|^2 / ((1/n) sum_c |x_c|^2).
 
 The inputs are synthetic draws of the distributions the paper's appendix uses for this experiment
@@ -29,10 +30,14 @@ def expected_q2(bits: int) -> float:
 
 
 def theory_vnmse(b: float, keep: float = 1.0) -> float:
-    """Asymptotic vNMSE for budget b (0.5, or an integer >= 1) when a fraction `keep` of the packets arrives."""
+    """Asymptotic vNMSE for budget b (0.5, an integer >= 1, or an integer + 1/2) when a fraction `keep` of the
+    packets arrives.  b = k + 1/2 mixes the two quantizers half and half (Sec. 4.1: 0.317 at b = 1.5)."""
     bits = max(1, int(b))
     p = keep * min(1.0, b)
-    return 1.0 / (p * expected_q2(bits)) - 1.0
+    e = expected_q2(bits)
+    if b > 1 and b != int(b):
+        e = 0.5 * e + 0.5 * expected_q2(bits + 1)
+    return 1.0 / (p * e) - 1.0
 
 
 def draw(dist: str, d: int, gen, device):

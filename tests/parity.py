@@ -51,29 +51,47 @@ def check_encode(x: np.ndarray, seed: int, client: int, b_q8: int, gpu_msg: o.Me
     assert abs(gpu_msg.N2 - ref.N2) <= 1e-12 * ref.N2
     bits, _ = o.budget(b_q8)
     thresholds, centroids = o.tables(bits)
-    nsent = tr.kept.size
-    got = o.unpack_indices(gpu_msg.payload, bits, nsent)
-    want = tr.idx[tr.kept]
-    # padding bits after the last index are zero
-    used = nsent * bits
+    D = tr.z.size
     allbits = ((gpu_msg.payload[:, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(-1)
-    assert not allbits[used:].any()
+    if o.mixed(b_q8):
+        # b = bits + 1/2: per-coordinate width; both parts of the payload are zero after their last bit
+        wa, wb = o.plane_words(D, b_q8)
+        assert not allbits[D * bits: wa * 32].any() and not allbits[wa * 32 + D // 2:].any()
+        got = o.unpack_mixed(gpu_msg.payload, D, b_q8, tr.up)
+        want = tr.idx
+        t_hi, c_hi = o.tables(bits + 1)
+        z_sent, up_sent = tr.z, tr.up
+    else:
+        nsent = tr.kept.size
+        got = o.unpack_indices(gpu_msg.payload, bits, nsent)
+        want = tr.idx[tr.kept]
+        assert not allbits[nsent * bits:].any()                  # padding bits after the last index are zero
+        z_sent, up_sent = tr.z[tr.kept], None
     bad = np.flatnonzero(got != want)
-    stats.coords += nsent
+    stats.coords += want.size
     stats.mismatches += bad.size
     if bad.size:
         lo = np.minimum(got[bad], want[bad])
         assert np.all(np.abs(got[bad] - want[bad]) == 1), "index differs by more than one interval"
-        dist = np.abs(tr.z[tr.kept][bad] - thresholds[lo])
+        if up_sent is None:
+            thr = thresholds[lo]
+        else:
+            thr = np.where(up_sent[bad], t_hi[np.minimum(lo, t_hi.size - 1)], thresholds[np.minimum(lo, thresholds.size - 1)])
+        dist = np.abs(z_sent[bad] - thr)
         stats.worst_boundary_distance = max(stats.worst_boundary_distance, float(dist.max()))
         assert dist.max() <= INDEX_BOUNDARY_TOL, f"index mismatch {dist.max():.3e} away from its threshold"
     # The scale belongs to the message's own indices (Sec. 2.3: S = |x|^2 / <R(x), Q>): one allowed flip at an
     # outer threshold moves <R(x),Q> by ~1e-7..1e-6 of its value at D = 2^20, so the reference is the float64
     # inner product taken with the indices the GPU actually sent.
     idx_gpu = tr.idx.copy()
-    idx_gpu[tr.kept] = got
+    if up_sent is None:
+        idx_gpu[tr.kept] = got
+        Q = centroids[idx_gpu]
+    else:
+        idx_gpu = got
+        Q = np.where(tr.up, c_hi[np.minimum(idx_gpu, c_hi.size - 1)], centroids[np.minimum(idx_gpu, centroids.size - 1)])
     y = tr.z * (math.sqrt(ref.N2) / math.sqrt(tr.z.size))          # R(x) = z / eta
-    ip_ref = float(np.dot(y, centroids[idx_gpu]))
+    ip_ref = float(np.dot(y, Q))
     assert abs(gpu_msg.IP - ip_ref) <= SCALE_RTOL * ip_ref, (gpu_msg.IP, ip_ref, ref.IP)
     s_ref = ref.N2 / ip_ref
     assert abs(gpu_msg.S - s_ref) <= SCALE_RTOL * s_ref

@@ -89,17 +89,20 @@ def test_single_workgroup_sizes(ctx, d):
     _run_case(ctx, xs, [0, 1, 2], w.b_q8, w.seed)
     if d >= 2:
         _run_case(ctx, xs, [7, 8, 9], [128, 768, 256], w.seed + 1)
+        _run_case(ctx, xs, [4, 5, 6], [384, 640, 896], w.seed + 2)
 
 
 @pytest.mark.parametrize("d", [4097, 8192, 20_000, (1 << 16) + 17, 300_000, 1 << 18])
 def test_multi_pass_sizes(ctx, d):
-    w = synth.Workload("t", 5, d, [128, 256, 512, 1024, 768], 200 + d % 1000, "lognormal_signed")
-    xs = [synth.client_vector(w, c) for c in range(5)]
-    _run_case(ctx, xs, [3, 1, 4, 1_000_000, 5], w.b_q8, w.seed)
+    w = synth.Workload("t", 8, d, [128, 256, 512, 1024, 768, 384, 640, 896], 200 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(8)]
+    _run_case(ctx, xs, [3, 1, 4, 1_000_000, 5, 9, 2, 6], w.b_q8, w.seed)
+    if d > 60_000:                                            # and with lost packets
+        _run_case(ctx, xs[5:], [9, 2, 6], w.b_q8[5:], w.seed, drop_q32=int(0.2 * 2 ** 32), also_oracle_msgs=False)
 
 
 @pytest.mark.parametrize("d,budgets", [(1 << 21, [256, 1024]), ((1 << 21) + 5, [128, 512, 768]), (5_000_000, [256, 512]),
-                                       (3_000_000, [768, 768])])
+                                       (3_000_000, [768, 768]), (2_500_000, [384, 640, 896]), (1 << 23, [384, 256])])
 def test_workgroup_tile_sizes(ctx, d, budgets):
     # D = 2^21, 2^22, 2^23: strided pass of 7, 8, 9 bits in workgroup tiles + 14-bit contiguous pass
     n = len(budgets)

@@ -36,6 +36,8 @@ def test_theory_values_are_the_printed_ones():
     assert abs(vnmse.theory_vnmse(2) - 0.1331) < 1e-3                       # Example 2 prints 0.134 (from 0.88228)
     assert abs(vnmse.theory_vnmse(0.5) - (math.pi - 1)) < 1e-12             # Sec. 4.1 / Lemma 4.3 with p = 1/2
     assert abs(vnmse.theory_vnmse(1, keep=0.9) - (math.pi / 2 / 0.9 - 1)) < 1e-12
+    assert abs(vnmse.theory_vnmse(1.5) - 0.317) < 1e-3                      # Sec. 4.1
+    assert abs(vnmse.theory_vnmse(3) - 0.03572) < 1e-4                      # Sec. 4.3 (the I_3 value)
 
 
 @pytest.mark.parametrize("dist", ["normal", "lognormal"])
@@ -45,7 +47,7 @@ def test_vnmse_close_to_theory(ctx, dist):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(11)
     x = vnmse.draw(dist, d, gen, torch.device("cuda:0"))
-    for b in (0.5, 1, 2, 4):
+    for b in (0.5, 1, 1.5, 2, 2.5, 3, 3.5, 4):
         v, se = vnmse.measure_vnmse(ctx, x, int(b * 256), 16, seed=3)
         th = vnmse.theory_vnmse(b)
         print(f"{dist} b={b}: vNMSE {v:.5f} +- {se:.5f}, theory {th:.5f}", flush=True)
