@@ -295,6 +295,16 @@ def quantize_indices(z: np.ndarray, thresholds: np.ndarray) -> np.ndarray:
 # Supported here: integer b >= 1 (Q_{I_b});  b = 1/2 (Q_{I_1} + keep one of every
 # two rotated coordinates).
 # ----------------------------------------------------------------------------
+PRE_ROTATION = 0x10000   # flag in b_q8: sub-sample before the rotation (with b_q8 & 0xFFFF = 128)
+
+
+def pre_rotation(b_q8: int) -> bool:
+    """Sec. 4.1, the paper's default for b < 1: sparsify first, then run the 1-bit method in the smaller
+    dimension.  reading: b = 1/2 only, the kept coordinate of every pair (2g, 2g+1) of x is the one at
+    offset bit g of the sub-sampling stream (a stratified sample of exact size ceil(d/2))."""
+    return b_q8 == (PRE_ROTATION | 128)
+
+
 def budget(b_q8: int):
     """-> (bits per kept coordinate, keep-one-in-k).  For b = k + 1/2 the bits are k (every coordinate
     has k bits in the first part of the payload; see mixed())."""
@@ -385,12 +395,14 @@ class Message:
             "<IIQIIIIdddQ", buf[:HEADER_BYTES])
         if magic != MAGIC:
             raise ValueError("bad magic")
-        nw = payload_words(1 << log2D, b_q8)
+        nw = payload_words(1 << log2D, 256 if pre_rotation(b_q8) else b_q8)
         payload = np.frombuffer(buf, dtype="<u4", count=nw, offset=HEADER_BYTES).copy()
         return Message(log2D, d, b_q8, client, status, S, N2, IP, seed, payload)
 
 
 def message_bytes(d: int, b_q8: int) -> int:
+    if pre_rotation(b_q8):
+        return HEADER_BYTES + 4 * payload_words(padded_dim((d + 1) // 2), 256)
     return HEADER_BYTES + 4 * payload_words(padded_dim(d), b_q8)
 
 
@@ -465,8 +477,28 @@ def unpack_mixed(payload: np.ndarray, D: int, b_q8: int, up: np.ndarray) -> np.n
     return idx
 
 
+def sparsify_pairs(x: np.ndarray, seed: int, client: int):
+    """(1/p) m o x with p = 1/2, compacted: element g is 2 x[2g + off_g] (0 beyond the end of x).
+    Sec. 4.1 random sparsification; its expectation over the offsets is x scattered back."""
+    d = x.size
+    g = np.arange((d + 1) // 2)
+    src = 2 * g + subsample_offsets(seed, client, g.size).astype(np.int64)
+    xp = np.concatenate([x, [0.0]])
+    return 2.0 * xp[np.minimum(src, d)], src
+
+
 def encode(x: np.ndarray, seed: int, client: int, b_q8: int, want_trace: bool = False):
     x = np.asarray(x, dtype=np.float64)
+    if pre_rotation(b_q8):
+        # the 1-bit method on the sparsified vector; the message keeps the original d and the flagged budget
+        if x.size < 2:
+            raise ValueError("sub-sampling in pairs needs at least two coordinates")
+        xs, _ = sparsify_pairs(x, seed, client)
+        inner = encode(xs, seed, client, 256, want_trace)
+        msg, tr = inner if want_trace else (inner, None)
+        msg.d = x.size
+        msg.b_q8 = b_q8
+        return (msg, tr) if want_trace else msg
     d = x.size
     D = padded_dim(d)
     bits, k = budget(b_q8)
@@ -547,6 +579,15 @@ def decode_rotated(msg: Message, bitmap: np.ndarray | None = None) -> np.ndarray
 
 
 def decode(msg: Message, d: int, bitmap: np.ndarray | None = None) -> np.ndarray:
+    if pre_rotation(msg.b_q8):
+        # decode the 1-bit message of dimension ceil(d/2), then put every value back where it was taken from
+        dp = (d + 1) // 2
+        inner = Message(msg.log2D, dp, 256, msg.client, msg.status, msg.S, msg.N2, msg.IP, msg.seed, msg.payload)
+        xs_hat = decode(inner, dp, bitmap)
+        src = 2 * np.arange(dp) + subsample_offsets(msg.seed, msg.client, dp).astype(np.int64)
+        out = np.zeros(d + 1)
+        out[np.minimum(src, d)] = xs_hat
+        return out[:d]
     yhat = decode_rotated(msg, bitmap)
     return rotate_inverse(yhat, msg.seed, msg.client)[:d]
 

@@ -543,3 +543,73 @@ def test_half_integer_budget_unbiased_and_lossy():
     full = o.decode_rotated(msg, None)
     assert not yh[2048:3072].any()
     np.testing.assert_allclose(yh[:2048], full[:2048] * (4 / 3), rtol=1e-14)
+
+
+# ---- b = 1/2 with the sparsification before the rotation (Sec. 4.1, the paper's default for b < 1)
+PRE_HALF = o.PRE_ROTATION | 128
+
+
+def test_pre_rotation_by_hand_d4():
+    seed, client = 2, 0
+    off = o.subsample_offsets(seed, client, 2).tolist()
+    x = [3.0, -1.0, 0.5, 2.0]
+    xs = [2.0 * x[0 + off[0]], 2.0 * x[2 + off[1]]]            # (1/p) m o x, compacted; p = 1/2
+    s = [1.0 - 2.0 * v for v in o.sign_bits(seed, client, 2).tolist()]
+    a = [s[0] * xs[0], s[1] * xs[1]]
+    y = [(a[0] + a[1]) / math.sqrt(2.0), (a[0] - a[1]) / math.sqrt(2.0)]
+    n2 = xs[0] ** 2 + xs[1] ** 2
+    c = math.sqrt(2.0 / math.pi)
+    Q = [c if v >= 0 else -c for v in y]
+    S = n2 / (y[0] * Q[0] + y[1] * Q[1])
+    w = [S * Q[0], S * Q[1]]
+    v = [(w[0] + w[1]) / math.sqrt(2.0), (w[0] - w[1]) / math.sqrt(2.0)]
+    xs_hat = [s[0] * v[0], s[1] * v[1]]
+    want = [0.0] * 4
+    want[0 + off[0]] = xs_hat[0]
+    want[2 + off[1]] = xs_hat[1]
+    msg = o.encode(np.array(x), seed, client, PRE_HALF)
+    assert (msg.log2D, msg.d, msg.b_q8) == (1, 4, PRE_HALF)
+    assert msg.payload.tolist() == [(1 if y[0] >= 0 else 0) | (1 if y[1] >= 0 else 0) << 1, 0]
+    assert abs(msg.N2 - n2) < 1e-13 and abs(msg.S - S) < 1e-12
+    np.testing.assert_allclose(o.decode(msg, 4), want, atol=1e-12)
+
+
+def test_pre_rotation_sparsification_is_unbiased_with_error_one_over_p_minus_one():
+    # Sec. 4.1: random sparsification (1/p) m o x has vNMSE 1/p - 1 (= 1 at p = 1/2) and mean x
+    d = 501
+    rng = np.random.default_rng(3)
+    x = rng.lognormal(size=d)
+    acc = np.zeros(d); err = 0.0
+    trials = 4000
+    for sd in range(trials):
+        xs, src = o.sparsify_pairs(x, sd, 0)
+        back = np.zeros(d + 1); back[np.minimum(src, d)] = xs; back = back[:d]
+        acc += back; err += np.sum((back - x) ** 2)
+    assert abs(err / trials / np.dot(x, x) - 1.0) < 0.03
+    assert np.linalg.norm(acc / trials - x) / np.linalg.norm(x) < 1.3 * math.sqrt(1.0 / trials)
+
+
+def test_pre_rotation_message_is_the_one_bit_message_of_half_the_dimension():
+    d = 6000
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal(d)
+    msg = o.encode(x, 9, 3, PRE_HALF)
+    assert msg.log2D == 12 and msg.payload.size == 4096 // 32 and msg.d == d      # D' = 4096, not 8192
+    assert o.message_bytes(d, PRE_HALF) == len(msg.to_bytes()) == 64 + 4096 // 8
+    xs, src = o.sparsify_pairs(x, 9, 3)
+    inner = o.encode(xs, 9, 3, 256)
+    np.testing.assert_array_equal(inner.payload, msg.payload)
+    assert inner.S == msg.S and inner.N2 == msg.N2
+    got = o.decode(o.Message.from_bytes(msg.to_bytes()), d)
+    assert np.count_nonzero(got) == d // 2                                         # one coordinate of every pair
+    np.testing.assert_allclose(got[src], o.decode(inner, d // 2), rtol=0, atol=0)
+
+
+def test_pre_rotation_vnmse_is_pi_minus_one():
+    # error of the sparsification (1/p - 1) plus 1/p times the 1-bit error: (1/p)(1 + vNMSE_1) - 1 = pi - 1,
+    # the value Sec. 4.1 / Lemma 4.3 give for sparsification after the rotation ("similar in both cases")
+    d = 1 << 12
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(d)
+    v = np.mean([o.vnmse_single(x, o.decode(o.encode(x, sd, 0, PRE_HALF), d)) for sd in range(60)])
+    assert abs(v - (math.pi - 1)) < 0.03 * (math.pi - 1)
