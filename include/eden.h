@@ -45,6 +45,12 @@
  *     with I_{k+1}, the other one with I_k.  The paper flips an independent coin per coordinate,
  *     which makes the message length random; choosing exactly one coordinate of every pair is as
  *     content independent and gives exactly (k + 1/2) D bits at positions known without a scan).
+ *     EDEN_B_HALF_PRE (0x10080): b = 1/2 with the sparsification before the rotation (Sec. 4.1, the
+ *     paper's default for b < 1): x'[g] = 2 x[2g + o_g], g < ceil(d/2), o_g = bit (g & 63) of word (g >> 6)
+ *     of the SUB-SAMPLING stream (x read as 0 beyond d), is encoded with b = 1 in dimension ceil(d/2): the
+ *     transform and the message are half as large; the decoder puts value g back at 2g + o_g and leaves the
+ *     other coordinate of the pair 0.  In one call either every sender uses this budget or none (the
+ *     transform dimension differs).  The header keeps d and this b_q8; log2(D) is that of ceil(d/2).
  *   - Index of a coordinate = rank of its interval in ascending order (0 = most negative).  At an
  *     interval endpoint the interval closer to zero is taken; z = 0 belongs to the non-negative
  *     side (Sec. 2.2.1 and its footnote).
@@ -65,6 +71,8 @@
  */
 #ifndef EDEN_H
 #define EDEN_H
+
+#define EDEN_B_HALF_PRE 0x10080u
 
 #include <stddef.h>
 #include <stdint.h>

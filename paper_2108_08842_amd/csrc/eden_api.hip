@@ -110,6 +110,7 @@ struct Timed {
 extern "C" {
 
 size_t eden_message_bytes(uint64_t d, uint32_t b_q8) {
+    if (b_q8 == kPreHalf) return d >= 2 ? eden_message_bytes((d + 1) / 2, 256) : 0;
     int bits, k;
     if (d == 0 || d > (1ull << EDEN_MAX_LOG2_D) || !budget_of(b_q8, bits, k)) return 0;
     const uint64_t D = 1ull << ceil_log2(d);
@@ -198,6 +199,12 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return EDEN_ERR_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // sparsification before the rotation: all senders or none; the transform then has dimension ceil(d/2)
+    int pre = 0;
+    for (uint32_t c = 0; c < n; ++c) pre += (b_q8[c] == kPreHalf);
+    if (pre != 0 && pre != (int)n) return EDEN_ERR_INVALID_ARG;
+    const uint64_t d_src = d;
+    if (pre) d = (d + 1) / 2;
     const int log2D = ceil_log2(d);
     const Plan pl = make_plan(log2D);
 
@@ -209,11 +216,11 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             B.x[i] = x_dev[first + i];
             B.msg[i] = msgs_dev[first + i];
             B.client[i] = client_ids[first + i];
-            B.b_q8[i] = b_q8[first + i];
+            B.b_q8[i] = pre ? 256u : b_q8[first + i];
         }
         if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_ENC_SMALL, nb, st);
-            launch_enc_small(B, nb, d, log2D, seed, ctx->tables, ctx->dev_status, st);
+            launch_enc_small(B, nb, d_src, pre, log2D, seed, ctx->tables, ctx->dev_status, st);
         } else {
             // contiguous pass first (it reads x, and only the tiles that hold part of x), strided passes after it in
             // place on the workspace, the last one quantizing and packing
@@ -224,8 +231,8 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             {
                 Timed t(ctx, EDEN_K_ENC_FIRST, nb, st);
                 nparts_n2 = pl.lo_bits == 14
-                                ? launch_enc_lo14_first(B, nb, d, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st)
-                                : launch_enc_lo_first(B, nb, d, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st);
+                                ? launch_enc_lo14_first(B, nb, d_src, pre, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st)
+                                : launch_enc_lo_first(B, nb, d_src, pre, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st);
             }
             if (need_thresholds) {
                 Timed t(ctx, EDEN_K_ENC_NORM, nb, st);
@@ -247,7 +254,7 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
                 }
             }
             Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
-            launch_enc_finish(B, nb, d, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
+            launch_enc_finish(B, nb, d_src, pre, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
                               ctx->dev_status, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
@@ -268,6 +275,11 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return EDEN_ERR_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    int pre = 0;                                                 // sparsification before the rotation: all or none
+    for (uint32_t c = 0; c < n; ++c) pre += (b_q8[c] == kPreHalf);
+    if (pre != 0 && pre != (int)n) return EDEN_ERR_INVALID_ARG;
+    const uint64_t d_src = d;
+    if (pre) d = (d + 1) / 2;
     const int log2D = ceil_log2(d);
     const Plan pl = make_plan(log2D);
 
@@ -279,18 +291,18 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             B.msg[i] = msgs_dev[first + i];
             B.bitmap[i] = recv_bitmaps_dev ? recv_bitmaps_dev[first + i] : nullptr;
             B.client[i] = client_ids[first + i];
-            B.b_q8[i] = b_q8[first + i];
+            B.b_q8[i] = pre ? 256u : b_q8[first + i];
         }
         if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);
-            launch_dec_small(B, nb, d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
+            launch_dec_small(B, nb, d_src, pre, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
         } else {
             // Strided passes first (every sender on its own), contiguous pass last (sums the senders in registers
             // and touches acc once).  With a single strided pass the workspace of a b <= 1 sender holds int16.
             const int narrow = (pl.nhi == 1) ? 1 : 0;
             {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
-                launch_dec_prepare(B, nb, d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
+                launch_dec_prepare(B, nb, d_src, pre, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
             }
             for (int i = pl.nhi - 1; i >= 0; --i) {
                 const HiPass &h = pl.hi[i];
@@ -307,9 +319,9 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
             }
             Timed t(ctx, EDEN_K_DEC_LAST, nb, st);
             if (pl.lo_bits == 14)
-                launch_dec_lo14_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, 2 * ctx->compute_units,
+                launch_dec_lo14_last(B, nb, d_src, pre, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, 2 * ctx->compute_units,
                                      ctx->dec_partial, ctx->dec_partial_tiles, st);
-            else launch_dec_lo_last(B, nb, d, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
+            else launch_dec_lo_last(B, nb, d_src, pre, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
     }

@@ -34,6 +34,10 @@ __host__ __device__ inline uint64_t hash_word(uint64_t key, uint64_t j) { return
 // b = 1.5, 2.5, 3.5 ("mixed"): every coordinate has floor(b) bits in the first part of the payload and one
 // coordinate of every pair, chosen by the MIX stream, one more bit in a second part (it is quantized with the
 // next finer table).
+// b = 1/2 with the sparsification before the rotation (Sec. 4.1, the paper's default for b < 1): the vector
+// x'[g] = 2 x[2g + offset_g] of dimension ceil(d/2) is encoded with b = 1; the kernels then see b_q8 = 256 and
+// only the gather (first encode pass), the scatter (last decode pass) and the header know about it.
+constexpr uint32_t kPreHalf = 0x10000u | 128u;
 __host__ __device__ inline bool budget_mixed(uint32_t b_q8) { return b_q8 == 384 || b_q8 == 640 || b_q8 == 896; }
 __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
     if (b_q8 == 128) { bits = 1; k = 2; return true; }

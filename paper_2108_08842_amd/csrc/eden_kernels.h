@@ -13,26 +13,28 @@ namespace eden {
 // sender got.
 
 // wave-tile passes and the small kernels (eden_kernels.hip)
-uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T, double *partials,
-                             uint32_t partial_stride, hipStream_t st);
+// `d` with a `pre` flag next to it is the caller's dimension; pre != 0 (b = 1/2 with the sparsification before the
+// rotation) means the transformed vector has dimension ceil(d/2).  Every other `d` is the transformed dimension.
+uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
+                             double *partials, uint32_t partial_stride, hipStream_t st);
 uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, int p, uint64_t seed,
                             const float *T, double *partials, uint32_t partial_stride, const EncScratch *scratch,
                             hipStream_t st);
 void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint32_t partial_stride, uint32_t nparts,
                      EncScratch *scratch, const DevTables *tab, hipStream_t st);
-void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials_n2,
-                       uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip, uint32_t partial_stride,
-                       uint32_t *dev_status, hipStream_t st);
-void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed,
+                       const double *partials_n2, uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip,
+                       uint32_t partial_stride, uint32_t *dev_status, hipStream_t st);
+void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st);
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                          const DecScratch *scratch, int narrow, float *T, hipStream_t st);
-void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st);
-void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
                       uint32_t *dev_status, hipStream_t st);
-void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
                       float *acc, uint32_t *dev_status, hipStream_t st);
 void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
                      hipStream_t st);
@@ -47,11 +49,11 @@ void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
                           const DecScratch *scratch, int narrow, float *T, hipStream_t st);
 
 // 14-bit contiguous passes for D >= 2^19 (eden_kernels_lo14.hip)
-uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T,
+uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
                                double *partials, uint32_t partial_stride, hipStream_t st);
 // `resident`: workgroups of the kernel the device holds at once (2 per CU); `partial`: room for `partial_tiles`
 // tiles of 2^14 floats, used when tiles are split over several workgroups by sender
-void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const float *T,
                           const DecScratch *scratch, int narrow, float *acc, uint32_t resident, float *partial,
                           uint32_t partial_tiles, hipStream_t st);
 

@@ -327,7 +327,9 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
 // pass that follows reads the others as zero through its buffer bounds.  Loads and stores are both in the
 // layout "register j = coordinates 64 j + lane" (256 contiguous bytes per wave access), so the tile goes
 // through the wave-private 64x64 LDS transpose twice.
-__global__ __launch_bounds__(128) void k_enc_lo_first(EncBatch B, uint64_t d, int log2D, uint64_t seed, float *T,
+// `pre` (b = 1/2 with the sparsification first, Sec. 4.1): the vector that is transformed is
+// x'[g] = 2 x[2g + o_g], g < ceil(d_src/2), o_g from the SUB-SAMPLING stream; x is read as 0 beyond d_src.
+__global__ __launch_bounds__(128) void k_enc_lo_first(EncBatch B, uint64_t d_src, int pre, int log2D, uint64_t seed, float *T,
                                                       double *partials, uint32_t partial_stride) {
     __shared__ float lds[2][64 * kLdsRow];
     __shared__ double red[2];
@@ -336,12 +338,23 @@ __global__ __launch_bounds__(128) void k_enc_lo_first(EncBatch B, uint64_t d, in
     const uint32_t wv = wave_in_block();
     const uint32_t tile = blockIdx.x * 2u + wv;
     const uint64_t tile_base = (uint64_t)tile << kLoBits;
+    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the vector that is transformed
     double n2 = 0.0;
     if (tile_base < d) {                                         // wave-uniform; no block-wide barrier inside
-        const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));          // reads past d give the zero padding
+        const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d_src * 4));      // reads past d_src give the zero padding
         float v[64];
+        if (pre) {
+            // register j = 64 consecutive pairs = one word of offsets: lane l hashes the word of register l
+            const uint64_t offs = hash_word(stream_key(seed, kStreamSubsample, B.client[c]), (tile_base >> 6) + lane);
 #pragma unroll
-        for (int j = 0; j < 64; ++j) v[j] = buf_load(rx, lane * 4u, (uint32_t)tile_base * 4u + 256u * j);
+            for (int j = 0; j < 64; ++j) {
+                const uint32_t odd = __builtin_amdgcn_inverse_ballot_w64(wave_read64(offs, j)) ? 4u : 0u;
+                v[j] = 2.0f * buf_load(rx, lane * 8u + odd, (uint32_t)tile_base * 8u + 512u * j);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 64; ++j) v[j] = buf_load(rx, lane * 4u, (uint32_t)tile_base * 4u + 256u * j);
+        }
 #pragma unroll
         for (int j = 0; j < 64; ++j) n2 += (double)v[j] * (double)v[j];
         // register j = 64 consecutive coordinates = one sign word: lane l hashes the word of register l,
@@ -376,7 +389,7 @@ __global__ __launch_bounds__(128) void k_enc_lo_first(EncBatch B, uint64_t d, in
 // One workgroup per sender: sums the partials of sum_i u_i q_i in index order, forms
 // <R(x),Q> = D^-1/2 sum and the scale S = |x|^2 / <R(x),Q> (Sec. 2.3), writes the header.
 // A zero or non-finite vector gets S = 0, a status bit and an all-zero payload.
-__global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int log2D, uint64_t seed,
+__global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int pre, int log2D, uint64_t seed,
                                                     const double *partials_n2, uint32_t nparts_n2,
                                                     const double *partials_ip, uint32_t nparts_ip,
                                                     uint32_t partial_stride, uint32_t payload_words_b1,
@@ -404,7 +417,7 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int 
     }
     if (threadIdx.x == 0) {
         MsgHeader h;
-        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = b_q8; h.client = B.client[c];
+        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = pre ? kPreHalf : b_q8; h.client = B.client[c];
         h.zero = 0; h.seed = seed; h.N2 = n2;
         if (valid) {
             h.IP = total * exp2(-0.5 * (double)log2D);       // <R(x),Q> = D^-1/2 sum u_i q_i
@@ -426,13 +439,13 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int 
 // that arrived (Sec. 4.2: the receiver finds p by counting), and build the dequantization table
 // (S / (p sqrt(D))) * q_l  -- S/p from Sec. 4.2, D^-1/2 from the inverse rotation.
 __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap, uint32_t client, uint32_t b_q8,
-                                        uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+                                        uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
                                         DecScratch *out, uint32_t *dev_status) {
     const uint32_t lane = lane_id();
     const MsgHeader h = *static_cast<const MsgHeader *>(msg);
     uint32_t flags = 0;
-    if (h.magic != kMagic || h.log2D != (uint32_t)log2D || h.d != d || h.b_q8 != b_q8 || h.client != client ||
-        h.seed != seed)
+    if (h.magic != kMagic || h.log2D != (uint32_t)log2D || h.d != d || h.b_q8 != (pre ? kPreHalf : b_q8) ||
+        h.client != client || h.seed != seed)
         flags |= EDEN_DEV_HEADER_MISMATCH;
     else
         flags |= h.status & (EDEN_DEV_ZERO_VECTOR | EDEN_DEV_NONFINITE);
@@ -471,21 +484,25 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
     }
 }
 
-__global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t d, int log2D, uint64_t seed,
+__global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t d, int pre, int log2D, uint64_t seed,
                                                     const DevTables *tab, DecScratch *scratch, uint32_t *dev_status) {
     const uint32_t c = blockIdx.x;
-    dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, log2D, seed, tab, &scratch[c], dev_status);
+    dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, pre, log2D, seed, tab, &scratch[c], dev_status);
 }
 
 // Decode, last pass in wave tiles: index bits 0..11 of H for every sender, that sender's sign diagonal
 // (R^-1 = s o D^-1/2 H, Sec. 2.2.2; D^-1/2 is inside the dequantization scale), sum over senders in registers,
 // one contiguous read-modify-write of acc.  A lane ends with 64 consecutive coordinates = one sign word.
-__global__ __launch_bounds__(128) void k_dec_lo_last(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+// `pre` (b = 1/2 with the sparsification first, Sec. 4.1): the decoded vector has dimension ceil(d_src/2) and value g
+// of sender c belongs at coordinate 2g + o_g of acc (o_g from c's SUB-SAMPLING stream); since the places differ from
+// sender to sender, every sender's values are added to acc directly.
+__global__ __launch_bounds__(128) void k_dec_lo_last(DecBatch B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed,
                                                      const float *T, const DecScratch *scratch, int narrow, float *acc) {
     __shared__ float lds[2][64 * kLdsRow];
     const uint32_t lane = lane_id(), wv = wave_in_block();
     const uint32_t tile = blockIdx.x * 2u + wv;
     const uint64_t tile_base = (uint64_t)tile << kLoBits;
+    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the decoded vector
     if (tile_base >= d) return;                                  // whole tile in the padding (no block-wide barrier below)
     const uint64_t first = tile_base + 64u * lane;               // this lane's 64 coordinates after the transpose
     float *L = lds[wv];
@@ -518,6 +535,16 @@ __global__ __launch_bounds__(128) void k_dec_lo_last(DecBatch B, uint32_t n, uin
         const uint32_t scale = __float_as_uint(i16 ? scratch[c].deq[1] : 1.0f) & 0x7FFFFFFFu;   // > 0; x*1+s is exact
         const uint64_t word = hash_word(stream_key(seed, kStreamSign, B.client[c]), first >> 6);
         const uint32_t wlo = (uint32_t)word, whi = (uint32_t)(word >> 32);
+        if (pre) {
+            const uint64_t offs = hash_word(stream_key(seed, kStreamSubsample, B.client[c]), first >> 6);
+#pragma unroll
+            for (int k = 0; k < 64; ++k) {
+                const uint32_t sbit = ((k < 32 ? wlo : whi) << (31 - (k & 31))) & 0x80000000u;
+                const uint64_t pos = 2 * (first + k) + ((offs >> k) & 1ull);
+                if (first + k < d && pos < d_src) acc[pos] = fmaf(v[k], __uint_as_float(scale | sbit), acc[pos]);
+            }
+            continue;
+        }
 #pragma unroll
         for (int k = 0; k < 32; ++k)
             sum[k] = fmaf(v[k], __uint_as_float(scale | ((wlo << (31 - k)) & 0x80000000u)), sum[k]);   // bit 1 -> s_i = -1
@@ -525,6 +552,7 @@ __global__ __launch_bounds__(128) void k_dec_lo_last(DecBatch B, uint32_t n, uin
         for (int k = 0; k < 32; ++k)
             sum[32 + k] = fmaf(v[32 + k], __uint_as_float(scale | ((whi << (31 - k)) & 0x80000000u)), sum[32 + k]);
     }
+    if (pre) return;
     if (first + 64 <= d) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
@@ -590,7 +618,7 @@ __device__ inline void fwht_lds(float *buf, uint32_t D) {
     __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int log2D, uint64_t seed,
+__global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int pre, int log2D, uint64_t seed,
                                                    const DevTables *tab, uint32_t *dev_status) {
     __shared__ float buf[kLoTile];
     __shared__ uint8_t code[kLoTile];
@@ -600,9 +628,16 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int l
     const uint32_t D = 1u << log2D;
     const float *x = B.x[c];
     const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+    const uint64_t prekey = stream_key(seed, kStreamSubsample, B.client[c]);
     double n2p = 0.0;
     for (uint32_t i = threadIdx.x; i < D; i += 256) {
-        const float xi = (i < d) ? x[i] : 0.0f;
+        float xi;
+        if (pre) {                                             // Sec. 4.1: x'[i] = 2 x[2i + o_i], sparsification before the rotation
+            const uint64_t src = 2ull * i + ((hash_word(prekey, i >> 6) >> (i & 63u)) & 1ull);
+            xi = (src < d) ? 2.0f * x[src] : 0.0f;
+        } else {
+            xi = (i < d) ? x[i] : 0.0f;
+        }
         n2p += (double)xi * (double)xi;
         const bool neg = (hash_word(key, i >> 6) >> (i & 63u)) & 1ull;
         buf[i] = (neg ? -xi : xi) + 0.0f;
@@ -663,7 +698,7 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int l
     }
     if (threadIdx.x == 0) {
         MsgHeader h;
-        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = b_q8; h.client = B.client[c];
+        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = pre ? kPreHalf : b_q8; h.client = B.client[c];
         h.zero = 0; h.seed = seed; h.N2 = n2;
         if (valid) {
             h.IP = ipt * exp2(-0.5 * (double)log2D);
@@ -680,7 +715,7 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int l
 
 // One workgroup decodes the whole batch: per sender fill LDS with the dequantized rotated vector,
 // transform, apply the signs and add into per-thread sums; acc is touched once at the end.
-__global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+__global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed,
                                                    const DevTables *tab, float *acc, uint32_t *dev_status) {
     __shared__ float buf[kLoTile];
     __shared__ DecScratch s;
@@ -691,7 +726,7 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
     for (uint32_t c = 0; c < n; ++c) {
         __syncthreads();
         if (threadIdx.x < 64)
-            dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, log2D, seed, tab, &s, dev_status);
+            dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, pre, log2D, seed, tab, &s, dev_status);
         __syncthreads();
         const uint32_t b_q8 = B.b_q8[c];
         int bits, k;
@@ -729,14 +764,20 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
             const uint32_t i = threadIdx.x + 256u * r;
             if (i < D) {
                 const bool neg = (hash_word(key, i >> 6) >> (i & 63u)) & 1ull;
-                sum[r] += neg ? -buf[i] : buf[i];
+                const float val = neg ? -buf[i] : buf[i];
+                if (pre) {                                     // value i of this sender belongs at 2i + o_i (Sec. 4.1)
+                    const uint64_t pos = 2ull * i + ((hash_word(subkey, i >> 6) >> (i & 63u)) & 1ull);
+                    if (pos < d) acc[pos] += val;
+                } else {
+                    sum[r] += val;
+                }
             }
         }
     }
 #pragma unroll
     for (int r = 0; r < kLoTile / 256; ++r) {
         const uint32_t i = threadIdx.x + 256u * r;
-        if (i < d && i < D) acc[i] += sum[r];
+        if (!pre && i < d && i < D) acc[i] += sum[r];
     }
 }
 
@@ -785,11 +826,11 @@ void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint
                      EncScratch *scratch, const DevTables *tab, hipStream_t st) {
     hipLaunchKernelGGL(k_enc_norm, dim3(n), dim3(256), 0, st, B, partials, partial_stride, nparts, scratch, tab);
 }
-void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const double *partials_n2,
-                       uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip, uint32_t partial_stride,
-                       uint32_t *dev_status, hipStream_t st) {
+void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed,
+                       const double *partials_n2, uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip,
+                       uint32_t partial_stride, uint32_t *dev_status, hipStream_t st) {
     const uint32_t words_b1 = 1u << (log2D - 5);
-    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, log2D, seed, partials_n2, nparts_n2, partials_ip,
+    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, pre, log2D, seed, partials_n2, nparts_n2, partials_ip,
                        nparts_ip, partial_stride, words_b1, dev_status);
 }
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
@@ -799,21 +840,22 @@ void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_ele
     EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_first<MM>, grid, dim3(256), 0, st, B, keep_elems, log2D, p, seed, scratch, narrow,
                                          T));
 }
-uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T, double *partials,
-                             uint32_t partial_stride, hipStream_t st) {
+uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, float *T,
+                             double *partials, uint32_t partial_stride, hipStream_t st) {
+    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;
     const uint32_t tiles = (uint32_t)((d + (1u << kLoBits) - 1) >> kLoBits);
     dim3 grid((tiles + 1) / 2, n);
-    hipLaunchKernelGGL(k_enc_lo_first, grid, dim3(128), 0, st, B, d, log2D, seed, T, partials, partial_stride);
+    hipLaunchKernelGGL(k_enc_lo_first, grid, dim3(128), 0, st, B, d_src, pre, log2D, seed, T, partials, partial_stride);
     return grid.x;
 }
-void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st) {
-    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, d, log2D, seed, tab, scratch, dev_status);
+    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, d, pre, log2D, seed, tab, scratch, dev_status);
 }
-void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
     dim3 grid(1u << (log2D - kLoBits - 1));
-    hipLaunchKernelGGL(k_dec_lo_last, grid, dim3(128), 0, st, B, n, d, log2D, seed, T, scratch, narrow, acc);
+    hipLaunchKernelGGL(k_dec_lo_last, grid, dim3(128), 0, st, B, n, d, pre, log2D, seed, T, scratch, narrow, acc);
 }
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st) {
     const int vec = ((reinterpret_cast<uintptr_t>(acc) | reinterpret_cast<uintptr_t>(mean)) & 15u) == 0;
@@ -830,13 +872,13 @@ void launch_sq_error(const float *a, const float *b, uint64_t d, double *partial
     hipLaunchKernelGGL(k_sq_error, dim3(blocks), dim3(256), 0, st, a, b, d, partials);
     hipLaunchKernelGGL(k_sq_error_finish, dim3(1), dim3(256), 0, st, partials, blocks, out);
 }
-void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab,
+void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
                       uint32_t *dev_status, hipStream_t st) {
-    hipLaunchKernelGGL(k_enc_small, dim3(n), dim3(256), 0, st, B, d, log2D, seed, tab, dev_status);
+    hipLaunchKernelGGL(k_enc_small, dim3(n), dim3(256), 0, st, B, d, pre, log2D, seed, tab, dev_status);
 }
-void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const DevTables *tab, float *acc,
-                      uint32_t *dev_status, hipStream_t st) {
-    hipLaunchKernelGGL(k_dec_small, dim3(1), dim3(256), 0, st, B, n, d, log2D, seed, tab, acc, dev_status);
+void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
+                      float *acc, uint32_t *dev_status, hipStream_t st) {
+    hipLaunchKernelGGL(k_dec_small, dim3(1), dim3(256), 0, st, B, n, d, pre, log2D, seed, tab, acc, dev_status);
 }
 void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st) {
     hipLaunchKernelGGL(k_hash_bits, dim3((uint32_t)((nwords + 255) / 256)), dim3(256), 0, st, key, nwords, out);

@@ -81,30 +81,48 @@ __device__ inline void lo14_store_runs(const float (&v)[32], float *L, float *ds
 // the rotation from the shared seed (Sec. 2.1), |x|^2 for eta and S (Sec. 2.2.1, 2.3), index bits 0..13 of H.
 // Only the ceil(d / 2^14) tiles that hold part of x are transformed and written: a tile of padding stays zero
 // under these 14 bits, and the strided pass that follows reads it as zero through its buffer bounds.
-template <int TPW>
-__global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t d, int log2D, uint64_t seed, float *T,
+// PRE (b = 1/2 with the sparsification first, Sec. 4.1): the vector that is transformed is x'[g] = 2 x[2g + o_g],
+// g < ceil(d_src/2), o_g from the SUB-SAMPLING stream; x is read as 0 beyond d_src.
+template <int TPW, bool PRE>
+__global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t d_src, int log2D, uint64_t seed, float *T,
                                                         double *partials, uint32_t partial_stride) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14LdsWords];
     __shared__ double red[8];
     const uint32_t c = blockIdx.y, t = threadIdx.x, lane = t & 63u;
     const uint32_t wv = wave_in_block();
+    const uint64_t d = PRE ? (d_src + 1) / 2 : d_src;            // dimension of the vector that is transformed
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);
-    const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d * 4));               // reads past d give the zero padding
+    const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d_src * 4));           // reads past d_src give the zero padding
     float *Tc = T + ((size_t)c << log2D);
     const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+    const uint64_t prekey = stream_key(seed, kStreamSubsample, B.client[c]);
     const uint32_t lane_off = (wv * 64u + lane) * 4u;
     const uint32_t tile0 = blockIdx.x * TPW;
     double n2 = 0.0;
-    float next[32];
+    // element 512 a + 64 wave + lane of a tile; with PRE it comes from x[2 i + o_i], and register a of this wave is
+    // 64 consecutive pairs = one word of offsets (lane l < 32 hashes the word of register l)
+    auto load_tile = [&](uint32_t tile, float (&dst)[32]) {
+        if constexpr (PRE) {
+            const uint64_t offs = hash_word(prekey, ((uint64_t)tile << (kLo14Bits - 6)) + 8u * (lane & 31u) + wv);
 #pragma unroll
-    for (int a = 0; a < 32; ++a) next[a] = buf_load(rx, lane_off, (tile0 << (kLo14Bits + 2)) + 2048u * a);
+            for (int a = 0; a < 32; ++a) {
+                const uint32_t odd = __builtin_amdgcn_inverse_ballot_w64(wave_read64(offs, a)) ? 4u : 0u;
+                dst[a] = buf_load(rx, 2u * lane_off + odd, (tile << (kLo14Bits + 3)) + 4096u * a);
+            }
+        } else {
+#pragma unroll
+            for (int a = 0; a < 32; ++a) dst[a] = buf_load(rx, lane_off, (tile << (kLo14Bits + 2)) + 2048u * a);
+        }
+    };
+    float next[32];
+    load_tile(tile0, next);
 #pragma unroll
     for (int k = 0; k < TPW; ++k) {
         const uint32_t tile = tile0 + k;
         if (tile >= tiles) break;                                // same decision in every thread of the workgroup
         float u[32];
 #pragma unroll
-        for (int a = 0; a < 32; ++a) u[a] = next[a];
+        for (int a = 0; a < 32; ++a) u[a] = PRE ? 2.0f * next[a] : next[a];
 #pragma unroll
         for (int a = 0; a < 32; ++a) {
             n2 += (double)u[a] * (double)u[a];
@@ -115,10 +133,7 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
         const uint64_t mine = hash_word(key, ((uint64_t)tile << (kLo14Bits - 6)) + 8u * (lane & 31u) + wv);
 #pragma unroll
         for (int a = 0; a < 32; ++a) u[a] = negate_where(u[a], wave_read64(mine, a)) + 0.0f;   // + 0: no negative zeros
-        if (k + 1 < TPW) {
-#pragma unroll
-            for (int a = 0; a < 32; ++a) next[a] = buf_load(rx, lane_off, ((tile + 1u) << (kLo14Bits + 2)) + 2048u * a);
-        }
+        if (k + 1 < TPW) load_tile(tile + 1u, next);
         lo14_forward32(u, lds);
         lo14_store_runs(u, lds + wv * kXbWave, Tc + ((size_t)tile << kLo14Bits) + 2048u * wv);
         if (k + 1 < TPW) __syncthreads();                        // LDS is reused by the next tile
@@ -137,11 +152,19 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
 // tiles get one workgroup each that sums all n senders into acc.  Each of the remaining tiles gets K workgroups: group 0 sums its share of the senders into acc,
 // group k > 0 stores its sum in partial[k-1][tile - full_tiles][2^14]; k_dec_lo14_combine then adds those to
 // acc in the order k = 1, 2, ... (fixed, so the result does not depend on scheduling).
-__global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+//
+// PRE (b = 1/2 with the sparsification first, Sec. 4.1): the decoded vectors have dimension ceil(d_src/2) and value g
+// of sender c belongs at coordinate 2g + o_g of acc (o_g from c's SUB-SAMPLING stream).  A thread then keeps the 64
+// accumulator coordinates of its 32 pairs in registers and adds every value to the member of the pair it belongs
+// to; the launcher does not split tiles in this mode.
+template <bool PRE>
+__global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d_src, int log2D, uint64_t seed,
                                                        const float *T, const DecScratch *scratch, int narrow, float *acc,
                                                        uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
                                                        float *partial) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14LdsWords];
+    constexpr int NS = PRE ? 64 : 32;                            // accumulator coordinates per thread
+    const uint64_t d = d_src;                                    // bound of acc
     const uint32_t t = threadIdx.x, lane = t & 63u, wv = t >> 6;
     uint32_t tile = blockIdx.x, c_begin = 0, c_end = n;
     float *part_run = nullptr;                                   // this thread's 32 values in the partial buffer
@@ -155,9 +178,9 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     const uint64_t tile_base = (uint64_t)tile << kLo14Bits;
     const uint64_t first = tile_base + 32u * t;
     const size_t in_off = tile_base + wv * 64u + lane;
-    float sum[32];
+    float sum[NS];
 #pragma unroll
-    for (int e = 0; e < 32; ++e) sum[e] = 0.0f;
+    for (int e = 0; e < NS; ++e) sum[e] = 0.0f;
 
     auto load = [&](uint32_t c, float (&dst_regs)[32]) {
         if (narrow && B.b_q8[c] <= 256u) {
@@ -171,13 +194,14 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
         }
     };
     float next[32];
-    if (c_begin < c_end) load(c_begin, next);
+    if (!PRE && c_begin < c_end) load(c_begin, next);            // with 64 accumulators there is no room to load ahead
     for (uint32_t c = c_begin; c < c_end; ++c) {
         const bool i16 = narrow && B.b_q8[c] <= 256u;
         float u[32];
+        if constexpr (PRE) load(c, next);
 #pragma unroll
         for (int a = 0; a < 32; ++a) u[a] = i16 ? (float)__float_as_int(next[a]) : next[a];
-        if (c + 1 < c_end) load(c + 1, next);
+        if (!PRE && c + 1 < c_end) load(c + 1, next);
         lo14_forward32(u, lds);
         const uint32_t scale = __float_as_uint(i16 ? scratch[c].deq[1] : 1.0f) & 0x7FFFFFFFu;   // > 0; x*1+s is exact
         // the wave's 2048 coordinates use 32 sign words: lane l < 32 hashes word l, every thread fetches its own
@@ -187,12 +211,44 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
         const uint32_t wlo = (uint32_t)__shfl((int)(uint32_t)mine, (int)src, 64);
         const uint32_t whi = (uint32_t)__shfl((int)(uint32_t)(mine >> 32), (int)src, 64);
         const uint32_t bits = (t & 1u) ? whi : wlo;              // 32 sign bits of this thread's run
+        if constexpr (PRE) {
+            const uint64_t okey = stream_key(seed, kStreamSubsample, B.client[c]);
+            const uint64_t omine = hash_word(okey, ((tile_base + 512u * (wv * 4u)) >> 6) + (lane & 31u));
+            const uint32_t olo = (uint32_t)__shfl((int)(uint32_t)omine, (int)src, 64);
+            const uint32_t ohi = (uint32_t)__shfl((int)(uint32_t)(omine >> 32), (int)src, 64);
+            const uint32_t offs = (t & 1u) ? ohi : olo;          // which member of each of this thread's 32 pairs
 #pragma unroll
-        for (int e = 0; e < 32; ++e) {
-            const uint32_t sgn = (bits << (31 - e)) & 0x80000000u;          // hash bit 1 -> s_i = -1
-            sum[e] = fmaf(u[e], __uint_as_float(scale | sgn), sum[e]);
+            for (int e = 0; e < 32; ++e) {
+                const uint32_t sgn = (bits << (31 - e)) & 0x80000000u;
+                const float val = u[e] * __uint_as_float(scale | sgn);
+                const bool odd = (offs >> e) & 1u;
+                sum[2 * e] += odd ? 0.0f : val;
+                sum[2 * e + 1] += odd ? val : 0.0f;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                const uint32_t sgn = (bits << (31 - e)) & 0x80000000u;          // hash bit 1 -> s_i = -1
+                sum[e] = fmaf(u[e], __uint_as_float(scale | sgn), sum[e]);
+            }
         }
         __syncthreads();                                         // LDS is reused by the next sender
+    }
+    if constexpr (PRE) {                                         // this thread's 32 pairs = 64 consecutive coordinates of acc
+        const uint64_t out = 2 * first;
+        if (out + 64 <= d) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                float4 a = *reinterpret_cast<const float4 *>(acc + out + 4 * q);
+                a.x += sum[4 * q]; a.y += sum[4 * q + 1]; a.z += sum[4 * q + 2]; a.w += sum[4 * q + 3];
+                *reinterpret_cast<float4 *>(acc + out + 4 * q) = a;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 64; ++e)
+                if (out + e < d) acc[out + e] += sum[e];
+        }
+        return;
     }
     if (part_run) {
 #pragma unroll
@@ -231,22 +287,31 @@ __global__ __launch_bounds__(256) void k_dec_lo14_combine(float *acc, uint64_t d
         if (i + e < d) acc[i + e] = s[e];
 }
 
-uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, float *T,
+uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, float *T,
                                double *partials, uint32_t partial_stride, hipStream_t st) {
+    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);
-    if (tiles >= 256) {                                          // pairs of tiles: the second one's loads overlap the first
-        dim3 grid((tiles + 1) / 2, n);
-        hipLaunchKernelGGL(k_enc_lo14_first<2>, grid, dim3(512), 0, st, B, d, log2D, seed, T, partials, partial_stride);
-        return grid.x;
+    const bool pairs = tiles >= 256;                             // pairs of tiles: the second one's loads overlap the first
+    dim3 grid(pairs ? (tiles + 1) / 2 : tiles, n);
+    if (pre) {
+        if (pairs) hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_lo14_first<2, true>), grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
+        else hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_lo14_first<1, true>), grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
+    } else {
+        if (pairs) hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_lo14_first<2, false>), grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
+        else hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_lo14_first<1, false>), grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
     }
-    dim3 grid(tiles, n);
-    hipLaunchKernelGGL(k_enc_lo14_first<1>, grid, dim3(512), 0, st, B, d, log2D, seed, T, partials, partial_stride);
     return grid.x;
 }
-void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, const float *T,
                           const DecScratch *scratch, int narrow, float *acc, uint32_t resident, float *partial,
                           uint32_t partial_tiles, hipStream_t st) {
+    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the decoded vectors
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);     // tiles that reach below d
+    if (pre) {
+        hipLaunchKernelGGL(k_dec_lo14_last<true>, dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, narrow, acc,
+                           tiles, 1u, 0u, partial);
+        return;
+    }
     // Fewer tiles than half the resident workgroups: split every tile K ways by sender so that the chip is filled
     // (measured 2.2x on 64 tiles x 32 senders).  With more tiles than resident workgroups, splitting only the
     // last, partly filled round was measured 3..10% slower than leaving it: a CU with one workgroup runs it faster.
@@ -258,8 +323,8 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int log2D, 
     }
     if (K == 1) { full = tiles; rest = 0; }
     dim3 grid(full + rest * K);
-    hipLaunchKernelGGL(k_dec_lo14_last, grid, dim3(512), 0, st, B, n, d, log2D, seed, T, scratch, narrow, acc, full, K, rest,
-                       partial);
+    hipLaunchKernelGGL(k_dec_lo14_last<false>, grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, narrow, acc, full, K,
+                       rest, partial);
     if (K > 1) {
         dim3 cgrid((uint32_t)((((uint64_t)rest << kLo14Bits) / 4 + 255) / 256));
         hipLaunchKernelGGL(k_dec_lo14_combine, cgrid, dim3(256), 0, st, acc, d, full, K, rest, partial);

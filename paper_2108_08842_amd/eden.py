@@ -31,6 +31,7 @@ EXPORTS = [
     "eden_make_subsample_bits", "eden_get_tables", "eden_strerror", "eden_profile_enable", "eden_profile_collect",
     "eden_kernel_name", "eden_sq_error",
 ]
+B_HALF_PRE = 0x10080     # b = 1/2 with the sparsification before the rotation (EDEN_B_HALF_PRE)
 KERNEL_KINDS = ["enc_first", "mid", "enc_last", "dec_prepare", "dec_first", "dec_last", "finalize_mean",
                 "enc_small", "dec_small", "enc_norm", "enc_finish"]
 

@@ -111,6 +111,8 @@ def main(argv=None):
     ap.add_argument("--trials", type=int, default=32)
     ap.add_argument("--senders", type=int, default=8, help="senders of the NMSE round (0: skip it)")
     ap.add_argument("--loss", type=float, default=0.0, help="fraction of packets dropped at the receiver")
+    ap.add_argument("--pre-rotation", action="store_true",
+                    help="b = 0.5 sparsifies before the rotation (Sec. 4.1, the paper's default) instead of after it")
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args(argv)
     assert torch.cuda.is_available(), "this experiment runs on the GPU"
@@ -127,7 +129,7 @@ def main(argv=None):
             ctx = eden.Context(d_max=d, n_max=max(trials, args.senders, 1), device=0)
             x = draw(dist, d, gen, dev)
             for b in args.budgets:
-                b_q8 = int(round(b * 256))
+                b_q8 = eden.B_HALF_PRE if (args.pre_rotation and b == 0.5) else int(round(b * 256))
                 v, se = measure_vnmse(ctx, x, b_q8, trials, args.seed, drop_q32)
                 th = theory_vnmse(b, 1.0 - args.loss)
                 line = f"{dist:11s} {d:9d} {b:4g} {v:9.5f} {se:8.5f} {th:8.5f}"

@@ -25,7 +25,7 @@ def _run_case(ctx, xs, client_ids, budgets, seed, drop_q32=0, also_oracle_msgs=T
     """Encode on the GPU, compare with the oracle; decode the same messages on both sides."""
     from paper_2108_08842_amd import eden
     n, d = len(xs), xs[0].size
-    D = o.padded_dim(d)
+    D = o.padded_dim((d + 1) // 2 if o.pre_rotation(budgets[0]) else d)       # dimension of the transform
     print(f"case n={n} d={d} D=2^{D.bit_length() - 1} budgets={sorted(set(budgets))} seed={seed} drop={drop_q32}", flush=True)
     x_dev = [torch.from_numpy(x).cuda() for x in xs]
     msgs = ctx.encode(x_dev, client_ids, budgets, seed)
@@ -233,7 +233,23 @@ def test_argument_errors(ctx):
     ctx.last_device_status()
 
 
-@pytest.mark.gpu
+@pytest.mark.parametrize("d", [2, 3, 100, 4097, 8191, 8193, 20_001, 300_000, (1 << 20) + 3, 2_500_001])
+def test_sparsification_before_the_rotation(ctx, d):
+    # b = 1/2, the paper's default variant (Sec. 4.1): gather, 1-bit method in dimension ceil(d/2), scatter
+    from paper_2108_08842_amd import eden
+    w = synth.Workload("t", 3, d, [eden.B_HALF_PRE] * 3, 900 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(3)]
+    _run_case(ctx, xs, [3, 4, 5], w.b_q8, w.seed)
+    if d > 5000:
+        _run_case(ctx, xs, [3, 4, 5], w.b_q8, w.seed + 1, drop_q32=int(0.25 * 2 ** 32), also_oracle_msgs=False)
+    # a call mixes this budget with others: refused
+    x_dev = [torch.from_numpy(x).cuda() for x in xs[:2]]
+    msgs = ctx.alloc_messages(d, [eden.B_HALF_PRE, eden.B_HALF_PRE])
+    rc = ctx.encode_raw([t.data_ptr() for t in x_dev], [0, 1], [eden.B_HALF_PRE, 256], d, 1, [m.data_ptr() for m in msgs],
+                        [m.numel() + 1 << 20 for m in msgs])
+    assert rc == eden.ERR_INVALID_ARG
+
+
 def test_mismatch_fraction_over_all_cases():
     # runs last in this file: every encode comparison made so far in this process is in the pool
     pool = parity.check_pool()

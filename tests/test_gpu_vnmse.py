@@ -54,6 +54,18 @@ def test_vnmse_close_to_theory(ctx, dist):
         assert abs(v - th) <= 5 * se + 0.03 * th
 
 
+def test_vnmse_with_sparsification_before_the_rotation(ctx):
+    # Sec. 4.1: "the resulting vNMSE is similar in both cases"; (1/p)(1 + vNMSE_1) - 1 = pi - 1 at p = 1/2
+    from paper_2108_08842_amd import eden, vnmse
+    d = 1 << 16
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(14)
+    x = vnmse.draw("normal", d, gen, torch.device("cuda:0"))
+    v, se = vnmse.measure_vnmse(ctx, x, eden.B_HALF_PRE, 16, seed=6)
+    print(f"pre-rotation b=0.5: vNMSE {v:.5f} +- {se:.5f}, theory {math.pi - 1:.5f}", flush=True)
+    assert abs(v - (math.pi - 1)) <= 5 * se + 0.03 * (math.pi - 1)
+
+
 def test_vnmse_with_packet_loss(ctx):
     from paper_2108_08842_amd import vnmse
     d = 1 << 18                                                  # 256 packets: the arrived fraction is close to 0.9
