@@ -207,9 +207,10 @@ template <> struct WordVec<4> { using type = uint4; };
 // Rows of the workspace at or above ceil(d / 2^14) were not written by the first pass (they are zero padding
 // transformed over bits 0..13, i.e. zero): the buffer bounds return 0 for them without touching memory.
 // A workgroup handles TPW neighbouring column blocks; the loads of the next one are issued into the registers
-// that each half of the exchange has just written to LDS.  UNIT: every sender of the launch has b <= 1; the
+// that each half of the exchange has just written to LDS.  MODE 0: every sender of the launch has b <= 1; the
 // words of the TPW tiles are then kept and stored together (one row of a tile is only 4 bytes of payload).
-template <int M, int TPW, bool UNIT>
+// MODE 1: any integer budget or b = 1/2.  MODE 2: also the budgets k + 1/2 (they need more registers).
+template <int M, int TPW, int MODE>
 __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                    const float *T, double *partials,
                                                                    uint32_t partial_stride, const EncScratch *scratch) {
@@ -218,6 +219,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
     __shared__ double red[X::THREADS / 64];
     constexpr int p = kHixP;
     constexpr int NW = X::RP / 32;
+    constexpr bool UNIT = MODE == 0;
     const uint32_t c = blockIdx.y;
     const uint32_t tile0 = xcd_local_tile<16 / TPW>() * TPW;
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
@@ -255,14 +257,12 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
             if (UNIT || b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
             else {
                 uint16_t *part_b = reinterpret_cast<uint16_t *>(payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4);
-                switch (b_q8) {
-                    case 384u: hix_quantize_pack<M, 1, true>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
-                    case 512u: hix_quantize_pack<M, 2, false>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
-                    case 640u: hix_quantize_pack<M, 2, true>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
-                    case 768u: hix_quantize_pack<M, 3, false>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
-                    case 896u: hix_quantize_pack<M, 3, true>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
-                    default: hix_quantize_pack<M, 4, false>(out, ph, sc, payload, part_b, mixkey, base, ip); break;
-                }
+                if (MODE == 2 && b_q8 == 384u) hix_quantize_pack<M, 1, true>(out, ph, sc, payload, part_b, mixkey, base, ip);
+                else if (MODE == 2 && b_q8 == 640u) hix_quantize_pack<M, 2, true>(out, ph, sc, payload, part_b, mixkey, base, ip);
+                else if (MODE == 2 && b_q8 == 896u) hix_quantize_pack<M, 3, true>(out, ph, sc, payload, part_b, mixkey, base, ip);
+                else if (b_q8 == 512u) hix_quantize_pack<M, 2, false>(out, ph, sc, payload, part_b, mixkey, base, ip);
+                else if (b_q8 == 768u) hix_quantize_pack<M, 3, false>(out, ph, sc, payload, part_b, mixkey, base, ip);
+                else hix_quantize_pack<M, 4, false>(out, ph, sc, payload, part_b, mixkey, base, ip);
             }
         }
     }
@@ -524,8 +524,10 @@ __device__ inline void fwht_pk(s16x2 (&v)[N]) {
     }
 }
 
+// (Four waves per SIMD are requested so that two of the 512-thread workgroups of M = 10 share a CU: measured
+// 0.103 ms against 0.133 ms per launch on 16 senders at D = 2^24, at the price of five spilled registers.)
 template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first_pk(DecBatch B, uint64_t d, int log2D, uint64_t seed, float *T) {
+__global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatch B, uint64_t d, int log2D, uint64_t seed, float *T) {
     using X = HiX<M>;
     constexpr int p = kHixP;
     __shared__ uint32_t lds[X::LDS_FLOATS];
@@ -628,23 +630,27 @@ static uint32_t hix_tiles(int M, int log2D) { return 1u << (log2D - M - 5); }
 uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
                              double *partials, uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
     const uint32_t tiles = hix_tiles(M, log2D);                  // 512 whenever this pass sits directly on lo14
-    bool unit = true;                                            // every sender b <= 1
-    for (uint32_t c = 0; c < n; ++c) unit = unit && B.b_q8[c] <= 256u;
+    bool unit = true, mixed = false;                             // every sender b <= 1; some sender b = k + 1/2
+    for (uint32_t c = 0; c < n; ++c) {
+        unit = unit && B.b_q8[c] <= 256u;
+        mixed = mixed || budget_mixed(B.b_q8[c]);
+    }
+#define EDEN_ENC_HIX_LAST(TPW, MODE)                                                                                          \
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, TPW, MODE>), grid, dim3(HiX<MM>::THREADS), 0, st, B, \
+                                          d, log2D, seed, T, partials, partial_stride, scratch))
     if (unit && tiles % 128u == 0) {                             // four neighbouring tiles per workgroup
         dim3 grid(tiles / 4, n);
-        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, 4, true>), grid, dim3(HiX<MM>::THREADS), 0, st,
-                                              B, d, log2D, seed, T, partials, partial_stride, scratch));
+        EDEN_ENC_HIX_LAST(4, 0);
         return grid.x;
     }
     if (M < 10 && tiles % 256u == 0) {                           // two neighbouring tiles per workgroup (M = 10 would
         dim3 grid(tiles / 2, n);                                 // need more than 128 registers: one workgroup per CU)
-        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, 2, false>), grid, dim3(HiX<MM>::THREADS), 0, st,
-                                              B, d, log2D, seed, T, partials, partial_stride, scratch));
+        if (mixed) { EDEN_ENC_HIX_LAST(2, 2); } else { EDEN_ENC_HIX_LAST(2, 1); }
         return grid.x;
     }
     dim3 grid(tiles, n);
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, 1, false>), grid, dim3(HiX<MM>::THREADS), 0, st, B,
-                                          d, log2D, seed, T, partials, partial_stride, scratch));
+    if (mixed) { EDEN_ENC_HIX_LAST(1, 2); } else { EDEN_ENC_HIX_LAST(1, 1); }
+#undef EDEN_ENC_HIX_LAST
     return grid.x;
 }
 void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems, uint64_t store_elems, hipStream_t st) {
