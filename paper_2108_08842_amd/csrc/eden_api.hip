@@ -55,23 +55,27 @@ uint64_t round_up(uint64_t d, int bits) { return ((d + (1ull << bits) - 1) >> bi
 struct HiPass {
     bool wg;    // workgroup-tile kernel (32-column tiles) or wave-tile kernel (64-column tiles)
     int M, p;   // bits transformed, lowest bit
+    bool wide;  // wave-tile kernel with 8 columns per lane (top pass of the three-pass sizes, b = 1, 2, 4)
 };
 struct Plan {
     int lo_bits;        // 0: single-workgroup path (D <= 4096)
     int nhi;
     HiPass hi[2];       // ascending p
 };
-Plan make_plan(int log2D) {
+// `wide_ok`: every sender of the launch has b = 1, 2 or 4 (what the wide top tile packs).
+Plan make_plan(int log2D, bool wide_ok) {
     Plan pl{};
     if (log2D <= kLoBits) return pl;
     if (log2D <= 18) {
-        pl.lo_bits = 12; pl.nhi = 1; pl.hi[0] = {false, log2D - 12, 12};
+        pl.lo_bits = 12; pl.nhi = 1; pl.hi[0] = {false, log2D - 12, 12, false};
     } else if (log2D <= 24) {
         const int M = log2D - 14;
-        pl.lo_bits = 14; pl.nhi = 1; pl.hi[0] = {M > 6, M, 14};
+        pl.lo_bits = 14; pl.nhi = 1; pl.hi[0] = {M > 6, M, 14, false};
+    } else if (wide_ok) {
+        pl.lo_bits = 14; pl.nhi = 2; pl.hi[0] = {true, log2D - 17, 14, false}; pl.hi[1] = {false, 3, log2D - 3, true};
     } else {
         // the pass next to the payload gets as many rows per wave as the remaining bits allow (16..64)
-        pl.lo_bits = 14; pl.nhi = 2; pl.hi[0] = {true, 7, 14}; pl.hi[1] = {false, log2D - 21, 21};
+        pl.lo_bits = 14; pl.nhi = 2; pl.hi[0] = {true, 7, 14, false}; pl.hi[1] = {false, log2D - 21, 21, false};
     }
     return pl;
 }
@@ -206,7 +210,9 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
     const uint64_t d_src = d;
     if (pre) d = (d + 1) / 2;
     const int log2D = ceil_log2(d);
-    const Plan pl = make_plan(log2D);
+    bool wide_ok = true;
+    for (uint32_t c = 0; c < n; ++c) wide_ok = wide_ok && (pre || b_q8[c] == 256u || b_q8[c] == 512u || b_q8[c] == 1024u);
+    const Plan pl = make_plan(log2D, wide_ok);
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
         const uint32_t nb = (n - first < (uint32_t)kMaxBatch) ? n - first : (uint32_t)kMaxBatch;
@@ -247,10 +253,12 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
                     valid = round_up(d, h.p + h.M);
                 } else {
                     Timed t(ctx, EDEN_K_ENC_LAST, nb, st);
-                    nparts_ip = h.wg ? launch_enc_hix_last(h.M, B, nb, d, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
-                                                           ctx->enc_scratch, st)
-                                     : launch_enc_hi_last(h.M, B, nb, valid, log2D, h.p, seed, ctx->T, part_ip,
-                                                          ctx->partial_stride, ctx->enc_scratch, st);
+                    nparts_ip = h.wg     ? launch_enc_hix_last(h.M, B, nb, d, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
+                                                               ctx->enc_scratch, st)
+                                : h.wide ? launch_enc_wide_last(B, nb, valid, log2D, ctx->T, part_ip, ctx->partial_stride,
+                                                                ctx->enc_scratch, st)
+                                         : launch_enc_hi_last(h.M, B, nb, valid, log2D, h.p, seed, ctx->T, part_ip,
+                                                              ctx->partial_stride, ctx->enc_scratch, st);
                 }
             }
             Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
@@ -281,7 +289,9 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
     const uint64_t d_src = d;
     if (pre) d = (d + 1) / 2;
     const int log2D = ceil_log2(d);
-    const Plan pl = make_plan(log2D);
+    bool wide_ok = true;
+    for (uint32_t c = 0; c < n; ++c) wide_ok = wide_ok && (pre || b_q8[c] == 256u || b_q8[c] == 512u || b_q8[c] == 1024u);
+    const Plan pl = make_plan(log2D, wide_ok);
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
         const uint32_t nb = (n - first < (uint32_t)kMaxBatch) ? n - first : (uint32_t)kMaxBatch;
@@ -311,6 +321,7 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
                 if (i == pl.nhi - 1) {
                     Timed t(ctx, EDEN_K_DEC_FIRST, nb, st);
                     if (h.wg) launch_dec_hix_first(h.M, B, nb, d, log2D, seed, ctx->dec_scratch, narrow, ctx->T, st);
+                    else if (h.wide) launch_dec_wide_first(B, nb, keep, log2D, ctx->dec_scratch, ctx->T, st);
                     else launch_dec_hi_first(h.M, B, nb, keep, log2D, h.p, seed, ctx->dec_scratch, narrow, ctx->T, st);
                 } else {
                     Timed t(ctx, EDEN_K_MID, nb, st);

@@ -321,6 +321,143 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
 }
 
 // ------------------------------------------------------------------------------------------------
+// Wide strided tiles for the top three index bits of the three-pass sizes (D >= 2^25), budgets b = 1, 2, 4:
+// a wave owns 8 rows of 512 consecutive coordinates at stride 2^p (p = log2 D - 3).  A lane holds, of every row,
+// the columns 4 l .. 4 l + 3 and 256 + 4 l .. 256 + 4 l + 3: each workspace access of a wave is then one dense
+// kilobyte (16 bytes per lane, no gaps; with 8 adjacent columns per lane the two halves of every 128-byte line
+// were written by different instructions and 1.7x the bytes reached memory), and a lane's four indices of a
+// half row are 4 b bits of payload: a half-word / byte / nibble per lane, 32..128 dense bytes per wave
+// (the one-column-per-lane wave tile moves a b = 4 payload in 32-byte pieces).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kWideRows = 8, kWideCols = 512;
+
+__device__ inline void wide_fwht(float (&v)[kWideRows][8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float col[kWideRows];
+#pragma unroll
+        for (int r = 0; r < kWideRows; ++r) col[r] = v[r][e];
+        fwht_regs<kWideRows>(col);
+#pragma unroll
+        for (int r = 0; r < kWideRows; ++r) v[r][e] = col[r];
+    }
+}
+__device__ inline uint32_t wide_lane_xor1(uint32_t x) {         // value held by lane ^ 1
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);
+}
+
+// Encode, last pass (see k_enc_hi_last): index bits p .. p+2, quantization, sum_i u_i q_i, packing.
+__global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t valid_elems, int log2D, const float *T,
+                                                       double *partials, uint32_t partial_stride,
+                                                       const EncScratch *scratch) {
+    __shared__ double red[4];
+    const uint32_t c = blockIdx.y;
+    const uint32_t lane = lane_id();
+    const int p = log2D - 3;
+    const uint32_t tile = blockIdx.x * 4u + wave_in_block();     // 2^(p-9) column blocks, all 8 rows
+    const uint32_t base = tile * (uint32_t)kWideCols;
+    const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), (uint32_t)(valid_elems * 4));
+    float v[kWideRows][8];
+#pragma unroll
+    for (int r = 0; r < kWideRows; ++r) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const u32x4_t q = __builtin_amdgcn_raw_buffer_load_b128(rt, (int)(lane * 16u),
+                                                                     (int)((base + 256u * h + ((uint32_t)r << p)) * 4u), kStream);
+            v[r][4 * h] = __uint_as_float(q.x); v[r][4 * h + 1] = __uint_as_float(q.y);
+            v[r][4 * h + 2] = __uint_as_float(q.z); v[r][4 * h + 3] = __uint_as_float(q.w);
+        }
+    }
+    wide_fwht(v);
+    char *payload = static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES;
+    const uint32_t b_q8 = B.b_q8[c];
+    const EncScratch *sc = &scratch[c];
+    float ip = 0.0f;
+#pragma unroll
+    for (int r = 0; r < kWideRows; ++r) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t group = (base + 256u * h + ((uint32_t)r << p)) / 4u + lane;   // this lane's 4 coordinates
+            uint32_t word = 0;
+            if (b_q8 == 256u) {                                  // I_1: the index is the sign, |Q| = q_1
+                float sa = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    sa += fabsf(v[r][4 * h + e]);
+                    word |= ((~__float_as_uint(v[r][4 * h + e])) >> 31) << e;        // index 1 = non-negative
+                }
+                ip = fmaf(sa, kQ1, ip);
+                word |= wide_lane_xor1(word) << 4;               // two lanes = one byte
+                if (!(lane & 1u)) reinterpret_cast<uint8_t *>(payload)[group >> 1] = (uint8_t)word;
+            } else if (b_q8 == 512u) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) word |= quantize_one<2>(v[r][4 * h + e], sc->thr, sc->qpos, ip) << (2 * e);
+                reinterpret_cast<uint8_t *>(payload)[group] = (uint8_t)word;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) word |= quantize_one<8>(v[r][4 * h + e], sc->thr, sc->qpos, ip) << (4 * e);
+                reinterpret_cast<uint16_t *>(payload)[group] = (uint16_t)word;
+            }
+        }
+    }
+    const double block_total = block_sum<256>((double)ip, red);
+    if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
+}
+
+// Decode, first pass (see k_dec_hi_first): unpack, dequantize, zero the rows whose packet was lost, index bits
+// p .. p+2.  A row segment of 512 coordinates lies inside one packet of 1024.
+__global__ __launch_bounds__(256) void k_dec_wide_first(DecBatch B, uint64_t keep_elems, int log2D, const DecScratch *scratch,
+                                                        float *T) {
+    __shared__ float table[4][16];
+    const uint32_t c = blockIdx.y;
+    const uint32_t lane = lane_id(), wv = wave_in_block();
+    const int p = log2D - 3;
+    const uint32_t tile = blockIdx.x * 4u + wv;
+    const uint32_t base = tile * (uint32_t)kWideCols;
+    if (lane < 16) table[wv][lane] = scratch[c].deq[lane];
+    wave_lds_sync();
+    const float *tb = table[wv];
+    const char *payload = static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES;
+    const uint32_t b_q8 = B.b_q8[c];
+    const uint32_t *bm = B.bitmap[c];
+    float v[kWideRows][8];
+#pragma unroll
+    for (int r = 0; r < kWideRows; ++r) {
+        const uint32_t first = base + ((uint32_t)r << p);
+        const uint32_t pk = first >> 10;
+        const bool here = bm ? ((bm[pk >> 5] >> (pk & 31u)) & 1u) != 0u : true;       // wave-uniform
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t group = (first + 256u * h) / 4u + lane;                   // this lane's 4 coordinates
+            uint32_t word;
+            if (b_q8 == 256u) word = (uint32_t)reinterpret_cast<const uint8_t *>(payload)[group >> 1] >> (4u * (lane & 1u));
+            else if (b_q8 == 512u) word = reinterpret_cast<const uint8_t *>(payload)[group];
+            else word = reinterpret_cast<const uint16_t *>(payload)[group];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t idx;
+                if (b_q8 == 256u) idx = (word >> e) & 1u;
+                else if (b_q8 == 512u) idx = (word >> (2 * e)) & 3u;
+                else idx = (word >> (4 * e)) & 15u;
+                v[r][4 * h + e] = here ? tb[idx] : 0.0f;
+            }
+        }
+    }
+    wide_fwht(v);
+    const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), (uint32_t)(keep_elems * 4));
+#pragma unroll
+    for (int r = 0; r < kWideRows; ++r) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            u32x4_t q = {__float_as_uint(v[r][4 * h]), __float_as_uint(v[r][4 * h + 1]), __float_as_uint(v[r][4 * h + 2]),
+                         __float_as_uint(v[r][4 * h + 3])};
+            __builtin_amdgcn_raw_buffer_store_b128(q, rt, (int)(lane * 16u), (int)((base + 256u * h + ((uint32_t)r << p)) * 4u),
+                                                   kStream);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Encode, first pass in wave tiles: x -> T.  Zero padding (Sec. 5: the transform needs a power of two), the
 // sign diagonal of the rotation from the shared seed (Sec. 2.1), |x|^2 for eta and S (Sec. 2.2.1, 2.3), index
 // bits 0..11 of H.  Only the ceil(d / 4096) tiles that hold part of x are transformed and written; the strided
@@ -821,6 +958,17 @@ uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid
     EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_enc_hi_last<MM>, grid, dim3(256), 0, st, B, valid_elems, log2D, p, seed, T, partials,
                                          partial_stride, scratch));
     return grid.x;
+}
+uint32_t launch_enc_wide_last(const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, const float *T, double *partials,
+                              uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
+    dim3 grid(1u << (log2D - 3 - 9 - 2), n);                     // D / 8 rows / 512 columns / 4 waves
+    hipLaunchKernelGGL(k_enc_wide_last, grid, dim3(256), 0, st, B, valid_elems, log2D, T, partials, partial_stride, scratch);
+    return grid.x;
+}
+void launch_dec_wide_first(const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, const DecScratch *scratch, float *T,
+                           hipStream_t st) {
+    dim3 grid(1u << (log2D - 3 - 9 - 2), n);
+    hipLaunchKernelGGL(k_dec_wide_first, grid, dim3(256), 0, st, B, keep_elems, log2D, scratch, T);
 }
 void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint32_t partial_stride, uint32_t nparts,
                      EncScratch *scratch, const DevTables *tab, hipStream_t st) {

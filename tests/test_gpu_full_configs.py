@@ -125,6 +125,36 @@ def test_three_pass_size():
     ctx.close()
 
 
+def test_three_pass_size_wide_tiles():
+    """D = 2^25 with b = 1, 2, 4 only: lo14, workgroup-tile strided pass on bits 14..21, and the wide wave tile
+    (8 rows x 512 columns, 8 columns per lane) on bits 22..24 next to the payload."""
+    from paper_2108_08842_amd import eden
+    d = (1 << 24) + 54321
+    w = synth.Workload("three_pass_wide", 3, d, [256, 512, 1024], 26, "lognormal_signed")
+    print(f"three passes, wide tiles: n=3 d={d} D=2^25 budgets={w.b_q8} seed={w.seed}", flush=True)
+    xs = [synth.client_vector(w, c) for c in range(3)]
+    ctx = eden.Context(d_max=d, n_max=3, device=0)
+    ids = [2, 7, 11]
+    msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], ids, w.b_q8, w.seed)
+    assert ctx.last_device_status() == 0
+    stats = parity.EncodeParity()
+    om = [parity.to_oracle_message(m) for m in msgs]
+    for c in range(3):
+        parity.check_encode(xs[c], w.seed, ids[c], w.b_q8[c], om[c], stats)
+    parity.finish_encode(stats)
+    print("encode:", stats, flush=True)
+    bm = [ctx.make_loss_bitmap(w.seed, cid, 1 << 25, int(0.1 * 2 ** 32)) for cid in ids]
+    acc = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs, ids, w.b_q8, d, w.seed, acc, bm)
+    got = ctx.finalize_mean(acc, 3).cpu().numpy()
+    want = o.decode_mean(om, d, [b.cpu().numpy().view(np.uint32) for b in bm])
+    err = parity.rel_l2(got, want)
+    print(f"decode of 3 senders with 10% loss: rel L2 {err:.2e}", flush=True)
+    assert err <= parity.MEAN_REL_L2
+    assert ctx.last_device_status() == 0
+    ctx.close()
+
+
 @pytest.mark.timeout(600)
 def test_config5_full_size():
     """n=8, d=2^27, b=4: three passes through memory.  One sender is checked coordinate by coordinate on sampled
