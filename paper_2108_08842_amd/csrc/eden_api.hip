@@ -1,6 +1,6 @@
 // C ABI of the EDEN library (see include/eden.h for the contract of every call).
 // Host code only: argument checks, the pass plan, workspace, launches.  Every step of the path runs
-// in the kernels of eden_kernels.hip.
+// in the kernels of eden_kernels.hip, eden_kernels_lo14.hip and eden_kernels_wg.hip.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -51,7 +51,8 @@ uint64_t round_up(uint64_t d, int bits) { return ((d + (1ull << bits) - 1) >> bi
 
 // Pass plan.  The contiguous pass covers the low 12 bits (wave tiles) or 14 bits (workgroup tiles); the
 // bits above it are covered by one or two strided passes: wave tiles handle up to 6 bits each,
-// workgroup tiles 7..10 bits.  D <= 2^24 needs two passes in all, D up to 2^27 three.
+// workgroup tiles 7..10 bits.  D <= 2^24 needs two passes in all, D up to 2^27 three.  Encode runs the
+// passes in ascending bit order (contiguous first), decode in descending order (contiguous last).
 struct HiPass {
     bool wg;    // workgroup-tile kernel (32-column tiles) or wave-tile kernel (64-column tiles)
     int M, p;   // bits transformed, lowest bit
@@ -90,7 +91,6 @@ struct DeviceGuard {
     }
     ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
 };
-
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 

@@ -13,7 +13,8 @@
 // of the rotation, and one 128-byte line of the workspace or the accumulator.
 //
 // 32 registers (instead of 64) halve the LDS a wave needs for its exchanges, which doubles the number of
-// resident waves per CU (16); these passes are bound by vector-ALU issue, not by memory.
+// resident waves per CU (16).  The encode pass built on this is bound by memory, the decode pass (which repeats
+// the transform for every sender of a tile) by vector-ALU issue.
 #include "eden_device.h"
 #include "eden_kernels.h"
 

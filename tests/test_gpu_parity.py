@@ -250,6 +250,25 @@ def test_sparsification_before_the_rotation(ctx, d):
     assert rc == eden.ERR_INVALID_ARG
 
 
+def test_random_shapes_and_budgets(ctx):
+    # 60 seeded random cases: dimension (log-uniform up to 2^18 + tail), number of senders, any supported budget
+    # per sender, sometimes lost packets, sometimes the sparsification before the rotation
+    from paper_2108_08842_amd import eden
+    rng = np.random.default_rng(20240)
+    budgets_all = [128, 256, 384, 512, 640, 768, 896, 1024]
+    dists = ["normal", "lognormal", "lognormal_signed", "normal_outliers", "layers"]
+    for case in range(60):
+        d = int(2 ** rng.uniform(1.0, 18.2))
+        n = int(rng.integers(1, 6))
+        pre = rng.random() < 0.15
+        budgets = [eden.B_HALF_PRE] * n if pre else [int(b) for b in rng.choice(budgets_all, n)]
+        w = synth.Workload("t", n, d, budgets, 5000 + case, dists[case % len(dists)])
+        xs = [synth.client_vector(w, c) for c in range(n)]
+        ids = [int(v) for v in rng.choice(1 << 20, n, replace=False)]
+        drop = int(rng.choice([0, 0, int(0.3 * 2 ** 32)])) if d >= (1 << 14) else 0    # at least 8 packets
+        _run_case(ctx, xs, ids, w.b_q8, int(rng.integers(0, 2 ** 62)), drop_q32=drop, also_oracle_msgs=(case % 4 == 0))
+
+
 def test_mismatch_fraction_over_all_cases():
     # runs last in this file: every encode comparison made so far in this process is in the pool
     pool = parity.check_pool()
