@@ -72,6 +72,40 @@ MEASURED_TRAFFIC = {
 }
 
 
+def time_config(k, eden, synth, torch, steps=5, warmup=2):
+    """ms per step and Gcoords/s of synthetic configuration k (same step as the headline)."""
+    w = synth.config(k)
+    n, d = w.n, w.d
+    D = 1 << (d - 1).bit_length()
+    xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(n)]
+    ctx = eden.Context(d_max=d, n_max=n, device=0)
+    msgs = ctx.alloc_messages(d, w.b_q8)
+    acc = torch.zeros(d, dtype=torch.float32, device="cuda")
+    bitmaps = [ctx.make_loss_bitmap(w.seed, w.client_ids[c], D, w.drop_q32) for c in range(n)] if w.drop_q32 else None
+
+    def step():
+        acc.zero_()
+        ctx.encode(xs, w.client_ids, w.b_q8, w.seed, msgs=msgs)
+        ctx.decode_accumulate(msgs, w.client_ids, w.b_q8, d, w.seed, acc, bitmaps)
+        ctx.finalize_mean(acc, n, out=acc)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    assert ctx.last_device_status() == 0
+    res = {"workload": w.name, "ms_per_step": round(ms, 4), "Gcoords_per_s": round(2.0 * n * D / (ms * 1e-3) / 1e9, 2),
+           "model_frac_of_peak": round(model_bytes(n, d, D, w.b_q8) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    ctx.close()
+    del xs, msgs, acc, ctx
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +113,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="synthetic configuration 1..5 (4 = the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short timing of the other four synthetic configurations")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel kind, print a table to stderr")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -207,6 +243,12 @@ def main():
                      "algorithmic_bytes": sum(dom_bytes) / len(dom_bytes),
                      "avg_launch_ms": round(avg_ms, 4), "launches": len(dom_ms)},
     }
+
+    if not args.no_other_configs and args.config == 4:
+        # the other synthetic configurations, a few steps each (not the headline; parity tests cover them)
+        del xs, msgs, acc, mean, ctx
+        torch.cuda.empty_cache()
+        out["other_configs"] = [time_config(k, eden, synth, torch) for k in (1, 2, 3, 5)]
 
     if not args.no_cpu_baseline:
         from oracle import eden_oracle as o
