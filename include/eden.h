@@ -18,6 +18,9 @@
  *   - The caller owns every buffer it passes.  The library reads inputs, writes outputs,
  *     and keeps no caller pointer after the call returns.  Its only own device memory is the
  *     context workspace allocated by eden_create.
+ *   - A context serialises its work through that workspace: calls on one context must be issued from
+ *     one thread at a time and on one stream (or on streams the caller orders); two calls that run
+ *     concurrently on the same context race.  Use one context per concurrent stream.
  *   - `stream` is a hipStream_t cast to void* (NULL = the default stream).  Encode, decode and
  *     finalize only enqueue work on that stream; they never synchronise the host.
  *     Conditions that can only be seen on the device (zero or non-finite vector, nothing
@@ -103,7 +106,8 @@ typedef enum eden_status {
 
 /* Creates a context on HIP device `hip_device` able to handle vectors up to d_max coordinates and
  * batches up to n_max senders per call.  Allocates the workspace: min(n_max, 32) * 4 * D_max bytes for the
- * transform's intermediate passes (none if D_max <= 4096) plus a few KiB of partial sums per sender;
+ * transform's intermediate passes (none if D_max <= 4096), 32 MiB for sender-group sums of the last decode
+ * pass when D_max >= 2^19 and n_max > 1, plus a few KiB of partial sums per sender;
  * solves the Lloyd-Max tables of Sec. 3 in double precision on the host and uploads them.
  * On failure *out is NULL. */
 int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device);
