@@ -57,6 +57,7 @@ STREAM_SIGN = 0        # Rademacher diagonal of the rotation
 STREAM_SUBSAMPLE = 1   # which coordinate of each group is kept when b < 1
 STREAM_LOSS = 2        # Bernoulli packet drops (test helper)
 STREAM_MIX = 3         # which coordinate of each pair gets the extra bit when b is k + 1/2
+STREAM_SPARSE = 4      # sort keys of the m-of-64 sparsification before the rotation (b = m/64)
 
 PACKET_COORDS = 1024   # reading: a packet is 1024 consecutive rotated coordinates
 
@@ -305,6 +306,32 @@ def pre_rotation(b_q8: int) -> bool:
     return b_q8 == (PRE_ROTATION | 128)
 
 
+SPARSE = 0x20000         # flag in b_q8: b = m/64 with m = b_q8 & 0xFFFF, sparsification before the rotation
+SPARSE_BLOCK = 64
+
+
+def sparse_m(b_q8: int) -> int:
+    """m of an m-of-64 budget, 0 for every other budget."""
+    m = b_q8 & 0xFFFF
+    return m if (b_q8 & ~0xFFFF) == SPARSE and 1 <= m < SPARSE_BLOCK else 0
+
+
+def sparse_selection(seed: int, client: int, d: int, m: int) -> np.ndarray:
+    """Sec. 4.1 random sparsification with p = m/64, before the rotation: the mask is a uniformly random
+    sample of exact size.  reading: a stratified one -- of every 64 consecutive coordinates (the last
+    block padded with virtual zeros up to 64) exactly the m with the smallest 16-bit hash keys are kept,
+    ties broken by position; key of coordinate i = bits 16 (i & 3) .. +15 of word (i >> 2) of the SPARSE
+    stream.  Returns, for every slot r = 64-block * m + rank among the block's kept coordinates in
+    position order, the coordinate it holds (>= d for a kept virtual zero)."""
+    nblk = (d + SPARSE_BLOCK - 1) // SPARSE_BLOCK
+    n = nblk * SPARSE_BLOCK
+    words = hash_words(stream_key(seed, STREAM_SPARSE, client), 0, n // 4)
+    keys = ((words[:, None] >> (np.uint64(16) * np.arange(4, dtype=np.uint64))) & np.uint64(0xFFFF)).reshape(nblk, SPARSE_BLOCK)
+    order = np.argsort(keys.astype(np.int64) * SPARSE_BLOCK + np.arange(SPARSE_BLOCK), axis=1)   # (key, position) ascending
+    kept = np.sort(order[:, :m], axis=1)                           # positions of the m smallest, in position order
+    return (kept + np.arange(nblk)[:, None] * SPARSE_BLOCK).reshape(-1)
+
+
 def budget(b_q8: int):
     """-> (bits per kept coordinate, keep-one-in-k).  For b = k + 1/2 the bits are k (every coordinate
     has k bits in the first part of the payload; see mixed())."""
@@ -395,12 +422,14 @@ class Message:
             "<IIQIIIIdddQ", buf[:HEADER_BYTES])
         if magic != MAGIC:
             raise ValueError("bad magic")
-        nw = payload_words(1 << log2D, 256 if pre_rotation(b_q8) else b_q8)
+        nw = payload_words(1 << log2D, 256 if (pre_rotation(b_q8) or sparse_m(b_q8)) else b_q8)
         payload = np.frombuffer(buf, dtype="<u4", count=nw, offset=HEADER_BYTES).copy()
         return Message(log2D, d, b_q8, client, status, S, N2, IP, seed, payload)
 
 
 def message_bytes(d: int, b_q8: int) -> int:
+    if sparse_m(b_q8):
+        return HEADER_BYTES + 4 * payload_words(padded_dim(sparse_m(b_q8) * ((d + SPARSE_BLOCK - 1) // SPARSE_BLOCK)), 256)
     if pre_rotation(b_q8):
         return HEADER_BYTES + 4 * payload_words(padded_dim((d + 1) // 2), 256)
     return HEADER_BYTES + 4 * payload_words(padded_dim(d), b_q8)
@@ -489,6 +518,17 @@ def sparsify_pairs(x: np.ndarray, seed: int, client: int):
 
 def encode(x: np.ndarray, seed: int, client: int, b_q8: int, want_trace: bool = False):
     x = np.asarray(x, dtype=np.float64)
+    if sparse_m(b_q8):
+        # b = m/64: the 1-bit method on the kept coordinates (a vector of m * ceil(d/64) entries).  The factor 1/p
+        # of the sparsification is applied by the receiver: the method is scale equivariant, and the sender then
+        # works on the values of x themselves.
+        src = sparse_selection(seed, client, x.size, sparse_m(b_q8))
+        xs = np.concatenate([x, np.zeros(SPARSE_BLOCK)])[src]
+        inner = encode(xs, seed, client, 256, want_trace)
+        msg, tr = inner if want_trace else (inner, None)
+        msg.d = x.size
+        msg.b_q8 = b_q8
+        return (msg, tr) if want_trace else msg
     if pre_rotation(b_q8):
         # the 1-bit method on the sparsified vector; the message keeps the original d and the flagged budget
         if x.size < 2:
@@ -579,6 +619,14 @@ def decode_rotated(msg: Message, bitmap: np.ndarray | None = None) -> np.ndarray
 
 
 def decode(msg: Message, d: int, bitmap: np.ndarray | None = None) -> np.ndarray:
+    if sparse_m(msg.b_q8):
+        m = sparse_m(msg.b_q8)
+        src = sparse_selection(msg.seed, msg.client, d, m)
+        inner = Message(msg.log2D, src.size, 256, msg.client, msg.status, msg.S, msg.N2, msg.IP, msg.seed, msg.payload)
+        xs_hat = decode(inner, src.size, bitmap) * (SPARSE_BLOCK / m)            # the 1/p of the sparsification
+        out = np.zeros(d + SPARSE_BLOCK)
+        out[src] = xs_hat
+        return out[:d]
     if pre_rotation(msg.b_q8):
         # decode the 1-bit message of dimension ceil(d/2), then put every value back where it was taken from
         dp = (d + 1) // 2

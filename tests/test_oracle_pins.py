@@ -613,3 +613,73 @@ def test_pre_rotation_vnmse_is_pi_minus_one():
     x = rng.standard_normal(d)
     v = np.mean([o.vnmse_single(x, o.decode(o.encode(x, sd, 0, PRE_HALF), d)) for sd in range(60)])
     assert abs(v - (math.pi - 1)) < 0.03 * (math.pi - 1)
+
+
+# ---- b = m/64: m-of-64 random sparsification before the rotation (Sec. 4.1 sub-bit compression, general p)
+def test_sparse_selection_is_exact_size_uniform_and_per_sender():
+    d, m = 1000, 6
+    src = o.sparse_selection(5, 2, d, m)
+    nblk = 16
+    assert src.size == m * nblk
+    blocks = src.reshape(nblk, m)
+    assert np.all(blocks // 64 == np.arange(nblk)[:, None])              # m slots per block of 64, in order
+    assert np.all(np.diff(blocks, axis=1) > 0)                           # increasing positions, no repeats
+    assert not np.array_equal(src, o.sparse_selection(5, 3, d, m)) and not np.array_equal(src, o.sparse_selection(6, 2, d, m))
+    # the m smallest keys of a block, brute force with Python tuples on one block
+    words = o.hash_words(o.stream_key(5, o.STREAM_SPARSE, 2), 0, 16 * nblk)
+    keys = [int((int(words[i >> 2]) >> (16 * (i & 3))) & 0xFFFF) for i in range(64 * 3, 64 * 4)]
+    want = sorted(pos for _, pos in sorted((k, j) for j, k in enumerate(keys))[:m])
+    assert (blocks[3] - 64 * 3).tolist() == want
+    # every position is kept with probability m/64
+    hits = np.zeros(64)
+    trials = 3000
+    for sd in range(trials):
+        hits[o.sparse_selection(sd, 0, 64, m)] += 1
+    assert np.all(np.abs(hits / trials - m / 64) < 5 * math.sqrt(m / 64 * (1 - m / 64) / trials))
+
+
+def test_sparse_budget_message_and_error_level():
+    m = 4
+    B = o.SPARSE | m
+    d = 1 << 14                                                           # m * d / 64 = 1024: no padding of the kept vector
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal(d)
+    msg = o.encode(x, 7, 1, B)
+    assert (msg.log2D, msg.d, msg.b_q8) == (10, d, B) and msg.payload.size == 1024 // 32
+    assert o.message_bytes(d, B) == len(msg.to_bytes()) == 64 + 128
+    src = o.sparse_selection(7, 1, d, m)
+    inner = o.encode(x[src], 7, 1, 256)
+    np.testing.assert_array_equal(inner.payload, msg.payload)
+    assert inner.S == msg.S
+    got = o.decode(o.Message.from_bytes(msg.to_bytes()), d)
+    np.testing.assert_allclose(got[src], o.decode(inner, src.size) * (64 / m), rtol=1e-15)
+    rest = np.ones(d, dtype=bool); rest[src] = False
+    assert not got[rest].any()
+    # Sec. 4.1: sparsification error 1/p - 1, then the 1-bit error on top: (1 + vNMSE_1)/p - 1 = (pi/2)/p - 1
+    # (the form the paper evaluates at p = 0.1); here p = 1/16
+    v = np.mean([o.vnmse_single(x, o.decode(o.encode(x, sd, 0, B), d)) for sd in range(80)])
+    th = math.pi / 2 * 16 - 1
+    assert abs(v - th) < 0.04 * th
+    # and the sparsification alone is unbiased with error 1/p - 1
+    acc = np.zeros(d); err = 0.0
+    for sd in range(400):
+        s2 = o.sparse_selection(sd, 0, d, m)
+        back = np.zeros(d); back[s2] = x[s2] * 16
+        acc += back; err += np.sum((back - x) ** 2)
+    assert abs(err / 400 / np.dot(x, x) - 15.0) < 0.6
+    assert np.linalg.norm(acc / 400 - x) / np.linalg.norm(x) < 1.3 * math.sqrt(15.0 / 400)
+
+
+def test_sparse_budget_ragged_end():
+    # d not a multiple of 64: virtual zeros after d may be selected; they carry nothing and are dropped on decode
+    d, m = 150, 20
+    B = o.SPARSE | m
+    x = np.arange(1.0, d + 1)
+    src = o.sparse_selection(3, 0, d, m)
+    assert src.size == 3 * m and (src >= d).any() and src.max() < 192
+    msg, tr = o.encode(x, 3, 0, B, want_trace=True)
+    assert msg.log2D == 6 and tr.z.size == 64
+    xh = o.decode(msg, d)
+    not_kept = np.ones(d, dtype=bool)
+    not_kept[src[src < d]] = False
+    assert xh.size == d and not xh[not_kept].any() and np.count_nonzero(xh) > 30
