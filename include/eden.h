@@ -37,7 +37,8 @@
  *     where s_i = -1.
  *   - Hash: word(key, j) = mix(key + PHI*(j+1)), mix = the splitmix64 output function,
  *     key = mix(mix(seed + PHI) + PHI*((stream << 32) | client) + PHI), PHI = 0x9E3779B97F4A7C15;
- *     streams: 0 = signs, 1 = sub-sampling, 2 = packet loss, 3 = mix (which coordinates get the extra bit).
+ *     streams: 0 = signs, 1 = sub-sampling, 2 = packet loss, 3 = mix (which coordinates get the extra bit),
+ *     4 = sparse (sort keys of the m-of-64 sparsification).
  *   - Bit budget b is passed as b_q8 = 256*b.  Supported: 256, 512, 768, 1024 (b = 1, 2, 3, 4, the
  *     2^b-level Lloyd-Max quantizer of N(0,1), Sec. 3); 128 (b = 1/2: the b = 1 quantizer,
  *     then of every two consecutive rotated coordinates (2g, 2g+1) only the one at offset
@@ -54,6 +55,14 @@
  *     transform and the message are half as large; the decoder puts value g back at 2g + o_g and leaves the
  *     other coordinate of the pair 0.  In one call either every sender uses this budget or none (the
  *     transform dimension differs).  The header keeps d and this b_q8; log2(D) is that of ceil(d/2).
+ *     EDEN_B_SPARSE(m) (0x20000 | m, 1 <= m <= 63): b = m/64, sub-bit compression with p = m/64 and the
+ *     sparsification before the rotation (Sec. 4.1).  Of every 64 consecutive coordinates of x (the last block
+ *     padded with virtual zeros) exactly the m with the smallest 16-bit keys are kept, ties broken by position;
+ *     key of coordinate i = bits 16 (i & 3) .. +15 of word (i >> 2) of the SPARSE stream (stream 4).  The
+ *     m ceil(d/64) kept values, in order, are encoded with b = 1 (unscaled: the method is scale equivariant), and
+ *     the decoder multiplies by 64/m and puts them back.  Senders are processed one at a time (their kept sets
+ *     differ); a call uses such budgets for all senders or for none; packets of a received-packet bitmap refer
+ *     to the kept vector.  The first call with such a budget allocates d_max + 64 floats in the context.
  *   - Index of a coordinate = rank of its interval in ascending order (0 = most negative).  At an
  *     interval endpoint the interval closer to zero is taken; z = 0 belongs to the non-negative
  *     side (Sec. 2.2.1 and its footnote).
@@ -76,6 +85,7 @@
 #define EDEN_H
 
 #define EDEN_B_HALF_PRE 0x10080u
+#define EDEN_B_SPARSE(m) (0x20000u | (unsigned)(m))
 
 #include <stddef.h>
 #include <stdint.h>

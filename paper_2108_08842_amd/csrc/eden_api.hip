@@ -27,6 +27,8 @@ struct eden_ctx {
     uint32_t compute_units;      // of the context's device
     float *dec_partial;          // sums of sender groups when the last decode pass splits tiles (D_max >= 2^19)
     uint32_t dec_partial_tiles;  // its size in tiles of 2^14 floats
+    float *stage;                // d_max + 64 floats: the kept coordinates of one sender with a budget b = m/64;
+                                 // allocated by the first call that uses such a budget
     EncScratch *enc_scratch; // slots
     DecScratch *dec_scratch; // slots
     DevTables *tables;
@@ -115,6 +117,7 @@ extern "C" {
 
 size_t eden_message_bytes(uint64_t d, uint32_t b_q8) {
     if (b_q8 == kPreHalf) return d >= 2 ? eden_message_bytes((d + 1) / 2, 256) : 0;
+    if (sparse_m(b_q8)) return (d >= 1 && d <= (1ull << EDEN_MAX_LOG2_D)) ? eden_message_bytes(sparse_m(b_q8) * ((d + 63) / 64), 256) : 0;
     int bits, k;
     if (d == 0 || d > (1ull << EDEN_MAX_LOG2_D) || !budget_of(b_q8, bits, k)) return 0;
     const uint64_t D = 1ull << ceil_log2(d);
@@ -182,36 +185,23 @@ int eden_destroy(eden_ctx *ctx) {
     bool ok = guard.ok;
     for (hipEvent_t e : ctx->prof_start) ok = (hipEventDestroy(e) == hipSuccess) && ok;
     for (hipEvent_t e : ctx->prof_stop) ok = (hipEventDestroy(e) == hipSuccess) && ok;
-    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
+    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->stage, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
     for (void *p : ptrs)
         if (p) ok = (hipFree(p) == hipSuccess) && ok;
     delete ctx;
     return ok ? EDEN_OK : EDEN_ERR_HIP;
 }
 
-int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8,
-                uint32_t n, uint64_t d, uint64_t seed, void *const *msgs_dev, const size_t *msg_capacity,
-                void *stream) {
-    if (!ctx || !x_dev || !client_ids || !b_q8 || !msgs_dev || !msg_capacity) return EDEN_ERR_INVALID_ARG;
-    if (n == 0 || n > ctx->n_max || d == 0 || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
-    for (uint32_t c = 0; c < n; ++c) {
-        if (!x_dev[c] || !msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
-        const size_t need = eden_message_bytes(d, b_q8[c]);
-        if (need == 0) return EDEN_ERR_INVALID_ARG;
-        if (msg_capacity[c] < need) return EDEN_ERR_CAPACITY;
-    }
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return EDEN_ERR_HIP;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    // sparsification before the rotation: all senders or none; the transform then has dimension ceil(d/2)
-    int pre = 0;
-    for (uint32_t c = 0; c < n; ++c) pre += (b_q8[c] == kPreHalf);
-    if (pre != 0 && pre != (int)n) return EDEN_ERR_INVALID_ARG;
-    const uint64_t d_src = d;
-    if (pre) d = (d + 1) / 2;
+// Encodes n senders whose transformed vectors all have the same dimension.  `b_kernel`: the budgets the kernels
+// quantize with; `b_hdr`, `hdr_d`: what the headers record; `d_src`, `pre`: the length of the vectors x points to and
+// whether they are sparsified in pairs on the way in.
+static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_kernel,
+                        const uint32_t *b_hdr, uint32_t n, uint64_t d_src, int pre, uint64_t hdr_d, uint64_t seed,
+                        void *const *msgs_dev, hipStream_t st) {
+    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the vector that is transformed
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
-    for (uint32_t c = 0; c < n; ++c) wide_ok = wide_ok && (pre || b_q8[c] == 256u || b_q8[c] == 512u || b_q8[c] == 1024u);
+    for (uint32_t c = 0; c < n; ++c) wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u);
     const Plan pl = make_plan(log2D, wide_ok);
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
@@ -222,11 +212,12 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             B.x[i] = x_dev[first + i];
             B.msg[i] = msgs_dev[first + i];
             B.client[i] = client_ids[first + i];
-            B.b_q8[i] = pre ? 256u : b_q8[first + i];
+            B.b_q8[i] = b_kernel[first + i];
+            B.hdr_b_q8[i] = b_hdr[first + i];
         }
         if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_ENC_SMALL, nb, st);
-            launch_enc_small(B, nb, d_src, pre, log2D, seed, ctx->tables, ctx->dev_status, st);
+            launch_enc_small(B, nb, d_src, pre, hdr_d, log2D, seed, ctx->tables, ctx->dev_status, st);
         } else {
             // contiguous pass first (it reads x, and only the tiles that hold part of x), strided passes after it in
             // place on the workspace, the last one quantizing and packing
@@ -262,7 +253,7 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
                 }
             }
             Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
-            launch_enc_finish(B, nb, d_src, pre, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
+            launch_enc_finish(B, nb, hdr_d, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
                               ctx->dev_status, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
@@ -270,27 +261,62 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
     return EDEN_OK;
 }
 
-int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
-                           const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
-                           const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream) {
-    if (!ctx || !msgs_dev || !client_ids || !b_q8 || !acc_dev) return EDEN_ERR_INVALID_ARG;
-    if (reinterpret_cast<uintptr_t>(acc_dev) & 15u) return EDEN_ERR_INVALID_ARG;
+// Budgets that change the dimension of the transform (sparsification before the rotation) cannot share a call with
+// the others: 0 = none of the senders, 1 = all in pairs (EDEN_B_HALF_PRE), 2 = all m-of-64, -1 = a mix.
+static int sparsify_mode(const uint32_t *b_q8, uint32_t n) {
+    uint32_t pre = 0, sp = 0;
+    for (uint32_t c = 0; c < n; ++c) { pre += (b_q8[c] == kPreHalf); sp += (sparse_m(b_q8[c]) != 0); }
+    if (pre == 0 && sp == 0) return 0;
+    if (pre == n) return 1;
+    if (sp == n) return 2;
+    return -1;
+}
+static bool ensure_stage(eden_ctx *ctx) {
+    if (ctx->stage) return true;
+    return hipMalloc(&ctx->stage, (size_t)(ctx->d_max + 64) * sizeof(float)) == hipSuccess;
+}
+
+int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8, uint32_t n,
+                uint64_t d, uint64_t seed, void *const *msgs_dev, const size_t *msg_capacity, void *stream) {
+    if (!ctx || !x_dev || !client_ids || !b_q8 || !msgs_dev || !msg_capacity) return EDEN_ERR_INVALID_ARG;
     if (n == 0 || n > ctx->n_max || d == 0 || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
     for (uint32_t c = 0; c < n; ++c) {
-        if (!msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
-        if (eden_message_bytes(d, b_q8[c]) == 0) return EDEN_ERR_INVALID_ARG;
+        if (!x_dev[c] || !msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
+        const size_t need = eden_message_bytes(d, b_q8[c]);
+        if (need == 0) return EDEN_ERR_INVALID_ARG;
+        if (msg_capacity[c] < need) return EDEN_ERR_CAPACITY;
     }
+    const int mode = sparsify_mode(b_q8, n);
+    if (mode < 0) return EDEN_ERR_INVALID_ARG;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return EDEN_ERR_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int pre = 0;                                                 // sparsification before the rotation: all or none
-    for (uint32_t c = 0; c < n; ++c) pre += (b_q8[c] == kPreHalf);
-    if (pre != 0 && pre != (int)n) return EDEN_ERR_INVALID_ARG;
-    const uint64_t d_src = d;
-    if (pre) d = (d + 1) / 2;
+    std::vector<uint32_t> ones(n, 256u);                         // the sparsifying budgets quantize with b = 1
+    if (mode == 0) return encode_range(ctx, x_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, msgs_dev, st);
+    if (mode == 1) return encode_range(ctx, x_dev, client_ids, ones.data(), b_q8, n, d, 1, d, seed, msgs_dev, st);
+    // b = m/64: sender by sender, the kept coordinates packed into the staging vector, then the 1-bit method on it
+    if (!ensure_stage(ctx)) return EDEN_ERR_HIP;
+    for (uint32_t c = 0; c < n; ++c) {
+        const uint32_t m = sparse_m(b_q8[c]);
+        launch_sparse_gather(x_dev[c], d, m, seed, client_ids[c], ctx->stage, st);
+        if (!launch_ok()) return EDEN_ERR_HIP;
+        const float *xs = ctx->stage;
+        const int rc = encode_range(ctx, &xs, &client_ids[c], ones.data(), &b_q8[c], 1, (uint64_t)m * ((d + 63) / 64), 0, d, seed,
+                                    &msgs_dev[c], st);
+        if (rc != EDEN_OK) return rc;
+    }
+    return EDEN_OK;
+}
+
+// Decodes n messages whose transformed vectors all have the same dimension and adds them to acc (see encode_range
+// for the arguments; `d_src` is the length of acc, `bitmaps` may be null).
+static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids, const uint32_t *b_kernel,
+                        const uint32_t *b_hdr, uint32_t n, uint64_t d_src, int pre, uint64_t hdr_d, uint64_t seed,
+                        const uint32_t *const *bitmaps, float *acc_dev, hipStream_t st) {
+    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the decoded vectors
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
-    for (uint32_t c = 0; c < n; ++c) wide_ok = wide_ok && (pre || b_q8[c] == 256u || b_q8[c] == 512u || b_q8[c] == 1024u);
+    for (uint32_t c = 0; c < n; ++c) wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u);
     const Plan pl = make_plan(log2D, wide_ok);
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
@@ -299,20 +325,21 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
         std::memset(&B, 0, sizeof(B));
         for (uint32_t i = 0; i < nb; ++i) {
             B.msg[i] = msgs_dev[first + i];
-            B.bitmap[i] = recv_bitmaps_dev ? recv_bitmaps_dev[first + i] : nullptr;
+            B.bitmap[i] = bitmaps ? bitmaps[first + i] : nullptr;
             B.client[i] = client_ids[first + i];
-            B.b_q8[i] = pre ? 256u : b_q8[first + i];
+            B.b_q8[i] = b_kernel[first + i];
+            B.hdr_b_q8[i] = b_hdr[first + i];
         }
         if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);
-            launch_dec_small(B, nb, d_src, pre, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
+            launch_dec_small(B, nb, d_src, pre, hdr_d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
         } else {
             // Strided passes first (every sender on its own), contiguous pass last (sums the senders in registers
             // and touches acc once).  With a single strided pass the workspace of a b <= 1 sender holds int16.
             const int narrow = (pl.nhi == 1) ? 1 : 0;
             {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
-                launch_dec_prepare(B, nb, d_src, pre, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
+                launch_dec_prepare(B, nb, hdr_d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
             }
             for (int i = pl.nhi - 1; i >= 0; --i) {
                 const HiPass &h = pl.hi[i];
@@ -334,6 +361,42 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
                                      ctx->dec_partial, ctx->dec_partial_tiles, st);
             else launch_dec_lo_last(B, nb, d_src, pre, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
         }
+        if (!launch_ok()) return EDEN_ERR_HIP;
+    }
+    return EDEN_OK;
+}
+
+int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
+                           const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
+                           const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream) {
+    if (!ctx || !msgs_dev || !client_ids || !b_q8 || !acc_dev) return EDEN_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(acc_dev) & 15u) return EDEN_ERR_INVALID_ARG;
+    if (n == 0 || n > ctx->n_max || d == 0 || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
+    for (uint32_t c = 0; c < n; ++c) {
+        if (!msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
+        if (eden_message_bytes(d, b_q8[c]) == 0) return EDEN_ERR_INVALID_ARG;
+    }
+    const int mode = sparsify_mode(b_q8, n);
+    if (mode < 0) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::vector<uint32_t> ones(n, 256u);
+    if (mode == 0) return decode_range(ctx, msgs_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, recv_bitmaps_dev, acc_dev, st);
+    if (mode == 1) return decode_range(ctx, msgs_dev, client_ids, ones.data(), b_q8, n, d, 1, d, seed, recv_bitmaps_dev, acc_dev, st);
+    // b = m/64: sender by sender (the kept coordinates differ), the 1-bit decode into the staging vector (the factor
+    // 64/m is folded into the dequantization), then the values go back to their coordinates of acc
+    if (!ensure_stage(ctx)) return EDEN_ERR_HIP;
+    for (uint32_t c = 0; c < n; ++c) {
+        const uint32_t m = sparse_m(b_q8[c]);
+        const uint64_t dk = (uint64_t)m * ((d + 63) / 64);
+        launch_fill_zero(ctx->stage, dk, st);
+        if (!launch_ok()) return EDEN_ERR_HIP;
+        const uint32_t *bm = recv_bitmaps_dev ? recv_bitmaps_dev[c] : nullptr;
+        const int rc = decode_range(ctx, &msgs_dev[c], &client_ids[c], ones.data(), &b_q8[c], 1, dk, 0, d, seed,
+                                    recv_bitmaps_dev ? &bm : nullptr, ctx->stage, st);
+        if (rc != EDEN_OK) return rc;
+        launch_sparse_scatter(ctx->stage, d, m, seed, client_ids[c], acc_dev, st);
         if (!launch_ok()) return EDEN_ERR_HIP;
     }
     return EDEN_OK;

@@ -16,7 +16,7 @@ constexpr int kLdsRow = 68;              // padded row length (floats) of the 64
 
 // ---- shared randomness (Sec. 2.1): counter hash = splitmix64 stream started at a per-(seed,stream,client) key
 constexpr uint64_t kPhi = 0x9E3779B97F4A7C15ull;
-enum : uint32_t { kStreamSign = 0, kStreamSubsample = 1, kStreamLoss = 2, kStreamMix = 3 };
+enum : uint32_t { kStreamSign = 0, kStreamSubsample = 1, kStreamLoss = 2, kStreamMix = 3, kStreamSparse = 4 };
 
 __host__ __device__ inline uint64_t mix64(uint64_t z) {
     z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
@@ -38,6 +38,15 @@ __host__ __device__ inline uint64_t hash_word(uint64_t key, uint64_t j) { return
 // x'[g] = 2 x[2g + offset_g] of dimension ceil(d/2) is encoded with b = 1; the kernels then see b_q8 = 256 and
 // only the gather (first encode pass), the scatter (last decode pass) and the header know about it.
 constexpr uint32_t kPreHalf = 0x10000u | 128u;
+// b = m/64, 1 <= m <= 63 (Sec. 4.1 sub-bit compression with p = m/64, sparsification before the rotation): of every
+// 64 consecutive coordinates the m with the smallest 16-bit keys of the SPARSE stream are kept (ties by position)
+// and the vector of kept coordinates is encoded with b = 1; the receiver multiplies by 64/m.  Only a gather kernel
+// before the encoder, a scatter kernel after the decoder and the header know about it.
+constexpr uint32_t kSparseFlag = 0x20000u;
+__host__ __device__ inline uint32_t sparse_m(uint32_t b_q8) {
+    const uint32_t m = b_q8 & 0xFFFFu;
+    return ((b_q8 & ~0xFFFFu) == kSparseFlag && m >= 1 && m <= 63) ? m : 0;
+}
 __host__ __device__ inline bool budget_mixed(uint32_t b_q8) { return b_q8 == 384 || b_q8 == 640 || b_q8 == 896; }
 __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
     if (b_q8 == 128) { bits = 1; k = 2; return true; }
@@ -97,13 +106,15 @@ struct EncBatch {
     const float *x[kMaxBatch];
     void *msg[kMaxBatch];
     uint32_t client[kMaxBatch];
-    uint32_t b_q8[kMaxBatch];
+    uint32_t b_q8[kMaxBatch];       // what the kernels quantize with
+    uint32_t hdr_b_q8[kMaxBatch];   // what the header says (differs for the budgets that sparsify before the rotation)
 };
 struct DecBatch {
     const void *msg[kMaxBatch];
     const uint32_t *bitmap[kMaxBatch];
     uint32_t client[kMaxBatch];
     uint32_t b_q8[kMaxBatch];
+    uint32_t hdr_b_q8[kMaxBatch];
 };
 
 // ---- wave-level helpers

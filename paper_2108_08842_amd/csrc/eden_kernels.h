@@ -27,20 +27,24 @@ void launch_dec_wide_first(const DecBatch &B, uint32_t n, uint64_t keep_elems, i
                            hipStream_t st);
 void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint32_t partial_stride, uint32_t nparts,
                      EncScratch *scratch, const DevTables *tab, hipStream_t st);
-void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed,
+void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed,
                        const double *partials_n2, uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip,
                        uint32_t partial_stride, uint32_t *dev_status, hipStream_t st);
-void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
+void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st);
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                          const DecScratch *scratch, int narrow, float *T, hipStream_t st);
 void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st);
-void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
-                      uint32_t *dev_status, hipStream_t st);
-void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
-                      float *acc, uint32_t *dev_status, hipStream_t st);
+void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
+                      const DevTables *tab, uint32_t *dev_status, hipStream_t st);
+void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
+                      const DevTables *tab, float *acc, uint32_t *dev_status, hipStream_t st);
+// b = m/64: the kept coordinates of x packed into `stage` (m per block of 64), and added back from it into acc
+void launch_sparse_gather(const float *x, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *stage, hipStream_t st);
+void launch_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *acc, hipStream_t st);
+void launch_fill_zero(float *p, uint64_t count, hipStream_t st);
 void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
                      hipStream_t st);
 void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st);

@@ -526,7 +526,7 @@ __global__ __launch_bounds__(128) void k_enc_lo_first(EncBatch B, uint64_t d_src
 // One workgroup per sender: sums the partials of sum_i u_i q_i in index order, forms
 // <R(x),Q> = D^-1/2 sum and the scale S = |x|^2 / <R(x),Q> (Sec. 2.3), writes the header.
 // A zero or non-finite vector gets S = 0, a status bit and an all-zero payload.
-__global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int pre, int log2D, uint64_t seed,
+__global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t hdr_d, int log2D, uint64_t seed,
                                                     const double *partials_n2, uint32_t nparts_n2,
                                                     const double *partials_ip, uint32_t nparts_ip,
                                                     uint32_t partial_stride, uint32_t payload_words_b1,
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int 
     }
     if (threadIdx.x == 0) {
         MsgHeader h;
-        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = pre ? kPreHalf : b_q8; h.client = B.client[c];
+        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = hdr_d; h.b_q8 = B.hdr_b_q8[c]; h.client = B.client[c];
         h.zero = 0; h.seed = seed; h.N2 = n2;
         if (valid) {
             h.IP = total * exp2(-0.5 * (double)log2D);       // <R(x),Q> = D^-1/2 sum u_i q_i
@@ -575,13 +575,14 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t d, int 
 // One wave per message: check the header against what the receiver agreed on, count the coordinates
 // that arrived (Sec. 4.2: the receiver finds p by counting), and build the dequantization table
 // (S / (p sqrt(D))) * q_l  -- S/p from Sec. 4.2, D^-1/2 from the inverse rotation.
+// `hdr_d`, `hdr_b_q8`: what the header must say; `b_q8`: the budget the kernels dequantize with.
 __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap, uint32_t client, uint32_t b_q8,
-                                        uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
+                                        uint32_t hdr_b_q8, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
                                         DecScratch *out, uint32_t *dev_status) {
     const uint32_t lane = lane_id();
     const MsgHeader h = *static_cast<const MsgHeader *>(msg);
     uint32_t flags = 0;
-    if (h.magic != kMagic || h.log2D != (uint32_t)log2D || h.d != d || h.b_q8 != (pre ? kPreHalf : b_q8) ||
+    if (h.magic != kMagic || h.log2D != (uint32_t)log2D || h.d != hdr_d || h.b_q8 != hdr_b_q8 ||
         h.client != client || h.seed != seed)
         flags |= EDEN_DEV_HEADER_MISMATCH;
     else
@@ -607,6 +608,7 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
     if (flags == 0 && arrived == 0) flags |= EDEN_DEV_NOTHING_ARRIVED;
     double coef = 0.0;
     if (flags == 0) coef = h.S * exp2(0.5 * (double)log2D) / (double)arrived;     // S / (p sqrt(D)), p = arrived / D
+    if (sparse_m(hdr_b_q8)) coef *= 64.0 / (double)sparse_m(hdr_b_q8);             // the 1/p of the sparsification (Sec. 4.1)
     if (lane < 32) {                                             // lanes 16..31: the finer table of a mixed budget
         const int tb = (lane < 16 || !budget_mixed(b_q8)) ? bits : bits + 1;
         const int H = 1 << (tb - 1), l = (int)(lane & 15u);
@@ -621,10 +623,10 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
     }
 }
 
-__global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t d, int pre, int log2D, uint64_t seed,
+__global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t hdr_d, int log2D, uint64_t seed,
                                                     const DevTables *tab, DecScratch *scratch, uint32_t *dev_status) {
     const uint32_t c = blockIdx.x;
-    dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, pre, log2D, seed, tab, &scratch[c], dev_status);
+    dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], hdr_d, log2D, seed, tab, &scratch[c], dev_status);
 }
 
 // Decode, last pass in wave tiles: index bits 0..11 of H for every sender, that sender's sign diagonal
@@ -717,6 +719,47 @@ __global__ void k_finalize_mean(const float *acc, uint64_t d, float n, float *me
     }
 }
 
+// ---- b = m/64: sparsification before the rotation with p = m/64 (Sec. 4.1).  One wave per block of 64 consecutive
+// coordinates.  Lane l holds the 16-bit key of coordinate 64 block + l (bits 16 (i & 3) .. +15 of word i >> 2 of the
+// SPARSE stream); its rank among the 64 (key, position) pairs is counted against every lane's pair; the m smallest
+// are kept, and a kept coordinate's slot is 64-block * m + its rank among the kept ones in position order.
+__device__ inline bool sparse_kept(uint64_t key, uint64_t block, uint32_t m, uint32_t lane, uint32_t &slot_in_block) {
+    const uint64_t i = block * 64u + lane;
+    const uint32_t k16 = (uint32_t)(hash_word(key, i >> 2) >> (16u * (uint32_t)(i & 3u))) & 0xFFFFu;
+    const uint32_t mine = (k16 << 6) | lane;
+    uint32_t rank = 0;
+#pragma unroll
+    for (int j = 0; j < 64; ++j) rank += (uint32_t)__builtin_amdgcn_readlane(mine, j) < mine ? 1u : 0u;
+    const bool kept = rank < m;
+    const uint64_t mask = __ballot(kept);
+    slot_in_block = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+    return kept;
+}
+// stage[block m + slot] = x[i] for the kept coordinates (0 for a kept position beyond d)
+__global__ __launch_bounds__(256) void k_sparse_gather(const float *x, uint64_t d, uint32_t m, uint64_t key, float *stage) {
+    const uint32_t lane = lane_id();
+    const uint64_t block = (uint64_t)blockIdx.x * 4u + wave_in_block();
+    if (block * 64u >= d) return;
+    uint32_t slot;
+    const bool kept = sparse_kept(key, block, m, lane, slot);
+    const uint64_t i = block * 64u + lane;
+    if (kept) stage[block * m + slot] = (i < d) ? x[i] : 0.0f;
+}
+// acc[i] += stage[block m + slot] for the kept coordinates below d (the factor 64/m is already in the values)
+__global__ __launch_bounds__(256) void k_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t key, float *acc) {
+    const uint32_t lane = lane_id();
+    const uint64_t block = (uint64_t)blockIdx.x * 4u + wave_in_block();
+    if (block * 64u >= d) return;
+    uint32_t slot;
+    const bool kept = sparse_kept(key, block, m, lane, slot);
+    const uint64_t i = block * 64u + lane;
+    if (kept && i < d) acc[i] += stage[block * m + slot];
+}
+__global__ __launch_bounds__(256) void k_fill_zero(float *p, uint64_t count) {
+    const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (i < count) p[i] = 0.0f;
+}
+
 // Experiment helper: sum_i (a_i - b_i)^2 and sum_i a_i^2 in double, the two terms of the (v)NMSE definitions
 // (Sec. 2.1: NMSE; Sec. 2.3: vNMSE).  Per-workgroup partials, then one workgroup adds them in index order.
 __global__ __launch_bounds__(256) void k_sq_error(const float *a, const float *b, uint64_t d, double *partials) {
@@ -755,7 +798,7 @@ __device__ inline void fwht_lds(float *buf, uint32_t D) {
     __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int pre, int log2D, uint64_t seed,
+__global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
                                                    const DevTables *tab, uint32_t *dev_status) {
     __shared__ float buf[kLoTile];
     __shared__ uint8_t code[kLoTile];
@@ -835,7 +878,7 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
     }
     if (threadIdx.x == 0) {
         MsgHeader h;
-        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = d; h.b_q8 = pre ? kPreHalf : b_q8; h.client = B.client[c];
+        h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = hdr_d; h.b_q8 = B.hdr_b_q8[c]; h.client = B.client[c];
         h.zero = 0; h.seed = seed; h.N2 = n2;
         if (valid) {
             h.IP = ipt * exp2(-0.5 * (double)log2D);
@@ -852,8 +895,8 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
 
 // One workgroup decodes the whole batch: per sender fill LDS with the dequantized rotated vector,
 // transform, apply the signs and add into per-thread sums; acc is touched once at the end.
-__global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed,
-                                                   const DevTables *tab, float *acc, uint32_t *dev_status) {
+__global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D,
+                                                   uint64_t seed, const DevTables *tab, float *acc, uint32_t *dev_status) {
     __shared__ float buf[kLoTile];
     __shared__ DecScratch s;
     const uint32_t D = 1u << log2D;
@@ -863,7 +906,7 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
     for (uint32_t c = 0; c < n; ++c) {
         __syncthreads();
         if (threadIdx.x < 64)
-            dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], d, pre, log2D, seed, tab, &s, dev_status);
+            dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], hdr_d, log2D, seed, tab, &s, dev_status);
         __syncthreads();
         const uint32_t b_q8 = B.b_q8[c];
         int bits, k;
@@ -974,11 +1017,11 @@ void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint
                      EncScratch *scratch, const DevTables *tab, hipStream_t st) {
     hipLaunchKernelGGL(k_enc_norm, dim3(n), dim3(256), 0, st, B, partials, partial_stride, nparts, scratch, tab);
 }
-void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed,
+void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed,
                        const double *partials_n2, uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip,
                        uint32_t partial_stride, uint32_t *dev_status, hipStream_t st) {
     const uint32_t words_b1 = 1u << (log2D - 5);
-    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, d, pre, log2D, seed, partials_n2, nparts_n2, partials_ip,
+    hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, hdr_d, log2D, seed, partials_n2, nparts_n2, partials_ip,
                        nparts_ip, partial_stride, words_b1, dev_status);
 }
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
@@ -996,9 +1039,9 @@ uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d_src, int 
     hipLaunchKernelGGL(k_enc_lo_first, grid, dim3(128), 0, st, B, d_src, pre, log2D, seed, T, partials, partial_stride);
     return grid.x;
 }
-void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
+void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st) {
-    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, d, pre, log2D, seed, tab, scratch, dev_status);
+    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, hdr_d, log2D, seed, tab, scratch, dev_status);
 }
 void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
@@ -1011,6 +1054,19 @@ void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean,
     const uint32_t blocks = (uint32_t)((d + per_block - 1) / per_block);
     hipLaunchKernelGGL(k_finalize_mean, dim3(blocks), dim3(256), 0, st, acc, d, (float)n, mean, vec);
 }
+void launch_sparse_gather(const float *x, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *stage, hipStream_t st) {
+    const uint32_t blocks = (uint32_t)((d + 63) / 64);
+    hipLaunchKernelGGL(k_sparse_gather, dim3((blocks + 3) / 4), dim3(256), 0, st, x, d, m, stream_key(seed, kStreamSparse, client),
+                       stage);
+}
+void launch_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *acc, hipStream_t st) {
+    const uint32_t blocks = (uint32_t)((d + 63) / 64);
+    hipLaunchKernelGGL(k_sparse_scatter, dim3((blocks + 3) / 4), dim3(256), 0, st, stage, d, m,
+                       stream_key(seed, kStreamSparse, client), acc);
+}
+void launch_fill_zero(float *p, uint64_t count, hipStream_t st) {
+    hipLaunchKernelGGL(k_fill_zero, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st, p, count);
+}
 void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
                      hipStream_t st) {
     uint32_t blocks = (uint32_t)((d + 1023) / 1024);
@@ -1020,13 +1076,13 @@ void launch_sq_error(const float *a, const float *b, uint64_t d, double *partial
     hipLaunchKernelGGL(k_sq_error, dim3(blocks), dim3(256), 0, st, a, b, d, partials);
     hipLaunchKernelGGL(k_sq_error_finish, dim3(1), dim3(256), 0, st, partials, blocks, out);
 }
-void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
-                      uint32_t *dev_status, hipStream_t st) {
-    hipLaunchKernelGGL(k_enc_small, dim3(n), dim3(256), 0, st, B, d, pre, log2D, seed, tab, dev_status);
+void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
+                      const DevTables *tab, uint32_t *dev_status, hipStream_t st) {
+    hipLaunchKernelGGL(k_enc_small, dim3(n), dim3(256), 0, st, B, d, pre, hdr_d, log2D, seed, tab, dev_status);
 }
-void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const DevTables *tab,
-                      float *acc, uint32_t *dev_status, hipStream_t st) {
-    hipLaunchKernelGGL(k_dec_small, dim3(1), dim3(256), 0, st, B, n, d, pre, log2D, seed, tab, acc, dev_status);
+void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
+                      const DevTables *tab, float *acc, uint32_t *dev_status, hipStream_t st) {
+    hipLaunchKernelGGL(k_dec_small, dim3(1), dim3(256), 0, st, B, n, d, pre, hdr_d, log2D, seed, tab, acc, dev_status);
 }
 void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st) {
     hipLaunchKernelGGL(k_hash_bits, dim3((uint32_t)((nwords + 255) / 256)), dim3(256), 0, st, key, nwords, out);

@@ -32,6 +32,14 @@ EXPORTS = [
     "eden_kernel_name", "eden_sq_error",
 ]
 B_HALF_PRE = 0x10080     # b = 1/2 with the sparsification before the rotation (EDEN_B_HALF_PRE)
+
+
+def B_SPARSE(m: int) -> int:
+    """b = m/64, 1 <= m <= 63: m of every 64 coordinates are kept before the rotation (EDEN_B_SPARSE(m))."""
+    assert 1 <= m <= 63
+    return 0x20000 | m
+
+
 KERNEL_KINDS = ["enc_first", "mid", "enc_last", "dec_prepare", "dec_first", "dec_last", "finalize_mean",
                 "enc_small", "dec_small", "enc_norm", "enc_finish"]
 

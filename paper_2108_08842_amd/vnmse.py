@@ -29,6 +29,16 @@ def expected_q2(bits: int) -> float:
     return sum((cdf(edges[k + 1]) - cdf(edges[k])) * q[k] ** 2 for k in range(len(q)))
 
 
+def theory_sparse(m: int, d: int) -> float:
+    """b = m/64 with the sparsification before the rotation (Sec. 4.1): error of the sparsification, 1/p - 1, plus
+    1/p times the 1-bit error of the kept vector; that vector has m ceil(d/64) entries and is padded to a power of
+    two, which spreads the 1-bit error over the padding as well."""
+    p = m / 64.0
+    kept = m * ((d + 63) // 64)
+    padded = 1 << max(0, (kept - 1).bit_length())
+    return (1.0 + (1.0 / expected_q2(1) - 1.0) * kept / padded) / p - 1.0
+
+
 def theory_vnmse(b: float, keep: float = 1.0) -> float:
     """Asymptotic vNMSE for budget b (0.5, an integer >= 1, or an integer + 1/2) when a fraction `keep` of the
     packets arrives.  b = k + 1/2 mixes the two quantizers half and half (Sec. 4.1: 0.317 at b = 1.5)."""
@@ -38,6 +48,11 @@ def theory_vnmse(b: float, keep: float = 1.0) -> float:
     if b > 1 and b != int(b):
         e = 0.5 * e + 0.5 * expected_q2(bits + 1)
     return 1.0 / (p * e) - 1.0
+
+
+def eden_b_half_pre() -> int:
+    from . import eden
+    return eden.B_HALF_PRE
 
 
 def draw(dist: str, d: int, gen, device):
@@ -67,7 +82,12 @@ def measure_vnmse(ctx, x, b_q8: int, trials: int, seed: int, drop_q32: int = 0):
     """Mean and standard error of |x - x_hat|^2 / |x|^2 over `trials` independent senders of the same x."""
     import torch
     d = x.numel()
-    D = 1 << max(0, (d - 1).bit_length())
+    dt = d                                              # dimension of the transform (the packets of a loss bitmap refer to it)
+    if b_q8 == eden_b_half_pre():
+        dt = (d + 1) // 2
+    elif (b_q8 >> 16) == 2:
+        dt = (b_q8 & 0xFFFF) * ((d + 63) // 64)
+    D = 1 << max(0, (dt - 1).bit_length())
     ids = list(range(trials))
     msgs = ctx.encode([x] * trials, ids, [b_q8] * trials, seed)
     acc = torch.empty(d, dtype=torch.float32, device=x.device)
@@ -129,10 +149,15 @@ def main(argv=None):
             ctx = eden.Context(d_max=d, n_max=max(trials, args.senders, 1), device=0)
             x = draw(dist, d, gen, dev)
             for b in args.budgets:
-                b_q8 = eden.B_HALF_PRE if (args.pre_rotation and b == 0.5) else int(round(b * 256))
+                if b < 1 and b != 0.5:                          # b = m/64: m of every 64 coordinates, before the rotation
+                    m = max(1, min(63, int(round(b * 64))))
+                    b, b_q8 = m / 64.0, eden.B_SPARSE(m)
+                    th = theory_sparse(m, d) if not drop_q32 else float("nan")
+                else:
+                    b_q8 = eden.B_HALF_PRE if (args.pre_rotation and b == 0.5) else int(round(b * 256))
+                    th = theory_vnmse(b, 1.0 - args.loss)
                 v, se = measure_vnmse(ctx, x, b_q8, trials, args.seed, drop_q32)
-                th = theory_vnmse(b, 1.0 - args.loss)
-                line = f"{dist:11s} {d:9d} {b:4g} {v:9.5f} {se:8.5f} {th:8.5f}"
+                line = f"{dist:11s} {d:9d} {b:4.3g} {v:9.5f} {se:8.5f} {th:8.5f}"
                 if args.senders > 0 and not drop_q32:
                     xs = [draw(dist, d, gen, dev) for _ in range(args.senders)]
                     nm = measure_nmse(ctx, xs, [b_q8] * args.senders, args.seed + 1)

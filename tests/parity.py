@@ -49,7 +49,7 @@ def check_encode(x: np.ndarray, seed: int, client: int, b_q8: int, gpu_msg: o.Me
         assert gpu_msg.S == 0.0 and not gpu_msg.payload.any()
         return
     assert abs(gpu_msg.N2 - ref.N2) <= 1e-12 * ref.N2
-    if o.pre_rotation(b_q8):
+    if o.pre_rotation(b_q8) or o.sparse_m(b_q8):
         b_q8 = 256          # the trace is that of the 1-bit message of the sparsified vector (Sec. 4.1)
     bits, _ = o.budget(b_q8)
     thresholds, centroids = o.tables(bits)

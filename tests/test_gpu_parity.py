@@ -25,7 +25,11 @@ def _run_case(ctx, xs, client_ids, budgets, seed, drop_q32=0, also_oracle_msgs=T
     """Encode on the GPU, compare with the oracle; decode the same messages on both sides."""
     from paper_2108_08842_amd import eden
     n, d = len(xs), xs[0].size
-    D = o.padded_dim((d + 1) // 2 if o.pre_rotation(budgets[0]) else d)       # dimension of the transform
+    if o.sparse_m(budgets[0]):                                  # dimension of the transform (packet bitmaps refer to it)
+        assert len({o.sparse_m(b) for b in budgets}) == 1
+        D = o.padded_dim(o.sparse_m(budgets[0]) * ((d + 63) // 64))
+    else:
+        D = o.padded_dim((d + 1) // 2 if o.pre_rotation(budgets[0]) else d)
     print(f"case n={n} d={d} D=2^{D.bit_length() - 1} budgets={sorted(set(budgets))} seed={seed} drop={drop_q32}", flush=True)
     x_dev = [torch.from_numpy(x).cuda() for x in xs]
     msgs = ctx.encode(x_dev, client_ids, budgets, seed)
@@ -248,6 +252,20 @@ def test_sparsification_before_the_rotation(ctx, d):
     rc = ctx.encode_raw([t.data_ptr() for t in x_dev], [0, 1], [eden.B_HALF_PRE, 256], d, 1, [m.data_ptr() for m in msgs],
                         [m.numel() + 1 << 20 for m in msgs])
     assert rc == eden.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("d,m", [(40, 50), (64, 63), (65, 6), (1000, 3), (5000, 45), (70_000, 6), (300_001, 13), (3_000_000, 6),
+                                 (11_173_962 // 4, 32)])
+def test_sparse_budgets_m_of_64(ctx, d, m):
+    # b = m/64 (Sec. 4.1, sub-bit compression with p = m/64): gather, 1-bit method on the kept coordinates, scatter
+    from paper_2108_08842_amd import eden
+    B = eden.B_SPARSE(m)
+    w = synth.Workload("t", 3, d, [B] * 3, 1300 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(3)]
+    _run_case(ctx, xs, [8, 9, 10], w.b_q8, w.seed)
+    if m * ((d + 63) // 64) >= 8192:
+        _run_case(ctx, xs, [8, 9, 10], w.b_q8, w.seed + 1, drop_q32=int(0.25 * 2 ** 32), also_oracle_msgs=False)
+    assert eden.message_bytes(d, B) == o.message_bytes(d, B)
 
 
 def test_random_shapes_and_budgets(ctx):

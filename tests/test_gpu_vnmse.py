@@ -66,6 +66,21 @@ def test_vnmse_with_sparsification_before_the_rotation(ctx):
     assert abs(v - (math.pi - 1)) <= 5 * se + 0.03 * (math.pi - 1)
 
 
+def test_vnmse_of_sparse_budgets(ctx):
+    # Sec. 4.1: (1 + vNMSE_1)/p - 1 = (pi/2)/p - 1, the form the paper evaluates at p = 0.1; p = m/64 here
+    from paper_2108_08842_amd import eden, vnmse
+    d = 1 << 16
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(15)
+    x = vnmse.draw("lognormal", d, gen, torch.device("cuda:0"))
+    for m in (4, 6, 45):                                        # 4: the kept vector is a power of two long (no padding)
+        v, se = vnmse.measure_vnmse(ctx, x, eden.B_SPARSE(m), 24, seed=7)
+        th = vnmse.theory_sparse(m, d)
+        print(f"b={m}/64: vNMSE {v:.4f} +- {se:.4f}, theory {th:.4f}", flush=True)
+        assert abs(v - th) <= 5 * se + 0.03 * th
+    assert abs(vnmse.theory_sparse(4, d) - (math.pi / 2 * 16 - 1)) < 1e-12
+
+
 def test_vnmse_with_packet_loss(ctx):
     from paper_2108_08842_amd import vnmse
     d = 1 << 18                                                  # 256 packets: the arrived fraction is close to 0.9
