@@ -721,16 +721,21 @@ __global__ void k_finalize_mean(const float *acc, uint64_t d, float n, float *me
 
 // ---- b = m/64: sparsification before the rotation with p = m/64 (Sec. 4.1).  One wave per block of 64 consecutive
 // coordinates.  Lane l holds the 16-bit key of coordinate 64 block + l (bits 16 (i & 3) .. +15 of word i >> 2 of the
-// SPARSE stream); its rank among the 64 (key, position) pairs is counted against every lane's pair; the m smallest
-// are kept, and a kept coordinate's slot is 64-block * m + its rank among the kept ones in position order.
+// SPARSE stream); the m smallest of the 64 (key, position) pairs are kept, and a kept coordinate's slot is
+// 64-block * m + its rank among the kept ones in position order.
 __device__ inline bool sparse_kept(uint64_t key, uint64_t block, uint32_t m, uint32_t lane, uint32_t &slot_in_block) {
     const uint64_t i = block * 64u + lane;
     const uint32_t k16 = (uint32_t)(hash_word(key, i >> 2) >> (16u * (uint32_t)(i & 3u))) & 0xFFFFu;
-    const uint32_t mine = (k16 << 6) | lane;
-    uint32_t rank = 0;
+    const uint32_t mine = (k16 << 6) | lane;                     // 22 bits, all 64 different
+    // the (m+1)-th smallest pair, bit by bit: the largest t with |{pairs < t}| <= m (a count per bit instead of a
+    // rank per lane against all 64 pairs)
+    uint32_t t = 0;
 #pragma unroll
-    for (int j = 0; j < 64; ++j) rank += (uint32_t)__builtin_amdgcn_readlane(mine, j) < mine ? 1u : 0u;
-    const bool kept = rank < m;
+    for (int bit = 21; bit >= 0; --bit) {
+        const uint32_t cand = t | (1u << bit);
+        if ((uint32_t)__popcll(__ballot(mine < cand)) <= m) t = cand;
+    }
+    const bool kept = mine < t;
     const uint64_t mask = __ballot(kept);
     slot_in_block = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
     return kept;
