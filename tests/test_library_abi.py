@@ -57,3 +57,21 @@ def test_error_strings(eden):
     assert eden.strerror(0) == "ok"
     assert "argument" in eden.strerror(eden.ERR_INVALID_ARG)
     assert "small" in eden.strerror(eden.ERR_CAPACITY)
+
+
+def test_header_is_plain_c_and_library_links_from_c(tmp_path):
+    """A C99 program that includes include/eden.h, links the library and calls the entry points that need no GPU."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    from paper_2108_08842_amd import eden
+    eden.lib()                                                  # the library must be built
+    libdir = os.path.join(ROOT, "paper_2108_08842_amd")
+    exe = tmp_path / "abi_check"
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c", "abi_check.c"), "-o", str(exe), "-L", libdir, "-leden_hip", "-lm",
+           f"-Wl,-rpath,{libdir}"]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
+    assert "abi ok" in out.stdout
