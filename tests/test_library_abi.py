@@ -59,14 +59,12 @@ def test_error_strings(eden):
     assert "small" in eden.strerror(eden.ERR_CAPACITY)
 
 
-def test_header_is_plain_c_and_library_links_from_c(tmp_path):
+def test_header_is_plain_c_and_library_links_from_c(eden, tmp_path):
     """A C99 program that includes include/eden.h, links the library and calls the entry points that need no GPU."""
     import shutil
     import subprocess
     if shutil.which("gcc") is None:
         pytest.skip("no gcc")
-    from paper_2108_08842_amd import eden
-    eden.lib()                                                  # the library must be built
     libdir = os.path.join(ROOT, "paper_2108_08842_amd")
     exe = tmp_path / "abi_check"
     cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
