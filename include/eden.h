@@ -18,6 +18,9 @@
  *   - The caller owns every buffer it passes.  The library reads inputs, writes outputs,
  *     and keeps no caller pointer after the call returns.  Its only own device memory is the
  *     context workspace allocated by eden_create.
+ *   - eden_encode, eden_decode_accumulate and eden_finalize_mean only launch kernels on `stream`: no
+ *     allocation (except the first call with an EDEN_B_SPARSE budget), no memset, no host synchronisation,
+ *     so they may be captured in a HIP graph.
  *   - A context serialises its work through that workspace: calls on one context must be issued from
  *     one thread at a time and on one stream (or on streams the caller orders); two calls that run
  *     concurrently on the same context race.  Use one context per concurrent stream.

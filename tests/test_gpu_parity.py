@@ -287,6 +287,48 @@ def test_random_shapes_and_budgets(ctx):
         _run_case(ctx, xs, ids, w.b_q8, int(rng.integers(0, 2 ** 62)), drop_q32=drop, also_oracle_msgs=(case % 4 == 0))
 
 
+def test_step_can_be_captured_in_a_graph(ctx):
+    # encode + decode + mean make no allocation and no host synchronisation, so a caller may capture them; every
+    # replay, with other work in between, must reproduce the eager result bit for bit
+    d, n = 300_000, 6
+    w = synth.Workload("t", n, d, [128, 256, 384, 512, 768, 1024], 4242, "lognormal")
+    D = o.padded_dim(d)
+    xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(n)]
+    ids = list(range(n))
+    msgs = ctx.alloc_messages(d, w.b_q8)
+    bitmaps = [ctx.make_loss_bitmap(w.seed, c, D, int(0.1 * 2 ** 32)) for c in ids]
+    acc = torch.zeros(d, device="cuda")
+    mean = torch.empty_like(acc)
+
+    def step():
+        acc.zero_()
+        ctx.encode(xs, ids, w.b_q8, w.seed, msgs=msgs)
+        ctx.decode_accumulate(msgs, ids, w.b_q8, d, w.seed, acc, bitmaps)
+        ctx.finalize_mean(acc, n, out=mean)
+
+    step()
+    torch.cuda.synchronize()
+    eager = mean.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                               # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        mean.fill_(7.0)
+        for m in msgs:
+            m.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(mean, eager)
+        assert float((acc * 2).sum()) == float((acc * 2).sum())      # eager work between the replays
+    assert ctx.last_device_status() == 0
+
+
 def test_mismatch_fraction_over_all_cases():
     # runs last in this file: every encode comparison made so far in this process is in the pool
     pool = parity.check_pool()
