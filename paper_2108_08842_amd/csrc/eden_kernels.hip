@@ -85,8 +85,8 @@ __device__ inline void store_row_planes(const uint32_t (&plane)[4][2], uint32_t 
 // stream selects is quantized with I_{K+1}; the top bit of its index goes to the second part, one bit per pair.
 // `my_row`: first coordinate of the row that this lane (< R) finishes.
 template <int R, int K, bool MIX>
-__device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *sc, uint64_t mixkey, uint64_t my_row,
-                                        uint32_t *part_a, uint32_t *part_b, float &ip) {
+__device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *sc, const float *qtab, uint64_t mixkey,
+                                        uint64_t my_row, uint32_t *part_a, uint32_t *part_b, float &ip) {
     constexpr int H = 1 << (K - 1);
     const uint32_t lane = lane_id();
     uint32_t plane[4][2], top[2] = {0u, 0u};
@@ -100,12 +100,12 @@ __device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *s
         if constexpr (MIX) {
             const uint32_t offs = __builtin_amdgcn_readlane(offs_mine, r);
             const bool up = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
-            code = quantize_mixed<K>(v[r], up, sc, ip);
+            code = quantize_mixed<K>(v[r], up, sc, qtab, ip);
             const uint64_t m = __ballot((code >> K) & 1u);
             top[0] = put_lane<r>(lo32(m), top[0]);
             top[1] = put_lane<r>(hi32(m), top[1]);
         } else {
-            code = quantize_one<H>(v[r], sc->thr, sc->qpos, ip);
+            code = quantize_one<H>(v[r], sc, qtab, ip);
         }
 #pragma unroll
         for (int b = 0; b < K; ++b) {
@@ -133,6 +133,7 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
                                                      const EncScratch *scratch) {
     constexpr int R = 1 << M;
     __shared__ double red[4];
+    __shared__ float qtabs[4][16];
     const uint32_t c = blockIdx.y;
     const uint32_t lane = lane_id();
     const uint32_t tile = blockIdx.x * 4u + wave_in_block();
@@ -178,15 +179,18 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
             }
         } else {
             const EncScratch *sc = &scratch[c];
+            float *qtab = qtabs[wave_in_block()];
+            fill_qtab(qtab, sc, lane);
+            wave_lds_sync();
             const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
             uint32_t *part_b = payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4;
             switch (b_q8) {
-                case 384u: hi_quantize_pack<R, 1, true>(v, sc, mixkey, my_row, payload, part_b, ip); break;
-                case 512u: hi_quantize_pack<R, 2, false>(v, sc, mixkey, my_row, payload, part_b, ip); break;
-                case 640u: hi_quantize_pack<R, 2, true>(v, sc, mixkey, my_row, payload, part_b, ip); break;
-                case 768u: hi_quantize_pack<R, 3, false>(v, sc, mixkey, my_row, payload, part_b, ip); break;
-                case 896u: hi_quantize_pack<R, 3, true>(v, sc, mixkey, my_row, payload, part_b, ip); break;
-                default: hi_quantize_pack<R, 4, false>(v, sc, mixkey, my_row, payload, part_b, ip); break;
+                case 384u: hi_quantize_pack<R, 1, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 512u: hi_quantize_pack<R, 2, false>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 640u: hi_quantize_pack<R, 2, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 768u: hi_quantize_pack<R, 3, false>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 896u: hi_quantize_pack<R, 3, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                default: hi_quantize_pack<R, 4, false>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
             }
         }
     }
@@ -372,6 +376,10 @@ __global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t vali
     char *payload = static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES;
     const uint32_t b_q8 = B.b_q8[c];
     const EncScratch *sc = &scratch[c];
+    __shared__ float qtabs[4][16];
+    float *qtab = qtabs[wave_in_block()];
+    fill_qtab(qtab, sc, lane);
+    wave_lds_sync();
     float ip = 0.0f;
 #pragma unroll
     for (int r = 0; r < kWideRows; ++r) {
@@ -391,11 +399,11 @@ __global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t vali
                 if (!(lane & 1u)) reinterpret_cast<uint8_t *>(payload)[group >> 1] = (uint8_t)word;
             } else if (b_q8 == 512u) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) word |= quantize_one<2>(v[r][4 * h + e], sc->thr, sc->qpos, ip) << (2 * e);
+                for (int e = 0; e < 4; ++e) word |= quantize_one<2>(v[r][4 * h + e], sc, qtab, ip) << (2 * e);
                 reinterpret_cast<uint8_t *>(payload)[group] = (uint8_t)word;
             } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) word |= quantize_one<8>(v[r][4 * h + e], sc->thr, sc->qpos, ip) << (4 * e);
+                for (int e = 0; e < 4; ++e) word |= quantize_one<8>(v[r][4 * h + e], sc, qtab, ip) << (4 * e);
                 reinterpret_cast<uint16_t *>(payload)[group] = (uint16_t)word;
             }
         }

@@ -111,8 +111,8 @@ __device__ inline uint32_t hix_word_row(int ph, int w) {
 // every pair that the MIX stream selects is quantized with I_{BITS+1}; the top bit of its index goes to the
 // second part of the payload, one bit per pair = 16 bits per row segment of a tile.
 template <int M, int BITS, bool MIX>
-__device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph, const EncScratch *sc, uint32_t *payload,
-                                         uint16_t *part_b, uint64_t mixkey, uint64_t base, float &ip) {
+__device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph, const EncScratch *sc, const float *qtab,
+                                         uint32_t *payload, uint16_t *part_b, uint64_t mixkey, uint64_t base, float &ip) {
     using X = HiX<M>;
     constexpr int p = kHixP;
     constexpr int H = 1 << (BITS - 1);
@@ -137,12 +137,12 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
             const uint32_t ob = __builtin_amdgcn_readlane(offs16[s / 32], 32 + s % 32);
             const uint32_t offs = (lane < 32u) ? oa : ob;
             const bool up = ((offs >> (col >> 1)) & 1u) == (col & 1u);
-            code = quantize_mixed<BITS>(out[s], up, sc, ip);
+            code = quantize_mixed<BITS>(out[s], up, sc, qtab, ip);
             const uint64_t m = __ballot((code >> BITS) & 1u);
             top[s / 32] = put_lane<s % 32>(lo32(m), top[s / 32]);
             top[s / 32] = put_lane<32 + s % 32>(hi32(m), top[s / 32]);
         } else {
-            code = quantize_one<H>(out[s], sc->thr, sc->qpos, ip);
+            code = quantize_one<H>(out[s], sc, qtab, ip);
         }
 #pragma unroll
         for (int b = 0; b < BITS; ++b) {
@@ -217,6 +217,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
     using X = HiX<M>;
     __shared__ float lds[X::LDS_FLOATS];
     __shared__ double red[X::THREADS / 64];
+    __shared__ float qtab[16];                                   // centroids; published by the first barrier of the exchange
     constexpr int p = kHixP;
     constexpr int NW = X::RP / 32;
     constexpr bool UNIT = MODE == 0;
@@ -230,6 +231,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
     const EncScratch *sc = &scratch[c];
     const uint32_t off1 = ((g << p) + col) * 4u;                         // stage-1 rows: g + RL r
     const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
+    if (!UNIT) fill_qtab(qtab, sc, threadIdx.x);
     float ip = 0.0f;
     uint32_t held[TPW][X::PH][NW];
     float v[64];
@@ -257,12 +259,12 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
             if (UNIT || b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
             else {
                 uint16_t *part_b = reinterpret_cast<uint16_t *>(payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4);
-                if (MODE == 2 && b_q8 == 384u) hix_quantize_pack<M, 1, true>(out, ph, sc, payload, part_b, mixkey, base, ip);
-                else if (MODE == 2 && b_q8 == 640u) hix_quantize_pack<M, 2, true>(out, ph, sc, payload, part_b, mixkey, base, ip);
-                else if (MODE == 2 && b_q8 == 896u) hix_quantize_pack<M, 3, true>(out, ph, sc, payload, part_b, mixkey, base, ip);
-                else if (b_q8 == 512u) hix_quantize_pack<M, 2, false>(out, ph, sc, payload, part_b, mixkey, base, ip);
-                else if (b_q8 == 768u) hix_quantize_pack<M, 3, false>(out, ph, sc, payload, part_b, mixkey, base, ip);
-                else hix_quantize_pack<M, 4, false>(out, ph, sc, payload, part_b, mixkey, base, ip);
+                if (MODE == 2 && b_q8 == 384u) hix_quantize_pack<M, 1, true>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
+                else if (MODE == 2 && b_q8 == 640u) hix_quantize_pack<M, 2, true>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
+                else if (MODE == 2 && b_q8 == 896u) hix_quantize_pack<M, 3, true>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
+                else if (b_q8 == 512u) hix_quantize_pack<M, 2, false>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
+                else if (b_q8 == 768u) hix_quantize_pack<M, 3, false>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
+                else hix_quantize_pack<M, 4, false>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
             }
         }
     }
