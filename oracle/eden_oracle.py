@@ -26,6 +26,8 @@ Pins (tests/test_oracle_*.py) tie each part to something other than itself:
                         empirical vNMSE against the printed asymptotic values
   * b = k + 1/2      -> a d=4 case worked by hand with the printed I_1 / I_2 values, the printed
                         0.317 at b = 1.5, exact size and mask structure, tangent identity
+  * uniform grid     -> the printed Delta_3 = 0.5224 with entropy 3 bits and vNMSE 0.022741 (Sec. 4.3),
+                        quadrature of the centres of mass, nearest-grid-point property
   * hash             -> the published splitmix64 test vector (seed 0)
 parity unpinned: the b=4 table has no printed value in the paper (it is pinned
 only by the Lloyd fixed-point conditions, symmetry and the rate-distortion
@@ -306,6 +308,41 @@ def pre_rotation(b_q8: int) -> bool:
     return b_q8 == (PRE_ROTATION | 128)
 
 
+GRID = 0x30000           # flag in b_q8: uniform-grid quantizer of Sec. 4.3 with Delta = (b_q8 & 0xFFFF) / 32768
+GRID_MAX_INDEX = 127     # reading: indices are sent as one signed byte each (before any entropy coder); the outermost
+                         # intervals extend to infinity
+
+
+def grid_delta(b_q8: int) -> float:
+    """Delta of a uniform-grid budget, 0.0 for every other budget (Sec. 4.3: I_Delta = {[Delta (n - 1/2), Delta (n + 1/2)]})."""
+    q = b_q8 & 0xFFFF
+    return q / 32768.0 if (b_q8 & ~0xFFFF) == GRID and q >= 1 else 0.0
+
+
+def grid_centroids(delta: float) -> np.ndarray:
+    """c[n], n = 0..127: centre of mass of N(0,1) on [Delta (n - 1/2), Delta (n + 1/2)] (Sec. 3: the optimal value of an
+    interval), the last one on [Delta 126.5, inf).  c[0] = 0 by symmetry; the value of index -n is -c[n]."""
+    c = np.zeros(GRID_MAX_INDEX + 1)
+    for n in range(1, GRID_MAX_INDEX + 1):
+        a = delta * (n - 0.5)
+        b = delta * (n + 0.5) if n < GRID_MAX_INDEX else math.inf
+        m = _mass(a, b)
+        c[n] = (_pdf(a) - (_pdf(b) if math.isfinite(b) else 0.0)) / m if m > 0.0 else a   # beyond double range: the edge
+    return c
+
+
+def grid_indices(z: np.ndarray, delta: float) -> np.ndarray:
+    """n = round(z / Delta) (Sec. 4.3), ties to even, clipped to the byte range."""
+    return np.clip(np.rint(z / delta), -GRID_MAX_INDEX, GRID_MAX_INDEX).astype(np.int64)
+
+
+def empirical_entropy_bits(idx: np.ndarray) -> float:
+    """-sum f log2 f over the frequencies of the indices: what an ideal entropy coder would spend per coordinate (Sec. 4.3)."""
+    _, counts = np.unique(idx, return_counts=True)
+    f = counts / idx.size
+    return float(-(f * np.log2(f)).sum())
+
+
 SPARSE = 0x20000         # flag in b_q8: b = m/64 with m = b_q8 & 0xFFFF, sparsification before the rotation
 SPARSE_BLOCK = 64
 
@@ -341,6 +378,8 @@ def budget(b_q8: int):
         return 1, 2
     if mixed(b_q8):
         return b_q8 // 256, 1
+    if grid_delta(b_q8):
+        return 8, 1                                 # one byte per coordinate on the wire (see GRID_MAX_INDEX)
     raise ValueError(f"unsupported bit budget b_q8={b_q8}")
 
 
@@ -422,12 +461,14 @@ class Message:
             "<IIQIIIIdddQ", buf[:HEADER_BYTES])
         if magic != MAGIC:
             raise ValueError("bad magic")
-        nw = payload_words(1 << log2D, 256 if (pre_rotation(b_q8) or sparse_m(b_q8)) else b_q8)
+        nw = payload_words(1 << log2D, 2048 if grid_delta(b_q8) else 256 if (pre_rotation(b_q8) or sparse_m(b_q8)) else b_q8)
         payload = np.frombuffer(buf, dtype="<u4", count=nw, offset=HEADER_BYTES).copy()
         return Message(log2D, d, b_q8, client, status, S, N2, IP, seed, payload)
 
 
 def message_bytes(d: int, b_q8: int) -> int:
+    if grid_delta(b_q8):
+        return HEADER_BYTES + 4 * payload_words(padded_dim(d), 2048)
     if sparse_m(b_q8):
         return HEADER_BYTES + 4 * payload_words(padded_dim(sparse_m(b_q8) * ((d + SPARSE_BLOCK - 1) // SPARSE_BLOCK)), 256)
     if pre_rotation(b_q8):
@@ -557,6 +598,19 @@ def encode(x: np.ndarray, seed: int, client: int, b_q8: int, want_trace: bool = 
         return (msg, None) if want_trace else msg
 
     y = rotate(x, seed, client)                    # R(x)
+    if grid_delta(b_q8):
+        # Sec. 4.3: the interval set I_Delta; the scale is S = |x|^2 / <R(x), Q> as for every interval set (Sec. 2.3)
+        delta = grid_delta(b_q8)
+        z = (math.sqrt(D) / math.sqrt(N2)) * y
+        idx = grid_indices(z, delta)
+        Q = np.sign(idx) * grid_centroids(delta)[np.abs(idx)]
+        IP = float(np.dot(y, Q))
+        if IP <= 0.0:                              # every coordinate fell into the interval around 0 (huge Delta)
+            msg = Message(D.bit_length() - 1, d, b_q8, client, STATUS_ZERO_VECTOR, 0.0, N2, 0.0, seed, np.zeros(nw, np.uint32))
+            return (msg, None) if want_trace else msg
+        payload = pack_indices(idx & 0xFF, 8, nw)   # two's complement bytes
+        msg = Message(D.bit_length() - 1, d, b_q8, client, 0, N2 / IP, N2, IP, seed, payload)
+        return (msg, EncodeTrace(z=z, idx=idx, kept=np.arange(D))) if want_trace else msg
     if mixed(b_q8):
         return _encode_mixed(y, N2, d, D, bits, b_q8, seed, client, want_trace)
     z, idx, Q, IP, S = quantize_and_scale(y, N2, bits)
@@ -585,10 +639,20 @@ def decode_rotated(msg: Message, bitmap: np.ndarray | None = None) -> np.ndarray
     """(S/p) * m o Q  in the rotated domain, all D coordinates."""
     D = 1 << msg.log2D
     bits, k = budget(msg.b_q8)
-    _, centroids = tables(bits)
     yhat = np.zeros(D, dtype=np.float64)
     if msg.status != 0:
         return yhat
+    if grid_delta(msg.b_q8):
+        raw = unpack_indices(msg.payload, 8, D)
+        idx = np.where(raw >= 128, raw - 256, raw)
+        Q = np.sign(idx) * grid_centroids(grid_delta(msg.b_q8))[np.minimum(np.abs(idx), GRID_MAX_INDEX)]
+        arrived = np.repeat(bitmap_to_packet_flags(bitmap, D), min(D, PACKET_COORDS))[:D]
+        count = int(arrived.sum())
+        if count == 0:
+            return yhat
+        yhat[arrived] = (msg.S / (count / D)) * Q[arrived]
+        return yhat
+    _, centroids = tables(bits)
     if mixed(msg.b_q8):
         up = upgraded_mask(msg.seed, msg.client, D)
         idx = unpack_mixed(msg.payload, D, msg.b_q8, up)

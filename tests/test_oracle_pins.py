@@ -683,3 +683,56 @@ def test_sparse_budget_ragged_end():
     not_kept = np.ones(d, dtype=bool)
     not_kept[src[src < d]] = False
     assert xh.size == d and not xh[not_kept].any() and np.count_nonzero(xh) > 30
+
+
+# ---- uniform-grid quantizer I_Delta (Sec. 4.3)
+def test_grid_quantizer_printed_values(golden):
+    # Delta_3 = 0.5224: entropy 3 bits and vNMSE 0.022741, both from the interval probabilities by plain erf sums
+    delta = golden["delta_3"]
+    c = o.grid_centroids(delta)
+    Phi = lambda v: 0.5 * math.erfc(-v / math.sqrt(2.0))
+    H = 0.0; EQ2 = 0.0
+    for n in range(-15, 16):                                              # |z| < 8.1: the rest has mass 1e-15
+        p = Phi(delta * (n + 0.5)) - Phi(delta * (n - 0.5))
+        H -= p * math.log2(p)
+        EQ2 += p * c[abs(n)] ** 2
+    assert abs(H - 3.0) < 2e-3
+    assert abs(1.0 / EQ2 - 1.0 - golden["vnmse_delta_3"]) < 2e-6
+    # the rate-distortion bound of Sec. 4.3: vNMSE >= 4^-b / (1 - 4^-b)
+    assert 1.0 / EQ2 - 1.0 > 4.0 ** -3 / (1 - 4.0 ** -3)
+    # centroids: inside their interval, odd symmetry by construction, quadrature of the centre of mass for two of them
+    from scipy import integrate
+    for n in (1, 5):
+        a, b = delta * (n - 0.5), delta * (n + 0.5)
+        num = integrate.quad(lambda t: t * math.exp(-t * t / 2), a, b, epsabs=1e-14)[0]
+        den = integrate.quad(lambda t: math.exp(-t * t / 2), a, b, epsabs=1e-14)[0]
+        assert abs(c[n] - num / den) < 1e-12
+    assert c[0] == 0.0 and np.all(np.diff(c[:60]) > 0) and np.all(np.abs(c[1:60] - delta * np.arange(1, 60)) < delta / 2)
+
+
+def test_grid_quantizer_path(golden):
+    q15 = round(golden["delta_3"] * 32768)
+    B = o.GRID | q15
+    d = 1 << 13
+    rng = np.random.default_rng(31)
+    x = rng.lognormal(size=d)
+    msg, tr = o.encode(x, 4, 2, B, want_trace=True)
+    assert o.message_bytes(d, B) == len(msg.to_bytes()) == 64 + d                # one byte per coordinate
+    np.testing.assert_array_equal(tr.idx, np.rint(tr.z / (q15 / 32768)).astype(np.int64))    # nothing clipped here
+    raw = np.frombuffer(msg.payload.tobytes(), dtype=np.int8)
+    np.testing.assert_array_equal(raw, tr.idx.astype(np.int8))                   # byte i = index i, two's complement
+    # round(z / Delta) is the nearest grid point
+    assert np.all(np.abs(tr.z - tr.idx * (q15 / 32768)) <= q15 / 65536 + 1e-12)
+    xh = o.decode(o.Message.from_bytes(msg.to_bytes()), d)
+    assert abs(np.dot(xh, x) - np.dot(x, x)) < 1e-10 * np.dot(x, x)              # tangent property of the scale
+    v = np.mean([o.vnmse_single(x, o.decode(o.encode(x, s, 0, B), d)) for s in range(12)])
+    assert abs(v - golden["vnmse_delta_3"]) < 0.03 * golden["vnmse_delta_3"]
+    assert abs(o.empirical_entropy_bits(tr.idx) - 3.0) < 0.03                    # concentrates around H (Sec. 4.3)
+    # loss: zero fill and 1/p
+    bm = np.array([0b11111101], dtype=np.uint32)
+    y = o.decode_rotated(msg, bm); full = o.decode_rotated(msg, None)
+    assert not y[1024:2048].any()
+    np.testing.assert_allclose(y[:1024], full[:1024] * (8 / 7), rtol=1e-14)
+    # an outlier beyond 127 Delta is clipped to the last interval
+    z = np.array([100.0, -100.0, 0.2, 0.27])
+    assert o.grid_indices(z, 0.5).tolist() == [127, -127, 0, 1]
