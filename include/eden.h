@@ -66,6 +66,12 @@
  *     the decoder multiplies by 64/m and puts them back.  Senders are processed one at a time (their kept sets
  *     differ); a call uses such budgets for all senders or for none; packets of a received-packet bitmap refer
  *     to the kept vector.  The first call with such a budget allocates d_max + 64 floats in the context.
+ *     EDEN_B_GRID(q) (0x30000 | q, 1 <= q <= 65535): the uniform-grid quantizer of Sec. 4.3 with
+ *     Delta = q / 32768: index n = round(z / Delta) (ties to even), clipped to +-127 and sent as one signed byte
+ *     per coordinate (the payload is D bytes; an entropy coder would bring it to about H(Delta) bits per
+ *     coordinate, 3 bits at Delta = 0.5224); the value of index n is the centre of mass of N(0,1) on
+ *     [Delta (n - 1/2), Delta (n + 1/2)] (the outermost intervals run to infinity).  A vector whose coordinates
+ *     all round to n = 0 is reported like a zero vector.
  *   - Index of a coordinate = rank of its interval in ascending order (0 = most negative).  At an
  *     interval endpoint the interval closer to zero is taken; z = 0 belongs to the non-negative
  *     side (Sec. 2.2.1 and its footnote).
@@ -89,6 +95,7 @@
 
 #define EDEN_B_HALF_PRE 0x10080u
 #define EDEN_B_SPARSE(m) (0x20000u | (unsigned)(m))
+#define EDEN_B_GRID(q) (0x30000u | (unsigned)(q))
 
 #include <stddef.h>
 #include <stdint.h>
@@ -187,6 +194,12 @@ int eden_make_subsample_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, u
  * a_dev, b_dev: device, fp32[d], read only.  out_dev: device, 2 doubles, written.  Asynchronous on `stream`;
  * uses the context's encoder scratch, so it must not overlap an eden_encode on another stream. */
 int eden_sq_error(eden_ctx *ctx, const float *a_dev, const float *b_dev, uint64_t d, double *out_dev, void *stream);
+
+/* Experiment helper (Sec. 4.3): out_dev[0] = the empirical entropy -sum f log2 f, in bits per coordinate, of the D
+ * one-byte indices of a message encoded with an EDEN_B_GRID budget: what an ideal entropy coder would spend.
+ * msg_dev: device, the message; out_dev: device, 1 double, written.  Asynchronous on `stream`; uses 1 KiB of the
+ * context, so calls on one context must not overlap. */
+int eden_index_entropy(eden_ctx *ctx, const void *msg_dev, uint64_t d, uint32_t b_q8, double *out_dev, void *stream);
 
 /* Copies the library's own Lloyd-Max tables for an integer budget `bits` (1..4) to host arrays:
  * thresholds[2^bits - 1] and centroids[2^bits], ascending, double precision (Sec. 3). */

@@ -27,6 +27,7 @@ struct eden_ctx {
     uint32_t compute_units;      // of the context's device
     float *dec_partial;          // sums of sender groups when the last decode pass splits tiles (D_max >= 2^19)
     uint32_t dec_partial_tiles;  // its size in tiles of 2^14 floats
+    uint32_t *hist;              // 256 counters for eden_index_entropy
     float *stage;                // d_max + 64 floats: the kept coordinates of one sender with a budget b = m/64;
                                  // allocated by the first call that uses such a budget
     EncScratch *enc_scratch; // slots
@@ -65,7 +66,7 @@ struct Plan {
     int nhi;
     HiPass hi[2];       // ascending p
 };
-// `wide_ok`: every sender of the launch has b = 1, 2 or 4 (what the wide top tile packs).
+// `wide_ok`: every sender of the launch has b = 1, 2, 4 or a uniform-grid budget (what the wide top tile packs).
 Plan make_plan(int log2D, bool wide_ok) {
     Plan pl{};
     if (log2D <= kLoBits) return pl;
@@ -159,6 +160,7 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     ok = ok && hipMalloc(&ctx->dec_scratch, ctx->slots * sizeof(DecScratch)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->tables, sizeof(DevTables)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->dev_status, sizeof(uint32_t)) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->hist, 256 * sizeof(uint32_t)) == hipSuccess;
     if (ok) {
         DevTables host{};
         for (int bits = 1; bits <= EDEN_MAX_TABLE_BITS; ++bits) {
@@ -185,7 +187,7 @@ int eden_destroy(eden_ctx *ctx) {
     bool ok = guard.ok;
     for (hipEvent_t e : ctx->prof_start) ok = (hipEventDestroy(e) == hipSuccess) && ok;
     for (hipEvent_t e : ctx->prof_stop) ok = (hipEventDestroy(e) == hipSuccess) && ok;
-    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->stage, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
+    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->stage, ctx->hist, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
     for (void *p : ptrs)
         if (p) ok = (hipFree(p) == hipSuccess) && ok;
     delete ctx;
@@ -201,7 +203,8 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
     const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the vector that is transformed
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
-    for (uint32_t c = 0; c < n; ++c) wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u);
+    for (uint32_t c = 0; c < n; ++c)
+        wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u || grid_q15(b_kernel[c]) != 0u);
     const Plan pl = make_plan(log2D, wide_ok);
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
@@ -316,7 +319,8 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
     const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the decoded vectors
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
-    for (uint32_t c = 0; c < n; ++c) wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u);
+    for (uint32_t c = 0; c < n; ++c)
+        wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u || grid_q15(b_kernel[c]) != 0u);
     const Plan pl = make_plan(log2D, wide_ok);
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
@@ -455,6 +459,16 @@ int eden_make_subsample_bits(eden_ctx *ctx, uint64_t seed, uint32_t client_id, u
     if (!guard.ok) return EDEN_ERR_HIP;
     const uint64_t nwords = D >= 128 ? D / 128 : 1;
     launch_hash_bits(stream_key(seed, kStreamSubsample, client_id), nwords, bits_dev, static_cast<hipStream_t>(stream));
+    return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
+}
+
+int eden_index_entropy(eden_ctx *ctx, const void *msg_dev, uint64_t d, uint32_t b_q8, double *out_dev, void *stream) {
+    if (!ctx || !msg_dev || !out_dev || d == 0 || d > ctx->d_max || !grid_q15(b_q8)) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    const uint64_t D = 1ull << ceil_log2(d);
+    launch_byte_entropy(static_cast<const uint8_t *>(msg_dev) + EDEN_HEADER_BYTES, D, ctx->hist, out_dev,
+                        static_cast<hipStream_t>(stream));
     return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
 }
 

@@ -47,12 +47,21 @@ __host__ __device__ inline uint32_t sparse_m(uint32_t b_q8) {
     const uint32_t m = b_q8 & 0xFFFFu;
     return ((b_q8 & ~0xFFFFu) == kSparseFlag && m >= 1 && m <= 63) ? m : 0;
 }
+// Uniform-grid quantizer of Sec. 4.3: the intervals [Delta (n - 1/2), Delta (n + 1/2)], Delta = (b_q8 & 0xFFFF) / 32768;
+// the index n = round(z / Delta), clipped to +-127, travels as one signed byte (what an entropy coder would shrink to
+// about H(Delta) bits); the value of an interval is its centre of mass under N(0,1).
+constexpr uint32_t kGridFlag = 0x30000u;
+constexpr int kGridMax = 127;
+__host__ __device__ inline uint32_t grid_q15(uint32_t b_q8) {
+    return ((b_q8 & ~0xFFFFu) == kGridFlag && (b_q8 & 0xFFFFu) >= 1u) ? (b_q8 & 0xFFFFu) : 0u;
+}
 __host__ __device__ inline bool budget_mixed(uint32_t b_q8) { return b_q8 == 384 || b_q8 == 640 || b_q8 == 896; }
 __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
     if (b_q8 == 128) { bits = 1; k = 2; return true; }
     if (b_q8 == 256 || b_q8 == 512 || b_q8 == 768 || b_q8 == 1024 || budget_mixed(b_q8)) {
         bits = (int)(b_q8 >> 8); k = 1; return true;
     }
+    if (grid_q15(b_q8)) { bits = 8; k = 1; return true; }
     return false;
 }
 // bytes of the first part of the payload (the floor(b)-bit indices), a multiple of 8
@@ -91,7 +100,9 @@ struct EncScratch {
     float qpos[8];          // positive centroids
     float thr2[8];          // mixed budgets: the same for I_{floor(b)+1}
     float qpos2[8];
-    unsigned pad[2];
+    float grid_inv;         // uniform grid: 1 / (Delta |x|), so that round(u * grid_inv) is the index
+    unsigned pad;
+    float grid_c[kGridMax + 1];     // uniform grid: centre of mass of the interval of index n >= 0
 };
 
 // per-message scalars of one decode
@@ -100,6 +111,7 @@ struct DecScratch {
     float deq2[16];         // mixed budgets: the same for the indices of I_{floor(b)+1}
     uint32_t flags;
     uint32_t pad[3];
+    float grid_deq[kGridMax + 1];   // uniform grid: (S / (p sqrt(D))) * centre of mass of index n >= 0
 };
 
 struct EncBatch {
@@ -310,6 +322,30 @@ __device__ inline void pack3_planes(uint32_t p0, uint32_t p1, uint32_t p2, uint3
 // the `bits`-wide code that starts `shift` bits into the 64-bit little-endian window w1:w0
 __device__ inline uint32_t code_at(uint32_t w0, uint32_t w1, uint32_t shift, int bits) {
     return __builtin_amdgcn_alignbit(w1, w0, shift) & ((1u << bits) - 1u);
+}
+
+// Centre of mass of N(0,1) on [delta (n - 1/2), delta (n + 1/2)], n >= 1; the interval of n = 127 runs to infinity
+// (Sec. 3: the optimal value of an interval; Sec. 4.3: the uniform grid).
+__device__ inline double grid_centroid(double delta, int n) {
+    const double a = delta * (n - 0.5), b = delta * (n + 0.5);
+    const bool open = n >= kGridMax;
+    const double mass = 0.5 * (erfc(a * 0.7071067811865476) - (open ? 0.0 : erfc(b * 0.7071067811865476)));
+    const double num = 0.3989422804014327 * (exp(-0.5 * a * a) - (open ? 0.0 : exp(-0.5 * b * b)));
+    return mass > 0.0 ? num / mass : a;
+}
+// index of one coordinate on the uniform grid (as a signed byte in the low 8 bits) and its contribution |u| c to
+// sum_i u_i Q_i; `ctab`: the centres of mass in LDS
+__device__ inline uint32_t quantize_grid(float u, float grid_inv, const float *ctab, float &ip) {
+    const float n = fminf(fmaxf(rintf(u * grid_inv), -(float)kGridMax), (float)kGridMax);
+    ip = fmaf(fabsf(u), ctab[(int)fabsf(n)], ip);
+    return (uint32_t)(int)n & 0xFFu;
+}
+// value of a received byte: sign(n) * table[|n|]
+__device__ inline float dequantize_grid(uint32_t byte, const float *dtab) {
+    const int n = (int)(int8_t)byte;
+    const int a = n < 0 ? -n : n;
+    const float m = dtab[a > kGridMax ? kGridMax : a];           // (a sender never writes -128)
+    return n < 0 ? -m : m;
 }
 
 // b = K + 1/2 (Sec. 4.1): the index of one coordinate, K+1 bits wide where `up` (quantized with I_{K+1}), else K

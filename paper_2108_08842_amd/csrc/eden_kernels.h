@@ -45,6 +45,7 @@ void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, uint64
 void launch_sparse_gather(const float *x, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *stage, hipStream_t st);
 void launch_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *acc, hipStream_t st);
 void launch_fill_zero(float *p, uint64_t count, hipStream_t st);
+void launch_byte_entropy(const uint8_t *bytes, uint64_t count, uint32_t *hist, double *out, hipStream_t st);
 void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
                      hipStream_t st);
 void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st);

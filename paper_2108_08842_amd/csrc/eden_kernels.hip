@@ -26,6 +26,10 @@ __device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8,
     budget_of(b_q8, bits, k);
     s->n2 = n2;
     const double norm = sqrt(n2);
+    if (grid_q15(b_q8)) {                                        // uniform grid: no table of thresholds, only the step
+        s->grid_inv = (float)(32768.0 / ((double)grid_q15(b_q8) * norm));
+        return;
+    }
     const int finer = budget_mixed(b_q8) ? bits + 1 : bits;
     for (int i = 0; i < 8; ++i) {
         s->thr[i] = (float)(tab->t[bits][i] * norm);
@@ -33,6 +37,11 @@ __device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8,
         s->thr2[i] = (float)(tab->t[finer][i] * norm);
         s->qpos2[i] = (float)tab->q[finer][i];
     }
+}
+// the centres of mass of the uniform grid's intervals, one per thread (tid < 128)
+__device__ inline void fill_grid_centroids(EncScratch *s, uint32_t b_q8, uint32_t tid) {
+    const uint32_t q15 = grid_q15(b_q8);
+    if (q15 && tid <= (uint32_t)kGridMax) s->grid_c[tid] = tid ? (float)grid_centroid((double)q15 / 32768.0, (int)tid) : 0.0f;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -134,6 +143,7 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
     constexpr int R = 1 << M;
     __shared__ double red[4];
     __shared__ float qtabs[4][16];
+    __shared__ float gtabs[4][kGridMax + 1];
     const uint32_t c = blockIdx.y;
     const uint32_t lane = lane_id();
     const uint32_t tile = blockIdx.x * 4u + wave_in_block();
@@ -184,6 +194,17 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
             wave_lds_sync();
             const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
             uint32_t *part_b = payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4;
+            if (grid_q15(b_q8)) {
+                // Sec. 4.3: index = round(z / Delta) as one byte per coordinate; a row of the tile is 64 consecutive bytes
+                float *ctab = gtabs[wave_in_block()];
+                ctab[lane] = sc->grid_c[lane];
+                ctab[64 + lane] = sc->grid_c[64 + lane];
+                wave_lds_sync();
+                const float inv = sc->grid_inv;
+                uint8_t *bytes = reinterpret_cast<uint8_t *>(payload);
+#pragma unroll
+                for (int r = 0; r < R; ++r) bytes[base + ((uint64_t)r << p) + lane] = (uint8_t)quantize_grid(v[r], inv, ctab, ip);
+            } else
             switch (b_q8) {
                 case 384u: hi_quantize_pack<R, 1, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
                 case 512u: hi_quantize_pack<R, 2, false>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
@@ -210,6 +231,7 @@ __global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *part
     for (uint32_t i = threadIdx.x; i < nparts; i += 256) s += pc[i];
     const double total = block_sum<256>(s, red);
     if (threadIdx.x == 0) fill_enc_scratch(&scratch[c], total, B.b_q8[c], tab);
+    fill_grid_centroids(&scratch[c], B.b_q8[c], threadIdx.x);
 }
 
 // Decode, first pass in wave tiles (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit
@@ -222,6 +244,7 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
                                                       const DecScratch *scratch, int narrow, float *T) {
     constexpr int R = 1 << M;
     __shared__ float table[4][32];
+    __shared__ float gtabs[4][kGridMax + 1];                     // uniform grid: dequantized centres of mass
     const uint32_t c = blockIdx.y;
     const uint32_t lane = lane_id(), wv = wave_in_block();
     const uint32_t tile = blockIdx.x * 4u + wv;
@@ -233,6 +256,7 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
     const bool i16 = narrow && b_q8 <= 256u;
     if (lane < 16) table[wv][lane] = (i16 && lane == 1) ? 1.0f : scratch[c].deq[lane];
     else if (lane < 32) table[wv][lane] = scratch[c].deq2[lane - 16];
+    if (grid_q15(b_q8)) { gtabs[wv][lane] = scratch[c].grid_deq[lane]; gtabs[wv][64 + lane] = scratch[c].grid_deq[64 + lane]; }
     wave_lds_sync();
     const float *tb = table[wv], *tb2 = table[wv] + 16;
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
@@ -260,6 +284,12 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
             const uint32_t neg = (~(w >> (lane >> 1)) & 1u) << 31;          // index 0 = negative
             v[r] = kept ? __uint_as_float(mag | neg) : 0.0f;
         }
+    } else if (grid_q15(b_q8)) {
+        // Sec. 4.3: one signed byte per coordinate, the index on the uniform grid
+        const rsrc_t rp = make_rsrc(reinterpret_cast<const uint8_t *>(payload) + base, payload_bytes - (uint32_t)base);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            v[r] = dequantize_grid((uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rp, (int)lane, (int)((uint32_t)r << p), 0), gtabs[wv]);
     } else if (budget_mixed(b_q8)) {
         // b = bits + 1/2 (Sec. 4.1): every coordinate has `bits` bits in the first part; the coordinate of each pair
         // that the MIX stream selects was quantized with the finer table and has its top bit in the second part
@@ -377,8 +407,10 @@ __global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t vali
     const uint32_t b_q8 = B.b_q8[c];
     const EncScratch *sc = &scratch[c];
     __shared__ float qtabs[4][16];
-    float *qtab = qtabs[wave_in_block()];
+    __shared__ float gtabs[4][kGridMax + 1];
+    float *qtab = qtabs[wave_in_block()], *gtab = gtabs[wave_in_block()];
     fill_qtab(qtab, sc, lane);
+    if (grid_q15(b_q8)) { gtab[lane] = sc->grid_c[lane]; gtab[64 + lane] = sc->grid_c[64 + lane]; }
     wave_lds_sync();
     float ip = 0.0f;
 #pragma unroll
@@ -401,6 +433,10 @@ __global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t vali
 #pragma unroll
                 for (int e = 0; e < 4; ++e) word |= quantize_one<2>(v[r][4 * h + e], sc, qtab, ip) << (2 * e);
                 reinterpret_cast<uint8_t *>(payload)[group] = (uint8_t)word;
+            } else if (grid_q15(b_q8)) {                          // Sec. 4.3: one byte per coordinate
+#pragma unroll
+                for (int e = 0; e < 4; ++e) word |= quantize_grid(v[r][4 * h + e], sc->grid_inv, gtab, ip) << (8 * e);
+                reinterpret_cast<uint32_t *>(payload)[group] = word;
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) word |= quantize_one<8>(v[r][4 * h + e], sc, qtab, ip) << (4 * e);
@@ -422,11 +458,13 @@ __global__ __launch_bounds__(256) void k_dec_wide_first(DecBatch B, uint64_t kee
     const int p = log2D - 3;
     const uint32_t tile = blockIdx.x * 4u + wv;
     const uint32_t base = tile * (uint32_t)kWideCols;
+    __shared__ float gtabs[4][kGridMax + 1];
+    const uint32_t b_q8 = B.b_q8[c];
     if (lane < 16) table[wv][lane] = scratch[c].deq[lane];
+    if (grid_q15(b_q8)) { gtabs[wv][lane] = scratch[c].grid_deq[lane]; gtabs[wv][64 + lane] = scratch[c].grid_deq[64 + lane]; }
     wave_lds_sync();
     const float *tb = table[wv];
     const char *payload = static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES;
-    const uint32_t b_q8 = B.b_q8[c];
     const uint32_t *bm = B.bitmap[c];
     float v[kWideRows][8];
 #pragma unroll
@@ -440,14 +478,16 @@ __global__ __launch_bounds__(256) void k_dec_wide_first(DecBatch B, uint64_t kee
             uint32_t word;
             if (b_q8 == 256u) word = (uint32_t)reinterpret_cast<const uint8_t *>(payload)[group >> 1] >> (4u * (lane & 1u));
             else if (b_q8 == 512u) word = reinterpret_cast<const uint8_t *>(payload)[group];
+            else if (grid_q15(b_q8)) word = reinterpret_cast<const uint32_t *>(payload)[group];
             else word = reinterpret_cast<const uint16_t *>(payload)[group];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                uint32_t idx;
-                if (b_q8 == 256u) idx = (word >> e) & 1u;
-                else if (b_q8 == 512u) idx = (word >> (2 * e)) & 3u;
-                else idx = (word >> (4 * e)) & 15u;
-                v[r][4 * h + e] = here ? tb[idx] : 0.0f;
+                float val;
+                if (b_q8 == 256u) val = tb[(word >> e) & 1u];
+                else if (b_q8 == 512u) val = tb[(word >> (2 * e)) & 3u];
+                else if (grid_q15(b_q8)) val = dequantize_grid((word >> (8 * e)) & 0xFFu, gtabs[wv]);
+                else val = tb[(word >> (4 * e)) & 15u];
+                v[r][4 * h + e] = here ? val : 0.0f;
             }
         }
     }
@@ -553,11 +593,18 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t hdr_d, 
     if (threadIdx.x == 0) n2_shared = n2_t0;
     __syncthreads();
     const double n2 = n2_shared;
-    const bool valid = (n2 > 0.0) && (n2 < INFINITY);
+    __shared__ double ip_shared;
+    if (threadIdx.x == 0) ip_shared = total;
+    __syncthreads();
+    // <R(x),Q> = 0 can only happen on a uniform grid so coarse that every coordinate falls into the interval around 0
+    const bool valid = (n2 > 0.0) && (n2 < INFINITY) && (ip_shared > 0.0);
     const uint32_t b_q8 = B.b_q8[c];
     if (!valid) {
         uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-        const uint64_t nw = ((uint64_t)payload_words_b1 * b_q8) >> 8;      // payload words for this budget
+        int bits, k;
+        budget_of(b_q8, bits, k);
+        const uint64_t D = 32ull * payload_words_b1;
+        const uint64_t nw = (payload_a_bytes(D, bits, k) + payload_b_bytes(D, b_q8)) / 4;
         for (uint64_t i = threadIdx.x; i < nw; i += 256) payload[i] = 0u;
     }
     if (threadIdx.x == 0) {
@@ -570,7 +617,7 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t hdr_d, 
             h.status = 0;
         } else {
             h.IP = 0.0; h.S = 0.0;
-            h.status = (n2 == 0.0) ? EDEN_DEV_ZERO_VECTOR : EDEN_DEV_NONFINITE;
+            h.status = (n2 >= 0.0 && n2 < INFINITY) ? EDEN_DEV_ZERO_VECTOR : EDEN_DEV_NONFINITE;
             atomicOr(dev_status, h.status);
         }
         *static_cast<MsgHeader *>(B.msg[c]) = h;
@@ -624,6 +671,14 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
         if (l < 2 * H) q = (l >= H) ? tab->q[tb][l - H] : -tab->q[tb][H - 1 - l];
         if (lane < 16) out->deq[l] = (float)(coef * q);
         else out->deq2[l] = (float)(coef * q);
+    }
+    if (grid_q15(b_q8)) {                                        // uniform grid: the centres of mass, two per lane
+        const double delta = (double)grid_q15(b_q8) / 32768.0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int n = (int)lane + 64 * h;
+            out->grid_deq[n] = n ? (float)(coef * grid_centroid(delta, n)) : 0.0f;
+        }
     }
     if (lane == 0) {
         out->flags = flags;
@@ -773,6 +828,24 @@ __global__ __launch_bounds__(256) void k_fill_zero(float *p, uint64_t count) {
     if (i < count) p[i] = 0.0f;
 }
 
+// Experiment helper (Sec. 4.3): histogram of the one-byte indices of a uniform-grid message and its entropy
+// -sum f log2 f in bits per coordinate, what an ideal entropy coder would spend.
+__global__ __launch_bounds__(256) void k_byte_histogram(const uint8_t *bytes, uint64_t count, uint32_t *hist) {
+    __shared__ uint32_t local[256];
+    local[threadIdx.x] = 0;
+    __syncthreads();
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < count; i += (uint64_t)gridDim.x * 256u)
+        atomicAdd(&local[bytes[i]], 1u);
+    __syncthreads();
+    if (local[threadIdx.x]) atomicAdd(&hist[threadIdx.x], local[threadIdx.x]);
+}
+__global__ __launch_bounds__(256) void k_histogram_entropy(const uint32_t *hist, uint64_t count, double *out) {
+    __shared__ double red[4];
+    const double f = (double)hist[threadIdx.x] / (double)count;
+    const double h = block_sum<256>(f > 0.0 ? -f * log2(f) : 0.0, red);
+    if (threadIdx.x == 0) out[0] = h;
+}
+
 // Experiment helper: sum_i (a_i - b_i)^2 and sum_i a_i^2 in double, the two terms of the (v)NMSE definitions
 // (Sec. 2.1: NMSE; Sec. 2.3: vNMSE).  Per-workgroup partials, then one workgroup adds them in index order.
 __global__ __launch_bounds__(256) void k_sq_error(const float *a, const float *b, uint64_t d, double *partials) {
@@ -838,17 +911,22 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
     const double n2t = block_sum<256>(n2p, red);
     const uint32_t b_q8 = B.b_q8[c];
     if (threadIdx.x == 0) fill_enc_scratch(&s, n2t, b_q8, tab);
+    fill_grid_centroids(&s, b_q8, threadIdx.x);
     fwht_lds(buf, D);                                          // includes the barriers that publish `s`
     int bits, k;
     budget_of(b_q8, bits, k);
     const int H = 1 << (bits - 1);
     const double n2 = s.n2;
-    const bool valid = (n2 > 0.0) && (n2 < INFINITY);
     float ip = 0.0f;
     const bool mix = budget_mixed(b_q8);                       // b = k + 1/2: one coordinate of every pair uses I_{k+1}
     const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
+    const bool grid = grid_q15(b_q8) != 0u;                    // Sec. 4.3: index = round(z / Delta), one byte
     for (uint32_t i = threadIdx.x; i < D; i += 256) {
         const float u = buf[i];
+        if (grid) {
+            code[i] = (uint8_t)quantize_grid(u, s.grid_inv, s.grid_c, ip);
+            continue;
+        }
         const float a = fabsf(u);
         const uint32_t g = i >> 1;
         const bool up = mix && ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u));
@@ -860,7 +938,13 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
         const uint32_t neg = __float_as_uint(u) >> 31;
         code[i] = (uint8_t)(neg ? (uint32_t)(Hu - 1) - mag : (uint32_t)Hu + mag);
     }
-    const double ipt = block_sum<256>((double)ip, red);        // barriers inside also publish `code`
+    const double ipt_t0 = block_sum<256>((double)ip, red);     // barriers inside also publish `code`
+    __shared__ double ip_shared;
+    if (threadIdx.x == 0) ip_shared = ipt_t0;
+    __syncthreads();
+    const double ipt = ip_shared;
+    // (a uniform grid so coarse that every coordinate falls into the interval around 0 leaves <R(x),Q> = 0)
+    const bool valid = (n2 > 0.0) && (n2 < INFINITY) && (ipt > 0.0);
     uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     const uint32_t nsent = D / (uint32_t)k;                    // transmitted indices
     const uint32_t nwords = 2u * ((nsent * (uint32_t)bits + 63u) / 64u);
@@ -899,7 +983,7 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
             h.status = 0;
         } else {
             h.IP = 0.0; h.S = 0.0;
-            h.status = (n2 == 0.0) ? EDEN_DEV_ZERO_VECTOR : EDEN_DEV_NONFINITE;
+            h.status = (n2 >= 0.0 && n2 < INFINITY) ? EDEN_DEV_ZERO_VECTOR : EDEN_DEV_NONFINITE;
             atomicOr(dev_status, h.status);
         }
         *static_cast<MsgHeader *>(B.msg[c]) = h;
@@ -942,7 +1026,7 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
             const uint32_t bitpos = j * (uint32_t)bits, w0 = bitpos >> 5;
             const uint32_t next = (w0 + 1u < nwords) ? payload[w0 + 1u] : 0u;       // a 3-bit index may straddle two words
             const uint32_t idx = code_at(payload[w0], next, bitpos & 31u, bits);
-            float val = s.deq[idx];
+            float val = grid_q15(b_q8) ? dequantize_grid(idx, s.grid_deq) : s.deq[idx & 15u];
             if (mix) {
                 const uint32_t g = i >> 1;
                 if ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u))
@@ -1079,6 +1163,14 @@ void launch_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t 
 }
 void launch_fill_zero(float *p, uint64_t count, hipStream_t st) {
     hipLaunchKernelGGL(k_fill_zero, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st, p, count);
+}
+void launch_byte_entropy(const uint8_t *bytes, uint64_t count, uint32_t *hist, double *out, hipStream_t st) {
+    launch_fill_zero(reinterpret_cast<float *>(hist), 256, st);          // 256 words of zero bits
+    uint32_t blocks = (uint32_t)((count + 4095) / 4096);
+    if (blocks > 2048u) blocks = 2048u;
+    if (blocks < 1u) blocks = 1u;
+    hipLaunchKernelGGL(k_byte_histogram, dim3(blocks), dim3(256), 0, st, bytes, count, hist);
+    hipLaunchKernelGGL(k_histogram_entropy, dim3(1), dim3(256), 0, st, hist, count, out);
 }
 void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
                      hipStream_t st) {

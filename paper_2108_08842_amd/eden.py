@@ -29,9 +29,16 @@ EXPORTS = [
     "eden_create", "eden_destroy", "eden_message_bytes", "eden_encode", "eden_decode_accumulate",
     "eden_finalize_mean", "eden_last_device_status", "eden_make_loss_bitmap", "eden_make_sign_bits",
     "eden_make_subsample_bits", "eden_get_tables", "eden_strerror", "eden_profile_enable", "eden_profile_collect",
-    "eden_kernel_name", "eden_sq_error",
+    "eden_kernel_name", "eden_sq_error", "eden_index_entropy",
 ]
 B_HALF_PRE = 0x10080     # b = 1/2 with the sparsification before the rotation (EDEN_B_HALF_PRE)
+
+
+def B_GRID(delta: float) -> int:
+    """Uniform-grid quantizer of Sec. 4.3 with step `delta` (0 < delta < 2): EDEN_B_GRID(round(delta * 32768))."""
+    q = int(round(delta * 32768))
+    assert 1 <= q <= 65535
+    return 0x30000 | q
 
 
 def B_SPARSE(m: int) -> int:
@@ -94,6 +101,8 @@ def lib():
     L.eden_kernel_name.restype = ctypes.c_char_p
     L.eden_sq_error.argtypes = [vp, vp, vp, u64, vp, vp]
     L.eden_sq_error.restype = ci
+    L.eden_index_entropy.argtypes = [vp, vp, u64, u32, vp, vp]
+    L.eden_index_entropy.restype = ci
     _lib = L
     return L
 
@@ -239,6 +248,16 @@ class Context:
                                          ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
         if rc != OK:
             raise EdenError(rc, "eden_make_loss_bitmap")
+        return out
+
+    def index_entropy(self, msg, d: int, b_q8: int, stream=None):
+        """-> device tensor of 1 double: empirical entropy (bits per coordinate) of a uniform-grid message."""
+        import torch
+        out = torch.empty(1, dtype=torch.float64, device=msg.device)
+        rc = lib().eden_index_entropy(self._h, ctypes.c_void_p(msg.data_ptr()), d, b_q8, ctypes.c_void_p(out.data_ptr()),
+                                      _stream_ptr(stream))
+        if rc != OK:
+            raise EdenError(rc, "eden_index_entropy")
         return out
 
     def sq_error(self, a, b, out=None, stream=None):

@@ -39,6 +39,25 @@ def theory_sparse(m: int, d: int) -> float:
     return (1.0 + (1.0 / expected_q2(1) - 1.0) * kept / padded) / p - 1.0
 
 
+def theory_grid(delta: float):
+    """Uniform grid of Sec. 4.3 with step delta: (asymptotic vNMSE 1/E[Q^2] - 1, entropy of the indices in bits), from
+    the interval probabilities and centres of mass under N(0,1)."""
+    cdf = lambda v: 0.5 * math.erfc(-v / math.sqrt(2.0))
+    pdf = lambda v: math.exp(-0.5 * v * v) / math.sqrt(2.0 * math.pi)
+    eq2, ent = 0.0, 0.0
+    n = 0
+    while delta * (n - 0.5) < 8.5:
+        a, b = delta * (n - 0.5), delta * (n + 0.5)
+        p = cdf(b) - cdf(a) if n == 0 else 0.5 * (math.erfc(a / math.sqrt(2.0)) - math.erfc(b / math.sqrt(2.0)))
+        if p > 0.0:
+            c = (pdf(a) - pdf(b)) / p
+            w = 1.0 if n == 0 else 2.0                  # the interval of -n mirrors the one of n
+            eq2 += w * p * c * c
+            ent -= w * p * math.log2(p)
+        n += 1
+    return 1.0 / eq2 - 1.0, ent
+
+
 def theory_vnmse(b: float, keep: float = 1.0) -> float:
     """Asymptotic vNMSE for budget b (0.5, an integer >= 1, or an integer + 1/2) when a fraction `keep` of the
     packets arrives.  b = k + 1/2 mixes the two quantizers half and half (Sec. 4.1: 0.317 at b = 1.5)."""
@@ -133,6 +152,8 @@ def main(argv=None):
     ap.add_argument("--loss", type=float, default=0.0, help="fraction of packets dropped at the receiver")
     ap.add_argument("--pre-rotation", action="store_true",
                     help="b = 0.5 sparsifies before the rotation (Sec. 4.1, the paper's default) instead of after it")
+    ap.add_argument("--grid", type=float, nargs="*", default=[],
+                    help="steps Delta of the uniform-grid quantizer (Sec. 4.3) to measure as well, e.g. 0.5224")
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args(argv)
     assert torch.cuda.is_available(), "this experiment runs on the GPU"
@@ -163,6 +184,14 @@ def main(argv=None):
                     nm = measure_nmse(ctx, xs, [b_q8] * args.senders, args.seed + 1)
                     line += f" {nm:9.5f} {th / args.senders:8.5f}"
                 print(line, flush=True)
+            for delta in args.grid:
+                b_q8 = eden.B_GRID(delta)
+                v, se = measure_vnmse(ctx, x, b_q8, trials, args.seed, drop_q32)
+                th, ent = theory_grid(delta)
+                msg = ctx.encode([x], [0], [b_q8], args.seed)[0]
+                h = float(ctx.index_entropy(msg, d, b_q8)[0])
+                print(f"{dist:11s} {d:9d} grid Delta={delta:g}: vNMSE {v:.6f} +- {se:.6f} (theory {th:.6f}), "
+                      f"entropy {h:.4f} bits (theory {ent:.4f})", flush=True)
 
 
 if __name__ == "__main__":

@@ -51,6 +51,8 @@ def check_encode(x: np.ndarray, seed: int, client: int, b_q8: int, gpu_msg: o.Me
     assert abs(gpu_msg.N2 - ref.N2) <= 1e-12 * ref.N2
     if o.pre_rotation(b_q8) or o.sparse_m(b_q8):
         b_q8 = 256          # the trace is that of the 1-bit message of the sparsified vector (Sec. 4.1)
+    if o.grid_delta(b_q8):
+        return _check_encode_grid(ref, tr, b_q8, gpu_msg, stats)
     bits, _ = o.budget(b_q8)
     thresholds, centroids = o.tables(bits)
     D = tr.z.size
@@ -97,6 +99,29 @@ def check_encode(x: np.ndarray, seed: int, client: int, b_q8: int, gpu_msg: o.Me
     assert abs(gpu_msg.IP - ip_ref) <= SCALE_RTOL * ip_ref, (gpu_msg.IP, ip_ref, ref.IP)
     s_ref = ref.N2 / ip_ref
     assert abs(gpu_msg.S - s_ref) <= SCALE_RTOL * s_ref
+
+
+def _check_encode_grid(ref, tr, b_q8, gpu_msg, stats):
+    """Uniform grid (Sec. 4.3): byte i = round(z_i / Delta); the boundaries are Delta (n + 1/2)."""
+    delta = o.grid_delta(b_q8)
+    D = tr.z.size
+    raw = np.frombuffer(gpu_msg.payload.tobytes(), dtype=np.int8)
+    assert not raw[D:].any()
+    got = raw[:D].astype(np.int64)
+    want = tr.idx
+    bad = np.flatnonzero(got != want)
+    stats.coords += D
+    stats.mismatches += bad.size
+    if bad.size:
+        assert np.all(np.abs(got[bad] - want[bad]) == 1), "index differs by more than one interval"
+        dist = np.abs(tr.z[bad] - delta * (np.minimum(got[bad], want[bad]) + 0.5))
+        stats.worst_boundary_distance = max(stats.worst_boundary_distance, float(dist.max()))
+        assert dist.max() <= INDEX_BOUNDARY_TOL, f"index mismatch {dist.max():.3e} away from its boundary"
+    Q = np.sign(got) * o.grid_centroids(delta)[np.abs(got)]
+    y = tr.z * (math.sqrt(ref.N2) / math.sqrt(D))
+    ip_ref = float(np.dot(y, Q))
+    assert abs(gpu_msg.IP - ip_ref) <= SCALE_RTOL * ip_ref, (gpu_msg.IP, ip_ref, ref.IP)
+    assert abs(gpu_msg.S - ref.N2 / ip_ref) <= SCALE_RTOL * ref.N2 / ip_ref
 
 
 POOL = EncodeParity()        # every case of the session

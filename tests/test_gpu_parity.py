@@ -268,6 +268,19 @@ def test_sparse_budgets_m_of_64(ctx, d, m):
     assert eden.message_bytes(d, B) == o.message_bytes(d, B)
 
 
+@pytest.mark.parametrize("d", [1, 70, 4096, 5000, 70_000, 300_000, (1 << 20) + 1, 2_500_000])
+def test_uniform_grid_budgets(ctx, d):
+    # Sec. 4.3: index = round(z / Delta) in one byte; Delta_3 = 0.5224 (3 bits of entropy), a fine and a coarse grid
+    from paper_2108_08842_amd import eden
+    budgets = [eden.B_GRID(0.5224), eden.B_GRID(0.1), eden.B_GRID(1.5), 512]
+    w = synth.Workload("t", 4, d, budgets, 1700 + d % 1000, "normal_outliers")
+    xs = [synth.client_vector(w, c) for c in range(4)]
+    _run_case(ctx, xs, [1, 2, 3, 4], w.b_q8, w.seed)
+    if d >= (1 << 14):
+        _run_case(ctx, xs, [1, 2, 3, 4], w.b_q8, w.seed + 1, drop_q32=int(0.2 * 2 ** 32), also_oracle_msgs=False)
+    assert eden.message_bytes(d, budgets[0]) == o.message_bytes(d, budgets[0])
+
+
 def test_random_shapes_and_budgets(ctx):
     # 60 seeded random cases: dimension (log-uniform up to 2^18 + tail), number of senders, any supported budget
     # per sender, sometimes lost packets, sometimes the sparsification before the rotation

@@ -81,6 +81,29 @@ def test_vnmse_of_sparse_budgets(ctx):
     assert abs(vnmse.theory_sparse(4, d) - (math.pi / 2 * 16 - 1)) < 1e-12
 
 
+def test_uniform_grid_vnmse_and_entropy(ctx):
+    # Sec. 4.3: Delta_3 = 0.5224 gives 3 bits of entropy and vNMSE 0.022741
+    from paper_2108_08842_amd import eden, vnmse
+    th, ent = vnmse.theory_grid(0.5224)
+    assert abs(th - 0.022741) < 2e-6 and abs(ent - 3.0) < 2e-3
+    d = 1 << 17
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(16)
+    x = vnmse.draw("lognormal", d, gen, torch.device("cuda:0"))
+    B = eden.B_GRID(0.5224)
+    v, se = vnmse.measure_vnmse(ctx, x, B, 16, seed=8)
+    msg = ctx.encode([x], [0], [B], 8)[0]
+    h = float(ctx.index_entropy(msg, d, B)[0])
+    print(f"grid 0.5224: vNMSE {v:.6f} +- {se:.6f} (0.022741), entropy {h:.4f} bits (3.0)", flush=True)
+    assert abs(v - 0.022741) <= 5 * se + 0.02 * 0.022741
+    assert abs(h - 3.0) < 0.02
+    # the entropy kernel against numpy on the same bytes
+    raw = msg.cpu().numpy()[64:64 + d]
+    counts = np.bincount(raw, minlength=256).astype(np.float64)
+    f = counts[counts > 0] / d
+    assert abs(h - float(-(f * np.log2(f)).sum())) < 1e-12
+
+
 def test_vnmse_with_packet_loss(ctx):
     from paper_2108_08842_amd import vnmse
     d = 1 << 18                                                  # 256 packets: the arrived fraction is close to 0.9
