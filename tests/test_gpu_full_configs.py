@@ -67,6 +67,47 @@ def test_config4_full_size():
     ctx.close()
 
 
+@pytest.mark.timeout(600)
+def test_every_budget_at_the_headline_size():
+    """d = 11,173,962 (D = 2^24: the 10-bit workgroup tile with its two exchange halves), one sender per budget kind,
+    every sender checked coordinate by coordinate against the oracle, then decoded with 10% of the packets lost."""
+    from paper_2108_08842_amd import eden
+    d = synth.config(4).d
+    groups = [[128, 384, 512, 640, 768, 896, 1024, eden.B_GRID(0.5224)],      # one call: same transform dimension
+              [eden.B_HALF_PRE, eden.B_HALF_PRE],
+              [eden.B_SPARSE(6), eden.B_SPARSE(45)]]
+    ctx = eden.Context(d_max=d, n_max=8, device=0)
+    for gi, budgets in enumerate(groups):
+        n = len(budgets)
+        w = synth.Workload("all_budgets", n, d, budgets, 60 + gi, "layers")
+        xs = [synth.client_vector(w, c) for c in range(n)]
+        ids = list(range(20, 20 + n))
+        print(f"headline size, budgets {budgets}", flush=True)
+        msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], ids, budgets, w.seed)
+        assert ctx.last_device_status() == 0
+        stats = parity.EncodeParity()
+        om = [parity.to_oracle_message(m) for m in msgs]
+        for c in range(n):
+            parity.check_encode(xs[c], w.seed, ids[c], budgets[c], om[c], stats)
+        parity.finish_encode(stats)
+        print("encode:", stats, flush=True)
+        # packets refer to the transformed vector; the m-of-64 senders have their own dimensions
+        if o.sparse_m(budgets[0]):
+            Ds = [o.padded_dim(o.sparse_m(b) * ((d + 63) // 64)) for b in budgets]
+        else:
+            Ds = [o.padded_dim((d + 1) // 2 if o.pre_rotation(budgets[0]) else d)] * n
+        bm = [ctx.make_loss_bitmap(w.seed, ids[c], Ds[c], int(0.1 * 2 ** 32)) for c in range(n)]
+        acc = torch.zeros(d, device="cuda")
+        ctx.decode_accumulate(msgs, ids, budgets, d, w.seed, acc, bm)
+        got = ctx.finalize_mean(acc, n).cpu().numpy()
+        want = o.decode_mean(om, d, [b.cpu().numpy().view(np.uint32) for b in bm])
+        err = parity.rel_l2(got, want)
+        print(f"decode with 10% loss: rel L2 {err:.2e}", flush=True)
+        assert err <= parity.MEAN_REL_L2
+        assert ctx.last_device_status() == 0
+    ctx.close()
+
+
 def _sampled_rows_check(x64, seed, client, idx_gpu_at, samples, thresholds):
     """Indices of single coordinates computed one by one: z_i = sqrt(D)/|x| * D^-1/2 * sum_j H[i][j] s_j x_j."""
     D = o.padded_dim(x64.size)
