@@ -325,32 +325,44 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
 // `load_elems` were not written by the pass before (encode: zero padding) and read as zero; elements at or above
 // `store_elems` are not read by the pass after (decode: they end in the padding) and are not written.  A tile
 // that lies wholly beyond either bound has nothing to do.
-template <int M>
+// TPW neighbouring column blocks per workgroup: the loads of the next one are issued into the registers that each
+// half of the exchange has just written to LDS (see k_enc_hix_last).
+template <int M, int TPW>
 __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D, uint64_t load_elems, uint64_t store_elems) {
     using X = HiX<M>;
     __shared__ float lds[X::LDS_FLOATS];
     constexpr int p = kHixP;
-    const uint64_t base = hix_base<M>(blockIdx.x, p);
-    const uint64_t block_start = base >> (p + M) << (p + M);
+    const uint32_t tile0 = blockIdx.x * TPW;                     // the TPW tiles lie in the same 2^(p+M) block
+    const uint64_t base0 = hix_base<M>(tile0, p);
+    const uint64_t block_start = base0 >> (p + M) << (p + M);
     if (block_start >= load_elems || block_start >= store_elems) return;     // same decision in the whole workgroup
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
     const rsrc_t rl = make_rsrc(T + ((size_t)blockIdx.y << log2D), (uint32_t)(load_elems * 4));
     const rsrc_t rs = make_rsrc(T + ((size_t)blockIdx.y << log2D), (uint32_t)(store_elems * 4));
-    const uint32_t base_off = (uint32_t)base * 4u;
     const uint32_t off1 = ((g << p) + col) * 4u;
     const uint32_t off2 = (((g * X::RHL * X::RL) << p) + col) * 4u;
     float v[64];
 #pragma unroll
-    for (int r = 0; r < 64; ++r) v[r] = buf_load(rl, off1, base_off + (((uint32_t)X::RL * r) << (p + 2)));
-    fwht_regs<64>(v);
-    float out[X::RP];
-    hix_exchange<M, 0>(v, lds, out);
+    for (int r = 0; r < 64; ++r) v[r] = buf_load(rl, off1, (uint32_t)base0 * 4u + (((uint32_t)X::RL * r) << (p + 2)));
 #pragma unroll
-    for (int s = 0; s < X::RP; ++s) buf_store(rs, off2, base_off + (hix_row2<M>(0, 0, s) << (p + 2)), out[s]);
-    if constexpr (X::PH == 2) {
-        hix_exchange<M, 1>(v, lds, out);
+    for (int k = 0; k < TPW; ++k) {
+        const uint32_t base_off = (uint32_t)hix_base<M>(tile0 + k, p) * 4u;
+        const uint32_t next_off = (uint32_t)hix_base<M>(tile0 + k + 1, p) * 4u;
+        fwht_regs<64>(v);
+        float out[X::RP];
 #pragma unroll
-        for (int s = 0; s < X::RP; ++s) buf_store(rs, off2, base_off + (hix_row2<M>(0, 1, s) << (p + 2)), out[s]);
+        for (int ph = 0; ph < X::PH; ++ph) {
+            if (ph == 0) hix_exchange_write<M, 0>(v, lds);
+            else hix_exchange_write<M, X::PH - 1>(v, lds);
+            if (k + 1 < TPW) {
+#pragma unroll
+                for (int r = ph * X::RP; r < (ph + 1) * X::RP; ++r)
+                    v[r] = buf_load(rl, off1, next_off + (((uint32_t)X::RL * r) << (p + 2)));
+            }
+            hix_exchange_read<M>(lds, out);
+#pragma unroll
+            for (int s = 0; s < X::RP; ++s) buf_store(rs, off2, base_off + (hix_row2<M>(0, ph, s) << (p + 2)), out[s]);
+        }
     }
 }
 
@@ -678,8 +690,9 @@ uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, i
     return grid.x;
 }
 void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems, uint64_t store_elems, hipStream_t st) {
-    dim3 grid(hix_tiles(M, log2D), n);
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_hix_mid<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D, load_elems, store_elems));
+    dim3 grid(hix_tiles(M, log2D) / 2, n);                       // 2^(p-5) = 512 tiles per block of 2^(p+M): pairs never straddle
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_hix_mid<MM, 2>), grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D,
+                                          load_elems, store_elems));
 }
 void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
                           const DecScratch *scratch, int narrow, float *T, hipStream_t st) {
