@@ -63,9 +63,9 @@
  *     padded with virtual zeros) exactly the m with the smallest 16-bit keys are kept, ties broken by position;
  *     key of coordinate i = bits 16 (i & 3) .. +15 of word (i >> 2) of the SPARSE stream (stream 4).  The
  *     m ceil(d/64) kept values, in order, are encoded with b = 1 (unscaled: the method is scale equivariant), and
- *     the decoder multiplies by 64/m and puts them back.  Senders are processed one at a time (their kept sets
- *     differ); a call uses such budgets for all senders or for none; packets of a received-packet bitmap refer
- *     to the kept vector.  The first call with such a budget allocates d_max + 64 floats in the context.
+ *     the decoder multiplies by 64/m and puts them back.  Senders that share m are processed in batches, others
+ *     one at a time; a call uses such budgets for all senders or for none; packets of a received-packet bitmap refer
+ *     to the kept vector.  The first call that has to go sender by sender allocates d_max + 64 floats in the context.
  *     EDEN_B_GRID(q) (0x30000 | q, 1 <= q <= 65535): the uniform-grid quantizer of Sec. 4.3 with
  *     Delta = q / 32768: index n = round(z / Delta) (ties to even), clipped to +-127 and sent as one signed byte
  *     per coordinate (the payload is D bytes; an entropy coder would bring it to about H(Delta) bits per

@@ -297,7 +297,34 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
     std::vector<uint32_t> ones(n, 256u);                         // the sparsifying budgets quantize with b = 1
     if (mode == 0) return encode_range(ctx, x_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, msgs_dev, st);
     if (mode == 1) return encode_range(ctx, x_dev, client_ids, ones.data(), b_q8, n, d, 1, d, seed, msgs_dev, st);
-    // b = m/64: sender by sender, the kept coordinates packed into the staging vector, then the 1-bit method on it
+    // b = m/64.  Senders that share m and a multi-pass size: a launch gathers the kept coordinates of a batch into the
+    // workspace slots, and the 1-bit method then runs on the slots in place (a first-pass workgroup has read a tile
+    // before it writes it).
+    const uint32_t m0 = sparse_m(b_q8[0]);
+    const uint64_t dk0 = (uint64_t)m0 * ((d + 63) / 64);
+    bool same_m = ctx->T != nullptr && ceil_log2(dk0) > kLoBits;
+    for (uint32_t c = 0; c < n; ++c) same_m = same_m && sparse_m(b_q8[c]) == m0;
+    if (same_m) {
+        const int log2Dk = ceil_log2(dk0);
+        for (uint32_t first = 0; first < n; first += ctx->slots) {
+            const uint32_t nb = (n - first < ctx->slots) ? n - first : ctx->slots;
+            EncBatch B;
+            std::memset(&B, 0, sizeof(B));
+            const float *slots_x[kMaxBatch];
+            for (uint32_t i = 0; i < nb; ++i) {
+                B.x[i] = x_dev[first + i];
+                B.client[i] = client_ids[first + i];
+                slots_x[i] = ctx->T + ((size_t)i << log2Dk);
+            }
+            launch_sparse_gather_batch(B, nb, d, m0, seed, ctx->T, log2Dk, st);
+            if (!launch_ok()) return EDEN_ERR_HIP;
+            const int rc = encode_range(ctx, slots_x, &client_ids[first], ones.data(), &b_q8[first], nb, dk0, 0, d, seed,
+                                        &msgs_dev[first], st);
+            if (rc != EDEN_OK) return rc;
+        }
+        return EDEN_OK;
+    }
+    // otherwise sender by sender: the kept coordinates packed into the staging vector, then the 1-bit method on it
     if (!ensure_stage(ctx)) return EDEN_ERR_HIP;
     for (uint32_t c = 0; c < n; ++c) {
         const uint32_t m = sparse_m(b_q8[c]);
@@ -312,11 +339,12 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
 }
 
 // Decodes n messages whose transformed vectors all have the same dimension and adds them to acc (see encode_range
-// for the arguments; `d_src` is the length of acc, `bitmaps` may be null).
+// for the arguments; `d_src` is the length of acc, `bitmaps` may be null).  pre == 2 (multi-pass sizes only, n at
+// most one launch): nothing is added to acc; every sender's decoded vector is left in its workspace slot.
 static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids, const uint32_t *b_kernel,
                         const uint32_t *b_hdr, uint32_t n, uint64_t d_src, int pre, uint64_t hdr_d, uint64_t seed,
                         const uint32_t *const *bitmaps, float *acc_dev, hipStream_t st) {
-    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the decoded vectors
+    const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vectors
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
     for (uint32_t c = 0; c < n; ++c)
@@ -340,7 +368,7 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
         } else {
             // Strided passes first (every sender on its own), contiguous pass last (sums the senders in registers
             // and touches acc once).  With a single strided pass the workspace of a b <= 1 sender holds int16.
-            const int narrow = (pl.nhi == 1) ? 1 : 0;
+            const int narrow = (pl.nhi == 1 && pre != 2) ? 1 : 0;
             {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
                 launch_dec_prepare(B, nb, hdr_d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
@@ -388,8 +416,30 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
     std::vector<uint32_t> ones(n, 256u);
     if (mode == 0) return decode_range(ctx, msgs_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, recv_bitmaps_dev, acc_dev, st);
     if (mode == 1) return decode_range(ctx, msgs_dev, client_ids, ones.data(), b_q8, n, d, 1, d, seed, recv_bitmaps_dev, acc_dev, st);
-    // b = m/64: sender by sender (the kept coordinates differ), the 1-bit decode into the staging vector (the factor
-    // 64/m is folded into the dequantization), then the values go back to their coordinates of acc
+    // b = m/64 (the factor 64/m is folded into the dequantization).  Senders that share m and a multi-pass size: a batch
+    // is decoded without summing, every sender into its own workspace slot, and one launch adds the values to the
+    // coordinates of acc they were taken from.
+    const uint32_t m0 = sparse_m(b_q8[0]);
+    const uint64_t dk0 = (uint64_t)m0 * ((d + 63) / 64);
+    bool same_m = ctx->T != nullptr && ceil_log2(dk0) > kLoBits;
+    for (uint32_t c = 0; c < n; ++c) same_m = same_m && sparse_m(b_q8[c]) == m0;
+    if (same_m) {
+        const int log2Dk = ceil_log2(dk0);
+        for (uint32_t first = 0; first < n; first += ctx->slots) {
+            const uint32_t nb = (n - first < ctx->slots) ? n - first : ctx->slots;
+            const int rc = decode_range(ctx, &msgs_dev[first], &client_ids[first], ones.data(), &b_q8[first], nb, dk0, 2, d, seed,
+                                        recv_bitmaps_dev ? &recv_bitmaps_dev[first] : nullptr, acc_dev, st);
+            if (rc != EDEN_OK) return rc;
+            DecBatch B;
+            std::memset(&B, 0, sizeof(B));
+            for (uint32_t i = 0; i < nb; ++i) B.client[i] = client_ids[first + i];
+            launch_sparse_scatter_batch(B, nb, d, m0, seed, ctx->T, log2Dk, acc_dev, st);
+            if (!launch_ok()) return EDEN_ERR_HIP;
+        }
+        return EDEN_OK;
+    }
+    // otherwise sender by sender (the kept coordinates differ): the 1-bit decode into the staging vector, then the values
+    // go back to their coordinates of acc
     if (!ensure_stage(ctx)) return EDEN_ERR_HIP;
     for (uint32_t c = 0; c < n; ++c) {
         const uint32_t m = sparse_m(b_q8[c]);

@@ -34,7 +34,9 @@ void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t hdr_d, int log2D
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st);
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                          const DecScratch *scratch, int narrow, float *T, hipStream_t st);
-void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const float *T,
+// pre: 0 = sum the senders into acc; 1 = the same with the pairs scatter of EDEN_B_HALF_PRE; 2 = no sum, every sender's
+// decoded vector goes back into its own workspace slot (fp32, `narrow` must be 0)
+void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st);
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st);
 void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
@@ -44,6 +46,10 @@ void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, uint64
 // b = m/64: the kept coordinates of x packed into `stage` (m per block of 64), and added back from it into acc
 void launch_sparse_gather(const float *x, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *stage, hipStream_t st);
 void launch_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *acc, hipStream_t st);
+void launch_sparse_gather_batch(const EncBatch &B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed, float *T, int log2Dk,
+                                hipStream_t st);
+void launch_sparse_scatter_batch(const DecBatch &B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed, const float *T, int log2Dk,
+                                 float *acc, hipStream_t st);
 void launch_fill_zero(float *p, uint64_t count, hipStream_t st);
 void launch_byte_entropy(const uint8_t *bytes, uint64_t count, uint32_t *hist, double *out, hipStream_t st);
 void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
@@ -63,7 +69,7 @@ uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int pr
                                double *partials, uint32_t partial_stride, hipStream_t st);
 // `resident`: workgroups of the kernel the device holds at once (2 per CU); `partial`: room for `partial_tiles`
 // tiles of 2^14 floats, used when tiles are split over several workgroups by sender
-void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const float *T,
+void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
                           const DecScratch *scratch, int narrow, float *acc, uint32_t resident, float *partial,
                           uint32_t partial_tiles, hipStream_t st);
 

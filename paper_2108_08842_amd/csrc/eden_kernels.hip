@@ -698,13 +698,15 @@ __global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t hdr_d, 
 // `pre` (b = 1/2 with the sparsification first, Sec. 4.1): the decoded vector has dimension ceil(d_src/2) and value g
 // of sender c belongs at coordinate 2g + o_g of acc (o_g from c's SUB-SAMPLING stream); since the places differ from
 // sender to sender, every sender's values are added to acc directly.
+// pre == 2: nothing is summed; every sender's decoded vector is written back into its own workspace slot (fp32, in
+// place: a wave has read its tile before it writes it), for a caller that puts the values elsewhere afterwards.
 __global__ __launch_bounds__(128) void k_dec_lo_last(DecBatch B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed,
-                                                     const float *T, const DecScratch *scratch, int narrow, float *acc) {
+                                                     float *T, const DecScratch *scratch, int narrow, float *acc) {
     __shared__ float lds[2][64 * kLdsRow];
     const uint32_t lane = lane_id(), wv = wave_in_block();
     const uint32_t tile = blockIdx.x * 2u + wv;
     const uint64_t tile_base = (uint64_t)tile << kLoBits;
-    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the decoded vector
+    const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vector
     if (tile_base >= d) return;                                  // whole tile in the padding (no block-wide barrier below)
     const uint64_t first = tile_base + 64u * lane;               // this lane's 64 coordinates after the transpose
     float *L = lds[wv];
@@ -737,6 +739,21 @@ __global__ __launch_bounds__(128) void k_dec_lo_last(DecBatch B, uint32_t n, uin
         const uint32_t scale = __float_as_uint(i16 ? scratch[c].deq[1] : 1.0f) & 0x7FFFFFFFu;   // > 0; x*1+s is exact
         const uint64_t word = hash_word(stream_key(seed, kStreamSign, B.client[c]), first >> 6);
         const uint32_t wlo = (uint32_t)word, whi = (uint32_t)(word >> 32);
+        if (pre == 2) {
+            float *dst = T + ((size_t)c << log2D) + first;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                float o4[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int k = 4 * q + e;
+                    const uint32_t sbit = ((k < 32 ? wlo : whi) << (31 - (k & 31))) & 0x80000000u;
+                    o4[e] = v[k] * __uint_as_float(scale | sbit);
+                }
+                *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(o4[0], o4[1], o4[2], o4[3]);
+            }
+            continue;
+        }
         if (pre) {
             const uint64_t offs = hash_word(stream_key(seed, kStreamSubsample, B.client[c]), first >> 6);
 #pragma unroll
@@ -822,6 +839,32 @@ __global__ __launch_bounds__(256) void k_sparse_scatter(const float *stage, uint
     const bool kept = sparse_kept(key, block, m, lane, slot);
     const uint64_t i = block * 64u + lane;
     if (kept && i < d) acc[i] += stage[block * m + slot];
+}
+// The same for a batch of senders that share m: sender blockIdx.y gathers into its workspace slot, and the scatter
+// adds, coordinate by coordinate, the values of all senders whose selection holds the coordinate.
+__global__ __launch_bounds__(256) void k_sparse_gather_batch(EncBatch B, uint64_t d, uint32_t m, uint64_t seed, float *T,
+                                                             int log2Dk) {
+    const uint32_t lane = lane_id(), c = blockIdx.y;
+    const uint64_t block = (uint64_t)blockIdx.x * 4u + wave_in_block();
+    if (block * 64u >= d) return;
+    uint32_t slot;
+    const bool kept = sparse_kept(stream_key(seed, kStreamSparse, B.client[c]), block, m, lane, slot);
+    const uint64_t i = block * 64u + lane;
+    if (kept) T[((size_t)c << log2Dk) + block * m + slot] = (i < d) ? B.x[c][i] : 0.0f;
+}
+__global__ __launch_bounds__(256) void k_sparse_scatter_batch(DecBatch B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed,
+                                                              const float *T, int log2Dk, float *acc) {
+    const uint32_t lane = lane_id();
+    const uint64_t block = (uint64_t)blockIdx.x * 4u + wave_in_block();
+    if (block * 64u >= d) return;
+    float sum = 0.0f;
+    for (uint32_t c = 0; c < n; ++c) {
+        uint32_t slot;
+        const bool kept = sparse_kept(stream_key(seed, kStreamSparse, B.client[c]), block, m, lane, slot);
+        if (kept) sum += T[((size_t)c << log2Dk) + block * m + slot];
+    }
+    const uint64_t i = block * 64u + lane;
+    if (i < d) acc[i] += sum;
 }
 __global__ __launch_bounds__(256) void k_fill_zero(float *p, uint64_t count) {
     const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
@@ -1140,7 +1183,7 @@ void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t hdr_d, int log2D
                         DecScratch *scratch, uint32_t *dev_status, hipStream_t st) {
     hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, hdr_d, log2D, seed, tab, scratch, dev_status);
 }
-void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, const float *T,
+void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
     dim3 grid(1u << (log2D - kLoBits - 1));
     hipLaunchKernelGGL(k_dec_lo_last, grid, dim3(128), 0, st, B, n, d, pre, log2D, seed, T, scratch, narrow, acc);
@@ -1160,6 +1203,16 @@ void launch_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t 
     const uint32_t blocks = (uint32_t)((d + 63) / 64);
     hipLaunchKernelGGL(k_sparse_scatter, dim3((blocks + 3) / 4), dim3(256), 0, st, stage, d, m,
                        stream_key(seed, kStreamSparse, client), acc);
+}
+void launch_sparse_gather_batch(const EncBatch &B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed, float *T, int log2Dk,
+                                hipStream_t st) {
+    const uint32_t blocks = (uint32_t)((d + 63) / 64);
+    hipLaunchKernelGGL(k_sparse_gather_batch, dim3((blocks + 3) / 4, n), dim3(256), 0, st, B, d, m, seed, T, log2Dk);
+}
+void launch_sparse_scatter_batch(const DecBatch &B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed, const float *T, int log2Dk,
+                                 float *acc, hipStream_t st) {
+    const uint32_t blocks = (uint32_t)((d + 63) / 64);
+    hipLaunchKernelGGL(k_sparse_scatter_batch, dim3((blocks + 3) / 4), dim3(256), 0, st, B, n, d, m, seed, T, log2Dk, acc);
 }
 void launch_fill_zero(float *p, uint64_t count, hipStream_t st) {
     hipLaunchKernelGGL(k_fill_zero, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st, p, count);

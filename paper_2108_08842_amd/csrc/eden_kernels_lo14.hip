@@ -158,11 +158,14 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
 // of sender c belongs at coordinate 2g + o_g of acc (o_g from c's SUB-SAMPLING stream).  A thread then keeps the 64
 // accumulator coordinates of its 32 pairs in registers and adds every value to the member of the pair it belongs
 // to; the launcher does not split tiles in this mode.
+// `separate`: K = n, one sender per workgroup, nothing is summed: every sender's decoded tile is written back into its own
+// workspace slot (`partial` is then the workspace; fp32, in place: the workgroup has read the tile before it writes
+// it), for a caller that puts the values elsewhere afterwards.
 template <bool PRE>
 __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d_src, int log2D, uint64_t seed,
                                                        const float *T, const DecScratch *scratch, int narrow, float *acc,
                                                        uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
-                                                       float *partial) {
+                                                       float *partial, int separate) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14LdsWords];
     constexpr int NS = PRE ? 64 : 32;                            // accumulator coordinates per thread
     const uint64_t d = d_src;                                    // bound of acc
@@ -174,7 +177,8 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
         tile = full_tiles + idx / K;
         c_begin = (uint32_t)(((uint64_t)n * k) / K);
         c_end = (uint32_t)(((uint64_t)n * (k + 1)) / K);
-        if (k > 0) part_run = partial + (((size_t)(k - 1) * split_tiles + (tile - full_tiles)) << kLo14Bits) + 32u * t;
+        if (separate) part_run = partial + ((size_t)k << log2D) + ((size_t)tile << kLo14Bits) + 32u * t;
+        else if (k > 0) part_run = partial + (((size_t)(k - 1) * split_tiles + (tile - full_tiles)) << kLo14Bits) + 32u * t;
     }
     const uint64_t tile_base = (uint64_t)tile << kLo14Bits;
     const uint64_t first = tile_base + 32u * t;
@@ -303,14 +307,19 @@ uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d_src, in
     }
     return grid.x;
 }
-void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, const float *T,
+void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, float *T,
                           const DecScratch *scratch, int narrow, float *acc, uint32_t resident, float *partial,
                           uint32_t partial_tiles, hipStream_t st) {
-    const uint64_t d = pre ? (d_src + 1) / 2 : d_src;            // dimension of the decoded vectors
+    const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vectors
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);     // tiles that reach below d
-    if (pre) {
+    if (pre == 1) {
         hipLaunchKernelGGL(k_dec_lo14_last<true>, dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, narrow, acc,
-                           tiles, 1u, 0u, partial);
+                           tiles, 1u, 0u, partial, 0);
+        return;
+    }
+    if (pre == 2) {                                              // every sender on its own, back into its workspace slot
+        hipLaunchKernelGGL(k_dec_lo14_last<false>, dim3(tiles * n), dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, 0, acc,
+                           0u, n, tiles, T, 1);
         return;
     }
     // Fewer tiles than half the resident workgroups: split every tile K ways by sender so that the chip is filled
@@ -325,7 +334,7 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     if (K == 1) { full = tiles; rest = 0; }
     dim3 grid(full + rest * K);
     hipLaunchKernelGGL(k_dec_lo14_last<false>, grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, narrow, acc, full, K,
-                       rest, partial);
+                       rest, partial, 0);
     if (K > 1) {
         dim3 cgrid((uint32_t)((((uint64_t)rest << kLo14Bits) / 4 + 255) / 256));
         hipLaunchKernelGGL(k_dec_lo14_combine, cgrid, dim3(256), 0, st, acc, d, full, K, rest, partial);

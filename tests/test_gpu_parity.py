@@ -268,6 +268,30 @@ def test_sparse_budgets_m_of_64(ctx, d, m):
     assert eden.message_bytes(d, B) == o.message_bytes(d, B)
 
 
+def test_sparse_budgets_with_different_m_in_one_call(ctx):
+    # senders with different m have kept vectors of different sizes: they go through one at a time; senders that
+    # share m go through in batches; both ways give the same messages and the same sum
+    from paper_2108_08842_amd import eden
+    d = 200_000
+    budgets = [eden.B_SPARSE(6), eden.B_SPARSE(32), eden.B_SPARSE(6), eden.B_SPARSE(63)]
+    w = synth.Workload("t", 4, d, budgets, 1444, "lognormal")
+    xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(4)]
+    ids = [5, 6, 7, 8]
+    msgs = ctx.encode(xs, ids, budgets, w.seed)
+    acc = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs, ids, budgets, d, w.seed, acc)
+    same = ctx.encode([xs[0], xs[2]], [5, 7], [budgets[0], budgets[2]], w.seed)      # batched path (same m)
+    assert torch.equal(same[0], msgs[0]) and torch.equal(same[1], msgs[2])
+    one_by_one = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(same, [5, 7], [budgets[0], budgets[2]], d, w.seed, one_by_one)
+    for c in (1, 3):
+        ctx.decode_accumulate([msgs[c]], [ids[c]], [budgets[c]], d, w.seed, one_by_one)
+    assert ctx.last_device_status() == 0
+    assert float((acc - one_by_one).norm() / one_by_one.norm()) < 1e-6
+    want = o.decode_mean([parity.to_oracle_message(m) for m in msgs], d)
+    assert parity.rel_l2((acc / 4).cpu().numpy(), want) <= parity.MEAN_REL_L2
+
+
 @pytest.mark.parametrize("d", [1, 70, 4096, 5000, 70_000, 300_000, (1 << 20) + 1, 2_500_000])
 def test_uniform_grid_budgets(ctx, d):
     # Sec. 4.3: index = round(z / Delta) in one byte; Delta_3 = 0.5224 (3 bits of entropy), a fine and a coarse grid
