@@ -366,6 +366,44 @@ def test_step_can_be_captured_in_a_graph(ctx):
     assert ctx.last_device_status() == 0
 
 
+def test_two_contexts_on_two_streams_and_kernel_timing(ctx):
+    # one context per concurrent stream: two rounds in flight at once give the results of the same rounds run alone;
+    # the optional kernel timing reports every launch of the kinds it was asked for
+    from paper_2108_08842_amd import eden
+    d, n = 1_500_000, 4
+    w = synth.Workload("t", n, d, [256, 512, 128, 1024], 777, "layers")
+    xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(n)]
+    ids = list(range(n))
+    other = eden.Context(d_max=d, n_max=n, device=0)
+
+    def round_on(context, seed, stream):
+        with torch.cuda.stream(stream):
+            msgs = context.encode(xs, ids, w.b_q8, seed)
+            acc = torch.zeros(d, device="cuda")
+            context.decode_accumulate(msgs, ids, w.b_q8, d, seed, acc)
+            return msgs, context.finalize_mean(acc, n)
+
+    cur = torch.cuda.current_stream()
+    alone = [round_on(ctx, 1, cur), round_on(other, 2, cur)]
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    s1.wait_stream(cur); s2.wait_stream(cur)
+    together = [round_on(ctx, 1, s1), round_on(other, 2, s2)]
+    torch.cuda.synchronize()
+    for (m_a, mean_a), (m_t, mean_t) in zip(alone, together):
+        assert all(torch.equal(a, b) for a, b in zip(m_a, m_t)) and torch.equal(mean_a, mean_t)
+    assert ctx.last_device_status() == 0 and other.last_device_status() == 0
+
+    other.profile_enable(["enc_first", "enc_last", "dec_first", "dec_last"], 64)
+    round_on(other, 3, cur)
+    torch.cuda.synchronize()
+    recs = other.profile_collect()
+    assert [k for k, _, _ in recs] == ["enc_first", "enc_last", "dec_first", "dec_last"]
+    assert all(s == n and 0.0 < ms < 50.0 for _, s, ms in recs)
+    other.profile_enable([], 0)
+    other.close()
+
+
 def test_mismatch_fraction_over_all_cases():
     # runs last in this file: every encode comparison made so far in this process is in the pool
     pool = parity.check_pool()
