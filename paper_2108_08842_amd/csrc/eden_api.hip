@@ -151,7 +151,7 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     bool ok = true;
     if (ctx->log2D_max > kLoBits)
         ok = ok && hipMalloc(&ctx->T, (size_t)ctx->slots * D_max * sizeof(float)) == hipSuccess;
-    if (ctx->log2D_max >= 19 && ctx->slots > 1) {                // one round of split tiles at most
+    if (ctx->log2D_max >= 19 && ctx->slots > 1) {                // at most as many split tiles as workgroups fit on the chip
         ctx->dec_partial_tiles = 2 * ctx->compute_units;
         ok = ok && hipMalloc(&ctx->dec_partial, ((size_t)ctx->dec_partial_tiles << 14) * sizeof(float)) == hipSuccess;
     }

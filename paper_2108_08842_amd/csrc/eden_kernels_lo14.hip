@@ -1,13 +1,13 @@
 // The 14-bit contiguous pass with 32 registers per thread (gfx950).
 //
 // A workgroup of 8 waves owns 2^14 consecutive coordinates.  Every thread keeps 32 values, so the 14 index
-// bits are covered by three rounds of in-register butterflies:
+// bits are covered by three groups of in-register butterfly stages:
 //
-//   round 1   bits 9..13   v[a] = coordinate 512 a + 64 wave + lane  (coalesced loads, 256 B per wave load)
+//   group 1   bits 9..13   v[a] = coordinate 512 a + 64 wave + lane  (coalesced loads, 256 B per wave load)
 //   exchange  through LDS between all waves (registers <-> bits 4..8)
-//   round 2   bits 4..8
+//   group 2   bits 4..8
 //   exchange  through LDS inside groups of 16 lanes (registers <-> bits 0..3, bit 4 stays a register bit)
-//   round 3   bits 0..3
+//   group 3   bits 0..3
 //
 // Afterwards thread t holds the 32 consecutive coordinates 32 t + e, e = 0..31: one half of a 64-bit sign word
 // of the rotation, and one 128-byte line of the workspace or the accumulator.
@@ -324,7 +324,7 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     }
     // Fewer tiles than half the resident workgroups: split every tile K ways by sender so that the chip is filled
     // (measured 2.2x on 64 tiles x 32 senders).  With more tiles than resident workgroups, splitting only the
-    // last, partly filled round was measured 3..10% slower than leaving it: a CU with one workgroup runs it faster.
+    // last, partly filled wave of workgroups was measured 3..10% slower than leaving it: a CU with one workgroup runs it faster.
     uint32_t full = 0, rest = tiles, K = 1;
     if (2 * tiles <= resident) {
         K = resident / tiles;
