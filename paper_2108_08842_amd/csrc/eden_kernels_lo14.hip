@@ -56,13 +56,13 @@ __device__ inline void lo14_forward32(float (&v)[32], float *lds) {
 
 // Stores the 32 consecutive values every thread holds after lo14_forward32 as whole 128-byte lines: thread t's
 // run starts at coordinate 32 t of the tile, so a wave owns 2048 consecutive coordinates; a wave-private
-// transpose through LDS (quads swizzled by the row so that both directions are conflict free) lets 8
-// neighbouring lanes store one line.  `L`: this wave's 2048 floats of LDS; `dst`: the wave's first coordinate.
+// transpose through LDS (quads swizzled by the low three bits of the row: eight neighbouring lanes then hit 32
+// different banks in both directions; measured with SQ_LDS_BANK_CONFLICT) lets 8 neighbouring lanes store one line.  `L`: this wave's 2048 floats of LDS; `dst`: the wave's first coordinate.
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 __device__ inline void lo14_store_runs(const float (&v)[32], float *L, float *dst) {
     const uint32_t lane = threadIdx.x & 63u;
     wave_lds_sync();
-    const uint32_t swz = (lane >> 1) & 7u;
+    const uint32_t swz = lane & 7u;
 #pragma unroll
     for (int q = 0; q < 8; ++q)
         *reinterpret_cast<float4 *>(&L[lane * 32u + 4u * ((uint32_t)q ^ swz)]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
@@ -72,7 +72,7 @@ __device__ inline void lo14_store_runs(const float (&v)[32], float *L, float *ds
     for (int j = 0; j < 8; ++j) {
         const uint32_t row = 8u * (uint32_t)j + (lane >> 3);
         const float4 x = *reinterpret_cast<const float4 *>(&L[row * 32u + 4u * pos]);
-        const uint32_t quad = pos ^ ((row >> 1) & 7u);
+        const uint32_t quad = pos ^ (row & 7u);
         f32x4_t y = {x.x, x.y, x.z, x.w};
         __builtin_nontemporal_store(y, reinterpret_cast<f32x4_t *>(dst + row * 32u + 4u * quad));
     }
