@@ -253,13 +253,54 @@ def lloyd_max(levels: int, tol: float = 1e-14, max_iter: int = 2_000_000):
     return t, q
 
 
+def max_shooting(levels: int):
+    """The same fixed point (Sec. 3: centroids are centres of mass, thresholds are midpoints) for an even number of
+    levels, found the way Max (1960) did: guess the smallest positive centroid q_0; the centroid condition on
+    [0, t_1] gives t_1, the midpoint condition gives q_1 = 2 t_1 - q_0, the centroid condition on [t_1, t_2] gives t_2,
+    and so on; the guess is right when the last centroid equals the centre of mass of the last, unbounded interval.
+    Bisection on q_0.  Lloyd's iteration needs minutes for 256 levels; this takes a fraction of a second."""
+    from scipy.optimize import brentq
+    if levels < 4 or levels % 2:
+        raise ValueError("even number of levels >= 4")
+    H = levels // 2
+
+    def chain(q0):
+        t, q = [0.0], [q0]
+        for _ in range(H - 1):
+            a, target = t[-1], q[-1]
+            if not a < target < centre_of_mass(a, math.inf):
+                return None, (1.0 if target >= centre_of_mass(a, math.inf) else -1.0)
+            hi = target + 1.0
+            while centre_of_mass(a, hi) < target:
+                hi += 1.0
+            b = brentq(lambda v: centre_of_mass(a, v) - target, target, hi, xtol=1e-15, rtol=1e-15)
+            t.append(b)
+            q.append(2.0 * b - target)
+        return (t, q), q[-1] - centre_of_mass(t[-1], math.inf)
+
+    lo, hi = 1e-9, math.sqrt(2.0 / math.pi)
+    for _ in range(200):
+        mid = 0.5 * (lo + hi)
+        _, r = chain(mid)
+        if r > 0.0:
+            hi = mid
+        else:
+            lo = mid
+        if hi - lo < 1e-17:
+            break
+    (t, q), _ = chain(lo)
+    tp, qp = np.array(t[1:]), np.array(q)
+    return np.concatenate([-tp[::-1], [0.0], tp]), np.concatenate([-qp[::-1], qp])
+
+
 _TABLE_CACHE: dict[int, tuple[np.ndarray, np.ndarray]] = {}
 
 
 def tables(bits: int):
-    """(thresholds, centroids) of I_b / Q_{I_b} for an integer bit budget b (Sec. 3)."""
+    """(thresholds, centroids) of I_b / Q_{I_b} for an integer bit budget b (Sec. 3).  Up to 32 levels by Lloyd's
+    iteration, above that by the shooting method (both solve the same two conditions)."""
     if bits not in _TABLE_CACHE:
-        _TABLE_CACHE[bits] = lloyd_max(1 << bits)
+        _TABLE_CACHE[bits] = lloyd_max(1 << bits) if bits <= 5 else max_shooting(1 << bits)
     return _TABLE_CACHE[bits]
 
 

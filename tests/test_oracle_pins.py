@@ -736,3 +736,42 @@ def test_grid_quantizer_path(golden):
     # an outlier beyond 127 Delta is clipped to the last interval
     z = np.array([100.0, -100.0, 0.2, 0.27])
     assert o.grid_indices(z, 0.5).tolist() == [127, -127, 0, 1]
+
+
+# ---- tables for b = 6, 7, 8 (Sec. 3 conditions solved by shooting instead of Lloyd's iteration)
+def test_shooting_tables_agree_with_lloyd_and_with_quadrature():
+    from scipy import integrate
+    t_s, q_s = o.max_shooting(32)
+    t_l, q_l = o.lloyd_max(32)
+    assert np.max(np.abs(q_s - q_l)) < 5e-12 and np.max(np.abs(t_s - t_l)) < 5e-12
+    for bits in (6, 8):
+        t, q = o.tables(bits)
+        n = 1 << bits
+        assert t.size == n - 1 and q.size == n and np.all(np.diff(q) > 0) and np.all(np.diff(t) > 0)
+        np.testing.assert_allclose(q, -q[::-1], atol=0)                       # symmetric family (Sec. 2.2.1, property 1)
+        np.testing.assert_allclose(t, 0.5 * (q[:-1] + q[1:]), atol=1e-12)     # thresholds are midpoints
+        edges = np.concatenate([[-np.inf], t, [np.inf]])
+        for k in (n // 2, n // 2 + 1, n - 2, n - 1):                          # centres of mass by quadrature
+            num = integrate.quad(lambda v: v * math.exp(-v * v / 2), edges[k], edges[k + 1], epsabs=1e-15)[0]
+            den = integrate.quad(lambda v: math.exp(-v * v / 2), edges[k], edges[k + 1], epsabs=1e-15)[0]
+            assert abs(q[k] - num / den) < 1e-9
+        # E[Q^2] = 1 - MSE and the rate-distortion bound MSE >= 4^-b (Sec. 4.3)
+        mse = 1.0 - o.expected_q2(t, q)
+        assert 4.0 ** -bits < mse < 3.0 * 4.0 ** -bits
+
+
+@pytest.mark.parametrize("b_q8", [1280, 1536, 1792, 2048])
+def test_wide_integer_budgets_through_the_path(b_q8):
+    bits = b_q8 // 256
+    d = 3000
+    rng = np.random.default_rng(b_q8)
+    x = rng.standard_normal(d)
+    msg, tr = o.encode(x, 2, 1, b_q8, want_trace=True)
+    assert o.message_bytes(d, b_q8) == len(msg.to_bytes()) == 64 + 4096 * bits // 8
+    back = o.Message.from_bytes(msg.to_bytes())
+    np.testing.assert_array_equal(o.unpack_indices(back.payload, bits, 4096), tr.idx)
+    xh = o.decode(back, d)
+    assert abs(np.dot(xh, x) - np.dot(x, x)) < 1e-10 * np.dot(x, x)
+    th, c = o.tables(bits)
+    v = o.vnmse_single(x, xh)
+    assert abs(v - (1 / o.expected_q2(th, c) - 1) * d / 4096) < 0.2 * (1 / o.expected_q2(th, c) - 1)
