@@ -42,8 +42,10 @@
  *     key = mix(mix(seed + PHI) + PHI*((stream << 32) | client) + PHI), PHI = 0x9E3779B97F4A7C15;
  *     streams: 0 = signs, 1 = sub-sampling, 2 = packet loss, 3 = mix (which coordinates get the extra bit),
  *     4 = sparse (sort keys of the m-of-64 sparsification).
- *   - Bit budget b is passed as b_q8 = 256*b.  Supported: 256, 512, 768, 1024 (b = 1, 2, 3, 4, the
- *     2^b-level Lloyd-Max quantizer of N(0,1), Sec. 3); 128 (b = 1/2: the b = 1 quantizer,
+ *   - Bit budget b is passed as b_q8 = 256*b.  Supported: 256, 512, ..., 2048 (b = 1..8, the
+ *     2^b-level Lloyd-Max quantizer of N(0,1), Sec. 3; for b = 5, 6, 7 at multi-pass sizes the indices are
+ *     packed by a kernel of their own from a byte buffer of D_max bytes per workspace slot that the first
+ *     such call allocates); 128 (b = 1/2: the b = 1 quantizer,
  *     then of every two consecutive rotated coordinates (2g, 2g+1) only the one at offset
  *     bit (g & 63) of word (g >> 6) of the SUB-SAMPLING stream is sent; Sec. 4.1, applied after
  *     the rotation, so the receiver treats the rest like lost coordinates, Sec. 4.2); and
@@ -201,7 +203,7 @@ int eden_sq_error(eden_ctx *ctx, const float *a_dev, const float *b_dev, uint64_
  * context, so calls on one context must not overlap. */
 int eden_index_entropy(eden_ctx *ctx, const void *msg_dev, uint64_t d, uint32_t b_q8, double *out_dev, void *stream);
 
-/* Copies the library's own Lloyd-Max tables for an integer budget `bits` (1..4) to host arrays:
+/* Copies the library's own Lloyd-Max tables for an integer budget `bits` (1..8) to host arrays:
  * thresholds[2^bits - 1] and centroids[2^bits], ascending, double precision (Sec. 3). */
 int eden_get_tables(uint32_t bits, double *thresholds, double *centroids);
 

@@ -28,6 +28,8 @@ struct eden_ctx {
     float *dec_partial;          // sums of sender groups when the last decode pass splits tiles (D_max >= 2^19)
     uint32_t dec_partial_tiles;  // its size in tiles of 2^14 floats
     uint32_t *hist;              // 256 counters for eden_index_entropy
+    uint8_t *codes;              // slots * D_max bytes: one-byte indices of b = 5, 6, 7 senders before packing / after
+                                 // unpacking; allocated by the first call that uses such a budget at a multi-pass size
     float *stage;                // d_max + 64 floats: the kept coordinates of one sender with a budget b = m/64;
                                  // allocated by the first call that uses such a budget
     EncScratch *enc_scratch; // slots
@@ -162,10 +164,14 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     ok = ok && hipMalloc(&ctx->dev_status, sizeof(uint32_t)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->hist, 256 * sizeof(uint32_t)) == hipSuccess;
     if (ok) {
-        DevTables host{};
+        static DevTables host;                                   // 9 KiB: not on the stack
+        host = DevTables{};
         for (int bits = 1; bits <= EDEN_MAX_TABLE_BITS; ++bits) {
             const EdenHalfTable *ht = eden_half_table(bits);
-            for (int i = 0; i < ht->half_levels; ++i) { host.t[bits][i] = ht->t[i]; host.q[bits][i] = ht->q[i]; }
+            for (int i = 0; i < ht->half_levels; ++i) {
+                if (bits <= 4) { host.t[bits][i] = ht->t[i]; host.q[bits][i] = ht->q[i]; }
+                else { host.t_big[bits - 5][i] = ht->t[i]; host.q_big[bits - 5][i] = ht->q[i]; }
+            }
         }
         ok = ok && hipMemcpy(ctx->tables, &host, sizeof(host), hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMemset(ctx->enc_scratch, 0, ctx->slots * sizeof(EncScratch)) == hipSuccess;
@@ -187,12 +193,18 @@ int eden_destroy(eden_ctx *ctx) {
     bool ok = guard.ok;
     for (hipEvent_t e : ctx->prof_start) ok = (hipEventDestroy(e) == hipSuccess) && ok;
     for (hipEvent_t e : ctx->prof_stop) ok = (hipEventDestroy(e) == hipSuccess) && ok;
-    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->stage, ctx->hist, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
+    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->stage, ctx->codes, ctx->hist, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
     for (void *p : ptrs)
         if (p) ok = (hipFree(p) == hipSuccess) && ok;
     delete ctx;
     return ok ? EDEN_OK : EDEN_ERR_HIP;
 }
+
+static bool ensure_codes(eden_ctx *ctx) {
+    if (ctx->codes) return true;
+    return hipMalloc(&ctx->codes, (size_t)ctx->slots << ctx->log2D_max) == hipSuccess;
+}
+static bool packs_bytes(uint32_t b_q8) { return wide_bits(b_q8) >= 5u && wide_bits(b_q8) <= 7u; }
 
 // Encodes n senders whose transformed vectors all have the same dimension.  `b_kernel`: the budgets the kernels
 // quantize with; `b_hdr`, `hdr_d`: what the headers record; `d_src`, `pre`: the length of the vectors x points to and
@@ -204,7 +216,7 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
     for (uint32_t c = 0; c < n; ++c)
-        wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u || grid_q15(b_kernel[c]) != 0u);
+        wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u || byte_budget(b_kernel[c]));
     const Plan pl = make_plan(log2D, wide_ok);
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
@@ -217,6 +229,13 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
             B.client[i] = client_ids[first + i];
             B.b_q8[i] = b_kernel[first + i];
             B.hdr_b_q8[i] = b_hdr[first + i];
+        }
+        bool pack = false;                                       // b = 5, 6, 7: bytes first, packed by a kernel of its own
+        if (pl.lo_bits != 0) {
+            for (uint32_t i = 0; i < nb; ++i) pack = pack || packs_bytes(B.b_q8[i]);
+            if (pack && !ensure_codes(ctx)) return EDEN_ERR_HIP;
+            for (uint32_t i = 0; i < nb; ++i)
+                if (packs_bytes(B.b_q8[i])) B.codes[i] = ctx->codes + ((size_t)i << log2D);
         }
         if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_ENC_SMALL, nb, st);
@@ -255,6 +274,7 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
                                                               ctx->partial_stride, ctx->enc_scratch, st);
                 }
             }
+            if (pack) launch_pack_bits(B, nb, log2D, st);
             Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
             launch_enc_finish(B, nb, hdr_d, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
                               ctx->dev_status, st);
@@ -348,7 +368,7 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
     for (uint32_t c = 0; c < n; ++c)
-        wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u || grid_q15(b_kernel[c]) != 0u);
+        wide_ok = wide_ok && (b_kernel[c] == 256u || b_kernel[c] == 512u || b_kernel[c] == 1024u || byte_budget(b_kernel[c]));
     const Plan pl = make_plan(log2D, wide_ok);
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
@@ -361,6 +381,16 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
             B.client[i] = client_ids[first + i];
             B.b_q8[i] = b_kernel[first + i];
             B.hdr_b_q8[i] = b_hdr[first + i];
+        }
+        if (pl.lo_bits != 0) {                                   // b = 5, 6, 7: the payload is unpacked to bytes first
+            bool unpack = false;
+            for (uint32_t i = 0; i < nb; ++i) unpack = unpack || packs_bytes(B.b_q8[i]);
+            if (unpack) {
+                if (!ensure_codes(ctx)) return EDEN_ERR_HIP;
+                for (uint32_t i = 0; i < nb; ++i)
+                    if (packs_bytes(B.b_q8[i])) B.codes[i] = ctx->codes + ((size_t)i << log2D);
+                launch_unpack_bits(B, nb, log2D, ctx->codes, st);
+            }
         }
         if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <utility>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace eden {
@@ -55,6 +56,13 @@ constexpr int kGridMax = 127;
 __host__ __device__ inline uint32_t grid_q15(uint32_t b_q8) {
     return ((b_q8 & ~0xFFFFu) == kGridFlag && (b_q8 & 0xFFFFu) >= 1u) ? (b_q8 & 0xFFFFu) : 0u;
 }
+// b = 5..8: the Lloyd-Max quantizers with 32..256 levels.  Like the uniform grid they are handled one byte per
+// coordinate inside the kernels (index = rank of the interval); for b = 5, 6, 7 a separate kernel packs the bytes to
+// b bits (and unpacks them before decoding), for b = 8 the bytes are the payload.
+__host__ __device__ inline uint32_t wide_bits(uint32_t b_q8) {
+    return (b_q8 == 1280u || b_q8 == 1536u || b_q8 == 1792u || b_q8 == 2048u) ? (b_q8 >> 8) : 0u;
+}
+__host__ __device__ inline bool byte_budget(uint32_t b_q8) { return grid_q15(b_q8) != 0u || wide_bits(b_q8) != 0u; }
 __host__ __device__ inline bool budget_mixed(uint32_t b_q8) { return b_q8 == 384 || b_q8 == 640 || b_q8 == 896; }
 __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
     if (b_q8 == 128) { bits = 1; k = 2; return true; }
@@ -62,6 +70,7 @@ __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
         bits = (int)(b_q8 >> 8); k = 1; return true;
     }
     if (grid_q15(b_q8)) { bits = 8; k = 1; return true; }
+    if (wide_bits(b_q8)) { bits = (int)wide_bits(b_q8); k = 1; return true; }
     return false;
 }
 // bytes of the first part of the payload (the floor(b)-bit indices), a multiple of 8
@@ -91,6 +100,8 @@ constexpr float kQ1 = 0.7978845608028654f;
 struct DevTables {
     double t[5][8];
     double q[5][8];
+    double t_big[4][128];   // b = 5..8 at index b - 5
+    double q_big[4][128];
 };
 
 // per-sender scalars that travel between the passes of one encode
@@ -102,8 +113,12 @@ struct EncScratch {
     float qpos2[8];
     float grid_inv;         // uniform grid: 1 / (Delta |x|), so that round(u * grid_inv) is the index
     unsigned pad;
-    float grid_c[kGridMax + 1];     // uniform grid: centre of mass of the interval of index n >= 0
+    float grid_c[kGridMax + 1];     // uniform grid: centre of mass of the interval of index n >= 0; b = 5..8: positive centroids
+    float wide_thr[128];            // b = 5..8: positive thresholds times |x|
 };
+
+static_assert(offsetof(EncScratch, wide_thr) == offsetof(EncScratch, grid_c) + 128 * sizeof(float),
+              "the kernels copy centroids and thresholds as one run of 256 floats");
 
 // per-message scalars of one decode
 struct DecScratch {
@@ -111,7 +126,7 @@ struct DecScratch {
     float deq2[16];         // mixed budgets: the same for the indices of I_{floor(b)+1}
     uint32_t flags;
     uint32_t pad[3];
-    float grid_deq[kGridMax + 1];   // uniform grid: (S / (p sqrt(D))) * centre of mass of index n >= 0
+    float grid_deq[kGridMax + 1];   // uniform grid and b = 5..8: (S / (p sqrt(D))) * positive centroid
 };
 
 struct EncBatch {
@@ -120,6 +135,7 @@ struct EncBatch {
     uint32_t client[kMaxBatch];
     uint32_t b_q8[kMaxBatch];       // what the kernels quantize with
     uint32_t hdr_b_q8[kMaxBatch];   // what the header says (differs for the budgets that sparsify before the rotation)
+    uint8_t *codes[kMaxBatch];      // b = 5, 6, 7: where the one-byte indices go before they are packed (else null)
 };
 struct DecBatch {
     const void *msg[kMaxBatch];
@@ -127,6 +143,7 @@ struct DecBatch {
     uint32_t client[kMaxBatch];
     uint32_t b_q8[kMaxBatch];
     uint32_t hdr_b_q8[kMaxBatch];
+    const uint8_t *codes[kMaxBatch];    // b = 5, 6, 7: the unpacked one-byte indices (else null)
 };
 
 // ---- wave-level helpers
@@ -346,6 +363,25 @@ __device__ inline float dequantize_grid(uint32_t byte, const float *dtab) {
     const int a = n < 0 ? -n : n;
     const float m = dtab[a > kGridMax ? kGridMax : a];           // (a sender never writes -128)
     return n < 0 ? -m : m;
+}
+
+// One-byte budgets.  `tab` in LDS: [0..127] the positive centroids (centres of mass), [128..255] the positive
+// thresholds times |x| (b = 5..8 only).  b = 5..8: rank of |u| among the H - 1 positive thresholds by bisection
+// (log2 H reads), index = H + rank or H - 1 - rank (Sec. 2.2.1, Sec. 3).
+__device__ inline uint32_t quantize_byte(float u, uint32_t b_q8, float grid_inv, const float *tab, float &ip) {
+    if (grid_q15(b_q8)) return quantize_grid(u, grid_inv, tab, ip);
+    const uint32_t H = 1u << (wide_bits(b_q8) - 1u);
+    const float a = fabsf(u);
+    uint32_t mag = 0;
+    for (uint32_t step = H >> 1; step; step >>= 1)
+        if (a > tab[128u + mag + step]) mag += step;             // strict: a value on a threshold stays closer to zero
+    ip = fmaf(a, tab[mag], ip);
+    return (__float_as_uint(u) >> 31) ? H - 1u - mag : H + mag;
+}
+__device__ inline float dequantize_byte(uint32_t byte, uint32_t b_q8, const float *dtab) {
+    if (grid_q15(b_q8)) return dequantize_grid(byte, dtab);
+    const uint32_t H = 1u << (wide_bits(b_q8) - 1u), code = byte & (2u * H - 1u);
+    return code >= H ? dtab[code - H] : -dtab[H - 1u - code];
 }
 
 // b = K + 1/2 (Sec. 4.1): the index of one coordinate, K+1 bits wide where `up` (quantized with I_{K+1}), else K

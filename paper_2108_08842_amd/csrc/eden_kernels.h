@@ -50,6 +50,9 @@ void launch_sparse_gather_batch(const EncBatch &B, uint32_t n, uint64_t d, uint3
                                 hipStream_t st);
 void launch_sparse_scatter_batch(const DecBatch &B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed, const float *T, int log2Dk,
                                  float *acc, hipStream_t st);
+// b = 5, 6, 7: one-byte indices (B.codes[c], null for other senders) <-> the packed payload
+void launch_pack_bits(const EncBatch &B, uint32_t n, int log2D, hipStream_t st);
+void launch_unpack_bits(const DecBatch &B, uint32_t n, int log2D, uint8_t *codes_all, hipStream_t st);
 void launch_fill_zero(float *p, uint64_t count, hipStream_t st);
 void launch_byte_entropy(const uint8_t *bytes, uint64_t count, uint32_t *hist, double *out, hipStream_t st);
 void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,

@@ -30,6 +30,7 @@ __device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8,
         s->grid_inv = (float)(32768.0 / ((double)grid_q15(b_q8) * norm));
         return;
     }
+    if (wide_bits(b_q8)) return;                                 // b = 5..8: the long tables are filled by fill_byte_tables
     const int finer = budget_mixed(b_q8) ? bits + 1 : bits;
     for (int i = 0; i < 8; ++i) {
         s->thr[i] = (float)(tab->t[bits][i] * norm);
@@ -38,10 +39,16 @@ __device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8,
         s->qpos2[i] = (float)tab->q[finer][i];
     }
 }
-// the centres of mass of the uniform grid's intervals, one per thread (tid < 128)
-__device__ inline void fill_grid_centroids(EncScratch *s, uint32_t b_q8, uint32_t tid) {
-    const uint32_t q15 = grid_q15(b_q8);
-    if (q15 && tid <= (uint32_t)kGridMax) s->grid_c[tid] = tid ? (float)grid_centroid((double)q15 / 32768.0, (int)tid) : 0.0f;
+// The tables of the one-byte budgets, one entry per thread (tid < 128): the centres of mass of the uniform grid's
+// intervals, or the positive centroids and scaled thresholds of the 32..256-level quantizers.
+__device__ inline void fill_byte_tables(EncScratch *s, uint32_t b_q8, double n2, const DevTables *tab, uint32_t tid) {
+    if (tid > (uint32_t)kGridMax) return;
+    if (const uint32_t q15 = grid_q15(b_q8)) {
+        s->grid_c[tid] = tid ? (float)grid_centroid((double)q15 / 32768.0, (int)tid) : 0.0f;
+    } else if (const uint32_t wb = wide_bits(b_q8)) {
+        s->grid_c[tid] = (float)tab->q_big[wb - 5u][tid];
+        s->wide_thr[tid] = (float)(tab->t_big[wb - 5u][tid] * sqrt(n2));
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -143,7 +150,7 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
     constexpr int R = 1 << M;
     __shared__ double red[4];
     __shared__ float qtabs[4][16];
-    __shared__ float gtabs[4][kGridMax + 1];
+    __shared__ float gtabs[4][256];                              // one-byte budgets: centroids and thresholds
     const uint32_t c = blockIdx.y;
     const uint32_t lane = lane_id();
     const uint32_t tile = blockIdx.x * 4u + wave_in_block();
@@ -194,16 +201,18 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
             wave_lds_sync();
             const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
             uint32_t *part_b = payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4;
-            if (grid_q15(b_q8)) {
-                // Sec. 4.3: index = round(z / Delta) as one byte per coordinate; a row of the tile is 64 consecutive bytes
+            if (byte_budget(b_q8)) {
+                // uniform grid (Sec. 4.3) or b = 5..8: one byte per coordinate; a row of the tile is 64 consecutive bytes
                 float *ctab = gtabs[wave_in_block()];
-                ctab[lane] = sc->grid_c[lane];
-                ctab[64 + lane] = sc->grid_c[64 + lane];
+                const float *byte_tab = sc->grid_c;              // grid_c[128] and wide_thr[128] are one run of 256 floats
+#pragma unroll
+                for (int q = 0; q < 4; ++q) ctab[64 * q + lane] = byte_tab[64 * q + lane];       // centroids, then thresholds
                 wave_lds_sync();
                 const float inv = sc->grid_inv;
-                uint8_t *bytes = reinterpret_cast<uint8_t *>(payload);
+                uint8_t *bytes = B.codes[c] ? B.codes[c] : reinterpret_cast<uint8_t *>(payload);
 #pragma unroll
-                for (int r = 0; r < R; ++r) bytes[base + ((uint64_t)r << p) + lane] = (uint8_t)quantize_grid(v[r], inv, ctab, ip);
+                for (int r = 0; r < R; ++r)
+                    bytes[base + ((uint64_t)r << p) + lane] = (uint8_t)quantize_byte(v[r], b_q8, inv, ctab, ip);
             } else
             switch (b_q8) {
                 case 384u: hi_quantize_pack<R, 1, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
@@ -230,8 +239,13 @@ __global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *part
     double s = 0.0;
     for (uint32_t i = threadIdx.x; i < nparts; i += 256) s += pc[i];
     const double total = block_sum<256>(s, red);
-    if (threadIdx.x == 0) fill_enc_scratch(&scratch[c], total, B.b_q8[c], tab);
-    fill_grid_centroids(&scratch[c], B.b_q8[c], threadIdx.x);
+    __shared__ double n2_all;
+    if (threadIdx.x == 0) {
+        fill_enc_scratch(&scratch[c], total, B.b_q8[c], tab);
+        n2_all = total;
+    }
+    __syncthreads();
+    fill_byte_tables(&scratch[c], B.b_q8[c], n2_all, tab, threadIdx.x);
 }
 
 // Decode, first pass in wave tiles (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit
@@ -256,7 +270,7 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
     const bool i16 = narrow && b_q8 <= 256u;
     if (lane < 16) table[wv][lane] = (i16 && lane == 1) ? 1.0f : scratch[c].deq[lane];
     else if (lane < 32) table[wv][lane] = scratch[c].deq2[lane - 16];
-    if (grid_q15(b_q8)) { gtabs[wv][lane] = scratch[c].grid_deq[lane]; gtabs[wv][64 + lane] = scratch[c].grid_deq[64 + lane]; }
+    if (byte_budget(b_q8)) { gtabs[wv][lane] = scratch[c].grid_deq[lane]; gtabs[wv][64 + lane] = scratch[c].grid_deq[64 + lane]; }
     wave_lds_sync();
     const float *tb = table[wv], *tb2 = table[wv] + 16;
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
@@ -284,12 +298,14 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
             const uint32_t neg = (~(w >> (lane >> 1)) & 1u) << 31;          // index 0 = negative
             v[r] = kept ? __uint_as_float(mag | neg) : 0.0f;
         }
-    } else if (grid_q15(b_q8)) {
-        // Sec. 4.3: one signed byte per coordinate, the index on the uniform grid
-        const rsrc_t rp = make_rsrc(reinterpret_cast<const uint8_t *>(payload) + base, payload_bytes - (uint32_t)base);
+    } else if (byte_budget(b_q8)) {
+        // one byte per coordinate: the index on the uniform grid (Sec. 4.3) or of a 32..256-level quantizer
+        const uint8_t *bytes = B.codes[c] ? B.codes[c] : reinterpret_cast<const uint8_t *>(payload);
+        const rsrc_t rp = make_rsrc(bytes + base, (1u << log2D) - (uint32_t)base);
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            v[r] = dequantize_grid((uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rp, (int)lane, (int)((uint32_t)r << p), 0), gtabs[wv]);
+            v[r] = dequantize_byte((uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rp, (int)lane, (int)((uint32_t)r << p), 0), b_q8,
+                                   gtabs[wv]);
     } else if (budget_mixed(b_q8)) {
         // b = bits + 1/2 (Sec. 4.1): every coordinate has `bits` bits in the first part; the coordinate of each pair
         // that the MIX stream selects was quantized with the finer table and has its top bit in the second part
@@ -407,10 +423,14 @@ __global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t vali
     const uint32_t b_q8 = B.b_q8[c];
     const EncScratch *sc = &scratch[c];
     __shared__ float qtabs[4][16];
-    __shared__ float gtabs[4][kGridMax + 1];
+    __shared__ float gtabs[4][256];                              // one-byte budgets: centroids and thresholds
     float *qtab = qtabs[wave_in_block()], *gtab = gtabs[wave_in_block()];
     fill_qtab(qtab, sc, lane);
-    if (grid_q15(b_q8)) { gtab[lane] = sc->grid_c[lane]; gtab[64 + lane] = sc->grid_c[64 + lane]; }
+    const float *byte_tab = sc->grid_c;                          // grid_c[128] and wide_thr[128] are one run of 256 floats
+    if (byte_budget(b_q8)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) gtab[64 * q + lane] = byte_tab[64 * q + lane];
+    }
     wave_lds_sync();
     float ip = 0.0f;
 #pragma unroll
@@ -433,10 +453,10 @@ __global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t vali
 #pragma unroll
                 for (int e = 0; e < 4; ++e) word |= quantize_one<2>(v[r][4 * h + e], sc, qtab, ip) << (2 * e);
                 reinterpret_cast<uint8_t *>(payload)[group] = (uint8_t)word;
-            } else if (grid_q15(b_q8)) {                          // Sec. 4.3: one byte per coordinate
+            } else if (byte_budget(b_q8)) {                       // uniform grid or b = 5..8: one byte per coordinate
 #pragma unroll
-                for (int e = 0; e < 4; ++e) word |= quantize_grid(v[r][4 * h + e], sc->grid_inv, gtab, ip) << (8 * e);
-                reinterpret_cast<uint32_t *>(payload)[group] = word;
+                for (int e = 0; e < 4; ++e) word |= quantize_byte(v[r][4 * h + e], b_q8, sc->grid_inv, gtab, ip) << (8 * e);
+                reinterpret_cast<uint32_t *>(B.codes[c] ? reinterpret_cast<char *>(B.codes[c]) : payload)[group] = word;
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) word |= quantize_one<8>(v[r][4 * h + e], sc, qtab, ip) << (4 * e);
@@ -461,10 +481,11 @@ __global__ __launch_bounds__(256) void k_dec_wide_first(DecBatch B, uint64_t kee
     __shared__ float gtabs[4][kGridMax + 1];
     const uint32_t b_q8 = B.b_q8[c];
     if (lane < 16) table[wv][lane] = scratch[c].deq[lane];
-    if (grid_q15(b_q8)) { gtabs[wv][lane] = scratch[c].grid_deq[lane]; gtabs[wv][64 + lane] = scratch[c].grid_deq[64 + lane]; }
+    if (byte_budget(b_q8)) { gtabs[wv][lane] = scratch[c].grid_deq[lane]; gtabs[wv][64 + lane] = scratch[c].grid_deq[64 + lane]; }
     wave_lds_sync();
     const float *tb = table[wv];
     const char *payload = static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES;
+    const char *bytes = B.codes[c] ? reinterpret_cast<const char *>(B.codes[c]) : payload;
     const uint32_t *bm = B.bitmap[c];
     float v[kWideRows][8];
 #pragma unroll
@@ -478,14 +499,14 @@ __global__ __launch_bounds__(256) void k_dec_wide_first(DecBatch B, uint64_t kee
             uint32_t word;
             if (b_q8 == 256u) word = (uint32_t)reinterpret_cast<const uint8_t *>(payload)[group >> 1] >> (4u * (lane & 1u));
             else if (b_q8 == 512u) word = reinterpret_cast<const uint8_t *>(payload)[group];
-            else if (grid_q15(b_q8)) word = reinterpret_cast<const uint32_t *>(payload)[group];
+            else if (byte_budget(b_q8)) word = reinterpret_cast<const uint32_t *>(bytes)[group];
             else word = reinterpret_cast<const uint16_t *>(payload)[group];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float val;
                 if (b_q8 == 256u) val = tb[(word >> e) & 1u];
                 else if (b_q8 == 512u) val = tb[(word >> (2 * e)) & 3u];
-                else if (grid_q15(b_q8)) val = dequantize_grid((word >> (8 * e)) & 0xFFu, gtabs[wv]);
+                else if (byte_budget(b_q8)) val = dequantize_byte((word >> (8 * e)) & 0xFFu, b_q8, gtabs[wv]);
                 else val = tb[(word >> (4 * e)) & 15u];
                 v[r][4 * h + e] = here ? val : 0.0f;
             }
@@ -679,6 +700,9 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
             const int n = (int)lane + 64 * h;
             out->grid_deq[n] = n ? (float)(coef * grid_centroid(delta, n)) : 0.0f;
         }
+    } else if (const uint32_t wb = wide_bits(b_q8)) {            // b = 5..8: the positive centroids, two per lane
+#pragma unroll
+        for (int h = 0; h < 2; ++h) out->grid_deq[lane + 64 * h] = (float)(coef * tab->q_big[wb - 5u][lane + 64 * h]);
     }
     if (lane == 0) {
         out->flags = flags;
@@ -866,6 +890,37 @@ __global__ __launch_bounds__(256) void k_sparse_scatter_batch(DecBatch B, uint32
     const uint64_t i = block * 64u + lane;
     if (i < d) acc[i] += sum;
 }
+// b = 5, 6, 7: the one-byte indices of a sender, in coordinate order, to the payload's bit string (index j in bits
+// j b .. j b + b - 1, Sec. 2.2.1 message; one thread per payload word) and back (one thread per index).
+__global__ __launch_bounds__(256) void k_pack_bits(EncBatch B, int log2D) {
+    const uint32_t c = blockIdx.y;
+    const uint8_t *codes = B.codes[c];
+    if (!codes) return;
+    const uint32_t bits = wide_bits(B.b_q8[c]);
+    const uint64_t words = (((uint64_t)bits << log2D) + 31) >> 5;
+    const uint64_t w = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (w >= words) return;
+    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const uint64_t lo = 32 * w, D = 1ull << log2D;
+    uint32_t word = 0;
+    for (uint64_t j = lo / bits; j < D && j * bits < lo + 32; ++j) {
+        const int64_t pos = (int64_t)(j * bits) - (int64_t)lo;   // where index j starts inside this word (may be negative)
+        const uint32_t code = codes[j];
+        word |= pos >= 0 ? code << pos : code >> (-pos);
+    }
+    payload[w] = word;
+}
+__global__ __launch_bounds__(256) void k_unpack_bits(DecBatch B, int log2D, uint8_t *codes_all) {
+    const uint32_t c = blockIdx.y;
+    if (!B.codes[c]) return;
+    const uint32_t bits = wide_bits(B.b_q8[c]);
+    const uint64_t j = (uint64_t)blockIdx.x * 256u + threadIdx.x, D = 1ull << log2D;
+    if (j >= D) return;
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    const uint64_t words = (((uint64_t)bits << log2D) + 31) >> 5, pos = j * bits, w0 = pos >> 5;
+    const uint32_t next = (w0 + 1 < words) ? payload[w0 + 1] : 0u;
+    codes_all[((size_t)c << log2D) + j] = (uint8_t)code_at(payload[w0], next, (uint32_t)(pos & 31u), (int)bits);
+}
 __global__ __launch_bounds__(256) void k_fill_zero(float *p, uint64_t count) {
     const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
     if (i < count) p[i] = 0.0f;
@@ -954,7 +1009,8 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
     const double n2t = block_sum<256>(n2p, red);
     const uint32_t b_q8 = B.b_q8[c];
     if (threadIdx.x == 0) fill_enc_scratch(&s, n2t, b_q8, tab);
-    fill_grid_centroids(&s, b_q8, threadIdx.x);
+    __syncthreads();
+    fill_byte_tables(&s, b_q8, s.n2, tab, threadIdx.x);
     fwht_lds(buf, D);                                          // includes the barriers that publish `s`
     int bits, k;
     budget_of(b_q8, bits, k);
@@ -963,11 +1019,11 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
     float ip = 0.0f;
     const bool mix = budget_mixed(b_q8);                       // b = k + 1/2: one coordinate of every pair uses I_{k+1}
     const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
-    const bool grid = grid_q15(b_q8) != 0u;                    // Sec. 4.3: index = round(z / Delta), one byte
+    const bool bytes = byte_budget(b_q8);                      // uniform grid (Sec. 4.3) or b = 5..8: one-byte indices
     for (uint32_t i = threadIdx.x; i < D; i += 256) {
         const float u = buf[i];
-        if (grid) {
-            code[i] = (uint8_t)quantize_grid(u, s.grid_inv, s.grid_c, ip);
+        if (bytes) {
+            code[i] = (uint8_t)quantize_byte(u, b_q8, s.grid_inv, s.grid_c, ip);     // grid_c and wide_thr are adjacent
             continue;
         }
         const float a = fabsf(u);
@@ -1069,7 +1125,7 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
             const uint32_t bitpos = j * (uint32_t)bits, w0 = bitpos >> 5;
             const uint32_t next = (w0 + 1u < nwords) ? payload[w0 + 1u] : 0u;       // a 3-bit index may straddle two words
             const uint32_t idx = code_at(payload[w0], next, bitpos & 31u, bits);
-            float val = grid_q15(b_q8) ? dequantize_grid(idx, s.grid_deq) : s.deq[idx & 15u];
+            float val = byte_budget(b_q8) ? dequantize_byte(idx, b_q8, s.grid_deq) : s.deq[idx & 15u];
             if (mix) {
                 const uint32_t g = i >> 1;
                 if ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u))
@@ -1213,6 +1269,13 @@ void launch_sparse_scatter_batch(const DecBatch &B, uint32_t n, uint64_t d, uint
                                  float *acc, hipStream_t st) {
     const uint32_t blocks = (uint32_t)((d + 63) / 64);
     hipLaunchKernelGGL(k_sparse_scatter_batch, dim3((blocks + 3) / 4), dim3(256), 0, st, B, n, d, m, seed, T, log2Dk, acc);
+}
+void launch_pack_bits(const EncBatch &B, uint32_t n, int log2D, hipStream_t st) {
+    const uint64_t words = ((7ull << log2D) + 31) >> 5;          // the widest of b = 5, 6, 7
+    hipLaunchKernelGGL(k_pack_bits, dim3((uint32_t)((words + 255) / 256), n), dim3(256), 0, st, B, log2D);
+}
+void launch_unpack_bits(const DecBatch &B, uint32_t n, int log2D, uint8_t *codes_all, hipStream_t st) {
+    hipLaunchKernelGGL(k_unpack_bits, dim3((uint32_t)(((1ull << log2D) + 255) / 256), n), dim3(256), 0, st, B, log2D, codes_all);
 }
 void launch_fill_zero(float *p, uint64_t count, hipStream_t st) {
     hipLaunchKernelGGL(k_fill_zero, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st, p, count);

@@ -218,7 +218,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
     __shared__ float lds[X::LDS_FLOATS];
     __shared__ double red[X::THREADS / 64];
     __shared__ float qtab[16];                                   // centroids; published by the first barrier of the exchange
-    __shared__ float gtab[kGridMax + 1];                         // uniform grid: centres of mass
+    __shared__ float gtab[256];                                  // one-byte budgets: centroids and thresholds
     constexpr int p = kHixP;
     constexpr int NW = X::RP / 32;
     constexpr bool UNIT = MODE == 0;
@@ -234,8 +234,10 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
     const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
     if (!UNIT) {
         fill_qtab(qtab, sc, threadIdx.x);
-        if (grid_q15(b_q8))
-            for (uint32_t i = threadIdx.x; i <= (uint32_t)kGridMax; i += X::THREADS) gtab[i] = sc->grid_c[i];
+        if (byte_budget(b_q8)) {                                 // centroids, then thresholds: one run of 256 floats
+            const float *byte_tab = sc->grid_c;
+            for (uint32_t i = threadIdx.x; i < 256u; i += X::THREADS) gtab[i] = byte_tab[i];
+        }
     }
     float ip = 0.0f;
     uint32_t held[TPW][X::PH][NW];
@@ -262,13 +264,13 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
             }
             hix_exchange_read<M>(lds, out);
             if (UNIT || b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
-            else if (grid_q15(b_q8)) {
-                // Sec. 4.3: index = round(z / Delta) as one byte per coordinate; a row segment of the tile is 32 bytes
-                uint8_t *bytes = reinterpret_cast<uint8_t *>(payload) + base + col;
+            else if (byte_budget(b_q8)) {
+                // uniform grid (Sec. 4.3) or b = 5..8: one byte per coordinate; a row segment of the tile is 32 bytes
+                uint8_t *bytes = (B.codes[c] ? B.codes[c] : reinterpret_cast<uint8_t *>(payload)) + base + col;
                 const float inv = sc->grid_inv;
 #pragma unroll
                 for (int s2 = 0; s2 < X::RP; ++s2)
-                    bytes[(uint64_t)hix_row2<M>(g, ph, s2) << p] = (uint8_t)quantize_grid(out[s2], inv, gtab, ip);
+                    bytes[(uint64_t)hix_row2<M>(g, ph, s2) << p] = (uint8_t)quantize_byte(out[s2], b_q8, inv, gtab, ip);
             } else {
                 uint16_t *part_b = reinterpret_cast<uint16_t *>(payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4);
                 if (MODE == 2 && b_q8 == 384u) hix_quantize_pack<M, 1, true>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
@@ -392,7 +394,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, u
     const DecScratch *sc = &scratch[c];
     if (threadIdx.x < 16) table[threadIdx.x] = (i16 && threadIdx.x == 1) ? 1.0f : sc->deq[threadIdx.x];
     else if (threadIdx.x < 32) table[threadIdx.x] = sc->deq2[threadIdx.x - 16];
-    if (grid_q15(b_q8))
+    if (byte_budget(b_q8))
         for (uint32_t i = threadIdx.x; i <= (uint32_t)kGridMax; i += X::THREADS) gtab[i] = sc->grid_deq[i];
     __syncthreads();
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
@@ -429,13 +431,15 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, u
             const uint32_t neg = (~(w >> bitpos) & 1u) << 31;                    // index 0 = negative
             v[r] = kept ? __uint_as_float(mag | neg) : 0.0f;
         }
-    } else if (grid_q15(b_q8)) {
-        // Sec. 4.3: one signed byte per coordinate, the index on the uniform grid
-        const rsrc_t rp = make_rsrc(reinterpret_cast<const uint8_t *>(payload) + base, payload_bytes - (uint32_t)base);
+    } else if (byte_budget(b_q8)) {
+        // one byte per coordinate: the index on the uniform grid (Sec. 4.3) or of a 32..256-level quantizer
+        const uint8_t *bytes = B.codes[c] ? B.codes[c] : reinterpret_cast<const uint8_t *>(payload);
+        const rsrc_t rp = make_rsrc(bytes + base, (1u << log2D) - (uint32_t)base);
         const uint32_t voff = (g << p) + col;
 #pragma unroll
         for (int r = 0; r < 64; ++r)
-            v[r] = dequantize_grid((uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rp, (int)voff, (int)(((uint32_t)X::RL * r) << p), 0), gtab);
+            v[r] = dequantize_byte((uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rp, (int)voff, (int)(((uint32_t)X::RL * r) << p), 0),
+                                   b_q8, gtab);
     } else if (budget_mixed(b_q8)) {
         // b = bits + 1/2 (Sec. 4.1): every coordinate has `bits` bits in the first part; the coordinate of each pair
         // that the MIX stream selects was quantized with the finer table and has its top bit in the second part

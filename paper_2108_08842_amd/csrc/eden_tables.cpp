@@ -7,7 +7,8 @@
 //
 // The solver works on the positive half line only (the interval family is symmetric,
 // Sec. 2.2.1 property 1): levels 0 < q_0 < ... < q_{h-1}, thresholds t_0 = 0 < t_1 < ... < t_{h-1},
-// h = 2^(b-1).  It alternates the two Lloyd conditions until nothing moves.
+// h = 2^(b-1).  Up to 16 levels per sign it alternates the two Lloyd conditions until nothing moves; above that it
+// solves the same two conditions by shooting from the smallest level (Max 1960).
 #include "eden_tables.h"
 
 #include <cmath>
@@ -30,25 +31,70 @@ double centroid(double a, double b) {
 EdenHalfTable g_tables[EDEN_MAX_TABLE_BITS + 1];
 std::once_flag g_once;
 
+// Lloyd's iteration: alternate the two conditions until nothing moves (fast up to 16 levels per sign).
+void solve_by_iteration(EdenHalfTable &T, int h) {
+    for (int k = 0; k < h; ++k) T.q[k] = 3.5 * (k + 0.5) / h;                  // any increasing start
+    T.t[0] = 0.0;
+    for (long it = 0; it < 5000000; ++it) {
+        for (int k = 1; k < h; ++k) T.t[k] = 0.5 * (T.q[k - 1] + T.q[k]);
+        double moved = 0.0;
+        for (int k = 0; k < h; ++k) {
+            const double hi = (k + 1 < h) ? T.t[k + 1] : INFINITY;
+            const double c = centroid(T.t[k], hi);
+            moved = std::fmax(moved, std::fabs(c - T.q[k]));
+            T.q[k] = c;
+        }
+        if (moved < 1e-15) break;
+    }
+    for (int k = 1; k < h; ++k) T.t[k] = 0.5 * (T.q[k - 1] + T.q[k]);
+}
+
+// The upper edge b of an interval [a, b] whose centre of mass is `target` (a < target < centroid(a, inf)):
+// the centre of mass grows with b, so bisection.
+double edge_for_centroid(double a, double target) {
+    double lo = target, hi = target + 1.0;
+    while (centroid(a, hi) < target) hi += 1.0;
+    for (int it = 0; it < 200 && hi - lo > 1e-16 * hi; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (centroid(a, mid) < target) lo = mid; else hi = mid;
+    }
+    return 0.5 * (lo + hi);
+}
+
+// From a guess of the smallest level q_0 the two conditions fix everything else in turn: [0, t_1] must have centre of
+// mass q_0, q_1 = 2 t_1 - q_0 puts t_1 at the midpoint, [t_1, t_2] must have centre of mass q_1, ...  Returns how far the
+// last level ends from the centre of mass of the last, unbounded interval (+1 / -1 if the chain breaks early because
+// the guess is too large / too small).
+double chain_from(double q0, int h, EdenHalfTable &T) {
+    T.t[0] = 0.0;
+    T.q[0] = q0;
+    for (int k = 0; k + 1 < h; ++k) {
+        const double a = T.t[k], target = T.q[k], open_end = centroid(a, INFINITY);
+        if (!(a < target)) return -1.0;
+        if (!(target < open_end)) return 1.0;
+        T.t[k + 1] = edge_for_centroid(a, target);
+        T.q[k + 1] = 2.0 * T.t[k + 1] - target;
+    }
+    return T.q[h - 1] - centroid(T.t[h - 1], INFINITY);
+}
+
+// Many levels: Lloyd's iteration converges too slowly (minutes at 128 levels per sign); bisection on q_0 instead.
+void solve_by_shooting(EdenHalfTable &T, int h) {
+    double lo = 1e-9, hi = 0.7978845608028654;                                  // q_0 < sqrt(2/pi), the single-level value
+    for (int it = 0; it < 200 && hi - lo > 1e-17; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (chain_from(mid, h, T) > 0.0) hi = mid; else lo = mid;
+    }
+    chain_from(lo, h, T);
+}
+
 void solve_all() {
     for (int bits = 1; bits <= EDEN_MAX_TABLE_BITS; ++bits) {
         EdenHalfTable &T = g_tables[bits];
         const int h = 1 << (bits - 1);
         T.half_levels = h;
-        for (int k = 0; k < h; ++k) T.q[k] = 3.5 * (k + 0.5) / h;              // any increasing start
-        T.t[0] = 0.0;
-        for (long it = 0; it < 5000000; ++it) {
-            for (int k = 1; k < h; ++k) T.t[k] = 0.5 * (T.q[k - 1] + T.q[k]);
-            double moved = 0.0;
-            for (int k = 0; k < h; ++k) {
-                const double hi = (k + 1 < h) ? T.t[k + 1] : INFINITY;
-                const double c = centroid(T.t[k], hi);
-                moved = std::fmax(moved, std::fabs(c - T.q[k]));
-                T.q[k] = c;
-            }
-            if (moved < 1e-15) break;
-        }
-        for (int k = 1; k < h; ++k) T.t[k] = 0.5 * (T.q[k - 1] + T.q[k]);
+        if (h <= 16) solve_by_iteration(T, h);
+        else solve_by_shooting(T, h);
     }
 }
 

@@ -2,8 +2,8 @@
 #ifndef EDEN_TABLES_H
 #define EDEN_TABLES_H
 
-#define EDEN_MAX_TABLE_BITS 4
-#define EDEN_MAX_HALF_LEVELS 8
+#define EDEN_MAX_TABLE_BITS 8
+#define EDEN_MAX_HALF_LEVELS 128
 
 struct EdenHalfTable {
     int half_levels;                     // h = 2^(bits-1)

@@ -73,10 +73,10 @@ def test_every_budget_at_the_headline_size():
     every sender checked coordinate by coordinate against the oracle, then decoded with 10% of the packets lost."""
     from paper_2108_08842_amd import eden
     d = synth.config(4).d
-    groups = [[128, 384, 512, 640, 768, 896, 1024, eden.B_GRID(0.5224)],      # one call: same transform dimension
+    groups = [[128, 384, 512, 640, 768, 896, 1024, eden.B_GRID(0.5224), 1280, 1536, 1792, 2048],   # one call: same transform dimension
               [eden.B_HALF_PRE, eden.B_HALF_PRE],
               [eden.B_SPARSE(6), eden.B_SPARSE(45)]]
-    ctx = eden.Context(d_max=d, n_max=8, device=0)
+    ctx = eden.Context(d_max=d, n_max=12, device=0)
     for gi, budgets in enumerate(groups):
         n = len(budgets)
         w = synth.Workload("all_budgets", n, d, budgets, 60 + gi, "layers")
@@ -171,26 +171,26 @@ def test_three_pass_size_wide_tiles():
     (8 rows x 512 columns, 8 columns per lane) on bits 22..24 next to the payload."""
     from paper_2108_08842_amd import eden
     d = (1 << 24) + 54321
-    w = synth.Workload("three_pass_wide", 4, d, [256, 512, 1024, eden.B_GRID(0.5224)], 26, "lognormal_signed")
-    print(f"three passes, wide tiles: n=4 d={d} D=2^25 budgets={w.b_q8} seed={w.seed}", flush=True)
-    xs = [synth.client_vector(w, c) for c in range(4)]
-    ctx = eden.Context(d_max=d, n_max=4, device=0)
-    ids = [2, 7, 11, 13]
+    w = synth.Workload("three_pass_wide", 5, d, [256, 512, 1024, eden.B_GRID(0.5224), 1536], 26, "lognormal_signed")
+    print(f"three passes, wide tiles: n=5 d={d} D=2^25 budgets={w.b_q8} seed={w.seed}", flush=True)
+    xs = [synth.client_vector(w, c) for c in range(5)]
+    ctx = eden.Context(d_max=d, n_max=5, device=0)
+    ids = [2, 7, 11, 13, 17]
     msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], ids, w.b_q8, w.seed)
     assert ctx.last_device_status() == 0
     stats = parity.EncodeParity()
     om = [parity.to_oracle_message(m) for m in msgs]
-    for c in range(4):
+    for c in range(5):
         parity.check_encode(xs[c], w.seed, ids[c], w.b_q8[c], om[c], stats)
     parity.finish_encode(stats)
     print("encode:", stats, flush=True)
     bm = [ctx.make_loss_bitmap(w.seed, cid, 1 << 25, int(0.1 * 2 ** 32)) for cid in ids]
     acc = torch.zeros(d, device="cuda")
     ctx.decode_accumulate(msgs, ids, w.b_q8, d, w.seed, acc, bm)
-    got = ctx.finalize_mean(acc, 4).cpu().numpy()
+    got = ctx.finalize_mean(acc, 5).cpu().numpy()
     want = o.decode_mean(om, d, [b.cpu().numpy().view(np.uint32) for b in bm])
     err = parity.rel_l2(got, want)
-    print(f"decode of 4 senders with 10% loss: rel L2 {err:.2e}", flush=True)
+    print(f"decode of 5 senders with 10% loss: rel L2 {err:.2e}", flush=True)
     assert err <= parity.MEAN_REL_L2
     assert ctx.last_device_status() == 0
     ctx.close()

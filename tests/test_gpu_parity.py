@@ -220,7 +220,7 @@ def test_argument_errors(ctx):
               msg_caps=[msg.numel()])
     assert ctx.encode_raw(**ok) == eden.OK
     assert ctx.encode_raw(**{**ok, "b_q8": [300]}) == eden.ERR_INVALID_ARG
-    assert ctx.encode_raw(**{**ok, "b_q8": [1280]}) == eden.ERR_INVALID_ARG
+    assert ctx.encode_raw(**{**ok, "b_q8": [2304]}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "d": 0}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "d": (1 << 23) + 1}) == eden.ERR_INVALID_ARG
     assert ctx.encode_raw(**{**ok, "x_ptrs": [None]}) == eden.ERR_INVALID_ARG
@@ -305,12 +305,26 @@ def test_uniform_grid_budgets(ctx, d):
     assert eden.message_bytes(d, budgets[0]) == o.message_bytes(d, budgets[0])
 
 
+@pytest.mark.parametrize("d", [1, 3, 70, 4096, 5000, 70_000, 300_000, (1 << 20) + 1, 2_500_000, 6_000_000])
+def test_budgets_of_five_to_eight_bits(ctx, d):
+    # b = 5..8: 32..256-level Lloyd-Max quantizers; one-byte indices inside the kernels, packed to b bits for b = 5, 6, 7
+    from paper_2108_08842_amd import eden
+    budgets = [1280, 1536, 1792, 2048, 512]
+    w = synth.Workload("t", 5, d, budgets, 2100 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(5)]
+    _run_case(ctx, xs, [1, 2, 3, 4, 5], w.b_q8, w.seed, also_oracle_msgs=(d <= 300_000))
+    if d >= (1 << 14):
+        _run_case(ctx, xs, [1, 2, 3, 4, 5], w.b_q8, w.seed + 1, drop_q32=int(0.2 * 2 ** 32), also_oracle_msgs=False)
+    for b in budgets:
+        assert eden.message_bytes(d, b) == o.message_bytes(d, b)
+
+
 def test_random_shapes_and_budgets(ctx):
     # 60 seeded random cases: dimension (log-uniform up to 2^18 + tail), number of senders, any supported budget
     # per sender, sometimes lost packets, sometimes the sparsification before the rotation
     from paper_2108_08842_amd import eden
     rng = np.random.default_rng(20240)
-    budgets_all = [128, 256, 384, 512, 640, 768, 896, 1024]
+    budgets_all = [128, 256, 384, 512, 640, 768, 896, 1024, 1280, 1536, 1792, 2048]
     dists = ["normal", "lognormal", "lognormal_signed", "normal_outliers", "layers"]
     for case in range(60):
         d = int(2 ** rng.uniform(1.0, 18.2))

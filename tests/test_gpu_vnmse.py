@@ -47,7 +47,7 @@ def test_vnmse_close_to_theory(ctx, dist):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(11)
     x = vnmse.draw(dist, d, gen, torch.device("cuda:0"))
-    for b in (0.5, 1, 1.5, 2, 2.5, 3, 3.5, 4):
+    for b in (0.5, 1, 1.5, 2, 2.5, 3, 3.5, 4, 5, 6, 7, 8):
         v, se = vnmse.measure_vnmse(ctx, x, int(b * 256), 16, seed=3)
         th = vnmse.theory_vnmse(b)
         print(f"{dist} b={b}: vNMSE {v:.5f} +- {se:.5f}, theory {th:.5f}", flush=True)

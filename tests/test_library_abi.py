@@ -42,15 +42,17 @@ def test_message_bytes_matches_oracle(eden):
     assert eden.message_bytes(100, 300) == 0
 
 
-@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_library_tables_match_oracle_tables(eden, bits):
-    # two independent Lloyd-Max solvers (C++ on the positive half line, numpy on the full line)
+    # two independent Lloyd-Max solvers (C++ on the positive half line, numpy on the full line; above 32 levels both
+    # shoot from the smallest level, where the end of the chain is the least accurate: 3e-10 at 256 levels)
     t, q = eden.get_tables(bits)
     to, qo = o.tables(bits)
-    np.testing.assert_allclose(t, to, atol=2e-12)
-    np.testing.assert_allclose(q, qo, atol=2e-12)
+    tol = 2e-12 if bits <= 5 else 1e-9
+    np.testing.assert_allclose(t, to, atol=tol)
+    np.testing.assert_allclose(q, qo, atol=tol)
     # and fp32 rounding of either is the same number almost everywhere
-    assert np.sum(np.float32(q) != np.float32(qo)) == 0
+    assert np.sum(np.float32(q) != np.float32(qo)) <= (0 if bits <= 5 else 2)
 
 
 def test_error_strings(eden):
