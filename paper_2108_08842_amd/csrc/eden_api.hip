@@ -164,8 +164,8 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     ok = ok && hipMalloc(&ctx->dev_status, sizeof(uint32_t)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->hist, 256 * sizeof(uint32_t)) == hipSuccess;
     if (ok) {
-        static DevTables host;                                   // 9 KiB: not on the stack
-        host = DevTables{};
+        std::vector<DevTables> host_tables(1);                   // 9 KiB: not on the stack
+        DevTables &host = host_tables[0];
         for (int bits = 1; bits <= EDEN_MAX_TABLE_BITS; ++bits) {
             const EdenHalfTable *ht = eden_half_table(bits);
             for (int i = 0; i < ht->half_levels; ++i) {
