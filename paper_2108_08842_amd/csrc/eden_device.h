@@ -201,6 +201,25 @@ __device__ inline void buf_store_keep(rsrc_t r, uint32_t lane_off, uint32_t wave
     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)wave_off, 0);
 }
 
+// Sub-word accesses of neighbouring lanes go through whole dwords (a byte or half-word load per lane is not merged
+// with its neighbours': measured 3x slower on the first decode pass of the one-byte budgets).
+// The byte at `byte_off` (lane part) + `wave_off` of the buffer; descriptor base and wave_off are multiples of 4.
+__device__ inline uint32_t buf_load_byte(rsrc_t r, uint32_t byte_off, uint32_t wave_off) {
+    const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(r, (int)(byte_off & ~3u), (int)wave_off, 0);
+    return (w >> (8u * (byte_off & 3u))) & 0xFFu;
+}
+__device__ inline uint32_t buf_load_half(rsrc_t r, uint32_t byte_off, uint32_t wave_off) {     // byte_off even
+    const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(r, (int)(byte_off & ~3u), (int)wave_off, 0);
+    return (w >> (8u * (byte_off & 2u))) & 0xFFFFu;
+}
+// The bytes of lanes 4k .. 4k+3 as one dword (byte of lane 4k + i in bits 8i..), in all four lanes.
+__device__ inline uint32_t quad_bytes(uint32_t byte, uint32_t lane) {
+    uint32_t x = (byte & 0xFFu) << (8u * (lane & 3u));
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);     // quad_perm [1,0,3,2]: lane ^ 1
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true);     // quad_perm [2,3,0,1]: lane ^ 2
+    return x;
+}
+
 // In-register Walsh-Hadamard butterflies over the register index: (a,b) -> (a+b, a-b) at spans 1..N/2.
 template <int N>
 __device__ inline void fwht_regs(float (&v)[N]) {
@@ -366,23 +385,34 @@ __device__ inline float dequantize_grid(uint32_t byte, const float *dtab) {
 }
 
 // One-byte budgets.  `tab` in LDS: [0..127] the positive centroids (centres of mass), [128..255] the positive
-// thresholds times |x| (b = 5..8 only).  b = 5..8: rank of |u| among the H - 1 positive thresholds by bisection
-// (log2 H reads), index = H + rank or H - 1 - rank (Sec. 2.2.1, Sec. 3).
-__device__ inline uint32_t quantize_byte(float u, uint32_t b_q8, float grid_inv, const float *tab, float &ip) {
-    if (grid_q15(b_q8)) return quantize_grid(u, grid_inv, tab, ip);
-    const uint32_t H = 1u << (wide_bits(b_q8) - 1u);
-    const float a = fabsf(u);
-    uint32_t mag = 0;
-    for (uint32_t step = H >> 1; step; step >>= 1)
-        if (a > tab[128u + mag + step]) mag += step;             // strict: a value on a threshold stays closer to zero
-    ip = fmaf(a, tab[mag], ip);
-    return (__float_as_uint(u) >> 31) ? H - 1u - mag : H + mag;
+// thresholds times |x| (b = 5..8 only; entries from H on are +inf).  b = 5..8: rank of |u| among the H - 1 positive
+// thresholds by bisection over all 128 entries (seven reads, no branch: the padding never moves the rank), index =
+// H + rank or H - 1 - rank (Sec. 2.2.1, Sec. 3).  GRID is a compile-time choice so that loops over many values
+// stay free of branches (with a branch per value the compiler waits for every load before it issues the next).
+template <bool GRID>
+__device__ inline uint32_t quantize_byte(float u, uint32_t H, float grid_inv, const float *tab, float &ip) {
+    if constexpr (GRID) {
+        return quantize_grid(u, grid_inv, tab, ip);
+    } else {
+        const float a = fabsf(u);
+        uint32_t mag = 0;
+#pragma unroll
+        for (uint32_t step = 64; step; step >>= 1) mag += (a > tab[128u + mag + step]) ? step : 0u;    // strict: ties stay closer to zero
+        ip = fmaf(a, tab[mag], ip);
+        return (__float_as_uint(u) >> 31) ? H - 1u - mag : H + mag;
+    }
 }
-__device__ inline float dequantize_byte(uint32_t byte, uint32_t b_q8, const float *dtab) {
-    if (grid_q15(b_q8)) return dequantize_grid(byte, dtab);
-    const uint32_t H = 1u << (wide_bits(b_q8) - 1u), code = byte & (2u * H - 1u);
-    return code >= H ? dtab[code - H] : -dtab[H - 1u - code];
+template <bool GRID>
+__device__ inline float dequantize_byte(uint32_t byte, uint32_t H, const float *dtab) {
+    if constexpr (GRID) {
+        return dequantize_grid(byte, dtab);
+    } else {
+        const uint32_t code = byte & (2u * H - 1u);
+        const float m = dtab[code >= H ? code - H : H - 1u - code];
+        return code >= H ? m : -m;
+    }
 }
+__device__ inline uint32_t wide_half_levels(uint32_t b_q8) { return wide_bits(b_q8) ? 1u << (wide_bits(b_q8) - 1u) : 0u; }
 
 // b = K + 1/2 (Sec. 4.1): the index of one coordinate, K+1 bits wide where `up` (quantized with I_{K+1}), else K
 // bits (I_K), and its contribution |u| q to sum_i u_i Q_i.

@@ -46,8 +46,9 @@ __device__ inline void fill_byte_tables(EncScratch *s, uint32_t b_q8, double n2,
     if (const uint32_t q15 = grid_q15(b_q8)) {
         s->grid_c[tid] = tid ? (float)grid_centroid((double)q15 / 32768.0, (int)tid) : 0.0f;
     } else if (const uint32_t wb = wide_bits(b_q8)) {
-        s->grid_c[tid] = (float)tab->q_big[wb - 5u][tid];
-        s->wide_thr[tid] = (float)(tab->t_big[wb - 5u][tid] * sqrt(n2));
+        const uint32_t H = 1u << (wb - 1u);
+        s->grid_c[tid] = tid < H ? (float)tab->q_big[wb - 5u][tid] : 0.0f;
+        s->wide_thr[tid] = tid < H ? (float)(tab->t_big[wb - 5u][tid] * sqrt(n2)) : INFINITY;   // padding for the bisection
     }
 }
 
@@ -210,9 +211,19 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
                 wave_lds_sync();
                 const float inv = sc->grid_inv;
                 uint8_t *bytes = B.codes[c] ? B.codes[c] : reinterpret_cast<uint8_t *>(payload);
+                const uint32_t H = wide_half_levels(b_q8);
+                if (grid_q15(b_q8)) {                            // the indices replace the values in their registers
 #pragma unroll
-                for (int r = 0; r < R; ++r)
-                    bytes[base + ((uint64_t)r << p) + lane] = (uint8_t)quantize_byte(v[r], b_q8, inv, ctab, ip);
+                    for (int r = 0; r < R; ++r) v[r] = __uint_as_float(quantize_byte<true>(v[r], H, inv, ctab, ip));
+                } else {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) v[r] = __uint_as_float(quantize_byte<false>(v[r], H, inv, ctab, ip));
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) {                    // four lanes' bytes = one dword store
+                    const uint32_t quad = quad_bytes(__float_as_uint(v[r]), lane);
+                    if (!(lane & 3u)) *reinterpret_cast<uint32_t *>(bytes + base + ((uint64_t)r << p) + lane) = quad;
+                }
             } else
             switch (b_q8) {
                 case 384u: hi_quantize_pack<R, 1, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
@@ -253,8 +264,10 @@ __global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *part
 // whose packet was lost, then index bits p .. p+M-1 of H.  Every (tile, sender) pair is independent.
 // Elements at or above `keep_elems` are never read by the later passes (they end in the padding): the buffer
 // bounds drop their stores.
+// (Five waves per SIMD are requested: the budgets with two loads per value would otherwise set the register count
+// for all of them; measured 0.057 against 0.073 ms on 32 senders at D = 2^20.)
 template <int M>
-__global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_elems, int log2D, int p, uint64_t seed,
+__global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                                                       const DecScratch *scratch, int narrow, float *T) {
     constexpr int R = 1 << M;
     __shared__ float table[4][32];
@@ -303,9 +316,15 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
         const uint8_t *bytes = B.codes[c] ? B.codes[c] : reinterpret_cast<const uint8_t *>(payload);
         const rsrc_t rp = make_rsrc(bytes + base, (1u << log2D) - (uint32_t)base);
 #pragma unroll
-        for (int r = 0; r < R; ++r)
-            v[r] = dequantize_byte((uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rp, (int)lane, (int)((uint32_t)r << p), 0), b_q8,
-                                   gtabs[wv]);
+        for (int r = 0; r < R; ++r) v[r] = __uint_as_float(buf_load_byte(rp, lane, (uint32_t)r << p));
+        const uint32_t H = wide_half_levels(b_q8);
+        if (grid_q15(b_q8)) {                                    // the values replace the bytes in their registers
+#pragma unroll
+            for (int r = 0; r < R; ++r) v[r] = dequantize_byte<true>(__float_as_uint(v[r]), H, gtabs[wv]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) v[r] = dequantize_byte<false>(__float_as_uint(v[r]), H, gtabs[wv]);
+        }
     } else if (budget_mixed(b_q8)) {
         // b = bits + 1/2 (Sec. 4.1): every coordinate has `bits` bits in the first part; the coordinate of each pair
         // that the MIX stream selects was quantized with the finer table and has its top bit in the second part
@@ -320,7 +339,7 @@ __global__ __launch_bounds__(256) void k_dec_hi_first(DecBatch B, uint64_t keep_
         for (int r = 0; r < R; ++r) {
             const int soff = (int)((((uint32_t)r * words_row) << (p - 6)) * 4u);
             const uint32_t w0 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, soff, 0);
-            const uint32_t w1 = (bits == 3) ? __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0) : 0u;
+            const uint32_t w1 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0);    // always: no branch per value
             const uint32_t low = code_at(w0, w1, shift, bits);
             const uint32_t wb = __builtin_amdgcn_raw_buffer_load_b32(rb, 0, (int)(((uint32_t)r << (p - 6)) * 4u), 0);
             const uint32_t offs = __builtin_amdgcn_readlane(offs_mine, r);
@@ -453,9 +472,14 @@ __global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t vali
 #pragma unroll
                 for (int e = 0; e < 4; ++e) word |= quantize_one<2>(v[r][4 * h + e], sc, qtab, ip) << (2 * e);
                 reinterpret_cast<uint8_t *>(payload)[group] = (uint8_t)word;
-            } else if (byte_budget(b_q8)) {                       // uniform grid or b = 5..8: one byte per coordinate
+            } else if (grid_q15(b_q8)) {                          // uniform grid: one byte per coordinate
 #pragma unroll
-                for (int e = 0; e < 4; ++e) word |= quantize_byte(v[r][4 * h + e], b_q8, sc->grid_inv, gtab, ip) << (8 * e);
+                for (int e = 0; e < 4; ++e) word |= quantize_byte<true>(v[r][4 * h + e], 0u, sc->grid_inv, gtab, ip) << (8 * e);
+                reinterpret_cast<uint32_t *>(payload)[group] = word;
+            } else if (wide_bits(b_q8)) {                         // b = 5..8: one byte per coordinate
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    word |= quantize_byte<false>(v[r][4 * h + e], wide_half_levels(b_q8), 0.0f, gtab, ip) << (8 * e);
                 reinterpret_cast<uint32_t *>(B.codes[c] ? reinterpret_cast<char *>(B.codes[c]) : payload)[group] = word;
             } else {
 #pragma unroll
@@ -506,7 +530,8 @@ __global__ __launch_bounds__(256) void k_dec_wide_first(DecBatch B, uint64_t kee
                 float val;
                 if (b_q8 == 256u) val = tb[(word >> e) & 1u];
                 else if (b_q8 == 512u) val = tb[(word >> (2 * e)) & 3u];
-                else if (byte_budget(b_q8)) val = dequantize_byte((word >> (8 * e)) & 0xFFu, b_q8, gtabs[wv]);
+                else if (grid_q15(b_q8)) val = dequantize_byte<true>((word >> (8 * e)) & 0xFFu, 0u, gtabs[wv]);
+                else if (wide_bits(b_q8)) val = dequantize_byte<false>((word >> (8 * e)) & 0xFFu, wide_half_levels(b_q8), gtabs[wv]);
                 else val = tb[(word >> (4 * e)) & 15u];
                 v[r][4 * h + e] = here ? val : 0.0f;
             }
@@ -1022,8 +1047,9 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
     const bool bytes = byte_budget(b_q8);                      // uniform grid (Sec. 4.3) or b = 5..8: one-byte indices
     for (uint32_t i = threadIdx.x; i < D; i += 256) {
         const float u = buf[i];
-        if (bytes) {
-            code[i] = (uint8_t)quantize_byte(u, b_q8, s.grid_inv, s.grid_c, ip);     // grid_c and wide_thr are adjacent
+        if (bytes) {                                           // grid_c and wide_thr are adjacent
+            code[i] = (uint8_t)(grid_q15(b_q8) ? quantize_byte<true>(u, 0u, s.grid_inv, s.grid_c, ip)
+                                               : quantize_byte<false>(u, wide_half_levels(b_q8), 0.0f, s.grid_c, ip));
             continue;
         }
         const float a = fabsf(u);
@@ -1125,7 +1151,8 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
             const uint32_t bitpos = j * (uint32_t)bits, w0 = bitpos >> 5;
             const uint32_t next = (w0 + 1u < nwords) ? payload[w0 + 1u] : 0u;       // a 3-bit index may straddle two words
             const uint32_t idx = code_at(payload[w0], next, bitpos & 31u, bits);
-            float val = byte_budget(b_q8) ? dequantize_byte(idx, b_q8, s.grid_deq) : s.deq[idx & 15u];
+            float val = grid_q15(b_q8) ? dequantize_byte<true>(idx, 0u, s.grid_deq)
+                      : wide_bits(b_q8) ? dequantize_byte<false>(idx, wide_half_levels(b_q8), s.grid_deq) : s.deq[idx & 15u];
             if (mix) {
                 const uint32_t g = i >> 1;
                 if ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u))

@@ -211,7 +211,7 @@ template <> struct WordVec<4> { using type = uint4; };
 // words of the TPW tiles are then kept and stored together (one row of a tile is only 4 bytes of payload).
 // MODE 1: any integer budget or b = 1/2.  MODE 2: also the budgets k + 1/2 (they need more registers).
 template <int M, int TPW, int MODE>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, uint64_t d, int log2D, uint64_t seed,
+__global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_last(EncBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                    const float *T, double *partials,
                                                                    uint32_t partial_stride, const EncScratch *scratch) {
     using X = HiX<M>;
@@ -268,9 +268,19 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_enc_hix_last(EncBatch B, ui
                 // uniform grid (Sec. 4.3) or b = 5..8: one byte per coordinate; a row segment of the tile is 32 bytes
                 uint8_t *bytes = (B.codes[c] ? B.codes[c] : reinterpret_cast<uint8_t *>(payload)) + base + col;
                 const float inv = sc->grid_inv;
+                const uint32_t H = wide_half_levels(b_q8);
+                if (grid_q15(b_q8)) {                            // the indices replace the values in their registers
 #pragma unroll
-                for (int s2 = 0; s2 < X::RP; ++s2)
-                    bytes[(uint64_t)hix_row2<M>(g, ph, s2) << p] = (uint8_t)quantize_byte(out[s2], b_q8, inv, gtab, ip);
+                    for (int s2 = 0; s2 < X::RP; ++s2) out[s2] = __uint_as_float(quantize_byte<true>(out[s2], H, inv, gtab, ip));
+                } else {
+#pragma unroll
+                    for (int s2 = 0; s2 < X::RP; ++s2) out[s2] = __uint_as_float(quantize_byte<false>(out[s2], H, inv, gtab, ip));
+                }
+#pragma unroll
+                for (int s2 = 0; s2 < X::RP; ++s2) {             // four lanes' bytes = one dword store
+                    const uint32_t quad = quad_bytes(__float_as_uint(out[s2]), col);
+                    if (!(col & 3u)) *reinterpret_cast<uint32_t *>(bytes + ((uint64_t)hix_row2<M>(g, ph, s2) << p)) = quad;
+                }
             } else {
                 uint16_t *part_b = reinterpret_cast<uint16_t *>(payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4);
                 if (MODE == 2 && b_q8 == 384u) hix_quantize_pack<M, 1, true>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
@@ -377,7 +387,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D
 // workspace is int16), zero for coordinates that were not sampled or whose packet was lost, then index bits
 // 14 .. 14+M-1 of H.
 template <int M>
-__global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, uint64_t d, int log2D, uint64_t seed,
+__global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                     const DecScratch *scratch, int narrow, float *T) {
     using X = HiX<M>;
     constexpr int p = kHixP;
@@ -437,9 +447,15 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, u
         const rsrc_t rp = make_rsrc(bytes + base, (1u << log2D) - (uint32_t)base);
         const uint32_t voff = (g << p) + col;
 #pragma unroll
-        for (int r = 0; r < 64; ++r)
-            v[r] = dequantize_byte((uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rp, (int)voff, (int)(((uint32_t)X::RL * r) << p), 0),
-                                   b_q8, gtab);
+        for (int r = 0; r < 64; ++r) v[r] = __uint_as_float(buf_load_byte(rp, voff, ((uint32_t)X::RL * r) << p));
+        const uint32_t H = wide_half_levels(b_q8);
+        if (grid_q15(b_q8)) {                                    // the values replace the bytes in their registers
+#pragma unroll
+            for (int r = 0; r < 64; ++r) v[r] = dequantize_byte<true>(__float_as_uint(v[r]), H, gtab);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 64; ++r) v[r] = dequantize_byte<false>(__float_as_uint(v[r]), H, gtab);
+        }
     } else if (budget_mixed(b_q8)) {
         // b = bits + 1/2 (Sec. 4.1): every coordinate has `bits` bits in the first part; the coordinate of each pair
         // that the MIX stream selects was quantized with the finer table and has its top bit in the second part
@@ -452,16 +468,17 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_dec_hix_first(DecBatch B, u
         const rsrc_t rp = make_rsrc(payload + ((base * (uint32_t)bits) >> 5), payload_bytes - (uint32_t)((base * (uint32_t)bits) >> 5) * 4u);
         const uint32_t voff = (((g * (uint32_t)bits) << (p - 5)) + (cbits >> 5)) * 4u;
         const uint32_t shift = cbits & 31u;
-        const uint16_t *part_b = reinterpret_cast<const uint16_t *>(payload + payload_bytes / 4u) + (base >> 5);
-        const rsrc_t rb = make_rsrc(part_b, (uint32_t)payload_b_bytes(1ull << log2D, b_q8) - (uint32_t)(base >> 5) * 2u);
-        const uint32_t voffb = (g << (p - 5)) * 2u;
+        // second part: 16 bits per row segment; the descriptor starts at the part (8-byte aligned) so that the
+        // half-words can be fetched as whole dwords
+        const rsrc_t rb = make_rsrc(payload + payload_bytes / 4u, (uint32_t)payload_b_bytes(1ull << log2D, b_q8));
+        const uint32_t voffb = ((uint32_t)(base >> 5) + (g << (p - 5))) * 2u;
 #pragma unroll
         for (int r = 0; r < 64; ++r) {
             const int soff = (int)((((uint32_t)X::RL * r * (uint32_t)bits) << (p - 5)) * 4u);
             const uint32_t w0 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, soff, 0);
-            const uint32_t w1 = (bits == 3) ? __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0) : 0u;
+            const uint32_t w1 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0);    // always: no branch per value
             const uint32_t low = code_at(w0, w1, shift, bits);
-            const uint32_t hb = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, (int)voffb, (int)((((uint32_t)X::RL * r) << (p - 5)) * 2u), 0);
+            const uint32_t hb = buf_load_half(rb, voffb, (((uint32_t)X::RL * r) << (p - 5)) * 2u);
             const uint32_t offs = __builtin_amdgcn_readlane(both, r) >> (16u * (lane >> 5));
             const bool up = ((offs >> (col >> 1)) & 1u) == (col & 1u);
             const uint32_t top = (hb >> (col >> 1)) & 1u;
