@@ -365,10 +365,14 @@ __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t ke
         const uint32_t voff = (lbits >> 5) * 4u, shift = lbits & 31u;
         const uint32_t mag = __float_as_uint(tb[1]);
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)r * (uint32_t)bits) << (p - 5)) * 4u), 0);
-            const uint32_t idx = (w >> shift) & ((1u << bits) - 1u);
-            v[r] = (bits == 1) ? __uint_as_float(mag | ((~idx & 1u) << 31)) : tb[idx];
+        for (int r = 0; r < R; ++r)                              // all loads first, no choice per value in between
+            v[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, (int)((((uint32_t)r * (uint32_t)bits) << (p - 5)) * 4u), 0));
+        if (bits == 1) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) v[r] = __uint_as_float(mag | ((~(__float_as_uint(v[r]) >> shift) & 1u) << 31));
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) v[r] = tb[(__float_as_uint(v[r]) >> shift) & ((1u << bits) - 1u)];
         }
     }
     if (B.bitmap[c]) {
@@ -452,41 +456,57 @@ __global__ __launch_bounds__(256) void k_enc_wide_last(EncBatch B, uint64_t vali
     }
     wave_lds_sync();
     float ip = 0.0f;
+    // the choice of the budget sits outside the loops over the 16 groups (group = this lane's 4 coordinates of a row half)
+    auto for_groups = [&](auto &&pack) {
 #pragma unroll
-    for (int r = 0; r < kWideRows; ++r) {
+        for (int r = 0; r < kWideRows; ++r)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t group = (base + 256u * h + ((uint32_t)r << p)) / 4u + lane;   // this lane's 4 coordinates
+            for (int h = 0; h < 2; ++h) pack((base + 256u * h + ((uint32_t)r << p)) / 4u + lane, r, h);
+    };
+    if (b_q8 == 256u) {                                          // I_1: the index is the sign, |Q| = q_1
+        for_groups([&](uint32_t group, int r, int h) {
+            float sa = 0.0f;
             uint32_t word = 0;
-            if (b_q8 == 256u) {                                  // I_1: the index is the sign, |Q| = q_1
-                float sa = 0.0f;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    sa += fabsf(v[r][4 * h + e]);
-                    word |= ((~__float_as_uint(v[r][4 * h + e])) >> 31) << e;        // index 1 = non-negative
-                }
-                ip = fmaf(sa, kQ1, ip);
-                word |= wide_lane_xor1(word) << 4;               // two lanes = one byte
-                if (!(lane & 1u)) reinterpret_cast<uint8_t *>(payload)[group >> 1] = (uint8_t)word;
-            } else if (b_q8 == 512u) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) word |= quantize_one<2>(v[r][4 * h + e], sc, qtab, ip) << (2 * e);
-                reinterpret_cast<uint8_t *>(payload)[group] = (uint8_t)word;
-            } else if (grid_q15(b_q8)) {                          // uniform grid: one byte per coordinate
-#pragma unroll
-                for (int e = 0; e < 4; ++e) word |= quantize_byte<true>(v[r][4 * h + e], 0u, sc->grid_inv, gtab, ip) << (8 * e);
-                reinterpret_cast<uint32_t *>(payload)[group] = word;
-            } else if (wide_bits(b_q8)) {                         // b = 5..8: one byte per coordinate
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    word |= quantize_byte<false>(v[r][4 * h + e], wide_half_levels(b_q8), 0.0f, gtab, ip) << (8 * e);
-                reinterpret_cast<uint32_t *>(B.codes[c] ? reinterpret_cast<char *>(B.codes[c]) : payload)[group] = word;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) word |= quantize_one<8>(v[r][4 * h + e], sc, qtab, ip) << (4 * e);
-                reinterpret_cast<uint16_t *>(payload)[group] = (uint16_t)word;
+            for (int e = 0; e < 4; ++e) {
+                sa += fabsf(v[r][4 * h + e]);
+                word |= ((~__float_as_uint(v[r][4 * h + e])) >> 31) << e;            // index 1 = non-negative
             }
-        }
+            ip = fmaf(sa, kQ1, ip);
+            word |= wide_lane_xor1(word) << 4;                   // two lanes = one byte
+            if (!(lane & 1u)) reinterpret_cast<uint8_t *>(payload)[group >> 1] = (uint8_t)word;
+        });
+    } else if (b_q8 == 512u) {
+        for_groups([&](uint32_t group, int r, int h) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) word |= quantize_one<2>(v[r][4 * h + e], sc, qtab, ip) << (2 * e);
+            reinterpret_cast<uint8_t *>(payload)[group] = (uint8_t)word;
+        });
+    } else if (grid_q15(b_q8)) {                                  // uniform grid: one byte per coordinate
+        const float inv = sc->grid_inv;
+        for_groups([&](uint32_t group, int r, int h) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) word |= quantize_byte<true>(v[r][4 * h + e], 0u, inv, gtab, ip) << (8 * e);
+            reinterpret_cast<uint32_t *>(payload)[group] = word;
+        });
+    } else if (wide_bits(b_q8)) {                                 // b = 5..8: one byte per coordinate
+        const uint32_t H = wide_half_levels(b_q8);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(B.codes[c] ? reinterpret_cast<char *>(B.codes[c]) : payload);
+        for_groups([&](uint32_t group, int r, int h) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) word |= quantize_byte<false>(v[r][4 * h + e], H, 0.0f, gtab, ip) << (8 * e);
+            dst[group] = word;
+        });
+    } else {
+        for_groups([&](uint32_t group, int r, int h) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) word |= quantize_one<8>(v[r][4 * h + e], sc, qtab, ip) << (4 * e);
+            reinterpret_cast<uint16_t *>(payload)[group] = (uint16_t)word;
+        });
     }
     const double block_total = block_sum<256>((double)ip, red);
     if (threadIdx.x == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
@@ -511,31 +531,50 @@ __global__ __launch_bounds__(256) void k_dec_wide_first(DecBatch B, uint64_t kee
     const char *payload = static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES;
     const char *bytes = B.codes[c] ? reinterpret_cast<const char *>(B.codes[c]) : payload;
     const uint32_t *bm = B.bitmap[c];
-    float v[kWideRows][8];
+    // which of the 8 rows arrived (wave-uniform), then all payload loads, then the table look-ups: the choice of the
+    // budget sits outside the loops so that the loads are issued back to back
+    uint32_t here = 0xFFu;
+    if (bm) {
+        here = 0;
 #pragma unroll
-    for (int r = 0; r < kWideRows; ++r) {
-        const uint32_t first = base + ((uint32_t)r << p);
-        const uint32_t pk = first >> 10;
-        const bool here = bm ? ((bm[pk >> 5] >> (pk & 31u)) & 1u) != 0u : true;       // wave-uniform
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t group = (first + 256u * h) / 4u + lane;                   // this lane's 4 coordinates
-            uint32_t word;
-            if (b_q8 == 256u) word = (uint32_t)reinterpret_cast<const uint8_t *>(payload)[group >> 1] >> (4u * (lane & 1u));
-            else if (b_q8 == 512u) word = reinterpret_cast<const uint8_t *>(payload)[group];
-            else if (byte_budget(b_q8)) word = reinterpret_cast<const uint32_t *>(bytes)[group];
-            else word = reinterpret_cast<const uint16_t *>(payload)[group];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float val;
-                if (b_q8 == 256u) val = tb[(word >> e) & 1u];
-                else if (b_q8 == 512u) val = tb[(word >> (2 * e)) & 3u];
-                else if (grid_q15(b_q8)) val = dequantize_byte<true>((word >> (8 * e)) & 0xFFu, 0u, gtabs[wv]);
-                else if (wide_bits(b_q8)) val = dequantize_byte<false>((word >> (8 * e)) & 0xFFu, wide_half_levels(b_q8), gtabs[wv]);
-                else val = tb[(word >> (4 * e)) & 15u];
-                v[r][4 * h + e] = here ? val : 0.0f;
-            }
+        for (int r = 0; r < kWideRows; ++r) {
+            const uint32_t pk = (base + ((uint32_t)r << p)) >> 10;
+            here |= ((bm[pk >> 5] >> (pk & 31u)) & 1u) << r;
         }
+    }
+    float v[kWideRows][8];
+    uint32_t word[kWideRows][2];
+    auto for_groups = [&](auto &&fetch) {                        // group = this lane's 4 coordinates of (row, half)
+#pragma unroll
+        for (int r = 0; r < kWideRows; ++r)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) word[r][h] = fetch((base + ((uint32_t)r << p) + 256u * h) / 4u + lane);
+    };
+    auto for_values = [&](auto &&value) {
+#pragma unroll
+        for (int r = 0; r < kWideRows; ++r)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[r][4 * h + e] = ((here >> r) & 1u) ? value(word[r][h], e) : 0.0f;
+    };
+    const float *gt = gtabs[wv];
+    if (b_q8 == 256u) {
+        for_groups([&](uint32_t g) { return (uint32_t)reinterpret_cast<const uint8_t *>(payload)[g >> 1] >> (4u * (lane & 1u)); });
+        for_values([&](uint32_t w, int e) { return tb[(w >> e) & 1u]; });
+    } else if (b_q8 == 512u) {
+        for_groups([&](uint32_t g) { return (uint32_t)reinterpret_cast<const uint8_t *>(payload)[g]; });
+        for_values([&](uint32_t w, int e) { return tb[(w >> (2 * e)) & 3u]; });
+    } else if (grid_q15(b_q8)) {
+        for_groups([&](uint32_t g) { return reinterpret_cast<const uint32_t *>(bytes)[g]; });
+        for_values([&](uint32_t w, int e) { return dequantize_byte<true>((w >> (8 * e)) & 0xFFu, 0u, gt); });
+    } else if (wide_bits(b_q8)) {
+        const uint32_t H = wide_half_levels(b_q8);
+        for_groups([&](uint32_t g) { return reinterpret_cast<const uint32_t *>(bytes)[g]; });
+        for_values([&](uint32_t w, int e) { return dequantize_byte<false>((w >> (8 * e)) & 0xFFu, H, gt); });
+    } else {
+        for_groups([&](uint32_t g) { return (uint32_t)reinterpret_cast<const uint16_t *>(payload)[g]; });
+        for_values([&](uint32_t w, int e) { return tb[(w >> (4 * e)) & 15u]; });
     }
     wide_fwht(v);
     const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), (uint32_t)(keep_elems * 4));
