@@ -955,35 +955,66 @@ __global__ __launch_bounds__(256) void k_sparse_scatter_batch(DecBatch B, uint32
     if (i < d) acc[i] += sum;
 }
 // b = 5, 6, 7: the one-byte indices of a sender, in coordinate order, to the payload's bit string (index j in bits
-// j b .. j b + b - 1, Sec. 2.2.1 message; one thread per payload word) and back (one thread per index).
+// j b .. j b + b - 1, Sec. 2.2.1 message) and back.  A thread handles 32 indices = 32 bytes = b payload words.
+template <int BITS>
+__device__ inline void pack32(const uint8_t *codes, uint32_t *words) {
+    uint32_t in[8];
+    const uint4 lo = reinterpret_cast<const uint4 *>(codes)[0], hi = reinterpret_cast<const uint4 *>(codes)[1];
+    in[0] = lo.x; in[1] = lo.y; in[2] = lo.z; in[3] = lo.w; in[4] = hi.x; in[5] = hi.y; in[6] = hi.z; in[7] = hi.w;
+    uint32_t out[BITS];
+#pragma unroll
+    for (int w = 0; w < BITS; ++w) out[w] = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        const uint32_t code = (in[j >> 2] >> (8 * (j & 3))) & ((1u << BITS) - 1u);
+        const int pos = j * BITS;
+        out[pos >> 5] |= code << (pos & 31);
+        if ((pos & 31) + BITS > 32) out[(pos >> 5) + 1] |= code >> (32 - (pos & 31));
+    }
+#pragma unroll
+    for (int w = 0; w < BITS; ++w) words[w] = out[w];
+}
+template <int BITS>
+__device__ inline void unpack32(const uint32_t *words, uint8_t *codes) {
+    uint32_t in[BITS + 1];
+#pragma unroll
+    for (int w = 0; w < BITS; ++w) in[w] = words[w];
+    in[BITS] = 0;
+    uint32_t out[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) out[q] = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        const int pos = j * BITS;
+        const uint32_t code = code_at(in[pos >> 5], in[(pos >> 5) + 1], (uint32_t)(pos & 31), BITS);
+        out[j >> 2] |= code << (8 * (j & 3));
+    }
+    reinterpret_cast<uint4 *>(codes)[0] = make_uint4(out[0], out[1], out[2], out[3]);
+    reinterpret_cast<uint4 *>(codes)[1] = make_uint4(out[4], out[5], out[6], out[7]);
+}
 __global__ __launch_bounds__(256) void k_pack_bits(EncBatch B, int log2D) {
     const uint32_t c = blockIdx.y;
     const uint8_t *codes = B.codes[c];
     if (!codes) return;
+    const uint64_t g = (uint64_t)blockIdx.x * 256u + threadIdx.x;        // group of 32 indices
+    if (g >= (1ull << log2D) / 32) return;
     const uint32_t bits = wide_bits(B.b_q8[c]);
-    const uint64_t words = (((uint64_t)bits << log2D) + 31) >> 5;
-    const uint64_t w = (uint64_t)blockIdx.x * 256u + threadIdx.x;
-    if (w >= words) return;
-    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const uint64_t lo = 32 * w, D = 1ull << log2D;
-    uint32_t word = 0;
-    for (uint64_t j = lo / bits; j < D && j * bits < lo + 32; ++j) {
-        const int64_t pos = (int64_t)(j * bits) - (int64_t)lo;   // where index j starts inside this word (may be negative)
-        const uint32_t code = codes[j];
-        word |= pos >= 0 ? code << pos : code >> (-pos);
-    }
-    payload[w] = word;
+    uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES) + g * bits;
+    if (bits == 5) pack32<5>(codes + 32 * g, payload);
+    else if (bits == 6) pack32<6>(codes + 32 * g, payload);
+    else pack32<7>(codes + 32 * g, payload);
 }
 __global__ __launch_bounds__(256) void k_unpack_bits(DecBatch B, int log2D, uint8_t *codes_all) {
     const uint32_t c = blockIdx.y;
     if (!B.codes[c]) return;
+    const uint64_t g = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (g >= (1ull << log2D) / 32) return;
     const uint32_t bits = wide_bits(B.b_q8[c]);
-    const uint64_t j = (uint64_t)blockIdx.x * 256u + threadIdx.x, D = 1ull << log2D;
-    if (j >= D) return;
-    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const uint64_t words = (((uint64_t)bits << log2D) + 31) >> 5, pos = j * bits, w0 = pos >> 5;
-    const uint32_t next = (w0 + 1 < words) ? payload[w0 + 1] : 0u;
-    codes_all[((size_t)c << log2D) + j] = (uint8_t)code_at(payload[w0], next, (uint32_t)(pos & 31u), (int)bits);
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES) + g * bits;
+    uint8_t *codes = codes_all + ((size_t)c << log2D) + 32 * g;
+    if (bits == 5) unpack32<5>(payload, codes);
+    else if (bits == 6) unpack32<6>(payload, codes);
+    else unpack32<7>(payload, codes);
 }
 __global__ __launch_bounds__(256) void k_fill_zero(float *p, uint64_t count) {
     const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
@@ -1336,12 +1367,13 @@ void launch_sparse_scatter_batch(const DecBatch &B, uint32_t n, uint64_t d, uint
     const uint32_t blocks = (uint32_t)((d + 63) / 64);
     hipLaunchKernelGGL(k_sparse_scatter_batch, dim3((blocks + 3) / 4), dim3(256), 0, st, B, n, d, m, seed, T, log2Dk, acc);
 }
-void launch_pack_bits(const EncBatch &B, uint32_t n, int log2D, hipStream_t st) {
-    const uint64_t words = ((7ull << log2D) + 31) >> 5;          // the widest of b = 5, 6, 7
-    hipLaunchKernelGGL(k_pack_bits, dim3((uint32_t)((words + 255) / 256), n), dim3(256), 0, st, B, log2D);
+void launch_pack_bits(const EncBatch &B, uint32_t n, int log2D, hipStream_t st) {          // multi-pass sizes: D >= 2^13
+    const uint64_t groups = (1ull << log2D) / 32;
+    hipLaunchKernelGGL(k_pack_bits, dim3((uint32_t)((groups + 255) / 256), n), dim3(256), 0, st, B, log2D);
 }
 void launch_unpack_bits(const DecBatch &B, uint32_t n, int log2D, uint8_t *codes_all, hipStream_t st) {
-    hipLaunchKernelGGL(k_unpack_bits, dim3((uint32_t)(((1ull << log2D) + 255) / 256), n), dim3(256), 0, st, B, log2D, codes_all);
+    const uint64_t groups = (1ull << log2D) / 32;
+    hipLaunchKernelGGL(k_unpack_bits, dim3((uint32_t)((groups + 255) / 256), n), dim3(256), 0, st, B, log2D, codes_all);
 }
 void launch_fill_zero(float *p, uint64_t count, hipStream_t st) {
     hipLaunchKernelGGL(k_fill_zero, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st, p, count);
