@@ -61,14 +61,14 @@ uint64_t round_up(uint64_t d, int bits) { return ((d + (1ull << bits) - 1) >> bi
 struct HiPass {
     bool wg;    // workgroup-tile kernel (32-column tiles) or wave-tile kernel (64-column tiles)
     int M, p;   // bits transformed, lowest bit
-    bool wide;  // wave-tile kernel with 8 columns per lane (top pass of the three-pass sizes, b = 1, 2, 4)
+    bool wide;  // wave-tile kernel with 8 columns per lane (top pass of the three-pass sizes; b = 1, 2, 4, 5..8, grid)
 };
 struct Plan {
     int lo_bits;        // 0: single-workgroup path (D <= 4096)
     int nhi;
     HiPass hi[2];       // ascending p
 };
-// `wide_ok`: every sender of the launch has b = 1, 2, 4 or a uniform-grid budget (what the wide top tile packs).
+// `wide_ok`: every sender of the launch has b = 1, 2, 4 or a one-byte budget (what the wide top tile packs).
 Plan make_plan(int log2D, bool wide_ok) {
     Plan pl{};
     if (log2D <= kLoBits) return pl;

@@ -20,7 +20,8 @@ uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d, int pre,
 uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, int p, uint64_t seed,
                             const float *T, double *partials, uint32_t partial_stride, const EncScratch *scratch,
                             hipStream_t st);
-// wide strided tiles (8 rows x 512 columns per wave) for the top three index bits of D >= 2^25, b = 1, 2, 4
+// wide strided tiles (8 rows x 512 columns per wave) for the top three index bits of D >= 2^25; b = 1, 2, 4, 5..8 and
+// the uniform grid
 uint32_t launch_enc_wide_last(const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, const float *T, double *partials,
                               uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
 void launch_dec_wide_first(const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, const DecScratch *scratch, float *T,

@@ -394,7 +394,8 @@ __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t ke
 }
 
 // ------------------------------------------------------------------------------------------------
-// Wide strided tiles for the top three index bits of the three-pass sizes (D >= 2^25), budgets b = 1, 2, 4:
+// Wide strided tiles for the top three index bits of the three-pass sizes (D >= 2^25), budgets b = 1, 2, 4 and the
+// one-byte budgets (b = 5..8, uniform grid):
 // a wave owns 8 rows of 512 consecutive coordinates at stride 2^p (p = log2 D - 3).  A lane holds, of every row,
 // the columns 4 l .. 4 l + 3 and 256 + 4 l .. 256 + 4 l + 3: each workspace access of a wave is then one dense
 // kilobyte (16 bytes per lane, no gaps; with 8 adjacent columns per lane the two halves of every 128-byte line
