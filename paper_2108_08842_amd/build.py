@@ -2,10 +2,12 @@
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libeden_hip.so")
+OBJ_DIR = os.path.join(ROOT, "_build")
 SOURCES = ["eden_tables.cpp", "eden_kernels.hip", "eden_kernels_wg.hip", "eden_kernels_lo14.hip", "eden_api.hip"]
 
 
@@ -16,24 +18,45 @@ def hipcc_path() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = True) -> str:
-    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           # packed fp32 instructions are kept off on the test machines
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG, "csrc")]
-    cmd += [os.path.join(PKG, "csrc", s) for s in SOURCES]
-    cmd += ["-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (proc.stdout + proc.stderr).splitlines() if "packed-fp32-ops" not in l)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+    return out
+
+
+def _stale(src: str, obj: str) -> bool:
+    if not os.path.exists(obj):
+        return True
+    csrc = os.path.join(PKG, "csrc")
+    deps = [src, os.path.join(ROOT, "include", "eden.h")] + [os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith(".h")]
+    return any(os.path.getmtime(dep) > os.path.getmtime(obj) for dep in deps)
+
+
+def build(verbose: bool = True, incremental: bool = False) -> str:
+    """Compiles every source to an object file (in parallel, one hipcc each) and links the shared library.
+    `incremental`: skip sources whose object file is newer than the source and every header."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    common = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+              # packed fp32 instructions are kept off on this hardware pool
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG, "csrc")]
+    objs = [os.path.join(OBJ_DIR, s + ".o") for s in SOURCES]
+    cmds = [common + ["-c", os.path.join(PKG, "csrc", s), "-o", o] for s, o in zip(SOURCES, objs)
+            if not incremental or _stale(os.path.join(PKG, "csrc", s), o)]
+    with ThreadPoolExecutor(max(1, len(cmds))) as pool:
+        outs = list(pool.map(lambda c: _run(c, verbose), cmds))
+    outs.append(_run([hipcc_path(), "--offload-arch=gfx950", "-fPIC", "-shared"] + objs + ["-o", LIB], verbose))
+    if verbose:
+        text = "\n".join(o for o in outs if o.strip())
+        if text:
+            print(text)
     return LIB
 
 
 if __name__ == "__main__":
-    build()
+    build(incremental="--incremental" in sys.argv)
     sys.exit(0)
