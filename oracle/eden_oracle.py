@@ -58,7 +58,7 @@ _M2 = 0x94D049BB133111EB
 STREAM_SIGN = 0        # Rademacher diagonal of the rotation
 STREAM_SUBSAMPLE = 1   # which coordinate of each group is kept when b < 1
 STREAM_LOSS = 2        # Bernoulli packet drops (test helper)
-STREAM_MIX = 3         # which coordinate of each pair gets the extra bit when b is k + 1/2
+STREAM_MIX = 3         # which coordinates get the extra bit when b > 1 is not an integer
 STREAM_SPARSE = 4      # sort keys of the m-of-64 sparsification before the rotation (b = m/64)
 
 PACKET_COORDS = 1024   # reading: a packet is 1024 consecutive rotated coordinates
@@ -129,6 +129,19 @@ def mix_offsets(seed: int, client: int, n_pairs: int) -> np.ndarray:
     message has exactly (k + 1/2) D bits and every position in it is known without a scan."""
     key = stream_key(seed, STREAM_MIX, client)
     return _bits_of_words(hash_words(key, 0, (n_pairs + 63) // 64), n_pairs)
+
+
+def coin_bits(seed: int, client: int, D: int, frac_q8: int) -> np.ndarray:
+    """For a general non-integer budget b > 1 (Sec. 4.1, super-bit compression): True at the coordinates that are
+    quantized with I_{floor(b)+1}.  The paper simulates an independent coin of probability b - floor(b) per
+    coordinate from the shared randomness.  reading: the coin of coordinate i is the byte (i & 7) of word (i >> 3)
+    of the MIX stream, and the coordinate gets the extra bit iff that byte is below frac_q8 = 256 (b - floor(b)),
+    so budgets are resolved in steps of 1/256 bit."""
+    key = stream_key(seed, STREAM_MIX, client)
+    words = hash_words(key, 0, (D + 7) // 8)
+    shifts = np.uint64(8) * np.arange(8, dtype=np.uint64)
+    coins = ((words[:, None] >> shifts[None, :]) & np.uint64(0xFF)).reshape(-1)[:D]
+    return coins < np.uint64(frac_q8)
 
 
 def n_packets(D: int) -> int:
@@ -410,9 +423,22 @@ def sparse_selection(seed: int, client: int, d: int, m: int) -> np.ndarray:
     return (kept + np.arange(nblk)[:, None] * SPARSE_BLOCK).reshape(-1)
 
 
+COIN = 0x40000           # flag in b_q8: general non-integer b = (b_q8 & 0xFFFF) / 256 in (1, 4), one coin per coordinate
+
+
+def fractional(b_q8: int) -> bool:
+    """Sec. 4.1, super-bit compression with a non-integer budget, in the paper's own form: every coordinate uses
+    I_{floor(b)+1} with probability b - floor(b), independently (see coin_bits), so the message length is random.
+    floor(b) = 1, 2, 3 (the finer table is at most I_4)."""
+    low = b_q8 & 0xFFFF
+    return (b_q8 & ~0xFFFF) == COIN and 256 < low < 1024 and low % 256 != 0
+
+
 def budget(b_q8: int):
-    """-> (bits per kept coordinate, keep-one-in-k).  For b = k + 1/2 the bits are k (every coordinate
-    has k bits in the first part of the payload; see mixed())."""
+    """-> (bits per kept coordinate, keep-one-in-k).  For non-integer b > 1 the bits are floor(b) (every coordinate
+    has floor(b) bits in the first part of the payload; see mixed() and fractional())."""
+    if fractional(b_q8):
+        return (b_q8 & 0xFFFF) // 256, 1
     if b_q8 >= 256 and b_q8 % 256 == 0 and b_q8 // 256 <= 8:
         return b_q8 // 256, 1
     if b_q8 == 128:
@@ -443,6 +469,19 @@ def payload_words(D: int, b_q8: int) -> int:
     """uint32 words of payload."""
     a, b = plane_words(D, b_q8)
     return a + b
+
+
+def plane_words_fractional(D: int, b_q8: int, extra_bits: int):
+    """-> (words of the floor(b)-bit index part, words of the extra-bit part) of a general non-integer budget;
+    `extra_bits`: how many coordinates carry the extra bit.  Each part is rounded up to two words (reading)."""
+    k, _ = budget(b_q8)
+    return 2 * ((D * k + 63) // 64), 2 * ((extra_bits + 63) // 64)
+
+
+def payload_words_fractional(D: int, b_q8: int, seed: int, client: int) -> int:
+    """uint32 words of payload of a general non-integer budget: fixed by the coins alone (never by the data)."""
+    up = coin_bits(seed, client, D, b_q8 & 0xFF)
+    return sum(plane_words_fractional(D, b_q8, int(up.sum())))
 
 
 def pack_indices(idx: np.ndarray, bits: int, n_words: int) -> np.ndarray:
@@ -487,27 +526,36 @@ class Message:
     IP: float
     seed: int
     payload: np.ndarray = field(repr=False)
+    extra_bits: int = 0    # general non-integer budgets: coordinates that carry the extra bit (length of the second part)
 
     def to_bytes(self) -> bytes:
         import struct
         head = struct.pack("<IIQIIIIdddQ", MAGIC, self.log2D, self.d, self.b_q8, self.client,
-                           self.status, 0, self.S, self.N2, self.IP, self.seed & _MASK64)
+                           self.status, self.extra_bits, self.S, self.N2, self.IP, self.seed & _MASK64)
         assert len(head) == HEADER_BYTES
         return head + self.payload.astype("<u4").tobytes()
 
     @staticmethod
     def from_bytes(buf: bytes) -> "Message":
         import struct
-        magic, log2D, d, b_q8, client, status, _r, S, N2, IP, seed = struct.unpack(
+        magic, log2D, d, b_q8, client, status, extra, S, N2, IP, seed = struct.unpack(
             "<IIQIIIIdddQ", buf[:HEADER_BYTES])
         if magic != MAGIC:
             raise ValueError("bad magic")
-        nw = payload_words(1 << log2D, 2048 if grid_delta(b_q8) else 256 if (pre_rotation(b_q8) or sparse_m(b_q8)) else b_q8)
+        if fractional(b_q8):
+            nw = sum(plane_words_fractional(1 << log2D, b_q8, extra))
+        else:
+            nw = payload_words(1 << log2D, 2048 if grid_delta(b_q8) else 256 if (pre_rotation(b_q8) or sparse_m(b_q8)) else b_q8)
         payload = np.frombuffer(buf, dtype="<u4", count=nw, offset=HEADER_BYTES).copy()
-        return Message(log2D, d, b_q8, client, status, S, N2, IP, seed, payload)
+        return Message(log2D, d, b_q8, client, status, S, N2, IP, seed, payload, extra)
 
 
 def message_bytes(d: int, b_q8: int) -> int:
+    """Bytes a buffer must have for one message; for a general non-integer budget the capacity that fits any outcome of
+    the coins (the transmitted length is fixed by the coins and stands in the header)."""
+    if fractional(b_q8):
+        D = padded_dim(d)
+        return HEADER_BYTES + 4 * sum(plane_words_fractional(D, b_q8, D))
     if grid_delta(b_q8):
         return HEADER_BYTES + 4 * payload_words(padded_dim(d), 2048)
     if sparse_m(b_q8):
@@ -588,6 +636,43 @@ def unpack_mixed(payload: np.ndarray, D: int, b_q8: int, up: np.ndarray) -> np.n
     return idx
 
 
+def _encode_fractional(y, N2, d, D, b_q8, seed, client, want_trace):
+    """General non-integer b > 1 (Sec. 4.1): coordinate i is quantized with I_{k+1}, k = floor(b), if its coin says so
+    (probability b - k), else with I_k; S = |x|^2 / <R(x), Q> with that coordinate-wise Q (Sec. 2.3).
+    reading of the layout: first the low k bits of every coordinate's index, packed as for budget k; then one bit for
+    every coordinate with a coin, in coordinate order: the top bit of its (k+1)-bit index."""
+    k, _ = budget(b_q8)
+    t_lo, c_lo = tables(k)
+    t_hi, c_hi = tables(k + 1)
+    eta = math.sqrt(D) / math.sqrt(N2)
+    z = eta * y
+    up = coin_bits(seed, client, D, b_q8 & 0xFF)
+    idx = np.where(up, quantize_indices(z, t_hi), quantize_indices(z, t_lo))
+    Q = np.where(up, c_hi[np.minimum(idx, c_hi.size - 1)], c_lo[np.minimum(idx, c_lo.size - 1)])
+    IP = float(np.dot(y, Q))
+    S = N2 / IP
+    extra = int(up.sum())
+    wa, wb = plane_words_fractional(D, b_q8, extra)
+    low = idx & ((1 << k) - 1)
+    top = (idx[up] >> k) & 1
+    payload = np.concatenate([pack_indices(low, k, wa), pack_indices(top, 1, wb)])
+    msg = Message(D.bit_length() - 1, d, b_q8, client, 0, S, N2, IP, seed, payload, extra)
+    if want_trace:
+        return msg, EncodeTrace(z=z, idx=idx, kept=np.arange(D), up=up)
+    return msg
+
+
+def unpack_fractional(payload: np.ndarray, D: int, b_q8: int, up: np.ndarray) -> np.ndarray:
+    """The per-coordinate indices of a general non-integer budget's payload (k+1 bits wide where `up`, else k)."""
+    k, _ = budget(b_q8)
+    extra = int(up.sum())
+    wa, wb = plane_words_fractional(D, b_q8, extra)
+    idx = unpack_indices(payload[:wa], k, D)
+    top = unpack_indices(payload[wa:wa + wb], 1, extra)
+    idx[up] |= top << k
+    return idx
+
+
 def sparsify_pairs(x: np.ndarray, seed: int, client: int):
     """(1/p) m o x with p = 1/2, compacted: element g is 2 x[2g + off_g] (0 beyond the end of x).
     Sec. 4.1 random sparsification; its expectation over the offsets is x scattered back."""
@@ -626,16 +711,17 @@ def encode(x: np.ndarray, seed: int, client: int, b_q8: int, want_trace: bool = 
     bits, k = budget(b_q8)
     if D < k:
         raise ValueError("sub-bit budget needs at least one whole group of coordinates")
-    nw = payload_words(D, b_q8)
+    extra = int(coin_bits(seed, client, D, b_q8 & 0xFF).sum()) if fractional(b_q8) else 0
+    nw = sum(plane_words_fractional(D, b_q8, extra)) if fractional(b_q8) else payload_words(D, b_q8)
 
     N2 = float(np.dot(x, x))                       # |x|^2  (= |R(x)|^2, Sec. 2.2.1)
     if not math.isfinite(N2):
         msg = Message(D.bit_length() - 1, d, b_q8, client, STATUS_NONFINITE, 0.0, N2, 0.0, seed,
-                      np.zeros(nw, np.uint32))
+                      np.zeros(nw, np.uint32), extra)
         return (msg, None) if want_trace else msg
     if N2 == 0.0:                                  # the x = 0 case the paper sets aside (Sec. 2.1 footnote)
         msg = Message(D.bit_length() - 1, d, b_q8, client, STATUS_ZERO_VECTOR, 0.0, 0.0, 0.0, seed,
-                      np.zeros(nw, np.uint32))
+                      np.zeros(nw, np.uint32), extra)
         return (msg, None) if want_trace else msg
 
     y = rotate(x, seed, client)                    # R(x)
@@ -654,6 +740,8 @@ def encode(x: np.ndarray, seed: int, client: int, b_q8: int, want_trace: bool = 
         return (msg, EncodeTrace(z=z, idx=idx, kept=np.arange(D))) if want_trace else msg
     if mixed(b_q8):
         return _encode_mixed(y, N2, d, D, bits, b_q8, seed, client, want_trace)
+    if fractional(b_q8):
+        return _encode_fractional(y, N2, d, D, b_q8, seed, client, want_trace)
     z, idx, Q, IP, S = quantize_and_scale(y, N2, bits)
 
     if k == 1:
@@ -694,9 +782,13 @@ def decode_rotated(msg: Message, bitmap: np.ndarray | None = None) -> np.ndarray
         yhat[arrived] = (msg.S / (count / D)) * Q[arrived]
         return yhat
     _, centroids = tables(bits)
-    if mixed(msg.b_q8):
-        up = upgraded_mask(msg.seed, msg.client, D)
-        idx = unpack_mixed(msg.payload, D, msg.b_q8, up)
+    if mixed(msg.b_q8) or fractional(msg.b_q8):
+        if mixed(msg.b_q8):
+            up = upgraded_mask(msg.seed, msg.client, D)
+            idx = unpack_mixed(msg.payload, D, msg.b_q8, up)
+        else:
+            up = coin_bits(msg.seed, msg.client, D, msg.b_q8 & 0xFF)
+            idx = unpack_fractional(msg.payload, D, msg.b_q8, up)
         _, c_hi = tables(bits + 1)
         Q = np.where(up, c_hi[np.minimum(idx, c_hi.size - 1)], centroids[np.minimum(idx, centroids.size - 1)])
         arrived = np.repeat(bitmap_to_packet_flags(bitmap, D), min(D, PACKET_COORDS))[:D]

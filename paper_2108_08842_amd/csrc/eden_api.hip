@@ -29,9 +29,8 @@ struct eden_ctx {
     uint32_t dec_partial_tiles;  // its size in tiles of 2^14 floats
     uint32_t *hist;              // 256 counters for eden_index_entropy
     uint8_t *codes;              // slots * D_max bytes: one-byte indices of b = 5, 6, 7 senders before packing / after
-                                 // unpacking; allocated by the first call that uses such a budget at a multi-pass size
-    float *stage;                // d_max + 64 floats: the kept coordinates of one sender with a budget b = m/64;
-                                 // allocated by the first call that uses such a budget
+                                 // unpacking (multi-pass sizes only)
+    float *stage;                // d_max + 64 floats: the kept coordinates of one sender with a budget b = m/64
     EncScratch *enc_scratch; // slots
     DecScratch *dec_scratch; // slots
     DevTables *tables;
@@ -151,8 +150,11 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     ctx->compute_units = (uint32_t)cus;
 
     bool ok = true;
-    if (ctx->log2D_max > kLoBits)
+    if (ctx->log2D_max > kLoBits) {
         ok = ok && hipMalloc(&ctx->T, (size_t)ctx->slots * D_max * sizeof(float)) == hipSuccess;
+        ok = ok && hipMalloc(&ctx->codes, (size_t)ctx->slots * D_max) == hipSuccess;
+    }
+    ok = ok && hipMalloc(&ctx->stage, (size_t)(d_max + 64) * sizeof(float)) == hipSuccess;
     if (ctx->log2D_max >= 19 && ctx->slots > 1) {                // at most as many split tiles as workgroups fit on the chip
         ctx->dec_partial_tiles = 2 * ctx->compute_units;
         ok = ok && hipMalloc(&ctx->dec_partial, ((size_t)ctx->dec_partial_tiles << 14) * sizeof(float)) == hipSuccess;
@@ -200,10 +202,6 @@ int eden_destroy(eden_ctx *ctx) {
     return ok ? EDEN_OK : EDEN_ERR_HIP;
 }
 
-static bool ensure_codes(eden_ctx *ctx) {
-    if (ctx->codes) return true;
-    return hipMalloc(&ctx->codes, (size_t)ctx->slots << ctx->log2D_max) == hipSuccess;
-}
 static bool packs_bytes(uint32_t b_q8) { return wide_bits(b_q8) >= 5u && wide_bits(b_q8) <= 7u; }
 
 // Encodes n senders whose transformed vectors all have the same dimension.  `b_kernel`: the budgets the kernels
@@ -233,7 +231,6 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
         bool pack = false;                                       // b = 5, 6, 7: bytes first, packed by a kernel of its own
         if (pl.lo_bits != 0) {
             for (uint32_t i = 0; i < nb; ++i) pack = pack || packs_bytes(B.b_q8[i]);
-            if (pack && !ensure_codes(ctx)) return EDEN_ERR_HIP;
             for (uint32_t i = 0; i < nb; ++i)
                 if (packs_bytes(B.b_q8[i])) B.codes[i] = ctx->codes + ((size_t)i << log2D);
         }
@@ -294,29 +291,31 @@ static int sparsify_mode(const uint32_t *b_q8, uint32_t n) {
     if (sp == n) return 2;
     return -1;
 }
-static bool ensure_stage(eden_ctx *ctx) {
-    if (ctx->stage) return true;
-    return hipMalloc(&ctx->stage, (size_t)(ctx->d_max + 64) * sizeof(float)) == hipSuccess;
-}
 
-int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8, uint32_t n,
-                uint64_t d, uint64_t seed, void *const *msgs_dev, const size_t *msg_capacity, void *stream) {
-    if (!ctx || !x_dev || !client_ids || !b_q8 || !msgs_dev || !msg_capacity) return EDEN_ERR_INVALID_ARG;
-    if (n == 0 || n > ctx->n_max || d == 0 || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
+// Argument checks of eden_encode that do not depend on a context.
+static int check_encode_args(const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8, uint32_t n, uint64_t d,
+                             void *const *msgs_dev, const size_t *msg_capacity) {
+    if (!x_dev || !client_ids || !b_q8 || !msgs_dev || !msg_capacity || n == 0 || d == 0) return EDEN_ERR_INVALID_ARG;
     for (uint32_t c = 0; c < n; ++c) {
         if (!x_dev[c] || !msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
         const size_t need = eden_message_bytes(d, b_q8[c]);
         if (need == 0) return EDEN_ERR_INVALID_ARG;
         if (msg_capacity[c] < need) return EDEN_ERR_CAPACITY;
     }
+    return sparsify_mode(b_q8, n) < 0 ? EDEN_ERR_INVALID_ARG : EDEN_OK;
+}
+
+// The sender side on a context whose device is current and whose limits the arguments respect.
+static int encode_on(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8, uint32_t n,
+                     uint64_t d, uint64_t seed, void *const *msgs_dev, hipStream_t st) {
     const int mode = sparsify_mode(b_q8, n);
-    if (mode < 0) return EDEN_ERR_INVALID_ARG;
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return EDEN_ERR_HIP;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    std::vector<uint32_t> ones(n, 256u);                         // the sparsifying budgets quantize with b = 1
+    uint32_t ones_small[64];                                     // the sparsifying budgets quantize with b = 1
+    std::vector<uint32_t> ones_big;
+    const uint32_t *ones = ones_small;
+    if (n <= 64) { for (uint32_t c = 0; c < n; ++c) ones_small[c] = 256u; }
+    else { ones_big.assign(n, 256u); ones = ones_big.data(); }
     if (mode == 0) return encode_range(ctx, x_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, msgs_dev, st);
-    if (mode == 1) return encode_range(ctx, x_dev, client_ids, ones.data(), b_q8, n, d, 1, d, seed, msgs_dev, st);
+    if (mode == 1) return encode_range(ctx, x_dev, client_ids, ones, b_q8, n, d, 1, d, seed, msgs_dev, st);
     // b = m/64.  Senders that share m and a multi-pass size: a launch gathers the kept coordinates of a batch into the
     // workspace slots, and the 1-bit method then runs on the slots in place (a first-pass workgroup has read a tile
     // before it writes it).
@@ -338,24 +337,34 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
             }
             launch_sparse_gather_batch(B, nb, d, m0, seed, ctx->T, log2Dk, st);
             if (!launch_ok()) return EDEN_ERR_HIP;
-            const int rc = encode_range(ctx, slots_x, &client_ids[first], ones.data(), &b_q8[first], nb, dk0, 0, d, seed,
+            const int rc = encode_range(ctx, slots_x, &client_ids[first], ones, &b_q8[first], nb, dk0, 0, d, seed,
                                         &msgs_dev[first], st);
             if (rc != EDEN_OK) return rc;
         }
         return EDEN_OK;
     }
     // otherwise sender by sender: the kept coordinates packed into the staging vector, then the 1-bit method on it
-    if (!ensure_stage(ctx)) return EDEN_ERR_HIP;
     for (uint32_t c = 0; c < n; ++c) {
         const uint32_t m = sparse_m(b_q8[c]);
         launch_sparse_gather(x_dev[c], d, m, seed, client_ids[c], ctx->stage, st);
         if (!launch_ok()) return EDEN_ERR_HIP;
         const float *xs = ctx->stage;
-        const int rc = encode_range(ctx, &xs, &client_ids[c], ones.data(), &b_q8[c], 1, (uint64_t)m * ((d + 63) / 64), 0, d, seed,
+        const int rc = encode_range(ctx, &xs, &client_ids[c], ones, &b_q8[c], 1, (uint64_t)m * ((d + 63) / 64), 0, d, seed,
                                     &msgs_dev[c], st);
         if (rc != EDEN_OK) return rc;
     }
     return EDEN_OK;
+}
+
+int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8, uint32_t n,
+                uint64_t d, uint64_t seed, void *const *msgs_dev, const size_t *msg_capacity, void *stream) {
+    if (!ctx) return EDEN_ERR_INVALID_ARG;
+    const int rc = check_encode_args(x_dev, client_ids, b_q8, n, d, msgs_dev, msg_capacity);
+    if (rc != EDEN_OK) return rc;
+    if (n > ctx->n_max || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    return encode_on(ctx, x_dev, client_ids, b_q8, n, d, seed, msgs_dev, static_cast<hipStream_t>(stream));
 }
 
 // Decodes n messages whose transformed vectors all have the same dimension and adds them to acc (see encode_range
@@ -386,7 +395,6 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
             bool unpack = false;
             for (uint32_t i = 0; i < nb; ++i) unpack = unpack || packs_bytes(B.b_q8[i]);
             if (unpack) {
-                if (!ensure_codes(ctx)) return EDEN_ERR_HIP;
                 for (uint32_t i = 0; i < nb; ++i)
                     if (packs_bytes(B.b_q8[i])) B.codes[i] = ctx->codes + ((size_t)i << log2D);
                 launch_unpack_bits(B, nb, log2D, ctx->codes, st);
@@ -470,7 +478,6 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
     }
     // otherwise sender by sender (the kept coordinates differ): the 1-bit decode into the staging vector, then the values
     // go back to their coordinates of acc
-    if (!ensure_stage(ctx)) return EDEN_ERR_HIP;
     for (uint32_t c = 0; c < n; ++c) {
         const uint32_t m = sparse_m(b_q8[c]);
         const uint64_t dk = (uint64_t)m * ((d + 63) / 64);

@@ -25,6 +25,50 @@ def test_hash_is_splitmix64(golden):
         assert int(w[j]) == o.mix64(key + 0x9E3779B97F4A7C15 * (1000 + j + 1))
 
 
+def test_stream_keys_and_bit_order_against_the_published_vector(golden, monkeypatch):
+    """Typed constants only: nothing here is read back from the functions under test.
+    The published splitmix64 stream from state 0 is E220A8397B1DCDAF, 6E789E6AA1B965F4, 06C45D188009454F.
+    (a) With the round seed 2^64 - PHI the inner mix is mix(0) = 0, so the key of (stream 0, client c) is
+        mix(PHI (c + 1)) = the (c+1)-th published output: the client id sits in the low half of the tag.
+    (b) With the key forced to 0 the hash words are the published outputs themselves, so the bit and byte order of
+        every stream can be written down by hand: word 0 ends in ...CDAF, AF = 1010 1111 -> bits 0..7 = 1,1,1,1,0,1,0,1,
+        CD = 1100 1101 -> bits 8..15 = 1,0,1,1,0,0,1,1; word 1 ends in ...F4 = 1111 0100 -> bits 64..71 = 0,0,1,0,1,1,1,1."""
+    seed = (1 << 64) - 0x9E3779B97F4A7C15
+    assert o.stream_key(seed, o.STREAM_SIGN, 0) == 0xE220A8397B1DCDAF
+    assert o.stream_key(seed, o.STREAM_SIGN, 1) == 0x6E789E6AA1B965F4
+    assert o.stream_key(seed, o.STREAM_SIGN, 2) == 0x06C45D188009454F
+    # the stream id sits in the high half of the tag: a different stream is a different key
+    assert len({o.stream_key(seed, st, 0) for st in range(5)}) == 5
+    monkeypatch.setattr(o, "stream_key", lambda seed, stream, client: 0)
+    first16 = [1, 1, 1, 1, 0, 1, 0, 1, 1, 0, 1, 1, 0, 0, 1, 1]
+    assert o.sign_bits(0, 0, 16).tolist() == first16
+    assert o.sign_bits(0, 0, 72).tolist()[64:] == [0, 0, 1, 0, 1, 1, 1, 1]
+    assert o.rademacher(0, 0, 8).tolist() == [-1.0, -1.0, -1.0, -1.0, 1.0, -1.0, 1.0, -1.0]      # bit 1 -> s_i = -1
+    assert o.subsample_offsets(0, 0, 16).tolist() == first16
+    assert o.mix_offsets(0, 0, 16).tolist() == first16
+    # coins of the general non-integer budgets: byte (i & 7) of word (i >> 3); word 0 = E2 20 A8 39 7B 1D CD AF from
+    # the top, so coordinates 0..7 draw AF, CD, 1D, 7B, 39, A8, 20, E2 = 175, 205, 29, 123, 57, 168, 32, 226
+    assert o.coin_bits(0, 0, 8, 128).tolist() == [False, False, True, True, True, False, True, False]
+    assert o.coin_bits(0, 0, 8, 30).tolist() == [False, False, True, False, False, False, False, False]
+    # word 1 = 6E 78 9E 6A A1 B9 65 F4 from the top: coordinates 8..11 draw F4, 65, B9, A1 = 244, 101, 185, 161
+    assert o.coin_bits(0, 0, 12, 170).tolist()[8:] == [False, True, False, True]
+    # packet drops: packet j is dropped iff the top 32 bits of word j are below the threshold:
+    # E220A839 > 6E789E6A > 06C45D18, so a threshold of 0x10000000 drops packet 2 only and 0x70000000 drops 1 and 2
+    assert o.loss_bitmap(0, 0, 3 * 1024, 0x10000000).tolist() == [0b011]
+    assert o.loss_bitmap(0, 0, 3 * 1024, 0x70000000).tolist() == [0b001]
+    # m-of-64 sparsification keys: 16-bit key of coordinate i = bits 16 (i & 3) .. of word (i >> 2), so coordinates
+    # 0..11 draw CDAF, 7B1D, A839, E220 | 65F4, A1B9, 9E6A, 6E78 | 454F, 8009, 5D18, 06C4.  Whatever the other 52 keys
+    # of the block are, a kept coordinate among these twelve must have a smaller typed key than a dropped one.
+    typed = [0xCDAF, 0x7B1D, 0xA839, 0xE220, 0x65F4, 0xA1B9, 0x9E6A, 0x6E78, 0x454F, 0x8009, 0x5D18, 0x06C4]
+    for m in (8, 24, 40, 56):
+        kept = set(o.sparse_selection(0, 0, 64, m).tolist())
+        assert len(kept) == m
+        inside = [i for i in range(12) if i in kept]
+        outside = [i for i in range(12) if i not in kept]
+        assert all(typed[i] < typed[j] for i in inside for j in outside)
+    assert 11 in set(o.sparse_selection(0, 0, 64, 8).tolist())           # 06C4: among the 8 smallest of 64 with near certainty
+
+
 def test_sign_streams_balanced_and_independent():
     D = 1 << 16
     a = o.sign_bits(1, 0, D).astype(np.int64)
@@ -545,6 +589,115 @@ def test_half_integer_budget_unbiased_and_lossy():
     np.testing.assert_allclose(yh[:2048], full[:2048] * (4 / 3), rtol=1e-14)
 
 
+# ---- general non-integer b > 1 in the paper's own form: an independent coin per coordinate (Sec. 4.1)
+def COIN(b: float) -> int:
+    return o.COIN | int(round(256 * b))
+
+
+def test_coin_budget_by_hand_d4():
+    # b = 1.5 on four coordinates, every step typed out; only the coins are taken from the stream (their byte order
+    # is pinned against the published vector above)
+    seed, client = 6, 2
+    s = [1.0 - 2.0 * v for v in o.sign_bits(seed, client, 4).tolist()]
+    up = o.coin_bits(seed, client, 4, 128).tolist()
+    assert 0 < sum(up) < 4                            # this seed mixes both quantizers
+    x = [0.75, 2.0, -3.0, 0.1]
+    a = [s[i] * x[i] for i in range(4)]
+    u = [a[0] + a[1] + a[2] + a[3], a[0] - a[1] + a[2] - a[3], a[0] + a[1] - a[2] - a[3], a[0] - a[1] - a[2] + a[3]]
+    y = [v / 2.0 for v in u]
+    n2 = sum(v * v for v in x)
+    z = [math.sqrt(4.0 / n2) * v for v in y]
+    c1 = math.sqrt(2.0 / math.pi)
+    t2, q2 = 0.9816, (0.45278, 1.51042)              # Sec. 3, Example 2 (five printed digits)
+    Q, low, top = [], [], []
+    for i in range(4):
+        if up[i]:
+            mag = 1 if abs(z[i]) > t2 else 0
+            idx = (2 + mag) if z[i] >= 0 else (1 - mag)
+            Q.append(math.copysign(q2[mag], z[i]))
+            low.append(idx & 1); top.append(idx >> 1)
+        else:
+            Q.append(c1 if z[i] >= 0 else -c1)
+            low.append(1 if z[i] >= 0 else 0)
+    ip = sum(y[i] * Q[i] for i in range(4))
+    msg, tr = o.encode(np.array(x), seed, client, COIN(1.5), want_trace=True)
+    assert tr.up.tolist() == up and msg.extra_bits == sum(up)
+    second = sum(bit << r for r, bit in enumerate(top))                   # one bit per coin, in coordinate order
+    assert msg.payload.tolist() == [low[0] | low[1] << 1 | low[2] << 2 | low[3] << 3, 0, second, 0]
+    assert abs(msg.IP - ip) < 2e-5 * abs(ip)          # the printed table values carry five digits
+    assert abs(msg.S - n2 / ip) < 2e-5 * abs(n2 / ip)
+    w = [msg.S * Q[i] for i in range(4)]
+    v = [w[0] + w[1] + w[2] + w[3], w[0] - w[1] + w[2] - w[3], w[0] + w[1] - w[2] - w[3], w[0] - w[1] - w[2] + w[3]]
+    xhat = [s[i] * v[i] / 2.0 for i in range(4)]
+    np.testing.assert_allclose(o.decode(msg, 4), xhat, rtol=3e-5, atol=1e-5)
+
+
+@pytest.mark.parametrize("b", [1.3, 1.5, 2.7, 3.5, 1 + 1 / 256, 4 - 1 / 256])
+def test_coin_budget_size_rate_and_round_trip(b):
+    d, D = 30_000, 1 << 15
+    b_q8 = COIN(b)
+    k, f = int(b), b - int(b)
+    rng = np.random.default_rng(int(b * 256))
+    x = rng.standard_normal(d)
+    msg, tr = o.encode(x, 13, 3, b_q8, want_trace=True)
+    U = int(tr.up.sum())
+    assert msg.extra_bits == U
+    assert abs(U - f * D) <= 4.0 * math.sqrt(D * f * (1 - f)) + 1          # bits per coordinate concentrate around b
+    assert msg.payload.size == 2 * ((D * k + 63) // 64) + 2 * ((U + 63) // 64)
+    assert len(msg.to_bytes()) <= o.message_bytes(d, b_q8) == 64 + D * k // 8 + D // 8
+    assert not np.array_equal(tr.up, o.coin_bits(13, 4, D, b_q8 & 0xFF))   # per sender
+    assert not np.array_equal(tr.up, o.coin_bits(14, 3, D, b_q8 & 0xFF))   # per round
+    # neighbouring coins are independent (the stratified k + 1/2 budgets are not)
+    both = np.mean(tr.up[0::2] & tr.up[1::2])
+    assert abs(both - f * f) < 4.0 * math.sqrt(f * f * (1 - f * f) / (D / 2)) + 2.0 / D
+    back = o.Message.from_bytes(msg.to_bytes() + b"\0" * 64)              # a buffer longer than the message
+    assert back.extra_bits == U and back.payload.size == msg.payload.size
+    np.testing.assert_array_equal(o.unpack_fractional(back.payload, D, b_q8, tr.up), tr.idx)
+    t_lo, _ = o.tables(k); t_hi, _ = o.tables(k + 1)
+    np.testing.assert_array_equal(tr.idx[~tr.up], o.quantize_indices(tr.z[~tr.up], t_lo))
+    np.testing.assert_array_equal(tr.idx[tr.up], o.quantize_indices(tr.z[tr.up], t_hi))
+    xh = o.decode(back, d)
+    assert abs(np.dot(xh, x) - np.dot(x, x)) < 1e-10 * np.dot(x, x)       # tangent property (Sec. 2.3)
+
+
+def test_coin_budget_vnmse_matches_printed_value(golden):
+    # Sec. 4.1: 1 / ((1 - f) E[Q_k^2] + f E[Q_{k+1}^2]) - 1; b = 1.5 -> 0.317 as printed
+    d = 1 << 13
+    rng = np.random.default_rng(9)
+    x = rng.lognormal(size=d)
+    for b in (1.5, 1.25, 2.7):
+        k, f = int(b), b - int(b)
+        th = 1 / ((1 - f) * o.expected_q2(*o.tables(k)) + f * o.expected_q2(*o.tables(k + 1))) - 1
+        v = np.mean([o.vnmse_single(x, o.decode(o.encode(x, s, 0, COIN(b)), d)) for s in range(12)])
+        assert abs(v - th) < 0.03 * th, (b, v, th)
+        if b == 1.5:
+            assert abs(v - golden["vnmse_b1p5"]) < 0.01
+
+
+def test_coin_budget_unbiased_and_lossy():
+    d, trials = 512, 4000
+    rng = np.random.default_rng(22)
+    x = rng.standard_normal(d)
+    acc = np.zeros(d); sq = 0.0
+    for tr in range(trials):
+        xh = o.decode(o.encode(x, seed=tr, client=0, b_q8=COIN(1.3)), d)
+        acc += xh; sq += np.sum((xh - x) ** 2)
+    vn = sq / trials / np.dot(x, x)
+    err = np.linalg.norm(acc / trials - x) / np.linalg.norm(x)
+    assert err < 1.3 * math.sqrt(vn / trials)
+    d = 4096
+    x = rng.standard_normal(d)
+    msg = o.encode(x, 5, 2, COIN(2.25))
+    bm = np.array([0b1011], dtype=np.uint32)                              # packet 2 of 4 lost
+    yh = o.decode_rotated(msg, bm)
+    full = o.decode_rotated(msg, None)
+    assert not yh[2048:3072].any()
+    np.testing.assert_allclose(yh[:2048], full[:2048] * (4 / 3), rtol=1e-14)
+    # a zero vector still has the length its coins give
+    z = o.encode(np.zeros(100), 5, 2, COIN(2.25))
+    assert z.status == o.STATUS_ZERO_VECTOR and z.extra_bits == int(o.coin_bits(5, 2, 128, 64).sum()) and not z.payload.any()
+
+
 # ---- b = 1/2 with the sparsification before the rotation (Sec. 4.1, the paper's default for b < 1)
 PRE_HALF = o.PRE_ROTATION | 128
 
@@ -744,7 +897,7 @@ def test_shooting_tables_agree_with_lloyd_and_with_quadrature():
     t_s, q_s = o.max_shooting(32)
     t_l, q_l = o.lloyd_max(32)
     assert np.max(np.abs(q_s - q_l)) < 5e-12 and np.max(np.abs(t_s - t_l)) < 5e-12
-    for bits in (6, 8):
+    for bits in (6, 7, 8):
         t, q = o.tables(bits)
         n = 1 << bits
         assert t.size == n - 1 and q.size == n and np.all(np.diff(q) > 0) and np.all(np.diff(t) > 0)
