@@ -358,10 +358,9 @@ static int encode_on(eden_ctx *ctx, const float *const *x_dev, const uint32_t *c
 
 int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8, uint32_t n,
                 uint64_t d, uint64_t seed, void *const *msgs_dev, const size_t *msg_capacity, void *stream) {
-    if (!ctx) return EDEN_ERR_INVALID_ARG;
+    if (!ctx || n > ctx->n_max || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
     const int rc = check_encode_args(x_dev, client_ids, b_q8, n, d, msgs_dev, msg_capacity);
     if (rc != EDEN_OK) return rc;
-    if (n > ctx->n_max || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return EDEN_ERR_HIP;
     return encode_on(ctx, x_dev, client_ids, b_q8, n, d, seed, msgs_dev, static_cast<hipStream_t>(stream));
