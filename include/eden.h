@@ -113,7 +113,8 @@ typedef enum eden_status {
     EDEN_ERR_INVALID_ARG = -1,      /* NULL pointer, d = 0, d > 2^27, n = 0, unsupported budget, n or d above the context's limits */
     EDEN_ERR_CAPACITY = -2,         /* a message buffer is smaller than eden_message_bytes() */
     EDEN_ERR_HIP = -3,              /* a HIP runtime call failed */
-    EDEN_ERR_NO_DEVICE = -4         /* no usable gfx950 device / device index out of range */
+    EDEN_ERR_NO_DEVICE = -4,        /* no usable gfx950 device / device index out of range */
+    EDEN_ERR_STATIC_LIMIT = -5      /* eden_encode_static: n or d above EDEN_STATIC_MAX_N / EDEN_STATIC_MAX_D */
 } eden_status;
 
 /* bits of the status word in a message header and of the device status word */
@@ -153,6 +154,20 @@ size_t eden_message_bytes(uint64_t d, uint32_t b_q8);
 int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client_ids,
                 const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
                 void *const *msgs_dev, const size_t *msg_capacity, void *stream);
+
+/* eden_encode for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical messages as eden_encode, but no context: the
+ * workspace is a fixed device array inside the library (about 45 MiB on every GPU the library is loaded on, held until
+ * the process ends), so the call is limited to n <= EDEN_STATIC_MAX_N senders of d <= EDEN_STATIC_MAX_D coordinates;
+ * beyond that it returns EDEN_ERR_STATIC_LIMIT and does nothing.  It runs on the current HIP device and calls no
+ * hipMalloc, hipFree or other allocating routine; the first call on a device also looks up the array's address, uploads
+ * the Lloyd-Max tables through kernel arguments and synchronises `stream` once.  Device-side conditions are recorded in
+ * the message headers only.  All calls on one GPU share the array, which keeps the last call's contents (every call
+ * overwrites what it reads): calls that overlap on one GPU, on any streams, race. */
+#define EDEN_STATIC_MAX_D 1048576u
+#define EDEN_STATIC_MAX_N 8u
+int eden_encode_static(const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8, uint32_t n,
+                       uint64_t d, uint64_t seed, void *const *msgs_dev, const size_t *msg_capacity, void *stream);
 
 /* Receiver side for a batch of n messages: for each, unpack, centroid lookup, zero the coordinates
  * that were not sampled or whose packet did not arrive, multiply by S/p with p = (coordinates that

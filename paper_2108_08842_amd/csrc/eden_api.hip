@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -98,6 +99,18 @@ struct DeviceGuard {
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
+// The Lloyd-Max tables of Sec. 3 (positive halves) in the layout the kernels read.
+void fill_host_tables(DevTables &host) {
+    std::memset(&host, 0, sizeof(host));
+    for (int bits = 1; bits <= EDEN_MAX_TABLE_BITS; ++bits) {
+        const EdenHalfTable *ht = eden_half_table(bits);
+        for (int i = 0; i < ht->half_levels; ++i) {
+            if (bits <= 4) { host.t[bits][i] = ht->t[i]; host.q[bits][i] = ht->q[i]; }
+            else { host.t_big[bits - 5][i] = ht->t[i]; host.q_big[bits - 5][i] = ht->q[i]; }
+        }
+    }
+}
+
 // Brackets one kernel launch with two events when timing of that kernel kind is switched on.
 struct Timed {
     eden_ctx *ctx;
@@ -168,13 +181,7 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     if (ok) {
         std::vector<DevTables> host_tables(1);                   // 9 KiB: not on the stack
         DevTables &host = host_tables[0];
-        for (int bits = 1; bits <= EDEN_MAX_TABLE_BITS; ++bits) {
-            const EdenHalfTable *ht = eden_half_table(bits);
-            for (int i = 0; i < ht->half_levels; ++i) {
-                if (bits <= 4) { host.t[bits][i] = ht->t[i]; host.q[bits][i] = ht->q[i]; }
-                else { host.t_big[bits - 5][i] = ht->t[i]; host.q_big[bits - 5][i] = ht->q[i]; }
-            }
-        }
+        fill_host_tables(host);
         ok = ok && hipMemcpy(ctx->tables, &host, sizeof(host), hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMemset(ctx->enc_scratch, 0, ctx->slots * sizeof(EncScratch)) == hipSuccess;
         ok = ok && hipMemset(ctx->dec_scratch, 0, ctx->slots * sizeof(DecScratch)) == hipSuccess;
@@ -364,6 +371,97 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return EDEN_ERR_HIP;
     return encode_on(ctx, x_dev, client_ids, b_q8, n, d, seed, msgs_dev, static_cast<hipStream_t>(stream));
+}
+
+// ---- eden_encode_static: the sender side for callers that cannot allocate.  Everything eden_encode keeps in a context
+// (workspace slots, byte indices, staging vector, partial sums, per-sender scalars, tables) lives in one file-scope
+// device array instead; every GPU the library is loaded on holds its own copy until the process ends.
+namespace {
+constexpr size_t static_align(size_t x) { return (x + 255) & ~(size_t)255; }
+constexpr int kStaticLog2D = 20;
+static_assert((1ull << kStaticLog2D) == EDEN_STATIC_MAX_D && EDEN_STATIC_MAX_N <= kMaxBatch, "limits of the static entry point");
+constexpr size_t kStaticDmax = (size_t)1 << kStaticLog2D;
+constexpr uint32_t kStaticPartialStride = (uint32_t)(kStaticDmax / 256 + 16);
+constexpr size_t kOffT = 0;
+constexpr size_t kOffCodes = kOffT + static_align(EDEN_STATIC_MAX_N * kStaticDmax * sizeof(float));
+constexpr size_t kOffStage = kOffCodes + static_align(EDEN_STATIC_MAX_N * kStaticDmax);
+constexpr size_t kOffPartials = kOffStage + static_align((kStaticDmax + 64) * sizeof(float));
+constexpr size_t kOffEncScratch = kOffPartials + static_align(2 * (size_t)EDEN_STATIC_MAX_N * kStaticPartialStride * sizeof(double));
+constexpr size_t kOffTables = kOffEncScratch + static_align(EDEN_STATIC_MAX_N * sizeof(EncScratch));
+constexpr size_t kOffStatus = kOffTables + static_align(sizeof(DevTables));
+constexpr size_t kStaticBytes = kOffStatus + 256;               // about 45 MiB
+constexpr int kStaticMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+struct StaticDevice {
+    bool ready = false;
+    eden_ctx ctx;
+};
+StaticDevice g_static[kStaticMaxDevices];
+std::mutex g_static_mutex;
+
+// Once per device, with that device current: the address of this device's copy of `scratch` (the array's name is only a
+// host-side handle, never a device address), the context that points into it, zeroed scalars and the tables.  The
+// tables travel as kernel arguments, so nothing here allocates or stages a copy.
+int static_context(int dev, hipStream_t st, eden_ctx **out) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticDevice &S = g_static[dev];
+    if (!S.ready) {
+        unsigned char *ptr = nullptr;
+        if (hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return EDEN_ERR_HIP;
+        eden_ctx &c = S.ctx;
+        c.device = dev;
+        c.d_max = EDEN_STATIC_MAX_D;
+        c.log2D_max = kStaticLog2D;
+        c.n_max = EDEN_STATIC_MAX_N;
+        c.slots = EDEN_STATIC_MAX_N;
+        c.T = reinterpret_cast<float *>(ptr + kOffT);
+        c.codes = ptr + kOffCodes;
+        c.stage = reinterpret_cast<float *>(ptr + kOffStage);
+        c.partials = reinterpret_cast<double *>(ptr + kOffPartials);
+        c.partial_stride = kStaticPartialStride;
+        c.enc_scratch = reinterpret_cast<EncScratch *>(ptr + kOffEncScratch);
+        c.tables = reinterpret_cast<DevTables *>(ptr + kOffTables);
+        c.dev_status = reinterpret_cast<uint32_t *>(ptr + kOffStatus);
+        c.dec_partial = nullptr; c.dec_partial_tiles = 0; c.hist = nullptr; c.dec_scratch = nullptr;
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        c.compute_units = (uint32_t)cus;
+        launch_fill_zero(reinterpret_cast<float *>(ptr + kOffEncScratch), (kOffStatus + 256 - kOffEncScratch) / sizeof(float), st);
+        std::vector<DevTables> host_tables(1);
+        fill_host_tables(host_tables[0]);
+        const double *src = reinterpret_cast<const double *>(&host_tables[0]);
+        const uint32_t total = (uint32_t)(sizeof(DevTables) / sizeof(double));
+        for (uint32_t first = 0; first < total; first += kArgDoubles) {
+            const uint32_t count = total - first < (uint32_t)kArgDoubles ? total - first : (uint32_t)kArgDoubles;
+            launch_store_doubles(src + first, count, reinterpret_cast<double *>(c.tables) + first, st);
+        }
+        if (!launch_ok()) return EDEN_ERR_HIP;
+        // a later call may come on another stream: the set-up must have finished before it starts
+        if (hipStreamSynchronize(st) != hipSuccess) return EDEN_ERR_HIP;
+        S.ready = true;
+    }
+    *out = &S.ctx;
+    return EDEN_OK;
+}
+}  // namespace
+
+int eden_encode_static(const float *const *x_dev, const uint32_t *client_ids, const uint32_t *b_q8, uint32_t n, uint64_t d,
+                       uint64_t seed, void *const *msgs_dev, const size_t *msg_capacity, void *stream) {
+    if (n > EDEN_STATIC_MAX_N || (d > EDEN_STATIC_MAX_D && d <= (1ull << EDEN_MAX_LOG2_D))) return EDEN_ERR_STATIC_LIMIT;
+    const int rc = check_encode_args(x_dev, client_ids, b_q8, n, d, msgs_dev, msg_capacity);
+    if (rc != EDEN_OK) return rc;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return EDEN_ERR_HIP;
+    if (dev < 0 || dev >= kStaticMaxDevices) return EDEN_ERR_NO_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    eden_ctx *ctx = nullptr;
+    const int rs = static_context(dev, st, &ctx);
+    if (rs != EDEN_OK) return rs;
+    return encode_on(ctx, x_dev, client_ids, b_q8, n, d, seed, msgs_dev, st);
 }
 
 // Decodes n messages whose transformed vectors all have the same dimension and adds them to acc (see encode_range
@@ -632,6 +730,7 @@ const char *eden_strerror(int status) {
         case EDEN_ERR_CAPACITY: return "message buffer too small";
         case EDEN_ERR_HIP: return "HIP runtime error";
         case EDEN_ERR_NO_DEVICE: return "no usable device";
+        case EDEN_ERR_STATIC_LIMIT: return "beyond the size limits of the allocation-free entry point";
         default: return "unknown status";
     }
 }

@@ -55,6 +55,9 @@ void launch_sparse_scatter_batch(const DecBatch &B, uint32_t n, uint64_t d, uint
 void launch_pack_bits(const EncBatch &B, uint32_t n, int log2D, hipStream_t st);
 void launch_unpack_bits(const DecBatch &B, uint32_t n, int log2D, uint8_t *codes_all, hipStream_t st);
 void launch_fill_zero(float *p, uint64_t count, hipStream_t st);
+// dst[i] = src_host[i], i < count <= kArgDoubles: the values travel as kernel arguments (no copy is staged)
+constexpr int kArgDoubles = 256;
+void launch_store_doubles(const double *src_host, uint32_t count, double *dst, hipStream_t st);
 void launch_byte_entropy(const uint8_t *bytes, uint64_t count, uint32_t *hist, double *out, hipStream_t st);
 void launch_sq_error(const float *a, const float *b, uint64_t d, double *partials, uint32_t max_parts, double *out,
                      hipStream_t st);

@@ -1255,6 +1255,12 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
     }
 }
 
+// Writes up to kArgDoubles doubles that travel as kernel arguments (for a caller that may neither allocate nor stage a copy).
+struct ArgDoubles { double v[kArgDoubles]; };
+__global__ __launch_bounds__(kArgDoubles) void k_store_doubles(ArgDoubles a, uint32_t count, double *dst) {
+    if (threadIdx.x < count) dst[threadIdx.x] = a.v[threadIdx.x];
+}
+
 // ------------------------------------------------------------------------------------------------
 // test helpers: the hash streams written out
 __global__ void k_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out) {
@@ -1403,6 +1409,11 @@ void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, uint64
 void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
                       const DevTables *tab, float *acc, uint32_t *dev_status, hipStream_t st) {
     hipLaunchKernelGGL(k_dec_small, dim3(1), dim3(256), 0, st, B, n, d, pre, hdr_d, log2D, seed, tab, acc, dev_status);
+}
+void launch_store_doubles(const double *src_host, uint32_t count, double *dst, hipStream_t st) {
+    ArgDoubles a;
+    for (uint32_t i = 0; i < (uint32_t)kArgDoubles; ++i) a.v[i] = i < count ? src_host[i] : 0.0;
+    hipLaunchKernelGGL(k_store_doubles, dim3(1), dim3(kArgDoubles), 0, st, a, count, dst);
 }
 void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t st) {
     hipLaunchKernelGGL(k_hash_bits, dim3((uint32_t)((nwords + 255) / 256)), dim3(256), 0, st, key, nwords, out);

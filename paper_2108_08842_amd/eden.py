@@ -18,6 +18,9 @@ ERR_INVALID_ARG = -1
 ERR_CAPACITY = -2
 ERR_HIP = -3
 ERR_NO_DEVICE = -4
+ERR_STATIC_LIMIT = -5
+STATIC_MAX_D = 1 << 20
+STATIC_MAX_N = 8
 DEV_ZERO_VECTOR = 1
 DEV_NONFINITE = 2
 DEV_HEADER_MISMATCH = 4
@@ -29,7 +32,7 @@ EXPORTS = [
     "eden_create", "eden_destroy", "eden_message_bytes", "eden_encode", "eden_decode_accumulate",
     "eden_finalize_mean", "eden_last_device_status", "eden_make_loss_bitmap", "eden_make_sign_bits",
     "eden_make_subsample_bits", "eden_get_tables", "eden_strerror", "eden_profile_enable", "eden_profile_collect",
-    "eden_kernel_name", "eden_sq_error", "eden_index_entropy",
+    "eden_kernel_name", "eden_sq_error", "eden_index_entropy", "eden_encode_static",
 ]
 B_HALF_PRE = 0x10080     # b = 1/2 with the sparsification before the rotation (EDEN_B_HALF_PRE)
 
@@ -77,6 +80,8 @@ def lib():
     L.eden_message_bytes.restype = sz
     L.eden_encode.argtypes = [vp, P(vp), P(u32), P(u32), u32, u64, u64, P(vp), P(sz), vp]
     L.eden_encode.restype = ci
+    L.eden_encode_static.argtypes = [P(vp), P(u32), P(u32), u32, u64, u64, P(vp), P(sz), vp]
+    L.eden_encode_static.restype = ci
     L.eden_decode_accumulate.argtypes = [vp, P(vp), P(u32), P(u32), u32, u64, u64, P(vp), vp, vp]
     L.eden_decode_accumulate.restype = ci
     L.eden_finalize_mean.argtypes = [vp, vp, u64, u32, vp, vp]
@@ -137,6 +142,24 @@ def _u32_array(values: Sequence[int]):
 
 def _ptr_array(ptrs: Sequence[Optional[int]]):
     return (ctypes.c_void_p * len(ptrs))(*[ctypes.c_void_p(p) if p else None for p in ptrs])
+
+
+def encode_static_raw(x_ptrs, client_ids, b_q8, d, seed, msg_ptrs, msg_caps, stream=None) -> int:
+    """eden_encode_static on the current device: the library's status code, nothing raised."""
+    n = len(x_ptrs)
+    caps = (ctypes.c_size_t * n)(*[int(c) for c in msg_caps])
+    return lib().eden_encode_static(_ptr_array(x_ptrs), _u32_array(client_ids), _u32_array(b_q8), n, d,
+                                    ctypes.c_uint64(seed & (2 ** 64 - 1)), _ptr_array(msg_ptrs), caps, _stream_ptr(stream))
+
+
+def encode_static(xs, client_ids, b_q8, seed: int, msgs, stream=None):
+    """The sender side without a context and without any allocation: `msgs` are caller-allocated uint8 tensors."""
+    d = xs[0].numel()
+    rc = encode_static_raw([x.data_ptr() for x in xs], client_ids, b_q8, d, seed, [m.data_ptr() for m in msgs],
+                           [m.numel() for m in msgs], stream)
+    if rc != OK:
+        raise EdenError(rc, "eden_encode_static")
+    return msgs
 
 
 class Context:
