@@ -58,7 +58,6 @@ __device__ inline void lo14_forward32(float (&v)[32], float *lds) {
 // run starts at coordinate 32 t of the tile, so a wave owns 2048 consecutive coordinates; a wave-private
 // transpose through LDS (quads swizzled by the low three bits of the row: eight neighbouring lanes then hit 32
 // different banks in both directions; measured with SQ_LDS_BANK_CONFLICT) lets 8 neighbouring lanes store one line.  `L`: this wave's 2048 floats of LDS; `dst`: the wave's first coordinate.
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
 __device__ inline void lo14_store_runs(const float (&v)[32], float *L, float *dst) {
     const uint32_t lane = threadIdx.x & 63u;
     wave_lds_sync();
@@ -73,8 +72,9 @@ __device__ inline void lo14_store_runs(const float (&v)[32], float *L, float *ds
         const uint32_t row = 8u * (uint32_t)j + (lane >> 3);
         const float4 x = *reinterpret_cast<const float4 *>(&L[row * 32u + 4u * pos]);
         const uint32_t quad = pos ^ (row & 7u);
-        f32x4_t y = {x.x, x.y, x.z, x.w};
-        __builtin_nontemporal_store(y, reinterpret_cast<f32x4_t *>(dst + row * 32u + 4u * quad));
+        // (write-back stores: with the streaming hint this pass ran 13% slower; the pass that reads the tiles back does
+        // better with the hint on its loads)
+        *reinterpret_cast<float4 *>(dst + row * 32u + 4u * quad) = x;
     }
 }
 
@@ -84,61 +84,48 @@ __device__ inline void lo14_store_runs(const float (&v)[32], float *L, float *ds
 // under these 14 bits, and the strided pass that follows reads it as zero through its buffer bounds.
 // PRE (b = 1/2 with the sparsification first, Sec. 4.1): the vector that is transformed is x'[g] = 2 x[2g + o_g],
 // g < ceil(d_src/2), o_g from the SUB-SAMPLING stream; x is read as 0 beyond d_src.
-template <int TPW, bool PRE>
+template <bool PRE>
 __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t d_src, int log2D, uint64_t seed, float *T,
                                                         double *partials, uint32_t partial_stride) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14LdsWords];
     __shared__ double red[8];
     const uint32_t c = blockIdx.y, t = threadIdx.x, lane = t & 63u;
     const uint32_t wv = wave_in_block();
-    const uint64_t d = PRE ? (d_src + 1) / 2 : d_src;            // dimension of the vector that is transformed
-    const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);
     const rsrc_t rx = make_rsrc(B.x[c], (uint32_t)(d_src * 4));           // reads past d_src give the zero padding
     float *Tc = T + ((size_t)c << log2D);
     const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
-    const uint64_t prekey = stream_key(seed, kStreamSubsample, B.client[c]);
     const uint32_t lane_off = (wv * 64u + lane) * 4u;
-    const uint32_t tile0 = blockIdx.x * TPW;
-    double n2 = 0.0;
-    // element 512 a + 64 wave + lane of a tile; with PRE it comes from x[2 i + o_i], and register a of this wave is
+    const uint32_t tile = blockIdx.x;                            // one tile per workgroup: two workgroups share a CU, and
+                                                                 // their phases interleave better than two tiles in one
+                                                                 // workgroup with the second one's loads issued early
+    // element 512 a + 64 wave + lane of the tile; with PRE it comes from x[2 i + o_i], and register a of this wave is
     // 64 consecutive pairs = one word of offsets (lane l < 32 hashes the word of register l)
-    auto load_tile = [&](uint32_t tile, float (&dst)[32]) {
-        if constexpr (PRE) {
-            const uint64_t offs = hash_word(prekey, ((uint64_t)tile << (kLo14Bits - 6)) + 8u * (lane & 31u) + wv);
-#pragma unroll
-            for (int a = 0; a < 32; ++a) {
-                const uint32_t odd = __builtin_amdgcn_inverse_ballot_w64(wave_read64(offs, a)) ? 4u : 0u;
-                dst[a] = buf_load(rx, 2u * lane_off + odd, (tile << (kLo14Bits + 3)) + 4096u * a);
-            }
-        } else {
-#pragma unroll
-            for (int a = 0; a < 32; ++a) dst[a] = buf_load(rx, lane_off, (tile << (kLo14Bits + 2)) + 2048u * a);
-        }
-    };
-    float next[32];
-    load_tile(tile0, next);
-#pragma unroll
-    for (int k = 0; k < TPW; ++k) {
-        const uint32_t tile = tile0 + k;
-        if (tile >= tiles) break;                                // same decision in every thread of the workgroup
-        float u[32];
-#pragma unroll
-        for (int a = 0; a < 32; ++a) u[a] = PRE ? 2.0f * next[a] : next[a];
+    float u[32];
+    if constexpr (PRE) {
+        const uint64_t prekey = stream_key(seed, kStreamSubsample, B.client[c]);
+        const uint64_t offs = hash_word(prekey, ((uint64_t)tile << (kLo14Bits - 6)) + 8u * (lane & 31u) + wv);
 #pragma unroll
         for (int a = 0; a < 32; ++a) {
-            n2 += (double)u[a] * (double)u[a];
-            if ((a & 7) == 7) __builtin_amdgcn_sched_barrier(0);     // keeps the widened values of one group live at a time
+            const uint32_t odd = __builtin_amdgcn_inverse_ballot_w64(wave_read64(offs, a)) ? 4u : 0u;
+            u[a] = 2.0f * buf_load(rx, 2u * lane_off + odd, (tile << (kLo14Bits + 3)) + 4096u * a);
         }
-        // register a of this wave = 64 consecutive coordinates = one sign word: lane l < 32 hashes the word of
-        // register l, register a reads it back as a lane mask
-        const uint64_t mine = hash_word(key, ((uint64_t)tile << (kLo14Bits - 6)) + 8u * (lane & 31u) + wv);
+    } else {
 #pragma unroll
-        for (int a = 0; a < 32; ++a) u[a] = negate_where(u[a], wave_read64(mine, a)) + 0.0f;   // + 0: no negative zeros
-        if (k + 1 < TPW) load_tile(tile + 1u, next);
-        lo14_forward32(u, lds);
-        lo14_store_runs(u, lds + wv * kXbWave, Tc + ((size_t)tile << kLo14Bits) + 2048u * wv);
-        if (k + 1 < TPW) __syncthreads();                        // LDS is reused by the next tile
+        for (int a = 0; a < 32; ++a) u[a] = buf_load(rx, lane_off, (tile << (kLo14Bits + 2)) + 2048u * a);
     }
+    double n2 = 0.0;
+#pragma unroll
+    for (int a = 0; a < 32; ++a) {
+        n2 += (double)u[a] * (double)u[a];
+        if ((a & 7) == 7) __builtin_amdgcn_sched_barrier(0);     // keeps the widened values of one group live at a time
+    }
+    // register a of this wave = 64 consecutive coordinates = one sign word: lane l < 32 hashes the word of
+    // register l, register a reads it back as a lane mask
+    const uint64_t mine = hash_word(key, ((uint64_t)tile << (kLo14Bits - 6)) + 8u * (lane & 31u) + wv);
+#pragma unroll
+    for (int a = 0; a < 32; ++a) u[a] = negate_where(u[a], wave_read64(mine, a)) + 0.0f;   // + 0: no negative zeros
+    lo14_forward32(u, lds);
+    lo14_store_runs(u, lds + wv * kXbWave, Tc + ((size_t)tile << kLo14Bits) + 2048u * wv);
     const double block_total = block_sum<512>(n2, red);
     if (t == 0) partials[(size_t)c * partial_stride + blockIdx.x] = block_total;
 }
@@ -161,7 +148,10 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
 // `separate`: K = n, one sender per workgroup, nothing is summed: every sender's decoded tile is written back into its own
 // workspace slot (`partial` is then the workspace; fp32, in place: the workgroup has read the tile before it writes
 // it), for a caller that puts the values elsewhere afterwards.
-template <bool PRE>
+// ALL16: every sender of the launch has an int16 workspace (the common case of a b <= 1 round); the loads then go
+// through buffer descriptors (the offsets of the 32 rows sit in scalar registers: no address arithmetic per load) and
+// nothing in the sender loop chooses between the two formats.
+template <bool PRE, bool ALL16>
 __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d_src, int log2D, uint64_t seed,
                                                        const float *T, const DecScratch *scratch, int narrow, float *acc,
                                                        uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
@@ -188,7 +178,14 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     for (int e = 0; e < NS; ++e) sum[e] = 0.0f;
 
     auto load = [&](uint32_t c, float (&dst_regs)[32]) {
-        if (narrow && B.b_q8[c] <= 256u) {
+        if constexpr (ALL16) {
+            // int16 element i of the slot at byte 2 i; the tile lies inside the slot, so the bound is the slot's end
+            const rsrc_t r16 = make_rsrc(T + ((size_t)c << log2D), 2u << log2D);
+            const uint32_t lane_off = (wv * 64u + lane) * 2u, tile_off = (uint32_t)tile_base * 2u;
+#pragma unroll
+            for (int a = 0; a < 32; ++a)
+                dst_regs[a] = __int_as_float((int)(short)__builtin_amdgcn_raw_buffer_load_b16(r16, (int)lane_off, (int)(tile_off + 1024u * a), kStream));
+        } else if (narrow && B.b_q8[c] <= 256u) {
             const short *t16 = reinterpret_cast<const short *>(T + ((size_t)c << log2D)) + in_off;
 #pragma unroll
             for (int a = 0; a < 32; ++a) dst_regs[a] = __int_as_float((int)__builtin_nontemporal_load(t16 + 512 * a));
@@ -198,15 +195,20 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
             for (int a = 0; a < 32; ++a) dst_regs[a] = __builtin_nontemporal_load(t32 + 512 * a);
         }
     };
-    float next[32];
-    if (!PRE && c_begin < c_end) load(c_begin, next);            // with 64 accumulators there is no room to load ahead
-    for (uint32_t c = c_begin; c < c_end; ++c) {
-        const bool i16 = narrow && B.b_q8[c] <= 256u;
+    // One sender: `cur` holds its 32 loaded values (PRE: they are loaded here, with 64 accumulators there is no room to
+    // load ahead); the loads of sender c + 1 go into the same registers once the values have been converted.  (Two
+    // alternating register sets would save the compiler's copy of the loaded set, but need more than 128 registers.)
+    auto one_sender = [&](uint32_t c, float (&cur)[32]) {
+        const bool i16 = ALL16 || (narrow && B.b_q8[c] <= 256u);
         float u[32];
-        if constexpr (PRE) load(c, next);
+        if constexpr (PRE) load(c, cur);
 #pragma unroll
-        for (int a = 0; a < 32; ++a) u[a] = i16 ? (float)__float_as_int(next[a]) : next[a];
-        if (!PRE && c + 1 < c_end) load(c + 1, next);
+        for (int a = 0; a < 32; ++a) {
+            if constexpr (ALL16) u[a] = (float)__float_as_int(cur[a]);
+            else u[a] = i16 ? (float)__float_as_int(cur[a]) : cur[a];
+        }
+        __builtin_amdgcn_sched_barrier(0);                       // the conversions stay above the next sender's loads
+        if (!PRE && c + 1 < c_end) load(c + 1, cur);
         lo14_forward32(u, lds);
         const uint32_t scale = __float_as_uint(i16 ? scratch[c].deq[1] : 1.0f) & 0x7FFFFFFFu;   // > 0; x*1+s is exact
         // the wave's 2048 coordinates use 32 sign words: lane l < 32 hashes word l, every thread fetches its own
@@ -233,12 +235,18 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
         } else {
 #pragma unroll
             for (int e = 0; e < 32; ++e) {
-                const uint32_t sgn = (bits << (31 - e)) & 0x80000000u;          // hash bit 1 -> s_i = -1
-                sum[e] = fmaf(u[e], __uint_as_float(scale | sgn), sum[e]);
+                // hash bit 1 -> s_i = -1: the factor is the scale with bit e of the sign word moved to the sign position
+                // (one shift, one bit-field insert)
+                const uint32_t shifted = bits << (31 - e);
+                const uint32_t factor = (scale & 0x7FFFFFFFu) | (shifted & 0x80000000u);
+                sum[e] = fmaf(u[e], __uint_as_float(factor), sum[e]);
             }
         }
         __syncthreads();                                         // LDS is reused by the next sender
-    }
+    };
+    float loaded[32];
+    if (!PRE && c_begin < c_end) load(c_begin, loaded);
+    for (uint32_t c = c_begin; c < c_end; ++c) one_sender(c, loaded);
     if constexpr (PRE) {                                         // this thread's 32 pairs = 64 consecutive coordinates of acc
         const uint64_t out = 2 * first;
         if (out + 64 <= d) {
@@ -296,15 +304,9 @@ uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d_src, in
                                double *partials, uint32_t partial_stride, hipStream_t st) {
     const uint64_t d = pre ? (d_src + 1) / 2 : d_src;
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);
-    const bool pairs = tiles >= 256;                             // pairs of tiles: the second one's loads overlap the first
-    dim3 grid(pairs ? (tiles + 1) / 2 : tiles, n);
-    if (pre) {
-        if (pairs) hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_lo14_first<2, true>), grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
-        else hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_lo14_first<1, true>), grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
-    } else {
-        if (pairs) hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_lo14_first<2, false>), grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
-        else hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_lo14_first<1, false>), grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
-    }
+    dim3 grid(tiles, n);
+    if (pre) hipLaunchKernelGGL(k_enc_lo14_first<true>, grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
+    else hipLaunchKernelGGL(k_enc_lo14_first<false>, grid, dim3(512), 0, st, B, d_src, log2D, seed, T, partials, partial_stride);
     return grid.x;
 }
 void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, float *T,
@@ -313,15 +315,17 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vectors
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);     // tiles that reach below d
     if (pre == 1) {
-        hipLaunchKernelGGL(k_dec_lo14_last<true>, dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, narrow, acc,
-                           tiles, 1u, 0u, partial, 0);
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<true, false>), dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T,
+                           scratch, narrow, acc, tiles, 1u, 0u, partial, 0);
         return;
     }
     if (pre == 2) {                                              // every sender on its own, back into its workspace slot
-        hipLaunchKernelGGL(k_dec_lo14_last<false>, dim3(tiles * n), dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, 0, acc,
-                           0u, n, tiles, T, 1);
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, false>), dim3(tiles * n), dim3(512), 0, st, B, n, d_src, log2D, seed,
+                           T, scratch, 0, acc, 0u, n, tiles, T, 1);
         return;
     }
+    bool all16 = narrow != 0;                                    // every sender's workspace slot holds int16
+    for (uint32_t c = 0; c < n; ++c) all16 = all16 && B.b_q8[c] <= 256u;
     // Fewer tiles than half the resident workgroups: split every tile K ways by sender so that the chip is filled
     // (measured 2.2x on 64 tiles x 32 senders).  With more tiles than resident workgroups, splitting only the
     // last, partly filled wave of workgroups was measured 3..10% slower than leaving it: a CU with one workgroup runs it faster.
@@ -333,8 +337,12 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     }
     if (K == 1) { full = tiles; rest = 0; }
     dim3 grid(full + rest * K);
-    hipLaunchKernelGGL(k_dec_lo14_last<false>, grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, narrow, acc, full, K,
-                       rest, partial, 0);
+    if (all16)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, true>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
+                           narrow, acc, full, K, rest, partial, 0);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, false>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
+                           narrow, acc, full, K, rest, partial, 0);
     if (K > 1) {
         dim3 cgrid((uint32_t)((((uint64_t)rest << kLo14Bits) / 4 + 255) / 256));
         hipLaunchKernelGGL(k_dec_lo14_combine, cgrid, dim3(256), 0, st, acc, d, full, K, rest, partial);
