@@ -54,6 +54,12 @@
  *     with I_{k+1}, the other one with I_k.  The paper flips an independent coin per coordinate,
  *     which makes the message length random; choosing exactly one coordinate of every pair is as
  *     content independent and gives exactly (k + 1/2) D bits at positions known without a scan).
+ *     EDEN_B_COIN(q) (0x40000 | q, 256 < q < 1024, q not a multiple of 256): b = q/256, the non-integer budgets of
+ *     Sec. 4.1 in the paper's own form: coordinate i is quantized with I_{floor(b)+1} iff its coin says so, the coin
+ *     being "byte (i & 7) of word (i >> 3) of the MIX stream is below q & 255" (probability b - floor(b), independent
+ *     from coordinate to coordinate), else with I_{floor(b)}.  The message length then depends on the coins (never on
+ *     the data): eden_message_bytes returns the room that fits any outcome; the header records how many coordinates
+ *     got the extra bit, and the message ends 8 ceil(that / 64) bytes after the first part of the payload.
  *     EDEN_B_HALF_PRE (0x10080): b = 1/2 with the sparsification before the rotation (Sec. 4.1, the
  *     paper's default for b < 1): x'[g] = 2 x[2g + o_g], g < ceil(d/2), o_g = bit (g & 63) of word (g >> 6)
  *     of the SUB-SAMPLING stream (x read as 0 beyond d), is encoded with b = 1 in dimension ceil(d/2): the
@@ -80,13 +86,16 @@
  *   - Message = 64-byte little-endian header + payload of uint32 words:
  *       off  0 u32 magic 0x4E454445   off  4 u32 log2(D)      off  8 u64 d
  *       off 16 u32 b_q8               off 20 u32 client id    off 24 u32 status bits
- *       off 28 u32 0                  off 32 f64 S            off 40 f64 |x|^2
+ *       off 28 u32 extra bits (EDEN_B_COIN: coordinates with a coin; else 0)
+ *                                     off 32 f64 S            off 40 f64 |x|^2
  *       off 48 f64 <R(x), Q>          off 56 u64 seed
  *     Payload: the j-th transmitted index occupies bits [(j*b) mod 32, +b) of word floor(j*b/32),
  *     least significant bit first; the payload is padded with zero bits to a multiple of 64 bits.
  *     For b = k + 1/2 the payload has two such parts: first the low k bits of every coordinate's index
  *     (packed as for budget k), then, 64-bit aligned, one bit per pair: the top bit of the (k+1)-bit
  *     index of the pair's chosen coordinate.
+ *     For EDEN_B_COIN the payload has two parts as well: the low floor(b) bits of every coordinate's index, then, 64-bit
+ *     aligned, one bit for every coordinate with a coin, in coordinate order: the top bit of its index.
  *     S = |x|^2 / <R(x), Q(eta R(x))> is the sender's scale (Sec. 2.3), always computed over all
  *     D coordinates (the sender does not change under loss or sub-sampling, Sec. 4.2).
  *   - A packet is 1024 consecutive rotated coordinates (one packet if D < 1024).  A received-packet
@@ -98,6 +107,7 @@
 #define EDEN_B_HALF_PRE 0x10080u
 #define EDEN_B_SPARSE(m) (0x20000u | (unsigned)(m))
 #define EDEN_B_GRID(q) (0x30000u | (unsigned)(q))
+#define EDEN_B_COIN(q) (0x40000u | (unsigned)(q))
 
 #include <stddef.h>
 #include <stdint.h>
@@ -157,7 +167,7 @@ int eden_encode(eden_ctx *ctx, const float *const *x_dev, const uint32_t *client
 
 /* eden_encode for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same arguments, same kernels and bit-identical messages as eden_encode, but no context: the
- * workspace is a fixed device array inside the library (about 45 MiB on every GPU the library is loaded on, held until
+ * workspace is a fixed device array inside the library (about 47 MiB on every GPU the library is loaded on, held until
  * the process ends), so the call is limited to n <= EDEN_STATIC_MAX_N senders of d <= EDEN_STATIC_MAX_D coordinates;
  * beyond that it returns EDEN_ERR_STATIC_LIMIT and does nothing.  It runs on the current HIP device and calls no
  * hipMalloc, hipFree or other allocating routine; the first call on a device also looks up the array's address, uploads

@@ -32,6 +32,7 @@ struct eden_ctx {
     uint8_t *codes;              // slots * D_max bytes: one-byte indices of b = 5, 6, 7 senders before packing / after
                                  // unpacking (multi-pass sizes only)
     float *stage;                // d_max + 64 floats: the kept coordinates of one sender with a budget b = m/64
+    CoinTables coin;             // coin budgets at multi-pass sizes: masks and prefix sums of the coins, per slot
     EncScratch *enc_scratch; // slots
     DecScratch *dec_scratch; // slots
     DevTables *tables;
@@ -49,6 +50,12 @@ int ceil_log2(uint64_t d) {
     int l = 0;
     while ((1ull << l) < d) ++l;
     return l;
+}
+
+// groups of kCoinGroup blocks of 64 coordinates at the largest dimension
+uint32_t coin_group_stride(int log2D_max) {
+    const uint64_t words = log2D_max > 6 ? (1ull << (log2D_max - 6)) : 1;
+    return (uint32_t)((words + kCoinGroup - 1) / kCoinGroup);
 }
 
 // d rounded up to a multiple of 2^bits
@@ -168,6 +175,14 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
         ok = ok && hipMalloc(&ctx->codes, (size_t)ctx->slots * D_max) == hipSuccess;
     }
     ok = ok && hipMalloc(&ctx->stage, (size_t)(d_max + 64) * sizeof(float)) == hipSuccess;
+    ctx->coin = CoinTables{};
+    ctx->coin.group_stride = coin_group_stride(ctx->log2D_max);
+    if (ctx->log2D_max > kLoBits) {
+        ok = ok && hipMalloc(&ctx->coin.mask, (size_t)ctx->slots * (D_max / 64) * sizeof(uint64_t)) == hipSuccess;
+        ok = ok && hipMalloc(&ctx->coin.local, (size_t)ctx->slots * (D_max / 64) * sizeof(uint32_t)) == hipSuccess;
+        ok = ok && hipMalloc(&ctx->coin.group, (size_t)ctx->slots * ctx->coin.group_stride * sizeof(uint32_t)) == hipSuccess;
+    }
+    ok = ok && hipMalloc(&ctx->coin.total, ctx->slots * sizeof(uint32_t)) == hipSuccess;
     if (ctx->log2D_max >= 19 && ctx->slots > 1) {                // at most as many split tiles as workgroups fit on the chip
         ctx->dec_partial_tiles = 2 * ctx->compute_units;
         ok = ok && hipMalloc(&ctx->dec_partial, ((size_t)ctx->dec_partial_tiles << 14) * sizeof(float)) == hipSuccess;
@@ -202,7 +217,8 @@ int eden_destroy(eden_ctx *ctx) {
     bool ok = guard.ok;
     for (hipEvent_t e : ctx->prof_start) ok = (hipEventDestroy(e) == hipSuccess) && ok;
     for (hipEvent_t e : ctx->prof_stop) ok = (hipEventDestroy(e) == hipSuccess) && ok;
-    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->stage, ctx->codes, ctx->hist, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status};
+    void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->stage, ctx->codes, ctx->hist, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status,
+                    ctx->coin.mask, ctx->coin.local, ctx->coin.group, ctx->coin.total};
     for (void *p : ptrs)
         if (p) ok = (hipFree(p) == hipSuccess) && ok;
     delete ctx;
@@ -251,6 +267,14 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
             double *part_n2 = ctx->partials, *part_ip = ctx->partials + (size_t)ctx->slots * ctx->partial_stride;
             bool need_thresholds = false;                        // b = 1 and 1/2 quantize by sign alone
             for (uint32_t i = 0; i < nb; ++i) need_thresholds = need_thresholds || B.b_q8[i] > 256u;
+            bool coins = false;                                  // coin budgets: masks and prefix sums of the coins first
+            void *part_b[kMaxBatch] = {};
+            for (uint32_t i = 0; i < nb; ++i) {
+                if (!coin_q8(B.b_q8[i])) continue;
+                coins = true;
+                part_b[i] = static_cast<char *>(B.msg[i]) + EDEN_HEADER_BYTES + payload_a_bytes(1ull << log2D, (int)(coin_q8(B.b_q8[i]) >> 8), 1);
+            }
+            if (coins) launch_coin_tables(B.client, B.b_q8, part_b, nb, seed, log2D, ctx->coin, st);
             {
                 Timed t(ctx, EDEN_K_ENC_FIRST, nb, st);
                 nparts_n2 = pl.lo_bits == 14
@@ -271,17 +295,17 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
                 } else {
                     Timed t(ctx, EDEN_K_ENC_LAST, nb, st);
                     nparts_ip = h.wg     ? launch_enc_hix_last(h.M, B, nb, d, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
-                                                               ctx->enc_scratch, st)
+                                                               ctx->enc_scratch, ctx->coin, st)
                                 : h.wide ? launch_enc_wide_last(B, nb, valid, log2D, ctx->T, part_ip, ctx->partial_stride,
                                                                 ctx->enc_scratch, st)
                                          : launch_enc_hi_last(h.M, B, nb, valid, log2D, h.p, seed, ctx->T, part_ip,
-                                                              ctx->partial_stride, ctx->enc_scratch, st);
+                                                              ctx->partial_stride, ctx->enc_scratch, ctx->coin, st);
                 }
             }
             if (pack) launch_pack_bits(B, nb, log2D, st);
             Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
             launch_enc_finish(B, nb, hdr_d, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
-                              ctx->dev_status, st);
+                              ctx->dev_status, ctx->coin.total, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
     }
@@ -389,7 +413,13 @@ constexpr size_t kOffPartials = kOffStage + static_align((kStaticDmax + 64) * si
 constexpr size_t kOffEncScratch = kOffPartials + static_align(2 * (size_t)EDEN_STATIC_MAX_N * kStaticPartialStride * sizeof(double));
 constexpr size_t kOffTables = kOffEncScratch + static_align(EDEN_STATIC_MAX_N * sizeof(EncScratch));
 constexpr size_t kOffStatus = kOffTables + static_align(sizeof(DevTables));
-constexpr size_t kStaticBytes = kOffStatus + 256;               // about 45 MiB
+constexpr size_t kStaticCoinWords = kStaticDmax / 64;           // blocks of 64 coordinates per slot
+constexpr size_t kStaticCoinGroups = (kStaticCoinWords + kCoinGroup - 1) / kCoinGroup;
+constexpr size_t kOffCoinMask = kOffStatus + 256;
+constexpr size_t kOffCoinLocal = kOffCoinMask + static_align(EDEN_STATIC_MAX_N * kStaticCoinWords * sizeof(uint64_t));
+constexpr size_t kOffCoinGroup = kOffCoinLocal + static_align(EDEN_STATIC_MAX_N * kStaticCoinWords * sizeof(uint32_t));
+constexpr size_t kOffCoinTotal = kOffCoinGroup + static_align(EDEN_STATIC_MAX_N * kStaticCoinGroups * sizeof(uint32_t));
+constexpr size_t kStaticBytes = kOffCoinTotal + 256;            // about 47 MiB
 constexpr int kStaticMaxDevices = 64;
 }  // namespace
 
@@ -426,6 +456,11 @@ int static_context(int dev, hipStream_t st, eden_ctx **out) {
         c.enc_scratch = reinterpret_cast<EncScratch *>(ptr + kOffEncScratch);
         c.tables = reinterpret_cast<DevTables *>(ptr + kOffTables);
         c.dev_status = reinterpret_cast<uint32_t *>(ptr + kOffStatus);
+        c.coin.mask = reinterpret_cast<uint64_t *>(ptr + kOffCoinMask);
+        c.coin.local = reinterpret_cast<uint32_t *>(ptr + kOffCoinLocal);
+        c.coin.group = reinterpret_cast<uint32_t *>(ptr + kOffCoinGroup);
+        c.coin.total = reinterpret_cast<uint32_t *>(ptr + kOffCoinTotal);
+        c.coin.group_stride = (uint32_t)kStaticCoinGroups;
         c.dec_partial = nullptr; c.dec_partial_tiles = 0; c.hist = nullptr; c.dec_scratch = nullptr;
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
@@ -504,9 +539,12 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
             // Strided passes first (every sender on its own), contiguous pass last (sums the senders in registers
             // and touches acc once).  With a single strided pass the workspace of a b <= 1 sender holds int16.
             const int narrow = (pl.nhi == 1 && pre != 2) ? 1 : 0;
+            bool coins = false;                                  // the receiver draws and counts the same coins
+            for (uint32_t i = 0; i < nb; ++i) coins = coins || coin_q8(B.b_q8[i]);
+            if (coins) launch_coin_tables(B.client, B.b_q8, nullptr, nb, seed, log2D, ctx->coin, st);
             {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
-                launch_dec_prepare(B, nb, hdr_d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, st);
+                launch_dec_prepare(B, nb, hdr_d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, ctx->coin.total, st);
             }
             for (int i = pl.nhi - 1; i >= 0; --i) {
                 const HiPass &h = pl.hi[i];
@@ -514,9 +552,9 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
                 const uint64_t keep = round_up(d, h.p);
                 if (i == pl.nhi - 1) {
                     Timed t(ctx, EDEN_K_DEC_FIRST, nb, st);
-                    if (h.wg) launch_dec_hix_first(h.M, B, nb, d, log2D, seed, ctx->dec_scratch, narrow, ctx->T, st);
+                    if (h.wg) launch_dec_hix_first(h.M, B, nb, d, log2D, seed, ctx->dec_scratch, narrow, ctx->T, ctx->coin, st);
                     else if (h.wide) launch_dec_wide_first(B, nb, keep, log2D, ctx->dec_scratch, ctx->T, st);
-                    else launch_dec_hi_first(h.M, B, nb, keep, log2D, h.p, seed, ctx->dec_scratch, narrow, ctx->T, st);
+                    else launch_dec_hi_first(h.M, B, nb, keep, log2D, h.p, seed, ctx->dec_scratch, narrow, ctx->T, ctx->coin, st);
                 } else {
                     Timed t(ctx, EDEN_K_MID, nb, st);
                     launch_hix_mid(h.M, nb, ctx->T, log2D, round_up(d, h.p + h.M), keep, st);

@@ -64,7 +64,20 @@ __host__ __device__ inline uint32_t wide_bits(uint32_t b_q8) {
 }
 __host__ __device__ inline bool byte_budget(uint32_t b_q8) { return grid_q15(b_q8) != 0u || wide_bits(b_q8) != 0u; }
 __host__ __device__ inline bool budget_mixed(uint32_t b_q8) { return b_q8 == 384 || b_q8 == 640 || b_q8 == 896; }
+// General non-integer b > 1 in the paper's own form (Sec. 4.1): every coordinate is quantized with I_{floor(b)+1} with
+// probability b - floor(b), by an independent coin from the shared randomness: coordinate i gets the extra bit iff byte
+// (i & 7) of word (i >> 3) of the MIX stream is below 256 (b - floor(b)).  b = (b_q8 & 0xFFFF) / 256, 1 < b < 4, not an
+// integer.  The message length then depends on the coins (never on the data); positions in the second part of the payload
+// come from a prefix sum over the coins that a small kernel computes for sender and receiver alike.
+constexpr uint32_t kCoinFlag = 0x40000u;
+__host__ __device__ inline uint32_t coin_q8(uint32_t b_q8) {
+    const uint32_t low = b_q8 & 0xFFFFu;
+    return ((b_q8 & ~0xFFFFu) == kCoinFlag && low > 256u && low < 1024u && (low & 255u) != 0u) ? low : 0u;
+}
+// some coordinates carry one bit more than the others: the stratified k + 1/2 budgets and the coin budgets
+__host__ __device__ inline bool budget_two_tables(uint32_t b_q8) { return budget_mixed(b_q8) || coin_q8(b_q8) != 0u; }
 __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
+    if (coin_q8(b_q8)) { bits = (int)(coin_q8(b_q8) >> 8); k = 1; return true; }
     if (b_q8 == 128) { bits = 1; k = 2; return true; }
     if (b_q8 == 256 || b_q8 == 512 || b_q8 == 768 || b_q8 == 1024 || budget_mixed(b_q8)) {
         bits = (int)(b_q8 >> 8); k = 1; return true;
@@ -77,16 +90,34 @@ __host__ __device__ inline bool budget_of(uint32_t b_q8, int &bits, int &k) {
 __host__ __device__ inline uint64_t payload_a_bytes(uint64_t D, int bits, int k) {
     return ((((D / (uint64_t)k) * (uint64_t)bits) + 63) / 64) * 8;
 }
-// bytes of the second part (one bit per pair of coordinates) of a mixed budget
+// bytes of the second part (one bit per pair of coordinates) of a mixed budget; for a coin budget the room that fits
+// any outcome of the coins (one bit per coordinate)
 __host__ __device__ inline uint64_t payload_b_bytes(uint64_t D, uint32_t b_q8) {
+    if (coin_q8(b_q8)) return ((D + 63) / 64) * 8;
     return budget_mixed(b_q8) ? ((D / 2 + 63) / 64) * 8 : 0;
+}
+// bytes of the second part of a coin budget whose coins gave `extra_bits` coordinates the extra bit
+__host__ __device__ inline uint64_t coin_b_bytes(uint64_t extra_bits) { return ((extra_bits + 63) / 64) * 8; }
+
+// Coins of one sender, written by k_coin_masks / k_coin_scan: a lane mask per 64 consecutive coordinates, the number of
+// coins before each such block inside its group of 256 blocks, the number of coins before each group, and the total.
+constexpr int kCoinGroup = 256;          // blocks of 64 coordinates per group (one workgroup of k_coin_masks)
+struct CoinTables {
+    uint64_t *mask;                      // slot c: mask + (c << (log2D - 6)); bit j of word w: coordinate 64 w + j has a coin
+    uint32_t *local;                     // slot c: local + (c << (log2D - 6)); coins before block w inside its group
+    uint32_t *group;                     // slot c: group + c * group_stride; coins before group g
+    uint32_t *total;                     // total[c]: all coins of sender c = bits of the second part of its payload
+    uint32_t group_stride;
+};
+__device__ inline bool coin_of(uint64_t mixkey, uint64_t i, uint32_t frac) {
+    return ((uint32_t)(hash_word(mixkey, i >> 3) >> (8u * (uint32_t)(i & 7u))) & 0xFFu) < frac;
 }
 
 // ---- message header (64 bytes, little endian)
 struct MsgHeader {
     uint32_t magic, log2D;
     uint64_t d;
-    uint32_t b_q8, client, status, zero;
+    uint32_t b_q8, client, status, extra_bits;   // extra_bits: coin budgets only (bits of the second part), else 0
     double S, N2, IP;
     uint64_t seed;
 };
@@ -426,6 +457,40 @@ __device__ inline uint32_t quantize_mixed(float u, bool up, const EncScratch *sc
     const uint32_t code_lo = neg ? (uint32_t)(HL - 1) - mag_lo : (uint32_t)HL + mag_lo;
     const uint32_t code_hi = neg ? (uint32_t)(HH - 1) - mag_hi : (uint32_t)HH + mag_hi;
     return up ? code_hi : code_lo;
+}
+
+// ---- coin budgets: positions in the second part of the payload
+// coins before the block of 64 coordinates number w of sender slot c
+__device__ inline uint32_t coins_before(const CoinTables &ct, uint32_t c, int log2D, uint32_t w) {
+    return ct.group[(size_t)c * ct.group_stride + w / (uint32_t)kCoinGroup] + ct.local[((size_t)c << (log2D - 6)) + w];
+}
+__device__ inline uint64_t coin_mask_of(const CoinTables &ct, uint32_t c, int log2D, uint32_t w) {
+    return ct.mask[((size_t)c << (log2D - 6)) + w];
+}
+// set bits of `mask` below this lane's position
+__device__ inline uint32_t lanes_below(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi(hi32(mask), __builtin_amdgcn_mbcnt_lo(lo32(mask), 0u));
+}
+// the bits of `value` at the set positions of `mask`, moved together towards bit 0 in the same order
+__device__ inline uint64_t compress_bits(uint64_t value, uint64_t mask) {
+    uint64_t out = 0, place = 1;
+    while (mask) {
+        const uint64_t lowest = mask & (0 - mask);
+        if (value & lowest) out |= place;
+        place <<= 1;
+        mask ^= lowest;
+    }
+    return out;
+}
+// ORs the low `count` bits of `value` (the others are zero) into a zeroed little-endian bit string at bit `off`
+__device__ inline void or_bits(uint32_t *words, uint32_t off, uint64_t value, uint32_t count) {
+    if (!count) return;
+    const uint32_t w = off >> 5, sh = off & 31u;
+    const uint64_t low = value << sh;
+    const uint32_t v0 = (uint32_t)low, v1 = (uint32_t)(low >> 32), v2 = sh ? (uint32_t)(value >> (64u - sh)) : 0u;
+    if (v0) atomicOr(words + w, v0);
+    if (v1) atomicOr(words + w + 1, v1);
+    if (v2) atomicOr(words + w + 2, v2);
 }
 
 // Butterflies over the low LOGB bits of the register index only.

@@ -19,7 +19,11 @@ uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d, int pre,
                              double *partials, uint32_t partial_stride, hipStream_t st);
 uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, int p, uint64_t seed,
                             const float *T, double *partials, uint32_t partial_stride, const EncScratch *scratch,
-                            hipStream_t st);
+                            const CoinTables &ct, hipStream_t st);
+// coin budgets (multi-pass sizes): the coins of the senders that have such a budget, with their prefix sums; `part_b`
+// (encode) points at the second part of every such sender's payload, which is cleared; null on the receiver's side
+void launch_coin_tables(const uint32_t *clients, const uint32_t *b_q8, void *const *part_b, uint32_t n, uint64_t seed, int log2D,
+                        const CoinTables &ct, hipStream_t st);
 // wide strided tiles (8 rows x 512 columns per wave) for the top three index bits of D >= 2^25; b = 1, 2, 4, 5..8 and
 // the uniform grid
 uint32_t launch_enc_wide_last(const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, const float *T, double *partials,
@@ -30,11 +34,11 @@ void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint
                      EncScratch *scratch, const DevTables *tab, hipStream_t st);
 void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed,
                        const double *partials_n2, uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip,
-                       uint32_t partial_stride, uint32_t *dev_status, hipStream_t st);
+                       uint32_t partial_stride, uint32_t *dev_status, const uint32_t *coin_total, hipStream_t st);
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
-                        DecScratch *scratch, uint32_t *dev_status, hipStream_t st);
+                        DecScratch *scratch, uint32_t *dev_status, const uint32_t *coin_total, hipStream_t st);
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
-                         const DecScratch *scratch, int narrow, float *T, hipStream_t st);
+                         const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st);
 // pre: 0 = sum the senders into acc; 1 = the same with the pairs scatter of EDEN_B_HALF_PRE; 2 = no sum, every sender's
 // decoded vector goes back into its own workspace slot (fp32, `narrow` must be 0)
 void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
@@ -66,10 +70,11 @@ void launch_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t 
 
 // workgroup-tile strided passes for D >= 2^21 (eden_kernels_wg.hip)
 uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
-                             double *partials, uint32_t partial_stride, const EncScratch *scratch, hipStream_t st);
+                             double *partials, uint32_t partial_stride, const EncScratch *scratch, const CoinTables &ct,
+                             hipStream_t st);
 void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems, uint64_t store_elems, hipStream_t st);
 void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
-                          const DecScratch *scratch, int narrow, float *T, hipStream_t st);
+                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st);
 
 // 14-bit contiguous passes for D >= 2^19 (eden_kernels_lo14.hip)
 uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,

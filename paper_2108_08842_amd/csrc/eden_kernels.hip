@@ -31,7 +31,7 @@ __device__ inline void fill_enc_scratch(EncScratch *s, double n2, uint32_t b_q8,
         return;
     }
     if (wide_bits(b_q8)) return;                                 // b = 5..8: the long tables are filled by fill_byte_tables
-    const int finer = budget_mixed(b_q8) ? bits + 1 : bits;
+    const int finer = budget_two_tables(b_q8) ? bits + 1 : bits;
     for (int i = 0; i < 8; ++i) {
         s->thr[i] = (float)(tab->t[bits][i] * norm);
         s->qpos[i] = (float)tab->q[bits][i];
@@ -98,25 +98,33 @@ __device__ inline void store_row_planes(const uint32_t (&plane)[4][2], uint32_t 
 }
 
 // Quantizes the R rows of a wave tile (register r = row r, one column per lane) and packs them.  K: bits of every
-// index in the first part of the payload.  MIX (b = K + 1/2, Sec. 4.1): the coordinate of every pair that the MIX
+// index in the first part of the payload.  MIX = 1 (b = K + 1/2, Sec. 4.1): the coordinate of every pair that the MIX
 // stream selects is quantized with I_{K+1}; the top bit of its index goes to the second part, one bit per pair.
+// MIX = 2 (coin budgets, Sec. 4.1): the coordinates with a coin (`my_mask`: the coins of this lane's row) are quantized
+// with I_{K+1}; their top bits go to the second part in coordinate order, the row's first one at bit `my_off`.
 // `my_row`: first coordinate of the row that this lane (< R) finishes.
-template <int R, int K, bool MIX>
+template <int R, int K, int MIX>
 __device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *sc, const float *qtab, uint64_t mixkey,
-                                        uint64_t my_row, uint32_t *part_a, uint32_t *part_b, float &ip) {
+                                        uint64_t my_row, uint32_t *part_a, uint32_t *part_b, float &ip,
+                                        uint64_t my_mask = 0, uint32_t my_off = 0) {
     constexpr int H = 1 << (K - 1);
     const uint32_t lane = lane_id();
     uint32_t plane[4][2], top[2] = {0u, 0u};
 #pragma unroll
     for (int b = 0; b < 4; ++b) plane[b][0] = plane[b][1] = 0;
     // 64 pairs per hash word = 128 coordinates; a row segment uses 32 of them
-    const uint32_t offs_mine = MIX ? (uint32_t)(hash_word(mixkey, my_row >> 7) >> (32u * (uint32_t)((my_row >> 6) & 1u))) : 0u;
+    const uint32_t offs_mine = MIX == 1 ? (uint32_t)(hash_word(mixkey, my_row >> 7) >> (32u * (uint32_t)((my_row >> 6) & 1u))) : 0u;
     static_for<R>([&](auto RR) {
         constexpr int r = decltype(RR)::value;
         uint32_t code;
-        if constexpr (MIX) {
-            const uint32_t offs = __builtin_amdgcn_readlane(offs_mine, r);
-            const bool up = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
+        if constexpr (MIX != 0) {
+            bool up;
+            if constexpr (MIX == 1) {
+                const uint32_t offs = __builtin_amdgcn_readlane(offs_mine, r);
+                up = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
+            } else {
+                up = __builtin_amdgcn_inverse_ballot_w64(wave_read64(my_mask, r));
+            }
             code = quantize_mixed<K>(v[r], up, sc, qtab, ip);
             const uint64_t m = __ballot((code >> K) & 1u);
             top[0] = put_lane<r>(lo32(m), top[0]);
@@ -133,8 +141,12 @@ __device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *s
     });
     if (lane < R) {
         store_row_planes<K>(plane, part_a, my_row);
-        if constexpr (MIX)                                       // only the chosen coordinate of a pair can have the bit
+        if constexpr (MIX == 1)                                  // only the chosen coordinate of a pair can have the bit
             part_b[my_row >> 6] = even_bits(top[0] | (top[0] >> 1)) | (even_bits(top[1] | (top[1] >> 1)) << 16);
+        if constexpr (MIX == 2) {                                // only a coordinate with a coin can have the bit
+            const uint64_t top64 = (uint64_t)top[0] | ((uint64_t)top[1] << 32);
+            or_bits(part_b, my_off, compress_bits(top64, my_mask), (uint32_t)__popcll(my_mask));
+        }
     }
 }
 
@@ -147,7 +159,7 @@ __device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *s
 template <int M>
 __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_elems, int log2D, int p, uint64_t seed,
                                                      const float *T, double *partials, uint32_t partial_stride,
-                                                     const EncScratch *scratch) {
+                                                     const EncScratch *scratch, CoinTables ct) {
     constexpr int R = 1 << M;
     __shared__ double red[4];
     __shared__ float qtabs[4][16];
@@ -224,14 +236,23 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
                     const uint32_t quad = quad_bytes(__float_as_uint(v[r]), lane);
                     if (!(lane & 3u)) *reinterpret_cast<uint32_t *>(bytes + base + ((uint64_t)r << p) + lane) = quad;
                 }
+            } else if (const uint32_t cq = coin_q8(b_q8)) {
+                // the coins of this lane's row, and where the row's first extra bit goes in the second part
+                const uint32_t w = (uint32_t)(my_row >> 6);
+                const uint64_t my_mask = coin_mask_of(ct, c, log2D, w);
+                const uint32_t my_off = coins_before(ct, c, log2D, w);
+                uint32_t *part_c = payload + payload_a_bytes(1ull << log2D, (int)(cq >> 8), 1) / 4;
+                if ((cq >> 8) == 1u) hi_quantize_pack<R, 1, 2>(v, sc, qtab, mixkey, my_row, payload, part_c, ip, my_mask, my_off);
+                else if ((cq >> 8) == 2u) hi_quantize_pack<R, 2, 2>(v, sc, qtab, mixkey, my_row, payload, part_c, ip, my_mask, my_off);
+                else hi_quantize_pack<R, 3, 2>(v, sc, qtab, mixkey, my_row, payload, part_c, ip, my_mask, my_off);
             } else
             switch (b_q8) {
-                case 384u: hi_quantize_pack<R, 1, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
-                case 512u: hi_quantize_pack<R, 2, false>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
-                case 640u: hi_quantize_pack<R, 2, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
-                case 768u: hi_quantize_pack<R, 3, false>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
-                case 896u: hi_quantize_pack<R, 3, true>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
-                default: hi_quantize_pack<R, 4, false>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 384u: hi_quantize_pack<R, 1, 1>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 512u: hi_quantize_pack<R, 2, 0>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 640u: hi_quantize_pack<R, 2, 1>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 768u: hi_quantize_pack<R, 3, 0>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                case 896u: hi_quantize_pack<R, 3, 1>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
+                default: hi_quantize_pack<R, 4, 0>(v, sc, qtab, mixkey, my_row, payload, part_b, ip); break;
             }
         }
     }
@@ -268,7 +289,7 @@ __global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *part
 // for all of them; measured 0.057 against 0.073 ms on 32 senders at D = 2^20.)
 template <int M>
 __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t keep_elems, int log2D, int p, uint64_t seed,
-                                                      const DecScratch *scratch, int narrow, float *T) {
+                                                      const DecScratch *scratch, int narrow, float *T, CoinTables ct) {
     constexpr int R = 1 << M;
     __shared__ float table[4][32];
     __shared__ float gtabs[4][kGridMax + 1];                     // uniform grid: dequantized centres of mass
@@ -346,6 +367,28 @@ __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t ke
             const bool up = ((offs >> (lane >> 1)) & 1u) == (lane & 1u);
             const uint32_t top = (wb >> (lane >> 1)) & 1u;
             v[r] = up ? tb2[(top << bits) | low] : tb[low];
+        }
+    } else if (coin_q8(b_q8)) {
+        // coin budgets (Sec. 4.1): every coordinate has `bits` bits in the first part; a coordinate with a coin was
+        // quantized with the finer table and has its top bit in the second part, at the position of its rank among the coins
+        const uint32_t w = (uint32_t)(my_row >> 6);
+        const uint64_t mask_mine = coin_mask_of(ct, c, log2D, w);
+        const uint32_t off_mine = coins_before(ct, c, log2D, w);
+        const uint32_t lbits = lane * (uint32_t)bits, words_row = 2u * (uint32_t)bits;
+        const rsrc_t rp = make_rsrc(payload + (base >> 6) * words_row, payload_bytes - (uint32_t)(base >> 6) * words_row * 4u);
+        const rsrc_t rb = make_rsrc(payload + payload_bytes / 4u, (uint32_t)coin_b_bytes(ct.total[c]));
+        const uint32_t voff = (lbits >> 5) * 4u, shift = lbits & 31u;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int soff = (int)((((uint32_t)r * words_row) << (p - 6)) * 4u);
+            const uint32_t w0 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, soff, 0);
+            const uint32_t w1 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0);    // always: no branch per value
+            const uint32_t low = code_at(w0, w1, shift, bits);
+            const uint64_t m = wave_read64(mask_mine, r);
+            const uint32_t rank = __builtin_amdgcn_readlane(off_mine, r) + lanes_below(m);
+            const uint32_t wb = __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((rank >> 5) * 4u), 0, 0);   // beyond the part: 0
+            const uint32_t top = (wb >> (rank & 31u)) & 1u;
+            v[r] = __builtin_amdgcn_inverse_ballot_w64(m) ? tb2[(top << bits) | low] : tb[low];
         }
     } else if (bits == 3) {
         // 64 columns x 3 bits = 6 words per row; an index may straddle two words
@@ -664,7 +707,7 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t hdr_d, 
                                                     const double *partials_n2, uint32_t nparts_n2,
                                                     const double *partials_ip, uint32_t nparts_ip,
                                                     uint32_t partial_stride, uint32_t payload_words_b1,
-                                                    uint32_t *dev_status) {
+                                                    uint32_t *dev_status, const uint32_t *coin_total) {
     __shared__ double red[4];
     __shared__ double n2_shared;
     const uint32_t c = blockIdx.x;
@@ -690,13 +733,13 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t hdr_d, 
         int bits, k;
         budget_of(b_q8, bits, k);
         const uint64_t D = 32ull * payload_words_b1;
-        const uint64_t nw = (payload_a_bytes(D, bits, k) + payload_b_bytes(D, b_q8)) / 4;
+        const uint64_t nw = (payload_a_bytes(D, bits, k) + (coin_q8(b_q8) ? coin_b_bytes(coin_total[c]) : payload_b_bytes(D, b_q8))) / 4;
         for (uint64_t i = threadIdx.x; i < nw; i += 256) payload[i] = 0u;
     }
     if (threadIdx.x == 0) {
         MsgHeader h;
         h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = hdr_d; h.b_q8 = B.hdr_b_q8[c]; h.client = B.client[c];
-        h.zero = 0; h.seed = seed; h.N2 = n2;
+        h.extra_bits = coin_q8(b_q8) ? coin_total[c] : 0u; h.seed = seed; h.N2 = n2;
         if (valid) {
             h.IP = total * exp2(-0.5 * (double)log2D);       // <R(x),Q> = D^-1/2 sum u_i q_i
             h.S = n2 / h.IP;                                  // Sec. 2.3
@@ -717,14 +760,15 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t hdr_d, 
 // that arrived (Sec. 4.2: the receiver finds p by counting), and build the dequantization table
 // (S / (p sqrt(D))) * q_l  -- S/p from Sec. 4.2, D^-1/2 from the inverse rotation.
 // `hdr_d`, `hdr_b_q8`: what the header must say; `b_q8`: the budget the kernels dequantize with.
+// `extra_bits`: coin budgets only, the number of coins the receiver counted itself; the header must agree.
 __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap, uint32_t client, uint32_t b_q8,
                                         uint32_t hdr_b_q8, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
-                                        DecScratch *out, uint32_t *dev_status) {
+                                        DecScratch *out, uint32_t *dev_status, uint32_t extra_bits = 0) {
     const uint32_t lane = lane_id();
     const MsgHeader h = *static_cast<const MsgHeader *>(msg);
     uint32_t flags = 0;
     if (h.magic != kMagic || h.log2D != (uint32_t)log2D || h.d != hdr_d || h.b_q8 != hdr_b_q8 ||
-        h.client != client || h.seed != seed)
+        h.client != client || h.seed != seed || (coin_q8(b_q8) && h.extra_bits != extra_bits))
         flags |= EDEN_DEV_HEADER_MISMATCH;
     else
         flags |= h.status & (EDEN_DEV_ZERO_VECTOR | EDEN_DEV_NONFINITE);
@@ -751,7 +795,7 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
     if (flags == 0) coef = h.S * exp2(0.5 * (double)log2D) / (double)arrived;     // S / (p sqrt(D)), p = arrived / D
     if (sparse_m(hdr_b_q8)) coef *= 64.0 / (double)sparse_m(hdr_b_q8);             // the 1/p of the sparsification (Sec. 4.1)
     if (lane < 32) {                                             // lanes 16..31: the finer table of a mixed budget
-        const int tb = (lane < 16 || !budget_mixed(b_q8)) ? bits : bits + 1;
+        const int tb = (lane < 16 || !budget_two_tables(b_q8)) ? bits : bits + 1;
         const int H = 1 << (tb - 1), l = (int)(lane & 15u);
         double q = 0.0;
         if (l < 2 * H) q = (l >= H) ? tab->q[tb][l - H] : -tab->q[tb][H - 1 - l];
@@ -776,9 +820,85 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
 }
 
 __global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t hdr_d, int log2D, uint64_t seed,
-                                                    const DevTables *tab, DecScratch *scratch, uint32_t *dev_status) {
+                                                    const DevTables *tab, DecScratch *scratch, uint32_t *dev_status,
+                                                    const uint32_t *coin_total) {
     const uint32_t c = blockIdx.x;
-    dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], hdr_d, log2D, seed, tab, &scratch[c], dev_status);
+    dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], hdr_d, log2D, seed, tab, &scratch[c], dev_status,
+                     coin_q8(B.b_q8[c]) ? coin_total[c] : 0u);
+}
+
+// ---- coin budgets (Sec. 4.1): the coins of every sender of a launch that has such a budget, as lane masks per block of 64
+// coordinates, with the prefix sums that give every block its place in the second part of the payload.  Both sides run
+// this from the shared seed alone.  One thread per block of 64 coordinates (8 hash words of 8 coins each).
+struct CoinBatch {
+    uint32_t client[kMaxBatch];
+    uint32_t b_q8[kMaxBatch];
+    void *part_b[kMaxBatch];             // encode: the second part of the sender's payload, cleared here; decode: null
+};
+__device__ inline uint32_t block_exclusive_scan_256(uint32_t mine, uint32_t *wave_totals /* shared, 4 */, uint32_t &block_total) {
+    const uint32_t lane = lane_id(), wv = threadIdx.x >> 6;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = (uint32_t)__shfl_up((int)incl, o, 64);
+        if (lane >= (uint32_t)o) incl += v;
+    }
+    if (lane == 63) wave_totals[wv] = incl;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < 4; ++i) { before += i < wv ? wave_totals[i] : 0u; all += wave_totals[i]; }
+    __syncthreads();
+    block_total = all;
+    return before + incl - mine;
+}
+__global__ __launch_bounds__(256) void k_coin_masks(CoinBatch B, uint64_t seed, int log2D, CoinTables ct) {
+    __shared__ uint32_t wave_totals[4];
+    const uint32_t c = blockIdx.y;
+    const uint32_t frac = coin_q8(B.b_q8[c]) & 255u;
+    if (!frac) return;                                           // not a coin budget: the whole workgroup leaves
+    const uint32_t words = 1u << (log2D - 6);
+    const uint32_t w = blockIdx.x * (uint32_t)kCoinGroup + threadIdx.x;
+    uint64_t m = 0;
+    if (w < words) {
+        const uint64_t key = stream_key(seed, kStreamMix, B.client[c]);
+#pragma unroll
+        for (uint32_t j = 0; j < 8; ++j) {
+            const uint64_t h = hash_word(key, 8ull * w + j);
+#pragma unroll
+            for (uint32_t b = 0; b < 8; ++b)
+                if (((uint32_t)(h >> (8u * b)) & 0xFFu) < frac) m |= 1ull << (8u * j + b);
+        }
+    }
+    uint32_t group_total;
+    const uint32_t before = block_exclusive_scan_256((uint32_t)__popcll(m), wave_totals, group_total);
+    if (w < words) {
+        ct.mask[((size_t)c << (log2D - 6)) + w] = m;
+        ct.local[((size_t)c << (log2D - 6)) + w] = before;
+        if (B.part_b[c]) static_cast<uint64_t *>(B.part_b[c])[w] = 0ull;
+    }
+    if (threadIdx.x == 0) ct.group[(size_t)c * ct.group_stride + blockIdx.x] = group_total;
+}
+// One workgroup per sender: the group totals become the number of coins before each group, and the grand total.
+__global__ __launch_bounds__(256) void k_coin_scan(CoinBatch B, int log2D, CoinTables ct) {
+    __shared__ uint32_t wave_totals[4];
+    const uint32_t c = blockIdx.x;
+    if (!coin_q8(B.b_q8[c])) return;
+    const uint32_t words = 1u << (log2D - 6);
+    const uint32_t groups = (words + (uint32_t)kCoinGroup - 1) / (uint32_t)kCoinGroup;
+    const uint32_t per = (groups + 255u) / 256u;
+    uint32_t *g = ct.group + (size_t)c * ct.group_stride;
+    const uint32_t first = threadIdx.x * per;
+    uint32_t mine = 0;
+    for (uint32_t i = first; i < first + per && i < groups; ++i) mine += g[i];
+    uint32_t all;
+    uint32_t run = block_exclusive_scan_256(mine, wave_totals, all);
+    for (uint32_t i = first; i < first + per && i < groups; ++i) {
+        const uint32_t v = g[i];
+        g[i] = run;
+        run += v;
+    }
+    if (threadIdx.x == 0) ct.total[c] = all;
 }
 
 // Decode, last pass in wave tiles: index bits 0..11 of H for every sender, that sender's sign diagonal
@@ -1084,6 +1204,8 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
     __shared__ uint8_t code[kLoTile];
     __shared__ double red[4];
     __shared__ EncScratch s;
+    __shared__ uint32_t coin_words[kLoTile / 32];              // coin budgets: the second part of the payload
+    __shared__ uint32_t wave_totals[4];
     const uint32_t c = blockIdx.x;
     const uint32_t D = 1u << log2D;
     const float *x = B.x[c];
@@ -1114,6 +1236,7 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
     const double n2 = s.n2;
     float ip = 0.0f;
     const bool mix = budget_mixed(b_q8);                       // b = k + 1/2: one coordinate of every pair uses I_{k+1}
+    const uint32_t coin_frac = coin_q8(b_q8) & 255u;           // coin budgets: a coordinate with a coin uses I_{k+1}
     const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
     const bool bytes = byte_budget(b_q8);                      // uniform grid (Sec. 4.3) or b = 5..8: one-byte indices
     for (uint32_t i = threadIdx.x; i < D; i += 256) {
@@ -1125,7 +1248,8 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
         }
         const float a = fabsf(u);
         const uint32_t g = i >> 1;
-        const bool up = mix && ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u));
+        const bool up = coin_frac ? coin_of(mixkey, i, coin_frac)
+                                  : (mix && ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u)));
         const float *thr = up ? s.thr2 : s.thr, *qp = up ? s.qpos2 : s.qpos;
         const int Hu = up ? 2 * H : H;
         uint32_t mag = 0;
@@ -1169,10 +1293,29 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
             payload[nwords + w] = valid ? word : 0u;
         }
     }
+    uint32_t extra_bits = 0;
+    if (coin_frac) {
+        // second part: the top bits of the coordinates with a coin, in coordinate order.  A thread looks after 16
+        // consecutive coordinates; a scan over the threads gives the place of its bits.
+        for (uint32_t w = threadIdx.x; w < (uint32_t)kLoTile / 32u; w += 256) coin_words[w] = 0u;
+        uint32_t m16 = 0, t16 = 0;
+        for (uint32_t e = 0; e < 16u; ++e) {
+            const uint32_t i = 16u * threadIdx.x + e;
+            if (i < D && coin_of(mixkey, i, coin_frac)) {
+                m16 |= 1u << e;
+                t16 |= (((uint32_t)code[i] >> bits) & 1u) << e;
+            }
+        }
+        const uint32_t before = block_exclusive_scan_256((uint32_t)__popc(m16), wave_totals, extra_bits);   // barriers inside
+        or_bits(coin_words, before, compress_bits(t16, m16), (uint32_t)__popc(m16));
+        __syncthreads();
+        const uint32_t nwords_b = 2u * ((extra_bits + 63u) / 64u);
+        for (uint32_t w = threadIdx.x; w < nwords_b; w += 256) payload[nwords + w] = valid ? coin_words[w] : 0u;
+    }
     if (threadIdx.x == 0) {
         MsgHeader h;
         h.magic = kMagic; h.log2D = (uint32_t)log2D; h.d = hdr_d; h.b_q8 = B.hdr_b_q8[c]; h.client = B.client[c];
-        h.zero = 0; h.seed = seed; h.N2 = n2;
+        h.extra_bits = extra_bits; h.seed = seed; h.N2 = n2;
         if (valid) {
             h.IP = ipt * exp2(-0.5 * (double)log2D);
             h.S = n2 / h.IP;
@@ -1192,14 +1335,28 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
                                                    uint64_t seed, const DevTables *tab, float *acc, uint32_t *dev_status) {
     __shared__ float buf[kLoTile];
     __shared__ DecScratch s;
+    __shared__ uint32_t coin_m16[256], coin_pre[256], wave_totals[4];   // coin budgets: coins of 16 coordinates, coins before them
     const uint32_t D = 1u << log2D;
     float sum[kLoTile / 256];
 #pragma unroll
     for (int r = 0; r < kLoTile / 256; ++r) sum[r] = 0.0f;
     for (uint32_t c = 0; c < n; ++c) {
         __syncthreads();
+        const uint32_t coin_frac = coin_q8(B.b_q8[c]) & 255u;
+        uint32_t extra_bits = 0;
+        if (coin_frac) {                                         // the receiver draws the same coins and counts them
+            const uint64_t ckey = stream_key(seed, kStreamMix, B.client[c]);
+            uint32_t m16 = 0;
+            for (uint32_t e = 0; e < 16u; ++e) {
+                const uint32_t i = 16u * threadIdx.x + e;
+                if (i < D && coin_of(ckey, i, coin_frac)) m16 |= 1u << e;
+            }
+            coin_m16[threadIdx.x] = m16;
+            coin_pre[threadIdx.x] = block_exclusive_scan_256((uint32_t)__popc(m16), wave_totals, extra_bits);
+        }
         if (threadIdx.x < 64)
-            dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], hdr_d, log2D, seed, tab, &s, dev_status);
+            dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], hdr_d, log2D, seed, tab, &s, dev_status,
+                             extra_bits);
         __syncthreads();
         const uint32_t b_q8 = B.b_q8[c];
         int bits, k;
@@ -1228,6 +1385,10 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
                 const uint32_t g = i >> 1;
                 if ((uint32_t)((hash_word(mixkey, g >> 6) >> (g & 63u)) & 1ull) == (i & 1u))
                     val = s.deq2[(((payload[nwords + (g >> 5)] >> (g & 31u)) & 1u) << bits) | idx];
+            }
+            if (coin_frac && ((coin_m16[i >> 4] >> (i & 15u)) & 1u)) {
+                const uint32_t rank = coin_pre[i >> 4] + (uint32_t)__popc(coin_m16[i >> 4] & ((1u << (i & 15u)) - 1u));
+                val = s.deq2[(((payload[nwords + (rank >> 5)] >> (rank & 31u)) & 1u) << bits) | idx];
             }
             buf[i] = here ? val : 0.0f;
         }
@@ -1295,11 +1456,11 @@ __global__ void k_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uin
 
 uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, int p, uint64_t seed,
                             const float *T, double *partials, uint32_t partial_stride, const EncScratch *scratch,
-                            hipStream_t st) {
+                            const CoinTables &ct, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
     EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_enc_hi_last<MM>, grid, dim3(256), 0, st, B, valid_elems, log2D, p, seed, T, partials,
-                                         partial_stride, scratch));
+                                         partial_stride, scratch, ct));
     return grid.x;
 }
 uint32_t launch_enc_wide_last(const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, const float *T, double *partials,
@@ -1319,17 +1480,29 @@ void launch_enc_norm(const EncBatch &B, uint32_t n, const double *partials, uint
 }
 void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed,
                        const double *partials_n2, uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip,
-                       uint32_t partial_stride, uint32_t *dev_status, hipStream_t st) {
+                       uint32_t partial_stride, uint32_t *dev_status, const uint32_t *coin_total, hipStream_t st) {
     const uint32_t words_b1 = 1u << (log2D - 5);
     hipLaunchKernelGGL(k_enc_finish, dim3(n), dim3(256), 0, st, B, hdr_d, log2D, seed, partials_n2, nparts_n2, partials_ip,
-                       nparts_ip, partial_stride, words_b1, dev_status);
+                       nparts_ip, partial_stride, words_b1, dev_status, coin_total);
+}
+void launch_coin_tables(const uint32_t *clients, const uint32_t *b_q8, void *const *part_b, uint32_t n, uint64_t seed, int log2D,
+                        const CoinTables &ct, hipStream_t st) {
+    CoinBatch B;
+    for (uint32_t i = 0; i < (uint32_t)kMaxBatch; ++i) {
+        B.client[i] = i < n ? clients[i] : 0u;
+        B.b_q8[i] = i < n ? b_q8[i] : 0u;
+        B.part_b[i] = (i < n && part_b) ? part_b[i] : nullptr;
+    }
+    const uint32_t words = 1u << (log2D - 6);
+    hipLaunchKernelGGL(k_coin_masks, dim3((words + kCoinGroup - 1) / kCoinGroup, n), dim3(256), 0, st, B, seed, log2D, ct);
+    hipLaunchKernelGGL(k_coin_scan, dim3(n), dim3(256), 0, st, B, log2D, ct);
 }
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
-                         const DecScratch *scratch, int narrow, float *T, hipStream_t st) {
+                         const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
     EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_first<MM>, grid, dim3(256), 0, st, B, keep_elems, log2D, p, seed, scratch, narrow,
-                                         T));
+                                         T, ct));
 }
 uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, float *T,
                              double *partials, uint32_t partial_stride, hipStream_t st) {
@@ -1340,8 +1513,8 @@ uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d_src, int 
     return grid.x;
 }
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
-                        DecScratch *scratch, uint32_t *dev_status, hipStream_t st) {
-    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, hdr_d, log2D, seed, tab, scratch, dev_status);
+                        DecScratch *scratch, uint32_t *dev_status, const uint32_t *coin_total, hipStream_t st) {
+    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, hdr_d, log2D, seed, tab, scratch, dev_status, coin_total);
 }
 void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {

@@ -107,19 +107,22 @@ __device__ inline uint32_t hix_word_row(int ph, int w) {
 
 // Quantizes and packs the RP values a thread holds after one half of the exchange (rows hix_row2(g, PH, s)).
 // `word0`: payload word index of this tile's 32 columns in row 0; `base`: first coordinate of the tile.
-// BITS: bits of every index in the first part of the payload.  MIX (b = BITS + 1/2, Sec. 4.1): the coordinate of
+// BITS: bits of every index in the first part of the payload.  MIX = 1 (b = BITS + 1/2, Sec. 4.1): the coordinate of
 // every pair that the MIX stream selects is quantized with I_{BITS+1}; the top bit of its index goes to the
-// second part of the payload, one bit per pair = 16 bits per row segment of a tile.
-template <int M, int BITS, bool MIX>
+// second part of the payload, one bit per pair = 16 bits per row segment of a tile.  MIX = 2 (coin budgets, Sec. 4.1):
+// the coordinates with a coin use I_{BITS+1}; their top bits go to the second part (`part_c`) in coordinate order, at the
+// place the prefix sums over the coins give the row segment.
+template <int M, int BITS, int MIX>
 __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph, const EncScratch *sc, const float *qtab,
-                                         uint32_t *payload, uint16_t *part_b, uint64_t mixkey, uint64_t base, float &ip) {
+                                         uint32_t *payload, uint16_t *part_b, uint64_t mixkey, uint64_t base, float &ip,
+                                         const CoinTables &ct, uint32_t c, int log2D, uint32_t *part_c) {
     using X = HiX<M>;
     constexpr int p = kHixP;
     constexpr int H = 1 << (BITS - 1);
     constexpr int NW = X::RP / 32;                               // registers come in blocks of 32 = one word lane each
     const uint32_t lane = lane_id(), col = lane & 31u;
     const uint32_t word0 = (uint32_t)(base >> 5);
-    uint32_t plane[BITS][NW], top[NW], offs16[NW];
+    uint32_t plane[BITS][NW], top[NW], offs16[NW], coin_off[NW];
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
         top[w] = 0;
@@ -127,16 +130,23 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
         for (int b = 0; b < BITS; ++b) plane[b][w] = 0;
         // this lane's row for register block w, and the 16 pair offsets of that row segment (64 pairs per hash word)
         const uint64_t first = base + ((uint64_t)hix_word_row<M>(ph, w) << p);
-        offs16[w] = MIX ? (uint32_t)(hash_word(mixkey, first >> 7) >> (16u * (uint32_t)((first >> 5) & 3u))) & 0xFFFFu : 0u;
+        offs16[w] = MIX == 1 ? (uint32_t)(hash_word(mixkey, first >> 7) >> (16u * (uint32_t)((first >> 5) & 3u))) & 0xFFFFu : 0u;
+        coin_off[w] = 0;
+        if constexpr (MIX == 2) {                                // the 32 coins of that row segment: half of a block of 64
+            const uint32_t blk = (uint32_t)(first >> 6), upper = (uint32_t)(first >> 5) & 1u;
+            const uint64_t m64 = coin_mask_of(ct, c, log2D, blk);
+            offs16[w] = upper ? hi32(m64) : lo32(m64);
+            coin_off[w] = coins_before(ct, c, log2D, blk) + (upper ? (uint32_t)__popc(lo32(m64)) : 0u);
+        }
     }
     static_for<X::RP>([&](auto S) {
         constexpr int s = decltype(S)::value;
         uint32_t code;
-        if constexpr (MIX) {
+        if constexpr (MIX != 0) {
             const uint32_t oa = __builtin_amdgcn_readlane(offs16[s / 32], s % 32);
             const uint32_t ob = __builtin_amdgcn_readlane(offs16[s / 32], 32 + s % 32);
             const uint32_t offs = (lane < 32u) ? oa : ob;
-            const bool up = ((offs >> (col >> 1)) & 1u) == (col & 1u);
+            const bool up = MIX == 1 ? ((offs >> (col >> 1)) & 1u) == (col & 1u) : ((offs >> col) & 1u) != 0u;
             code = quantize_mixed<BITS>(out[s], up, sc, qtab, ip);
             const uint64_t m = __ballot((code >> BITS) & 1u);
             top[s / 32] = put_lane<s % 32>(lo32(m), top[s / 32]);
@@ -174,7 +184,9 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
                        (spread4(plane[2][w] >> (8 * k)) << 2) | (spread4(plane[3][w] >> (8 * k)) << 3);
             *reinterpret_cast<uint4 *>(payload + 4u * word) = make_uint4(o[0], o[1], o[2], o[3]);
         }
-        if constexpr (MIX) part_b[word] = (uint16_t)even_bits(top[w] | (top[w] >> 1));    // only the chosen one can be set
+        if constexpr (MIX == 1) part_b[word] = (uint16_t)even_bits(top[w] | (top[w] >> 1));    // only the chosen one can be set
+        if constexpr (MIX == 2)                                  // only a coordinate with a coin can have the bit
+            or_bits(part_c, coin_off[w], compress_bits(top[w], offs16[w]), (uint32_t)__popc(offs16[w]));
     }
 }
 
@@ -213,7 +225,8 @@ template <> struct WordVec<4> { using type = uint4; };
 template <int M, int TPW, int MODE>
 __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_last(EncBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                    const float *T, double *partials,
-                                                                   uint32_t partial_stride, const EncScratch *scratch) {
+                                                                   uint32_t partial_stride, const EncScratch *scratch,
+                                                                   CoinTables ct) {
     using X = HiX<M>;
     __shared__ float lds[X::LDS_FLOATS];
     __shared__ double red[X::THREADS / 64];
@@ -282,13 +295,22 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
                     if (!(col & 3u)) *reinterpret_cast<uint32_t *>(bytes + ((uint64_t)hix_row2<M>(g, ph, s2) << p)) = quad;
                 }
             } else {
-                uint16_t *part_b = reinterpret_cast<uint16_t *>(payload + payload_a_bytes(1ull << log2D, (int)(b_q8 >> 8), 1) / 4);
-                if (MODE == 2 && b_q8 == 384u) hix_quantize_pack<M, 1, true>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
-                else if (MODE == 2 && b_q8 == 640u) hix_quantize_pack<M, 2, true>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
-                else if (MODE == 2 && b_q8 == 896u) hix_quantize_pack<M, 3, true>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
-                else if (b_q8 == 512u) hix_quantize_pack<M, 2, false>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
-                else if (b_q8 == 768u) hix_quantize_pack<M, 3, false>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
-                else hix_quantize_pack<M, 4, false>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip);
+                int ibits, ik;
+                budget_of(b_q8, ibits, ik);
+                uint32_t *part_c = payload + payload_a_bytes(1ull << log2D, ibits, 1) / 4;       // second part, if any
+                uint16_t *part_b = reinterpret_cast<uint16_t *>(part_c);
+                const uint32_t cq = MODE == 2 ? coin_q8(b_q8) : 0u;
+#define EDEN_HIX_PACK(BITS, MIX) hix_quantize_pack<M, BITS, MIX>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip, ct, c, log2D, part_c)
+                if (cq && ibits == 1) EDEN_HIX_PACK(1, 2);
+                else if (cq && ibits == 2) EDEN_HIX_PACK(2, 2);
+                else if (cq) EDEN_HIX_PACK(3, 2);
+                else if (MODE == 2 && b_q8 == 384u) EDEN_HIX_PACK(1, 1);
+                else if (MODE == 2 && b_q8 == 640u) EDEN_HIX_PACK(2, 1);
+                else if (MODE == 2 && b_q8 == 896u) EDEN_HIX_PACK(3, 1);
+                else if (b_q8 == 512u) EDEN_HIX_PACK(2, 0);
+                else if (b_q8 == 768u) EDEN_HIX_PACK(3, 0);
+                else EDEN_HIX_PACK(4, 0);
+#undef EDEN_HIX_PACK
             }
         }
     }
@@ -388,7 +410,8 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D
 // 14 .. 14+M-1 of H.
 template <int M>
 __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B, uint64_t d, int log2D, uint64_t seed,
-                                                                    const DecScratch *scratch, int narrow, float *T) {
+                                                                    const DecScratch *scratch, int narrow, float *T,
+                                                                    CoinTables ct) {
     using X = HiX<M>;
     constexpr int p = kHixP;
     __shared__ float lds[X::LDS_FLOATS];
@@ -455,6 +478,35 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B
         } else {
 #pragma unroll
             for (int r = 0; r < 64; ++r) v[r] = dequantize_byte<false>(__float_as_uint(v[r]), H, gtab);
+        }
+    } else if (coin_q8(b_q8)) {
+        // coin budgets (Sec. 4.1): every coordinate has `bits` bits in the first part; a coordinate with a coin was
+        // quantized with the finer table and has its top bit in the second part, at the position of its rank among the
+        // coins.  Lane l fetches the coins of the two row segments the wave reads into register l.
+        const uint32_t upper = (uint32_t)(base >> 5) & 1u;       // which half of a block of 64 coordinates this tile's columns are
+        const uint32_t blk_a = (uint32_t)((base + row_a) >> 6), blk_b = (uint32_t)((base + row_b) >> 6);
+        const uint64_t m64_a = coin_mask_of(ct, c, log2D, blk_a), m64_b = coin_mask_of(ct, c, log2D, blk_b);
+        const uint32_t ma = upper ? hi32(m64_a) : lo32(m64_a), mb = upper ? hi32(m64_b) : lo32(m64_b);
+        const uint32_t oa = coins_before(ct, c, log2D, blk_a) + (upper ? (uint32_t)__popc(lo32(m64_a)) : 0u);
+        const uint32_t ob = coins_before(ct, c, log2D, blk_b) + (upper ? (uint32_t)__popc(lo32(m64_b)) : 0u);
+        const uint32_t cbits = col * (uint32_t)bits;
+        const rsrc_t rp = make_rsrc(payload + ((base * (uint32_t)bits) >> 5), payload_bytes - (uint32_t)((base * (uint32_t)bits) >> 5) * 4u);
+        const uint32_t voff = (((g * (uint32_t)bits) << (p - 5)) + (cbits >> 5)) * 4u;
+        const uint32_t shift = cbits & 31u;
+        const rsrc_t rb = make_rsrc(payload + payload_bytes / 4u, (uint32_t)coin_b_bytes(ct.total[c]));
+        const uint32_t below = (1u << col) - 1u;
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const int soff = (int)((((uint32_t)X::RL * r * (uint32_t)bits) << (p - 5)) * 4u);
+            const uint32_t w0 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff, soff, 0);
+            const uint32_t w1 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0);    // always: no branch per value
+            const uint32_t low = code_at(w0, w1, shift, bits);
+            const uint32_t m = (lane < 32u) ? __builtin_amdgcn_readlane(ma, r) : __builtin_amdgcn_readlane(mb, r);
+            const uint32_t o = (lane < 32u) ? __builtin_amdgcn_readlane(oa, r) : __builtin_amdgcn_readlane(ob, r);
+            const uint32_t rank = o + (uint32_t)__popc(m & below);
+            const uint32_t wb = __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((rank >> 5) * 4u), 0, 0);   // beyond the part: 0
+            const uint32_t top = (wb >> (rank & 31u)) & 1u;
+            v[r] = ((m >> col) & 1u) ? table[16u + ((top << bits) | low)] : table[low];
         }
     } else if (budget_mixed(b_q8)) {
         // b = bits + 1/2 (Sec. 4.1): every coordinate has `bits` bits in the first part; the coordinate of each pair
@@ -685,16 +737,17 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatc
 static uint32_t hix_tiles(int M, int log2D) { return 1u << (log2D - M - 5); }
 
 uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
-                             double *partials, uint32_t partial_stride, const EncScratch *scratch, hipStream_t st) {
+                             double *partials, uint32_t partial_stride, const EncScratch *scratch, const CoinTables &ct,
+                             hipStream_t st) {
     const uint32_t tiles = hix_tiles(M, log2D);                  // 512 whenever this pass sits directly on lo14
     bool unit = true, mixed = false;                             // every sender b <= 1; some sender b = k + 1/2
     for (uint32_t c = 0; c < n; ++c) {
         unit = unit && B.b_q8[c] <= 256u;
-        mixed = mixed || budget_mixed(B.b_q8[c]);
+        mixed = mixed || budget_two_tables(B.b_q8[c]);
     }
 #define EDEN_ENC_HIX_LAST(TPW, MODE)                                                                                          \
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, TPW, MODE>), grid, dim3(HiX<MM>::THREADS), 0, st, B, \
-                                          d, log2D, seed, T, partials, partial_stride, scratch))
+                                          d, log2D, seed, T, partials, partial_stride, scratch, ct))
     if (unit && tiles % 128u == 0) {                             // four neighbouring tiles per workgroup
         dim3 grid(tiles / 4, n);
         EDEN_ENC_HIX_LAST(4, 0);
@@ -716,7 +769,7 @@ void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems,
                                           load_elems, store_elems));
 }
 void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
-                          const DecScratch *scratch, int narrow, float *T, hipStream_t st) {
+                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st) {
     bool all_unit = narrow != 0;                                 // every sender b <= 1: packed int16 kernel
     for (uint32_t c = 0; c < n; ++c) all_unit = all_unit && B.b_q8[c] <= 256u;
     if (all_unit) {
@@ -726,6 +779,6 @@ void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
     }
     dim3 grid(hix_tiles(M, log2D), n);
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D, seed,
-                                          scratch, narrow, T));
+                                          scratch, narrow, T, ct));
 }
 }  // namespace eden

@@ -50,6 +50,14 @@ def B_SPARSE(m: int) -> int:
     return 0x20000 | m
 
 
+def B_COIN(b: float) -> int:
+    """General non-integer budget 1 < b < 4 (Sec. 4.1): every coordinate gets the extra bit with probability b - floor(b),
+    by an independent coin from the shared seed (EDEN_B_COIN(round(256 b)))."""
+    q = int(round(256 * b))
+    assert 256 < q < 1024 and q % 256 != 0
+    return 0x40000 | q
+
+
 KERNEL_KINDS = ["enc_first", "mid", "enc_last", "dec_prepare", "dec_first", "dec_last", "finalize_mean",
                 "enc_small", "dec_small", "enc_norm", "enc_finish"]
 

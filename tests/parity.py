@@ -184,7 +184,7 @@ def _check_scale(ref, tr, Q, gpu_msg):
 def _check_encode_fractional(ref, tr, b_q8, gpu_msg, stats):
     """General non-integer b > 1 (Sec. 4.1): per-coordinate width from the shared coins; the message length follows
     from the coins alone, so it must agree exactly."""
-    k = b_q8 // 256
+    k, _ = o.budget(b_q8)
     D = tr.z.size
     assert o.payload_words_fractional(D, b_q8, gpu_msg.seed, gpu_msg.client) == gpu_msg.payload.size
     got = o.unpack_fractional(gpu_msg.payload, D, b_q8, tr.up)

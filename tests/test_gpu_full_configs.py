@@ -83,10 +83,10 @@ def test_every_budget_at_the_headline_size():
     every sender checked coordinate by coordinate against the oracle, then decoded with 10% of the packets lost."""
     from paper_2108_08842_amd import eden
     d = synth.config(4).d
-    groups = [[128, 384, 512, 640, 768, 896, 1024, eden.B_GRID(0.5224), 1280, 1536, 1792, 2048],   # one call: same transform dimension
+    groups = [[128, 384, 512, 640, 768, 896, 1024, eden.B_GRID(0.5224), 1280, 1536, 1792, 2048, eden.B_COIN(2.7)],   # one call: same transform dimension
               [eden.B_HALF_PRE, eden.B_HALF_PRE],
               [eden.B_SPARSE(6), eden.B_SPARSE(45)]]
-    ctx = eden.Context(d_max=d, n_max=12, device=0)
+    ctx = eden.Context(d_max=d, n_max=13, device=0)
     for gi, budgets in enumerate(groups):
         n = len(budgets)
         w = synth.Workload("all_budgets", n, d, budgets, 60 + gi, "layers")
@@ -147,22 +147,24 @@ def test_three_pass_size():
     """D = 2^25: lo14, workgroup-tile strided pass on bits 14..20, wave-tile strided pass on bits 21..24."""
     from paper_2108_08842_amd import eden
     d = (1 << 24) + 12345
-    w = synth.Workload("three_pass", 2, d, [256, 768], 25, "normal_outliers")
-    print(f"three passes: n=2 d={d} D=2^25 budgets={w.b_q8} seed={w.seed}", flush=True)
-    xs = [synth.client_vector(w, c) for c in range(2)]
-    ctx = eden.Context(d_max=d, n_max=2, device=0)
-    msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], [5, 9], w.b_q8, w.seed)
+    coin = eden.B_COIN(1.5)
+    w = synth.Workload("three_pass", 3, d, [256, 768, coin], 25, "normal_outliers")
+    print(f"three passes: n=3 d={d} D=2^25 budgets={w.b_q8} seed={w.seed}", flush=True)
+    xs = [synth.client_vector(w, c) for c in range(3)]
+    ctx = eden.Context(d_max=d, n_max=3, device=0)
+    msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], [5, 9, 12], w.b_q8, w.seed)
     assert ctx.last_device_status() == 0
     stats = parity.EncodeParity()
     om = [parity.to_oracle_message(m) for m in msgs]
-    parity.check_encode(xs[1], w.seed, 9, 768, om[1], stats)         # one whole sender through the oracle (b = 3)
+    parity.check_encode(xs[1], w.seed, 9, 768, om[1], stats)         # two whole senders through the oracle (b = 3, 1.5)
+    parity.check_encode(xs[2], w.seed, 12, coin, om[2], stats)
     parity.finish_encode(stats)
     print("encode:", stats, flush=True)
-    bm = [ctx.make_loss_bitmap(w.seed, cid, 1 << 25, int(0.1 * 2 ** 32)) for cid in (5, 9)]
+    bm = [ctx.make_loss_bitmap(w.seed, cid, 1 << 25, int(0.1 * 2 ** 32)) for cid in (5, 9, 12)]
     acc = torch.zeros(d, device="cuda")
-    ctx.decode_accumulate(msgs[1:], [9], [768], d, w.seed, acc, bm[1:])
-    got = ctx.finalize_mean(acc, 1).cpu().numpy()
-    want = o.decode_mean([om[1]], d, [bm[1].cpu().numpy().view(np.uint32)])
+    ctx.decode_accumulate(msgs[1:], [9, 12], [768, coin], d, w.seed, acc, bm[1:])
+    got = ctx.finalize_mean(acc, 2).cpu().numpy()
+    want = o.decode_mean(om[1:], d, [b.cpu().numpy().view(np.uint32) for b in bm[1:]])
     err = parity.rel_l2(got, want)
     print(f"decode with 10% loss: rel L2 {err:.2e}", flush=True)
     assert err <= parity.MEAN_REL_L2

@@ -319,12 +319,28 @@ def test_budgets_of_five_to_eight_bits(ctx, d):
         assert eden.message_bytes(d, b) == o.message_bytes(d, b)
 
 
+@pytest.mark.parametrize("d", [1, 2, 3, 70, 4096, 5000, 70_000, 300_000, (1 << 20) + 1, 2_500_000, 6_000_000])
+def test_coin_budgets(ctx, d):
+    # general non-integer b > 1 (Sec. 4.1): an independent coin per coordinate decides which quantizer it uses; the
+    # message length follows from the coins and must agree with the oracle's to the word
+    from paper_2108_08842_amd import eden
+    budgets = [eden.B_COIN(1.3), eden.B_COIN(2.5), eden.B_COIN(3.9), eden.B_COIN(1 + 1 / 256), 384 if d >= 2 else 512]
+    w = synth.Workload("t", 5, d, budgets, 2600 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(5)]
+    _run_case(ctx, xs, [6, 7, 8, 9, 10], w.b_q8, w.seed, also_oracle_msgs=(d <= 300_000))
+    if d >= (1 << 14):
+        _run_case(ctx, xs, [6, 7, 8, 9, 10], w.b_q8, w.seed + 1, drop_q32=int(0.2 * 2 ** 32), also_oracle_msgs=False)
+    for b in budgets:
+        assert eden.message_bytes(d, b) == o.message_bytes(d, b)
+
+
 def test_random_shapes_and_budgets(ctx):
     # 60 seeded random cases: dimension (log-uniform up to 2^18 + tail), number of senders, any supported budget
     # per sender, sometimes lost packets, sometimes the sparsification before the rotation
     from paper_2108_08842_amd import eden
     rng = np.random.default_rng(20240)
-    budgets_all = [128, 256, 384, 512, 640, 768, 896, 1024, 1280, 1536, 1792, 2048]
+    budgets_all = [128, 256, 384, 512, 640, 768, 896, 1024, 1280, 1536, 1792, 2048, eden.B_COIN(1.7), eden.B_COIN(2.1),
+                   eden.B_COIN(3.5)]
     dists = ["normal", "lognormal", "lognormal_signed", "normal_outliers", "layers"]
     for case in range(60):
         d = int(2 ** rng.uniform(1.0, 18.2))
@@ -338,16 +354,23 @@ def test_random_shapes_and_budgets(ctx):
         _run_case(ctx, xs, ids, w.b_q8, int(rng.integers(0, 2 ** 62)), drop_q32=drop, also_oracle_msgs=(case % 4 == 0))
 
 
-def test_step_can_be_captured_in_a_graph(ctx):
+@pytest.mark.parametrize("kind", ["every_kind", "m_of_64_same", "m_of_64_different"])
+def test_step_can_be_captured_in_a_graph(ctx, kind):
     # encode + decode + mean make no allocation and no host synchronisation, so a caller may capture them; every
-    # replay, with other work in between, must reproduce the eager result bit for bit
-    d, n = 300_000, 6
-    w = synth.Workload("t", n, d, [128, 256, 384, 512, 768, 1024], 4242, "lognormal")
+    # replay, with other work in between, must reproduce the eager result bit for bit.  Covers the budgets whose
+    # buffers the context holds from its creation (byte indices of b = 6, staging of the m-of-64 budgets, coin tables).
+    from paper_2108_08842_amd import eden
+    d = 300_000
+    budgets = {"every_kind": [128, 256, 384, 512, 768, 1024, 1536, eden.B_COIN(2.3)],
+               "m_of_64_same": [eden.B_SPARSE(6)] * 3,
+               "m_of_64_different": [eden.B_SPARSE(6), eden.B_SPARSE(40)]}[kind]
+    n = len(budgets)
+    w = synth.Workload("t", n, d, budgets, 4242, "lognormal")
     D = o.padded_dim(d)
     xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(n)]
     ids = list(range(n))
     msgs = ctx.alloc_messages(d, w.b_q8)
-    bitmaps = [ctx.make_loss_bitmap(w.seed, c, D, int(0.1 * 2 ** 32)) for c in ids]
+    bitmaps = [ctx.make_loss_bitmap(w.seed, c, D, int(0.1 * 2 ** 32)) for c in ids] if kind == "every_kind" else None
     acc = torch.zeros(d, device="cuda")
     mean = torch.empty_like(acc)
 

@@ -38,8 +38,12 @@ def test_message_bytes_matches_oracle(eden):
                 assert eden.message_bytes(d, b) == 0
                 continue
             assert eden.message_bytes(d, b) == o.message_bytes(d, b)
+        for b in (384, 896, eden.B_COIN(1.5), eden.B_COIN(3.99), eden.B_GRID(0.5), 1536, eden.B_HALF_PRE, eden.B_SPARSE(9)):
+            if d >= 2:
+                assert eden.message_bytes(d, b) == o.message_bytes(d, b), (d, b)
     assert eden.message_bytes(0, 256) == 0
     assert eden.message_bytes(100, 300) == 0
+    assert eden.message_bytes(100, 0x40000 | 512) == 0 and eden.message_bytes(100, 0x40000 | 1100) == 0
 
 
 @pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 6, 7, 8])

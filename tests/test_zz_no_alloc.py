@@ -32,7 +32,7 @@ def test_static_encode_matches_encode_on_two_calls_in_a_row():
     assert torch.cuda.is_available()
     ctx = eden.Context(d_max=eden.STATIC_MAX_D, n_max=eden.STATIC_MAX_N, device=0)
     print("static encode: n=8 d=300001, every kind of budget", flush=True)
-    _both_ways(eden, ctx, 8, 300_001, [256, 512, 128, 768, 1536, 384, 1024, eden.B_GRID(0.5224)], 71, "lognormal_signed")
+    _both_ways(eden, ctx, 8, 300_001, [256, 512, 128, 768, 1536, 384, eden.B_COIN(2.4), eden.B_GRID(0.5224)], 71, "lognormal_signed")
     print("static encode: n=2 d=5000 (smaller, same workspace)", flush=True)
     _both_ways(eden, ctx, 2, 5000, [256, 1024], 72, "normal")
     print("static encode: n=3 d=2^20 (the limit), then d=700 (one workgroup per sender)", flush=True)
