@@ -19,7 +19,7 @@
  *     and keeps no caller pointer after the call returns.  Its only own device memory is the
  *     context workspace allocated by eden_create.
  *   - eden_encode, eden_decode_accumulate and eden_finalize_mean only launch kernels on `stream`: no
- *     allocation (except the first call with an EDEN_B_SPARSE budget), no memset, no host synchronisation,
+ *     allocation (every buffer any budget needs is allocated by eden_create), no memset, no host synchronisation,
  *     so they may be captured in a HIP graph.
  *   - A context serialises its work through that workspace: calls on one context must be issued from
  *     one thread at a time and on one stream (or on streams the caller orders); two calls that run
@@ -29,7 +29,6 @@
  *     Conditions that can only be seen on the device (zero or non-finite vector, nothing
  *     received, header mismatch) are recorded in the message header's status word and in a
  *     device status word that eden_last_device_status() reads (it synchronises).
- *   - One context must not be used from two streams at once (they would share the workspace).
  *
  * Dimensions and layout
  *   - d is padded with zeros to D = 2^ceil(log2 d); the rotation, the quantization and the
@@ -44,8 +43,7 @@
  *     4 = sparse (sort keys of the m-of-64 sparsification).
  *   - Bit budget b is passed as b_q8 = 256*b.  Supported: 256, 512, ..., 2048 (b = 1..8, the
  *     2^b-level Lloyd-Max quantizer of N(0,1), Sec. 3; for b = 5, 6, 7 at multi-pass sizes the indices are
- *     packed by a kernel of their own from a byte buffer of D_max bytes per workspace slot that the first
- *     such call allocates); 128 (b = 1/2: the b = 1 quantizer,
+ *     packed by a kernel of their own from a byte buffer of D_max bytes per workspace slot); 128 (b = 1/2: the b = 1 quantizer,
  *     then of every two consecutive rotated coordinates (2g, 2g+1) only the one at offset
  *     bit (g & 63) of word (g >> 6) of the SUB-SAMPLING stream is sent; Sec. 4.1, applied after
  *     the rotation, so the receiver treats the rest like lost coordinates, Sec. 4.2); and
@@ -73,9 +71,14 @@
  *     m ceil(d/64) kept values, in order, are encoded with b = 1 (unscaled: the method is scale equivariant), and
  *     the decoder multiplies by 64/m and puts them back.  Senders that share m are processed in batches, others
  *     one at a time; a call uses such budgets for all senders or for none; packets of a received-packet bitmap refer
- *     to the kept vector.  The first call that has to go sender by sender allocates d_max + 64 floats in the context.
+ *     to the kept vector.  When d is not a multiple of 64 some of the last block's kept positions fall on its virtual
+ *     zeros; for d < 64 it can happen that no real coordinate is kept at all (d = 4, m = 6, seed 0, client 0 is such a
+ *     case).  The message is then that of a zero vector: status EDEN_DEV_ZERO_VECTOR, S = 0, and the sender contributes
+ *     nothing to the mean in that round (the estimate stays unbiased over the seeds: every real coordinate is still kept
+ *     with probability m/64).  A caller that must tell this from x = 0 compares |x|^2 in the header with its own.
  *     EDEN_B_GRID(q) (0x30000 | q, 1 <= q <= 65535): the uniform-grid quantizer of Sec. 4.3 with
- *     Delta = q / 32768: index n = round(z / Delta) (ties to even), clipped to +-127 and sent as one signed byte
+ *     Delta = q / 32768: index n = sign(z) ceil(|z| / Delta - 1/2) (the nearest grid point; a value half way between
+ *     two goes to the one closer to zero, as the footnote of Sec. 2.2.1 asks), clipped to +-127 and sent as one signed byte
  *     per coordinate (the payload is D bytes; an entropy coder would bring it to about H(Delta) bits per
  *     coordinate, 3 bits at Delta = 0.5224); the value of index n is the centre of mass of N(0,1) on
  *     [Delta (n - 1/2), Delta (n + 1/2)] (the outermost intervals run to infinity).  A vector whose coordinates
@@ -138,9 +141,11 @@ typedef enum eden_status {
 #define EDEN_MAX_LOG2_D 27
 
 /* Creates a context on HIP device `hip_device` able to handle vectors up to d_max coordinates and
- * batches up to n_max senders per call.  Allocates the workspace: min(n_max, 32) * 4 * D_max bytes for the
- * transform's intermediate passes (none if D_max <= 4096), 32 MiB for sender-group sums of the last decode
- * pass when D_max >= 2^19 and n_max > 1, plus a few KiB of partial sums per sender;
+ * batches up to n_max senders per call.  Allocates everything any later call needs: per workspace slot (there are
+ * min(n_max, 32)) 4 * D_max bytes for the transform's intermediate passes, D_max bytes for the one-byte indices of
+ * b = 5, 6, 7 and 3/16 * D_max bytes for the coins of the EDEN_B_COIN budgets (none of the three if D_max <= 4096);
+ * 4 * (d_max + 64) bytes for the kept coordinates of an EDEN_B_SPARSE sender; 32 MiB for sender-group sums of the last
+ * decode pass when D_max >= 2^19 and n_max > 1; plus a few KiB of partial sums per sender;
  * solves the Lloyd-Max tables of Sec. 3 in double precision on the host and uploads them.
  * On failure *out is NULL. */
 int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device);

@@ -386,8 +386,10 @@ def grid_centroids(delta: float) -> np.ndarray:
 
 
 def grid_indices(z: np.ndarray, delta: float) -> np.ndarray:
-    """n = round(z / Delta) (Sec. 4.3), ties to even, clipped to the byte range."""
-    return np.clip(np.rint(z / delta), -GRID_MAX_INDEX, GRID_MAX_INDEX).astype(np.int64)
+    """Index of the interval [Delta (n - 1/2), Delta (n + 1/2)] that holds z (Sec. 4.3); a value on an endpoint goes to the
+    interval closer to zero (Sec. 2.2.1, footnote): n = sign(z) ceil(|z| / Delta - 1/2), clipped to the byte range."""
+    n = np.sign(z) * np.ceil(np.abs(z) / delta - 0.5)
+    return np.clip(n, -GRID_MAX_INDEX, GRID_MAX_INDEX).astype(np.int64)
 
 
 def empirical_entropy_bits(idx: np.ndarray) -> float:

@@ -49,7 +49,7 @@ __host__ __device__ inline uint32_t sparse_m(uint32_t b_q8) {
     return ((b_q8 & ~0xFFFFu) == kSparseFlag && m >= 1 && m <= 63) ? m : 0;
 }
 // Uniform-grid quantizer of Sec. 4.3: the intervals [Delta (n - 1/2), Delta (n + 1/2)], Delta = (b_q8 & 0xFFFF) / 32768;
-// the index n = round(z / Delta), clipped to +-127, travels as one signed byte (what an entropy coder would shrink to
+// the index n of the interval that holds z (endpoints: closer to zero), clipped to +-127, travels as one signed byte (what an entropy coder would shrink to
 // about H(Delta) bits); the value of an interval is its centre of mass under N(0,1).
 constexpr uint32_t kGridFlag = 0x30000u;
 constexpr int kGridMax = 127;
@@ -402,10 +402,13 @@ __device__ inline double grid_centroid(double delta, int n) {
 }
 // index of one coordinate on the uniform grid (as a signed byte in the low 8 bits) and its contribution |u| c to
 // sum_i u_i Q_i; `ctab`: the centres of mass in LDS
+// (a value on an interval endpoint goes to the interval closer to zero, Sec. 2.2.1 footnote: |n| = ceil(|z| / Delta - 1/2);
+// the subtraction is exact for every quotient that matters, so the rounding of the quotient is the only error)
 __device__ inline uint32_t quantize_grid(float u, float grid_inv, const float *ctab, float &ip) {
-    const float n = fminf(fmaxf(rintf(u * grid_inv), -(float)kGridMax), (float)kGridMax);
-    ip = fmaf(fabsf(u), ctab[(int)fabsf(n)], ip);
-    return (uint32_t)(int)n & 0xFFu;
+    const float m = fminf(ceilf(fabsf(u * grid_inv) - 0.5f), (float)kGridMax);
+    const int mag = (int)m;                                      // -0.0 below half a step: 0
+    ip = fmaf(fabsf(u), ctab[mag], ip);
+    return (uint32_t)((__float_as_uint(u) >> 31) ? -mag : mag) & 0xFFu;
 }
 // value of a received byte: sign(n) * table[|n|]
 __device__ inline float dequantize_grid(uint32_t byte, const float *dtab) {

@@ -30,6 +30,28 @@ def test_sq_error_matches_float64(ctx):
         assert abs(out[1] - a2) <= 1e-12 * a2
 
 
+def test_sq_error_matches_the_oracle_definitions(ctx):
+    # vNMSE of one sender (Sec. 2.3) and NMSE of a round (Sec. 2.1) as the oracle defines them, on the GPU's own estimates
+    from oracle import eden_oracle as o
+    from paper_2108_08842_amd import vnmse
+    d, n = 50_001, 5
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(21)
+    xs = [vnmse.draw("lognormal", d, gen, torch.device("cuda:0")) for _ in range(n)]
+    msgs = ctx.encode(xs, list(range(n)), [512] * n, 9)
+    acc = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs[:1], [0], [512], d, 9, acc)
+    out = ctx.sq_error(xs[0], acc).cpu().numpy()
+    want = o.vnmse_single(xs[0].cpu().numpy().astype(np.float64), acc.cpu().numpy().astype(np.float64))
+    assert abs(out[0] / out[1] - want) <= 1e-12 * want
+    got = vnmse.measure_nmse(ctx, xs, [512] * n, seed=9)
+    acc.zero_()
+    ctx.decode_accumulate(msgs, list(range(n)), [512] * n, d, 9, acc)
+    est = ctx.finalize_mean(acc, n).cpu().numpy().astype(np.float64)
+    want = o.nmse([x.cpu().numpy() for x in xs], est)
+    assert abs(got - want) <= 1e-5 * want          # the harness forms the true mean in fp32 on the device
+
+
 def test_theory_values_are_the_printed_ones():
     from paper_2108_08842_amd import vnmse
     assert abs(vnmse.theory_vnmse(1) - (math.pi / 2 - 1)) < 1e-12          # Sec. 3, Example 1: 0.571
@@ -38,6 +60,7 @@ def test_theory_values_are_the_printed_ones():
     assert abs(vnmse.theory_vnmse(1, keep=0.9) - (math.pi / 2 / 0.9 - 1)) < 1e-12
     assert abs(vnmse.theory_vnmse(1.5) - 0.317) < 1e-3                      # Sec. 4.1
     assert abs(vnmse.theory_vnmse(3) - 0.03572) < 1e-4                      # Sec. 4.3 (the I_3 value)
+    assert abs(vnmse.theory_vnmse(0.1) - 14.707) < 1e-3                     # Sec. 4.1, Cor. 4.2 example: pi/(2 * 0.1) - 1
 
 
 @pytest.mark.parametrize("dist", ["normal", "lognormal"])
@@ -48,10 +71,53 @@ def test_vnmse_close_to_theory(ctx, dist):
     gen.manual_seed(11)
     x = vnmse.draw(dist, d, gen, torch.device("cuda:0"))
     for b in (0.5, 1, 1.5, 2, 2.5, 3, 3.5, 4, 5, 6, 7, 8):
-        v, se = vnmse.measure_vnmse(ctx, x, int(b * 256), 16, seed=3)
+        v, se = vnmse.measure_vnmse(ctx, x, int(b * 256), 16, seed=3)      # k + 1/2: the one-of-every-pair variant
         th = vnmse.theory_vnmse(b)
         print(f"{dist} b={b}: vNMSE {v:.5f} +- {se:.5f}, theory {th:.5f}", flush=True)
         assert abs(v - th) <= 5 * se + 0.03 * th
+
+
+@pytest.mark.parametrize("dist", ["lognormal", "normal", "exponential", "chi2", "halfnormal", "beta"])
+def test_single_transform_meets_the_bound_for_every_distribution(ctx, dist):
+    # App. "Structured Rotation": one randomized Hadamard transform reaches the bound of Cor. 2.4 for these input
+    # distributions over a sweep of dimensions; sub-bit, integer and non-integer (coin) budgets; 100 trials at the
+    # smallest dimension, where a single trial is noisiest
+    from paper_2108_08842_amd import vnmse
+    for log2d, trials in ((12, 100), (15, 40), (18, 16)):
+        d = 1 << log2d
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(100 + log2d)
+        x = vnmse.draw(dist, d, gen, torch.device("cuda:0"))
+        for b in (0.25, 0.5, 1, 1.3, 2, 2.75, 4, 6):
+            bb, b_q8 = vnmse.budget_code(b)
+            th = vnmse.theory_sparse(b_q8 & 0xFFFF, d) if (b_q8 >> 16) == 2 else vnmse.theory_vnmse(bb)
+            v, se = vnmse.measure_vnmse(ctx, x, b_q8, trials, seed=5)
+            print(f"{dist} d=2^{log2d} b={bb:g}: vNMSE {v:.5f} +- {se:.5f}, theory {th:.5f}", flush=True)
+            # the bound is asymptotic: O(sqrt(log d / d)) above it at small d (Thm 2.3)
+            assert abs(v - th) <= 5 * se + (0.03 + 2.0 * math.sqrt(log2d / d)) * th
+
+
+def test_tail_drops_equal_sub_bit_compression(ctx):
+    # App. "Loss vs. Sub-bit" (d = 2^19): losing the tail of the packets and sending a uniformly sparsified vector give
+    # the same vNMSE when the same fraction of coordinates arrives, and both follow 1/(p E[Q^2]) - 1 (Lemma 4.3, Cor. 4.2)
+    from paper_2108_08842_amd import eden, vnmse
+    d = 1 << 19
+    big = eden.Context(d_max=d, n_max=16, device=0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(19)
+    x = vnmse.draw("lognormal", d, gen, torch.device("cuda:0"))
+    for f in (0.25, 0.5, 0.75):
+        bm, kept = vnmse.tail_drop_bitmap(d, f, torch.device("cuda:0"))
+        assert kept == 1.0 - f
+        v_loss, se_loss = vnmse.measure_vnmse(big, x, 256, 32, seed=2, bitmap=bm)
+        m = int(round(kept * 64))
+        v_sub, se_sub = vnmse.measure_vnmse(big, x, eden.B_SPARSE(m), 32, seed=2)
+        th = vnmse.theory_vnmse(1, kept)
+        print(f"p={kept}: tail drops {v_loss:.4f} +- {se_loss:.4f}, sub-bit {v_sub:.4f} +- {se_sub:.4f}, bound {th:.4f} "
+              f"(sub-bit with its padding: {vnmse.theory_sparse(m, d):.4f})", flush=True)
+        assert abs(v_loss - th) <= 5 * se_loss + 0.03 * th
+        assert abs(v_sub - vnmse.theory_sparse(m, d)) <= 5 * se_sub + 0.03 * th
+    big.close()
 
 
 def test_vnmse_with_sparsification_before_the_rotation(ctx):

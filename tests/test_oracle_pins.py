@@ -838,6 +838,20 @@ def test_sparse_budget_ragged_end():
     assert xh.size == d and not xh[not_kept].any() and np.count_nonzero(xh) > 30
 
 
+def test_sparse_budget_that_keeps_only_padding():
+    # d < 64: the m kept positions of the single block can all fall on its virtual zeros; the message is then that of a
+    # zero vector and decodes to nothing (documented behaviour of the m-of-64 budgets)
+    d, m = 4, 6
+    assert (o.sparse_selection(0, 0, d, m) >= d).all()
+    x = np.array([1.0, -2.0, 3.0, 0.5])
+    msg = o.encode(x, 0, 0, o.SPARSE | m)
+    assert msg.status == o.STATUS_ZERO_VECTOR and msg.S == 0.0 and not msg.payload.any()
+    assert not o.decode(msg, d).any()
+    # over the seeds every coordinate is still kept with probability m/64
+    kept = np.mean([(o.sparse_selection(s, 0, d, m) < d).sum() for s in range(4000)]) / d
+    assert abs(kept - m / 64) < 4 * math.sqrt((m / 64) * (1 - m / 64) / (4000 * d)) + 0.01
+
+
 # ---- uniform-grid quantizer I_Delta (Sec. 4.3)
 def test_grid_quantizer_printed_values(golden):
     # Delta_3 = 0.5224: entropy 3 bits and vNMSE 0.022741, both from the interval probabilities by plain erf sums
@@ -889,6 +903,10 @@ def test_grid_quantizer_path(golden):
     # an outlier beyond 127 Delta is clipped to the last interval
     z = np.array([100.0, -100.0, 0.2, 0.27])
     assert o.grid_indices(z, 0.5).tolist() == [127, -127, 0, 1]
+    # a value on an interval endpoint goes to the interval closer to zero (Sec. 2.2.1, footnote), on both sides of zero:
+    # with Delta = 1/2 the endpoints are +-0.25, +-0.75, +-1.25 (all exact in binary)
+    ends = np.array([0.25, -0.25, 0.75, -0.75, 1.25, -1.25, 0.0, 0.2500001, -0.7500001])
+    assert o.grid_indices(ends, 0.5).tolist() == [0, 0, 1, -1, 2, -2, 0, 1, -2]
 
 
 # ---- tables for b = 6, 7, 8 (Sec. 3 conditions solved by shooting instead of Lloyd's iteration)
