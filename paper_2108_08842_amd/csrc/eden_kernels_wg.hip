@@ -44,6 +44,17 @@ __device__ inline uint32_t xcd_local_tile() {
     return tile;
 }
 
+// The payload starts 64 bytes into a message, so its 128-byte memory lines do not start where the runs of neighbouring
+// tiles start: every line would be shared by two runs (two XCDs) and fetched twice (measured: 64 MiB for a 32 MiB payload).
+// Rotates the column-block index of a tile so that the runs start on line boundaries.  `row_bytes`: payload bytes of one
+// tile row, a power of two below 128; `cb_bits`: log2 of the column blocks per row.
+__device__ inline uint32_t align_runs_to_lines(uint32_t tile, uint32_t cb_bits, const void *payload, uint32_t row_bytes) {
+    const uint32_t per_line = 128u / row_bytes;
+    const uint32_t shift = (uint32_t)(reinterpret_cast<uintptr_t>(payload) / row_bytes) & (per_line - 1u);
+    const uint32_t mask = (1u << cb_bits) - 1u;
+    return (tile & ~mask) | ((tile - shift) & mask);
+}
+
 template <int M>
 __device__ inline uint64_t hix_base(uint32_t tile, int p) {
     const uint32_t cb_bits = (uint32_t)p - 5u;                   // 2^(p-5) blocks of 32 columns
@@ -418,11 +429,17 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B
     __shared__ float table[32];
     __shared__ float gtab[kGridMax + 1];                         // uniform grid: dequantized centres of mass
     const uint32_t c = blockIdx.y;
-    const uint32_t tile = xcd_local_tile();
+    const uint32_t b_q8 = B.b_q8[c];
+    uint32_t tile = xcd_local_tile();
+    {   // payload bytes of one tile row: 4 per index bit; the budgets with a power of two (2, 4, 8 bits) get aligned runs
+        int tb, tk;
+        budget_of(b_q8, tb, tk);
+        if (tk == 1 && (tb == 2 || tb == 4 || tb == 8) && !B.codes[c])
+            tile = align_runs_to_lines(tile, p - 5, static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES, 4u * (uint32_t)tb);
+    }
     const uint64_t base = hix_base<M>(tile, p);
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
     const uint32_t g0 = 2u * wave_in_block();
-    const uint32_t b_q8 = B.b_q8[c];
     const bool i16 = narrow && b_q8 <= 256u;
     const DecScratch *sc = &scratch[c];
     if (threadIdx.x < 16) table[threadIdx.x] = (i16 && threadIdx.x == 1) ? 1.0f : sc->deq[threadIdx.x];
@@ -641,14 +658,14 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatc
     constexpr int p = kHixP;
     __shared__ uint32_t lds[X::LDS_FLOATS];
     const uint32_t c = blockIdx.y;
-    const uint32_t tile = xcd_local_tile();
-    // 64-column blocks: 2^(p-6) of them per row
+    const uint32_t b_q8 = B.b_q8[c];
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
+    // 64-column blocks: 2^(p-6) of them per row, 8 (b = 1) or 4 (b = 1/2) payload bytes per row each
+    const uint32_t tile = align_runs_to_lines(xcd_local_tile(), p - 6, payload, b_q8 == 256u ? 8u : 4u);
     const uint32_t cb = tile & ((1u << (p - 6)) - 1u), upper = tile >> (p - 6);
     const uint64_t base = ((uint64_t)upper << (p + M)) | ((uint64_t)cb << 6);
     const uint32_t cp = threadIdx.x & 31u, g = threadIdx.x >> 5, lane = lane_id();
     const uint32_t g0 = 2u * wave_in_block();
-    const uint32_t b_q8 = B.b_q8[c];
-    const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     const uint32_t payload_bytes = (uint32_t)(((((1ull << log2D) >> (b_q8 == 128u)) + 63) >> 6) << 3);
     const uint64_t row_a = (uint64_t)hix_row1<M>(g0, lane) << p, row_b = (uint64_t)hix_row1<M>(g0 + 1, lane) << p;
     uint64_t recv_a = ~0ull, recv_b = ~0ull;                     // bit r: did the packet of register r's row arrive
