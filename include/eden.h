@@ -206,6 +206,16 @@ int eden_finalize_mean(eden_ctx *ctx, const float *acc_dev, uint64_t d, uint32_t
  * function, and clears them. */
 int eden_last_device_status(eden_ctx *ctx, void *stream, uint32_t *status_out);
 
+/* Synchronises `stream` and copies to flags_out[0 .. n-1] (host) the status bits of the first n messages of the most recent
+ * eden_decode_accumulate call on this context, in the order of that call: EDEN_DEV_HEADER_MISMATCH, EDEN_DEV_NOTHING_ARRIVED,
+ * or the sender's own EDEN_DEV_ZERO_VECTOR / EDEN_DEV_NONFINITE; 0 for a message that was decoded and added.  Tells which
+ * message of a batch the OR in eden_last_device_status came from.  n must not exceed that call's n. */
+int eden_last_decode_flags(eden_ctx *ctx, void *stream, uint32_t *flags_out, uint32_t n);
+
+/* Bytes of a message that have to travel, from a HOST copy of its 64-byte header: eden_message_bytes(d, b_q8) for every
+ * budget but EDEN_B_COIN, whose second part is as long as the coins made it; 0 if the header is not one of this library. */
+size_t eden_message_length(const void *header_host);
+
 /* Test helpers: the kernels' own hash streams, written out so that masks can be compared bit for bit.
  *   eden_make_loss_bitmap   packet j of `client` is dropped iff the top 32 bits of word(LOSS key, j)
  *                           are below drop_q32 (drop probability drop_q32 / 2^32); writes

@@ -37,6 +37,8 @@ struct eden_ctx {
     DecScratch *dec_scratch; // slots
     DevTables *tables;
     uint32_t *dev_status;
+    uint32_t *msg_flags;         // n_max words: the status bits of every message of the last eden_decode_accumulate call
+    uint32_t last_decode_n = 0;  // how many of them that call wrote
     // optional kernel timing (eden_profile_*)
     uint32_t prof_mask = 0;
     uint32_t prof_used = 0;
@@ -192,6 +194,7 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
     ok = ok && hipMalloc(&ctx->dec_scratch, ctx->slots * sizeof(DecScratch)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->tables, sizeof(DevTables)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->dev_status, sizeof(uint32_t)) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->msg_flags, (size_t)n_max * sizeof(uint32_t)) == hipSuccess;
     ok = ok && hipMalloc(&ctx->hist, 256 * sizeof(uint32_t)) == hipSuccess;
     if (ok) {
         std::vector<DevTables> host_tables(1);                   // 9 KiB: not on the stack
@@ -201,6 +204,7 @@ int eden_create(eden_ctx **out, uint64_t d_max, uint32_t n_max, int hip_device) 
         ok = ok && hipMemset(ctx->enc_scratch, 0, ctx->slots * sizeof(EncScratch)) == hipSuccess;
         ok = ok && hipMemset(ctx->dec_scratch, 0, ctx->slots * sizeof(DecScratch)) == hipSuccess;
         ok = ok && hipMemset(ctx->dev_status, 0, sizeof(uint32_t)) == hipSuccess;
+        ok = ok && hipMemset(ctx->msg_flags, 0, (size_t)n_max * sizeof(uint32_t)) == hipSuccess;
         ok = ok && hipDeviceSynchronize() == hipSuccess;
     }
     if (!ok) {
@@ -218,7 +222,7 @@ int eden_destroy(eden_ctx *ctx) {
     for (hipEvent_t e : ctx->prof_start) ok = (hipEventDestroy(e) == hipSuccess) && ok;
     for (hipEvent_t e : ctx->prof_stop) ok = (hipEventDestroy(e) == hipSuccess) && ok;
     void *ptrs[] = {ctx->T, ctx->dec_partial, ctx->stage, ctx->codes, ctx->hist, ctx->partials, ctx->enc_scratch, ctx->dec_scratch, ctx->tables, ctx->dev_status,
-                    ctx->coin.mask, ctx->coin.local, ctx->coin.group, ctx->coin.total};
+                    ctx->coin.mask, ctx->coin.local, ctx->coin.group, ctx->coin.total, ctx->msg_flags};
     for (void *p : ptrs)
         if (p) ok = (hipFree(p) == hipSuccess) && ok;
     delete ctx;
@@ -502,9 +506,10 @@ int eden_encode_static(const float *const *x_dev, const uint32_t *client_ids, co
 // Decodes n messages whose transformed vectors all have the same dimension and adds them to acc (see encode_range
 // for the arguments; `d_src` is the length of acc, `bitmaps` may be null).  pre == 2 (multi-pass sizes only, n at
 // most one launch): nothing is added to acc; every sender's decoded vector is left in its workspace slot.
+// `flags_out`: where the status word of message 0 of this range goes (device, one word per message).
 static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids, const uint32_t *b_kernel,
                         const uint32_t *b_hdr, uint32_t n, uint64_t d_src, int pre, uint64_t hdr_d, uint64_t seed,
-                        const uint32_t *const *bitmaps, float *acc_dev, hipStream_t st) {
+                        const uint32_t *const *bitmaps, float *acc_dev, uint32_t *flags_out, hipStream_t st) {
     const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vectors
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
@@ -534,7 +539,7 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
         }
         if (pl.lo_bits == 0) {
             Timed t(ctx, EDEN_K_DEC_SMALL, nb, st);
-            launch_dec_small(B, nb, d_src, pre, hdr_d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, st);
+            launch_dec_small(B, nb, d_src, pre, hdr_d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, flags_out + first, st);
         } else {
             // Strided passes first (every sender on its own), contiguous pass last (sums the senders in registers
             // and touches acc once).  With a single strided pass the workspace of a b <= 1 sender holds int16.
@@ -544,7 +549,8 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
             if (coins) launch_coin_tables(B.client, B.b_q8, nullptr, nb, seed, log2D, ctx->coin, st);
             {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
-                launch_dec_prepare(B, nb, hdr_d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, ctx->coin.total, st);
+                launch_dec_prepare(B, nb, hdr_d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, ctx->coin.total,
+                                   flags_out + first, st);
             }
             for (int i = pl.nhi - 1; i >= 0; --i) {
                 const HiPass &h = pl.hi[i];
@@ -587,8 +593,9 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
     if (!guard.ok) return EDEN_ERR_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::vector<uint32_t> ones(n, 256u);
-    if (mode == 0) return decode_range(ctx, msgs_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, recv_bitmaps_dev, acc_dev, st);
-    if (mode == 1) return decode_range(ctx, msgs_dev, client_ids, ones.data(), b_q8, n, d, 1, d, seed, recv_bitmaps_dev, acc_dev, st);
+    ctx->last_decode_n = n;
+    if (mode == 0) return decode_range(ctx, msgs_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, recv_bitmaps_dev, acc_dev, ctx->msg_flags, st);
+    if (mode == 1) return decode_range(ctx, msgs_dev, client_ids, ones.data(), b_q8, n, d, 1, d, seed, recv_bitmaps_dev, acc_dev, ctx->msg_flags, st);
     // b = m/64 (the factor 64/m is folded into the dequantization).  Senders that share m and a multi-pass size: a batch
     // is decoded without summing, every sender into its own workspace slot, and one launch adds the values to the
     // coordinates of acc they were taken from.
@@ -601,7 +608,7 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
         for (uint32_t first = 0; first < n; first += ctx->slots) {
             const uint32_t nb = (n - first < ctx->slots) ? n - first : ctx->slots;
             const int rc = decode_range(ctx, &msgs_dev[first], &client_ids[first], ones.data(), &b_q8[first], nb, dk0, 2, d, seed,
-                                        recv_bitmaps_dev ? &recv_bitmaps_dev[first] : nullptr, acc_dev, st);
+                                        recv_bitmaps_dev ? &recv_bitmaps_dev[first] : nullptr, acc_dev, ctx->msg_flags + first, st);
             if (rc != EDEN_OK) return rc;
             DecBatch B;
             std::memset(&B, 0, sizeof(B));
@@ -620,7 +627,7 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
         if (!launch_ok()) return EDEN_ERR_HIP;
         const uint32_t *bm = recv_bitmaps_dev ? recv_bitmaps_dev[c] : nullptr;
         const int rc = decode_range(ctx, &msgs_dev[c], &client_ids[c], ones.data(), &b_q8[c], 1, dk, 0, d, seed,
-                                    recv_bitmaps_dev ? &bm : nullptr, ctx->stage, st);
+                                    recv_bitmaps_dev ? &bm : nullptr, ctx->stage, ctx->msg_flags + c, st);
         if (rc != EDEN_OK) return rc;
         launch_sparse_scatter(ctx->stage, d, m, seed, client_ids[c], acc_dev, st);
         if (!launch_ok()) return EDEN_ERR_HIP;
@@ -650,6 +657,28 @@ int eden_last_device_status(eden_ctx *ctx, void *stream, uint32_t *status_out) {
     if (hipStreamSynchronize(st) != hipSuccess) return EDEN_ERR_HIP;
     *status_out = v;
     return EDEN_OK;
+}
+
+int eden_last_decode_flags(eden_ctx *ctx, void *stream, uint32_t *flags_out, uint32_t n) {
+    if (!ctx || !flags_out || n == 0 || n > ctx->last_decode_n) return EDEN_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(flags_out, ctx->msg_flags, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToHost, st) != hipSuccess) return EDEN_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return EDEN_ERR_HIP;
+    return EDEN_OK;
+}
+
+size_t eden_message_length(const void *header_host) {
+    if (!header_host) return 0;
+    MsgHeader h;
+    std::memcpy(&h, header_host, sizeof(h));
+    if (h.magic != kMagic || h.log2D > (uint32_t)EDEN_MAX_LOG2_D) return 0;
+    const size_t room = eden_message_bytes(h.d, h.b_q8);
+    if (room == 0 || !coin_q8(h.b_q8)) return room;
+    const uint64_t D = 1ull << h.log2D;
+    if (h.extra_bits > D) return 0;
+    return EDEN_HEADER_BYTES + (size_t)(payload_a_bytes(D, (int)(coin_q8(h.b_q8) >> 8), 1) + coin_b_bytes(h.extra_bits));
 }
 
 static bool pow2_dim(uint64_t D) { return D >= 1 && D <= (1ull << EDEN_MAX_LOG2_D) && (D & (D - 1)) == 0; }

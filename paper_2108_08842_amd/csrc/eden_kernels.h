@@ -36,7 +36,8 @@ void launch_enc_finish(const EncBatch &B, uint32_t n, uint64_t hdr_d, int log2D,
                        const double *partials_n2, uint32_t nparts_n2, const double *partials_ip, uint32_t nparts_ip,
                        uint32_t partial_stride, uint32_t *dev_status, const uint32_t *coin_total, hipStream_t st);
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
-                        DecScratch *scratch, uint32_t *dev_status, const uint32_t *coin_total, hipStream_t st);
+                        DecScratch *scratch, uint32_t *dev_status, const uint32_t *coin_total, uint32_t *msg_flags,
+                        hipStream_t st);
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st);
 // pre: 0 = sum the senders into acc; 1 = the same with the pairs scatter of EDEN_B_HALF_PRE; 2 = no sum, every sender's
@@ -46,8 +47,9 @@ void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int 
 void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean, hipStream_t st);
 void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
                       const DevTables *tab, uint32_t *dev_status, hipStream_t st);
+// `msg_flags` (may be null): one status word per message of the launch, written by the kernel that checks the headers
 void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
-                      const DevTables *tab, float *acc, uint32_t *dev_status, hipStream_t st);
+                      const DevTables *tab, float *acc, uint32_t *dev_status, uint32_t *msg_flags, hipStream_t st);
 // b = m/64: the kept coordinates of x packed into `stage` (m per block of 64), and added back from it into acc
 void launch_sparse_gather(const float *x, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *stage, hipStream_t st);
 void launch_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *acc, hipStream_t st);

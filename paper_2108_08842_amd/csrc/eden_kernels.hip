@@ -763,7 +763,8 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t hdr_d, 
 // `extra_bits`: coin budgets only, the number of coins the receiver counted itself; the header must agree.
 __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap, uint32_t client, uint32_t b_q8,
                                         uint32_t hdr_b_q8, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
-                                        DecScratch *out, uint32_t *dev_status, uint32_t extra_bits = 0) {
+                                        DecScratch *out, uint32_t *dev_status, uint32_t extra_bits = 0,
+                                        uint32_t *msg_flag = nullptr) {
     const uint32_t lane = lane_id();
     const MsgHeader h = *static_cast<const MsgHeader *>(msg);
     uint32_t flags = 0;
@@ -815,16 +816,17 @@ __device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap,
     }
     if (lane == 0) {
         out->flags = flags;
+        if (msg_flag) *msg_flag = flags;                         // per message, for eden_last_decode_flags
         if (flags & (EDEN_DEV_HEADER_MISMATCH | EDEN_DEV_NOTHING_ARRIVED)) atomicOr(dev_status, flags);
     }
 }
 
 __global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t hdr_d, int log2D, uint64_t seed,
                                                     const DevTables *tab, DecScratch *scratch, uint32_t *dev_status,
-                                                    const uint32_t *coin_total) {
+                                                    const uint32_t *coin_total, uint32_t *msg_flags) {
     const uint32_t c = blockIdx.x;
     dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], hdr_d, log2D, seed, tab, &scratch[c], dev_status,
-                     coin_q8(B.b_q8[c]) ? coin_total[c] : 0u);
+                     coin_q8(B.b_q8[c]) ? coin_total[c] : 0u, msg_flags ? msg_flags + c : nullptr);
 }
 
 // ---- coin budgets (Sec. 4.1): the coins of every sender of a launch that has such a budget, as lane masks per block of 64
@@ -1332,7 +1334,8 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
 // One workgroup decodes the whole batch: per sender fill LDS with the dequantized rotated vector,
 // transform, apply the signs and add into per-thread sums; acc is touched once at the end.
 __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D,
-                                                   uint64_t seed, const DevTables *tab, float *acc, uint32_t *dev_status) {
+                                                   uint64_t seed, const DevTables *tab, float *acc, uint32_t *dev_status,
+                                                   uint32_t *msg_flags) {
     __shared__ float buf[kLoTile];
     __shared__ DecScratch s;
     __shared__ uint32_t coin_m16[256], coin_pre[256], wave_totals[4];   // coin budgets: coins of 16 coordinates, coins before them
@@ -1356,7 +1359,7 @@ __global__ __launch_bounds__(256) void k_dec_small(DecBatch B, uint32_t n, uint6
         }
         if (threadIdx.x < 64)
             dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], hdr_d, log2D, seed, tab, &s, dev_status,
-                             extra_bits);
+                             extra_bits, msg_flags ? msg_flags + c : nullptr);
         __syncthreads();
         const uint32_t b_q8 = B.b_q8[c];
         int bits, k;
@@ -1513,8 +1516,10 @@ uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d_src, int 
     return grid.x;
 }
 void launch_dec_prepare(const DecBatch &B, uint32_t n, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
-                        DecScratch *scratch, uint32_t *dev_status, const uint32_t *coin_total, hipStream_t st) {
-    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, hdr_d, log2D, seed, tab, scratch, dev_status, coin_total);
+                        DecScratch *scratch, uint32_t *dev_status, const uint32_t *coin_total, uint32_t *msg_flags,
+                        hipStream_t st) {
+    hipLaunchKernelGGL(k_dec_prepare, dim3(n), dim3(64), 0, st, B, hdr_d, log2D, seed, tab, scratch, dev_status, coin_total,
+                       msg_flags);
 }
 void launch_dec_lo_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
                         const DecScratch *scratch, int narrow, float *acc, hipStream_t st) {
@@ -1580,8 +1585,8 @@ void launch_enc_small(const EncBatch &B, uint32_t n, uint64_t d, int pre, uint64
     hipLaunchKernelGGL(k_enc_small, dim3(n), dim3(256), 0, st, B, d, pre, hdr_d, log2D, seed, tab, dev_status);
 }
 void launch_dec_small(const DecBatch &B, uint32_t n, uint64_t d, int pre, uint64_t hdr_d, int log2D, uint64_t seed,
-                      const DevTables *tab, float *acc, uint32_t *dev_status, hipStream_t st) {
-    hipLaunchKernelGGL(k_dec_small, dim3(1), dim3(256), 0, st, B, n, d, pre, hdr_d, log2D, seed, tab, acc, dev_status);
+                      const DevTables *tab, float *acc, uint32_t *dev_status, uint32_t *msg_flags, hipStream_t st) {
+    hipLaunchKernelGGL(k_dec_small, dim3(1), dim3(256), 0, st, B, n, d, pre, hdr_d, log2D, seed, tab, acc, dev_status, msg_flags);
 }
 void launch_store_doubles(const double *src_host, uint32_t count, double *dst, hipStream_t st) {
     ArgDoubles a;

@@ -33,6 +33,7 @@ EXPORTS = [
     "eden_finalize_mean", "eden_last_device_status", "eden_make_loss_bitmap", "eden_make_sign_bits",
     "eden_make_subsample_bits", "eden_get_tables", "eden_strerror", "eden_profile_enable", "eden_profile_collect",
     "eden_kernel_name", "eden_sq_error", "eden_index_entropy", "eden_encode_static",
+    "eden_last_decode_flags", "eden_message_length",
 ]
 B_HALF_PRE = 0x10080     # b = 1/2 with the sparsification before the rotation (EDEN_B_HALF_PRE)
 
@@ -94,6 +95,10 @@ def lib():
     L.eden_decode_accumulate.restype = ci
     L.eden_finalize_mean.argtypes = [vp, vp, u64, u32, vp, vp]
     L.eden_finalize_mean.restype = ci
+    L.eden_last_decode_flags.argtypes = [vp, vp, P(u32), u32]
+    L.eden_last_decode_flags.restype = ci
+    L.eden_message_length.argtypes = [vp]
+    L.eden_message_length.restype = sz
     L.eden_last_device_status.argtypes = [vp, vp, P(u32)]
     L.eden_last_device_status.restype = ci
     L.eden_make_loss_bitmap.argtypes = [vp, u64, u32, u64, u32, vp, vp]
@@ -126,6 +131,13 @@ def strerror(code: int) -> str:
 
 def message_bytes(d: int, b_q8: int) -> int:
     return int(lib().eden_message_bytes(d, b_q8))
+
+
+def message_length(header: bytes) -> int:
+    """Bytes of a message that have to travel, from a host copy of (at least) its 64-byte header."""
+    assert len(header) >= HEADER_BYTES
+    buf = ctypes.create_string_buffer(bytes(header[:HEADER_BYTES]), HEADER_BYTES)
+    return int(lib().eden_message_length(ctypes.cast(buf, ctypes.c_void_p)))
 
 
 def get_tables(bits: int):
@@ -250,6 +262,14 @@ class Context:
         if rc != OK:
             raise EdenError(rc, "eden_last_device_status")
         return int(v.value)
+
+    def last_decode_flags(self, n: int, stream=None):
+        """Status bits of the first n messages of the most recent decode_accumulate call, in call order."""
+        out = (ctypes.c_uint32 * n)()
+        rc = lib().eden_last_decode_flags(self._h, _stream_ptr(stream), out, n)
+        if rc != OK:
+            raise EdenError(rc, "eden_last_decode_flags")
+        return [int(v) for v in out]
 
     def profile_enable(self, kinds, max_records: int = 4096):
         """Time every launch of the named kernel kinds with HIP events (empty list = off)."""

@@ -208,6 +208,15 @@ def test_degenerate_vectors_and_status(ctx):
         ctx.decode_accumulate(msgs[1:2], [1], [256], d, 9, acc3)
         assert not acc3.any().item()
         assert ctx.last_device_status() == eden.DEV_HEADER_MISMATCH
+        # which message of a batch it was: one status word per message of the last call
+        acc4 = torch.zeros(d, device="cuda")
+        ctx.decode_accumulate([msgs[1], msgs[1], msgs[1], msgs[0]], [1, 5, 1, 0], [512, 512, 512, 256], d, 9, acc4,
+                              [None, None, empty, None])
+        assert ctx.last_decode_flags(4) == [0, eden.DEV_HEADER_MISMATCH, eden.DEV_NOTHING_ARRIVED, eden.DEV_ZERO_VECTOR]
+        assert ctx.last_decode_flags(2) == [0, eden.DEV_HEADER_MISMATCH]
+        with pytest.raises(eden.EdenError):
+            ctx.last_decode_flags(5)
+        ctx.last_device_status()
 
 
 def test_argument_errors(ctx):

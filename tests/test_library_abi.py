@@ -59,6 +59,16 @@ def test_library_tables_match_oracle_tables(eden, bits):
     assert np.sum(np.float32(q) != np.float32(qo)) <= (0 if bits <= 5 else 2)
 
 
+def test_message_length_from_a_header(eden):
+    # what has to travel: the whole buffer for every budget but the coin budgets, whose second part follows the coins
+    x = np.random.default_rng(3).standard_normal(3000)
+    for b in (256, 512, 384, eden.B_GRID(0.5), eden.B_HALF_PRE, eden.B_SPARSE(7), eden.B_COIN(1.3), eden.B_COIN(3.5)):
+        m = o.encode(x, 4, 1, b)
+        raw = m.to_bytes()
+        assert eden.message_length(raw) == len(raw) <= eden.message_bytes(3000, b)
+    assert eden.message_length(bytes(64)) == 0
+
+
 def test_error_strings(eden):
     assert eden.strerror(0) == "ok"
     assert "argument" in eden.strerror(eden.ERR_INVALID_ARG)
