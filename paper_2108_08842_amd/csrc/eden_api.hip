@@ -279,10 +279,16 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
                 part_b[i] = static_cast<char *>(B.msg[i]) + EDEN_HEADER_BYTES + payload_a_bytes(1ull << log2D, (int)(coin_q8(B.b_q8[i]) >> 8), 1);
             }
             if (coins) launch_coin_tables(B.client, B.b_q8, part_b, nb, seed, log2D, ctx->coin, st);
+            // The workspace goes through the blocked layout when a workgroup-tile pass reads it back right away (two-pass
+            // plans of D >= 2^21), unless the first pass works in place on the workspace (its input is a slot): its
+            // workgroups would then overwrite rows that others have not read yet.
+            bool blocked = pl.lo_bits == 14 && pl.nhi == 1 && pl.hi[0].wg;
+            for (uint32_t i = 0; i < nb; ++i)
+                blocked = blocked && !(ctx->T && B.x[i] >= ctx->T && B.x[i] < ctx->T + ((size_t)ctx->slots << ctx->log2D_max));
             {
                 Timed t(ctx, EDEN_K_ENC_FIRST, nb, st);
                 nparts_n2 = pl.lo_bits == 14
-                                ? launch_enc_lo14_first(B, nb, d_src, pre, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st)
+                                ? launch_enc_lo14_first(B, nb, d_src, pre, blocked, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st)
                                 : launch_enc_lo_first(B, nb, d_src, pre, log2D, seed, ctx->T, part_n2, ctx->partial_stride, st);
             }
             if (need_thresholds) {
@@ -298,7 +304,7 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
                     valid = round_up(d, h.p + h.M);
                 } else {
                     Timed t(ctx, EDEN_K_ENC_LAST, nb, st);
-                    nparts_ip = h.wg     ? launch_enc_hix_last(h.M, B, nb, d, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
+                    nparts_ip = h.wg     ? launch_enc_hix_last(h.M, blocked, B, nb, d, log2D, seed, ctx->T, part_ip, ctx->partial_stride,
                                                                ctx->enc_scratch, ctx->coin, st)
                                 : h.wide ? launch_enc_wide_last(B, nb, valid, log2D, ctx->T, part_ip, ctx->partial_stride,
                                                                 ctx->enc_scratch, st)

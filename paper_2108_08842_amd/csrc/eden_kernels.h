@@ -71,7 +71,7 @@ void launch_hash_bits(uint64_t key, uint64_t nwords, uint64_t *out, hipStream_t 
 void launch_loss_bitmap(uint64_t key, uint32_t npk, uint32_t drop_q32, uint32_t *bitmap, hipStream_t st);
 
 // workgroup-tile strided passes for D >= 2^21 (eden_kernels_wg.hip)
-uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+uint32_t launch_enc_hix_last(int M, int blocked, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
                              double *partials, uint32_t partial_stride, const EncScratch *scratch, const CoinTables &ct,
                              hipStream_t st);
 void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems, uint64_t store_elems, hipStream_t st);
@@ -79,7 +79,9 @@ void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
                           const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st);
 
 // 14-bit contiguous passes for D >= 2^19 (eden_kernels_lo14.hip)
-uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
+// `blocked`: write the workspace in the blocked layout (eden_device.h: blocked_offset) that launch_enc_hix_last reads
+// when told so; not for a first pass that works in place on the workspace
+uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int pre, int blocked, int log2D, uint64_t seed, float *T,
                                double *partials, uint32_t partial_stride, hipStream_t st);
 // `resident`: workgroups of the kernel the device holds at once (2 per CU); `partial`: room for `partial_tiles`
 // tiles of 2^14 floats, used when tiles are split over several workgroups by sender

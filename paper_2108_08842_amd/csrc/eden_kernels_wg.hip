@@ -233,7 +233,8 @@ template <> struct WordVec<4> { using type = uint4; };
 // that each half of the exchange has just written to LDS.  MODE 0: every sender of the launch has b <= 1; the
 // words of the TPW tiles are then kept and stored together (one row of a tile is only 4 bytes of payload).
 // MODE 1: any integer budget or b = 1/2.  MODE 2: also the budgets k + 1/2 (they need more registers).
-template <int M, int TPW, int MODE>
+// BLK: the first pass wrote the workspace in the blocked layout (blocked_offset in eden_device.h).
+template <int M, int TPW, int MODE, bool BLK>
 __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_last(EncBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                    const float *T, double *partials,
                                                                    uint32_t partial_stride, const EncScratch *scratch,
@@ -249,12 +250,27 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
     const uint32_t c = blockIdx.y;
     const uint32_t tile0 = xcd_local_tile<16 / TPW>() * TPW;
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
-    const uint32_t rows_written = (uint32_t)((d + (1u << p) - 1) >> p);
+    uint32_t rows_written = (uint32_t)((d + (1u << p) - 1) >> p);
+    if (BLK) rows_written = (rows_written + kBlockRows - 1u) / kBlockRows * kBlockRows;      // whole blocks of rows are written
     const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), rows_written << (p + 2));
     uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     const uint32_t b_q8 = B.b_q8[c];
     const EncScratch *sc = &scratch[c];
-    const uint32_t off1 = ((g << p) + col) * 4u;                         // stage-1 rows: g + RL r
+    // stage-1 rows: g + RL r.  Byte offset of (row, column) inside the slot = a per-thread part + a part that is the same for
+    // the whole workgroup (row_off(r)) + the tile's column block
+    constexpr uint32_t RLB = X::RL >= kBlockRows ? X::RL / kBlockRows : 1u;
+    const uint32_t off1 = !BLK ? ((g << p) + col) * 4u
+                               : X::RL >= kBlockRows ? (((g >> kBlockRowBits) << (p + kBlockRowBits)) + ((g & (kBlockRows - 1u)) << 5) + col) * 4u
+                                                     : ((g << 5) + col) * 4u;
+    auto row_off = [](int r) -> uint32_t {                       // r is a compile-time constant after unrolling
+        if (!BLK) return ((uint32_t)X::RL * (uint32_t)r) << (p + 2);
+        if (X::RL >= kBlockRows) return (RLB * (uint32_t)r) << (p + kBlockRowBits + 2);
+        const uint32_t row = (uint32_t)X::RL * (uint32_t)r;      // RL = 2: rows g + 2 r, g = 0, 1
+        return ((row >> kBlockRowBits) << (p + kBlockRowBits + 2)) + ((row & (kBlockRows - 1u)) << 7);
+    };
+    auto tile_off = [](uint32_t tile) -> uint32_t {              // (two-pass plans: the tile index is the column block)
+        return BLK ? tile << (7 + kBlockRowBits) : (uint32_t)hix_base<M>(tile, p) * 4u;
+    };
     const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
     if (!UNIT) {
         fill_qtab(qtab, sc, threadIdx.x);
@@ -267,14 +283,14 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
     uint32_t held[TPW][X::PH][NW];
     float v[64];
     {
-        const uint32_t b0 = (uint32_t)hix_base<M>(tile0, p) * 4u;
+        const uint32_t b0 = tile_off(tile0);
 #pragma unroll
-        for (int r = 0; r < 64; ++r) v[r] = buf_load(rt, off1, b0 + (((uint32_t)X::RL * r) << (p + 2)));
+        for (int r = 0; r < 64; ++r) v[r] = buf_load(rt, off1, b0 + row_off(r));
     }
 #pragma unroll
     for (int k = 0; k < TPW; ++k) {
         const uint64_t base = hix_base<M>(tile0 + k, p);
-        const uint32_t next_off = (uint32_t)hix_base<M>(tile0 + k + 1, p) * 4u;
+        const uint32_t next_off = tile_off(tile0 + k + 1);
         fwht_regs<64>(v);
         float out[X::RP];
 #pragma unroll
@@ -284,7 +300,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
             if (k + 1 < TPW) {
 #pragma unroll
                 for (int r = ph * X::RP; r < (ph + 1) * X::RP; ++r)
-                    v[r] = buf_load(rt, off1, next_off + (((uint32_t)X::RL * r) << (p + 2)));
+                    v[r] = buf_load(rt, off1, next_off + row_off(r));
             }
             hix_exchange_read<M>(lds, out);
             if (UNIT || b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
@@ -753,7 +769,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatc
 
 static uint32_t hix_tiles(int M, int log2D) { return 1u << (log2D - M - 5); }
 
-uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
+uint32_t launch_enc_hix_last(int M, int blocked, const EncBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed, const float *T,
                              double *partials, uint32_t partial_stride, const EncScratch *scratch, const CoinTables &ct,
                              hipStream_t st) {
     const uint32_t tiles = hix_tiles(M, log2D);                  // 512 whenever this pass sits directly on lo14
@@ -763,8 +779,13 @@ uint32_t launch_enc_hix_last(int M, const EncBatch &B, uint32_t n, uint64_t d, i
         mixed = mixed || budget_two_tables(B.b_q8[c]);
     }
 #define EDEN_ENC_HIX_LAST(TPW, MODE)                                                                                          \
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, TPW, MODE>), grid, dim3(HiX<MM>::THREADS), 0, st, B, \
-                                          d, log2D, seed, T, partials, partial_stride, scratch, ct))
+    if (blocked) {                                                                                                            \
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, TPW, MODE, true>), grid, dim3(HiX<MM>::THREADS), \
+                                              0, st, B, d, log2D, seed, T, partials, partial_stride, scratch, ct))            \
+    } else {                                                                                                                  \
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, TPW, MODE, false>), grid, dim3(HiX<MM>::THREADS), \
+                                              0, st, B, d, log2D, seed, T, partials, partial_stride, scratch, ct))            \
+    }
     if (unit && tiles % 128u == 0) {                             // four neighbouring tiles per workgroup
         dim3 grid(tiles / 4, n);
         EDEN_ENC_HIX_LAST(4, 0);
