@@ -289,6 +289,186 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     }
 }
 
+// ---- the same pass for launches whose senders all have an int16 workspace of small exact integers (b <= 1, D <= 2^24:
+// |value| <= 2^10 after at most ten strided bits), with ten of the fourteen bits on the matrix cores.
+//
+// The tile is a 16 x 32 x 32 array (u, n, k) = index bits 10..13, 5..9, 0..4.  A wave owns two values of u.  For one u:
+//   step 1  bits 0..4   D1[n][k'] = sum_k X[n][k] H[k][k']: v_mfma_f32_32x32x16_f16 twice, X as the A operand straight from
+//           memory (a lane holds 16 consecutive int16 of its row n, converted to fp16: exact, |x| <= 2^10 < 2^11).
+//   step 2  bits 5..9   D2[n'][k'] = sum_n H[n'][n] D1[n][k']: the registers that hold D1 ARE a B operand (lane = column k',
+//           registers = 8 values of n per lane half), the Hadamard A operand is built with its columns in that order, so
+//           nothing moves between the steps.  |D1| <= 2^15 does not fit fp16's 11 bits: every value is split into its fp16
+//           truncation and the remainder (<= 5 bits, exact), and both go through the matrix cores into the same fp32
+//           accumulators (four instructions).  All sums are integers below 2^24: exact in fp32 in any order.
+//   exchange through LDS: lds[u][r][lane] = register r of the wave that owns u; wave w reads r = 2w, 2w + 1 of all 16 u
+//           (same lane: the exchange swaps the register index with the wave index, conflict free in both directions).
+//   step 3  bits 10..13 four butterfly stages over the 16 values of u in registers (fp32, exact).
+// Register (u, j) of thread (wave w, lane l = 32 h + m) then holds coordinate 1024 u + 32 n' + m of the tile with
+// n' = 8 (w / 2) + 4 h + 2 (w % 2) + j: 32 lanes cover one 128-byte line of acc, and the 32 sign bits of those lanes are one
+// half (j) of one 64-bit word of the sender's SIGN stream.
+// Per coordinate and sender this leaves about 10 vector instructions (conversion 1, split 2, butterflies 4, sign and
+// accumulate 3) where the all-vector version spends 19, and one exchange instead of two.
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+__device__ inline _Float16 hadamard_entry(uint32_t a, uint32_t b) {
+    return (__builtin_popcount(a & b) & 1) ? (_Float16)-1.0f : (_Float16)1.0f;
+}
+// eight int16 (four dwords) -> eight fp16, same order and same registers: each half of a dword is converted in place
+// (written out because the compiler converts into two registers and packs them again: three instructions per pair)
+__device__ inline half8_t halves_of_int16(uint32_t (&w)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        asm("v_cvt_f16_i16_sdwa %0, %0 dst_sel:WORD_0 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0\n\t"
+            "v_cvt_f16_i16_sdwa %0, %0 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_1\n\t"
+            "s_nop 1"                                            // the matrix instruction that reads it may come next
+            : "+v"(w[i]));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = {w[0], w[1], w[2], w[3]};
+    return __builtin_bit_cast(half8_t, v);
+}
+// x - (float)h for the fp16 in the low (HIGH = 0) or high half of `packed`: one mixed-precision fused multiply-add
+// (-1 * h + x, exact: h is x truncated to 11 bits)
+template <int HIGH>
+__device__ inline float minus_half(float x, uint32_t packed) {
+    float r;
+    if (HIGH) asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(-1.0f), "v"(x));
+    else asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(-1.0f), "v"(x));
+    return r;
+}
+
+__global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+                                                               const float *T, const DecScratch *scratch, float *acc,
+                                                               uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
+                                                               float *partial) {
+    __shared__ __attribute__((aligned(16))) float lds[1 << kLo14Bits];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wv = wave_in_block(), h = lane >> 5, m = lane & 31u;
+    uint32_t tile = blockIdx.x, c_begin = 0, c_end = n;
+    float *part = nullptr;                                       // this tile in the partial buffer
+    if (blockIdx.x >= full_tiles) {
+        const uint32_t idx = blockIdx.x - full_tiles, k = idx % K;
+        tile = full_tiles + idx / K;
+        c_begin = (uint32_t)(((uint64_t)n * k) / K);
+        c_end = (uint32_t)(((uint64_t)n * (k + 1)) / K);
+        if (k > 0) part = partial + (((size_t)(k - 1) * split_tiles + (tile - full_tiles)) << kLo14Bits);
+    }
+    const uint64_t tile_base = (uint64_t)tile << kLo14Bits;
+
+    // the two Hadamard operands: entry e of instruction q on lane (h, m)
+    //   step 1, B[k][k']: k' = m, k = 16 h + 8 q + e    (the 16 consecutive int16 a lane loads are k = 16 h .. 16 h + 15)
+    //   step 2, A[n'][n]: n' = m, n = row of D1 that register 8 q + e of lane half h holds = 16 q + 8 (e / 4) + 4 h + e % 4
+    half8_t Hk[2], Hn[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            Hk[q][e] = hadamard_entry(16u * h + 8u * q + e, m);
+            Hn[q][e] = hadamard_entry(16u * q + 8u * (e >> 2) + 4u * h + (e & 3), m);
+        }
+
+    float sum[32];                                               // sum[16 j + u]
+#pragma unroll
+    for (int e = 0; e < 32; ++e) sum[e] = 0.0f;
+
+    // raw[2 s + q]: int16 k = 16 h + 8 q .. + 7 of row n = m of unit u = wv + 8 s
+    const uint32_t lane_off = (m * 32u + 16u * h) * 2u;
+    auto load = [&](uint32_t c, uint32_t (&raw)[4][4]) {
+        const rsrc_t r16 = make_rsrc(T + ((size_t)c << log2D), 2u << log2D);       // the tile lies inside the slot
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const auto x = __builtin_amdgcn_raw_buffer_load_b128(
+                    r16, (int)lane_off, (int)(((uint32_t)tile_base + (wv + 8u * s) * 1024u + 8u * q) * 2u), kStream);
+                raw[2 * s + q][0] = x[0]; raw[2 * s + q][1] = x[1]; raw[2 * s + q][2] = x[2]; raw[2 * s + q][3] = x[3];
+            }
+    };
+    // sign words of this wave's coordinates: word (u, hh) = 16 u + 4 (wv / 2) + (wv % 2) + 2 hh of the tile; lane 16 hh + u
+    // of either half of the wave hashes it, lane (h, m) later fetches (u, h) for every u
+    const uint32_t my_word = 16u * (lane & 15u) + 4u * (wv >> 1) + (wv & 1u) + 2u * ((lane >> 4) & 1u);
+    const uint32_t sh = 31u - m;
+
+    uint32_t raw[4][4];
+    if (c_begin < c_end) load(c_begin, raw);
+    for (uint32_t c = c_begin; c < c_end; ++c) {
+        half8_t x[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = halves_of_int16(raw[i]);
+        __builtin_amdgcn_sched_barrier(0);                       // the conversions stay above the next sender's loads
+        if (c + 1 < c_end) load(c + 1, raw);
+        if (c > c_begin) __syncthreads();                        // every wave has read the previous sender's values
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            float16_t d1 = {0};
+            d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[2 * s], Hk[0], d1, 0, 0, 0);
+            d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[2 * s + 1], Hk[1], d1, 0, 0, 0);
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            u32x4 hi[2], lo[2];                                  // fp16 pairs: registers 2 i, 2 i + 1 of d1
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                const uint32_t top = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d1[r], d1[r + 1]));   // truncated to 11 bits
+                hi[r >> 3][(r & 7) >> 1] = top;
+                lo[r >> 3][(r & 7) >> 1] = __builtin_bit_cast(                                  // what is left: at most 5 bits
+                    uint32_t, __builtin_amdgcn_cvt_pkrtz(minus_half<0>(d1[r], top), minus_half<1>(d1[r + 1], top)));
+            }
+            float16_t d2 = {0};
+            d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[0], __builtin_bit_cast(half8_t, hi[0]), d2, 0, 0, 0);
+            d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[1], __builtin_bit_cast(half8_t, hi[1]), d2, 0, 0, 0);
+            d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[0], __builtin_bit_cast(half8_t, lo[0]), d2, 0, 0, 0);
+            d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[1], __builtin_bit_cast(half8_t, lo[1]), d2, 0, 0, 0);
+            float *L = lds + (wv + 8u * s) * 1024u + lane;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) L[64 * r] = d2[r];
+        }
+        __syncthreads();
+        float v0[16], v1[16];                                    // j = 0, 1
+        const float *R = lds + 128u * wv + lane;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) { v0[u] = R[1024 * u]; v1[u] = R[1024 * u + 64]; }
+        fwht_regs<16>(v0);
+        fwht_regs<16>(v1);
+        const uint32_t scale = __float_as_uint(scratch[c].deq[1]) & 0x7FFFFFFFu;     // > 0
+        const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
+        const uint64_t mine = hash_word(key, (tile_base >> 6) + my_word);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int src = (int)(32u * h + 16u * h + u);        // lane 16 h + u of this half of the wave
+            const uint32_t wlo = (uint32_t)__shfl((int)(uint32_t)mine, src, 64);
+            const uint32_t whi = (uint32_t)__shfl((int)(uint32_t)(mine >> 32), src, 64);
+            // hash bit 1 -> s_i = -1: the factor is the scale with this lane's bit of the word moved to the sign position
+            const uint32_t f0 = scale | ((wlo << sh) & 0x80000000u);
+            const uint32_t f1 = scale | ((whi << sh) & 0x80000000u);
+            sum[u] = fmaf(v0[u], __uint_as_float(f0), sum[u]);
+            sum[16 + u] = fmaf(v1[u], __uint_as_float(f1), sum[16 + u]);
+        }
+    }
+    // register (u, j): coordinate 1024 u + 32 n' + m of the tile
+    const uint32_t nrow = 8u * (wv >> 1) + 4u * h + 2u * (wv & 1u);
+    const uint32_t mine_off = 32u * nrow + m;
+    if (part) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            part[1024 * u + mine_off] = sum[u];
+            part[1024 * u + mine_off + 32] = sum[16 + u];
+        }
+    } else if (tile_base + (1u << kLo14Bits) <= d) {
+        float *A = acc + tile_base + mine_off;
+        float old[32];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) { old[u] = A[1024 * u]; old[16 + u] = A[1024 * u + 32]; }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) { A[1024 * u] = old[u] + sum[u]; A[1024 * u + 32] = old[16 + u] + sum[16 + u]; }
+    } else {                                                     // the one tile that straddles d
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const uint64_t i = tile_base + 1024u * u + mine_off;
+            if (i < d) acc[i] += sum[u];
+            if (i + 32 < d) acc[i + 32] += sum[16 + u];
+        }
+    }
+}
+
+
 // acc[i] += partial[0][i'] + partial[1][i'] + ... for the tiles that k_dec_lo14_last split over K workgroups
 // (added one after the other, in this order).  One thread per four coordinates.
 __global__ __launch_bounds__(256) void k_dec_lo14_combine(float *acc, uint64_t d, uint32_t full_tiles, uint32_t K,
@@ -351,7 +531,10 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     }
     if (K == 1) { full = tiles; rest = 0; }
     dim3 grid(full + rest * K);
-    if (all16)
+    if (all16 && log2D <= 24)                                    // |values| <= 2^10: ten of the bits on the matrix cores
+        hipLaunchKernelGGL(k_dec_lo14_last_mfma, grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, acc, full, K, rest,
+                           partial);
+    else if (all16)
         hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, true>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
                            narrow, acc, full, K, rest, partial, 0);
     else

@@ -116,6 +116,17 @@ def test_workgroup_tile_sizes(ctx, d, budgets):
               also_oracle_msgs=(d == 1 << 21))
 
 
+@pytest.mark.parametrize("d,n", [((1 << 19) + 3, 5), (1_500_000, 3), (2_500_001, 4), (5_000_000, 2), (1 << 23, 2)])
+def test_rounds_of_at_most_one_bit(ctx, d, n):
+    # every sender at b <= 1 and D = 2^20 .. 2^23: the receiver's contiguous pass runs ten of its fourteen bits on the
+    # matrix cores (exact integer arithmetic in fp16 pieces); few tiles (the small d) are also split over the senders
+    budgets = [256, 128, 256, 256, 128][:n]
+    w = synth.Workload("t", n, d, budgets, 900 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(n)]
+    _run_case(ctx, xs, list(range(21, 21 + n)), w.b_q8, w.seed, drop_q32=int(0.1 * 2 ** 32), also_oracle_msgs=False)
+    _run_case(ctx, xs[:2], [5, 6], [256, 256], w.seed, also_oracle_msgs=(d < 2_000_000))
+
+
 @pytest.mark.parametrize("d", [5000, 70_000, 300_000])
 def test_packet_loss_and_mixed_budgets(ctx, d):
     w = synth.Workload("t", 6, d, [128, 256, 512, 1024, 768, 128], 300 + d % 1000, "lognormal")
