@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Throughput of the EDEN hot path on one MI355X.
 
-One step = encode of all n senders + decode_accumulate of all n messages + finalize_mean on one
-synthetic batch that is already resident in device memory.  Prints ONE JSON line.
+One step = encode of all n senders + the receiver's round (decode of all n messages, sum, division by n:
+eden_decode_mean, which equals zero + eden_decode_accumulate + eden_finalize_mean bit for bit) on one synthetic
+batch that is already resident in device memory.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -38,11 +39,12 @@ def model_bytes(n, d, D, budgets):
     return total + 4 * d
 
 
-def kernel_bytes(kind, senders, d, D, mean_bits, narrow):
+def kernel_bytes(kind, senders, d, D, mean_bits, narrow, fused_mean=False):
     """Algorithmic bytes one launch of a kernel kind must move (what its role reads + what it writes).
     The contiguous pass works on whole tiles of 2^12 (D <= 2^18) or 2^14 coordinates and only touches the tiles
     that hold part of the first d coordinates; the strided passes read / write the rest as implicit zeros.
-    `narrow`: the decode workspace of this workload is int16 (every sender has b <= 1 and 2^13 <= D <= 2^24)."""
+    `narrow`: the decode workspace of this workload is int16 (every sender has b <= 1 and 2^13 <= D <= 2^24).
+    `fused_mean`: the last decode pass stores the mean (4 d) instead of a read-modify-write of the accumulator."""
     log2D = D.bit_length() - 1
     lo = 12 if log2D <= 18 else 14
 
@@ -60,7 +62,7 @@ def kernel_bytes(kind, senders, d, D, mean_bits, narrow):
         "dec_last": ws * ru(lo),                      # workspace in (per sender) ...
     }
     if kind == "dec_last":
-        return senders * per_sender[kind] + 8 * d     # ... plus one read-modify-write of the accumulator
+        return senders * per_sender[kind] + (4 if fused_mean else 8) * d     # ... plus the accumulator (or the mean)
     if kind == "finalize_mean":
         return 8 * d
     return senders * per_sender.get(kind, 0.0)
@@ -115,10 +117,8 @@ def time_config(k, eden, synth, torch, steps=20, warmup=3):
     bitmaps = [ctx.make_loss_bitmap(w.seed, w.client_ids[c], D, w.drop_q32) for c in range(n)] if w.drop_q32 else None
 
     def step():
-        acc.zero_()
         ctx.encode(xs, w.client_ids, w.b_q8, w.seed, msgs=msgs)
-        ctx.decode_accumulate(msgs, w.client_ids, w.b_q8, d, w.seed, acc, bitmaps)
-        ctx.finalize_mean(acc, n, out=acc)
+        ctx.decode_mean(msgs, w.client_ids, w.b_q8, d, w.seed, acc, bitmaps)
 
     for _ in range(warmup):
         step()
@@ -178,6 +178,10 @@ def main():
         bitmaps = [ctx.make_loss_bitmap(w.seed, w.client_ids[c], D, w.drop_q32) for c in range(n)]
 
     def step():
+        ctx.encode(xs, w.client_ids, w.b_q8, w.seed, msgs=msgs)
+        ctx.decode_mean(msgs, w.client_ids, w.b_q8, d, w.seed, mean, bitmaps)
+
+    def three_call_step():                                  # the receiver's round as three calls (not the headline)
         acc.zero_()
         ctx.encode(xs, w.client_ids, w.b_q8, w.seed, msgs=msgs)
         ctx.decode_accumulate(msgs, w.client_ids, w.b_q8, d, w.seed, acc, bitmaps)
@@ -196,11 +200,12 @@ def main():
     for kind, senders, ms in ctx.profile_collect():
         per_kind.setdefault(kind, []).append((senders, ms))
     dominant = max(per_kind, key=lambda k: sum(ms for _, ms in per_kind[k]))
-    step_alg_bytes = sum(kernel_bytes(kind, s_, d, D, mean_bits, narrow) for kind, recs_ in per_kind.items() for s_, _ in recs_)
+    fused = "finalize_mean" not in per_kind                 # the last decode pass stored the mean itself
+    step_alg_bytes = sum(kernel_bytes(kind, s_, d, D, mean_bits, narrow, fused) for kind, recs_ in per_kind.items() for s_, _ in recs_)
     if args.profile_all:
         for kind, recs in sorted(per_kind.items(), key=lambda kv: -sum(ms for _, ms in kv[1])):
             tot = sum(ms for _, ms in recs)
-            byts = sum(kernel_bytes(kind, s, d, D, mean_bits, narrow) for s, _ in recs)
+            byts = sum(kernel_bytes(kind, s, d, D, mean_bits, narrow, fused) for s, _ in recs)
             print(f"  {kind:14s} launches={len(recs):3d} total={tot:8.3f} ms  alg={byts / 1e9:7.3f} GB  "
                   f"{byts / 1e6 / max(tot, 1e-9):8.1f} GB/s", file=sys.stderr)
     ctx.profile_enable([dominant], 4096)
@@ -228,15 +233,11 @@ def main():
 
     enc_ms = timed(lambda: ctx.encode(xs, w.client_ids, w.b_q8, w.seed, msgs=msgs))
 
-    def decode_only():
-        acc.zero_()
-        ctx.decode_accumulate(msgs, w.client_ids, w.b_q8, d, w.seed, acc, bitmaps)
-        ctx.finalize_mean(acc, n, out=mean)
-
-    dec_ms = timed(decode_only)
+    dec_ms = timed(lambda: ctx.decode_mean(msgs, w.client_ids, w.b_q8, d, w.seed, mean, bitmaps))
+    three_ms = timed(three_call_step)
     graph_ms = graph_replay_ms(step, torch, args.steps)
     dom_ms = [ms for _, _, ms in recs]
-    dom_bytes = [kernel_bytes(k, s, d, D, mean_bits, narrow) for k, s, _ in recs]
+    dom_bytes = [kernel_bytes(k, s, d, D, mean_bits, narrow, fused) for k, s, _ in recs]
     avg_ms = sum(dom_ms) / len(dom_ms)
     achieved = (sum(dom_bytes) / len(dom_bytes)) / (avg_ms * 1e-3) / 1e9
 
@@ -263,6 +264,8 @@ def main():
         "value_counting_d": round(2.0 * n * d / (ms_per_step * 1e-3) / 1e9, 3),
         "encode_only": {"ms": round(enc_ms, 4), "Gcoords_per_s": round(n * D / (enc_ms * 1e-3) / 1e9, 1)},
         "decode_only": {"ms": round(dec_ms, 4), "Gcoords_per_s": round(n * D / (dec_ms * 1e-3) / 1e9, 1)},
+        "three_call_step": {"ms_per_step": round(three_ms, 4),
+                            "note": "zero + eden_decode_accumulate + eden_finalize_mean instead of eden_decode_mean"},
         "graph_replay": {"ms_per_step": round(graph_ms, 4), "Gcoords_per_s": round(coords_of(n, D) / (graph_ms * 1e-3) / 1e9, 1),
                          "note": "the same step replayed as one captured HIP graph; not the headline value"},
         "hbm_model": {"bytes_per_step": mbytes, "GBps": round(model_gbs, 1),

@@ -9,6 +9,7 @@
  *   eden_encode            -- the senders' side  (Sec. 2.2.1 rotation, quantization, Sec. 2.3 scale)
  *   eden_decode_accumulate -- the receiver's per-sender reconstruction, summed (Sec. 2.2.2, Sec. 4.2)
  *   eden_finalize_mean     -- the division by n   (Sec. 2.2.2)
+ * (eden_decode_mean is the last two in one call, for a round that one call decodes.)
  *
  * Conventions common to every call
  *   - Return value: 0 (EDEN_OK) or a negative eden_status.  Nothing throws or aborts.
@@ -18,7 +19,7 @@
  *   - The caller owns every buffer it passes.  The library reads inputs, writes outputs,
  *     and keeps no caller pointer after the call returns.  Its only own device memory is the
  *     context workspace allocated by eden_create.
- *   - eden_encode, eden_decode_accumulate and eden_finalize_mean only launch kernels on `stream`: no
+ *   - eden_encode, eden_decode_accumulate, eden_decode_mean and eden_finalize_mean only launch kernels on `stream`: no
  *     allocation (every buffer any budget needs is allocated by eden_create), no memset, no host synchronisation,
  *     so they may be captured in a HIP graph.
  *   - A context serialises its work through that workspace: calls on one context must be issued from
@@ -196,6 +197,18 @@ int eden_encode_static(const float *const *x_dev, const uint32_t *client_ids, co
 int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
                            const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
                            const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream);
+
+/* The receiver's whole round in one call (Sec. 2.2.2: reconstruct every sender's vector, average):
+ *   mean[i] = (1/n) sum_c x^_c[i],  i < d,
+ * the same numbers, bit for bit, as zeroing an accumulator, eden_decode_accumulate over the n messages and
+ * eden_finalize_mean with this n.  Arguments as in eden_decode_accumulate; mean_dev (device fp32[d], 16-byte
+ * aligned) is written only, whatever it held.  For rounds whose n messages are decoded by one call.  When one launch of
+ * the last pass sums all senders (no budget that sparsifies before the rotation, padded dimension at least 2^19, n at
+ * most 32) that pass stores the mean directly and the accumulator's three extra passes over memory (zero, read, divide)
+ * do not happen; in every other case the call runs those three steps itself on mean_dev. */
+int eden_decode_mean(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
+                     const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
+                     const uint32_t *const *recv_bitmaps_dev, float *mean_dev, void *stream);
 
 /* mean[i] = acc[i] / n for i < d (Sec. 2.2.2: the plain average, also with mixed budgets).
  * mean_dev may alias acc_dev. */

@@ -513,9 +513,11 @@ int eden_encode_static(const float *const *x_dev, const uint32_t *client_ids, co
 // for the arguments; `d_src` is the length of acc, `bitmaps` may be null).  pre == 2 (multi-pass sizes only, n at
 // most one launch): nothing is added to acc; every sender's decoded vector is left in its workspace slot.
 // `flags_out`: where the status word of message 0 of this range goes (device, one word per message).
+// `mean_n` > 0 (only where fused_mean_applies says so): acc is written with the sum divided by mean_n instead of added to.
 static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids, const uint32_t *b_kernel,
                         const uint32_t *b_hdr, uint32_t n, uint64_t d_src, int pre, uint64_t hdr_d, uint64_t seed,
-                        const uint32_t *const *bitmaps, float *acc_dev, uint32_t *flags_out, hipStream_t st) {
+                        const uint32_t *const *bitmaps, float *acc_dev, uint32_t *flags_out, hipStream_t st,
+                        float mean_n = 0.0f) {
     const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vectors
     const int log2D = ceil_log2(d);
     bool wide_ok = true;
@@ -575,7 +577,7 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
             Timed t(ctx, EDEN_K_DEC_LAST, nb, st);
             if (pl.lo_bits == 14)
                 launch_dec_lo14_last(B, nb, d_src, pre, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, 2 * ctx->compute_units,
-                                     ctx->dec_partial, ctx->dec_partial_tiles, st);
+                                     ctx->dec_partial, ctx->dec_partial_tiles, mean_n, st);
             else launch_dec_lo_last(B, nb, d_src, pre, log2D, seed, ctx->T, ctx->dec_scratch, narrow, acc_dev, st);
         }
         if (!launch_ok()) return EDEN_ERR_HIP;
@@ -583,21 +585,66 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
     return EDEN_OK;
 }
 
-int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
-                           const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
-                           const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream) {
-    if (!ctx || !msgs_dev || !client_ids || !b_q8 || !acc_dev) return EDEN_ERR_INVALID_ARG;
-    if (reinterpret_cast<uintptr_t>(acc_dev) & 15u) return EDEN_ERR_INVALID_ARG;
+// Argument checks shared by the two decode entry points; returns the sparsification mode (>= 0) or an error.
+static int check_decode_args(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids, const uint32_t *b_q8,
+                             uint32_t n, uint64_t d, const float *out_dev) {
+    if (!ctx || !msgs_dev || !client_ids || !b_q8 || !out_dev) return EDEN_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(out_dev) & 15u) return EDEN_ERR_INVALID_ARG;
     if (n == 0 || n > ctx->n_max || d == 0 || d > ctx->d_max) return EDEN_ERR_INVALID_ARG;
     for (uint32_t c = 0; c < n; ++c) {
         if (!msgs_dev[c] || (reinterpret_cast<uintptr_t>(msgs_dev[c]) & 15u)) return EDEN_ERR_INVALID_ARG;
         if (eden_message_bytes(d, b_q8[c]) == 0) return EDEN_ERR_INVALID_ARG;
     }
     const int mode = sparsify_mode(b_q8, n);
-    if (mode < 0) return EDEN_ERR_INVALID_ARG;
+    return mode < 0 ? EDEN_ERR_INVALID_ARG : mode;
+}
+
+static int decode_accumulate_on(eden_ctx *ctx, int mode, const void *const *msgs_dev, const uint32_t *client_ids,
+                                const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
+                                const uint32_t *const *recv_bitmaps_dev, float *acc_dev, hipStream_t st);
+
+int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
+                           const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
+                           const uint32_t *const *recv_bitmaps_dev, float *acc_dev, void *stream) {
+    const int mode = check_decode_args(ctx, msgs_dev, client_ids, b_q8, n, d, acc_dev);
+    if (mode < 0) return mode;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return EDEN_ERR_HIP;
+    return decode_accumulate_on(ctx, mode, msgs_dev, client_ids, b_q8, n, d, seed, recv_bitmaps_dev, acc_dev,
+                                static_cast<hipStream_t>(stream));
+}
+
+// The whole round of a receiver in one call.  When one launch of the 14-bit contiguous pass sums all the senders (no
+// sparsification before the rotation, D >= 2^19, at most kMaxBatch senders) that pass writes the mean itself: the
+// accumulator is neither zeroed, nor read, nor passed over once more for the division.  Otherwise the three steps run
+// one after the other on mean_dev.
+int eden_decode_mean(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids, const uint32_t *b_q8,
+                     uint32_t n, uint64_t d, uint64_t seed, const uint32_t *const *recv_bitmaps_dev, float *mean_dev,
+                     void *stream) {
+    const int mode = check_decode_args(ctx, msgs_dev, client_ids, b_q8, n, d, mean_dev);
+    if (mode < 0) return mode;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return EDEN_ERR_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (mode == 0 && n <= (uint32_t)kMaxBatch && make_plan(ceil_log2(d), false).lo_bits == 14) {
+        ctx->last_decode_n = n;
+        return decode_range(ctx, msgs_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, recv_bitmaps_dev, mean_dev, ctx->msg_flags, st,
+                            (float)n);
+    }
+    launch_fill_zero(mean_dev, d, st);
+    if (!launch_ok()) return EDEN_ERR_HIP;
+    const int rc = decode_accumulate_on(ctx, mode, msgs_dev, client_ids, b_q8, n, d, seed, recv_bitmaps_dev, mean_dev, st);
+    if (rc != EDEN_OK) return rc;
+    {
+        Timed t(ctx, EDEN_K_FINALIZE, n, st);
+        launch_finalize_mean(mean_dev, d, n, mean_dev, st);
+    }
+    return launch_ok() ? EDEN_OK : EDEN_ERR_HIP;
+}
+
+static int decode_accumulate_on(eden_ctx *ctx, int mode, const void *const *msgs_dev, const uint32_t *client_ids,
+                                const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
+                                const uint32_t *const *recv_bitmaps_dev, float *acc_dev, hipStream_t st) {
     std::vector<uint32_t> ones(n, 256u);
     ctx->last_decode_n = n;
     if (mode == 0) return decode_range(ctx, msgs_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, recv_bitmaps_dev, acc_dev, ctx->msg_flags, st);

@@ -84,10 +84,11 @@ void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
 uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d, int pre, int blocked, int log2D, uint64_t seed, float *T,
                                double *partials, uint32_t partial_stride, hipStream_t st);
 // `resident`: workgroups of the kernel the device holds at once (2 per CU); `partial`: room for `partial_tiles`
-// tiles of 2^14 floats, used when tiles are split over several workgroups by sender
+// tiles of 2^14 floats, used when tiles are split over several workgroups by sender.
+// `mean_n` > 0 (pre == 0 only): acc is not read; acc[i] = (0 + the sum over the senders) / mean_n
 void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d, int pre, int log2D, uint64_t seed, float *T,
                           const DecScratch *scratch, int narrow, float *acc, uint32_t resident, float *partial,
-                          uint32_t partial_tiles, hipStream_t st);
+                          uint32_t partial_tiles, float mean_n, hipStream_t st);
 
 }  // namespace eden
 #endif

@@ -163,7 +163,7 @@ template <bool PRE, bool ALL16>
 __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d_src, int log2D, uint64_t seed,
                                                        const float *T, const DecScratch *scratch, int narrow, float *acc,
                                                        uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
-                                                       float *partial, int separate) {
+                                                       float *partial, int separate, float mean_n) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14LdsWords];
     constexpr int NS = PRE ? 64 : 32;                            // accumulator coordinates per thread
     const uint64_t d = d_src;                                    // bound of acc
@@ -275,17 +275,24 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
 #pragma unroll
         for (int q = 0; q < 8; ++q)
             *reinterpret_cast<float4 *>(part_run + 4 * q) = make_float4(sum[4 * q], sum[4 * q + 1], sum[4 * q + 2], sum[4 * q + 3]);
-    } else if (tile_base + (1u << kLo14Bits) <= d) {
+        return;
+    }
+    // mean_n > 0: acc is written, not added to; the division happens here when no other workgroup adds to this tile
+    const bool overwrite = mean_n > 0.0f;
+    const float div = (overwrite && blockIdx.x < full_tiles) ? mean_n : 1.0f;
+    if (tile_base + (1u << kLo14Bits) <= d) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            float4 a = *reinterpret_cast<const float4 *>(acc + first + 4 * q);
-            a.x += sum[4 * q]; a.y += sum[4 * q + 1]; a.z += sum[4 * q + 2]; a.w += sum[4 * q + 3];
+            float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (!overwrite) a = *reinterpret_cast<const float4 *>(acc + first + 4 * q);
+            a.x = (a.x + sum[4 * q]) / div; a.y = (a.y + sum[4 * q + 1]) / div;
+            a.z = (a.z + sum[4 * q + 2]) / div; a.w = (a.w + sum[4 * q + 3]) / div;
             *reinterpret_cast<float4 *>(acc + first + 4 * q) = a;
         }
     } else {                                                     // the one tile that straddles d
 #pragma unroll
         for (int e = 0; e < 32; ++e)
-            if (first + e < d) acc[first + e] += sum[e];
+            if (first + e < d) acc[first + e] = ((overwrite ? 0.0f : acc[first + e]) + sum[e]) / div;
     }
 }
 
@@ -340,7 +347,7 @@ __device__ inline float minus_half(float x, uint32_t packed) {
 __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
                                                                const float *T, const DecScratch *scratch, float *acc,
                                                                uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
-                                                               float *partial) {
+                                                               float *partial, float mean_n) {
     __shared__ __attribute__((aligned(16))) float lds[1 << kLo14Bits];
     const uint32_t t = threadIdx.x, lane = t & 63u, wv = wave_in_block(), h = lane >> 5, m = lane & 31u;
     uint32_t tile = blockIdx.x, c_begin = 0, c_end = n;
@@ -451,28 +458,36 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
             part[1024 * u + mine_off] = sum[u];
             part[1024 * u + mine_off + 32] = sum[16 + u];
         }
-    } else if (tile_base + (1u << kLo14Bits) <= d) {
+        return;
+    }
+    // mean_n > 0: acc is written, not added to; the division happens here when no other workgroup adds to this tile
+    const bool overwrite = mean_n > 0.0f;
+    const float div = (overwrite && blockIdx.x < full_tiles) ? mean_n : 1.0f;
+    if (tile_base + (1u << kLo14Bits) <= d) {
         float *A = acc + tile_base + mine_off;
         float old[32];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) { old[u] = A[1024 * u]; old[16 + u] = A[1024 * u + 32]; }
+        for (int e = 0; e < 32; ++e) old[e] = 0.0f;
+        if (!overwrite) {
 #pragma unroll
-        for (int u = 0; u < 16; ++u) { A[1024 * u] = old[u] + sum[u]; A[1024 * u + 32] = old[16 + u] + sum[16 + u]; }
+            for (int u = 0; u < 16; ++u) { old[u] = A[1024 * u]; old[16 + u] = A[1024 * u + 32]; }
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) { A[1024 * u] = (old[u] + sum[u]) / div; A[1024 * u + 32] = (old[16 + u] + sum[16 + u]) / div; }
     } else {                                                     // the one tile that straddles d
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             const uint64_t i = tile_base + 1024u * u + mine_off;
-            if (i < d) acc[i] += sum[u];
-            if (i + 32 < d) acc[i + 32] += sum[16 + u];
+            if (i < d) acc[i] = ((overwrite ? 0.0f : acc[i]) + sum[u]) / div;
+            if (i + 32 < d) acc[i + 32] = ((overwrite ? 0.0f : acc[i + 32]) + sum[16 + u]) / div;
         }
     }
 }
 
-
 // acc[i] += partial[0][i'] + partial[1][i'] + ... for the tiles that k_dec_lo14_last split over K workgroups
-// (added one after the other, in this order).  One thread per four coordinates.
+// (added one after the other, in this order); with mean_n > 0 the total is divided by it.  One thread per four coordinates.
 __global__ __launch_bounds__(256) void k_dec_lo14_combine(float *acc, uint64_t d, uint32_t full_tiles, uint32_t K,
-                                                          uint32_t split_tiles, const float *partial) {
+                                                          uint32_t split_tiles, const float *partial, float mean_n) {
     const uint64_t local = ((uint64_t)blockIdx.x * 256u + threadIdx.x) * 4u;         // inside the split tiles
     const uint64_t i = ((uint64_t)full_tiles << kLo14Bits) + local;
     if (local >= ((uint64_t)split_tiles << kLo14Bits) || i >= d) return;
@@ -483,9 +498,10 @@ __global__ __launch_bounds__(256) void k_dec_lo14_combine(float *acc, uint64_t d
         const float4 p = *reinterpret_cast<const float4 *>(partial + (((size_t)(k - 1) * split_tiles) << kLo14Bits) + local);
         s[0] += p.x; s[1] += p.y; s[2] += p.z; s[3] += p.w;
     }
+    const float div = mean_n > 0.0f ? mean_n : 1.0f;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-        if (i + e < d) acc[i + e] = s[e];
+        if (i + e < d) acc[i + e] = s[e] / div;
 }
 
 uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d_src, int pre, int blocked, int log2D, uint64_t seed, float *T,
@@ -505,17 +521,17 @@ uint32_t launch_enc_lo14_first(const EncBatch &B, uint32_t n, uint64_t d_src, in
 }
 void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, float *T,
                           const DecScratch *scratch, int narrow, float *acc, uint32_t resident, float *partial,
-                          uint32_t partial_tiles, hipStream_t st) {
+                          uint32_t partial_tiles, float mean_n, hipStream_t st) {
     const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vectors
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);     // tiles that reach below d
     if (pre == 1) {
         hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<true, false>), dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T,
-                           scratch, narrow, acc, tiles, 1u, 0u, partial, 0);
+                           scratch, narrow, acc, tiles, 1u, 0u, partial, 0, 0.0f);
         return;
     }
     if (pre == 2) {                                              // every sender on its own, back into its workspace slot
         hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, false>), dim3(tiles * n), dim3(512), 0, st, B, n, d_src, log2D, seed,
-                           T, scratch, 0, acc, 0u, n, tiles, T, 1);
+                           T, scratch, 0, acc, 0u, n, tiles, T, 1, 0.0f);
         return;
     }
     bool all16 = narrow != 0;                                    // every sender's workspace slot holds int16
@@ -533,16 +549,16 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     dim3 grid(full + rest * K);
     if (all16 && log2D <= 24)                                    // |values| <= 2^10: ten of the bits on the matrix cores
         hipLaunchKernelGGL(k_dec_lo14_last_mfma, grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, acc, full, K, rest,
-                           partial);
+                           partial, mean_n);
     else if (all16)
         hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, true>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
-                           narrow, acc, full, K, rest, partial, 0);
+                           narrow, acc, full, K, rest, partial, 0, mean_n);
     else
         hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, false>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
-                           narrow, acc, full, K, rest, partial, 0);
+                           narrow, acc, full, K, rest, partial, 0, mean_n);
     if (K > 1) {
         dim3 cgrid((uint32_t)((((uint64_t)rest << kLo14Bits) / 4 + 255) / 256));
-        hipLaunchKernelGGL(k_dec_lo14_combine, cgrid, dim3(256), 0, st, acc, d, full, K, rest, partial);
+        hipLaunchKernelGGL(k_dec_lo14_combine, cgrid, dim3(256), 0, st, acc, d, full, K, rest, partial, mean_n);
     }
 }
 

@@ -33,7 +33,7 @@ EXPORTS = [
     "eden_finalize_mean", "eden_last_device_status", "eden_make_loss_bitmap", "eden_make_sign_bits",
     "eden_make_subsample_bits", "eden_get_tables", "eden_strerror", "eden_profile_enable", "eden_profile_collect",
     "eden_kernel_name", "eden_sq_error", "eden_index_entropy", "eden_encode_static",
-    "eden_last_decode_flags", "eden_message_length",
+    "eden_last_decode_flags", "eden_message_length", "eden_decode_mean",
 ]
 B_HALF_PRE = 0x10080     # b = 1/2 with the sparsification before the rotation (EDEN_B_HALF_PRE)
 
@@ -93,6 +93,8 @@ def lib():
     L.eden_encode_static.restype = ci
     L.eden_decode_accumulate.argtypes = [vp, P(vp), P(u32), P(u32), u32, u64, u64, P(vp), vp, vp]
     L.eden_decode_accumulate.restype = ci
+    L.eden_decode_mean.argtypes = [vp, P(vp), P(u32), P(u32), u32, u64, u64, P(vp), vp, vp]
+    L.eden_decode_mean.restype = ci
     L.eden_finalize_mean.argtypes = [vp, vp, u64, u32, vp, vp]
     L.eden_finalize_mean.restype = ci
     L.eden_last_decode_flags.argtypes = [vp, vp, P(u32), u32]
@@ -219,6 +221,13 @@ class Context:
                                             n, d, ctypes.c_uint64(seed & (2 ** 64 - 1)), bm,
                                             ctypes.c_void_p(acc_ptr), _stream_ptr(stream))
 
+    def decode_mean_raw(self, msg_ptrs, client_ids, b_q8, d, seed, bitmap_ptrs, mean_ptr, stream=None) -> int:
+        n = len(msg_ptrs)
+        bm = _ptr_array(bitmap_ptrs) if bitmap_ptrs is not None else None
+        return lib().eden_decode_mean(self._h, _ptr_array(msg_ptrs), _u32_array(client_ids), _u32_array(b_q8),
+                                      n, d, ctypes.c_uint64(seed & (2 ** 64 - 1)), bm,
+                                      ctypes.c_void_p(mean_ptr), _stream_ptr(stream))
+
     def finalize_mean_raw(self, acc_ptr, d, n, mean_ptr, stream=None) -> int:
         return lib().eden_finalize_mean(self._h, ctypes.c_void_p(acc_ptr), d, n, ctypes.c_void_p(mean_ptr),
                                         _stream_ptr(stream))
@@ -249,6 +258,15 @@ class Context:
             raise EdenError(rc, "eden_decode_accumulate")
         return acc
 
+    def decode_mean(self, msgs, client_ids, b_q8, d: int, seed: int, mean, bitmaps=None, stream=None):
+        """The receiver's whole round: mean = (1/n) sum of the n decoded vectors, written (not added) to `mean`."""
+        assert mean.is_cuda and mean.element_size() == 4 and mean.numel() == d and mean.is_contiguous()
+        bm = None if bitmaps is None else [None if b is None else b.data_ptr() for b in bitmaps]
+        rc = self.decode_mean_raw([m.data_ptr() for m in msgs], client_ids, b_q8, d, seed, bm, mean.data_ptr(), stream)
+        if rc != OK:
+            raise EdenError(rc, "eden_decode_mean")
+        return mean
+
     def finalize_mean(self, acc, n: int, out=None, stream=None):
         out = acc if out is None else out
         rc = self.finalize_mean_raw(acc.data_ptr(), acc.numel(), n, out.data_ptr(), stream)
@@ -264,7 +282,7 @@ class Context:
         return int(v.value)
 
     def last_decode_flags(self, n: int, stream=None):
-        """Status bits of the first n messages of the most recent decode_accumulate call, in call order."""
+        """Status bits of the first n messages of the most recent decode_accumulate / decode_mean call, in call order."""
         out = (ctypes.c_uint32 * n)()
         rc = lib().eden_last_decode_flags(self._h, _stream_ptr(stream), out, n)
         if rc != OK:

@@ -441,6 +441,42 @@ def test_step_can_be_captured_in_a_graph(ctx, kind):
     assert ctx.last_device_status() == 0
 
 
+@pytest.mark.parametrize("d,budgets,drop", [
+    (3000, [256, 512, 1024], 0),                               # one workgroup per sender: the three steps inside the call
+    (200_000, [128, 256, 768], 0.2),                           # 12-bit contiguous pass: the same
+    ((1 << 19) + 77, [256, 256, 128, 256, 256], 0.1),          # few tiles, split over the senders, matrix-core pass
+    (700_000, [512, 256, 1024, 384], 0),                       # few tiles, vector pass
+    (5_000_000, [256, 256, 256], 0.05),                        # many tiles, matrix-core pass, last tile ragged
+    (1 << 23, [1024, 256], 0),                                 # many tiles, vector pass
+    (2_500_000, [0x10080, 0x10080], 0),                        # sparsification before the rotation: the three steps
+    (400_000, ["sparse6", "sparse6"], 0),
+])
+def test_decode_mean_equals_the_three_steps(ctx, d, budgets, drop):
+    # eden_decode_mean writes what zero + eden_decode_accumulate + eden_finalize_mean leave, bit for bit, whatever the
+    # output buffer held, in the cases where the last pass stores the mean itself and in those where it does not
+    from paper_2108_08842_amd import eden
+    budgets = [eden.B_SPARSE(6) if b == "sparse6" else b for b in budgets]
+    n = len(budgets)
+    w = synth.Workload("t", n, d, budgets, 77 + d % 1000, "lognormal_signed")
+    xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(n)]
+    ids = list(range(50, 50 + n))
+    msgs = ctx.encode(xs, ids, w.b_q8, w.seed)
+    bitmaps = None
+    if drop:
+        D = o.padded_dim(d)
+        bitmaps = [ctx.make_loss_bitmap(w.seed, c, D, int(drop * 2 ** 32)) for c in ids]
+    acc = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs, ids, w.b_q8, d, w.seed, acc, bitmaps)
+    want = ctx.finalize_mean(acc, n, out=torch.empty_like(acc))
+    got = torch.full((d,), float("nan"), device="cuda")
+    ctx.decode_mean(msgs, ids, w.b_q8, d, w.seed, got, bitmaps)
+    torch.cuda.synchronize()
+    assert ctx.last_device_status() == 0
+    assert torch.equal(got.view(torch.int32), want.view(torch.int32))
+    assert ctx.last_decode_flags(n) == [0] * n
+    assert ctx.decode_mean_raw([m.data_ptr() for m in msgs], ids, w.b_q8, d, w.seed, None, got.data_ptr() + 4) == eden.ERR_INVALID_ARG
+
+
 def test_two_contexts_on_two_streams_and_kernel_timing(ctx):
     # one context per concurrent stream: two rounds in flight at once give the results of the same rounds run alone;
     # the optional kernel timing reports every launch of the kinds it was asked for
