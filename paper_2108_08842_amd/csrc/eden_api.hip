@@ -550,7 +550,7 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
             launch_dec_small(B, nb, d_src, pre, hdr_d, log2D, seed, ctx->tables, acc_dev, ctx->dev_status, flags_out + first, st);
         } else {
             // Strided passes first (every sender on its own), contiguous pass last (sums the senders in registers
-            // and touches acc once).  With a single strided pass the workspace of a b <= 1 sender holds int16.
+            // and touches acc once).  With a single strided pass the workspace of a b <= 1 sender holds fp16 (narrow_bits in eden_device.h).
             const int narrow = (pl.nhi == 1 && pre != 2) ? 1 : 0;
             bool coins = false;                                  // the receiver draws and counts the same coins
             for (uint32_t i = 0; i < nb; ++i) coins = coins || coin_q8(B.b_q8[i]);

@@ -462,6 +462,19 @@ __device__ inline uint32_t quantize_mixed(float u, bool up, const EncScratch *sc
     return up ? code_hi : code_lo;
 }
 
+// ---- narrow decode workspace.  After the strided pass of a two-pass size the values of a b <= 1 sender are integers of
+// magnitude at most 2^10 (+-1 or 0 through at most ten butterfly stages): the workspace holds them as fp16, which is exact
+// (11 significant bits) and is the operand type of the matrix-core pass that reads them back.
+__device__ inline short narrow_bits(float v) { return __builtin_bit_cast(short, (_Float16)v); }
+__device__ inline float narrow_value(short bits) { return (float)__builtin_bit_cast(_Float16, bits); }
+// two int16 in one register -> two fp16, in place (written out: the compiler converts into two registers and packs them)
+__device__ inline uint32_t narrow_pair_from_int16(uint32_t w) {
+    asm("v_cvt_f16_i16_sdwa %0, %0 dst_sel:WORD_0 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0\n\t"
+        "v_cvt_f16_i16_sdwa %0, %0 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_1"
+        : "+v"(w));
+    return w;
+}
+
 // ---- blocked layout of the encoder's workspace between the 14-bit contiguous pass and a workgroup-tile strided pass that
 // covers all the bits above it.  Element (row r, column block cb of 32 coordinates, column) of a sender's slot sits, in
 // floats, at ((r / R) * 512 + cb) * (R * 32) + (r % R) * 32 + column with R = kBlockRows: the 128-byte segments of R

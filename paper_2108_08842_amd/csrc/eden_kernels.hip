@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *part
 }
 
 // Decode, first pass in wave tiles (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit
-// pattern +-1 when the workspace of a b <= 1 sender is int16), zero for coordinates that were not sampled or
+// pattern +-1 when the workspace of a b <= 1 sender is fp16), zero for coordinates that were not sampled or
 // whose packet was lost, then index bits p .. p+M-1 of H.  Every (tile, sender) pair is independent.
 // Elements at or above `keep_elems` are never read by the later passes (they end in the padding): the buffer
 // bounds drop their stores.
@@ -423,11 +423,11 @@ __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t ke
         for (int r = 0; r < R; ++r) v[r] = ((recv >> r) & 1ull) ? v[r] : 0.0f;     // wave-uniform per row
     }
     fwht_regs<R>(v);
-    if (i16) {                                                   // exact integers of magnitude <= 2^M
+    if (i16) {                                                   // exact integers of magnitude <= 2^M, as fp16
         const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), (uint32_t)(keep_elems * 2));
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            __builtin_amdgcn_raw_buffer_store_b16((short)(int)v[r], rt, (int)(lane * 2u),
+            __builtin_amdgcn_raw_buffer_store_b16(narrow_bits(v[r]), rt, (int)(lane * 2u),
                                                   (int)(((uint32_t)base + ((uint32_t)r << p)) * 2u), kStream);
     } else {
         const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), (uint32_t)(keep_elems * 4));
@@ -930,7 +930,7 @@ __global__ __launch_bounds__(128) void k_dec_lo_last(DecBatch B, uint32_t n, uin
         if (i16) {
             const short *t16 = reinterpret_cast<const short *>(T + ((size_t)c << log2D)) + tile_base + lane;
 #pragma unroll
-            for (int j = 0; j < 64; ++j) v[j] = (float)(int)__builtin_nontemporal_load(t16 + 64 * j);
+            for (int j = 0; j < 64; ++j) v[j] = narrow_value(__builtin_nontemporal_load(t16 + 64 * j));
         } else {
             const float *t32 = T + ((size_t)c << log2D) + tile_base + lane;
 #pragma unroll

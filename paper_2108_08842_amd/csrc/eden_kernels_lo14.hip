@@ -140,7 +140,7 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
 
 // Decode, last pass: index bits 0..13 of H for every sender, that sender's sign diagonal (R^-1 = s o D^-1/2 H,
 // Sec. 2.2.2), sum over senders in registers, one contiguous read-modify-write of acc.
-// `narrow`: senders with b <= 1 have an int16 workspace holding exact integers; their magnitude S/(p sqrt D) q_1
+// `narrow`: senders with b <= 1 have an fp16 workspace holding exact integers; their magnitude S/(p sqrt D) q_1
 // is applied together with the sign.
 //
 // Work split.  A workgroup's time is proportional to the senders it sums and the chip holds `2 x CUs` of these
@@ -156,10 +156,7 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
 // `separate`: K = n, one sender per workgroup, nothing is summed: every sender's decoded tile is written back into its own
 // workspace slot (`partial` is then the workspace; fp32, in place: the workgroup has read the tile before it writes
 // it), for a caller that puts the values elsewhere afterwards.
-// ALL16: every sender of the launch has an int16 workspace (the common case of a b <= 1 round); the loads then go
-// through buffer descriptors (the offsets of the 32 rows sit in scalar registers: no address arithmetic per load) and
-// nothing in the sender loop chooses between the two formats.
-template <bool PRE, bool ALL16>
+template <bool PRE>
 __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d_src, int log2D, uint64_t seed,
                                                        const float *T, const DecScratch *scratch, int narrow, float *acc,
                                                        uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
@@ -186,14 +183,7 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     for (int e = 0; e < NS; ++e) sum[e] = 0.0f;
 
     auto load = [&](uint32_t c, float (&dst_regs)[32]) {
-        if constexpr (ALL16) {
-            // int16 element i of the slot at byte 2 i; the tile lies inside the slot, so the bound is the slot's end
-            const rsrc_t r16 = make_rsrc(T + ((size_t)c << log2D), 2u << log2D);
-            const uint32_t lane_off = (wv * 64u + lane) * 2u, tile_off = (uint32_t)tile_base * 2u;
-#pragma unroll
-            for (int a = 0; a < 32; ++a)
-                dst_regs[a] = __int_as_float((int)(short)__builtin_amdgcn_raw_buffer_load_b16(r16, (int)lane_off, (int)(tile_off + 1024u * a), kStream));
-        } else if (narrow && B.b_q8[c] <= 256u) {
+        if (narrow && B.b_q8[c] <= 256u) {
             const short *t16 = reinterpret_cast<const short *>(T + ((size_t)c << log2D)) + in_off;
 #pragma unroll
             for (int a = 0; a < 32; ++a) dst_regs[a] = __int_as_float((int)__builtin_nontemporal_load(t16 + 512 * a));
@@ -207,13 +197,12 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     // load ahead); the loads of sender c + 1 go into the same registers once the values have been converted.  (Two
     // alternating register sets would save the compiler's copy of the loaded set, but need more than 128 registers.)
     auto one_sender = [&](uint32_t c, float (&cur)[32]) {
-        const bool i16 = ALL16 || (narrow && B.b_q8[c] <= 256u);
+        const bool i16 = narrow && B.b_q8[c] <= 256u;
         float u[32];
         if constexpr (PRE) load(c, cur);
 #pragma unroll
         for (int a = 0; a < 32; ++a) {
-            if constexpr (ALL16) u[a] = (float)__float_as_int(cur[a]);
-            else u[a] = i16 ? (float)__float_as_int(cur[a]) : cur[a];
+            u[a] = i16 ? narrow_value((short)__float_as_int(cur[a])) : cur[a];
         }
         __builtin_amdgcn_sched_barrier(0);                       // the conversions stay above the next sender's loads
         if (!PRE && c + 1 < c_end) load(c + 1, cur);
@@ -296,12 +285,12 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     }
 }
 
-// ---- the same pass for launches whose senders all have an int16 workspace of small exact integers (b <= 1, D <= 2^24:
+// ---- the same pass for launches whose senders all have an fp16 workspace of small exact integers (b <= 1, D <= 2^24:
 // |value| <= 2^10 after at most ten strided bits), with ten of the fourteen bits on the matrix cores.
 //
 // The tile is a 16 x 32 x 32 array (u, n, k) = index bits 10..13, 5..9, 0..4.  A wave owns two values of u.  For one u:
 //   step 1  bits 0..4   D1[n][k'] = sum_k X[n][k] H[k][k']: v_mfma_f32_32x32x16_f16 twice, X as the A operand straight from
-//           memory (a lane holds 16 consecutive int16 of its row n, converted to fp16: exact, |x| <= 2^10 < 2^11).
+//           memory (a lane holds 16 consecutive fp16 of its row n: exact integers, |x| <= 2^10 < 2^11).
 //   step 2  bits 5..9   D2[n'][k'] = sum_n H[n'][n] D1[n][k']: the registers that hold D1 ARE a B operand (lane = column k',
 //           registers = 8 values of n per lane half), the Hadamard A operand is built with its columns in that order, so
 //           nothing moves between the steps.  |D1| <= 2^15 does not fit fp16's 11 bits: every value is split into its fp16
@@ -313,26 +302,13 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
 // Register (u, j) of thread (wave w, lane l = 32 h + m) then holds coordinate 1024 u + 32 n' + m of the tile with
 // n' = 8 (w / 2) + 4 h + 2 (w % 2) + j: 32 lanes cover one 128-byte line of acc, and the 32 sign bits of those lanes are one
 // half (j) of one 64-bit word of the sender's SIGN stream.
-// Per coordinate and sender this leaves about 10 vector instructions (conversion 1, split 2, butterflies 4, sign and
-// accumulate 3) where the all-vector version spends 19, and one exchange instead of two.
+// Per coordinate and sender this leaves about 9 vector instructions (split 2, butterflies 4, sign and accumulate 3)
+// where the all-vector version spends 19, and one exchange instead of two.
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 __device__ inline _Float16 hadamard_entry(uint32_t a, uint32_t b) {
     return (__builtin_popcount(a & b) & 1) ? (_Float16)-1.0f : (_Float16)1.0f;
-}
-// eight int16 (four dwords) -> eight fp16, same order and same registers: each half of a dword is converted in place
-// (written out because the compiler converts into two registers and packs them again: three instructions per pair)
-__device__ inline half8_t halves_of_int16(uint32_t (&w)[4]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        asm("v_cvt_f16_i16_sdwa %0, %0 dst_sel:WORD_0 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0\n\t"
-            "v_cvt_f16_i16_sdwa %0, %0 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_1\n\t"
-            "s_nop 1"                                            // the matrix instruction that reads it may come next
-            : "+v"(w[i]));
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 v = {w[0], w[1], w[2], w[3]};
-    return __builtin_bit_cast(half8_t, v);
 }
 // x - (float)h for the fp16 in the low (HIGH = 0) or high half of `packed`: one mixed-precision fused multiply-add
 // (-1 * h + x, exact: h is x truncated to 11 bits)
@@ -362,7 +338,7 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
     const uint64_t tile_base = (uint64_t)tile << kLo14Bits;
 
     // the two Hadamard operands: entry e of instruction q on lane (h, m)
-    //   step 1, B[k][k']: k' = m, k = 16 h + 8 q + e    (the 16 consecutive int16 a lane loads are k = 16 h .. 16 h + 15)
+    //   step 1, B[k][k']: k' = m, k = 16 h + 8 q + e    (the 16 consecutive fp16 a lane loads are k = 16 h .. 16 h + 15)
     //   step 2, A[n'][n]: n' = m, n = row of D1 that register 8 q + e of lane half h holds = 16 q + 8 (e / 4) + 4 h + e % 4
     half8_t Hk[2], Hn[2];
 #pragma unroll
@@ -377,7 +353,7 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
 #pragma unroll
     for (int e = 0; e < 32; ++e) sum[e] = 0.0f;
 
-    // raw[2 s + q]: int16 k = 16 h + 8 q .. + 7 of row n = m of unit u = wv + 8 s
+    // raw[2 s + q]: fp16 k = 16 h + 8 q .. + 7 of row n = m of unit u = wv + 8 s
     const uint32_t lane_off = (m * 32u + 16u * h) * 2u;
     auto load = [&](uint32_t c, uint32_t (&raw)[4][4]) {
         const rsrc_t r16 = make_rsrc(T + ((size_t)c << log2D), 2u << log2D);       // the tile lies inside the slot
@@ -398,10 +374,13 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
     uint32_t raw[4][4];
     if (c_begin < c_end) load(c_begin, raw);
     for (uint32_t c = c_begin; c < c_end; ++c) {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
         half8_t x[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = halves_of_int16(raw[i]);
-        __builtin_amdgcn_sched_barrier(0);                       // the conversions stay above the next sender's loads
+        for (int i = 0; i < 4; ++i) {
+            const u32x4 v = {raw[i][0], raw[i][1], raw[i][2], raw[i][3]};
+            x[i] = __builtin_bit_cast(half8_t, v);
+        }
         if (c + 1 < c_end) load(c + 1, raw);
         if (c > c_begin) __syncthreads();                        // every wave has read the previous sender's values
 #pragma unroll
@@ -409,7 +388,6 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
             float16_t d1 = {0};
             d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[2 * s], Hk[0], d1, 0, 0, 0);
             d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[2 * s + 1], Hk[1], d1, 0, 0, 0);
-            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
             u32x4 hi[2], lo[2];                                  // fp16 pairs: registers 2 i, 2 i + 1 of d1
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
@@ -525,16 +503,16 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vectors
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);     // tiles that reach below d
     if (pre == 1) {
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<true, false>), dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T,
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<true>), dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T,
                            scratch, narrow, acc, tiles, 1u, 0u, partial, 0, 0.0f);
         return;
     }
     if (pre == 2) {                                              // every sender on its own, back into its workspace slot
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, false>), dim3(tiles * n), dim3(512), 0, st, B, n, d_src, log2D, seed,
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false>), dim3(tiles * n), dim3(512), 0, st, B, n, d_src, log2D, seed,
                            T, scratch, 0, acc, 0u, n, tiles, T, 1, 0.0f);
         return;
     }
-    bool all16 = narrow != 0;                                    // every sender's workspace slot holds int16
+    bool all16 = narrow != 0;                                    // every sender's workspace slot holds fp16
     for (uint32_t c = 0; c < n; ++c) all16 = all16 && B.b_q8[c] <= 256u;
     // Fewer tiles than half the resident workgroups: split every tile K ways by sender so that the chip is filled
     // (measured 2.2x on 64 tiles x 32 senders).  With more tiles than resident workgroups, splitting only the
@@ -547,14 +525,11 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     }
     if (K == 1) { full = tiles; rest = 0; }
     dim3 grid(full + rest * K);
-    if (all16 && log2D <= 24)                                    // |values| <= 2^10: ten of the bits on the matrix cores
+    if (all16)                                                   // |values| <= 2^10: ten of the bits on the matrix cores
         hipLaunchKernelGGL(k_dec_lo14_last_mfma, grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, acc, full, K, rest,
                            partial, mean_n);
-    else if (all16)
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, true>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
-                           narrow, acc, full, K, rest, partial, 0, mean_n);
     else
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, false>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
                            narrow, acc, full, K, rest, partial, 0, mean_n);
     if (K > 1) {
         dim3 cgrid((uint32_t)((((uint64_t)rest << kLo14Bits) / 4 + 255) / 256));

@@ -433,7 +433,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D
 // registers and touches acc once, with fully contiguous accesses.
 
 // First decode pass (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit pattern when the
-// workspace is int16), zero for coordinates that were not sampled or whose packet was lost, then index bits
+// workspace is fp16), zero for coordinates that were not sampled or whose packet was lost, then index bits
 // 14 .. 14+M-1 of H.
 template <int M>
 __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B, uint64_t d, int log2D, uint64_t seed,
@@ -619,17 +619,17 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B
     const uint32_t rows_used = (uint32_t)((d + (1u << p) - 1) >> p);
     float out[X::RP];
     if (i16) {
-        // exact integers of magnitude <= 2^M: int16 at the same element index
+        // exact integers of magnitude <= 2^M: fp16 at the same element index
         const rsrc_t rt = make_rsrc(slot + (base_off >> 1), (rows_used << (p + 1)) - (base_off >> 1));
         hix_exchange<M, 0>(v, lds, out);
 #pragma unroll
         for (int s = 0; s < X::RP; ++s)
-            __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 0, s) << (p + 2)) >> 1), kStream);
+            __builtin_amdgcn_raw_buffer_store_b16(narrow_bits(out[s]), rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 0, s) << (p + 2)) >> 1), kStream);
         if constexpr (X::PH == 2) {
             hix_exchange<M, 1>(v, lds, out);
 #pragma unroll
             for (int s = 0; s < X::RP; ++s)
-                __builtin_amdgcn_raw_buffer_store_b16((short)(int)out[s], rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 1, s) << (p + 2)) >> 1), kStream);
+                __builtin_amdgcn_raw_buffer_store_b16(narrow_bits(out[s]), rt, (int)(off2 >> 1), (int)((hix_row2<M>(0, 1, s) << (p + 2)) >> 1), kStream);
         }
     } else {
         const rsrc_t rt = make_rsrc(slot + base_off, (rows_used << (p + 2)) - base_off);
@@ -647,7 +647,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B
 // First decode pass for senders with b <= 1, two columns per thread.  The unit pattern is +-1 or 0 and M <= 10
 // stages keep every value within +-1024, so the whole pass runs on pairs of int16 packed in one register
 // (v_pk_add_i16 / v_pk_sub_i16: two butterflies per instruction) and a tile is 64 columns wide: the workspace
-// is written in 128-byte segments.
+// is written in 128-byte segments, each pair converted to fp16 (the narrow workspace's type) just before its store.
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 template <int N, int LOGB>
@@ -731,7 +731,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatc
 #pragma unroll
     for (int r = 0; r < 64; ++r) v[r] = __builtin_bit_cast(s16x2, v32[r]);
     fwht_pk<64, 6>(v);
-    // int16 element i of the sender's slot sits at byte 2 i: the pair of this thread is one 32-bit store
+    // element i of the sender's slot (fp16) sits at byte 2 i: the pair of this thread is one 32-bit store, converted last
     char *slot = reinterpret_cast<char *>(T + ((size_t)c << log2D)) + base * 2u;
     // rows at or above ceil(d / 2^14) are never read by the last pass: the bounds drop their stores
     const uint32_t rows_used = (uint32_t)((d + (1u << p) - 1) >> p);
@@ -753,7 +753,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatc
         fwht_pk<X::RP, M - 6>(out);
 #pragma unroll
         for (int s2 = 0; s2 < X::RP; ++s2)
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, out[s2]), rt, (int)off2,
+            __builtin_amdgcn_raw_buffer_store_b32(narrow_pair_from_int16(__builtin_bit_cast(uint32_t, out[s2])), rt, (int)off2,
                                                   (int)((hix_row2<M>(0, ph, s2) << p) * 2u), kStream);
     }
 }
