@@ -142,8 +142,8 @@ def time_config(k, eden, synth, torch, steps=20, warmup=3):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20, help="untimed steps first (the clocks of a fresh box settle within about ten)")
     ap.add_argument("--config", type=int, default=4, help="synthetic configuration 1..5 (4 = the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
