@@ -462,6 +462,26 @@ __device__ inline uint32_t quantize_mixed(float u, bool up, const EncScratch *sc
     return up ? code_hi : code_lo;
 }
 
+// ---- operands of the matrix instructions (v_mfma_f32_32x32x16_f16 / _fp8_fp8).  Lane l = 32 h + m holds, of A (32 x 16), row m
+// and k = 8 h .. 8 h + 7; of B (16 x 32), column m and the same k; of the 32 x 32 result, column m and rows
+// 8 (r / 4) + 4 h + r % 4 in registers r = 0 .. 15 (checked on the device with random integer matrices).
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+// entry (a, b) of the Sylvester Hadamard matrix
+__device__ inline _Float16 hadamard_entry(uint32_t a, uint32_t b) {
+    return (__builtin_popcount(a & b) & 1) ? (_Float16)-1.0f : (_Float16)1.0f;
+}
+// the second operand of the second of two chained transforms: the 16 result registers of the first product (rows of D1 in
+// the order above) are, packed to fp16 in pairs, the B operands of two instructions (registers 0..7 and 8..15); entry e of
+// instruction q on lane (h, m) of the Hadamard A operand must then stand for row 16 q + 8 (e / 4) + 4 h + e % 4
+__device__ inline half8_t hadamard_rows_of_result(uint32_t q, uint32_t h, uint32_t m) {
+    half8_t r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = hadamard_entry(16u * q + 8u * ((uint32_t)e >> 2) + 4u * h + ((uint32_t)e & 3u), m);
+    return r;
+}
+
 // ---- narrow decode workspace.  After the strided pass of a two-pass size the values of a b <= 1 sender are integers of
 // magnitude at most 2^10 (+-1 or 0 through at most ten butterfly stages): the workspace holds them as fp16, which is exact
 // (11 significant bits) and is the operand type of the matrix-core pass that reads them back.

@@ -628,8 +628,8 @@ __global__ __launch_bounds__(256) void k_dec_wide_first(DecBatch B, uint64_t kee
         for (int h = 0; h < 2; ++h) {
             u32x4_t q = {__float_as_uint(v[r][4 * h]), __float_as_uint(v[r][4 * h + 1]), __float_as_uint(v[r][4 * h + 2]),
                          __float_as_uint(v[r][4 * h + 3])};
-            __builtin_amdgcn_raw_buffer_store_b128(q, rt, (int)(lane * 16u), (int)((base + 256u * h + ((uint32_t)r << p)) * 4u),
-                                                   kStream);
+            // (no scalar offset on a store of more than 64 bits: see the note in k_dec_hix_first_mfma)
+            __builtin_amdgcn_raw_buffer_store_b128(q, rt, (int)(lane * 16u + (base + 256u * h + ((uint32_t)r << p)) * 4u), 0, kStream);
         }
     }
 }

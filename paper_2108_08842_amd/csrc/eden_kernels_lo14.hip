@@ -304,12 +304,6 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
 // half (j) of one 64-bit word of the sender's SIGN stream.
 // Per coordinate and sender this leaves about 9 vector instructions (split 2, butterflies 4, sign and accumulate 3)
 // where the all-vector version spends 19, and one exchange instead of two.
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float16_t __attribute__((ext_vector_type(16)));
-
-__device__ inline _Float16 hadamard_entry(uint32_t a, uint32_t b) {
-    return (__builtin_popcount(a & b) & 1) ? (_Float16)-1.0f : (_Float16)1.0f;
-}
 // x - (float)h for the fp16 in the low (HIGH = 0) or high half of `packed`: one mixed-precision fused multiply-add
 // (-1 * h + x, exact: h is x truncated to 11 bits)
 template <int HIGH>
@@ -346,8 +340,9 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             Hk[q][e] = hadamard_entry(16u * h + 8u * q + e, m);
-            Hn[q][e] = hadamard_entry(16u * q + 8u * (e >> 2) + 4u * h + (e & 3), m);
         }
+    Hn[0] = hadamard_rows_of_result(0, h, m);
+    Hn[1] = hadamard_rows_of_result(1, h, m);
 
     float sum[32];                                               // sum[16 j + u]
 #pragma unroll
@@ -374,11 +369,10 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
     uint32_t raw[4][4];
     if (c_begin < c_end) load(c_begin, raw);
     for (uint32_t c = c_begin; c < c_end; ++c) {
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
         half8_t x[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const u32x4 v = {raw[i][0], raw[i][1], raw[i][2], raw[i][3]};
+            const u32x4_t v = {raw[i][0], raw[i][1], raw[i][2], raw[i][3]};
             x[i] = __builtin_bit_cast(half8_t, v);
         }
         if (c + 1 < c_end) load(c + 1, raw);
@@ -388,7 +382,7 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
             float16_t d1 = {0};
             d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[2 * s], Hk[0], d1, 0, 0, 0);
             d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[2 * s + 1], Hk[1], d1, 0, 0, 0);
-            u32x4 hi[2], lo[2];                                  // fp16 pairs: registers 2 i, 2 i + 1 of d1
+            u32x4_t hi[2], lo[2];                                  // fp16 pairs: registers 2 i, 2 i + 1 of d1
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
                 const uint32_t top = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d1[r], d1[r + 1]));   // truncated to 11 bits

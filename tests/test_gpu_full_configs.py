@@ -78,6 +78,38 @@ def test_config4_full_size():
 
 
 @pytest.mark.timeout(600)
+@pytest.mark.parametrize("d,drop", [(9_000_001, 0.1), ((1 << 24) - 5, 0.0), (8_400_000, 0.5)])
+def test_one_bit_round_at_two_to_the_24(d, drop):
+    # every sender at b = 1 and D = 2^24: both decode passes run on the matrix cores; with and without lost packets, d just
+    # above 2^23 (few rows of the second half of the workspace are kept), near 2^24 (all of them) and in between
+    from paper_2108_08842_amd import eden
+    n = 3
+    w = synth.Workload("t", n, d, [256] * n, 515 + d % 100, "lognormal_signed")
+    D = o.padded_dim(d)
+    assert D == 1 << 24
+    print(f"b = 1 round: n={n} d={d} D=2^24 drop={drop} seed={w.seed}", flush=True)
+    xs = [synth.client_vector(w, c) for c in range(n)]
+    ids = [7, 70, 700]
+    ctx = eden.Context(d_max=d, n_max=n, device=0)
+    msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], ids, w.b_q8, w.seed)
+    omsgs = [parity.to_oracle_message(m) for m in msgs]
+    bitmaps_dev = bitmaps_np = None
+    if drop:
+        bitmaps_dev = [ctx.make_loss_bitmap(w.seed, c, D, int(drop * 2 ** 32)) for c in ids]
+        bitmaps_dev[1] = None                                   # a sender whose packets all arrived, among others
+        bitmaps_np = [None if b is None else b.cpu().numpy().view(np.uint32) for b in bitmaps_dev]
+    mean = torch.full((d,), float("nan"), device="cuda")
+    ctx.decode_mean(msgs, ids, w.b_q8, d, w.seed, mean, bitmaps_dev)
+    torch.cuda.synchronize()
+    assert ctx.last_device_status() == 0
+    want = o.decode_mean(omsgs, d, bitmaps_np)
+    err = parity.rel_l2(mean.cpu().numpy(), want)
+    print(f"decode: rel L2 {err:.2e}", flush=True)
+    assert err <= parity.MEAN_REL_L2
+    ctx.close()
+
+
+@pytest.mark.timeout(600)
 def test_every_budget_at_the_headline_size():
     """d = 11,173,962 (D = 2^24: the 10-bit workgroup tile with its two exchange halves), one sender per budget kind,
     every sender checked coordinate by coordinate against the oracle, then decoded with 10% of the packets lost."""
