@@ -778,56 +778,34 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatc
 constexpr uint32_t kFp8One = 0x38383838u, kFp8Sign = 0x80808080u;
 constexpr int kPayRow = 33;                                      // LDS stride of the staged payload words: 32 + 1
 
-template <bool LOSS>
+// TPW neighbouring tiles per workgroup, one after the other: the Hadamard operands are built once, and the payload of the
+// next tile is fetched while this one is computed.
+template <bool LOSS, int TPW>
 __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint64_t d, int log2D, float *T) {
     constexpr int p = kHixP;
     __shared__ __attribute__((aligned(16))) uint32_t out_lds[512 * 32];          // one half of the tile: 512 rows x 128 bytes
     __shared__ uint32_t pay_lds[(LOSS ? 3 : 2) * 32 * kPayRow];                  // payload word 0, word 1 (, arrived) of every row
     const uint32_t c = blockIdx.y, t = threadIdx.x, lane = t & 63u, wv = wave_in_block(), h = lane >> 5, m = lane & 31u;
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const uint32_t cb = align_runs_to_lines(xcd_local_tile(), p - 6, payload, 8u) & ((1u << (p - 6)) - 1u);
+    const uint32_t tile0 = xcd_local_tile<16 / TPW>() * TPW;
     const rsrc_t rp = make_rsrc(payload, 1u << (log2D - 3));
-
-    // ---- the tile's 8 payload bytes of every row, staged so that lane m of a wave finds row 32 m + k at k * 33 + m
     const uint32_t *bm = LOSS ? B.bitmap[c] : nullptr;
+    auto column_block = [&](uint32_t k) { return align_runs_to_lines(tile0 + k, p - 6, payload, 8u) & ((1u << (p - 6)) - 1u); };
+    // the tile's 8 payload bytes of rows t and t + 512 (and whether their packets arrived)
+    auto fetch = [&](uint32_t cb, uint32_t (&w)[2][2], uint32_t (&arrived)[2]) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const uint32_t row = t + 512u * (uint32_t)j;
-        const auto w2 = __builtin_amdgcn_raw_buffer_load_b64(rp, (int)(row << (p - 3)), (int)(cb * 8u), 0);
-        const uint32_t at = (row & 31u) * kPayRow + (row >> 5);
-        pay_lds[at] = w2[0];
-        pay_lds[32 * kPayRow + at] = w2[1];
-        if constexpr (LOSS) {
-            const uint32_t pa = (row << (p - 10)) + (cb >> 4);   // packet of 1024 coordinates that holds this row's 64
-            pay_lds[2 * 32 * kPayRow + at] = (!bm || ((bm[pa >> 5] >> (pa & 31u)) & 1u)) ? 0xFFFFFFFFu : 0u;
-        }
-    }
-    __syncthreads();
-
-    // ---- this wave's byte (columns 8 cbyte .. + 7 of word dc) of this lane's 16 rows, four rows per register
-    const uint32_t dc = wv >> 2, cbyte = wv & 3u;
-    uint32_t Gn[2][2], Z[2][2];                                  // [instruction q][rows 4 eps .. 4 eps + 3 of its eight]
-    {
-        const uint32_t sel = 0x0C0C0000u | ((4u + cbyte) << 8) | cbyte;          // byte c of the second, then of the first operand
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-#pragma unroll
-            for (int eps = 0; eps < 2; ++eps) {
-                uint32_t w[4], z[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t at = (16u * q + 8u * h + 4u * eps + e) * kPayRow + m;
-                    w[e] = pay_lds[dc * 32 * kPayRow + at];
-                    z[e] = LOSS ? pay_lds[2 * 32 * kPayRow + at] : 0u;
-                }
-                const uint32_t g01 = __builtin_amdgcn_perm(w[1], w[0], sel), g23 = __builtin_amdgcn_perm(w[3], w[2], sel);
-                Gn[q][eps] = ~__builtin_amdgcn_perm(g23, g01, 0x05040100u);       // a set payload bit is +1: sign bit clear
-                Z[q][eps] = 0xFFFFFFFFu;
-                if constexpr (LOSS)
-                    Z[q][eps] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(z[3], z[2], 0x0C0C0400u),
-                                                      __builtin_amdgcn_perm(z[1], z[0], 0x0C0C0400u), 0x05040100u);
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t row = t + 512u * (uint32_t)j;
+            const auto w2 = __builtin_amdgcn_raw_buffer_load_b64(rp, (int)(row << (p - 3)), (int)(cb * 8u), 0);
+            w[j][0] = w2[0]; w[j][1] = w2[1];
+            arrived[j] = 0xFFFFFFFFu;
+            if constexpr (LOSS) {
+                const uint32_t pa = (row << (p - 10)) + (cb >> 4);                  // packet of 1024 coordinates that holds this row's 64
+                arrived[j] = (!bm || ((bm[pa >> 5] >> (pa & 31u)) & 1u)) ? 0xFFFFFFFFu : 0u;
             }
-    }
+        }
+    };
+
     // the two Hadamard operands: step 1, B[k][k'] in fp8 with k = 16 q + 8 h + e, k' = m; step 2 as documented above
     long Hk[2];
     half8_t Hn[2];
@@ -840,27 +818,71 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
         Hk[q] = (long)bits;
         Hn[q] = hadamard_rows_of_result((uint32_t)q, h, m);
     }
-
-    // rows at or above ceil(d / 2^14) are never read by the last pass: the buffer bounds drop their stores
+    // rows at or above ceil(d / 2^14) are never read by the last pass: the buffer bounds drop their stores (leaving them out
+    // of the exchange as well would take branches that cost more registers than the kernel has)
     const uint32_t rows_used = (uint32_t)((d + (1u << p) - 1) >> p);
     const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), rows_used << (p + 1));
-    static_for<2>([&](auto PP) {
-        constexpr int P = decltype(PP)::value;                   // rows 512 P .. 512 P + 511
-        // (the second time the compiler must not see that it computes the same products again: it would keep both halves
-        // of all results of the first time in registers instead, and spill)
+    uint32_t one = kFp8One;                                      // in a vector register: shift, and-or are then two instructions
+    asm volatile("" : "+v"(one));
+    const uint32_t dc = wv >> 2, cbyte = wv & 3u;                // this wave's eight columns: byte cbyte of payload word dc
+
+    uint32_t next_w[2][2], next_arrived[2];
+    fetch(column_block(0), next_w, next_arrived);
+#pragma unroll 1
+    for (uint32_t k = 0; k < (uint32_t)TPW; ++k) {
+        const uint32_t cb = column_block(k);
+        // ---- staged so that lane m of a wave finds row 32 m + k at k * 33 + m (the last reads of the previous tile's
+        // words lie three barriers back)
 #pragma unroll
-        for (int q = 0; q < 2; ++q) { asm volatile("" : "+v"(Gn[q][0])); asm volatile("" : "+v"(Gn[q][1])); }
-        uint32_t outp[4][8];                                     // [column pair][kept result register]: two fp16
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t row = t + 512u * (uint32_t)j;
+            const uint32_t at = (row & 31u) * kPayRow + (row >> 5);
+            pay_lds[at] = next_w[j][0];
+            pay_lds[32 * kPayRow + at] = next_w[j][1];
+            if constexpr (LOSS) pay_lds[2 * 32 * kPayRow + at] = next_arrived[j];
+        }
+        __syncthreads();                                         // also: every wave has read the previous tile's second half
+        if (k + 1 < (uint32_t)TPW) fetch(column_block(k + 1), next_w, next_arrived);
+
+        // ---- this wave's byte of this lane's 16 rows, four rows per register
+        uint32_t Gn[2][2], Z[2][2];                              // [instruction q][rows 4 eps .. 4 eps + 3 of its eight]
+        {
+            const uint32_t sel = 0x0C0C0000u | ((4u + cbyte) << 8) | cbyte;      // byte c of the second, then of the first operand
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int eps = 0; eps < 2; ++eps) {
+                    uint32_t w[4], z[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t at = (16u * q + 8u * h + 4u * eps + e) * kPayRow + m;
+                        w[e] = pay_lds[dc * 32 * kPayRow + at];
+                        z[e] = LOSS ? pay_lds[2 * 32 * kPayRow + at] : 0u;
+                    }
+                    const uint32_t g01 = __builtin_amdgcn_perm(w[1], w[0], sel), g23 = __builtin_amdgcn_perm(w[3], w[2], sel);
+                    Gn[q][eps] = ~__builtin_amdgcn_perm(g23, g01, 0x05040100u);   // a set payload bit is +1: sign bit clear
+                    Z[q][eps] = 0xFFFFFFFFu;
+                    if constexpr (LOSS)
+                        Z[q][eps] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(z[3], z[2], 0x0C0C0400u),
+                                                          __builtin_amdgcn_perm(z[1], z[0], 0x0C0C0400u), 0x05040100u);
+                }
+        }
+        // ---- all eight columns once.  Of every result the half i' < 16 (rows 0 .. 511) goes to LDS at once, one dword (two
+        // columns of one row) per store; the half i' >= 16 waits in registers until the first half has left the LDS.
+        // The dword of column pair tp of row r sits at position tp ^ ((r >> 3) & 3) of its 16-byte chunk, the chunk at
+        // position chunk ^ (r & 7) of the row: the 32 lanes of a store (32 consecutive rows) then hit 32 different banks.
+        uint32_t out1[4][8];                                     // [column pair][result register 8 + rr]: two fp16
+        const uint32_t chunk_mine = 4u * dc + cbyte;
         static_for<4>([&](auto TP) {
             constexpr int tp = decltype(TP)::value;
-            float keep[8];                                       // the even column of the pair
+            float keep[16];                                      // the even column of the pair
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int col = 2 * tp + u;                      // bit of the gathered bytes
                 long a[2];
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
-                    uint32_t lo = ((Gn[q][0] << (7 - col)) & kFp8Sign) | kFp8One, hi = ((Gn[q][1] << (7 - col)) & kFp8Sign) | kFp8One;
+                    uint32_t lo = ((Gn[q][0] << (7 - col)) & kFp8Sign) | one, hi = ((Gn[q][1] << (7 - col)) & kFp8Sign) | one;
                     if constexpr (LOSS) { lo &= Z[q][0]; hi &= Z[q][1]; }
                     a[q] = (long)(((uint64_t)hi << 32) | lo);
                 }
@@ -874,37 +896,54 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
                 float16_t d2 = {0};
                 d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[0], __builtin_bit_cast(half8_t, b2[0]), d2, 0, 0, 0);
                 d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[1], __builtin_bit_cast(half8_t, b2[1]), d2, 0, 0, 0);
+                if (u == 0) {
 #pragma unroll
-                for (int rr = 0; rr < 8; ++rr) {
-                    if (u == 0) keep[rr] = d2[8 * P + rr];
-                    else outp[tp][rr] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(keep[rr], d2[8 * P + rr]));
+                    for (int r = 0; r < 16; ++r) keep[r] = d2[r];
+                } else {
+#pragma unroll
+                    for (int rr = 0; rr < 8; ++rr) {
+                        // result register rr holds i' = 8 (rr / 4) + 4 h + rr % 4: row 32 i' + m of the first half
+                        const uint32_t row = 32u * (8u * ((uint32_t)rr >> 2) + 4u * h + ((uint32_t)rr & 3u)) + m;
+                        const uint32_t at = row * 32u + ((chunk_mine ^ (m & 7u)) << 2) + ((uint32_t)tp ^ ((m >> 3) & 3u));
+                        out_lds[at] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(keep[rr], d2[rr]));
+                        out1[tp][rr] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(keep[8 + rr], d2[8 + rr]));
+                    }
                 }
-                // one column after the other: interleaving them keeps several 16-register results alive and spills; the other
-                // waves of the SIMD fill the gaps
+                // one column after the other: interleaving them keeps several 16-register results alive and spills; the
+                // other waves of the SIMD fill the gaps
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
-        if (P == 1) __syncthreads();                             // the first half has left the LDS
-        // result register 8 P + rr holds i' = 16 P + 8 (rr / 4) + 4 h + rr % 4: row 32 i' + m; this wave's eight columns are
-        // 16-byte chunk 4 dc + cbyte of the row's 128 bytes
+        __syncthreads();
+        // (stores: the whole offset in the vector register and none in the scalar one.  For a store of more than 64 bits WITH
+        // a scalar offset the compiler assumes that the data registers may be overwritten by the very next instruction; on
+        // this chip that replaced the first of the four dwords, in some lanes, when the memory pipeline was busy.)
+        {   // first half: a thread's rows 64 it + (t >> 3) all have (row >> 3) & 3 = wave & 3
+            const uint32_t s = wv & 3u;
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const uint32_t row = 64u * (uint32_t)it + (t >> 3), chunk = t & 7u;
+                const u32x4_t v = *reinterpret_cast<const u32x4_t *>(&out_lds[(row * 8u + (chunk ^ (row & 7u))) * 4u]);
+                const uint32_t a0 = (s & 1u) ? v[1] : v[0], a1 = (s & 1u) ? v[0] : v[1], a2 = (s & 1u) ? v[3] : v[2], a3 = (s & 1u) ? v[2] : v[3];
+                const u32x4_t o = {(s & 2u) ? a2 : a0, (s & 2u) ? a3 : a1, (s & 2u) ? a0 : a2, (s & 2u) ? a1 : a3};
+                __builtin_amdgcn_raw_buffer_store_b128(o, rt, (int)((row << (p + 1)) + cb * 128u + chunk * 16u), 0, kStream);
+            }
+        }
+        __syncthreads();                                         // the first half has left the LDS
 #pragma unroll
         for (int rr = 0; rr < 8; ++rr) {
             const uint32_t row = 32u * (8u * ((uint32_t)rr >> 2) + 4u * h + ((uint32_t)rr & 3u)) + m;
-            const uint32_t chunk = (4u * dc + cbyte) ^ (row & 7u);
-            const u32x4_t v = {outp[0][rr], outp[1][rr], outp[2][rr], outp[3][rr]};
-            *reinterpret_cast<u32x4_t *>(&out_lds[(row * 8u + chunk) * 4u]) = v;
+            const u32x4_t v = {out1[0][rr], out1[1][rr], out1[2][rr], out1[3][rr]};
+            *reinterpret_cast<u32x4_t *>(&out_lds[(row * 8u + (chunk_mine ^ (row & 7u))) * 4u]) = v;
         }
         __syncthreads();
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const uint32_t row = 64u * (uint32_t)it + (t >> 3), chunk = t & 7u;
             const u32x4_t v = *reinterpret_cast<const u32x4_t *>(&out_lds[(row * 8u + (chunk ^ (row & 7u))) * 4u]);
-            // (the whole offset in the vector register and none in the scalar one: for a store of more than 64 bits WITH a
-            // scalar offset the compiler assumes that the data registers may be overwritten by the very next instruction;
-            // on this chip that replaced the first of the four dwords, in some lanes, when the memory pipeline was busy)
-            __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)(((512u * P + row) << (p + 1)) + cb * 128u + chunk * 16u), 0, kStream);
+            __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)(((512u + row) << (p + 1)) + cb * 128u + chunk * 16u), 0, kStream);
         }
-    });
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -962,9 +1001,10 @@ void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
     bool all_one = all_unit && M == 10, loss = false;            // every sender b = 1 at D = 2^24: the matrix-core pass
     for (uint32_t c = 0; c < n; ++c) { all_one = all_one && B.b_q8[c] == 256u; loss = loss || B.bitmap[c] != nullptr; }
     if (all_one) {
-        dim3 grid(hix_tiles(M, log2D) / 2, n);                   // 64-column tiles
-        if (loss) hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<true>), grid, dim3(512), 0, st, B, d, log2D, T);
-        else hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<false>), grid, dim3(512), 0, st, B, d, log2D, T);
+        constexpr int TPW = 1;                                   // (two: 86 us against 77, the loop needs more registers than there are)
+        dim3 grid(hix_tiles(M, log2D) / 2 / TPW, n);             // 64-column tiles, TPW per workgroup
+        if (loss) hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<true, TPW>), grid, dim3(512), 0, st, B, d, log2D, T);
+        else hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<false, TPW>), grid, dim3(512), 0, st, B, d, log2D, T);
         return;
     }
     if (all_unit) {
