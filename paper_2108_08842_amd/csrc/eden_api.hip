@@ -555,7 +555,11 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
             bool coins = false;                                  // the receiver draws and counts the same coins
             for (uint32_t i = 0; i < nb; ++i) coins = coins || coin_q8(B.b_q8[i]);
             if (coins) launch_coin_tables(B.client, B.b_q8, nullptr, nb, seed, log2D, ctx->coin, st);
-            {
+            // header checks, arrival counts and dequantization tables: a launch of its own, unless the first pass does them
+            const DecPrepareArgs prep{hdr_d, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, flags_out + first};
+            const HiPass &top = pl.hi[pl.nhi - 1];
+            const bool first_prepares = top.wg && !coins && dec_hix_first_prepares(top.M, B, nb, narrow);
+            if (!first_prepares) {
                 Timed t(ctx, EDEN_K_DEC_PREPARE, nb, st);
                 launch_dec_prepare(B, nb, hdr_d, log2D, seed, ctx->tables, ctx->dec_scratch, ctx->dev_status, ctx->coin.total,
                                    flags_out + first, st);
@@ -566,7 +570,8 @@ static int decode_range(eden_ctx *ctx, const void *const *msgs_dev, const uint32
                 const uint64_t keep = round_up(d, h.p);
                 if (i == pl.nhi - 1) {
                     Timed t(ctx, EDEN_K_DEC_FIRST, nb, st);
-                    if (h.wg) launch_dec_hix_first(h.M, B, nb, d, log2D, seed, ctx->dec_scratch, narrow, ctx->T, ctx->coin, st);
+                    if (h.wg) launch_dec_hix_first(h.M, B, nb, d, log2D, seed, ctx->dec_scratch, narrow, ctx->T, ctx->coin,
+                                                   first_prepares ? &prep : nullptr, st);
                     else if (h.wide) launch_dec_wide_first(B, nb, keep, log2D, ctx->dec_scratch, ctx->T, st);
                     else launch_dec_hi_first(h.M, B, nb, keep, log2D, h.p, seed, ctx->dec_scratch, narrow, ctx->T, ctx->coin, st);
                 } else {

@@ -75,8 +75,20 @@ uint32_t launch_enc_hix_last(int M, int blocked, const EncBatch &B, uint32_t n, 
                              double *partials, uint32_t partial_stride, const EncScratch *scratch, const CoinTables &ct,
                              hipStream_t st);
 void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems, uint64_t store_elems, hipStream_t st);
-void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
-                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st);
+// What dec_prepare_wave needs besides the batch; a first decode pass that is given it (`prep` not null) may do the work of
+// launch_dec_prepare itself, in one of its workgroups per sender, and then returns true: the caller leaves that launch out.
+struct DecPrepareArgs {
+    uint64_t hdr_d, seed;
+    const DevTables *tab;
+    DecScratch *scratch;
+    uint32_t *dev_status;
+    uint32_t *msg_flags;                 // null or one word per sender of the batch
+};
+bool launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, const DecPrepareArgs *prep,
+                          hipStream_t st);
+// whether launch_dec_hix_first would do so for this batch
+bool dec_hix_first_prepares(int M, const DecBatch &B, uint32_t n, int narrow);
 
 // 14-bit contiguous passes for D >= 2^19 (eden_kernels_lo14.hip)
 // `blocked`: write the workspace in the blocked layout (eden_device.h: blocked_offset) that launch_enc_hix_last reads

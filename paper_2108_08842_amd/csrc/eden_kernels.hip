@@ -756,71 +756,6 @@ __global__ __launch_bounds__(256) void k_enc_finish(EncBatch B, uint64_t hdr_d, 
 // ------------------------------------------------------------------------------------------------
 // decode side
 //
-// One wave per message: check the header against what the receiver agreed on, count the coordinates
-// that arrived (Sec. 4.2: the receiver finds p by counting), and build the dequantization table
-// (S / (p sqrt(D))) * q_l  -- S/p from Sec. 4.2, D^-1/2 from the inverse rotation.
-// `hdr_d`, `hdr_b_q8`: what the header must say; `b_q8`: the budget the kernels dequantize with.
-// `extra_bits`: coin budgets only, the number of coins the receiver counted itself; the header must agree.
-__device__ inline void dec_prepare_wave(const void *msg, const uint32_t *bitmap, uint32_t client, uint32_t b_q8,
-                                        uint32_t hdr_b_q8, uint64_t hdr_d, int log2D, uint64_t seed, const DevTables *tab,
-                                        DecScratch *out, uint32_t *dev_status, uint32_t extra_bits = 0,
-                                        uint32_t *msg_flag = nullptr) {
-    const uint32_t lane = lane_id();
-    const MsgHeader h = *static_cast<const MsgHeader *>(msg);
-    uint32_t flags = 0;
-    if (h.magic != kMagic || h.log2D != (uint32_t)log2D || h.d != hdr_d || h.b_q8 != hdr_b_q8 ||
-        h.client != client || h.seed != seed || (coin_q8(b_q8) && h.extra_bits != extra_bits))
-        flags |= EDEN_DEV_HEADER_MISMATCH;
-    else
-        flags |= h.status & (EDEN_DEV_ZERO_VECTOR | EDEN_DEV_NONFINITE);
-    const uint64_t D = 1ull << log2D;
-    const uint32_t npk = D >= EDEN_PACKET_COORDS ? (uint32_t)(D / EDEN_PACKET_COORDS) : 1u;
-    uint32_t got = 0;
-    if (bitmap) {
-        const uint32_t nw = (npk + 31u) / 32u;
-        for (uint32_t w = lane; w < nw; w += 64) {
-            uint32_t bits = bitmap[w];
-            if (w == nw - 1 && (npk & 31u)) bits &= (1u << (npk & 31u)) - 1u;
-            got += __popc(bits);
-        }
-        got = wave_sum_u32(got);
-    } else {
-        got = npk;
-    }
-    int bits, k;
-    budget_of(b_q8, bits, k);
-    const uint64_t per_packet = D >= EDEN_PACKET_COORDS ? EDEN_PACKET_COORDS : D;
-    const uint64_t arrived = (uint64_t)got * per_packet / (uint64_t)k;
-    if (flags == 0 && arrived == 0) flags |= EDEN_DEV_NOTHING_ARRIVED;
-    double coef = 0.0;
-    if (flags == 0) coef = h.S * exp2(0.5 * (double)log2D) / (double)arrived;     // S / (p sqrt(D)), p = arrived / D
-    if (sparse_m(hdr_b_q8)) coef *= 64.0 / (double)sparse_m(hdr_b_q8);             // the 1/p of the sparsification (Sec. 4.1)
-    if (lane < 32) {                                             // lanes 16..31: the finer table of a mixed budget
-        const int tb = (lane < 16 || !budget_two_tables(b_q8)) ? bits : bits + 1;
-        const int H = 1 << (tb - 1), l = (int)(lane & 15u);
-        double q = 0.0;
-        if (l < 2 * H) q = (l >= H) ? tab->q[tb][l - H] : -tab->q[tb][H - 1 - l];
-        if (lane < 16) out->deq[l] = (float)(coef * q);
-        else out->deq2[l] = (float)(coef * q);
-    }
-    if (grid_q15(b_q8)) {                                        // uniform grid: the centres of mass, two per lane
-        const double delta = (double)grid_q15(b_q8) / 32768.0;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int n = (int)lane + 64 * h;
-            out->grid_deq[n] = n ? (float)(coef * grid_centroid(delta, n)) : 0.0f;
-        }
-    } else if (const uint32_t wb = wide_bits(b_q8)) {            // b = 5..8: the positive centroids, two per lane
-#pragma unroll
-        for (int h = 0; h < 2; ++h) out->grid_deq[lane + 64 * h] = (float)(coef * tab->q_big[wb - 5u][lane + 64 * h]);
-    }
-    if (lane == 0) {
-        out->flags = flags;
-        if (msg_flag) *msg_flag = flags;                         // per message, for eden_last_decode_flags
-        if (flags & (EDEN_DEV_HEADER_MISMATCH | EDEN_DEV_NOTHING_ARRIVED)) atomicOr(dev_status, flags);
-    }
-}
-
 __global__ __launch_bounds__(64) void k_dec_prepare(DecBatch B, uint64_t hdr_d, int log2D, uint64_t seed,
                                                     const DevTables *tab, DecScratch *scratch, uint32_t *dev_status,
                                                     const uint32_t *coin_total, uint32_t *msg_flags) {

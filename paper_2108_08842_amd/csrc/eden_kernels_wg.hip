@@ -780,8 +780,10 @@ constexpr int kPayRow = 33;                                      // LDS stride o
 
 // TPW neighbouring tiles per workgroup, one after the other: the Hadamard operands are built once, and the payload of the
 // next tile is fetched while this one is computed.
-template <bool LOSS, int TPW>
-__global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint64_t d, int log2D, float *T) {
+// PREP: the first workgroup of every sender also does what k_dec_prepare does for that sender (nothing in this pass
+// depends on it; the last pass, a later launch, reads it).
+template <bool LOSS, int TPW, bool PREP>
+__global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint64_t d, int log2D, float *T, DecPrepareArgs prep) {
     constexpr int p = kHixP;
     __shared__ __attribute__((aligned(16))) uint32_t out_lds[512 * 32];          // one half of the tile: 512 rows x 128 bytes
     __shared__ uint32_t pay_lds[(LOSS ? 3 : 2) * 32 * kPayRow];                  // payload word 0, word 1 (, arrived) of every row
@@ -790,6 +792,11 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
     const uint32_t tile0 = xcd_local_tile<16 / TPW>() * TPW;
     const rsrc_t rp = make_rsrc(payload, 1u << (log2D - 3));
     const uint32_t *bm = LOSS ? B.bitmap[c] : nullptr;
+    if constexpr (PREP) {
+        if (blockIdx.x == 0 && wv == 0)
+            dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], prep.hdr_d, log2D, prep.seed, prep.tab,
+                             &prep.scratch[c], prep.dev_status, 0u, prep.msg_flags ? prep.msg_flags + c : nullptr);
+    }
     auto column_block = [&](uint32_t k) { return align_runs_to_lines(tile0 + k, p - 6, payload, 8u) & ((1u << (p - 6)) - 1u); };
     // the tile's 8 payload bytes of rows t and t + 512 (and whether their packets arrived)
     auto fetch = [&](uint32_t cb, uint32_t (&w)[2][2], uint32_t (&arrived)[2]) {
@@ -994,26 +1001,37 @@ void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems,
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_hix_mid<MM, 2>), grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D,
                                           load_elems, store_elems));
 }
-void launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
-                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st) {
+bool dec_hix_first_prepares(int M, const DecBatch &B, uint32_t n, int narrow) {
+    bool all_one = narrow != 0 && M == 10;
+    for (uint32_t c = 0; c < n; ++c) all_one = all_one && B.b_q8[c] == 256u;
+    return all_one;
+}
+bool launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
+                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, const DecPrepareArgs *prep,
+                          hipStream_t st) {
     bool all_unit = narrow != 0;                                 // every sender b <= 1: packed int16 kernel
     for (uint32_t c = 0; c < n; ++c) all_unit = all_unit && B.b_q8[c] <= 256u;
-    bool all_one = all_unit && M == 10, loss = false;            // every sender b = 1 at D = 2^24: the matrix-core pass
-    for (uint32_t c = 0; c < n; ++c) { all_one = all_one && B.b_q8[c] == 256u; loss = loss || B.bitmap[c] != nullptr; }
-    if (all_one) {
+    bool loss = false;
+    for (uint32_t c = 0; c < n; ++c) loss = loss || B.bitmap[c] != nullptr;
+    if (dec_hix_first_prepares(M, B, n, narrow)) {               // every sender b = 1 at D = 2^24: the matrix-core pass
         constexpr int TPW = 1;                                   // (two: 86 us against 77, the loop needs more registers than there are)
         dim3 grid(hix_tiles(M, log2D) / 2 / TPW, n);             // 64-column tiles, TPW per workgroup
-        if (loss) hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<true, TPW>), grid, dim3(512), 0, st, B, d, log2D, T);
-        else hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<false, TPW>), grid, dim3(512), 0, st, B, d, log2D, T);
-        return;
+        const DecPrepareArgs none{};
+#define EDEN_DEC_MFMA(LOSS, PREP) \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<LOSS, TPW, PREP>), grid, dim3(512), 0, st, B, d, log2D, T, prep ? *prep : none)
+        if (loss) { if (prep) EDEN_DEC_MFMA(true, true); else EDEN_DEC_MFMA(true, false); }
+        else { if (prep) EDEN_DEC_MFMA(false, true); else EDEN_DEC_MFMA(false, false); }
+#undef EDEN_DEC_MFMA
+        return prep != nullptr;
     }
     if (all_unit) {
         dim3 grid(hix_tiles(M, log2D) / 2, n);                   // 64-column tiles
         EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first_pk<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D, seed, T));
-        return;
+        return false;
     }
     dim3 grid(hix_tiles(M, log2D), n);
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D, seed,
                                           scratch, narrow, T, ct));
+    return false;
 }
 }  // namespace eden

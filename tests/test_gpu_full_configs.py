@@ -106,6 +106,16 @@ def test_one_bit_round_at_two_to_the_24(d, drop):
     err = parity.rel_l2(mean.cpu().numpy(), want)
     print(f"decode: rel L2 {err:.2e}", flush=True)
     assert err <= parity.MEAN_REL_L2
+    assert ctx.last_decode_flags(n) == [0] * n
+    # the first pass also checks the headers and counts the arrivals here: a sender that the receiver expects under
+    # another id contributes nothing and is reported; the other two are decoded as before
+    wrong = [ids[0], ids[1] + 1, ids[2]]
+    ctx.decode_mean(msgs, wrong, w.b_q8, d, w.seed, mean, bitmaps_dev)
+    assert ctx.last_device_status() == eden.DEV_HEADER_MISMATCH
+    assert ctx.last_decode_flags(n) == [0, eden.DEV_HEADER_MISMATCH, 0]
+    want2 = (o.decode(omsgs[0], d, None if bitmaps_np is None else bitmaps_np[0]) +
+             o.decode(omsgs[2], d, None if bitmaps_np is None else bitmaps_np[2])) / n
+    assert parity.rel_l2(mean.cpu().numpy(), want2) <= parity.MEAN_REL_L2
     ctx.close()
 
 
