@@ -43,7 +43,7 @@ def kernel_bytes(kind, senders, d, D, mean_bits, narrow, fused_mean=False):
     """Algorithmic bytes one launch of a kernel kind must move (what its role reads + what it writes).
     The contiguous pass works on whole tiles of 2^12 (D <= 2^18) or 2^14 coordinates and only touches the tiles
     that hold part of the first d coordinates; the strided passes read / write the rest as implicit zeros.
-    `narrow`: the decode workspace of this workload is int16 (every sender has b <= 1 and 2^13 <= D <= 2^24).
+    `narrow`: the decode workspace of this workload is fp16 (every sender has b <= 1 and 2^13 <= D <= 2^24).
     `fused_mean`: the last decode pass stores the mean (4 d) instead of a read-modify-write of the accumulator."""
     log2D = D.bit_length() - 1
     lo = 12 if log2D <= 18 else 14

@@ -778,6 +778,28 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatc
 constexpr uint32_t kFp8One = 0x38383838u, kFp8Sign = 0x80808080u;
 constexpr int kPayRow = 33;                                      // LDS stride of the staged payload words: 32 + 1
 
+// The two Hadamard operands of the pass, per lane l = 32 h + m, built by the compiler: words 0..3 the fp8 B operand of step 1
+// (two instructions q of 8 bytes: entry e is H[k][k'] with k = 16 q + 8 h + e, k' = m), words 4..11 the fp16 A operand of
+// step 2 (two instructions of 8 halves, rows in the order hadamard_rows_of_result documents).  Loading twelve words costs a
+// lane nothing next to computing 32 parities.
+struct FirstPassOperands { uint32_t w[64][12]; };
+constexpr uint32_t parity_of(uint32_t x) { x ^= x >> 16; x ^= x >> 8; x ^= x >> 4; x ^= x >> 2; x ^= x >> 1; return x & 1u; }
+constexpr FirstPassOperands make_first_pass_operands() {
+    FirstPassOperands t{};
+    for (uint32_t l = 0; l < 64; ++l) {
+        const uint32_t h = l >> 5, m = l & 31u;
+        for (uint32_t q = 0; q < 2; ++q)
+            for (uint32_t e = 0; e < 8; ++e) {
+                const uint32_t k = 16u * q + 8u * h + e;
+                t.w[l][2 * q + (e >> 2)] |= (0x38u | (parity_of(k & m) << 7)) << (8 * (e & 3));
+                const uint32_t row = 16u * q + 8u * (e >> 2) + 4u * h + (e & 3u);
+                t.w[l][4 + 4 * q + (e >> 1)] |= (0x3C00u | (parity_of(row & m) << 15)) << (16 * (e & 1));       // fp16 +-1
+            }
+    }
+    return t;
+}
+__device__ const FirstPassOperands kFirstPassOperands = make_first_pass_operands();
+
 // TPW neighbouring tiles per workgroup, one after the other: the Hadamard operands are built once, and the payload of the
 // next tile is fetched while this one is computed.
 // PREP: the first workgroup of every sender also does what k_dec_prepare does for that sender (nothing in this pass
@@ -813,17 +835,16 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
         }
     };
 
-    // the two Hadamard operands: step 1, B[k][k'] in fp8 with k = 16 q + 8 h + e, k' = m; step 2 as documented above
+    // the two Hadamard operands (kFirstPassOperands)
     long Hk[2];
     half8_t Hn[2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        uint64_t bits = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            bits |= (uint64_t)(0x38u | ((__builtin_popcount((16u * q + 8u * h + e) & m) & 1u) << 7)) << (8 * e);
-        Hk[q] = (long)bits;
-        Hn[q] = hadamard_rows_of_result((uint32_t)q, h, m);
+    {
+        const u32x4_t *mine = reinterpret_cast<const u32x4_t *>(kFirstPassOperands.w[lane]);
+        const u32x4_t k01 = mine[0], n0 = mine[1], n1 = mine[2];
+        Hk[0] = (long)(((uint64_t)k01[1] << 32) | k01[0]);
+        Hk[1] = (long)(((uint64_t)k01[3] << 32) | k01[2]);
+        Hn[0] = __builtin_bit_cast(half8_t, n0);
+        Hn[1] = __builtin_bit_cast(half8_t, n1);
     }
     // rows at or above ceil(d / 2^14) are never read by the last pass: the buffer bounds drop their stores (leaving them out
     // of the exchange as well would take branches that cost more registers than the kernel has)
