@@ -274,7 +274,7 @@ def main():
                               "coordinates) / step time / 8 TB/s; the kernels skip the zero padding, so they move less"},
         "hbm_kernels": {"bytes_per_step": step_alg_bytes, "GBps": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                         "frac_of_peak": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                        "note": "algorithmic bytes of the kernels as built (padding tiles skipped, int16 decode "
+                        "note": "algorithmic bytes of the kernels as built (padding tiles skipped, fp16 decode "
                                 "workspace for b <= 1) / step time / 8 TB/s"},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
