@@ -946,16 +946,14 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
         // (stores: the whole offset in the vector register and none in the scalar one.  For a store of more than 64 bits WITH
         // a scalar offset the compiler assumes that the data registers may be overwritten by the very next instruction; on
         // this chip that replaced the first of the four dwords, in some lanes, when the memory pipeline was busy.)
-        {   // first half: a thread's rows 64 it + (t >> 3) all have (row >> 3) & 3 = wave & 3
-            const uint32_t s = wv & 3u;
+        // first half: a thread's row in turn `it` is 256 (it / 4) + 32 wave + 8 (it % 4) + lane / 8, so that (row >> 3) & 3,
+        // the position swizzle of the dwords, is it % 4: known when the code is compiled
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const uint32_t row = 64u * (uint32_t)it + (t >> 3), chunk = t & 7u;
-                const u32x4_t v = *reinterpret_cast<const u32x4_t *>(&out_lds[(row * 8u + (chunk ^ (row & 7u))) * 4u]);
-                const uint32_t a0 = (s & 1u) ? v[1] : v[0], a1 = (s & 1u) ? v[0] : v[1], a2 = (s & 1u) ? v[3] : v[2], a3 = (s & 1u) ? v[2] : v[3];
-                const u32x4_t o = {(s & 2u) ? a2 : a0, (s & 2u) ? a3 : a1, (s & 2u) ? a0 : a2, (s & 2u) ? a1 : a3};
-                __builtin_amdgcn_raw_buffer_store_b128(o, rt, (int)((row << (p + 1)) + cb * 128u + chunk * 16u), 0, kStream);
-            }
+        for (int it = 0; it < 8; ++it) {
+            const uint32_t row = ((uint32_t)(it >> 2) << 8) + (wv << 5) + ((uint32_t)(it & 3) << 3) + (lane >> 3), chunk = lane & 7u;
+            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(&out_lds[(row * 8u + (chunk ^ (row & 7u))) * 4u]);
+            const u32x4_t o = {v[0 ^ (it & 3)], v[1 ^ (it & 3)], v[2 ^ (it & 3)], v[3 ^ (it & 3)]};
+            __builtin_amdgcn_raw_buffer_store_b128(o, rt, (int)((row << (p + 1)) + cb * 128u + chunk * 16u), 0, kStream);
         }
         __syncthreads();                                         // the first half has left the LDS
 #pragma unroll

@@ -61,6 +61,10 @@ def test_config4_full_size():
     err = parity.rel_l2(mean16, want)
     print(f"decode of {n} senders: rel L2 {err:.2e}", flush=True)
     assert err <= parity.MEAN_REL_L2
+    # the call the benchmark times for the receiver's round: the same bits, into a buffer that held something else
+    one_call = torch.full((d,), float("nan"), device="cuda")
+    ctx.decode_mean(msgs, w.client_ids, w.b_q8, d, w.seed, one_call)
+    assert torch.equal(one_call.cpu().view(torch.int32), torch.from_numpy(mean16).view(torch.int32))
     # the same batch in two halves gives the same sums (linearity of the receiver), and the NMSE is near the
     # single-sender vNMSE over n (Lemma 2.2; Sec. 3 Example 1)
     half = torch.zeros(d, device="cuda")
