@@ -543,11 +543,11 @@ __device__ inline void or_bits(uint32_t *words, uint32_t off, uint64_t value, ui
     if (v2) atomicOr(words + w + 2, v2);
 }
 
-// Butterflies over the low LOGB bits of the register index only.
-template <int N, int LOGB>
+// Butterflies over the low LOGB bits of the register index only (FIRST = 2: all but the stage over bit 0).
+template <int N, int LOGB, int FIRST = 1>
 __device__ inline void fwht_regs_low(float (&v)[N]) {
 #pragma unroll
-    for (int h = 1; h < (1 << LOGB); h <<= 1) {
+    for (int h = FIRST; h < (1 << LOGB); h <<= 1) {
 #pragma unroll
         for (int i = 0; i < N; i += 2 * h) {
 #pragma unroll

@@ -85,7 +85,8 @@ __device__ inline void hix_exchange_write(const float (&v)[64], float *lds) {
 #pragma unroll
     for (int i = 0; i < X::RP; ++i) lds[(i * X::RL + g) * 32 + col] = v[PHASE * X::RP + i];
 }
-template <int M>
+// ALL_STAGES = false leaves out the stage over bit 0 of the register index (see hix_sign_words_pairs).
+template <int M, bool ALL_STAGES = true>
 __device__ inline void hix_exchange_read(float *lds, float (&out)[HiX<M>::RP]) {
     using X = HiX<M>;
     const uint32_t col = threadIdx.x & 31u, g = threadIdx.x >> 5;
@@ -96,7 +97,7 @@ __device__ inline void hix_exchange_read(float *lds, float (&out)[HiX<M>::RP]) {
         out[s] = lds[((g * X::RHL + e) * X::RL + rl) * 32 + col];
     }
     __syncthreads();
-    fwht_regs_low<X::RP, M - 6>(out);
+    fwht_regs_low<X::RP, M - 6, ALL_STAGES ? 1 : 2>(out);
 }
 template <int M, int PHASE>
 __device__ inline void hix_exchange(const float (&v)[64], float *lds, float (&out)[HiX<M>::RP]) {
@@ -220,6 +221,29 @@ __device__ inline void hix_sign_words(const float (&out)[HiX<M>::RP], float &ip,
     });
 }
 
+// The same from the values BEFORE the last butterfly stage (registers 2 i and 2 i + 1 hold a and b; the transformed values
+// would be a + b and a - b).  The sign quantizer needs of them only their signs and the sum of their magnitudes:
+// a + b >= 0 is "not a < -b", a - b >= 0 is "not a < b" (the same decisions: rounding never changes the sign of a sum, and
+// the passes before leave no negative zeros), and |a + b| + |a - b| = 2 max(|a|, |b|), which, unlike the two sums, is exact.
+// Four instructions per pair (max, add, two compares) instead of six.
+template <int M>
+__device__ inline void hix_sign_words_pairs(const float (&out)[HiX<M>::RP], float &ip, uint32_t (&words)[HiX<M>::RP / 32]) {
+    using X = HiX<M>;
+    float sa = 0.0f;
+#pragma unroll
+    for (int s = 0; s < X::RP; s += 2) sa += fmaxf(fabsf(out[s]), fabsf(out[s + 1]));
+    ip = fmaf(2.0f * sa, kQ1, ip);
+#pragma unroll
+    for (int w = 0; w < X::RP / 32; ++w) words[w] = 0;
+    static_for<X::RP>([&](auto S) {
+        constexpr int s = decltype(S)::value;
+        const float a = out[s & ~1], b = out[s | 1];
+        const uint64_t m = (s & 1) ? __ballot(!(a < b)) : __ballot(!(a < -b));     // index 1 = non-negative
+        words[s / 32] = put_lane<s % 32>(lo32(m), words[s / 32]);
+        words[s / 32] = put_lane<32 + s % 32>(hi32(m), words[s / 32]);
+    });
+}
+
 template <int N> struct WordVec;
 template <> struct WordVec<1> { using type = uint32_t; };
 template <> struct WordVec<2> { using type = uint2; };
@@ -302,8 +326,9 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
                 for (int r = ph * X::RP; r < (ph + 1) * X::RP; ++r)
                     v[r] = buf_load(rt, off1, next_off + row_off(r));
             }
-            hix_exchange_read<M>(lds, out);
-            if (UNIT || b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
+            hix_exchange_read<M, !UNIT>(lds, out);               // every sender b <= 1: the last stage is fused into the signs
+            if (UNIT) hix_sign_words_pairs<M>(out, ip, held[k][ph]);
+            else if (b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
             else if (byte_budget(b_q8)) {
                 // uniform grid (Sec. 4.3) or b = 5..8: one byte per coordinate; a row segment of the tile is 32 bytes
                 uint8_t *bytes = (B.codes[c] ? B.codes[c] : reinterpret_cast<uint8_t *>(payload)) + base + col;
