@@ -411,16 +411,19 @@ def test_step_can_be_captured_in_a_graph(ctx, kind):
     bitmaps = [ctx.make_loss_bitmap(w.seed, c, D, int(0.1 * 2 ** 32)) for c in ids] if kind == "every_kind" else None
     acc = torch.zeros(d, device="cuda")
     mean = torch.empty_like(acc)
+    mean_one_call = torch.empty_like(acc)
 
     def step():
         acc.zero_()
         ctx.encode(xs, ids, w.b_q8, w.seed, msgs=msgs)
         ctx.decode_accumulate(msgs, ids, w.b_q8, d, w.seed, acc, bitmaps)
         ctx.finalize_mean(acc, n, out=mean)
+        ctx.decode_mean(msgs, ids, w.b_q8, d, w.seed, mean_one_call, bitmaps)
 
     step()
     torch.cuda.synchronize()
     eager = mean.clone()
+    assert torch.equal(mean_one_call, eager)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
@@ -431,12 +434,14 @@ def test_step_can_be_captured_in_a_graph(ctx, kind):
         step()
     for _ in range(3):
         mean.fill_(7.0)
+        mean_one_call.fill_(9.0)
         for m in msgs:
             m.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(mean, eager)
+        assert torch.equal(mean_one_call, eager)
         assert float((acc * 2).sum()) == float((acc * 2).sum())      # eager work between the replays
     assert ctx.last_device_status() == 0
 
