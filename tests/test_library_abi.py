@@ -69,6 +69,22 @@ def test_message_length_from_a_header(eden):
     assert eden.message_length(bytes(64)) == 0
 
 
+def test_no_wide_buffer_store_keeps_its_offset_in_a_scalar_register(tmp_path):
+    # the build's own check (a 128-bit buffer store with a scalar offset lost its first dword under load on the MI355X):
+    # it recognises the instruction form, and the assembly the last build left has none
+    import glob
+    from paper_2108_08842_amd import build
+    sample = tmp_path / "k-hip-amdgcn-amd-amdhsa-gfx950.s"
+    sample.write_text("\tbuffer_store_dwordx4 v[6:9], v98, s[4:7], s0 offen nt\n"
+                      "\tbuffer_store_dwordx4 v[2:5], v12, s[4:7], 0 offen nt\n"
+                      "\tbuffer_store_dwordx2 v[2:3], v12, s[4:7], s1 offen\n")
+    bad = build.wide_stores_with_scalar_offset(str(tmp_path))
+    assert len(bad) == 1 and ":1:" in bad[0]
+    if not glob.glob(os.path.join(build.OBJ_DIR, "*-hip-amdgcn-amd-amdhsa-gfx950.s")):
+        pytest.skip("no device assembly from a build in this tree")
+    assert build.wide_stores_with_scalar_offset() == []
+
+
 def test_error_strings(eden):
     assert eden.strerror(0) == "ok"
     assert "argument" in eden.strerror(eden.ERR_INVALID_ARG)
