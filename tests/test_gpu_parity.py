@@ -482,6 +482,46 @@ def test_decode_mean_equals_the_three_steps(ctx, d, budgets, drop):
     assert ctx.decode_mean_raw([m.data_ptr() for m in msgs], ids, w.b_q8, d, w.seed, None, got.data_ptr() + 4) == eden.ERR_INVALID_ARG
 
 
+def test_decode_mean_on_random_shapes(ctx):
+    # 40 seeded random rounds (dimension log-uniform up to 6e6, 1..6 senders, any budget per sender, sometimes lost
+    # packets, sometimes a sparsifying budget): the one-call receiver and the three calls leave the same bits
+    from paper_2108_08842_amd import eden
+    rng = np.random.default_rng(777)
+    budgets_all = [128, 256, 384, 512, 768, 1024, 1536, 2048, eden.B_COIN(2.3), eden.B_GRID(0.4)]
+    for case in range(40):
+        d = int(2 ** rng.uniform(1.0, 22.5))
+        n = int(rng.integers(1, 7))
+        kind = rng.random()
+        if kind < 0.1:
+            budgets = [eden.B_HALF_PRE] * n
+        elif kind < 0.2:
+            budgets = [eden.B_SPARSE(int(rng.integers(1, 64)))] * n
+        elif kind < 0.5:
+            budgets = [int(b) for b in rng.choice([128, 256], n)]      # a round of at most one bit
+        else:
+            budgets = [int(b) for b in rng.choice(budgets_all, n)]
+        budgets = [b if eden.message_bytes(d, b) else 512 for b in budgets]
+        w = synth.Workload("t", n, d, budgets, 9000 + case, "lognormal_signed")
+        xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(n)]
+        ids = [int(v) for v in rng.choice(1 << 20, n, replace=False)]
+        seed = int(rng.integers(0, 2 ** 62))
+        print(f"case {case}: d={d} n={n} budgets={budgets} seed={seed}", flush=True)
+        msgs = ctx.encode(xs, ids, w.b_q8, seed)
+        bitmaps = None
+        if d >= (1 << 14) and budgets[0] < 0x10000 and rng.random() < 0.4:
+            bitmaps = [ctx.make_loss_bitmap(seed, c, o.padded_dim(d), int(0.25 * 2 ** 32)) for c in ids]
+        acc = torch.zeros(d, device="cuda")
+        ctx.decode_accumulate(msgs, ids, w.b_q8, d, seed, acc, bitmaps)
+        want = ctx.finalize_mean(acc, n, out=torch.empty_like(acc))
+        flags = ctx.last_decode_flags(n)
+        got = torch.full((d,), float("nan"), device="cuda")
+        ctx.decode_mean(msgs, ids, w.b_q8, d, seed, got, bitmaps)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int32), want.view(torch.int32))
+        assert ctx.last_decode_flags(n) == flags
+        ctx.last_device_status()                                 # a zero vector or nothing arrived is a legitimate outcome here
+
+
 def test_two_contexts_on_two_streams_and_kernel_timing(ctx):
     # one context per concurrent stream: two rounds in flight at once give the results of the same rounds run alone;
     # the optional kernel timing reports every launch of the kinds it was asked for
