@@ -455,6 +455,7 @@ def test_step_can_be_captured_in_a_graph(ctx, kind):
     (1 << 23, [1024, 256], 0),                                 # many tiles, vector pass
     (2_500_000, [0x10080, 0x10080], 0),                        # sparsification before the rotation: the three steps
     (400_000, ["sparse6", "sparse6"], 0),
+    (600_000, [256, 128, 512, 1024] * 10, 0.1),                # more senders than one launch takes: the three steps
 ])
 def test_decode_mean_equals_the_three_steps(ctx, d, budgets, drop):
     # eden_decode_mean writes what zero + eden_decode_accumulate + eden_finalize_mean leave, bit for bit, whatever the
