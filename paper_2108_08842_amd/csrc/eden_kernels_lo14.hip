@@ -285,7 +285,8 @@ __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, u
     }
 }
 
-// ---- the same pass for launches whose senders all have an fp16 workspace of small exact integers (b <= 1, D <= 2^24:
+// ---- the same pass (index bits 0..13 of H, the sign diagonal and the sum over the senders, Sec. 2.2.2) for launches whose
+// senders all have an fp16 workspace of small exact integers (b <= 1, D <= 2^24:
 // |value| <= 2^10 after at most ten strided bits), with ten of the fourteen bits on the matrix cores.
 //
 // The tile is a 16 x 32 x 32 array (u, n, k) = index bits 10..13, 5..9, 0..4.  A wave owns two values of u.  For one u:

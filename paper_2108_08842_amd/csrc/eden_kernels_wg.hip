@@ -783,7 +783,9 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first_pk(DecBatc
     }
 }
 
-// First decode pass of a b = 1 round at D = 2^24 (ten strided bits) on the matrix cores.
+// First decode pass of a b = 1 round at D = 2^24 (ten strided bits) on the matrix cores: index bits 14..23 of the H in
+// R^-1 = s o D^-1/2 H (Sec. 2.2.2) applied to the unit pattern of the payload (+-1 per coordinate, I_1 of Sec. 3; 0 where the
+// packet was lost, Sec. 4.2).  The factor S / (p sqrt(D)) q_1 waits for the last pass.
 //
 // A tile is 64 columns x 1024 rows; the input is one payload bit per element (+1 for a set bit, 0 where the packet was
 // lost).  Row rho = 32 i + k.  For ONE column the 1024 values are a 32 x 32 matrix X[i][k] and the transform is H X H:
