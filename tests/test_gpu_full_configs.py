@@ -148,6 +148,36 @@ def test_half_bit_before_the_rotation_at_two_to_the_24():
     ctx.close()
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("ms", [[56, 56], [50, 60]], ids=["same_m", "different_m"])
+def test_m_of_64_budgets_at_two_to_the_24(ms):
+    # b = m/64 at d = 1.2 x 10^7: the kept coordinates (m ceil(d/64) = 9.4 .. 11.3 million) are a 1-bit problem at D = 2^24.
+    # Senders that share m go through the workspace in one batch (the first encode pass works in place there: no blocked
+    # layout; the decode leaves every sender's vector in its slot); different m go sender by sender through the staging
+    # vector, and each of those decodes is a one-sender b = 1 round on the matrix-core passes
+    from paper_2108_08842_amd import eden
+    n, d = 2, 12_000_000
+    budgets = [eden.B_SPARSE(m) for m in ms]
+    w = synth.Workload("t", n, d, budgets, 88, "lognormal_signed")
+    print(f"m of 64: d={d} m={ms} seed={w.seed}", flush=True)
+    xs = [synth.client_vector(w, c) for c in range(n)]
+    ids = [12, 21]
+    ctx = eden.Context(d_max=d, n_max=n, device=0)
+    msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], ids, w.b_q8, w.seed)
+    assert ctx.last_device_status() == 0
+    omsgs = [parity.to_oracle_message(m) for m in msgs]
+    stats = _check_senders_threaded(xs, w.seed, ids, w.b_q8, omsgs, [1], threads=1)
+    parity.finish_encode(stats)
+    mean = torch.full((d,), float("nan"), device="cuda")
+    ctx.decode_mean(msgs, ids, w.b_q8, d, w.seed, mean)
+    torch.cuda.synchronize()
+    assert ctx.last_device_status() == 0
+    err = parity.rel_l2(mean.cpu().numpy(), o.decode_mean(omsgs, d))
+    print(f"decode: rel L2 {err:.2e}", flush=True)
+    assert err <= parity.MEAN_REL_L2
+    ctx.close()
+
+
 @pytest.mark.timeout(600)
 def test_every_budget_at_the_headline_size():
     """d = 11,173,962 (D = 2^24: the 10-bit workgroup tile with its two exchange halves), one sender per budget kind,
