@@ -179,6 +179,39 @@ def test_m_of_64_budgets_at_two_to_the_24(ms):
 
 
 @pytest.mark.timeout(600)
+def test_more_senders_than_one_launch_at_two_to_the_24():
+    # 33 senders at b = 1, D = 2^24: encode and decode go through in launches of 32 and 1; the sum equals the two parts
+    # decoded by separate calls, bit for bit, and the part of one sender is the oracle's
+    from paper_2108_08842_amd import eden
+    n, d = 33, 8_500_000
+    w = synth.Workload("t", n, d, [256] * n, 97, "normal")
+    print(f"33 senders: d={d} seed={w.seed}", flush=True)
+    ctx = eden.Context(d_max=d, n_max=n, device=0)
+    xs = [torch.from_numpy(synth.client_vector(w, c)).cuda() for c in range(n)]
+    ids = list(range(100, 100 + n))
+    msgs = ctx.encode(xs, ids, w.b_q8, w.seed)
+    assert ctx.last_device_status() == 0
+    whole = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs, ids, w.b_q8, d, w.seed, whole)
+    parts = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs[:32], ids[:32], w.b_q8[:32], d, w.seed, parts)
+    last = torch.zeros(d, device="cuda")
+    ctx.decode_accumulate(msgs[32:], ids[32:], w.b_q8[32:], d, w.seed, last)
+    parts += last
+    assert torch.equal(whole, parts)
+    one_call = torch.empty(d, device="cuda")
+    ctx.decode_mean(msgs, ids, w.b_q8, d, w.seed, one_call)
+    assert torch.equal(one_call, ctx.finalize_mean(whole.clone(), n))
+    om = parity.to_oracle_message(msgs[32])
+    st = parity.EncodeParity()
+    parity.check_encode(xs[32].cpu().numpy(), w.seed, ids[32], 256, om, st)
+    parity.finish_encode(st)
+    assert parity.rel_l2(last.cpu().numpy(), o.decode(om, d)) <= parity.MEAN_REL_L2
+    assert ctx.last_device_status() == 0
+    ctx.close()
+
+
+@pytest.mark.timeout(600)
 def test_every_budget_at_the_headline_size():
     """d = 11,173,962 (D = 2^24: the 10-bit workgroup tile with its two exchange halves), one sender per budget kind,
     every sender checked coordinate by coordinate against the oracle, then decoded with 10% of the packets lost."""
