@@ -945,72 +945,162 @@ __global__ void k_finalize_mean(const float *acc, uint64_t d, float n, float *me
     }
 }
 
-// ---- b = m/64: sparsification before the rotation with p = m/64 (Sec. 4.1).  One wave per block of 64 consecutive
-// coordinates.  Lane l holds the 16-bit key of coordinate 64 block + l (bits 16 (i & 3) .. +15 of word i >> 2 of the
-// SPARSE stream); the m smallest of the 64 (key, position) pairs are kept, and a kept coordinate's slot is
-// 64-block * m + its rank among the kept ones in position order.
-__device__ inline bool sparse_kept(uint64_t key, uint64_t block, uint32_t m, uint32_t lane, uint32_t &slot_in_block) {
-    const uint64_t i = block * 64u + lane;
-    const uint32_t k16 = (uint32_t)(hash_word(key, i >> 2) >> (16u * (uint32_t)(i & 3u))) & 0xFFFFu;
-    const uint32_t mine = (k16 << 6) | lane;                     // 22 bits, all 64 different
-    // the (m+1)-th smallest pair, bit by bit: the largest t with |{pairs < t}| <= m (a count per bit instead of a
-    // rank per lane against all 64 pairs)
-    uint32_t t = 0;
+// ---- b = m/64: sparsification before the rotation with p = m/64 (Sec. 4.1).  Of every block of 64 consecutive
+// coordinates the m with the smallest (key, position) pairs are kept, the 16-bit key of coordinate i being bits
+// 16 (i & 3) .. +15 of word i >> 2 of the SPARSE stream; a kept coordinate's slot is block * m + its rank among the
+// kept ones in position order.
+// A wave takes four blocks: lane 16 r + l holds the four pairs of coordinates 64 block_r + 4 l .. + 3 (one word of the
+// stream).  The 64 pairs of a block are sorted by a bitonic network over (lane, register): register pairs inside the
+// lane, lanes through the cross-lane swizzle; the pair of rank m is the threshold.  The pairs travel as floats in
+// [1, 2) (22 bits in the mantissa: the same order), so that one median instruction is "the smaller" (third operand 0),
+// "the larger" (4) or "whichever this lane's side of the exchange keeps".
+template <int X>
+__device__ inline float lane_xor(float v) {          // the value of lane (l ^ X), X < 32
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x001F | (X << 10)));
+}
+__device__ inline void order2(float &a, float &b) {
+    const float lo = __builtin_amdgcn_fmed3f(a, b, 0.0f), hi = __builtin_amdgcn_fmed3f(a, b, 4.0f);
+    a = lo; b = hi;
+}
+// exchange with lane l ^ X (register 3 - e instead of e when FLIP); `side` is 0 in the lane that keeps the smaller
+template <int X, bool FLIP>
+__device__ inline void exchange(float (&v)[4], float side) {
+    float p[4];
 #pragma unroll
-    for (int bit = 21; bit >= 0; --bit) {
-        const uint32_t cand = t | (1u << bit);
-        if ((uint32_t)__popcll(__ballot(mine < cand)) <= m) t = cand;
+    for (int e = 0; e < 4; ++e) p[e] = lane_xor<X>(v[FLIP ? 3 - e : e]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_fmed3f(v[e], p[e], side);
+}
+__device__ inline void order_in_lane(float (&v)[4]) {     // distances 2 and 1 of a merge
+    order2(v[0], v[2]); order2(v[1], v[3]); order2(v[0], v[1]); order2(v[2], v[3]);
+}
+template <int N> __device__ inline uint32_t row_shr(uint32_t v) {     // lane l - N of the row of 16, 0 below the row
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x110 | N, 0xF, 0xF, true);
+}
+// Bit e of the result: coordinate 64 block + 4 (lane & 15) + e is kept; slot0: the slot in the block of this lane's
+// first kept coordinate (the others follow).  Every lane of the wave must call it (cross-lane exchanges).  Block
+// numbers and coordinates fit 32 bits (d <= 2^EDEN_MAX_LOG2_D).
+__device__ inline uint32_t sparse_kept4(uint64_t key, uint32_t block, uint32_t m, uint32_t lane, uint32_t &slot0) {
+    const uint32_t l = lane & 15u;
+    const uint64_t word = hash_word(key, (uint64_t)(block * 16u + l));
+    const uint32_t half[2] = {(uint32_t)word, (uint32_t)(word >> 32)};
+    float v[4], mine[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t k16 = (e & 1) ? (half[e >> 1] >> 16) : (half[e >> 1] & 0xFFFFu);
+        v[e] = mine[e] = __uint_as_float((0x3F800000u + (uint32_t)e + 4u * l) | (k16 << 6));     // all 64 different
     }
-    const bool kept = mine < t;
-    const uint64_t mask = __ballot(kept);
-    slot_in_block = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+    float side[4];                                       // lane bit b set: the upper partner at lane distance 2^b
+#pragma unroll
+    for (int b = 0; b < 4; ++b) side[b] = ((l >> b) & 1u) ? 4.0f : 0.0f;
+    // merges of 2, 4, ..., 64: the first step of a merge pairs position g with g ^ (size - 1), the others g ^ distance
+    order2(v[0], v[1]); order2(v[2], v[3]);
+    order2(v[0], v[3]); order2(v[1], v[2]); order2(v[0], v[1]); order2(v[2], v[3]);
+    exchange<1, true>(v, side[0]); order_in_lane(v);
+    exchange<3, true>(v, side[1]); exchange<1, false>(v, side[0]); order_in_lane(v);
+    exchange<7, true>(v, side[2]); exchange<2, false>(v, side[1]); exchange<1, false>(v, side[0]); order_in_lane(v);
+    exchange<15, true>(v, side[3]); exchange<4, false>(v, side[2]); exchange<2, false>(v, side[1]);
+    exchange<1, false>(v, side[0]); order_in_lane(v);
+    // the pair of rank m (0-based) sits in register m & 3 of lane m >> 2 of the row; the m pairs below it are kept
+    const float at = (m & 2u) ? ((m & 1u) ? v[3] : v[2]) : ((m & 1u) ? v[1] : v[0]);
+    const float t = __shfl(at, (int)((lane & 48u) | (m >> 2)));
+    uint32_t kept = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) kept |= (mine[e] < t ? 1u : 0u) << e;
+    const uint32_t cnt = (uint32_t)__popc(kept);
+    uint32_t incl = cnt;
+    incl += row_shr<1>(incl); incl += row_shr<2>(incl); incl += row_shr<4>(incl); incl += row_shr<8>(incl);
+    slot0 = incl - cnt;
     return kept;
 }
+__device__ inline uint32_t sparse_block_of_lane(uint32_t lane) {
+    return ((blockIdx.x * 4u + wave_in_block()) << 2) + (lane >> 4);
+}
+// the four coordinates of a lane: one 16-byte load when `vec` (pointer aligned) and all four are below d, else 0-padded
+__device__ inline void load4_padded(const float *x, uint32_t i, uint32_t d, bool vec, float (&v)[4]) {
+    if (vec && i + 3 < d) {
+        const float4 q = *reinterpret_cast<const float4 *>(x + i);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (i + e < d) ? x[i + e] : 0.0f;
+    }
+}
 // stage[block m + slot] = x[i] for the kept coordinates (0 for a kept position beyond d)
-__global__ __launch_bounds__(256) void k_sparse_gather(const float *x, uint64_t d, uint32_t m, uint64_t key, float *stage) {
+__global__ __launch_bounds__(256) void k_sparse_gather(const float *x, uint32_t d, uint32_t m, uint64_t key, float *stage) {
     const uint32_t lane = lane_id();
-    const uint64_t block = (uint64_t)blockIdx.x * 4u + wave_in_block();
-    if (block * 64u >= d) return;
+    const uint32_t block = sparse_block_of_lane(lane);
     uint32_t slot;
-    const bool kept = sparse_kept(key, block, m, lane, slot);
-    const uint64_t i = block * 64u + lane;
-    if (kept) stage[block * m + slot] = (i < d) ? x[i] : 0.0f;
+    const uint32_t kept = sparse_kept4(key, block, m, lane, slot);
+    if (block * 64u >= d) return;
+    float v[4];
+    load4_padded(x, block * 64u + 4u * (lane & 15u), d, (reinterpret_cast<uintptr_t>(x) & 15u) == 0, v);
+    slot += block * m;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if ((kept >> e) & 1u) stage[slot++] = v[e];
 }
 // acc[i] += stage[block m + slot] for the kept coordinates below d (the factor 64/m is already in the values)
-__global__ __launch_bounds__(256) void k_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t key, float *acc) {
+__global__ __launch_bounds__(256) void k_sparse_scatter(const float *stage, uint32_t d, uint32_t m, uint64_t key, float *acc) {
     const uint32_t lane = lane_id();
-    const uint64_t block = (uint64_t)blockIdx.x * 4u + wave_in_block();
-    if (block * 64u >= d) return;
+    const uint32_t block = sparse_block_of_lane(lane);
     uint32_t slot;
-    const bool kept = sparse_kept(key, block, m, lane, slot);
-    const uint64_t i = block * 64u + lane;
-    if (kept && i < d) acc[i] += stage[block * m + slot];
+    const uint32_t kept = sparse_kept4(key, block, m, lane, slot);
+    if (block * 64u >= d) return;
+    const uint32_t i = block * 64u + 4u * (lane & 15u);
+    slot += block * m;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if ((kept >> e) & 1u) {
+            const float s = stage[slot++];
+            if (i + e < d) acc[i + e] += s;
+        }
 }
 // The same for a batch of senders that share m: sender blockIdx.y gathers into its workspace slot, and the scatter
 // adds, coordinate by coordinate, the values of all senders whose selection holds the coordinate.
-__global__ __launch_bounds__(256) void k_sparse_gather_batch(EncBatch B, uint64_t d, uint32_t m, uint64_t seed, float *T,
+__global__ __launch_bounds__(256) void k_sparse_gather_batch(EncBatch B, uint32_t d, uint32_t m, uint64_t seed, float *T,
                                                              int log2Dk) {
     const uint32_t lane = lane_id(), c = blockIdx.y;
-    const uint64_t block = (uint64_t)blockIdx.x * 4u + wave_in_block();
-    if (block * 64u >= d) return;
+    const uint32_t block = sparse_block_of_lane(lane);
     uint32_t slot;
-    const bool kept = sparse_kept(stream_key(seed, kStreamSparse, B.client[c]), block, m, lane, slot);
-    const uint64_t i = block * 64u + lane;
-    if (kept) T[((size_t)c << log2Dk) + block * m + slot] = (i < d) ? B.x[c][i] : 0.0f;
+    const uint32_t kept = sparse_kept4(stream_key(seed, kStreamSparse, B.client[c]), block, m, lane, slot);
+    if (block * 64u >= d) return;
+    const float *x = B.x[c];
+    float v[4];
+    load4_padded(x, block * 64u + 4u * (lane & 15u), d, (reinterpret_cast<uintptr_t>(x) & 15u) == 0, v);
+    float *out = T + ((size_t)c << log2Dk);
+    slot += block * m;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if ((kept >> e) & 1u) out[slot++] = v[e];
 }
-__global__ __launch_bounds__(256) void k_sparse_scatter_batch(DecBatch B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed,
+__global__ __launch_bounds__(256) void k_sparse_scatter_batch(DecBatch B, uint32_t n, uint32_t d, uint32_t m, uint64_t seed,
                                                               const float *T, int log2Dk, float *acc) {
     const uint32_t lane = lane_id();
-    const uint64_t block = (uint64_t)blockIdx.x * 4u + wave_in_block();
-    if (block * 64u >= d) return;
-    float sum = 0.0f;
+    const uint32_t block = sparse_block_of_lane(lane);
+    if ((block & ~3u) * 64u >= d) return;                // the whole wave is beyond d
+    float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const bool inside = block * 64u < d;
     for (uint32_t c = 0; c < n; ++c) {
         uint32_t slot;
-        const bool kept = sparse_kept(stream_key(seed, kStreamSparse, B.client[c]), block, m, lane, slot);
-        if (kept) sum += T[((size_t)c << log2Dk) + block * m + slot];
+        const uint32_t kept = sparse_kept4(stream_key(seed, kStreamSparse, B.client[c]), block, m, lane, slot);
+        const float *in = T + ((size_t)c << log2Dk);
+        slot += block * m;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (inside && ((kept >> e) & 1u)) sum[e] += in[slot++];
     }
-    const uint64_t i = block * 64u + lane;
-    if (i < d) acc[i] += sum;
+    if (!inside) return;
+    const uint32_t i = block * 64u + 4u * (lane & 15u);
+    if ((reinterpret_cast<uintptr_t>(acc) & 15u) == 0 && i + 3 < d) {
+        float4 a = *reinterpret_cast<float4 *>(acc + i);
+        a.x += sum[0]; a.y += sum[1]; a.z += sum[2]; a.w += sum[3];
+        *reinterpret_cast<float4 *>(acc + i) = a;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (i + e < d) acc[i + e] += sum[e];
+    }
 }
 // b = 5, 6, 7: the one-byte indices of a sender, in coordinate order, to the payload's bit string (index j in bits
 // j b .. j b + b - 1, Sec. 2.2.1 message) and back.  A thread handles 32 indices = 32 bytes = b payload words.
@@ -1469,23 +1559,23 @@ void launch_finalize_mean(const float *acc, uint64_t d, uint32_t n, float *mean,
 }
 void launch_sparse_gather(const float *x, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *stage, hipStream_t st) {
     const uint32_t blocks = (uint32_t)((d + 63) / 64);
-    hipLaunchKernelGGL(k_sparse_gather, dim3((blocks + 3) / 4), dim3(256), 0, st, x, d, m, stream_key(seed, kStreamSparse, client),
+    hipLaunchKernelGGL(k_sparse_gather, dim3((blocks + 15) / 16), dim3(256), 0, st, x, (uint32_t)d, m, stream_key(seed, kStreamSparse, client),
                        stage);
 }
 void launch_sparse_scatter(const float *stage, uint64_t d, uint32_t m, uint64_t seed, uint32_t client, float *acc, hipStream_t st) {
     const uint32_t blocks = (uint32_t)((d + 63) / 64);
-    hipLaunchKernelGGL(k_sparse_scatter, dim3((blocks + 3) / 4), dim3(256), 0, st, stage, d, m,
+    hipLaunchKernelGGL(k_sparse_scatter, dim3((blocks + 15) / 16), dim3(256), 0, st, stage, (uint32_t)d, m,
                        stream_key(seed, kStreamSparse, client), acc);
 }
 void launch_sparse_gather_batch(const EncBatch &B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed, float *T, int log2Dk,
                                 hipStream_t st) {
     const uint32_t blocks = (uint32_t)((d + 63) / 64);
-    hipLaunchKernelGGL(k_sparse_gather_batch, dim3((blocks + 3) / 4, n), dim3(256), 0, st, B, d, m, seed, T, log2Dk);
+    hipLaunchKernelGGL(k_sparse_gather_batch, dim3((blocks + 15) / 16, n), dim3(256), 0, st, B, (uint32_t)d, m, seed, T, log2Dk);
 }
 void launch_sparse_scatter_batch(const DecBatch &B, uint32_t n, uint64_t d, uint32_t m, uint64_t seed, const float *T, int log2Dk,
                                  float *acc, hipStream_t st) {
     const uint32_t blocks = (uint32_t)((d + 63) / 64);
-    hipLaunchKernelGGL(k_sparse_scatter_batch, dim3((blocks + 3) / 4), dim3(256), 0, st, B, n, d, m, seed, T, log2Dk, acc);
+    hipLaunchKernelGGL(k_sparse_scatter_batch, dim3((blocks + 15) / 16), dim3(256), 0, st, B, n, (uint32_t)d, m, seed, T, log2Dk, acc);
 }
 void launch_pack_bits(const EncBatch &B, uint32_t n, int log2D, hipStream_t st) {          // multi-pass sizes: D >= 2^13
     const uint64_t groups = (1ull << log2D) / 32;
