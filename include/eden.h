@@ -203,9 +203,10 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
  * the same numbers, bit for bit, as zeroing an accumulator, eden_decode_accumulate over the n messages and
  * eden_finalize_mean with this n.  Arguments as in eden_decode_accumulate; mean_dev (device fp32[d], 16-byte
  * aligned) is written only, whatever it held.  For rounds whose n messages are decoded by one call.  When one launch of
- * the last pass sums all senders (no budget that sparsifies before the rotation, padded dimension at least 2^19, n at
- * most 32) that pass stores the mean directly and the accumulator's three extra passes over memory (zero, read, divide)
- * do not happen; in every other case the call runs those three steps itself on mean_dev. */
+ * the last pass sums all senders (no EDEN_B_SPARSE budget, padded dimension of the transform 2^19 .. 2^24 -- up to 2^27
+ * without EDEN_B_HALF_PRE --, n at most 32) that pass stores the mean directly and the accumulator's three extra passes
+ * over memory (zero, read, divide) do not happen; in every other case the call runs those three steps itself on
+ * mean_dev. */
 int eden_decode_mean(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids,
                      const uint32_t *b_q8, uint32_t n, uint64_t d, uint64_t seed,
                      const uint32_t *const *recv_bitmaps_dev, float *mean_dev, void *stream);

@@ -620,9 +620,9 @@ int eden_decode_accumulate(eden_ctx *ctx, const void *const *msgs_dev, const uin
 }
 
 // The whole round of a receiver in one call.  When one launch of the 14-bit contiguous pass sums all the senders (no
-// sparsification before the rotation, D >= 2^19, at most kMaxBatch senders) that pass writes the mean itself: the
-// accumulator is neither zeroed, nor read, nor passed over once more for the division.  Otherwise the three steps run
-// one after the other on mean_dev.
+// sparsification before the rotation or the one by pairs, D >= 2^19, at most kMaxBatch senders) that pass writes the mean
+// itself: the accumulator is neither zeroed, nor read, nor passed over once more for the division.  Otherwise the three
+// steps run one after the other on mean_dev.
 int eden_decode_mean(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t *client_ids, const uint32_t *b_q8,
                      uint32_t n, uint64_t d, uint64_t seed, const uint32_t *const *recv_bitmaps_dev, float *mean_dev,
                      void *stream) {
@@ -635,6 +635,15 @@ int eden_decode_mean(eden_ctx *ctx, const void *const *msgs_dev, const uint32_t 
         ctx->last_decode_n = n;
         return decode_range(ctx, msgs_dev, client_ids, b_q8, b_q8, n, d, 0, d, seed, recv_bitmaps_dev, mean_dev, ctx->msg_flags, st,
                             (float)n);
+    }
+    if (mode == 1 && n <= (uint32_t)kMaxBatch) {                 // pairs before the rotation: the same with one strided pass
+        const Plan pl = make_plan(ceil_log2((d + 1) / 2), true);
+        if (pl.lo_bits == 14 && pl.nhi == 1) {
+            std::vector<uint32_t> ones(n, 256u);
+            ctx->last_decode_n = n;
+            return decode_range(ctx, msgs_dev, client_ids, ones.data(), b_q8, n, d, 1, d, seed, recv_bitmaps_dev, mean_dev,
+                                ctx->msg_flags, st, (float)n);
+        }
     }
     launch_fill_zero(mean_dev, d, st);
     if (!launch_ok()) return EDEN_ERR_HIP;

@@ -459,6 +459,120 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
     }
 }
 
+// ---- the same matrix-core pass for senders that sparsified by pairs before the rotation (EDEN_B_HALF_PRE, Sec. 4.1): the
+// decoded vector has ceil(d / 2) coordinates, and coordinate g of sender c belongs to position 2 g + o_c(g) of the output
+// (o from the sender's SUBSAMPLE stream), the other position of the pair getting nothing from this sender.  Every
+// coordinate therefore needs two sums, and a thread of the kernel above has no registers for 64: here a workgroup has 16
+// waves, wave w owns the one unit u = w in steps 1 and 2, and reads register w of all 16 units back from the exchange,
+// so that a thread holds 16 coordinates (two sums each).  Register u of thread (wave w, lane 32 h + m) is coordinate
+// 1024 u + 32 n' + m of the tile with n' = 8 (w / 4) + 4 h + w % 4: its bit of the SIGN and SUBSAMPLE streams is bit
+// 32 (w % 2) + m of word 16 u + 4 (w / 4) + 2 h + (w / 2) % 2 of the tile, and the 32 lanes m write 64 consecutive floats.
+// mean_n > 0: the output is written ((0 + sum) / mean_n) instead of added to.
+__global__ __launch_bounds__(1024) void k_dec_lo14_last_pairs(DecBatch B, uint32_t n, uint64_t d_src, int log2D, uint64_t seed,
+                                                              const float *T, const DecScratch *scratch, float *acc, float mean_n) {
+    __shared__ __attribute__((aligned(16))) float lds[1 << kLo14Bits];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wv = wave_in_block(), h = lane >> 5, m = lane & 31u;
+    const uint64_t tile_base = (uint64_t)blockIdx.x << kLo14Bits;
+
+    half8_t Hk[2], Hn[2];                                        // as in k_dec_lo14_last_mfma
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Hk[q][e] = hadamard_entry(16u * h + 8u * q + e, m);
+    Hn[0] = hadamard_rows_of_result(0, h, m);
+    Hn[1] = hadamard_rows_of_result(1, h, m);
+
+    float even[16], odd[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) even[u] = odd[u] = 0.0f;
+
+    // raw[q]: fp16 k = 16 h + 8 q .. + 7 of row n = m of unit u = wv
+    const uint32_t lane_off = (m * 32u + 16u * h) * 2u;
+    auto load = [&](uint32_t c, uint32_t (&raw)[2][4]) {
+        const rsrc_t r16 = make_rsrc(T + ((size_t)c << log2D), 2u << log2D);       // the tile lies inside the slot
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const auto x = __builtin_amdgcn_raw_buffer_load_b128(r16, (int)lane_off,
+                                                                 (int)(((uint32_t)tile_base + wv * 1024u + 8u * q) * 2u), 0);
+            raw[q][0] = x[0]; raw[q][1] = x[1]; raw[q][2] = x[2]; raw[q][3] = x[3];
+        }
+    };
+    // lane 16 hh + uu of either half of the wave hashes word (uu, hh); lane (h, m) later fetches (u, h) for every u
+    const uint32_t my_word = 16u * (lane & 15u) + 4u * (wv >> 2) + 2u * ((lane >> 4) & 1u) + ((wv >> 1) & 1u);
+    const uint32_t sh = 31u - m;
+
+    uint32_t raw[2][4];
+    load(0, raw);
+    for (uint32_t c = 0; c < n; ++c) {
+        half8_t x[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const u32x4_t v = {raw[q][0], raw[q][1], raw[q][2], raw[q][3]};
+            x[q] = __builtin_bit_cast(half8_t, v);
+        }
+        if (c + 1 < n) load(c + 1, raw);
+        if (c > 0) __syncthreads();                              // every wave has read the previous sender's values
+        {
+            float16_t d1 = {0};
+            d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[0], Hk[0], d1, 0, 0, 0);
+            d1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[1], Hk[1], d1, 0, 0, 0);
+            u32x4_t hi[2], lo[2];                                // fp16 pairs: the truncation to 11 bits and what is left
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                const uint32_t top = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d1[r], d1[r + 1]));
+                hi[r >> 3][(r & 7) >> 1] = top;
+                lo[r >> 3][(r & 7) >> 1] = __builtin_bit_cast(
+                    uint32_t, __builtin_amdgcn_cvt_pkrtz(minus_half<0>(d1[r], top), minus_half<1>(d1[r + 1], top)));
+            }
+            float16_t d2 = {0};
+            d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[0], __builtin_bit_cast(half8_t, hi[0]), d2, 0, 0, 0);
+            d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[1], __builtin_bit_cast(half8_t, hi[1]), d2, 0, 0, 0);
+            d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[0], __builtin_bit_cast(half8_t, lo[0]), d2, 0, 0, 0);
+            d2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Hn[1], __builtin_bit_cast(half8_t, lo[1]), d2, 0, 0, 0);
+            float *L = lds + wv * 1024u + lane;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) L[64 * r] = d2[r];
+        }
+        __syncthreads();
+        float v[16];
+        const float *R = lds + 64u * wv + lane;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = R[1024 * u];
+        fwht_regs<16>(v);
+        const uint32_t scale = __float_as_uint(scratch[c].deq[1]) & 0x7FFFFFFFu;     // > 0
+        const uint64_t sign_word = hash_word(stream_key(seed, kStreamSign, B.client[c]), (tile_base >> 6) + my_word);
+        const uint64_t pick_word = hash_word(stream_key(seed, kStreamSubsample, B.client[c]), (tile_base >> 6) + my_word);
+        const uint32_t sign_half = (wv & 1u) ? (uint32_t)(sign_word >> 32) : (uint32_t)sign_word;
+        const uint32_t pick_half = (wv & 1u) ? (uint32_t)(pick_word >> 32) : (uint32_t)pick_word;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int src = (int)(32u * h + 16u * h + u);        // lane 16 h + u of this half of the wave
+            const uint32_t sw = (uint32_t)__shfl((int)sign_half, src, 64);
+            const uint32_t pw = (uint32_t)__shfl((int)pick_half, src, 64);
+            // hash bit 1 -> s_i = -1: the factor is the scale with this lane's bit of the word moved to the sign position
+            const float val = v[u] * __uint_as_float(scale | ((sw << sh) & 0x80000000u));
+            const bool second = (pw << sh) & 0x80000000u;        // the pair's second position was the one sent
+            even[u] += second ? 0.0f : val;
+            odd[u] += second ? val : 0.0f;
+        }
+    }
+    const bool overwrite = mean_n > 0.0f;
+    const float div = overwrite ? mean_n : 1.0f;
+    const uint32_t nrow = 8u * (wv >> 2) + 4u * h + (wv & 3u);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const uint64_t out = 2u * (tile_base + 1024u * (uint32_t)u + 32u * nrow + m);
+        if (out + 1 < d_src) {
+            float2 a = make_float2(0.0f, 0.0f);
+            if (!overwrite) a = *reinterpret_cast<const float2 *>(acc + out);
+            a.x = (a.x + even[u]) / div; a.y = (a.y + odd[u]) / div;
+            *reinterpret_cast<float2 *>(acc + out) = a;
+        } else if (out < d_src) {
+            acc[out] = ((overwrite ? 0.0f : acc[out]) + even[u]) / div;
+        }
+    }
+}
+
 // acc[i] += partial[0][i'] + partial[1][i'] + ... for the tiles that k_dec_lo14_last split over K workgroups
 // (added one after the other, in this order); with mean_n > 0 the total is divided by it.  One thread per four coordinates.
 __global__ __launch_bounds__(256) void k_dec_lo14_combine(float *acc, uint64_t d, uint32_t full_tiles, uint32_t K,
@@ -500,8 +614,12 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     const uint64_t d = pre == 1 ? (d_src + 1) / 2 : d_src;       // dimension of the decoded vectors
     const uint32_t tiles = (uint32_t)((d + (1u << kLo14Bits) - 1) >> kLo14Bits);     // tiles that reach below d
     if (pre == 1) {
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<true>), dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T,
-                           scratch, narrow, acc, tiles, 1u, 0u, partial, 0, 0.0f);
+        if (narrow)                                              // fp16 workspace of small integers: on the matrix cores
+            hipLaunchKernelGGL(k_dec_lo14_last_pairs, dim3(tiles), dim3(1024), 0, st, B, n, d_src, log2D, seed, T, scratch, acc,
+                               mean_n);
+        else
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<true>), dim3(tiles), dim3(512), 0, st, B, n, d_src, log2D, seed, T,
+                               scratch, narrow, acc, tiles, 1u, 0u, partial, 0, 0.0f);
         return;
     }
     if (pre == 2) {                                              // every sender on its own, back into its workspace slot

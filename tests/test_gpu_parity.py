@@ -453,7 +453,9 @@ def test_step_can_be_captured_in_a_graph(ctx, kind):
     (700_000, [512, 256, 1024, 384], 0),                       # few tiles, vector pass
     (5_000_000, [256, 256, 256], 0.05),                        # many tiles, matrix-core pass, last tile ragged
     (1 << 23, [1024, 256], 0),                                 # many tiles, vector pass
-    (2_500_000, [0x10080, 0x10080], 0),                        # sparsification before the rotation: the three steps
+    (2_500_001, [0x10080, 0x10080], 0),                        # pairs before the rotation: the pair-scattering pass stores the mean
+    (1_100_000, [0x10080] * 5, 0.15),                          # the same below the workgroup-tile sizes, with loss
+    (200_001, [0x10080, 0x10080], 0),                          # 12-bit contiguous pass: the three steps
     (400_000, ["sparse6", "sparse6"], 0),
     (600_000, [256, 128, 512, 1024] * 10, 0.1),                # more senders than one launch takes: the three steps
 ])
