@@ -831,29 +831,43 @@ __device__ const FirstPassOperands kFirstPassOperands = make_first_pass_operands
 // next tile is fetched while this one is computed.
 // PREP: the first workgroup of every sender also does what k_dec_prepare does for that sender (nothing in this pass
 // depends on it; the last pass, a later launch, reads it).
-template <bool LOSS, int TPW, bool PREP>
-__global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint64_t d, int log2D, float *T, DecPrepareArgs prep) {
+// HALF: every sender of the launch has b = 1/2 with the sub-sampling after the rotation (Sec. 4.1): a row's 64 columns are
+// 32 pairs with one payload bit each, and the SUBSAMPLE stream says which member of a pair the bit belongs to; the other
+// member is 0.  The operand bytes are then sign | magnitude with the magnitude 0x40 (2.0: one bit, so that a shift and a
+// mask make it from the presence bit) or 0, and the Hadamard operand of step 2 holds +-1/2 instead of +-1.
+template <bool LOSS, int TPW, bool PREP, bool HALF>
+__global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint64_t d, int log2D, uint64_t seed, float *T,
+                                                               DecPrepareArgs prep) {
     constexpr int p = kHixP;
     __shared__ __attribute__((aligned(16))) uint32_t out_lds[512 * 32];          // one half of the tile: 512 rows x 128 bytes
     __shared__ uint32_t pay_lds[(LOSS ? 3 : 2) * 32 * kPayRow];                  // payload word 0, word 1 (, arrived) of every row
     const uint32_t c = blockIdx.y, t = threadIdx.x, lane = t & 63u, wv = wave_in_block(), h = lane >> 5, m = lane & 31u;
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(static_cast<const char *>(B.msg[c]) + EDEN_HEADER_BYTES);
     const uint32_t tile0 = xcd_local_tile<16 / TPW>() * TPW;
-    const rsrc_t rp = make_rsrc(payload, 1u << (log2D - 3));
+    const rsrc_t rp = make_rsrc(payload, 1u << (log2D - (HALF ? 4 : 3)));
     const uint32_t *bm = LOSS ? B.bitmap[c] : nullptr;
+    const uint64_t subkey = HALF ? stream_key(seed, kStreamSubsample, B.client[c]) : 0ull;
     if constexpr (PREP) {
         if (blockIdx.x == 0 && wv == 0)
             dec_prepare_wave(B.msg[c], B.bitmap[c], B.client[c], B.b_q8[c], B.hdr_b_q8[c], prep.hdr_d, log2D, prep.seed, prep.tab,
                              &prep.scratch[c], prep.dev_status, 0u, prep.msg_flags ? prep.msg_flags + c : nullptr);
     }
-    auto column_block = [&](uint32_t k) { return align_runs_to_lines(tile0 + k, p - 6, payload, 8u) & ((1u << (p - 6)) - 1u); };
-    // the tile's 8 payload bytes of rows t and t + 512 (and whether their packets arrived)
+    auto column_block = [&](uint32_t k) {
+        return align_runs_to_lines(tile0 + k, p - 6, payload, HALF ? 4u : 8u) & ((1u << (p - 6)) - 1u);
+    };
+    // the tile's 8 payload bytes of rows t and t + 512 (and whether their packets arrived); HALF: 4 payload bytes, and the
+    // tile's half of the row's word of the SUBSAMPLE stream (64 pairs per word)
     auto fetch = [&](uint32_t cb, uint32_t (&w)[2][2], uint32_t (&arrived)[2]) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const uint32_t row = t + 512u * (uint32_t)j;
-            const auto w2 = __builtin_amdgcn_raw_buffer_load_b64(rp, (int)(row << (p - 3)), (int)(cb * 8u), 0);
-            w[j][0] = w2[0]; w[j][1] = w2[1];
+            if constexpr (HALF) {
+                w[j][0] = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)(row << (p - 4)), (int)(cb * 4u), 0);
+                w[j][1] = (uint32_t)(hash_word(subkey, (((uint64_t)row << p) + cb * 64u) >> 7) >> (32u * (cb & 1u)));
+            } else {
+                const auto w2 = __builtin_amdgcn_raw_buffer_load_b64(rp, (int)(row << (p - 3)), (int)(cb * 8u), 0);
+                w[j][0] = w2[0]; w[j][1] = w2[1];
+            }
             arrived[j] = 0xFFFFFFFFu;
             if constexpr (LOSS) {
                 const uint32_t pa = (row << (p - 10)) + (cb >> 4);                  // packet of 1024 coordinates that holds this row's 64
@@ -870,8 +884,8 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
         const u32x4_t k01 = mine[0], n0 = mine[1], n1 = mine[2];
         Hk[0] = (long)(((uint64_t)k01[1] << 32) | k01[0]);
         Hk[1] = (long)(((uint64_t)k01[3] << 32) | k01[2]);
-        Hn[0] = __builtin_bit_cast(half8_t, n0);
-        Hn[1] = __builtin_bit_cast(half8_t, n1);
+        Hn[0] = __builtin_bit_cast(half8_t, HALF ? n0 - 0x04000400u : n0);       // fp16 +-1 -> +-1/2: one off the exponent
+        Hn[1] = __builtin_bit_cast(half8_t, HALF ? n1 - 0x04000400u : n1);
     }
     // rows at or above ceil(d / 2^14) are never read by the last pass: the buffer bounds drop their stores (leaving them out
     // of the exchange as well would take branches that cost more registers than the kernel has)
@@ -901,7 +915,38 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
 
         // ---- this wave's byte of this lane's 16 rows, four rows per register
         uint32_t Gn[2][2], Z[2][2];                              // [instruction q][rows 4 eps .. 4 eps + 3 of its eight]
-        {
+        uint32_t Pn[2][2];                                       // HALF: bit t of a byte = column t of that row holds a value
+        if constexpr (HALF) {
+            // this wave's eight columns are four pairs: nibble 4 dc + cbyte of the row's payload word and of its offsets
+            const uint32_t nib = 4u * dc + cbyte, bsel = nib >> 1, nsh = 4u * (nib & 1u);
+            const uint32_t sel = 0x0C0C0000u | ((4u + bsel) << 8) | bsel;
+            auto pairs_to_columns = [](uint32_t x) {             // bit g of every byte's low nibble -> bit 2 g of the byte
+                x = (x | (x << 2)) & 0x33333333u;
+                return (x | (x << 1)) & 0x55555555u;
+            };
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int eps = 0; eps < 2; ++eps) {
+                    uint32_t w[4], f[4], z[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t at = (16u * q + 8u * h + 4u * eps + e) * kPayRow + m;
+                        w[e] = pay_lds[at];
+                        f[e] = pay_lds[32 * kPayRow + at];
+                        z[e] = LOSS ? pay_lds[2 * 32 * kPayRow + at] : 0u;
+                    }
+                    const uint32_t gw = __builtin_amdgcn_perm(__builtin_amdgcn_perm(w[3], w[2], sel), __builtin_amdgcn_perm(w[1], w[0], sel), 0x05040100u);
+                    const uint32_t gf = __builtin_amdgcn_perm(__builtin_amdgcn_perm(f[3], f[2], sel), __builtin_amdgcn_perm(f[1], f[0], sel), 0x05040100u);
+                    const uint32_t bits = pairs_to_columns((gw >> nsh) & 0x0F0F0F0Fu), second = pairs_to_columns((gf >> nsh) & 0x0F0F0F0Fu);
+                    Gn[q][eps] = ~(bits | (bits << 1));          // both members carry the pair's bit; a set bit is +1: sign clear
+                    Pn[q][eps] = (second << 1) | (second ^ 0x55555555u);          // the second member where the offset bit is set
+                    Z[q][eps] = 0xFFFFFFFFu;
+                    if constexpr (LOSS)
+                        Pn[q][eps] &= __builtin_amdgcn_perm(__builtin_amdgcn_perm(z[3], z[2], 0x0C0C0400u),
+                                                            __builtin_amdgcn_perm(z[1], z[0], 0x0C0C0400u), 0x05040100u);
+                }
+        } else {
             const uint32_t sel = 0x0C0C0000u | ((4u + cbyte) << 8) | cbyte;      // byte c of the second, then of the first operand
 #pragma unroll
             for (int q = 0; q < 2; ++q)
@@ -937,8 +982,18 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
                 long a[2];
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
-                    uint32_t lo = ((Gn[q][0] << (7 - col)) & kFp8Sign) | one, hi = ((Gn[q][1] << (7 - col)) & kFp8Sign) | one;
-                    if constexpr (LOSS) { lo &= Z[q][0]; hi &= Z[q][1]; }
+                    uint32_t lo, hi;
+                    if constexpr (HALF) {
+                        constexpr uint32_t kTwo = 0x40404040u;   // fp8 2.0 where the column holds a value (and its packet arrived)
+                        const uint32_t mlo = col < 7 ? (Pn[q][0] << (6 - (col < 7 ? col : 0))) & kTwo : (Pn[q][0] >> 1) & kTwo;
+                        const uint32_t mhi = col < 7 ? (Pn[q][1] << (6 - (col < 7 ? col : 0))) & kTwo : (Pn[q][1] >> 1) & kTwo;
+                        lo = ((Gn[q][0] << (7 - col)) & kFp8Sign) | mlo;
+                        hi = ((Gn[q][1] << (7 - col)) & kFp8Sign) | mhi;
+                    } else {
+                        lo = ((Gn[q][0] << (7 - col)) & kFp8Sign) | one;
+                        hi = ((Gn[q][1] << (7 - col)) & kFp8Sign) | one;
+                        if constexpr (LOSS) { lo &= Z[q][0]; hi &= Z[q][1]; }
+                    }
                     a[q] = (long)(((uint64_t)hi << 32) | lo);
                 }
                 float16_t d1 = {0};
@@ -1047,10 +1102,10 @@ void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems,
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_hix_mid<MM, 2>), grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D,
                                           load_elems, store_elems));
 }
-bool dec_hix_first_prepares(int M, const DecBatch &B, uint32_t n, int narrow) {
-    bool all_one = narrow != 0 && M == 10;
-    for (uint32_t c = 0; c < n; ++c) all_one = all_one && B.b_q8[c] == 256u;
-    return all_one;
+bool dec_hix_first_prepares(int M, const DecBatch &B, uint32_t n, int narrow) {        // all b = 1 or all b = 1/2 at D = 2^24
+    bool all_same = narrow != 0 && M == 10 && (B.b_q8[0] == 256u || B.b_q8[0] == 128u);
+    for (uint32_t c = 1; c < n; ++c) all_same = all_same && B.b_q8[c] == B.b_q8[0];
+    return all_same;
 }
 bool launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int log2D, uint64_t seed,
                           const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, const DecPrepareArgs *prep,
@@ -1059,14 +1114,18 @@ bool launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
     for (uint32_t c = 0; c < n; ++c) all_unit = all_unit && B.b_q8[c] <= 256u;
     bool loss = false;
     for (uint32_t c = 0; c < n; ++c) loss = loss || B.bitmap[c] != nullptr;
-    if (dec_hix_first_prepares(M, B, n, narrow)) {               // every sender b = 1 at D = 2^24: the matrix-core pass
+    if (dec_hix_first_prepares(M, B, n, narrow)) {               // every sender b = 1 (or 1/2) at D = 2^24: the matrix-core pass
         constexpr int TPW = 1;                                   // (two: 86 us against 77, the loop needs more registers than there are)
         dim3 grid(hix_tiles(M, log2D) / 2 / TPW, n);             // 64-column tiles, TPW per workgroup
         const DecPrepareArgs none{};
-#define EDEN_DEC_MFMA(LOSS, PREP) \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<LOSS, TPW, PREP>), grid, dim3(512), 0, st, B, d, log2D, T, prep ? *prep : none)
-        if (loss) { if (prep) EDEN_DEC_MFMA(true, true); else EDEN_DEC_MFMA(true, false); }
-        else { if (prep) EDEN_DEC_MFMA(false, true); else EDEN_DEC_MFMA(false, false); }
+        const bool half = B.b_q8[0] == 128u;
+#define EDEN_DEC_MFMA(LOSS, PREP, HALF)                                                                                        \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<LOSS, TPW, PREP, HALF>), grid, dim3(512), 0, st, B, d, log2D, seed, T, \
+                       prep ? *prep : none)
+#define EDEN_DEC_MFMA2(LOSS, PREP) do { if (half) EDEN_DEC_MFMA(LOSS, PREP, true); else EDEN_DEC_MFMA(LOSS, PREP, false); } while (0)
+        if (loss) { if (prep) EDEN_DEC_MFMA2(true, true); else EDEN_DEC_MFMA2(true, false); }
+        else { if (prep) EDEN_DEC_MFMA2(false, true); else EDEN_DEC_MFMA2(false, false); }
+#undef EDEN_DEC_MFMA2
 #undef EDEN_DEC_MFMA
         return prep != nullptr;
     }

@@ -82,16 +82,18 @@ def test_config4_full_size():
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("d,drop", [(9_000_001, 0.1), ((1 << 24) - 5, 0.0), (8_400_000, 0.5)])
-def test_one_bit_round_at_two_to_the_24(d, drop):
-    # every sender at b = 1 and D = 2^24: both decode passes run on the matrix cores; with and without lost packets, d just
-    # above 2^23 (few rows of the second half of the workspace are kept), near 2^24 (all of them) and in between
+@pytest.mark.parametrize("d,drop,b_q8", [(9_000_001, 0.1, 256), ((1 << 24) - 5, 0.0, 256), (8_400_000, 0.5, 256),
+                                         (9_500_003, 0.1, 128), ((1 << 24) - 5, 0.0, 128)])
+def test_one_bit_round_at_two_to_the_24(d, drop, b_q8):
+    # every sender at b = 1 (or every sender at b = 1/2, sub-sampled after the rotation) and D = 2^24: both decode passes run
+    # on the matrix cores; with and without lost packets, d just above 2^23 (few rows of the second half of the workspace
+    # are kept), near 2^24 (all of them) and in between
     from paper_2108_08842_amd import eden
     n = 3
-    w = synth.Workload("t", n, d, [256] * n, 515 + d % 100, "lognormal_signed")
+    w = synth.Workload("t", n, d, [b_q8] * n, 515 + d % 100, "lognormal_signed")
     D = o.padded_dim(d)
     assert D == 1 << 24
-    print(f"b = 1 round: n={n} d={d} D=2^24 drop={drop} seed={w.seed}", flush=True)
+    print(f"b = {b_q8 / 256} round: n={n} d={d} D=2^24 drop={drop} seed={w.seed}", flush=True)
     xs = [synth.client_vector(w, c) for c in range(n)]
     ids = [7, 70, 700]
     ctx = eden.Context(d_max=d, n_max=n, device=0)
