@@ -365,9 +365,8 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
             }
     };
     // sign words of this wave's coordinates: word (u, hh) = 16 u + 4 (wv / 2) + (wv % 2) + 2 hh of the tile; lane 16 hh + u
-    // of either half of the wave hashes it, lane (h, m) later fetches (u, h) for every u
+    // of either half of the wave hashes it
     const uint32_t my_word = 16u * (lane & 15u) + 4u * (wv >> 1) + (wv & 1u) + 2u * ((lane >> 4) & 1u);
-    const uint32_t sh = 31u - m;
 
     uint32_t raw[4][4];
     if (c_begin < c_end) load(c_begin, raw);
@@ -412,16 +411,19 @@ __global__ __launch_bounds__(512, 4) void k_dec_lo14_last_mfma(DecBatch B, uint3
         const uint32_t scale = __float_as_uint(scratch[c].deq[1]) & 0x7FFFFFFFu;     // > 0
         const uint64_t key = stream_key(seed, kStreamSign, B.client[c]);
         const uint64_t mine = hash_word(key, (tile_base >> 6) + my_word);
+        const uint32_t mine_lo = (uint32_t)mine, mine_hi = (uint32_t)(mine >> 32);
+        const float pos = __uint_as_float(scale);
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
-            const int src = (int)(32u * h + 16u * h + u);        // lane 16 h + u of this half of the wave
-            const uint32_t wlo = (uint32_t)__shfl((int)(uint32_t)mine, src, 64);
-            const uint32_t whi = (uint32_t)__shfl((int)(uint32_t)(mine >> 32), src, 64);
-            // hash bit 1 -> s_i = -1: the factor is the scale with this lane's bit of the word moved to the sign position
-            const uint32_t f0 = scale | ((wlo << sh) & 0x80000000u);
-            const uint32_t f1 = scale | ((whi << sh) & 0x80000000u);
-            sum[u] = fmaf(v0[u], __uint_as_float(f0), sum[u]);
-            sum[16 + u] = fmaf(v1[u], __uint_as_float(f1), sum[16 + u]);
+            // hash bit 1 -> s_i = -1.  Lanes u and 16 + u hold the words of the two halves of the wave: their low (j = 0) or high
+            // (j = 1) halves, side by side in a scalar register pair, are the 64 sign bits of the wave's lanes, and a select
+            // driven by that pair needs no lane to fetch or shift anything
+            const uint64_t neg0 = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mine_lo, 16 + u) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readlane((int)mine_lo, u);
+            const uint64_t neg1 = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mine_hi, 16 + u) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readlane((int)mine_hi, u);
+            sum[u] = fmaf(v0[u], __builtin_amdgcn_inverse_ballot_w64(neg0) ? -pos : pos, sum[u]);
+            sum[16 + u] = fmaf(v1[u], __builtin_amdgcn_inverse_ballot_w64(neg1) ? -pos : pos, sum[16 + u]);
         }
     }
     // register (u, j): coordinate 1024 u + 32 n' + m of the tile
@@ -497,9 +499,8 @@ __global__ __launch_bounds__(1024) void k_dec_lo14_last_pairs(DecBatch B, uint32
             raw[q][0] = x[0]; raw[q][1] = x[1]; raw[q][2] = x[2]; raw[q][3] = x[3];
         }
     };
-    // lane 16 hh + uu of either half of the wave hashes word (uu, hh); lane (h, m) later fetches (u, h) for every u
+    // lane 16 hh + uu of either half of the wave hashes word (uu, hh)
     const uint32_t my_word = 16u * (lane & 15u) + 4u * (wv >> 2) + 2u * ((lane >> 4) & 1u) + ((wv >> 1) & 1u);
-    const uint32_t sh = 31u - m;
 
     uint32_t raw[2][4];
     load(0, raw);
@@ -540,20 +541,25 @@ __global__ __launch_bounds__(1024) void k_dec_lo14_last_pairs(DecBatch B, uint32
         for (int u = 0; u < 16; ++u) v[u] = R[1024 * u];
         fwht_regs<16>(v);
         const uint32_t scale = __float_as_uint(scratch[c].deq[1]) & 0x7FFFFFFFu;     // > 0
-        const uint64_t sign_word = hash_word(stream_key(seed, kStreamSign, B.client[c]), (tile_base >> 6) + my_word);
-        const uint64_t pick_word = hash_word(stream_key(seed, kStreamSubsample, B.client[c]), (tile_base >> 6) + my_word);
-        const uint32_t sign_half = (wv & 1u) ? (uint32_t)(sign_word >> 32) : (uint32_t)sign_word;
-        const uint32_t pick_half = (wv & 1u) ? (uint32_t)(pick_word >> 32) : (uint32_t)pick_word;
+        // one hash per lane serves both streams: lanes 0..31 take the words of the SIGN stream, lanes 32..63 the same words of
+        // the SUBSAMPLE stream
+        const uint64_t sign_key = stream_key(seed, kStreamSign, B.client[c]), pick_key = stream_key(seed, kStreamSubsample, B.client[c]);
+        const uint64_t word = hash_word(h ? pick_key : sign_key, (tile_base >> 6) + my_word);
+        const uint32_t half = (wv & 1u) ? (uint32_t)(word >> 32) : (uint32_t)word;
+        const float pos = __uint_as_float(scale);
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
-            const int src = (int)(32u * h + 16u * h + u);        // lane 16 h + u of this half of the wave
-            const uint32_t sw = (uint32_t)__shfl((int)sign_half, src, 64);
-            const uint32_t pw = (uint32_t)__shfl((int)pick_half, src, 64);
-            // hash bit 1 -> s_i = -1: the factor is the scale with this lane's bit of the word moved to the sign position
-            const float val = v[u] * __uint_as_float(scale | ((sw << sh) & 0x80000000u));
-            const bool second = (pw << sh) & 0x80000000u;        // the pair's second position was the one sent
-            even[u] += second ? 0.0f : val;
-            odd[u] += second ? val : 0.0f;
+            // Lanes u and 16 + u hold the SIGN words of the two halves of the wave, lanes 32 + u and 48 + u the SUBSAMPLE words:
+            // side by side in a scalar register pair they are the 64 bits of the wave's lanes, and selects driven by such a
+            // pair need no lane to fetch or shift anything.  Hash bit 1 -> s_i = -1; offset bit 1 -> the pair's second position.
+            const uint64_t neg = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)half, 16 + u) << 32) |
+                                 (uint32_t)__builtin_amdgcn_readlane((int)half, u);
+            const uint64_t second = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)half, 48 + u) << 32) |
+                                    (uint32_t)__builtin_amdgcn_readlane((int)half, 32 + u);
+            const float factor = __builtin_amdgcn_inverse_ballot_w64(neg) ? -pos : pos;
+            const bool to_second = __builtin_amdgcn_inverse_ballot_w64(second);
+            even[u] = fmaf(v[u], to_second ? 0.0f : factor, even[u]);
+            odd[u] = fmaf(v[u], to_second ? factor : 0.0f, odd[u]);
         }
     }
     const bool overwrite = mean_n > 0.0f;
