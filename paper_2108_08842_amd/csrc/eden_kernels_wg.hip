@@ -835,9 +835,15 @@ __device__ const FirstPassOperands kFirstPassOperands = make_first_pass_operands
 // 32 pairs with one payload bit each, and the SUBSAMPLE stream says which member of a pair the bit belongs to; the other
 // member is 0.  The operand bytes are then sign | magnitude with the magnitude 0x40 (2.0: one bit, so that a shift and a
 // mask make it from the presence bit) or 0, and the Hadamard operand of step 2 holds +-1/2 instead of +-1.
-template <bool LOSS, int TPW, bool PREP, bool HALF>
+// M < 10 (D = 2^22, 2^23: 256 or 512 rows): the same products with the missing rows as zeros.  Row 32 i + k belongs to A row
+// i = lane m of step 1, so lanes m >= 2^(M-5) supply zero operands (their sign mask and magnitude are 0), the results with
+// i' < 2^(M-5) are the transform over M bits, and the rest (copies of them) is not stored.  The matrix cores and the operand
+// building then work 2^(10-M) times per stored byte, which the pass has room for.
+template <bool LOSS, int TPW, bool PREP, bool HALF, int M>
 __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint64_t d, int log2D, uint64_t seed, float *T,
                                                                DecPrepareArgs prep) {
+    static_assert(M >= 8 && M <= 10, "rows of the tile");
+    constexpr uint32_t kRows = 1u << M;
     constexpr int p = kHixP;
     __shared__ __attribute__((aligned(16))) uint32_t out_lds[512 * 32];          // one half of the tile: 512 rows x 128 bytes
     __shared__ uint32_t pay_lds[(LOSS ? 3 : 2) * 32 * kPayRow];                  // payload word 0, word 1 (, arrived) of every row
@@ -871,7 +877,7 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
             arrived[j] = 0xFFFFFFFFu;
             if constexpr (LOSS) {
                 const uint32_t pa = (row << (p - 10)) + (cb >> 4);                  // packet of 1024 coordinates that holds this row's 64
-                arrived[j] = (!bm || ((bm[pa >> 5] >> (pa & 31u)) & 1u)) ? 0xFFFFFFFFu : 0u;
+                arrived[j] = (row < kRows && (!bm || ((bm[pa >> 5] >> (pa & 31u)) & 1u))) ? 0xFFFFFFFFu : 0u;
             }
         }
     };
@@ -891,8 +897,10 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
     // of the exchange as well would take branches that cost more registers than the kernel has)
     const uint32_t rows_used = (uint32_t)((d + (1u << p) - 1) >> p);
     const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), rows_used << (p + 1));
-    uint32_t one = kFp8One;                                      // in a vector register: shift, and-or are then two instructions
+    const bool row_exists = m < (kRows >> 5);                    // A row i = m of step 1 holds rows 32 m + k of the tile
+    uint32_t one = row_exists ? kFp8One : 0u;                    // in a vector register: shift, and-or are then two instructions
     asm volatile("" : "+v"(one));
+    const uint32_t sign_mask = row_exists ? kFp8Sign : 0u, two_mask = row_exists ? 0x40404040u : 0u;
     const uint32_t dc = wv >> 2, cbyte = wv & 3u;                // this wave's eight columns: byte cbyte of payload word dc
 
     uint32_t next_w[2][2], next_arrived[2];
@@ -983,15 +991,14 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     uint32_t lo, hi;
-                    if constexpr (HALF) {
-                        constexpr uint32_t kTwo = 0x40404040u;   // fp8 2.0 where the column holds a value (and its packet arrived)
-                        const uint32_t mlo = col < 7 ? (Pn[q][0] << (6 - (col < 7 ? col : 0))) & kTwo : (Pn[q][0] >> 1) & kTwo;
-                        const uint32_t mhi = col < 7 ? (Pn[q][1] << (6 - (col < 7 ? col : 0))) & kTwo : (Pn[q][1] >> 1) & kTwo;
-                        lo = ((Gn[q][0] << (7 - col)) & kFp8Sign) | mlo;
-                        hi = ((Gn[q][1] << (7 - col)) & kFp8Sign) | mhi;
+                    if constexpr (HALF) {                        // fp8 2.0 where the column holds a value (and its packet arrived)
+                        const uint32_t mlo = col < 7 ? (Pn[q][0] << (6 - (col < 7 ? col : 0))) & two_mask : (Pn[q][0] >> 1) & two_mask;
+                        const uint32_t mhi = col < 7 ? (Pn[q][1] << (6 - (col < 7 ? col : 0))) & two_mask : (Pn[q][1] >> 1) & two_mask;
+                        lo = ((Gn[q][0] << (7 - col)) & sign_mask) | mlo;
+                        hi = ((Gn[q][1] << (7 - col)) & sign_mask) | mhi;
                     } else {
-                        lo = ((Gn[q][0] << (7 - col)) & kFp8Sign) | one;
-                        hi = ((Gn[q][1] << (7 - col)) & kFp8Sign) | one;
+                        lo = ((Gn[q][0] << (7 - col)) & sign_mask) | one;
+                        hi = ((Gn[q][1] << (7 - col)) & sign_mask) | one;
                         if constexpr (LOSS) { lo &= Z[q][0]; hi &= Z[q][1]; }
                     }
                     a[q] = (long)(((uint64_t)hi << 32) | lo);
@@ -1011,12 +1018,13 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
                     for (int r = 0; r < 16; ++r) keep[r] = d2[r];
                 } else {
 #pragma unroll
-                    for (int rr = 0; rr < 8; ++rr) {
+                    for (int rr = 0; rr < (M == 8 ? 4 : 8); ++rr) {          // (M = 8: rows below 256 are i' < 8)
                         // result register rr holds i' = 8 (rr / 4) + 4 h + rr % 4: row 32 i' + m of the first half
                         const uint32_t row = 32u * (8u * ((uint32_t)rr >> 2) + 4u * h + ((uint32_t)rr & 3u)) + m;
                         const uint32_t at = row * 32u + ((chunk_mine ^ (m & 7u)) << 2) + ((uint32_t)tp ^ ((m >> 3) & 3u));
                         out_lds[at] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(keep[rr], d2[rr]));
-                        out1[tp][rr] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(keep[8 + rr], d2[8 + rr]));
+                        if constexpr (M == 10)
+                            out1[tp][rr] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(keep[8 + rr], d2[8 + rr]));
                     }
                 }
                 // one column after the other: interleaving them keeps several 16-register results alive and spills; the
@@ -1031,25 +1039,27 @@ __global__ __launch_bounds__(512, 4) void k_dec_hix_first_mfma(DecBatch B, uint6
         // first half: a thread's row in turn `it` is 256 (it / 4) + 32 wave + 8 (it % 4) + lane / 8, so that (row >> 3) & 3,
         // the position swizzle of the dwords, is it % 4: known when the code is compiled
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
+        for (int it = 0; it < (M == 8 ? 4 : 8); ++it) {
             const uint32_t row = ((uint32_t)(it >> 2) << 8) + (wv << 5) + ((uint32_t)(it & 3) << 3) + (lane >> 3), chunk = lane & 7u;
             const u32x4_t v = *reinterpret_cast<const u32x4_t *>(&out_lds[(row * 8u + (chunk ^ (row & 7u))) * 4u]);
             const u32x4_t o = {v[0 ^ (it & 3)], v[1 ^ (it & 3)], v[2 ^ (it & 3)], v[3 ^ (it & 3)]};
             __builtin_amdgcn_raw_buffer_store_b128(o, rt, (int)((row << (p + 1)) + cb * 128u + chunk * 16u), 0, kStream);
         }
-        __syncthreads();                                         // the first half has left the LDS
+        if constexpr (M == 10) {
+            __syncthreads();                                     // the first half has left the LDS
 #pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
-            const uint32_t row = 32u * (8u * ((uint32_t)rr >> 2) + 4u * h + ((uint32_t)rr & 3u)) + m;
-            const u32x4_t v = {out1[0][rr], out1[1][rr], out1[2][rr], out1[3][rr]};
-            *reinterpret_cast<u32x4_t *>(&out_lds[(row * 8u + (chunk_mine ^ (row & 7u))) * 4u]) = v;
-        }
-        __syncthreads();
+            for (int rr = 0; rr < 8; ++rr) {
+                const uint32_t row = 32u * (8u * ((uint32_t)rr >> 2) + 4u * h + ((uint32_t)rr & 3u)) + m;
+                const u32x4_t v = {out1[0][rr], out1[1][rr], out1[2][rr], out1[3][rr]};
+                *reinterpret_cast<u32x4_t *>(&out_lds[(row * 8u + (chunk_mine ^ (row & 7u))) * 4u]) = v;
+            }
+            __syncthreads();
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const uint32_t row = 64u * (uint32_t)it + (t >> 3), chunk = t & 7u;
-            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(&out_lds[(row * 8u + (chunk ^ (row & 7u))) * 4u]);
-            __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)(((512u + row) << (p + 1)) + cb * 128u + chunk * 16u), 0, kStream);
+            for (int it = 0; it < 8; ++it) {
+                const uint32_t row = 64u * (uint32_t)it + (t >> 3), chunk = t & 7u;
+                const u32x4_t v = *reinterpret_cast<const u32x4_t *>(&out_lds[(row * 8u + (chunk ^ (row & 7u))) * 4u]);
+                __builtin_amdgcn_raw_buffer_store_b128(v, rt, (int)(((512u + row) << (p + 1)) + cb * 128u + chunk * 16u), 0, kStream);
+            }
         }
     }
 }
@@ -1102,8 +1112,8 @@ void launch_hix_mid(int M, uint32_t n, float *T, int log2D, uint64_t load_elems,
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_hix_mid<MM, 2>), grid, dim3(HiX<MM>::THREADS), 0, st, T, log2D,
                                           load_elems, store_elems));
 }
-bool dec_hix_first_prepares(int M, const DecBatch &B, uint32_t n, int narrow) {        // all b = 1 or all b = 1/2 at D = 2^24
-    bool all_same = narrow != 0 && M == 10 && (B.b_q8[0] == 256u || B.b_q8[0] == 128u);
+bool dec_hix_first_prepares(int M, const DecBatch &B, uint32_t n, int narrow) {        // all b = 1 or all b = 1/2 at D = 2^22 .. 2^24
+    bool all_same = narrow != 0 && M >= 8 && (B.b_q8[0] == 256u || B.b_q8[0] == 128u);
     for (uint32_t c = 1; c < n; ++c) all_same = all_same && B.b_q8[c] == B.b_q8[0];
     return all_same;
 }
@@ -1119,14 +1129,21 @@ bool launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
         dim3 grid(hix_tiles(M, log2D) / 2 / TPW, n);             // 64-column tiles, TPW per workgroup
         const DecPrepareArgs none{};
         const bool half = B.b_q8[0] == 128u;
-#define EDEN_DEC_MFMA(LOSS, PREP, HALF)                                                                                        \
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<LOSS, TPW, PREP, HALF>), grid, dim3(512), 0, st, B, d, log2D, seed, T, \
+#define EDEN_DEC_MFMA_M(LOSS, PREP, HALF, MM)                                                                                      \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first_mfma<LOSS, TPW, PREP, HALF, MM>), grid, dim3(512), 0, st, B, d, log2D, seed, T, \
                        prep ? *prep : none)
+#define EDEN_DEC_MFMA(LOSS, PREP, HALF)                                    \
+    do {                                                                   \
+        if (M == 10) EDEN_DEC_MFMA_M(LOSS, PREP, HALF, 10);                \
+        else if (M == 9) EDEN_DEC_MFMA_M(LOSS, PREP, HALF, 9);             \
+        else EDEN_DEC_MFMA_M(LOSS, PREP, HALF, 8);                         \
+    } while (0)
 #define EDEN_DEC_MFMA2(LOSS, PREP) do { if (half) EDEN_DEC_MFMA(LOSS, PREP, true); else EDEN_DEC_MFMA(LOSS, PREP, false); } while (0)
         if (loss) { if (prep) EDEN_DEC_MFMA2(true, true); else EDEN_DEC_MFMA2(true, false); }
         else { if (prep) EDEN_DEC_MFMA2(false, true); else EDEN_DEC_MFMA2(false, false); }
 #undef EDEN_DEC_MFMA2
 #undef EDEN_DEC_MFMA
+#undef EDEN_DEC_MFMA_M
         return prep != nullptr;
     }
     if (all_unit) {

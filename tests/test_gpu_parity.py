@@ -127,6 +127,17 @@ def test_rounds_of_at_most_one_bit(ctx, d, n):
     _run_case(ctx, xs[:2], [5, 6], [256, 256], w.seed, also_oracle_msgs=(d < 2_000_000))
 
 
+@pytest.mark.parametrize("d,b_q8,drop", [(3_000_001, 256, 0.1), (2_200_000, 128, 0.0), (6_000_000, 256, 0.0),
+                                         (4_300_007, 128, 0.2), (1 << 23, 128, 0.0)])
+def test_uniform_rounds_on_the_matrix_cores_below_two_to_the_24(ctx, d, b_q8, drop):
+    # every sender at b = 1, or every sender at b = 1/2, at D = 2^22 and 2^23: the first decode pass is the matrix-core one with
+    # 256 or 512 of its 1024 rows present (a mix of the two budgets, as in the test above, takes the packed-integer pass)
+    n = 3
+    w = synth.Workload("t", n, d, [b_q8] * n, 321 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(n)]
+    _run_case(ctx, xs, [11, 12, 13], w.b_q8, w.seed, drop_q32=int(drop * 2 ** 32) if drop else None)
+
+
 @pytest.mark.parametrize("d", [5000, 70_000, 300_000])
 def test_packet_loss_and_mixed_budgets(ctx, d):
     w = synth.Workload("t", 6, d, [128, 256, 512, 1024, 768, 128], 300 + d % 1000, "lognormal")
