@@ -287,6 +287,24 @@ def main():
     }
 
     if not args.no_other_configs and args.config == 4:
+        # the same vectors under other bit budgets, a few steps each (not the headline; parity tests cover them)
+        def time_budget(name, b):
+            bq = [b] * n
+            m2 = ctx.alloc_messages(d, bq)
+
+            def step2():
+                ctx.encode(xs, w.client_ids, bq, w.seed, msgs=m2)
+                ctx.decode_mean(m2, w.client_ids, bq, d, w.seed, mean)
+
+            for _ in range(10):
+                step2()
+            ms2 = timed(step2)
+            assert ctx.last_device_status() == 0
+            return {"budget": name, "ms_per_step": round(ms2, 4)}
+
+        out["other_budgets"] = [time_budget(name, b) for name, b in (
+            ("b=1/2 (sub-sampled after the rotation)", 128), ("b=1/2 (pairs before the rotation)", eden.B_HALF_PRE),
+            ("b=6/64 (6 of every 64 before the rotation)", eden.B_SPARSE(6)), ("b=2", 512), ("b=4", 1024))]
         # the other synthetic configurations, a few steps each (not the headline; parity tests cover them)
         del xs, msgs, acc, mean, ctx
         torch.cuda.empty_cache()
