@@ -342,6 +342,38 @@ template <int N, class F>
 __device__ inline void static_for(F &&f) {                       // f(integral_constant<int, 0>) ... f(<N-1>)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
+// The value of lane (l ^ X) of the same row of 16 lanes: data-parallel primitives where one exists for the pattern, the
+// cross-lane swizzle of the LDS unit (no memory access) for X = 4.
+template <int X>
+__device__ inline uint32_t lane_xor_u32(uint32_t v) {
+    static_assert(X == 1 || X == 2 || X == 4 || X == 8, "one lane bit");
+    if constexpr (X == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);        // quad_perm [1,0,3,2]
+    else if constexpr (X == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    else if constexpr (X == 8) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, false);  // row_ror:8
+    else return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x001F | (4 << 10));
+}
+// A word holds N = 32 / BITS items of BITS bits; the N lanes that differ only in their low log2 N lane bits transpose
+// them: item i of lane j becomes item j of lane i.  One step per lane bit b: the two lanes of a pair swap the items
+// whose index differs from their own side in bit b (a rotation by the width of 2^b items brings them into place; what it
+// wraps around falls outside the mask).
+template <int BITS, int B = 0>
+__device__ inline uint32_t transpose_items(uint32_t x, uint32_t lane) {
+    constexpr int N = 32 / BITS;
+    if constexpr ((1 << B) >= N) {
+        return x;
+    } else {
+        constexpr uint32_t width = (uint32_t)BITS << B;
+        constexpr uint32_t unit = (1u << width) - 1u;
+        uint32_t keep_low = 0;                               // items whose index has bit B clear
+#pragma unroll
+        for (uint32_t pos = 0; pos < 32u; pos += 2u * width) keep_low |= unit << pos;
+        const uint32_t t = lane_xor_u32<(1 << B)>(x);
+        const bool up = (lane >> B) & 1u;
+        const uint32_t other = __builtin_amdgcn_alignbit(t, t, up ? width : 32u - width);
+        const uint32_t mask = up ? ~keep_low : keep_low;
+        return transpose_items<BITS, B + 1>((mask & x) | (~mask & other), lane);
+    }
+}
 __device__ inline uint32_t even_bits(uint32_t x) {               // bits 0,2,4,..,30 -> bits 0..15
     x &= 0x55555555u;
     x = (x | (x >> 1)) & 0x33333333u;

@@ -124,7 +124,11 @@ __device__ inline uint32_t hix_word_row(int ph, int w) {
 // second part of the payload, one bit per pair = 16 bits per row segment of a tile.  MIX = 2 (coin budgets, Sec. 4.1):
 // the coordinates with a coin use I_{BITS+1}; their top bits go to the second part (`part_c`) in coordinate order, at the
 // place the prefix sums over the coins give the row segment.
-template <int M, int BITS, int MIX>
+// TRANSPOSE (BITS = 4, MIX = 0): instead of the ballots, a lane collects the indices of eight registers (rows) of its
+// column in one word, and the lanes of eight neighbouring columns transpose their words: each then holds one payload word of
+// one row.  2 instructions per register instead of 12, but more code: only the kernel instance whose senders all have b = 4
+// uses it (in the instance shared by all budgets it raised the register spills and cost b = 2 a quarter of its speed).
+template <int M, int BITS, int MIX, bool TRANSPOSE = false>
 __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph, const EncScratch *sc, const float *qtab,
                                          uint32_t *payload, uint16_t *part_b, uint64_t mixkey, uint64_t base, float &ip,
                                          const CoinTables &ct, uint32_t c, int log2D, uint32_t *part_c) {
@@ -134,6 +138,21 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
     constexpr int NW = X::RP / 32;                               // registers come in blocks of 32 = one word lane each
     const uint32_t lane = lane_id(), col = lane & 31u;
     const uint32_t word0 = (uint32_t)(base >> 5);
+    if constexpr (TRANSPOSE) {
+        static_assert(MIX == 0 && BITS == 4, "one nibble per coordinate");
+        constexpr int PER = 32 / BITS;
+        const uint32_t g = threadIdx.x >> 5, j = col & (uint32_t)(PER - 1), q = col / (uint32_t)PER;
+        static_for<X::RP / PER>([&](auto K) {
+            constexpr int k = decltype(K)::value;
+            uint32_t items = 0;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) items |= quantize_one<H>(out[PER * k + i], sc, qtab, ip) << (BITS * i);
+            items = transpose_items<BITS>(items, lane);
+            const uint32_t row = hix_row2<M>(g, ph, (int)(PER * k + j));
+            payload[(uint32_t)BITS * (word0 + (row << (p - 5))) + q] = items;
+        });
+        return;
+    }
     uint32_t plane[BITS][NW], top[NW], offs16[NW], coin_off[NW];
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
@@ -257,6 +276,7 @@ template <> struct WordVec<4> { using type = uint4; };
 // that each half of the exchange has just written to LDS.  MODE 0: every sender of the launch has b <= 1; the
 // words of the TPW tiles are then kept and stored together (one row of a tile is only 4 bytes of payload).
 // MODE 1: any integer budget or b = 1/2.  MODE 2: also the budgets k + 1/2 (they need more registers).
+// MODE 3: every sender of the launch has b = 4 (the instance holds nothing else: no spills, and the transposing pack).
 // BLK: the first pass wrote the workspace in the blocked layout (blocked_offset in eden_device.h).
 template <int M, int TPW, int MODE, bool BLK>
 __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_last(EncBatch B, uint64_t d, int log2D, uint64_t seed,
@@ -328,7 +348,10 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
             }
             hix_exchange_read<M, !UNIT>(lds, out);               // every sender b <= 1: the last stage is fused into the signs
             if (UNIT) hix_sign_words_pairs<M>(out, ip, held[k][ph]);
-            else if (b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
+            else if (MODE == 3) {
+                hix_quantize_pack<M, 4, 0, true>(out, ph, sc, qtab, payload, reinterpret_cast<uint16_t *>(payload), mixkey, base, ip, ct,
+                                                 c, log2D, payload);
+            } else if (b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
             else if (byte_budget(b_q8)) {
                 // uniform grid (Sec. 4.3) or b = 5..8: one byte per coordinate; a row segment of the tile is 32 bytes
                 uint8_t *bytes = (B.codes[c] ? B.codes[c] : reinterpret_cast<uint8_t *>(payload)) + base + col;
@@ -366,7 +389,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
             }
         }
     }
-    if (UNIT || b_q8 <= 256u) {
+    if (UNIT || (MODE != 3 && b_q8 <= 256u)) {
         // tile0 is a multiple of TPW: the TPW words of a row are neighbours, aligned to their common size
         const uint64_t base0 = hix_base<M>(tile0, p);
         const uint32_t word0 = (uint32_t)(base0 >> 5);
@@ -1079,10 +1102,11 @@ uint32_t launch_enc_hix_last(int M, int blocked, const EncBatch &B, uint32_t n, 
                              double *partials, uint32_t partial_stride, const EncScratch *scratch, const CoinTables &ct,
                              hipStream_t st) {
     const uint32_t tiles = hix_tiles(M, log2D);                  // 512 whenever this pass sits directly on lo14
-    bool unit = true, mixed = false;                             // every sender b <= 1; some sender b = k + 1/2
+    bool unit = true, mixed = false, four = true;                // every sender b <= 1; some sender b = k + 1/2; every sender b = 4
     for (uint32_t c = 0; c < n; ++c) {
         unit = unit && B.b_q8[c] <= 256u;
         mixed = mixed || budget_two_tables(B.b_q8[c]);
+        four = four && B.b_q8[c] == 1024u;
     }
 #define EDEN_ENC_HIX_LAST(TPW, MODE)                                                                                          \
     if (blocked) {                                                                                                            \
@@ -1099,11 +1123,11 @@ uint32_t launch_enc_hix_last(int M, int blocked, const EncBatch &B, uint32_t n, 
     }
     if (M < 10 && tiles % 256u == 0) {                           // two neighbouring tiles per workgroup (M = 10 would
         dim3 grid(tiles / 2, n);                                 // need more than 128 registers: one workgroup per CU)
-        if (mixed) { EDEN_ENC_HIX_LAST(2, 2); } else { EDEN_ENC_HIX_LAST(2, 1); }
+        if (four) { EDEN_ENC_HIX_LAST(2, 3); } else if (mixed) { EDEN_ENC_HIX_LAST(2, 2); } else { EDEN_ENC_HIX_LAST(2, 1); }
         return grid.x;
     }
     dim3 grid(tiles, n);
-    if (mixed) { EDEN_ENC_HIX_LAST(1, 2); } else { EDEN_ENC_HIX_LAST(1, 1); }
+    if (four) { EDEN_ENC_HIX_LAST(1, 3); } else if (mixed) { EDEN_ENC_HIX_LAST(1, 2); } else { EDEN_ENC_HIX_LAST(1, 1); }
 #undef EDEN_ENC_HIX_LAST
     return grid.x;
 }

@@ -126,6 +126,31 @@ def test_one_bit_round_at_two_to_the_24(d, drop, b_q8):
 
 
 @pytest.mark.timeout(600)
+def test_four_bit_round_at_two_to_the_24():
+    # every sender at b = 4 and D = 2^24: the strided encode pass is the instance that holds only this budget (indices packed
+    # by a transpose across lanes), one tile per workgroup
+    from paper_2108_08842_amd import eden
+    n, d = 2, 9_000_000
+    w = synth.Workload("t", n, d, [1024] * n, 4024, "lognormal_signed")
+    print(f"b = 4 round: n={n} d={d} D=2^24 seed={w.seed}", flush=True)
+    xs = [synth.client_vector(w, c) for c in range(n)]
+    ids = [31, 32]
+    ctx = eden.Context(d_max=d, n_max=n, device=0)
+    msgs = ctx.encode([torch.from_numpy(x).cuda() for x in xs], ids, w.b_q8, w.seed)
+    omsgs = [parity.to_oracle_message(m) for m in msgs]
+    stats = _check_senders_threaded(xs, w.seed, ids, w.b_q8, omsgs, [0, 1], threads=2)
+    parity.finish_encode(stats)
+    mean = torch.full((d,), float("nan"), device="cuda")
+    ctx.decode_mean(msgs, ids, w.b_q8, d, w.seed, mean)
+    torch.cuda.synchronize()
+    assert ctx.last_device_status() == 0
+    err = parity.rel_l2(mean.cpu().numpy(), o.decode_mean(omsgs, d))
+    print(f"decode: rel L2 {err:.2e}", flush=True)
+    assert err <= parity.MEAN_REL_L2
+    ctx.close()
+
+
+@pytest.mark.timeout(600)
 def test_half_bit_before_the_rotation_at_two_to_the_24():
     # b = 1/2 with the sparsification first (Sec. 4.1) at d = 2 x 10^7: the transformed vector has 10^7 + 1 coordinates, so
     # the 1-bit path runs at D = 2^24 and the receiver's first pass is the matrix-core one; the last pass scatters the pairs

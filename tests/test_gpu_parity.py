@@ -138,6 +138,16 @@ def test_uniform_rounds_on_the_matrix_cores_below_two_to_the_24(ctx, d, b_q8, dr
     _run_case(ctx, xs, [11, 12, 13], w.b_q8, w.seed, drop_q32=int(drop * 2 ** 32) if drop else None)
 
 
+@pytest.mark.parametrize("d", [(1 << 21) - 3, 3_000_001, 5_000_001])
+def test_rounds_of_four_bits_on_workgroup_tiles(ctx, d):
+    # every sender at b = 4 and D = 2^21 .. 2^23 (2^24: test_gpu_full_configs.py): the strided encode pass is the instance that holds only this budget (its
+    # indices are packed by a transpose across lanes instead of ballots)
+    n = 2
+    w = synth.Workload("t", n, d, [1024] * n, 4000 + d % 1000, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(n)]
+    _run_case(ctx, xs, [31, 32], w.b_q8, w.seed, drop_q32=int(0.1 * 2 ** 32) if d < 4_000_000 else 0, also_oracle_msgs=False)
+
+
 @pytest.mark.parametrize("d", [5000, 70_000, 300_000])
 def test_packet_loss_and_mixed_budgets(ctx, d):
     w = synth.Workload("t", 6, d, [128, 256, 512, 1024, 768, 128], 300 + d % 1000, "lognormal")
