@@ -324,6 +324,49 @@ __device__ inline uint32_t quantize_one(float u, const EncScratch *sc, const flo
     return neg ? (uint32_t)(H - 1) - mag : (uint32_t)H + mag;
 }
 
+// The same search through a table, for kernels that spend their time on it (H = 8: fourteen instructions above).  |u| is
+// cut into kRankCells cells of equal width, the last threshold falling into the last but one; a cell holds at most one
+// threshold (the Lloyd-Max thresholds of up to 16 levels lie at least six cells apart), so the rank is the number of
+// thresholds in lower cells plus one compare.  The result is the one of magnitude_rank for every input: the cell number is a
+// monotone function of |u| (a rounded product, clamped and truncated), hence a value in a higher cell than a threshold is above
+// it and one in a lower cell is below it, and inside the threshold's own cell the compare decides as it does there.  |x| = 0:
+// `inv` is 0, every value is 0 and lands in cell 0, whose threshold is 0: rank 0.
+constexpr int kRankCells = 64;
+struct RankCell {
+    float thr;              // the threshold inside the cell, +inf if there is none
+    float q_below, q_above; // centroids of the rank without and with that threshold passed
+    uint32_t below;         // thresholds in lower cells
+};
+__device__ inline uint32_t rank_cell_of(float a, float inv) { return (uint32_t)fminf(a * inv, (float)(kRankCells - 1)); }
+__device__ inline float rank_cell_scale(const EncScratch *sc, int H) {
+    const float last = sc->thr[H - 1];
+    return last > 0.0f ? (float)(kRankCells - 2) / last : 0.0f;
+}
+template <int H>
+__device__ inline void fill_rank_table(RankCell *cells, const EncScratch *sc, uint32_t thread, float inv) {
+    if (thread >= (uint32_t)kRankCells) return;
+    RankCell e{__builtin_inff(), 0.0f, 0.0f, 0u};
+#pragma unroll
+    for (int t = 1; t < H; ++t) {
+        const uint32_t cell = rank_cell_of(sc->thr[t], inv);
+        e.below += cell < thread ? 1u : 0u;
+        if (cell == thread) e.thr = sc->thr[t];
+    }
+    e.q_below = sc->qpos[e.below];
+    e.q_above = sc->qpos[e.below + 1u < (uint32_t)H ? e.below + 1u : (uint32_t)H - 1u];
+    cells[thread] = e;
+}
+template <int H>
+__device__ inline uint32_t quantize_one_table(float u, const RankCell *cells, float inv, float &ip) {
+    const float a = fabsf(u);
+    const RankCell e = cells[rank_cell_of(a, inv)];
+    const bool above = a > e.thr;
+    const uint32_t mag = e.below + (above ? 1u : 0u);
+    ip = fmaf(a, above ? e.q_above : e.q_below, ip);
+    const uint32_t neg = (uint32_t)((int)__float_as_uint(u) >> 31);      // all ones for a negative value
+    return (mag ^ neg) + (uint32_t)H;                                    // H + mag, or H - 1 - mag
+}
+
 // ---- collecting ballots in lanes, and bit interleaving for the packed payload
 __device__ inline uint32_t lo32(uint64_t x) { return (uint32_t)x; }
 __device__ inline uint32_t hi32(uint64_t x) { return (uint32_t)(x >> 32); }

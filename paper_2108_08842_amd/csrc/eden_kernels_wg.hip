@@ -131,7 +131,8 @@ __device__ inline uint32_t hix_word_row(int ph, int w) {
 template <int M, int BITS, int MIX, bool TRANSPOSE = false>
 __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph, const EncScratch *sc, const float *qtab,
                                          uint32_t *payload, uint16_t *part_b, uint64_t mixkey, uint64_t base, float &ip,
-                                         const CoinTables &ct, uint32_t c, int log2D, uint32_t *part_c) {
+                                         const CoinTables &ct, uint32_t c, int log2D, uint32_t *part_c,
+                                         const RankCell *cells = nullptr, float cell_scale = 0.0f) {
     using X = HiX<M>;
     constexpr int p = kHixP;
     constexpr int H = 1 << (BITS - 1);
@@ -146,7 +147,7 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
             constexpr int k = decltype(K)::value;
             uint32_t items = 0;
 #pragma unroll
-            for (int i = 0; i < PER; ++i) items |= quantize_one<H>(out[PER * k + i], sc, qtab, ip) << (BITS * i);
+            for (int i = 0; i < PER; ++i) items |= quantize_one_table<H>(out[PER * k + i], cells, cell_scale, ip) << (BITS * i);
             items = transpose_items<BITS>(items, lane);
             const uint32_t row = hix_row2<M>(g, ph, (int)(PER * k + j));
             payload[(uint32_t)BITS * (word0 + (row << (p - 5))) + q] = items;
@@ -288,6 +289,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
     __shared__ double red[X::THREADS / 64];
     __shared__ float qtab[16];                                   // centroids; published by the first barrier of the exchange
     __shared__ float gtab[256];                                  // one-byte budgets: centroids and thresholds
+    __shared__ RankCell cells[MODE == 3 ? kRankCells : 1];       // b = 4 alone: the interval search by table
     constexpr int p = kHixP;
     constexpr int NW = X::RP / 32;
     constexpr bool UNIT = MODE == 0;
@@ -316,6 +318,11 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
         return BLK ? tile << (7 + kBlockRowBits) : (uint32_t)hix_base<M>(tile, p) * 4u;
     };
     const uint64_t mixkey = stream_key(seed, kStreamMix, B.client[c]);
+    float cell_scale = 0.0f;
+    if constexpr (MODE == 3) {
+        cell_scale = rank_cell_scale(sc, 8);
+        fill_rank_table<8>(cells, sc, threadIdx.x, cell_scale);  // published, like qtab, by the first barrier of the exchange
+    }
     if (!UNIT) {
         fill_qtab(qtab, sc, threadIdx.x);
         if (byte_budget(b_q8)) {                                 // centroids, then thresholds: one run of 256 floats
@@ -350,7 +357,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
             if (UNIT) hix_sign_words_pairs<M>(out, ip, held[k][ph]);
             else if (MODE == 3) {
                 hix_quantize_pack<M, 4, 0, true>(out, ph, sc, qtab, payload, reinterpret_cast<uint16_t *>(payload), mixkey, base, ip, ct,
-                                                 c, log2D, payload);
+                                                 c, log2D, payload, cells, cell_scale);
             } else if (b_q8 <= 256u) hix_sign_words<M>(out, ip, held[k][ph]);
             else if (byte_budget(b_q8)) {
                 // uniform grid (Sec. 4.3) or b = 5..8: one byte per coordinate; a row segment of the tile is 32 bytes
@@ -1121,11 +1128,8 @@ uint32_t launch_enc_hix_last(int M, int blocked, const EncBatch &B, uint32_t n, 
         EDEN_ENC_HIX_LAST(2, 0);
         return grid.x;
     }
-    if (M < 10 && tiles % 256u == 0) {                           // two neighbouring tiles per workgroup (M = 10 would
-        dim3 grid(tiles / 2, n);                                 // need more than 128 registers: one workgroup per CU)
-        if (four) { EDEN_ENC_HIX_LAST(2, 3); } else if (mixed) { EDEN_ENC_HIX_LAST(2, 2); } else { EDEN_ENC_HIX_LAST(2, 1); }
-        return grid.x;
-    }
+    // every other launch: one tile per workgroup (with the blocked workspace two tiles per workgroup are slower at every size:
+    // 16 senders at D = 2^23, 0.151 -> 0.142 ms at b = 2, 0.34 -> 0.18 ms at b = 1.5, 0.255 -> 0.144 ms for the b = 4 instance)
     dim3 grid(tiles, n);
     if (four) { EDEN_ENC_HIX_LAST(1, 3); } else if (mixed) { EDEN_ENC_HIX_LAST(1, 2); } else { EDEN_ENC_HIX_LAST(1, 1); }
 #undef EDEN_ENC_HIX_LAST
