@@ -946,3 +946,16 @@ def test_wide_integer_budgets_through_the_path(b_q8):
     th, c = o.tables(bits)
     v = o.vnmse_single(x, xh)
     assert abs(v - (1 / o.expected_q2(th, c) - 1) * d / 4096) < 0.2 * (1 / o.expected_q2(th, c) - 1)
+
+
+def test_positive_thresholds_of_sixteen_levels_lie_several_search_cells_apart():
+    # the library's b = 4 encoder finds the interval of |z| through 64 equal cells over [0, t_max * 63 / 62) and assumes at
+    # most one threshold per cell (csrc/eden_device.h, RankCell): the Lloyd-Max thresholds of 16 levels (Sec. 3) are at
+    # least six cells apart, zero included, and scaling all of them by |x| / sqrt(D) changes nothing in that
+    thr, _ = o.tables(4)
+    pos = np.concatenate([[0.0], thr[thr > 0]])
+    assert pos.size == 8
+    cell = pos[-1] / 62.0
+    assert np.min(np.diff(pos)) > 6.0 * cell
+    cells = np.floor(pos[1:] / cell).astype(int)
+    assert len(set(cells.tolist())) == 7 and cells[-1] == 62
