@@ -156,7 +156,8 @@ __device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *s
 // ballot of one index bit is 64 payload bits of that row; lane r collects the ballots of row r and packs them.
 // Workspace elements at or above `valid_elems` were not written by the earlier passes because they are
 // zero (transformed zero padding): the buffer bounds return 0 for them.
-template <int M>
+// ONLY != 0: every sender of the launch has this budget (2 or 4 bits); the instance then holds that one branch.
+template <int M, uint32_t ONLY = 0>
 __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_elems, int log2D, int p, uint64_t seed,
                                                      const float *T, double *partials, uint32_t partial_stride,
                                                      const EncScratch *scratch, CoinTables ct) {
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_
         for (int r = 0; r < R; ++r) v[r] = buf_load(rt, lane_off, base_off + ((uint32_t)r << (p + 2)));
         fwht_regs<R>(v);
         uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-        const uint32_t b_q8 = B.b_q8[c];
+        const uint32_t b_q8 = ONLY ? ONLY : B.b_q8[c];
         const uint64_t my_row = base + ((uint64_t)(lane & (R - 1)) << p);       // lane r < R finishes row r
         if (b_q8 <= 256u) {
             // I_1 = {(-inf,0],[0,inf)}: the index is the sign; <R(x),Q> = q_1 sum |u| / sqrt(D)
@@ -287,7 +288,9 @@ __global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *part
 // bounds drop their stores.
 // (Five waves per SIMD are requested: the budgets with two loads per value would otherwise set the register count
 // for all of them; measured 0.057 against 0.073 ms on 32 senders at D = 2^20.)
-template <int M>
+// ONLY != 0: every sender of the launch has this budget (2 or 4 bits, indices in the payload); the instance then holds that
+// one branch (the shared one spills 304 bytes at its 96 registers).
+template <int M, uint32_t ONLY = 0>
 __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                                                       const DecScratch *scratch, int narrow, float *T, CoinTables ct) {
     constexpr int R = 1 << M;
@@ -300,7 +303,7 @@ __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t ke
     if (tile >= ntiles) return;
     uint64_t base;
     hi_tile_origin<M>(tile, p, base);
-    const uint32_t b_q8 = B.b_q8[c];
+    const uint32_t b_q8 = ONLY ? ONLY : B.b_q8[c];
     const bool i16 = narrow && b_q8 <= 256u;
     if (lane < 16) table[wv][lane] = (i16 && lane == 1) ? 1.0f : scratch[c].deq[lane];
     else if (lane < 32) table[wv][lane] = scratch[c].deq2[lane - 16];
@@ -1487,8 +1490,15 @@ uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid
                             const CoinTables &ct, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
-    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_enc_hi_last<MM>, grid, dim3(256), 0, st, B, valid_elems, log2D, p, seed, T, partials,
-                                         partial_stride, scratch, ct));
+    bool all2 = M >= 5, all4 = M >= 5;                           // one budget for all (two-pass sizes): its own instance
+    for (uint32_t c = 0; c < n; ++c) { all2 = all2 && B.b_q8[c] == 512u; all4 = all4 && B.b_q8[c] == 1024u; }
+#define EDEN_ENC_HI_LAST(MM, ONLY)                                                                                            \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hi_last<MM, ONLY>), grid, dim3(256), 0, st, B, valid_elems, log2D, p, seed, T, partials, \
+                       partial_stride, scratch, ct)
+    if (all2) { if (M == 5) EDEN_ENC_HI_LAST(5, 512u); else EDEN_ENC_HI_LAST(6, 512u); }
+    else if (all4) { if (M == 5) EDEN_ENC_HI_LAST(5, 1024u); else EDEN_ENC_HI_LAST(6, 1024u); }
+    else EDEN_HI_SWITCH(M, EDEN_ENC_HI_LAST(MM, 0u));
+#undef EDEN_ENC_HI_LAST
     return grid.x;
 }
 uint32_t launch_enc_wide_last(const EncBatch &B, uint32_t n, uint64_t valid_elems, int log2D, const float *T, double *partials,
@@ -1529,8 +1539,18 @@ void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_ele
                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
-    EDEN_HI_SWITCH(M, hipLaunchKernelGGL(k_dec_hi_first<MM>, grid, dim3(256), 0, st, B, keep_elems, log2D, p, seed, scratch, narrow,
-                                         T, ct));
+    bool all2 = M >= 5, all4 = M >= 5;                           // one budget for all (two-pass sizes): its own instance
+    for (uint32_t c = 0; c < n; ++c) {
+        all2 = all2 && B.b_q8[c] == 512u && !B.codes[c];
+        all4 = all4 && B.b_q8[c] == 1024u && !B.codes[c];
+    }
+#define EDEN_DEC_HI_FIRST(MM, ONLY)                                                                                           \
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hi_first<MM, ONLY>), grid, dim3(256), 0, st, B, keep_elems, log2D, p, seed, scratch, \
+                       narrow, T, ct)
+    if (all2) { if (M == 5) EDEN_DEC_HI_FIRST(5, 512u); else EDEN_DEC_HI_FIRST(6, 512u); }
+    else if (all4) { if (M == 5) EDEN_DEC_HI_FIRST(5, 1024u); else EDEN_DEC_HI_FIRST(6, 1024u); }
+    else EDEN_HI_SWITCH(M, EDEN_DEC_HI_FIRST(MM, 0u));
+#undef EDEN_DEC_HI_FIRST
 }
 uint32_t launch_enc_lo_first(const EncBatch &B, uint32_t n, uint64_t d_src, int pre, int log2D, uint64_t seed, float *T,
                              double *partials, uint32_t partial_stride, hipStream_t st) {

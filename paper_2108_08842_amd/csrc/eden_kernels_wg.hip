@@ -490,7 +490,9 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D
 // First decode pass (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit pattern when the
 // workspace is fp16), zero for coordinates that were not sampled or whose packet was lost, then index bits
 // 14 .. 14+M-1 of H.
-template <int M>
+// ONLY != 0: every sender of the launch has this budget (2 or 4 bits, indices in the payload): the instance then holds that
+// one branch, which takes it from 128 registers and spills to 97 (16 senders at D = 2^24: 0.180 -> 0.160 ms).
+template <int M, uint32_t ONLY = 0>
 __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                     const DecScratch *scratch, int narrow, float *T,
                                                                     CoinTables ct) {
@@ -500,7 +502,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B
     __shared__ float table[32];
     __shared__ float gtab[kGridMax + 1];                         // uniform grid: dequantized centres of mass
     const uint32_t c = blockIdx.y;
-    const uint32_t b_q8 = B.b_q8[c];
+    const uint32_t b_q8 = ONLY ? ONLY : B.b_q8[c];
     uint32_t tile = xcd_local_tile();
     {   // payload bytes of one tile row: 4 per index bit; the budgets with a power of two (2, 4, 8 bits) get aligned runs
         int tb, tk;
@@ -1180,8 +1182,16 @@ bool launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
         return false;
     }
     dim3 grid(hix_tiles(M, log2D), n);
-    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(k_dec_hix_first<MM>, grid, dim3(HiX<MM>::THREADS), 0, st, B, d, log2D, seed,
-                                          scratch, narrow, T, ct));
+    bool all2 = true, all4 = true;                               // one budget for all: the instance that holds nothing else
+    for (uint32_t c = 0; c < n; ++c) {
+        all2 = all2 && B.b_q8[c] == 512u && !B.codes[c];
+        all4 = all4 && B.b_q8[c] == 1024u && !B.codes[c];
+    }
+#define EDEN_DEC_HIX_FIRST(ONLY)                                                                                              \
+    EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first<MM, ONLY>), grid, dim3(HiX<MM>::THREADS), 0, st, B, d, \
+                                          log2D, seed, scratch, narrow, T, ct))
+    if (all2) { EDEN_DEC_HIX_FIRST(512u); } else if (all4) { EDEN_DEC_HIX_FIRST(1024u); } else { EDEN_DEC_HIX_FIRST(0u); }
+#undef EDEN_DEC_HIX_FIRST
     return false;
 }
 }  // namespace eden
