@@ -156,7 +156,7 @@ __device__ inline void hi_quantize_pack(const float (&v)[R], const EncScratch *s
 // ballot of one index bit is 64 payload bits of that row; lane r collects the ballots of row r and packs them.
 // Workspace elements at or above `valid_elems` were not written by the earlier passes because they are
 // zero (transformed zero padding): the buffer bounds return 0 for them.
-// ONLY != 0: every sender of the launch has this budget (2 or 4 bits); the instance then holds that one branch.
+// ONLY != 0: every sender of the launch has this budget (1, 2 or 4 bits); the instance then holds that one branch.
 template <int M, uint32_t ONLY = 0>
 __global__ __launch_bounds__(256) void k_enc_hi_last(EncBatch B, uint64_t valid_elems, int log2D, int p, uint64_t seed,
                                                      const float *T, double *partials, uint32_t partial_stride,
@@ -288,8 +288,8 @@ __global__ __launch_bounds__(256) void k_enc_norm(EncBatch B, const double *part
 // bounds drop their stores.
 // (Five waves per SIMD are requested: the budgets with two loads per value would otherwise set the register count
 // for all of them; measured 0.057 against 0.073 ms on 32 senders at D = 2^20.)
-// ONLY != 0: every sender of the launch has this budget (2 or 4 bits, indices in the payload); the instance then holds that
-// one branch (the shared one spills 304 bytes at its 96 registers).
+// ONLY != 0: every sender of the launch has this budget (1, 2 or 4 bits, indices in the payload); the instance then holds
+// that one branch (the shared one spills 304 bytes at its 96 registers).
 template <int M, uint32_t ONLY = 0>
 __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                                                       const DecScratch *scratch, int narrow, float *T, CoinTables ct) {
@@ -1490,12 +1490,17 @@ uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid
                             const CoinTables &ct, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
-    bool all2 = M >= 5, all4 = M >= 5;                           // one budget for all (two-pass sizes): its own instance
-    for (uint32_t c = 0; c < n; ++c) { all2 = all2 && B.b_q8[c] == 512u; all4 = all4 && B.b_q8[c] == 1024u; }
+    bool all1 = M >= 5, all2 = M >= 5, all4 = M >= 5;            // one budget for all (two-pass sizes): its own instance
+    for (uint32_t c = 0; c < n; ++c) {
+        all1 = all1 && B.b_q8[c] == 256u;
+        all2 = all2 && B.b_q8[c] == 512u;
+        all4 = all4 && B.b_q8[c] == 1024u;
+    }
 #define EDEN_ENC_HI_LAST(MM, ONLY)                                                                                            \
     hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hi_last<MM, ONLY>), grid, dim3(256), 0, st, B, valid_elems, log2D, p, seed, T, partials, \
                        partial_stride, scratch, ct)
-    if (all2) { if (M == 5) EDEN_ENC_HI_LAST(5, 512u); else EDEN_ENC_HI_LAST(6, 512u); }
+    if (all1) { if (M == 5) EDEN_ENC_HI_LAST(5, 256u); else EDEN_ENC_HI_LAST(6, 256u); }
+    else if (all2) { if (M == 5) EDEN_ENC_HI_LAST(5, 512u); else EDEN_ENC_HI_LAST(6, 512u); }
     else if (all4) { if (M == 5) EDEN_ENC_HI_LAST(5, 1024u); else EDEN_ENC_HI_LAST(6, 1024u); }
     else EDEN_HI_SWITCH(M, EDEN_ENC_HI_LAST(MM, 0u));
 #undef EDEN_ENC_HI_LAST
@@ -1539,15 +1544,17 @@ void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_ele
                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st) {
     const uint32_t ntiles = 1u << (log2D - 6 - M);
     dim3 grid((ntiles + 3) / 4, n);
-    bool all2 = M >= 5, all4 = M >= 5;                           // one budget for all (two-pass sizes): its own instance
+    bool all1 = M >= 5, all2 = M >= 5, all4 = M >= 5;            // one budget for all (two-pass sizes): its own instance
     for (uint32_t c = 0; c < n; ++c) {
+        all1 = all1 && B.b_q8[c] == 256u;
         all2 = all2 && B.b_q8[c] == 512u && !B.codes[c];
         all4 = all4 && B.b_q8[c] == 1024u && !B.codes[c];
     }
 #define EDEN_DEC_HI_FIRST(MM, ONLY)                                                                                           \
     hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hi_first<MM, ONLY>), grid, dim3(256), 0, st, B, keep_elems, log2D, p, seed, scratch, \
                        narrow, T, ct)
-    if (all2) { if (M == 5) EDEN_DEC_HI_FIRST(5, 512u); else EDEN_DEC_HI_FIRST(6, 512u); }
+    if (all1) { if (M == 5) EDEN_DEC_HI_FIRST(5, 256u); else EDEN_DEC_HI_FIRST(6, 256u); }
+    else if (all2) { if (M == 5) EDEN_DEC_HI_FIRST(5, 512u); else EDEN_DEC_HI_FIRST(6, 512u); }
     else if (all4) { if (M == 5) EDEN_DEC_HI_FIRST(5, 1024u); else EDEN_DEC_HI_FIRST(6, 1024u); }
     else EDEN_HI_SWITCH(M, EDEN_DEC_HI_FIRST(MM, 0u));
 #undef EDEN_DEC_HI_FIRST
