@@ -279,7 +279,8 @@ template <> struct WordVec<4> { using type = uint4; };
 // MODE 1: any integer budget or b = 1/2.  MODE 2: also the budgets k + 1/2 (they need more registers).
 // MODE 3: every sender of the launch has b = 4 (the instance holds nothing else: no spills, and the transposing pack).
 // BLK: the first pass wrote the workspace in the blocked layout (blocked_offset in eden_device.h).
-template <int M, int TPW, int MODE, bool BLK>
+// ONLY != 0: every sender of the launch has this budget; the instance holds that one branch of the quantizers.
+template <int M, int TPW, int MODE, bool BLK, uint32_t ONLY = 0>
 __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_last(EncBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                    const float *T, double *partials,
                                                                    uint32_t partial_stride, const EncScratch *scratch,
@@ -300,7 +301,7 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
     if (BLK) rows_written = (rows_written + kBlockRows - 1u) / kBlockRows * kBlockRows;      // whole blocks of rows are written
     const rsrc_t rt = make_rsrc(T + ((size_t)c << log2D), rows_written << (p + 2));
     uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES);
-    const uint32_t b_q8 = B.b_q8[c];
+    const uint32_t b_q8 = ONLY ? ONLY : B.b_q8[c];
     const EncScratch *sc = &scratch[c];
     // stage-1 rows: g + RL r.  Byte offset of (row, column) inside the slot = a per-thread part + a part that is the same for
     // the whole workgroup (row_off(r)) + the tile's column block
@@ -490,8 +491,8 @@ __global__ __launch_bounds__(HiX<M>::THREADS) void k_hix_mid(float *T, int log2D
 // First decode pass (Sec. 2.2.2, 4.2): unpack, centroid lookup times S/(p sqrt D) (or the unit pattern when the
 // workspace is fp16), zero for coordinates that were not sampled or whose packet was lost, then index bits
 // 14 .. 14+M-1 of H.
-// ONLY != 0: every sender of the launch has this budget (2 or 4 bits, indices in the payload): the instance then holds that
-// one branch, which takes it from 128 registers and spills to 97 (16 senders at D = 2^24: 0.180 -> 0.160 ms).
+// ONLY != 0: every sender of the launch has this budget (2, 3 or 4 bits, or k + 1/2; indices in the payload): the instance then
+// holds that one branch, which takes it from 128 registers and spills to 97 (16 senders at D = 2^24: 0.180 -> 0.160 ms).
 template <int M, uint32_t ONLY = 0>
 __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B, uint64_t d, int log2D, uint64_t seed,
                                                                     const DecScratch *scratch, int narrow, float *T,
@@ -1133,7 +1134,26 @@ uint32_t launch_enc_hix_last(int M, int blocked, const EncBatch &B, uint32_t n, 
     // every other launch: one tile per workgroup (with the blocked workspace two tiles per workgroup are slower at every size:
     // 16 senders at D = 2^23, 0.151 -> 0.142 ms at b = 2, 0.34 -> 0.18 ms at b = 1.5, 0.255 -> 0.144 ms for the b = 4 instance)
     dim3 grid(tiles, n);
-    if (four) { EDEN_ENC_HIX_LAST(1, 3); } else if (mixed) { EDEN_ENC_HIX_LAST(1, 2); } else { EDEN_ENC_HIX_LAST(1, 1); }
+    // One budget for all senders: b = 3 and the budgets k + 1/2 have instances that hold only their branch (the shared ones
+    // spill 76 and 188 bytes at M = 10; 16 senders at D = 2^24: 0.40 -> 0.24 ms at b = 1.5, 0.277 -> 0.253 ms at b = 3; at
+    // b = 2 such an instance gained nothing).
+    uint32_t same = B.b_q8[0];
+    for (uint32_t c = 1; c < n; ++c) if (B.b_q8[c] != same) same = 0;
+#define EDEN_ENC_HIX_ONLY(MODE, ONLY)                                                                                         \
+    if (blocked) {                                                                                                            \
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, 1, MODE, true, ONLY>), grid, dim3(HiX<MM>::THREADS), \
+                                              0, st, B, d, log2D, seed, T, partials, partial_stride, scratch, ct))            \
+    } else {                                                                                                                  \
+        EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_enc_hix_last<MM, 1, MODE, false, ONLY>), grid, dim3(HiX<MM>::THREADS), \
+                                              0, st, B, d, log2D, seed, T, partials, partial_stride, scratch, ct))            \
+    }
+    if (four) { EDEN_ENC_HIX_LAST(1, 3); }
+    else if (same == 768u) { EDEN_ENC_HIX_ONLY(1, 768u); }
+    else if (same == 384u) { EDEN_ENC_HIX_ONLY(2, 384u); }
+    else if (same == 640u) { EDEN_ENC_HIX_ONLY(2, 640u); }
+    else if (same == 896u) { EDEN_ENC_HIX_ONLY(2, 896u); }
+    else if (mixed) { EDEN_ENC_HIX_LAST(1, 2); } else { EDEN_ENC_HIX_LAST(1, 1); }
+#undef EDEN_ENC_HIX_ONLY
 #undef EDEN_ENC_HIX_LAST
     return grid.x;
 }
@@ -1190,7 +1210,12 @@ bool launch_dec_hix_first(int M, const DecBatch &B, uint32_t n, uint64_t d, int 
 #define EDEN_DEC_HIX_FIRST(ONLY)                                                                                              \
     EDEN_HIX_SWITCH(M, hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_hix_first<MM, ONLY>), grid, dim3(HiX<MM>::THREADS), 0, st, B, d, \
                                           log2D, seed, scratch, narrow, T, ct))
-    if (all2) { EDEN_DEC_HIX_FIRST(512u); } else if (all4) { EDEN_DEC_HIX_FIRST(1024u); } else { EDEN_DEC_HIX_FIRST(0u); }
+    uint32_t same = B.b_q8[0];
+    for (uint32_t c = 1; c < n; ++c) if (B.b_q8[c] != same) same = 0;
+    if (all2) { EDEN_DEC_HIX_FIRST(512u); } else if (all4) { EDEN_DEC_HIX_FIRST(1024u); }
+    else if (same == 768u) { EDEN_DEC_HIX_FIRST(768u); } else if (same == 384u) { EDEN_DEC_HIX_FIRST(384u); }
+    else if (same == 640u) { EDEN_DEC_HIX_FIRST(640u); } else if (same == 896u) { EDEN_DEC_HIX_FIRST(896u); }
+    else { EDEN_DEC_HIX_FIRST(0u); }
 #undef EDEN_DEC_HIX_FIRST
     return false;
 }

@@ -126,13 +126,14 @@ def test_one_bit_round_at_two_to_the_24(d, drop, b_q8):
 
 
 @pytest.mark.timeout(600)
-def test_four_bit_round_at_two_to_the_24():
-    # every sender at b = 4 and D = 2^24: the strided encode pass is the instance that holds only this budget (indices packed
-    # by a transpose across lanes), one tile per workgroup
+@pytest.mark.parametrize("b_q8", [1024, 384, 768])
+def test_round_of_one_budget_at_two_to_the_24(b_q8):
+    # every sender at b = 4 (or 1.5, or 3) and D = 2^24: the strided passes next to the payload are the instances that hold
+    # only this budget (b = 4: indices packed by a transpose across lanes), one tile per workgroup
     from paper_2108_08842_amd import eden
     n, d = 2, 9_000_000
-    w = synth.Workload("t", n, d, [1024] * n, 4024, "lognormal_signed")
-    print(f"b = 4 round: n={n} d={d} D=2^24 seed={w.seed}", flush=True)
+    w = synth.Workload("t", n, d, [b_q8] * n, 4024, "lognormal_signed")
+    print(f"b = {b_q8 / 256} round: n={n} d={d} D=2^24 seed={w.seed}", flush=True)
     xs = [synth.client_vector(w, c) for c in range(n)]
     ids = [31, 32]
     ctx = eden.Context(d_max=d, n_max=n, device=0)

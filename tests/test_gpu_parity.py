@@ -148,10 +148,11 @@ def test_rounds_of_four_bits_on_workgroup_tiles(ctx, d):
     _run_case(ctx, xs, [31, 32], w.b_q8, w.seed, drop_q32=int(0.1 * 2 ** 32) if d < 4_000_000 else 0, also_oracle_msgs=False)
 
 
-@pytest.mark.parametrize("d,b_q8", [(400_000, 512), (400_001, 1024), (1 << 20, 512), (900_000, 1024), (3_000_000, 512)])
+@pytest.mark.parametrize("d,b_q8", [(400_000, 512), (400_001, 1024), (1 << 20, 512), (900_000, 1024), (3_000_000, 512),
+                                    (2_200_000, 768), (2_500_000, 384), (3_000_001, 640), (5_000_000, 896), (6_000_000, 768)])
 def test_rounds_of_one_integer_budget(ctx, d, b_q8):
-    # every sender at b = 2 (or every sender at b = 4) at the two-pass sizes: the strided passes next to the payload run the
-    # instances that hold only that budget (wave tiles at D = 2^19, 2^20; workgroup tiles above)
+    # every sender at the same budget (2, 3, 4 bits or k + 1/2) at the two-pass sizes: the strided passes next to the payload
+    # run the instances that hold only that budget (wave tiles at D = 2^19, 2^20; workgroup tiles above)
     n = 3
     w = synth.Workload("t", n, d, [b_q8] * n, 7000 + d % 1000, "lognormal_signed")
     xs = [synth.client_vector(w, c) for c in range(n)]
