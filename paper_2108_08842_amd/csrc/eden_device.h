@@ -330,8 +330,11 @@ __device__ inline uint32_t quantize_one(float u, const EncScratch *sc, const flo
 // thresholds in lower cells plus one compare.  The result is the one of magnitude_rank for every input: the cell number is a
 // monotone function of |u| (a rounded product, clamped and truncated), hence a value in a higher cell than a threshold is above
 // it and one in a lower cell is below it, and inside the threshold's own cell the compare decides as it does there.  |x| = 0:
-// `inv` is 0, every value is 0 and lands in cell 0, whose threshold is 0: rank 0.
+// `inv` is 0, every value is 0 and lands in cell 0, whose threshold is 0: rank 0.  A vector so small that 62 / threshold
+// overflows (|x| / sqrt(D) below 1e-37) would put several thresholds into one cell: fill_rank_table reports that (a cell's
+// `below` of kRankCollision) and the caller counts thresholds for that sender instead.
 constexpr int kRankCells = 64;
+constexpr uint32_t kRankCollision = 0x80000000u;
 struct RankCell {
     float thr;              // the threshold inside the cell, +inf if there is none
     float q_below, q_above; // centroids of the rank without and with that threshold passed
@@ -346,14 +349,17 @@ template <int H>
 __device__ inline void fill_rank_table(RankCell *cells, const EncScratch *sc, uint32_t thread, float inv) {
     if (thread >= (uint32_t)kRankCells) return;
     RankCell e{__builtin_inff(), 0.0f, 0.0f, 0u};
+    uint32_t here = 0;
 #pragma unroll
     for (int t = 1; t < H; ++t) {
         const uint32_t cell = rank_cell_of(sc->thr[t], inv);
         e.below += cell < thread ? 1u : 0u;
-        if (cell == thread) e.thr = sc->thr[t];
+        if (cell == thread) { e.thr = sc->thr[t]; ++here; }
     }
+    const bool collision = __ballot(here > 1u && sc->thr[H - 1] > 0.0f) != 0ull;      // (threads 0..63 are one wave)
     e.q_below = sc->qpos[e.below];
     e.q_above = sc->qpos[e.below + 1u < (uint32_t)H ? e.below + 1u : (uint32_t)H - 1u];
+    if (collision) e.below = kRankCollision;
     cells[thread] = e;
 }
 template <int H>

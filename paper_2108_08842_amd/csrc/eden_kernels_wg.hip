@@ -143,11 +143,17 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
         static_assert(MIX == 0 && BITS == 4, "one nibble per coordinate");
         constexpr int PER = 32 / BITS;
         const uint32_t g = threadIdx.x >> 5, j = col & (uint32_t)(PER - 1), q = col / (uint32_t)PER;
+        const bool by_table = cells[0].below != kRankCollision;  // (see fill_rank_table; the same for the whole workgroup)
         static_for<X::RP / PER>([&](auto K) {
             constexpr int k = decltype(K)::value;
             uint32_t items = 0;
+            if (by_table) {
 #pragma unroll
-            for (int i = 0; i < PER; ++i) items |= quantize_one_table<H>(out[PER * k + i], cells, cell_scale, ip) << (BITS * i);
+                for (int i = 0; i < PER; ++i) items |= quantize_one_table<H>(out[PER * k + i], cells, cell_scale, ip) << (BITS * i);
+            } else {
+#pragma unroll
+                for (int i = 0; i < PER; ++i) items |= quantize_one<H>(out[PER * k + i], sc, qtab, ip) << (BITS * i);
+            }
             items = transpose_items<BITS>(items, lane);
             const uint32_t row = hix_row2<M>(g, ph, (int)(PER * k + j));
             payload[(uint32_t)BITS * (word0 + (row << (p - 5))) + q] = items;

@@ -159,6 +159,24 @@ def test_rounds_of_one_integer_budget(ctx, d, b_q8):
     _run_case(ctx, xs, [41, 42, 43], w.b_q8, w.seed, drop_q32=int(0.15 * 2 ** 32), also_oracle_msgs=(d < 1_000_000))
 
 
+@pytest.mark.parametrize("scale", [1.0, 2e-38])
+def test_four_bit_instance_writes_what_the_shared_kernel_writes(ctx, scale):
+    # a launch whose senders all have b = 4 (interval search by table, transposing pack) and a launch that mixes budgets (threshold
+    # counting, ballots) write the same message for the same sender, bit for bit; also for a vector so small that the table's
+    # cell width underflows and the instance has to count thresholds itself
+    d = (1 << 21) - 3
+    w = synth.Workload("t", 2, d, [1024, 1024], 99, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(2)]
+    xs[0] = (xs[0] / np.abs(xs[0]).max() * np.float32(scale)).astype(np.float32)
+    assert np.count_nonzero(xs[0]) > d // 2
+    x_dev = [torch.from_numpy(x).cuda() for x in xs]
+    alone = ctx.encode(x_dev, [5, 6], [1024, 1024], w.seed)
+    mixed = ctx.encode(x_dev, [5, 6], [1024, 512], w.seed)
+    torch.cuda.synchronize()
+    assert ctx.last_device_status() == 0
+    assert torch.equal(alone[0], mixed[0])
+
+
 @pytest.mark.parametrize("d", [5000, 70_000, 300_000])
 def test_packet_loss_and_mixed_budgets(ctx, d):
     w = synth.Workload("t", 6, d, [128, 256, 512, 1024, 768, 128], 300 + d % 1000, "lognormal")
