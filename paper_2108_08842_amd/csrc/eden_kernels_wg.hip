@@ -592,6 +592,14 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B
         const uint32_t shift = cbits & 31u;
         const rsrc_t rb = make_rsrc(payload + payload_bytes / 4u, (uint32_t)coin_b_bytes(ct.total[c]));
         const uint32_t below = (1u << col) - 1u;
+        // the top bits of a row segment's coins are at most 32 consecutive bits of the second part, from bit oa (ob) on: this
+        // lane fetches them for "its" two rows once (beyond the part: 0), and every lane finds its bit in the window
+        auto window = [&](uint32_t first_bit) {
+            const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((first_bit >> 5) * 4u), 0, 0);
+            const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((first_bit >> 5) * 4u + 4u), 0, 0);
+            return __builtin_amdgcn_alignbit(hi, lo, first_bit & 31u);
+        };
+        const uint32_t wa = window(oa), wb = window(ob);
 #pragma unroll
         for (int r = 0; r < 64; ++r) {
             const int soff = (int)((((uint32_t)X::RL * r * (uint32_t)bits) << (p - 5)) * 4u);
@@ -599,10 +607,8 @@ __global__ __launch_bounds__(HiX<M>::THREADS, 4) void k_dec_hix_first(DecBatch B
             const uint32_t w1 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0);    // always: no branch per value
             const uint32_t low = code_at(w0, w1, shift, bits);
             const uint32_t m = (lane < 32u) ? __builtin_amdgcn_readlane(ma, r) : __builtin_amdgcn_readlane(mb, r);
-            const uint32_t o = (lane < 32u) ? __builtin_amdgcn_readlane(oa, r) : __builtin_amdgcn_readlane(ob, r);
-            const uint32_t rank = o + (uint32_t)__popc(m & below);
-            const uint32_t wb = __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((rank >> 5) * 4u), 0, 0);   // beyond the part: 0
-            const uint32_t top = (wb >> (rank & 31u)) & 1u;
+            const uint32_t wnd = (lane < 32u) ? __builtin_amdgcn_readlane(wa, r) : __builtin_amdgcn_readlane(wb, r);
+            const uint32_t top = (wnd >> (uint32_t)__popc(m & below)) & 1u;
             v[r] = ((m >> col) & 1u) ? table[16u + ((top << bits) | low)] : table[low];
         }
     } else if (budget_mixed(b_q8)) {
