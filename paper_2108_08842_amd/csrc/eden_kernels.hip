@@ -381,6 +381,15 @@ __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t ke
         const rsrc_t rp = make_rsrc(payload + (base >> 6) * words_row, payload_bytes - (uint32_t)(base >> 6) * words_row * 4u);
         const rsrc_t rb = make_rsrc(payload + payload_bytes / 4u, (uint32_t)coin_b_bytes(ct.total[c]));
         const uint32_t voff = (lbits >> 5) * 4u, shift = lbits & 31u;
+        // the top bits of a row's coins are at most 64 consecutive bits of the second part, from bit off_mine on: the lane
+        // that looks after the row fetches them once (beyond the part: 0), and every lane finds its bit in that window
+        uint64_t window_mine;
+        {
+            const int at = (int)((off_mine >> 5) * 4u);
+            const uint32_t b0 = __builtin_amdgcn_raw_buffer_load_b32(rb, at, 0, 0), b1 = __builtin_amdgcn_raw_buffer_load_b32(rb, at + 4, 0, 0);
+            const uint32_t b2 = __builtin_amdgcn_raw_buffer_load_b32(rb, at + 8, 0, 0);
+            window_mine = ((uint64_t)__builtin_amdgcn_alignbit(b2, b1, off_mine & 31u) << 32) | __builtin_amdgcn_alignbit(b1, b0, off_mine & 31u);
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int soff = (int)((((uint32_t)r * words_row) << (p - 6)) * 4u);
@@ -388,9 +397,7 @@ __global__ __launch_bounds__(256, 5) void k_dec_hi_first(DecBatch B, uint64_t ke
             const uint32_t w1 = __builtin_amdgcn_raw_buffer_load_b32(rp, (int)voff + 4, soff, 0);    // always: no branch per value
             const uint32_t low = code_at(w0, w1, shift, bits);
             const uint64_t m = wave_read64(mask_mine, r);
-            const uint32_t rank = __builtin_amdgcn_readlane(off_mine, r) + lanes_below(m);
-            const uint32_t wb = __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((rank >> 5) * 4u), 0, 0);   // beyond the part: 0
-            const uint32_t top = (wb >> (rank & 31u)) & 1u;
+            const uint32_t top = (uint32_t)(wave_read64(window_mine, r) >> lanes_below(m)) & 1u;
             v[r] = __builtin_amdgcn_inverse_ballot_w64(m) ? tb2[(top << bits) | low] : tb[low];
         }
     } else if (bits == 3) {
@@ -1234,7 +1241,7 @@ __global__ __launch_bounds__(256) void k_enc_small(EncBatch B, uint64_t d, int p
     __shared__ uint8_t code[kLoTile];
     __shared__ double red[4];
     __shared__ EncScratch s;
-    __shared__ uint32_t coin_words[kLoTile / 32];              // coin budgets: the second part of the payload
+    __shared__ __attribute__((aligned(8))) uint32_t coin_words[kLoTile / 32];   // coin budgets: the second part of the payload
     __shared__ uint32_t wave_totals[4];
     const uint32_t c = blockIdx.x;
     const uint32_t D = 1u << log2D;
