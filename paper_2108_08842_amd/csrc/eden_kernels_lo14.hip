@@ -156,12 +156,15 @@ __global__ __launch_bounds__(512, 4) void k_enc_lo14_first(EncBatch B, uint64_t 
 // `separate`: K = n, one sender per workgroup, nothing is summed: every sender's decoded tile is written back into its own
 // workspace slot (`partial` is then the workspace; fp32, in place: the workgroup has read the tile before it writes
 // it), for a caller that puts the values elsewhere afterwards.
-template <bool PRE>
+// WIDE_ONLY: no sender of the launch has an fp16 slot (every b > 1): the instance without that branch in the sender loop
+// (116 registers instead of 125; 16 senders at D = 2^24: 0.170 -> 0.160 ms).
+template <bool PRE, bool WIDE_ONLY = false>
 __global__ __launch_bounds__(512) void k_dec_lo14_last(DecBatch B, uint32_t n, uint64_t d_src, int log2D, uint64_t seed,
-                                                       const float *T, const DecScratch *scratch, int narrow, float *acc,
+                                                       const float *T, const DecScratch *scratch, int narrow_arg, float *acc,
                                                        uint32_t full_tiles, uint32_t K, uint32_t split_tiles,
                                                        float *partial, int separate, float mean_n) {
     __shared__ __attribute__((aligned(16))) float lds[kLo14LdsWords];
+    const int narrow = WIDE_ONLY ? 0 : narrow_arg;
     constexpr int NS = PRE ? 64 : 32;                            // accumulator coordinates per thread
     const uint64_t d = d_src;                                    // bound of acc
     const uint32_t t = threadIdx.x, lane = t & 63u, wv = t >> 6;
@@ -649,9 +652,16 @@ void launch_dec_lo14_last(const DecBatch &B, uint32_t n, uint64_t d_src, int pre
     if (all16)                                                   // |values| <= 2^10: ten of the bits on the matrix cores
         hipLaunchKernelGGL(k_dec_lo14_last_mfma, grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch, acc, full, K, rest,
                            partial, mean_n);
-    else
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
-                           narrow, acc, full, K, rest, partial, 0, mean_n);
+    else {
+        bool none16 = true;                                      // no sender with an fp16 slot
+        for (uint32_t c = 0; c < n; ++c) none16 = none16 && !(narrow && B.b_q8[c] <= 256u);
+        if (none16)
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false, true>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T,
+                               scratch, narrow, acc, full, K, rest, partial, 0, mean_n);
+        else
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(k_dec_lo14_last<false>), grid, dim3(512), 0, st, B, n, d_src, log2D, seed, T, scratch,
+                               narrow, acc, full, K, rest, partial, 0, mean_n);
+    }
     if (K > 1) {
         dim3 cgrid((uint32_t)((((uint64_t)rest << kLo14Bits) / 4 + 255) / 256));
         hipLaunchKernelGGL(k_dec_lo14_combine, cgrid, dim3(256), 0, st, acc, d, full, K, rest, partial, mean_n);
