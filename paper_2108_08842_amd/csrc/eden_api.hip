@@ -279,6 +279,18 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
                 part_b[i] = static_cast<char *>(B.msg[i]) + EDEN_HEADER_BYTES + payload_a_bytes(1ull << log2D, (int)(coin_q8(B.b_q8[i]) >> 8), 1);
             }
             if (coins) launch_coin_tables(B.client, B.b_q8, part_b, nb, seed, log2D, ctx->coin, st);
+            // Coin senders whose last pass runs in workgroup tiles leave the pieces of the second part in the byte-index buffer
+            // (a word per 32 coordinates) and a small kernel strings them together: no atomics in the last pass.
+            const uint32_t *pieces[kMaxBatch] = {};
+            bool staged = false;
+            if (coins && ctx->codes && pl.hi[pl.nhi - 1].wg) {
+                for (uint32_t i = 0; i < nb; ++i) {
+                    if (!coin_q8(B.b_q8[i])) continue;
+                    B.codes[i] = ctx->codes + ((size_t)i << log2D);
+                    pieces[i] = reinterpret_cast<const uint32_t *>(B.codes[i]);
+                    staged = true;
+                }
+            }
             // The workspace goes through the blocked layout when a workgroup-tile pass reads it back right away (two-pass
             // plans of D >= 2^21), unless the first pass works in place on the workspace (its input is a slot): its
             // workgroups would then overwrite rows that others have not read yet.
@@ -313,6 +325,7 @@ static int encode_range(eden_ctx *ctx, const float *const *x_dev, const uint32_t
                 }
             }
             if (pack) launch_pack_bits(B, nb, log2D, st);
+            if (staged) launch_coin_pack(B.b_q8, pieces, part_b, nb, log2D, ctx->coin, st);
             Timed t(ctx, EDEN_K_ENC_FINISH, nb, st);
             launch_enc_finish(B, nb, hdr_d, log2D, seed, part_n2, nparts_n2, part_ip, nparts_ip, ctx->partial_stride,
                               ctx->dev_status, ctx->coin.total, st);

@@ -22,6 +22,8 @@ uint32_t launch_enc_hi_last(int M, const EncBatch &B, uint32_t n, uint64_t valid
                             const CoinTables &ct, hipStream_t st);
 // coin budgets (multi-pass sizes): the coins of the senders that have such a budget, with their prefix sums; `part_b`
 // (encode) points at the second part of every such sender's payload, which is cleared; null on the receiver's side
+void launch_coin_pack(const uint32_t *b_q8, const uint32_t *const *pieces, void *const *part_b, uint32_t n, int log2D,
+                      const CoinTables &ct, hipStream_t st);
 void launch_coin_tables(const uint32_t *clients, const uint32_t *b_q8, void *const *part_b, uint32_t n, uint64_t seed, int log2D,
                         const CoinTables &ct, hipStream_t st);
 // wide strided tiles (8 rows x 512 columns per wave) for the top three index bits of D >= 2^25; b = 1, 2, 4, 5..8 and

@@ -848,6 +848,47 @@ __global__ __launch_bounds__(256) void k_coin_scan(CoinBatch B, int log2D, CoinT
     if (threadIdx.x == 0) ct.total[c] = all;
 }
 
+// Coin budgets, encoder in workgroup tiles: the last pass leaves, for every segment of 32 consecutive coordinates, the top
+// bits of its coins moved together towards bit 0, one word per segment, in `pieces` (bits above the segment's number of
+// coins are 0).  This kernel strings them together into the second part of the payload (Sec. 4.1: one more bit for every
+// coordinate with a coin, in coordinate order).  A thread looks after one block of 64 coordinates; if one of the part's 64-bit
+// words begins inside the block's run of bits, the thread assembles that word from its own pieces and those of the blocks
+// after it.  Every word is written by exactly one thread: no atomics (they cost the last encode pass a third of its time).
+struct CoinPackBatch {
+    uint32_t b_q8[kMaxBatch];
+    const uint32_t *pieces[kMaxBatch];   // null: the sender's bits were placed by the last pass itself
+    uint64_t *part_b[kMaxBatch];
+};
+__global__ __launch_bounds__(256) void k_coin_pack(CoinPackBatch B, int log2D, CoinTables ct) {
+    const uint32_t c = blockIdx.y;
+    const uint32_t *pieces = B.pieces[c];
+    if (!coin_q8(B.b_q8[c]) || !pieces) return;
+    const uint32_t blocks = 1u << (log2D - 6);
+    const uint32_t k = blockIdx.x * 256u + threadIdx.x;
+    if (k >= blocks) return;
+    const uint64_t mine = coin_mask_of(ct, c, log2D, k);
+    const uint32_t count = (uint32_t)__popcll(mine);
+    const uint32_t start = coins_before(ct, c, log2D, k);       // this block's bits are [start, start + count) of the part
+    const uint32_t word = (start + 63u) >> 6;                    // the first word that begins at or after `start`
+    if ((uint64_t)word * 64u >= (uint64_t)start + count) return; // none begins inside this block's run
+    uint32_t skip = word * 64u - start;                          // bits of this block that belong to the word before
+    uint64_t bits = 0;
+    uint32_t have = 0;
+    for (uint32_t kk = k; have < 64u && kk < blocks; ++kk) {
+        const uint64_t m = kk == k ? mine : coin_mask_of(ct, c, log2D, kk);
+        const uint32_t lo = (uint32_t)__popc(lo32(m));
+        uint32_t n = lo + (uint32_t)__popc(hi32(m));
+        if (n == 0u) continue;
+        uint64_t run = (uint64_t)pieces[2u * kk] | ((uint64_t)pieces[2u * kk + 1u] << lo);
+        run >>= skip;                                            // (only the first block has bits to skip, fewer than it holds)
+        n -= skip;
+        skip = 0;
+        bits |= run << have;
+        have += n;
+    }
+    B.part_b[c][word] = bits;
+}
+
 // Decode, last pass in wave tiles: index bits 0..11 of H for every sender, that sender's sign diagonal
 // (R^-1 = s o D^-1/2 H, Sec. 2.2.2; D^-1/2 is inside the dequantization scale), sum over senders in registers,
 // one contiguous read-modify-write of acc.  A lane ends with 64 consecutive coordinates = one sign word.
@@ -1153,10 +1194,10 @@ __device__ inline void unpack32(const uint32_t *words, uint8_t *codes) {
 __global__ __launch_bounds__(256) void k_pack_bits(EncBatch B, int log2D) {
     const uint32_t c = blockIdx.y;
     const uint8_t *codes = B.codes[c];
-    if (!codes) return;
+    const uint32_t bits = wide_bits(B.b_q8[c]);
+    if (!codes || bits < 5u || bits > 7u) return;                // (a coin sender's buffer holds the pieces of its second part)
     const uint64_t g = (uint64_t)blockIdx.x * 256u + threadIdx.x;        // group of 32 indices
     if (g >= (1ull << log2D) / 32) return;
-    const uint32_t bits = wide_bits(B.b_q8[c]);
     uint32_t *payload = reinterpret_cast<uint32_t *>(static_cast<char *>(B.msg[c]) + EDEN_HEADER_BYTES) + g * bits;
     if (bits == 5) pack32<5>(codes + 32 * g, payload);
     else if (bits == 6) pack32<6>(codes + 32 * g, payload);
@@ -1546,6 +1587,17 @@ void launch_coin_tables(const uint32_t *clients, const uint32_t *b_q8, void *con
     const uint32_t words = 1u << (log2D - 6);
     hipLaunchKernelGGL(k_coin_masks, dim3((words + kCoinGroup - 1) / kCoinGroup, n), dim3(256), 0, st, B, seed, log2D, ct);
     hipLaunchKernelGGL(k_coin_scan, dim3(n), dim3(256), 0, st, B, log2D, ct);
+}
+void launch_coin_pack(const uint32_t *b_q8, const uint32_t *const *pieces, void *const *part_b, uint32_t n, int log2D,
+                      const CoinTables &ct, hipStream_t st) {
+    CoinPackBatch B;
+    for (uint32_t i = 0; i < (uint32_t)kMaxBatch; ++i) {
+        B.b_q8[i] = i < n ? b_q8[i] : 0u;
+        B.pieces[i] = i < n ? pieces[i] : nullptr;
+        B.part_b[i] = i < n ? static_cast<uint64_t *>(part_b[i]) : nullptr;
+    }
+    const uint32_t blocks = 1u << (log2D - 6);
+    hipLaunchKernelGGL(k_coin_pack, dim3((blocks + 255u) / 256u, n), dim3(256), 0, st, B, log2D, ct);
 }
 void launch_dec_hi_first(int M, const DecBatch &B, uint32_t n, uint64_t keep_elems, int log2D, int p, uint64_t seed,
                          const DecScratch *scratch, int narrow, float *T, const CoinTables &ct, hipStream_t st) {

@@ -132,7 +132,7 @@ template <int M, int BITS, int MIX, bool TRANSPOSE = false>
 __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph, const EncScratch *sc, const float *qtab,
                                          uint32_t *payload, uint16_t *part_b, uint64_t mixkey, uint64_t base, float &ip,
                                          const CoinTables &ct, uint32_t c, int log2D, uint32_t *part_c,
-                                         const RankCell *cells = nullptr, float cell_scale = 0.0f) {
+                                         const RankCell *cells = nullptr, float cell_scale = 0.0f, uint32_t *pieces = nullptr) {
     using X = HiX<M>;
     constexpr int p = kHixP;
     constexpr int H = 1 << (BITS - 1);
@@ -223,8 +223,13 @@ __device__ inline void hix_quantize_pack(const float (&out)[HiX<M>::RP], int ph,
             *reinterpret_cast<uint4 *>(payload + 4u * word) = make_uint4(o[0], o[1], o[2], o[3]);
         }
         if constexpr (MIX == 1) part_b[word] = (uint16_t)even_bits(top[w] | (top[w] >> 1));    // only the chosen one can be set
-        if constexpr (MIX == 2)                                  // only a coordinate with a coin can have the bit
-            or_bits(part_c, coin_off[w], compress_bits(top[w], offs16[w]), (uint32_t)__popc(offs16[w]));
+        if constexpr (MIX == 2) {                                // only a coordinate with a coin can have the bit
+            const uint32_t piece = (uint32_t)compress_bits(top[w], offs16[w]);
+            // either the piece goes to the staging array (word = number of the segment of 32 coordinates; k_coin_pack strings
+            // the pieces together) or straight to its bits of the second part, which neighbouring tiles share: atomics
+            if (pieces) pieces[word] = piece;
+            else or_bits(part_c, coin_off[w], piece, (uint32_t)__popc(offs16[w]));
+        }
     }
 }
 
@@ -389,7 +394,10 @@ __global__ __launch_bounds__(HiX<M>::THREADS, TPW == 1 ? 4 : 1) void k_enc_hix_l
                 uint32_t *part_c = payload + payload_a_bytes(1ull << log2D, ibits, 1) / 4;       // second part, if any
                 uint16_t *part_b = reinterpret_cast<uint16_t *>(part_c);
                 const uint32_t cq = MODE == 2 ? coin_q8(b_q8) : 0u;
-#define EDEN_HIX_PACK(BITS, MIX) hix_quantize_pack<M, BITS, MIX>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip, ct, c, log2D, part_c)
+                // coin budgets: a staging array for the pieces of the second part, if the host gave this sender one
+                uint32_t *pieces = cq ? reinterpret_cast<uint32_t *>(B.codes[c]) : nullptr;
+#define EDEN_HIX_PACK(BITS, MIX) \
+    hix_quantize_pack<M, BITS, MIX>(out, ph, sc, qtab, payload, part_b, mixkey, base, ip, ct, c, log2D, part_c, nullptr, 0.0f, pieces)
                 if (cq && ibits == 1) EDEN_HIX_PACK(1, 2);
                 else if (cq && ibits == 2) EDEN_HIX_PACK(2, 2);
                 else if (cq) EDEN_HIX_PACK(3, 2);

@@ -422,6 +422,17 @@ def test_coin_budgets(ctx, d):
         assert eden.message_bytes(d, b) == o.message_bytes(d, b)
 
 
+def test_coin_and_packed_byte_budgets_in_one_call(ctx):
+    # at the workgroup-tile sizes a coin sender's pieces of the second part and a b = 5..7 sender's one-byte indices both pass
+    # through the context's byte buffer, each in its sender's slot: one call with both kinds, and the very sparse and very dense coins
+    from paper_2108_08842_amd import eden
+    d = 2_300_007
+    budgets = [eden.B_COIN(2.3), 1536, eden.B_COIN(1 + 1 / 256), 1280, eden.B_COIN(3 + 255 / 256), 256]
+    w = synth.Workload("t", len(budgets), d, budgets, 2626, "lognormal_signed")
+    xs = [synth.client_vector(w, c) for c in range(len(budgets))]
+    _run_case(ctx, xs, list(range(60, 60 + len(budgets))), w.b_q8, w.seed, also_oracle_msgs=False)
+
+
 def test_random_shapes_and_budgets(ctx):
     # 60 seeded random cases: dimension (log-uniform up to 2^18 + tail), number of senders, any supported budget
     # per sender, sometimes lost packets, sometimes the sparsification before the rotation
